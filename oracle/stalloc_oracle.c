@@ -1,0 +1,345 @@
+/*
+ * CPU oracle for spatio-temporal allocation planning.
+ *
+ * THIS IS TEST INFRASTRUCTURE, not a product path: it exists so that the GPU
+ * library can be compared against something slow and obviously correct.  Only
+ * the tests, the smoke check and the benchmark's cpu_baseline leg may call it.
+ * It shares no code, headers, tables or helpers with the GPU library.
+ *
+ * What is computed (problem statement of Sec. 5.1):
+ *   a request is a rectangle  s bytes x [t_s, t_e)  (Sec. 4, request event m);
+ *   a plan gives every request a start address a (decision d = m + (a));
+ *   two decisions may not conflict in lifespan AND in address range at once;
+ *   the extent of a plan is max(d.a + d.s)  (Eq. 2, Eq. 6);
+ *   memory efficiency is M_a / M_r (Eq. 1): M_a = max over time of live bytes,
+ *   M_r = the plan's extent.
+ *
+ * Placement rule: requests are taken in a given order and each is put at the
+ * lowest address at which it conflicts with no request placed before it
+ * ("lowest available address", Sec. 5.1 HomoPhase fusion; larger-first so that
+ * smaller requests fill the unused intervals, Sec. 5.1 Global Planning).
+ * For a fixed order the result is unique.
+ *
+ * Readings taken where the text is silent:
+ *   - lifetimes are half-open [t_s, t_e): a request released at t and one
+ *     allocated at t do not conflict;
+ *   - address ranges are half-open [a, a+s): touching ranges do not conflict;
+ *   - no alignment is applied;
+ *   - among plans of equal extent the lowest plan index wins.
+ *
+ * Pins (tests/test_oracle_*.py): closed forms for time-cliques and
+ * time-disjoint traces, the equal-size case against Algorithm 1's layer count,
+ * stack-discipline traces, exhaustive search over all orders for n <= 8 against
+ * an independent exact search, a quadratic no-conflict check, a minimality
+ * re-derivation, and hand-worked examples under tests/golden/.
+ * No value printed in the paper exists for a placement (its worked figures are
+ * images), so parity with printed values is unpinned.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORC_OK = 0, ORC_INVALID_ARG = 1, ORC_BAD_TRACE = 2, ORC_OVERFLOW = 3, ORC_NOMEM = 4 };
+
+static int lifetimes_conflict(uint32_t ts_a, uint32_t te_a, uint32_t ts_b, uint32_t te_b)
+{
+    return ts_a < te_b && ts_b < te_a;
+}
+
+static int ranges_conflict(uint64_t a_a, uint64_t s_a, uint64_t a_b, uint64_t s_b)
+{
+    return a_a < a_b + s_b && a_b < a_a + s_a;
+}
+
+/* Trace sanity: sizes > 0, t_s < t_e <= t_end, sum of sizes below 2^63. */
+int oracle_check_trace(uint32_t n, uint32_t t_end, const uint64_t *size,
+                       const uint32_t *t_s, const uint32_t *t_e)
+{
+    if (n == 0 || !size || !t_s || !t_e) return ORC_INVALID_ARG;
+    uint64_t sum = 0;
+    for (uint32_t i = 0; i < n; ++i) {
+        if (size[i] == 0 || t_s[i] >= t_e[i] || t_e[i] > t_end) return ORC_BAD_TRACE;
+        if (size[i] >= (1ull << 63) || sum + size[i] >= (1ull << 63)) return ORC_OVERFLOW;
+        sum += size[i];
+    }
+    return ORC_OK;
+}
+
+typedef struct { uint64_t a; uint64_t end; } span_t;
+
+static int span_by_address(const void *pa, const void *pb)
+{
+    const span_t *x = (const span_t *)pa, *y = (const span_t *)pb;
+    if (x->a != y->a) return x->a < y->a ? -1 : 1;
+    if (x->end != y->end) return x->end < y->end ? -1 : 1;
+    return 0;
+}
+
+/* Lowest address x such that [x, x+s) meets none of the k spans. */
+static uint64_t lowest_free_address(span_t *spans, size_t k, uint64_t s)
+{
+    qsort(spans, k, sizeof(span_t), span_by_address);
+    uint64_t x = 0;
+    for (size_t c = 0; c < k; ++c) {
+        if (spans[c].a >= x + s) break;      /* the hole [x, spans[c].a) is large enough */
+        if (spans[c].end > x) x = spans[c].end;
+    }
+    return x;
+}
+
+/*
+ * One plan, every earlier request examined for every placement.
+ * order: permutation of 0..n-1.  a[i] receives request i's address.
+ */
+int oracle_plan_allpairs(uint32_t n, const uint64_t *size, const uint32_t *t_s,
+                         const uint32_t *t_e, const uint32_t *order,
+                         uint64_t *a, uint64_t *extent)
+{
+    if (n == 0 || !order || !a || !extent) return ORC_INVALID_ARG;
+    span_t *spans = (span_t *)malloc((size_t)n * sizeof(span_t));
+    if (!spans) return ORC_NOMEM;
+    uint64_t top = 0;
+    for (uint32_t k = 0; k < n; ++k) {
+        uint32_t i = order[k];
+        size_t m = 0;
+        for (uint32_t q = 0; q < k; ++q) {
+            uint32_t j = order[q];
+            if (lifetimes_conflict(t_s[i], t_e[i], t_s[j], t_e[j])) {
+                spans[m].a = a[j];
+                spans[m].end = a[j] + size[j];
+                ++m;
+            }
+        }
+        a[i] = lowest_free_address(spans, m, size[i]);
+        if (a[i] + size[i] > top) top = a[i] + size[i];
+    }
+    free(spans);
+    *extent = top;
+    return ORC_OK;
+}
+
+/*
+ * Lists, for every request, the requests whose lifetime conflicts with it
+ * (both directions).  Call with nbr == NULL to obtain the counts in
+ * nbr_begin[0..n] (as prefix sums), then again with storage.
+ */
+int oracle_conflict_lists(uint32_t n, const uint32_t *t_s, const uint32_t *t_e,
+                          uint64_t *nbr_begin, uint32_t *nbr)
+{
+    if (n == 0 || !nbr_begin) return ORC_INVALID_ARG;
+    uint64_t *fill = NULL;
+    if (nbr) {
+        fill = (uint64_t *)malloc((size_t)n * sizeof(uint64_t));
+        if (!fill) return ORC_NOMEM;
+        memcpy(fill, nbr_begin, (size_t)n * sizeof(uint64_t));
+    } else {
+        memset(nbr_begin, 0, ((size_t)n + 1) * sizeof(uint64_t));
+    }
+    for (uint32_t i = 0; i < n; ++i)
+        for (uint32_t j = i + 1; j < n; ++j)
+            if (lifetimes_conflict(t_s[i], t_e[i], t_s[j], t_e[j])) {
+                if (nbr) { nbr[fill[i]++] = j; nbr[fill[j]++] = i; }
+                else     { nbr_begin[i + 1]++; nbr_begin[j + 1]++; }
+            }
+    if (!nbr)
+        for (uint32_t i = 0; i < n; ++i) nbr_begin[i + 1] += nbr_begin[i];
+    free(fill);
+    return ORC_OK;
+}
+
+/* Same rule as oracle_plan_allpairs; candidates come from the conflict lists. */
+int oracle_plan_lists(uint32_t n, const uint64_t *size, const uint64_t *nbr_begin,
+                      const uint32_t *nbr, const uint32_t *order,
+                      uint64_t *a, uint64_t *extent)
+{
+    if (n == 0 || !order || !a || !extent || !nbr_begin) return ORC_INVALID_ARG;
+    uint64_t widest = 0;
+    for (uint32_t i = 0; i < n; ++i)
+        if (nbr_begin[i + 1] - nbr_begin[i] > widest) widest = nbr_begin[i + 1] - nbr_begin[i];
+    span_t *spans = (span_t *)malloc((size_t)(widest + 1) * sizeof(span_t));
+    uint8_t *placed = (uint8_t *)calloc(n, 1);
+    if (!spans || !placed) { free(spans); free(placed); return ORC_NOMEM; }
+    uint64_t top = 0;
+    for (uint32_t k = 0; k < n; ++k) {
+        uint32_t i = order[k];
+        size_t m = 0;
+        for (uint64_t e = nbr_begin[i]; e < nbr_begin[i + 1]; ++e) {
+            uint32_t j = nbr[e];
+            if (placed[j]) { spans[m].a = a[j]; spans[m].end = a[j] + size[j]; ++m; }
+        }
+        a[i] = lowest_free_address(spans, m, size[i]);
+        placed[i] = 1;
+        if (a[i] + size[i] > top) top = a[i] + size[i];
+    }
+    free(spans);
+    free(placed);
+    *extent = top;
+    return ORC_OK;
+}
+
+/* Index of the smallest extent; the lowest index among equals. */
+int oracle_best_plan(uint32_t P, const uint64_t *extent, uint32_t *best)
+{
+    if (P == 0 || !extent || !best) return ORC_INVALID_ARG;
+    uint32_t b = 0;
+    for (uint32_t p = 1; p < P; ++p)
+        if (extent[p] < extent[b]) b = p;
+    *best = b;
+    return ORC_OK;
+}
+
+/*
+ * Number of unordered pairs that conflict in lifespan and in address range,
+ * and the lexicographically first such pair (i < j); {~0, ~0} if none.
+ */
+int oracle_validate(uint32_t n, const uint64_t *size, const uint32_t *t_s,
+                    const uint32_t *t_e, const uint64_t *a,
+                    uint64_t *conflicts, uint32_t *first_pair)
+{
+    if (n == 0 || !a || !conflicts || !first_pair) return ORC_INVALID_ARG;
+    uint64_t cnt = 0;
+    first_pair[0] = first_pair[1] = 0xFFFFFFFFu;
+    for (uint32_t i = 0; i < n; ++i)
+        for (uint32_t j = i + 1; j < n; ++j)
+            if (lifetimes_conflict(t_s[i], t_e[i], t_s[j], t_e[j]) &&
+                ranges_conflict(a[i], size[i], a[j], size[j])) {
+                if (cnt == 0) { first_pair[0] = i; first_pair[1] = j; }
+                ++cnt;
+            }
+    *conflicts = cnt;
+    return ORC_OK;
+}
+
+/*
+ * M_a of Eq. 1 by its definition: for every t in [0, t_end) add up the sizes of
+ * the requests alive at t; keep the maximum and the earliest t reaching it.
+ */
+int oracle_lower_bound_definition(uint32_t n, uint32_t t_end, const uint64_t *size,
+                                  const uint32_t *t_s, const uint32_t *t_e,
+                                  uint64_t *max_live, uint32_t *t_at_max)
+{
+    if (n == 0 || !max_live) return ORC_INVALID_ARG;
+    uint64_t best = 0; uint32_t best_t = 0;
+    for (uint32_t t = 0; t < t_end; ++t) {
+        uint64_t live = 0;
+        for (uint32_t i = 0; i < n; ++i)
+            if (t_s[i] <= t && t < t_e[i]) live += size[i];
+        if (live > best) { best = live; best_t = t; }
+    }
+    *max_live = best;
+    if (t_at_max) *t_at_max = best_t;
+    return ORC_OK;
+}
+
+/* Same quantity from per-timestamp net changes and a running sum. */
+int oracle_lower_bound_sweep(uint32_t n, uint32_t t_end, const uint64_t *size,
+                             const uint32_t *t_s, const uint32_t *t_e,
+                             uint64_t *max_live, uint32_t *t_at_max)
+{
+    if (n == 0 || !max_live) return ORC_INVALID_ARG;
+    int64_t *net = (int64_t *)calloc((size_t)t_end + 1, sizeof(int64_t));
+    if (!net) return ORC_NOMEM;
+    for (uint32_t i = 0; i < n; ++i) {
+        net[t_s[i]] += (int64_t)size[i];
+        net[t_e[i]] -= (int64_t)size[i];
+    }
+    int64_t live = 0, best = 0; uint32_t best_t = 0;
+    for (uint32_t t = 0; t < t_end; ++t) {
+        live += net[t];
+        if (live > best) { best = live; best_t = t; }
+    }
+    free(net);
+    *max_live = (uint64_t)best;
+    if (t_at_max) *t_at_max = best_t;
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Exhaustive searches for very small traces                                 */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * Smallest extent over all n! placement orders (n <= 9) and the first order,
+ * in lexicographic enumeration, that reaches it.
+ */
+int oracle_best_over_all_orders(uint32_t n, const uint64_t *size, const uint32_t *t_s,
+                                const uint32_t *t_e, uint64_t *best_extent,
+                                uint32_t *best_order)
+{
+    if (n == 0 || n > 9 || !best_extent) return ORC_INVALID_ARG;
+    uint32_t perm[9]; uint64_t a[9];
+    for (uint32_t i = 0; i < n; ++i) perm[i] = i;
+    uint64_t best = ~0ull;
+    for (;;) {
+        uint64_t ext = 0;
+        int rc = oracle_plan_allpairs(n, size, t_s, t_e, perm, a, &ext);
+        if (rc) return rc;
+        if (ext < best) {
+            best = ext;
+            if (best_order) memcpy(best_order, perm, n * sizeof(uint32_t));
+        }
+        /* next permutation in lexicographic order */
+        int k = (int)n - 2;
+        while (k >= 0 && perm[k] > perm[k + 1]) --k;
+        if (k < 0) break;
+        int l = (int)n - 1;
+        while (perm[l] < perm[k]) --l;
+        uint32_t tmp = perm[k]; perm[k] = perm[l]; perm[l] = tmp;
+        for (int lo = k + 1, hi = (int)n - 1; lo < hi; ++lo, --hi) {
+            tmp = perm[lo]; perm[lo] = perm[hi]; perm[hi] = tmp;
+        }
+    }
+    *best_extent = best;
+    return ORC_OK;
+}
+
+/*
+ * True optimum of the placement problem for n <= 6 without any placement order:
+ * in some optimal plan every address is a sum of sizes of other requests (push
+ * every block down until it rests on address 0 or on another block), so it is
+ * enough to try, for each request, every subset sum of the other sizes.
+ */
+typedef struct {
+    uint32_t n; const uint64_t *size; const uint32_t *t_s; const uint32_t *t_e;
+    uint64_t a[6]; uint64_t best; uint64_t best_a[6];
+} exact_search_t;
+
+static void exact_search(exact_search_t *st, uint32_t i, uint64_t top)
+{
+    if (top >= st->best) return;
+    if (i == st->n) {
+        st->best = top;
+        memcpy(st->best_a, st->a, sizeof(st->a));
+        return;
+    }
+    uint32_t others = st->n - 1;
+    for (uint32_t mask = 0; mask < (1u << others); ++mask) {
+        uint64_t x = 0;
+        for (uint32_t b = 0, j = 0; j < st->n; ++j) {
+            if (j == i) continue;
+            if (mask & (1u << b)) x += st->size[j];
+            ++b;
+        }
+        int ok = 1;
+        for (uint32_t j = 0; j < i && ok; ++j)
+            if (lifetimes_conflict(st->t_s[i], st->t_e[i], st->t_s[j], st->t_e[j]) &&
+                ranges_conflict(x, st->size[i], st->a[j], st->size[j])) ok = 0;
+        if (!ok) continue;
+        st->a[i] = x;
+        uint64_t t2 = x + st->size[i] > top ? x + st->size[i] : top;
+        exact_search(st, i + 1, t2);
+    }
+}
+
+int oracle_exact_optimum(uint32_t n, const uint64_t *size, const uint32_t *t_s,
+                         const uint32_t *t_e, uint64_t *opt_extent, uint64_t *opt_a)
+{
+    if (n == 0 || n > 6 || !opt_extent) return ORC_INVALID_ARG;
+    exact_search_t st;
+    st.n = n; st.size = size; st.t_s = t_s; st.t_e = t_e; st.best = ~0ull;
+    memset(st.a, 0, sizeof(st.a));
+    exact_search(&st, 0, 0);
+    *opt_extent = st.best;
+    if (opt_a) memcpy(opt_a, st.best_a, n * sizeof(uint64_t));
+    return ORC_OK;
+}

@@ -1,0 +1,60 @@
+"""The pins must be sharp: a plausible mistake planted in a copy of the oracle's source
+(on the CPU, never in the GPU code) has to make at least one pin fail."""
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+import test_oracle_pins as pins
+
+MUTATIONS = {
+    "closed_lifetimes": ("return ts_a < te_b && ts_b < te_a;", "return ts_a <= te_b && ts_b <= te_a;"),
+    "closed_ranges": ("return a_a < a_b + s_b && a_b < a_a + s_a;", "return a_a <= a_b + s_b && a_b <= a_a + s_a;"),
+    "previous_end_not_max": ("if (spans[c].end > x) x = spans[c].end;", "x = spans[c].end;"),
+    "hole_needs_extra_byte": ("if (spans[c].a >= x + s) break;", "if (spans[c].a > x + s) break;"),
+    "lists_ignore_placed": ("if (placed[j]) { spans[m].a", "if (1) { spans[m].a"),
+    "live_includes_release_time": ("if (t_s[i] <= t && t < t_e[i]) live += size[i];",
+                                   "if (t_s[i] <= t && t <= t_e[i]) live += size[i];"),
+    "sweep_drops_release": ("net[t_e[i]] -= (int64_t)size[i];", "net[t_e[i]] -= 0;"),
+    "validate_skips_neighbour": ("for (uint32_t j = i + 1; j < n; ++j)\n            if (lifetimes_conflict(t_s[i], t_e[i], t_s[j], t_e[j]) &&",
+                                 "for (uint32_t j = i + 2; j < n; ++j)\n            if (lifetimes_conflict(t_s[i], t_e[i], t_s[j], t_e[j]) &&"),
+    "best_plan_last_of_equals": ("if (extent[p] < extent[b]) b = p;", "if (extent[p] <= extent[b]) b = p;"),
+    "sort_descending": ("if (x->a != y->a) return x->a < y->a ? -1 : 1;", "if (x->a != y->a) return x->a < y->a ? 1 : -1;"),
+    "extent_forgets_size": ("if (a[i] + size[i] > top) top = a[i] + size[i];\n    }\n    free(spans);\n    *extent",
+                            "if (a[i] > top) top = a[i];\n    }\n    free(spans);\n    *extent"),
+}
+
+
+def _battery(oracle):
+    for name in pins.GOLDEN:
+        for method in ("allpairs", "lists"):
+            pins.test_hand_worked_examples(oracle, name, method)
+    pins.test_time_clique_gives_prefix_sums(oracle)
+    pins.test_time_disjoint_all_at_zero(oracle)
+    pins.test_equal_sizes_start_order_reaches_layer_count(oracle, 0)
+    pins.test_stack_discipline_reaches_lower_bound(oracle)
+    for seed in range(6):
+        pins.test_all_orders_reach_exact_optimum(oracle, seed)
+        pins.test_random_traces_valid_and_minimal(oracle, seed, False)
+        pins.test_validate_counts_planted_conflicts(oracle, seed)
+    pins.test_validate_known_single_conflict(oracle)
+    pins.test_best_plan_prefers_lowest_index(oracle)
+
+
+def test_battery_passes_on_the_real_oracle(oracle):
+    _battery(oracle)
+
+
+@pytest.mark.parametrize("name", sorted(MUTATIONS))
+def test_planted_mistake_is_caught(oracle, tmp_path, name):
+    old, new = MUTATIONS[name]
+    src = open(os.path.join(os.path.dirname(oracle.__file__), "stalloc_oracle.c")).read()
+    assert src.count(old) >= 1, "mutation target not found in the oracle source"
+    c_file = tmp_path / "mutant.c"
+    so_file = tmp_path / "mutant.so"
+    c_file.write_text(src.replace(old, new))
+    subprocess.check_call(["gcc", "-O2", "-std=c99", "-shared", "-fPIC", "-o", str(so_file), str(c_file)])
+    with oracle.use_library(str(so_file)):
+        with pytest.raises(AssertionError):
+            _battery(oracle)
