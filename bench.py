@@ -1,0 +1,171 @@
+#!/usr/bin/env python3
+"""Benchmark of the planning hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic trace and its candidate
+orders, all inputs already resident in device memory:
+    stalloc_plan (all P orders, best plan kept)
+ -> stalloc_validate (the best plan, all pairs)
+ -> stalloc_lower_bound.
+The headline value is placed requests x plans per second, n * P * steps / time.
+
+Prints ONE JSON line.  `roofline` describes the dominant kernel (the placement
+kernel): algorithmic bytes = 28 B per placement (order entry, request record,
+address written) plus one stored list entry per lifetime-overlapping pair and plan,
+divided by the kernel time measured with events on the launch stream.
+`cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload on
+this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+ENTRY_BYTES = 24            # bytes of one placed-block list entry as stored by the kernel
+PER_PLACEMENT_BYTES = 28    # 4 B order entry + 16 B request record + 8 B address written
+LDS_PEAK_GBS = 256 * 128 * 2.4          # 256 CUs x 128 B/clk x 2.4 GHz = 78 643 GB/s
+HBM_PEAK_GBS = 8000.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=2, help="trace configuration 1..5 (default: 2)")
+    ap.add_argument("--plans", type=int, default=0, help="override the number of orders (0 = the configuration's)")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0, help="CPU work budget of the oracle baseline")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (orders are independent and would be split "
+              "across GPUs, but no multi-GPU path exists); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2507_16274_amd as S
+    from workloads import CONFIGS, make_orderings, make_trace, trace_stats
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+
+    cfg = CONFIGS[args.config]
+    tr = make_trace(args.config)
+    stats = trace_stats(tr)
+    P = args.plans or cfg.n_orderings
+    orders_np = make_orderings(tr, P)
+    n = tr.n
+
+    size, ta, tf = S.trace_to_device(tr)
+    orders = torch.from_numpy(orders_np.view(np.int32)).cuda()
+    cache_plan, cache_val, cache_lb = {}, {}, {}
+    outs = {"offsets": torch.empty((P, n), dtype=torch.int64, device="cuda"),
+            "peaks": torch.empty(P, dtype=torch.int64, device="cuda"),
+            "best_offsets": torch.empty(n, dtype=torch.int64, device="cuda"),
+            "best_plan": torch.empty(1, dtype=torch.int32, device="cuda"),
+            "status": torch.empty(1, dtype=torch.int32, device="cuda")}
+
+    ev_pairs = []
+
+    def step(timed: bool):
+        if timed:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+        plan = S.stalloc_plan(size, ta, tf, tr.t_end, orders, out=outs, workspace_cache=cache_plan)
+        if timed:
+            e1.record()
+            ev_pairs.append((e0, e1))
+        val = S.stalloc_validate(size, ta, tf, tr.t_end, plan["best_offsets"].view(1, n), workspace_cache=cache_val)
+        lb = S.stalloc_lower_bound(size, ta, tf, tr.t_end, workspace_cache=cache_lb)
+        return plan, val, lb
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        plan, val, lb = step(True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    S.check_status(plan, "stalloc_plan")
+    S.check_status(val, "stalloc_validate")
+    S.check_status(lb, "stalloc_lower_bound")
+    conflicts = int(val["conflicts"].item())
+    lower_bound = int(lb["lower_bound"].item())
+    peaks = plan["peaks"].cpu().numpy().view(np.uint64)
+    best = int(plan["best_plan"].item())
+    best_peak = int(peaks[best])
+    if conflicts != 0 or best_peak < lower_bound or best_peak != int(peaks.min()):
+        print(f"bench.py: inconsistent result (conflicts={conflicts}, best={best_peak}, lb={lower_bound})", file=sys.stderr)
+        return 1
+
+    ms_per_step = elapsed / args.steps * 1e3
+    value = n * P * args.steps / elapsed
+    plan_ms = float(np.mean([a.elapsed_time(b) for a, b in ev_pairs]))
+    algo_bytes = PER_PLACEMENT_BYTES * n * P + ENTRY_BYTES * stats["E"] * P
+    in_lds = n <= int(S.lib.stalloc_plan_lds_capacity())
+    achieved = algo_bytes / (plan_ms * 1e-3) / 1e9
+    peak = LDS_PEAK_GBS if in_lds else HBM_PEAK_GBS
+    result = {
+        "metric": "placed requests x plans / s",
+        "value": value,
+        "unit": "requests*plans/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u64",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{args.config - 1}] {cfg.name}: {cfg.description}", "n": n, "P": P,
+                   "T": stats["T"], "E": stats["E"], "distinct_sizes": stats["distinct_sizes"],
+                   "step": "stalloc_plan(all orders) + stalloc_validate(best plan) + stalloc_lower_bound"},
+        "quality": {"lower_bound": lower_bound, "best_peak": best_peak, "best_plan": best,
+                    "lower_bound_over_peak": lower_bound / best_peak,
+                    "median_lower_bound_over_peak": float(lower_bound / np.median(peaks.astype(np.float64)))},
+        "roofline": {"bound": "lds" if in_lds else "hbm", "kernel": "plan_kernel",
+                     "achieved": achieved, "peak": peak, "unit": "GB/s", "frac": achieved / peak,
+                     "traffic": None, "kernel_ms": plan_ms, "algorithmic_bytes": algo_bytes,
+                     "hbm_floor_GBs": PER_PLACEMENT_BYTES * n * P / (plan_ms * 1e-3) / 1e9},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1))
+        lists = oracle.conflict_lists(tr.t_alloc, tr.t_free)
+        t1 = time.perf_counter()
+        oracle.plan_lists(tr.size, lists, orders_np[0])
+        one = time.perf_counter() - t1
+        sample = int(max(1, min(P, args.cpu_seconds / max(one, 1e-6))))
+        rows = np.linspace(0, P - 1, sample).astype(np.int64)
+        t1 = time.perf_counter()
+        a_cpu, e_cpu = oracle.plan_many(tr.size, tr.t_alloc, tr.t_free, orders_np[rows], threads=cores,
+                                        method="lists", lists=lists)
+        wall = time.perf_counter() - t1
+        if not np.array_equal(e_cpu, peaks[rows]):
+            print("bench.py: GPU extents differ from the oracle on the baseline sample", file=sys.stderr)
+            return 1
+        result["cpu_baseline"] = {"value": n * sample / wall, "unit": "requests*plans/s", "cores": cores,
+                                  "kind": "oracle",
+                                  "sample": f"{sample} of {P} orders (evenly spaced), conflict-list oracle, "
+                                            f"{wall:.2f} s wall on {cores} threads"}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,124 @@
+/*
+ * stalloc -- offline spatio-temporal placement of an allocation trace on one GPU.
+ *
+ * A trace is the list M of memory request events of one training iteration
+ * (Sec. 4): request i is the rectangle  size[i] bytes x [t_alloc[i], t_free[i]).
+ * A plan gives every request a start address (allocation decision d = m + (a),
+ * Sec. 5.1) such that no two decisions conflict in lifespan and in address range
+ * at the same time (the constraint of Sec. 5.1).  The extent of a plan is
+ * max_i (a_i + size_i) (Eq. 2, Eq. 6); memory efficiency is E = M_a / M_r (Eq. 1)
+ * with M_a the maximum over time of live bytes and M_r the extent.
+ *
+ * Conventions shared by all entry points
+ *   - Every data pointer is a DEVICE pointer owned by the caller; nothing is
+ *     allocated or freed by the library.  `stalloc_trace` itself and
+ *     `workspace_bytes` live in HOST memory.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t, NULL = default stream) of
+ *     the current device and is asynchronous: outputs are valid once the stream
+ *     has been synchronised.
+ *   - Query-then-call workspace: with workspace == NULL the required size is
+ *     written to *workspace_bytes and nothing else happens.  Otherwise
+ *     *workspace_bytes must be at least that size and `workspace` 256-byte aligned.
+ *   - Return value: a stalloc_status for everything the host can see (NULL
+ *     pointers, n == 0, P == 0, workspace too small, launch failure).  Defects only
+ *     visible on the device (size 0, t_alloc >= t_free, t_free > t_end, sum of sizes
+ *     >= 2^63, an order entry >= n) are written as a stalloc_status to
+ *     `device_status[0]` (0 when clean); when it is non-zero every other output of
+ *     that call is unspecified, but all kernels still terminate normally.
+ *   - Lifetimes and address ranges are half-open; no alignment is applied; byte
+ *     quantities are uint64_t; timestamps are uint32_t event ranks below t_end.
+ *   - Calls that share a workspace or outputs must be ordered by the caller.
+ */
+#ifndef STALLOC_H
+#define STALLOC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum stalloc_status {
+    STALLOC_OK = 0,
+    STALLOC_ERR_INVALID_ARG = 1, /* NULL pointer, n == 0, P == 0, size limits, workspace too small */
+    STALLOC_ERR_BAD_TRACE = 2,   /* size 0, t_alloc >= t_free or t_free > t_end                  */
+    STALLOC_ERR_OVERFLOW = 3,    /* sum of sizes >= 2^63: addresses could wrap                    */
+    STALLOC_ERR_NOMEM = 4,       /* reserved                                                      */
+    STALLOC_ERR_DEVICE = 5,      /* a HIP call failed                                             */
+    STALLOC_ERR_BAD_ORDER = 6    /* an entry of `orders` is >= n                                  */
+} stalloc_status;
+
+/* Structure-of-arrays trace (Sec. 4: s, t_s, t_e of every request event). */
+typedef struct stalloc_trace {
+    uint32_t n;              /* number of requests, 1 <= n < 2^31                          */
+    uint32_t t_end;          /* number of timestamps: every t_free <= t_end < 2^31         */
+    const uint64_t *size;    /* device [n], bytes, > 0                                     */
+    const uint32_t *t_alloc; /* device [n]                                                 */
+    const uint32_t *t_free;  /* device [n], t_alloc[i] < t_free[i] <= t_end                */
+} stalloc_trace;
+
+/*
+ * Batched greedy placement: P candidate placement orders are evaluated
+ * independently and the plan with the smallest extent is kept.
+ *
+ * For plan p the requests are taken in the order orders[p][0..n-1]; each one gets
+ * the lowest address at which it conflicts with no request placed before it in
+ * that plan ("lowest available address", Sec. 5.1; large-first orders let small
+ * requests fill the unused intervals of larger ones, Sec. 5.1 Global Planning).
+ * For a given trace and order the result is unique.
+ *
+ *   orders        device [P][n] uint32, each row a permutation of 0..n-1.  A row
+ *                 with an entry >= n sets device_status to STALLOC_ERR_BAD_ORDER; a
+ *                 row that repeats entries is not detected and yields an unspecified
+ *                 (but memory-safe) plan.
+ *   offsets       device [P][n], address of request i in plan p at offsets[p*n+i];
+ *                 may be NULL when only extents / the best plan are wanted.
+ *   peaks         device [P], extent of each plan (Eq. 2).
+ *   best_offsets  device [n], addresses of the best plan; may be NULL.
+ *   best_plan     device [1], index of the smallest extent, lowest index among equals.
+ *   device_status device [1], see above; must not be NULL.
+ */
+int stalloc_plan(const stalloc_trace *trace, const uint32_t *orders, uint32_t P,
+                 uint64_t *offsets, uint64_t *peaks, uint64_t *best_offsets,
+                 uint32_t *best_plan, uint32_t *device_status,
+                 void *workspace, size_t *workspace_bytes, void *hip_stream);
+
+/*
+ * Pairwise check of the constraint of Sec. 5.1 for P plans of one trace.
+ *
+ *   offsets     device [P][n]
+ *   conflicts   device [P], number of unordered pairs (i, j) whose lifetimes
+ *               overlap and whose address ranges overlap
+ *   first_pair  device [P][2], the lexicographically first such pair with i < j,
+ *               {0xFFFFFFFF, 0xFFFFFFFF} when the plan is valid
+ */
+int stalloc_validate(const stalloc_trace *trace, const uint64_t *offsets, uint32_t P,
+                     uint64_t *conflicts, uint32_t *first_pair, uint32_t *device_status,
+                     void *workspace, size_t *workspace_bytes, void *hip_stream);
+
+/*
+ * M_a of Eq. 1: the maximum over t in [0, t_end) of the bytes alive at t, found
+ * with a prefix sum over the allocation/release events.  No plan can have a
+ * smaller extent.
+ *
+ *   lower_bound device [1]
+ *   t_at_max    device [1], the earliest t reaching the maximum; may be NULL
+ */
+int stalloc_lower_bound(const stalloc_trace *trace, uint64_t *lower_bound, uint32_t *t_at_max,
+                        uint32_t *device_status,
+                        void *workspace, size_t *workspace_bytes, void *hip_stream);
+
+/* Human-readable name of a stalloc_status; never NULL.  Host memory, static storage. */
+const char *stalloc_status_string(int status);
+
+/*
+ * Number of requests up to which stalloc_plan keeps each plan's placed-block list
+ * in LDS (above it the list lives in the workspace).  Informational.
+ */
+uint32_t stalloc_plan_lds_capacity(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STALLOC_H */

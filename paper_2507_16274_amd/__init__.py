@@ -1,0 +1,190 @@
+"""Thin binding of libstalloc.so (include/stalloc.h): argument marshalling only.
+
+Every step of the planning path runs inside the HIP library; PyTorch is used for
+device memory and streams.  There is no CPU fallback: if the library has not been
+built (`python paper_2507_16274_amd/build.py`) importing the entry points fails.
+
+Tensors are CUDA/HIP tensors on the current device.  Byte quantities are int64
+tensors holding the library's uint64 bit patterns (all values stay below 2^63);
+timestamps, orders and indices are int32 tensors holding uint32 values below 2^31.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional
+
+import torch  # loaded first so that the HIP runtime already in the process is shared
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libstalloc.so")
+
+STATUS = {0: "STALLOC_OK", 1: "STALLOC_ERR_INVALID_ARG", 2: "STALLOC_ERR_BAD_TRACE", 3: "STALLOC_ERR_OVERFLOW",
+          4: "STALLOC_ERR_NOMEM", 5: "STALLOC_ERR_DEVICE", 6: "STALLOC_ERR_BAD_ORDER"}
+EXPORTS = ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_status_string",
+           "stalloc_plan_lds_capacity")
+
+
+class StallocError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        super().__init__(f"{where}: {STATUS.get(code, code)}")
+        self.code = code
+
+
+class _Trace(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_uint32), ("t_end", ctypes.c_uint32), ("size", ctypes.c_void_p),
+                ("t_alloc", ctypes.c_void_p), ("t_free", ctypes.c_void_p)]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: build it with `python paper_2507_16274_amd/build.py` "
+                          "(hipcc, gfx950); there is no fallback path")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, u32 = ctypes.c_void_p, ctypes.c_uint32
+    szp = ctypes.POINTER(ctypes.c_size_t)
+    tp = ctypes.POINTER(_Trace)
+    lib.stalloc_plan.argtypes = [tp, vp, u32, vp, vp, vp, vp, vp, vp, szp, vp]
+    lib.stalloc_validate.argtypes = [tp, vp, u32, vp, vp, vp, vp, szp, vp]
+    lib.stalloc_lower_bound.argtypes = [tp, vp, vp, vp, vp, szp, vp]
+    for name in ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound"):
+        getattr(lib, name).restype = ctypes.c_int
+    lib.stalloc_status_string.argtypes = [ctypes.c_int]
+    lib.stalloc_status_string.restype = ctypes.c_char_p
+    lib.stalloc_plan_lds_capacity.argtypes = []
+    lib.stalloc_plan_lds_capacity.restype = ctypes.c_uint32
+    return lib
+
+
+lib = _load()
+
+
+def _dev(t: Optional[torch.Tensor], dtype: torch.dtype, name: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name}: expected a contiguous {dtype} tensor on the GPU")
+    return t.data_ptr()
+
+
+def _trace(size: torch.Tensor, t_alloc: torch.Tensor, t_free: torch.Tensor, t_end: int) -> _Trace:
+    n = size.numel()
+    if t_alloc.numel() != n or t_free.numel() != n:
+        raise ValueError("size, t_alloc and t_free must have the same length")
+    return _Trace(n, int(t_end), _dev(size, torch.int64, "size"), _dev(t_alloc, torch.int32, "t_alloc"),
+                  _dev(t_free, torch.int32, "t_free"))
+
+
+def _stream(stream: Optional[torch.cuda.Stream]) -> int:
+    return (stream or torch.cuda.current_stream()).cuda_stream
+
+
+def _workspace(nbytes: int, device, cache: Optional[Dict]) -> torch.Tensor:
+    if cache is not None:
+        ws = cache.get("ws")
+        if ws is None or ws.numel() < nbytes:
+            ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+            cache["ws"] = ws
+        return ws
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise StallocError(rc, where)
+
+
+def stalloc_plan(size, t_alloc, t_free, t_end: int, orders, *, want_offsets: bool = True,
+                 want_best_offsets: bool = True, stream=None, workspace_cache: Optional[Dict] = None,
+                 out: Optional[Dict] = None) -> Dict[str, torch.Tensor]:
+    """Enqueue stalloc_plan; returns the (asynchronously filled) output tensors.
+
+    orders: int32 [P][n].  Outputs: offsets int64 [P][n] (None unless want_offsets),
+    peaks int64 [P], best_offsets int64 [n] (None unless want_best_offsets),
+    best_plan int32 [1], status int32 [1].  `out` may carry preallocated outputs.
+    """
+    tr = _trace(size, t_alloc, t_free, t_end)
+    if orders.dim() != 2 or orders.shape[1] != tr.n:
+        raise ValueError("orders must be [P][n]")
+    P, n, dev = orders.shape[0], tr.n, size.device
+    out = dict(out) if out else {}
+    if want_offsets and out.get("offsets") is None:
+        out["offsets"] = torch.empty((P, n), dtype=torch.int64, device=dev)
+    if not want_offsets:
+        out["offsets"] = None
+    if out.get("peaks") is None:
+        out["peaks"] = torch.empty(P, dtype=torch.int64, device=dev)
+    if want_best_offsets and out.get("best_offsets") is None:
+        out["best_offsets"] = torch.empty(n, dtype=torch.int64, device=dev)
+    if not want_best_offsets:
+        out["best_offsets"] = None
+    if out.get("best_plan") is None:
+        out["best_plan"] = torch.empty(1, dtype=torch.int32, device=dev)
+    if out.get("status") is None:
+        out["status"] = torch.empty(1, dtype=torch.int32, device=dev)
+    args = (ctypes.byref(tr), _dev(orders, torch.int32, "orders"), P,
+            _dev(out["offsets"], torch.int64, "offsets"), _dev(out["peaks"], torch.int64, "peaks"),
+            _dev(out["best_offsets"], torch.int64, "best_offsets"),
+            _dev(out["best_plan"], torch.int32, "best_plan"), _dev(out["status"], torch.int32, "status"))
+    need = ctypes.c_size_t(0)
+    _check(lib.stalloc_plan(*args, None, ctypes.byref(need), None), "stalloc_plan(workspace query)")
+    ws = _workspace(need.value, dev, workspace_cache)
+    have = ctypes.c_size_t(ws.numel())
+    _check(lib.stalloc_plan(*args, ws.data_ptr(), ctypes.byref(have), _stream(stream)), "stalloc_plan")
+    out["workspace"] = ws
+    return out
+
+
+def stalloc_validate(size, t_alloc, t_free, t_end: int, offsets, *, stream=None,
+                     workspace_cache: Optional[Dict] = None) -> Dict[str, torch.Tensor]:
+    """offsets int64 [P][n] -> conflicts int64 [P], first_pair int32 [P][2] (-1, -1 when valid)."""
+    tr = _trace(size, t_alloc, t_free, t_end)
+    if offsets.dim() != 2 or offsets.shape[1] != tr.n:
+        raise ValueError("offsets must be [P][n]")
+    P, dev = offsets.shape[0], size.device
+    out = {"conflicts": torch.empty(P, dtype=torch.int64, device=dev),
+           "first_pair": torch.empty((P, 2), dtype=torch.int32, device=dev),
+           "status": torch.empty(1, dtype=torch.int32, device=dev)}
+    args = (ctypes.byref(tr), _dev(offsets, torch.int64, "offsets"), P, out["conflicts"].data_ptr(),
+            out["first_pair"].data_ptr(), out["status"].data_ptr())
+    need = ctypes.c_size_t(0)
+    _check(lib.stalloc_validate(*args, None, ctypes.byref(need), None), "stalloc_validate(workspace query)")
+    ws = _workspace(need.value, dev, workspace_cache)
+    have = ctypes.c_size_t(ws.numel())
+    _check(lib.stalloc_validate(*args, ws.data_ptr(), ctypes.byref(have), _stream(stream)), "stalloc_validate")
+    out["workspace"] = ws
+    return out
+
+
+def stalloc_lower_bound(size, t_alloc, t_free, t_end: int, *, stream=None,
+                        workspace_cache: Optional[Dict] = None) -> Dict[str, torch.Tensor]:
+    """-> lower_bound int64 [1], t_at_max int32 [1], status int32 [1]."""
+    tr = _trace(size, t_alloc, t_free, t_end)
+    dev = size.device
+    out = {"lower_bound": torch.empty(1, dtype=torch.int64, device=dev),
+           "t_at_max": torch.empty(1, dtype=torch.int32, device=dev),
+           "status": torch.empty(1, dtype=torch.int32, device=dev)}
+    args = (ctypes.byref(tr), out["lower_bound"].data_ptr(), out["t_at_max"].data_ptr(), out["status"].data_ptr())
+    need = ctypes.c_size_t(0)
+    _check(lib.stalloc_lower_bound(*args, None, ctypes.byref(need), None), "stalloc_lower_bound(workspace query)")
+    ws = _workspace(need.value, dev, workspace_cache)
+    have = ctypes.c_size_t(ws.numel())
+    _check(lib.stalloc_lower_bound(*args, ws.data_ptr(), ctypes.byref(have), _stream(stream)), "stalloc_lower_bound")
+    out["workspace"] = ws
+    return out
+
+
+def check_status(out: Dict[str, torch.Tensor], where: str = "stalloc") -> None:
+    """Synchronising read of the device status word; raises StallocError when non-zero."""
+    code = int(out["status"].item())
+    if code != 0:
+        raise StallocError(code, where)
+
+
+def trace_to_device(trace, device="cuda"):
+    """numpy trace (size uint64, t_alloc/t_free uint32) -> (size, t_alloc, t_free) device tensors."""
+    import numpy as np
+    size = torch.from_numpy(np.ascontiguousarray(trace.size).view(np.int64)).to(device)
+    ta = torch.from_numpy(np.ascontiguousarray(trace.t_alloc).view(np.int32)).to(device)
+    tf = torch.from_numpy(np.ascontiguousarray(trace.t_free).view(np.int32)).to(device)
+    return size, ta, tf

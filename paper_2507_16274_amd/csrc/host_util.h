@@ -1,0 +1,66 @@
+// Host-side helpers shared by the entry points: argument checks, workspace carving,
+// cached device properties.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/stalloc.h"
+
+namespace stalloc {
+
+constexpr size_t kAlign = 256;
+
+inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
+
+struct DeviceInfo {
+    int device = -1;
+    int cus = 0;
+    size_t lds_per_block = 0;   // largest LDS allocation one workgroup may use
+};
+
+// Properties of the current device (queried once per device).
+inline bool device_info(DeviceInfo* out)
+{
+    static DeviceInfo cache[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+    DeviceInfo& c = cache[dev];
+    if (c.device != dev) {
+        int cus = 0, lds = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
+        if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return false;
+        c.cus = cus;
+        c.lds_per_block = (size_t)lds;
+        c.device = dev;
+    }
+    *out = c;
+    return true;
+}
+
+inline bool trace_args_ok(const stalloc_trace* tr)
+{
+    return tr && tr->n >= 1 && tr->n < 0x80000000u && tr->t_end >= 1 && tr->t_end < 0x80000000u &&
+           tr->size && tr->t_alloc && tr->t_free;
+}
+
+// Carves 256-byte aligned pieces out of a caller-provided workspace.
+struct Carver {
+    unsigned char* base;
+    size_t used = 0;
+    explicit Carver(void* p) : base(static_cast<unsigned char*>(p)) {}
+    template <typename T>
+    T* take(size_t count)
+    {
+        T* p = base ? reinterpret_cast<T*>(base + used) : nullptr;
+        used += align_up(count * sizeof(T));
+        return p;
+    }
+};
+
+// Shared device-side trace check (defined in trace_check.hip).
+// acc: device uint64_t[4] scratch {sum of high halves, sum of low halves, flags, unused}.
+void launch_trace_check(const stalloc_trace& tr, uint64_t* acc, uint32_t* device_status, hipStream_t stream);
+
+}  // namespace stalloc

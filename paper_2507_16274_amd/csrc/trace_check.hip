@@ -1,0 +1,72 @@
+// Device-side sanity pass over a trace: sizes > 0, t_alloc < t_free <= t_end, and the
+// sum of sizes below 2^63 so that no address can wrap (requests are the events
+// m = (s, t_s, t_e) of Sec. 4).  The verdict lands in the caller's device status word.
+#include "host_util.h"
+#include "wave.h"
+
+namespace stalloc {
+
+__global__ void trace_check_init(uint64_t* acc, uint32_t* status)
+{
+    if (threadIdx.x < 4) acc[threadIdx.x] = 0;
+    if (threadIdx.x == 0) *status = STALLOC_OK;
+}
+
+__global__ void __launch_bounds__(256)
+trace_check_scan(const uint64_t* __restrict__ size, const uint32_t* __restrict__ ta,
+                 const uint32_t* __restrict__ tf, uint32_t n, uint32_t t_end, uint64_t* acc)
+{
+    uint64_t hi = 0, lo = 0;
+    uint32_t bad = 0;
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+        uint64_t s = size[i];
+        uint32_t a = ta[i], f = tf[i];
+        bad |= (s == 0) | (a >= f) | (f > t_end);
+        hi += s >> 32;               // n < 2^31 terms below 2^32 each: cannot wrap
+        lo += s & 0xffffffffull;
+    }
+    hi = wave_sum64(hi);
+    lo = wave_sum64(lo);
+    uint64_t any_bad = __builtin_amdgcn_ballot_w64(bad != 0);
+    if (lane_id() == 0) {
+        atomicAdd((unsigned long long*)&acc[0], (unsigned long long)hi);
+        atomicAdd((unsigned long long*)&acc[1], (unsigned long long)lo);
+        if (any_bad) atomicOr((unsigned long long*)&acc[2], 1ull);
+    }
+}
+
+__global__ void trace_check_finish(const uint64_t* acc, uint32_t* status)
+{
+    if (threadIdx.x != 0) return;
+    uint32_t code = STALLOC_OK;
+    // total = acc[0] * 2^32 + acc[1]  >= 2^63  <=>  acc[0] + (acc[1] >> 32) >= 2^31
+    if (acc[0] + (acc[1] >> 32) >= (1ull << 31)) code = STALLOC_ERR_OVERFLOW;
+    if (acc[2] & 1ull) code = STALLOC_ERR_BAD_TRACE;
+    if (code != STALLOC_OK) atomicMax(status, code);
+}
+
+void launch_trace_check(const stalloc_trace& tr, uint64_t* acc, uint32_t* device_status, hipStream_t stream)
+{
+    hipLaunchKernelGGL(trace_check_init, dim3(1), dim3(64), 0, stream, acc, device_status);
+    uint32_t blocks = (tr.n + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(trace_check_scan, dim3(blocks), dim3(256), 0, stream, tr.size, tr.t_alloc, tr.t_free,
+                       tr.n, tr.t_end, acc);
+    hipLaunchKernelGGL(trace_check_finish, dim3(1), dim3(64), 0, stream, acc, device_status);
+}
+
+}  // namespace stalloc
+
+extern "C" const char* stalloc_status_string(int status)
+{
+    switch (status) {
+        case STALLOC_OK: return "STALLOC_OK";
+        case STALLOC_ERR_INVALID_ARG: return "STALLOC_ERR_INVALID_ARG";
+        case STALLOC_ERR_BAD_TRACE: return "STALLOC_ERR_BAD_TRACE";
+        case STALLOC_ERR_OVERFLOW: return "STALLOC_ERR_OVERFLOW";
+        case STALLOC_ERR_NOMEM: return "STALLOC_ERR_NOMEM";
+        case STALLOC_ERR_DEVICE: return "STALLOC_ERR_DEVICE";
+        case STALLOC_ERR_BAD_ORDER: return "STALLOC_ERR_BAD_ORDER";
+        default: return "STALLOC_UNKNOWN_STATUS";
+    }
+}

@@ -1,0 +1,92 @@
+// Wave64 building blocks for gfx950: DPP scans / reductions on 64-bit unsigned values.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace stalloc {
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ uint64_t umax64(uint64_t a, uint64_t b) { return a > b ? a : b; }
+__device__ __forceinline__ uint64_t umin64(uint64_t a, uint64_t b) { return a < b ? a : b; }
+
+// DPP controls (GFX9 encoding)
+constexpr int kDppRowShr1 = 0x111, kDppRowShr2 = 0x112, kDppRowShr4 = 0x114, kDppRowShr8 = 0x118;
+constexpr int kDppRowBcast15 = 0x142, kDppRowBcast31 = 0x143, kDppWaveShr1 = 0x138;
+
+// Lanes whose DPP source does not exist, or whose row is masked out, receive `fill`.
+template <int kCtrl, int kRowMask = 0xf>
+__device__ __forceinline__ uint64_t dpp64(uint64_t fill, uint64_t v)
+{
+    uint32_t lo = __builtin_amdgcn_update_dpp((uint32_t)fill, (uint32_t)v, kCtrl, kRowMask, 0xf, false);
+    uint32_t hi = __builtin_amdgcn_update_dpp((uint32_t)(fill >> 32), (uint32_t)(v >> 32), kCtrl, kRowMask, 0xf, false);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+__device__ __forceinline__ uint64_t readlane64(uint64_t v, int lane)
+{
+    uint32_t lo = __builtin_amdgcn_readlane((uint32_t)v, lane);
+    uint32_t hi = __builtin_amdgcn_readlane((uint32_t)(v >> 32), lane);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// Inclusive running maximum over the 64 lanes of a wave (all lanes must be active).
+__device__ __forceinline__ uint64_t wave_scan_max64(uint64_t v)
+{
+    v = umax64(v, dpp64<kDppRowShr1>(0, v));
+    v = umax64(v, dpp64<kDppRowShr2>(0, v));
+    v = umax64(v, dpp64<kDppRowShr4>(0, v));
+    v = umax64(v, dpp64<kDppRowShr8>(0, v));
+    v = umax64(v, dpp64<kDppRowBcast15, 0xa>(0, v));
+    v = umax64(v, dpp64<kDppRowBcast31, 0xc>(0, v));
+    return v;
+}
+
+// Value of the previous lane; lane 0 receives `fill`.
+__device__ __forceinline__ uint64_t wave_shift_up64(uint64_t v, uint64_t fill)
+{
+    return dpp64<kDppWaveShr1>(fill, v);
+}
+
+__device__ __forceinline__ uint64_t wave_max64(uint64_t v) { return readlane64(wave_scan_max64(v), 63); }
+
+// 32-bit helpers ------------------------------------------------------------
+__device__ __forceinline__ uint32_t wave_sum32(uint32_t v)
+{
+    v += __builtin_amdgcn_update_dpp(0u, v, kDppRowShr1, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0u, v, kDppRowShr2, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0u, v, kDppRowShr4, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0u, v, kDppRowShr8, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0u, v, kDppRowBcast15, 0xa, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0u, v, kDppRowBcast31, 0xc, 0xf, false);
+    return __builtin_amdgcn_readlane(v, 63);
+}
+
+__device__ __forceinline__ uint64_t wave_sum64(uint64_t v)
+{
+    v += dpp64<kDppRowShr1>(0, v);
+    v += dpp64<kDppRowShr2>(0, v);
+    v += dpp64<kDppRowShr4>(0, v);
+    v += dpp64<kDppRowShr8>(0, v);
+    v += dpp64<kDppRowBcast15, 0xa>(0, v);
+    v += dpp64<kDppRowBcast31, 0xc>(0, v);
+    return readlane64(v, 63);
+}
+
+__device__ __forceinline__ uint64_t wave_min64(uint64_t v)
+{
+    const uint64_t top = ~0ull;
+    v = umin64(v, dpp64<kDppRowShr1>(top, v));
+    v = umin64(v, dpp64<kDppRowShr2>(top, v));
+    v = umin64(v, dpp64<kDppRowShr4>(top, v));
+    v = umin64(v, dpp64<kDppRowShr8>(top, v));
+    v = umin64(v, dpp64<kDppRowBcast15, 0xa>(top, v));
+    v = umin64(v, dpp64<kDppRowBcast31, 0xc>(top, v));
+    return readlane64(v, 63);
+}
+
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
+__device__ __forceinline__ int wave_id() { return (int)(threadIdx.x >> 6); }
+
+}  // namespace stalloc

@@ -1,0 +1,255 @@
+"""Parity of the HIP library (through its C ABI) with the CPU oracle: bit-exact addresses,
+extents, conflict counts, first pairs and live-byte maxima on the same seeded inputs."""
+import os
+
+import numpy as np
+import pytest
+
+from helpers import count_conflicts_fast, load_golden, random_trace
+from workloads import CONFIGS, make_orderings, make_trace
+
+pytestmark = pytest.mark.gpu
+
+THREADS = min(16, os.cpu_count() or 1)
+NONE_PAIR = (0xFFFFFFFF, 0xFFFFFFFF)
+
+
+@pytest.fixture(scope="module")
+def S():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2507_16274_amd as S
+    return S
+
+
+class _T:
+    def __init__(self, size, ts, te, t_end):
+        self.size, self.t_alloc, self.t_free, self.t_end = size, ts, te, t_end
+
+
+def _gpu_plan(S, tr, orders, **kw):
+    import torch
+    size, ta, tf = S.trace_to_device(tr)
+    o = torch.from_numpy(np.ascontiguousarray(orders).view(np.int32)).cuda()
+    out = S.stalloc_plan(size, ta, tf, tr.t_end, o, **kw)
+    torch.cuda.synchronize()
+    res = {"status": int(out["status"].item())}
+    if res["status"] == 0:
+        res["peaks"] = out["peaks"].cpu().numpy().view(np.uint64)
+        res["best_plan"] = int(out["best_plan"].item())
+        if out["offsets"] is not None:
+            res["offsets"] = out["offsets"].cpu().numpy().view(np.uint64)
+        if out["best_offsets"] is not None:
+            res["best_offsets"] = out["best_offsets"].cpu().numpy().view(np.uint64)
+    return res
+
+
+def _gpu_validate(S, tr, offsets):
+    import torch
+    size, ta, tf = S.trace_to_device(tr)
+    off = torch.from_numpy(np.ascontiguousarray(offsets).view(np.int64)).cuda()
+    out = S.stalloc_validate(size, ta, tf, tr.t_end, off)
+    torch.cuda.synchronize()
+    assert int(out["status"].item()) == 0
+    return (out["conflicts"].cpu().numpy().view(np.uint64),
+            out["first_pair"].cpu().numpy().view(np.uint32))
+
+
+def _gpu_lower_bound(S, tr):
+    import torch
+    size, ta, tf = S.trace_to_device(tr)
+    out = S.stalloc_lower_bound(size, ta, tf, tr.t_end)
+    torch.cuda.synchronize()
+    return int(out["status"].item()), int(out["lower_bound"].cpu().numpy().view(np.uint64)[0]), int(out["t_at_max"].item())
+
+
+def _compare_plans(S, oracle, tr, orders, method="lists", lists=None):
+    got = _gpu_plan(S, tr, orders)
+    assert got["status"] == 0
+    a, ext = oracle.plan_many(tr.size, tr.t_alloc, tr.t_free, orders, threads=THREADS, method=method, lists=lists)
+    assert np.array_equal(got["peaks"], ext), "extents differ"
+    bad = np.nonzero((got["offsets"] != a).any(axis=1))[0]
+    assert bad.size == 0, f"addresses differ in plans {bad[:8]}"
+    best = oracle.best_plan(ext)
+    assert got["best_plan"] == best
+    assert np.array_equal(got["best_offsets"], a[best])
+    return got, a, ext
+
+
+# --------------------------------------------------------------------------- lower bound
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_lower_bound_configs(S, oracle, cfg):
+    tr = make_trace(cfg)
+    status, lb, t_at = _gpu_lower_bound(S, tr)
+    assert status == 0
+    assert (lb, t_at) == oracle.lower_bound(tr.size, tr.t_alloc, tr.t_free, tr.t_end, "sweep")
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_lower_bound_random_with_ties(S, oracle, seed):
+    rng = np.random.default_rng(700 + seed)
+    n = int(rng.integers(1, 9000))
+    size, ts, te, t_end = random_trace(rng, n, t_max=int(rng.integers(2, 5000)))
+    size = size * np.uint64(rng.integers(1, 2 ** 30))
+    tr = _T(size, ts, te, t_end)
+    status, lb, t_at = _gpu_lower_bound(S, tr)
+    assert status == 0
+    assert (lb, t_at) == oracle.lower_bound(size, ts, te, t_end, "sweep")
+
+
+def test_lower_bound_plateau_reports_earliest_time(S, oracle):
+    size = np.asarray([5, 5, 5], np.uint64)
+    ts = np.asarray([10, 4100, 9000], np.uint32)
+    te = np.asarray([20, 4200, 9100], np.uint32)
+    tr = _T(size, ts, te, 10000)
+    assert _gpu_lower_bound(S, tr) == (0, 5, 10)
+    assert oracle.lower_bound(size, ts, te, 10000) == (5, 10)
+
+
+# --------------------------------------------------------------------------- validate
+
+def test_validate_hand_worked_and_planted(S, oracle):
+    for name in ("running_max.txt", "hole_and_tie.txt", "gap_fit.txt"):
+        g = load_golden(name)
+        tr = _T(g["size"], g["t_s"], g["t_e"], g["t_end"])
+        offs = np.asarray([c["a"] for c in g["cases"]], np.uint64)
+        cnt, pair = _gpu_validate(S, tr, offs)
+        assert not cnt.any() and (pair == 0xFFFFFFFF).all()
+        zero = np.zeros_like(offs[:1])
+        cnt, pair = _gpu_validate(S, tr, zero)
+        want = oracle.validate(tr.size, tr.t_alloc, tr.t_free, zero[0])
+        assert (int(cnt[0]), tuple(int(x) for x in pair[0])) == want and want[0] > 0
+
+
+@pytest.mark.parametrize("cfg", [1, 2])
+def test_validate_configs_with_planted_conflicts(S, oracle, cfg):
+    tr = make_trace(cfg)
+    rng = np.random.default_rng(800 + cfg)
+    orders = make_orderings(tr, 6)
+    a, _ = oracle.plan_many(tr.size, tr.t_alloc, tr.t_free, orders, threads=THREADS, method="lists")
+    bad = a.copy()
+    for p in range(1, 6):                      # plan 0 stays valid
+        for i in rng.choice(tr.n, size=p * 3, replace=False):
+            bad[p, i] = rng.integers(0, int(a[p].max()) + 1)
+    cnt, pair = _gpu_validate(S, tr, bad)
+    for p in range(6):
+        want = oracle.validate(tr.size, tr.t_alloc, tr.t_free, bad[p])
+        assert (int(cnt[p]), tuple(int(x) for x in pair[p])) == want
+    assert int(cnt[0]) == 0 and tuple(int(x) for x in pair[0]) == NONE_PAIR
+    assert int(cnt[1:].sum()) > 0
+
+
+def test_validate_ragged_tile_sizes(S, oracle):
+    rng = np.random.default_rng(810)
+    for n in (1, 2, 255, 256, 257, 513, 1000):
+        size, ts, te, t_end = random_trace(rng, n, t_max=40)
+        tr = _T(size, ts, te, t_end)
+        offs = rng.integers(0, 64, size=(3, n)).astype(np.uint64)
+        cnt, pair = _gpu_validate(S, tr, offs)
+        for p in range(3):
+            want = oracle.validate(size, ts, te, offs[p])
+            assert (int(cnt[p]), tuple(int(x) for x in pair[p])) == want
+
+
+# --------------------------------------------------------------------------- plan
+
+@pytest.mark.parametrize("name", ["running_max.txt", "hole_and_tie.txt", "gap_fit.txt"])
+def test_plan_hand_worked_examples(S, name):
+    g = load_golden(name)
+    tr = _T(g["size"], g["t_s"], g["t_e"], g["t_end"])
+    orders = np.asarray([c["order"] for c in g["cases"]], np.uint32)
+    got = _gpu_plan(S, tr, orders)
+    assert got["status"] == 0
+    assert got["offsets"].tolist() == [c["a"] for c in g["cases"]]
+    assert got["peaks"].tolist() == [c["extent"] for c in g["cases"]]
+    status, lb, t_at = _gpu_lower_bound(S, tr)
+    assert (lb, t_at) == g["max_live"]
+
+
+def test_plan_config1_all_orderings(S, oracle):
+    tr = make_trace(1)
+    orders = make_orderings(tr, CONFIGS[1].n_orderings)
+    got, a, ext = _compare_plans(S, oracle, tr, orders, method="allpairs")
+    cnt, pair = _gpu_validate(S, tr, got["offsets"])
+    assert not cnt.any()
+
+
+def test_plan_config2_all_orderings(S, oracle):
+    """Full size of the benchmark workload: 6144 requests x 1024 orders, every address compared."""
+    tr = make_trace(2)
+    orders = make_orderings(tr, CONFIGS[2].n_orderings)
+    got, a, ext = _compare_plans(S, oracle, tr, orders, method="lists")
+    cnt, pair = _gpu_validate(S, tr, got["offsets"])
+    assert not cnt.any() and (pair == 0xFFFFFFFF).all()
+    status, lb, _ = _gpu_lower_bound(S, tr)
+    assert (got["peaks"] >= lb).all()
+    # no outputs wanted except extents and the best plan
+    lean = _gpu_plan(S, tr, orders, want_offsets=False)
+    assert np.array_equal(lean["peaks"], ext) and np.array_equal(lean["best_offsets"], got["best_offsets"])
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_plan_random_traces(S, oracle, seed):
+    """Ties in timestamps, single requests, list lengths around wave / workgroup / side-buffer sizes."""
+    rng = np.random.default_rng(900 + seed)
+    n = [1, 2, 63, 64, 65, 127, 129, 1023, 1025, 2049, 700, 3000][seed]
+    size, ts, te, t_end = random_trace(rng, n, t_max=max(4, n // 3), unique_times=(seed % 2 == 1))
+    size = size * np.uint64(512)
+    tr = _T(size, ts, te, t_end)
+    P = 9
+    orders = np.stack([rng.permutation(n) for _ in range(P)]).astype(np.uint32)
+    orders[0] = np.argsort(-size.astype(np.int64), kind="stable")
+    orders[1] = np.argsort(ts, kind="stable")
+    _compare_plans(S, oracle, tr, orders, method="allpairs")
+
+
+def test_plan_closed_forms(S):
+    rng = np.random.default_rng(950)
+    n = 300
+    size = (rng.integers(1, 1000, n) * 512).astype(np.uint64)
+    order = rng.permutation(n).astype(np.uint32)[None, :]
+    clique = _T(size, np.zeros(n, np.uint32), np.full(n, 7, np.uint32), 7)
+    got = _gpu_plan(S, clique, order)
+    expect = np.zeros(n, np.uint64)
+    expect[order[0]] = np.concatenate([[0], np.cumsum(size[order[0]])[:-1]]).astype(np.uint64)
+    assert np.array_equal(got["offsets"][0], expect) and int(got["peaks"][0]) == int(size.sum())
+    ts = (np.arange(n) * 2).astype(np.uint32)
+    disjoint = _T(size, ts, ts + np.uint32(2), 2 * n)
+    got = _gpu_plan(S, disjoint, order)
+    assert not got["offsets"].any() and int(got["peaks"][0]) == int(size.max())
+
+
+def test_plan_large_list_in_workspace(S, oracle):
+    """Config 3 does not fit the LDS-resident list: sampled orders, every address compared."""
+    tr = make_trace(3)
+    assert tr.n > S.lib.stalloc_plan_lds_capacity()
+    rows = [0, 1, 2, 3, 4, 1025, 2046, 2047]
+    orders = make_orderings(tr, CONFIGS[3].n_orderings, rows=rows)
+    lists = oracle.conflict_lists(tr.t_alloc, tr.t_free)
+    got, a, ext = _compare_plans(S, oracle, tr, orders, method="lists", lists=lists)
+    cnt, _ = _gpu_validate(S, tr, got["offsets"])
+    assert not cnt.any()
+
+
+def test_plan_reports_malformed_inputs(S):
+    g = load_golden("gap_fit.txt")
+    orders = np.asarray([g["cases"][0]["order"]], np.uint32)
+    size = g["size"].copy(); size[2] = 0
+    assert _gpu_plan(S, _T(size, g["t_s"], g["t_e"], g["t_end"]), orders)["status"] == 2
+    te = g["t_e"].copy(); te[1] = g["t_s"][1]
+    assert _gpu_plan(S, _T(g["size"], g["t_s"], te, g["t_end"]), orders)["status"] == 2
+    assert _gpu_plan(S, _T(g["size"], g["t_s"], g["t_e"], g["t_end"] - 1), orders)["status"] == 2
+    big = g["size"].copy(); big[:] = 2 ** 61
+    assert _gpu_plan(S, _T(big, g["t_s"], g["t_e"], g["t_end"]), orders)["status"] == 3
+    bad_order = orders.copy(); bad_order[0, 3] = 6
+    assert _gpu_plan(S, _T(g["size"], g["t_s"], g["t_e"], g["t_end"]), bad_order)["status"] == 6
+    assert _gpu_lower_bound(S, _T(size, g["t_s"], g["t_e"], g["t_end"]))[0] == 2
+
+
+def test_plan_is_deterministic(S):
+    tr = make_trace(2)
+    orders = make_orderings(tr, 64)
+    a = _gpu_plan(S, tr, orders)
+    b = _gpu_plan(S, tr, orders)
+    assert np.array_equal(a["offsets"], b["offsets"]) and np.array_equal(a["peaks"], b["peaks"])

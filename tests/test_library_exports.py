@@ -1,0 +1,69 @@
+"""CPU-side checks of the C-ABI library: it loads and exports what include/stalloc.h declares."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "stalloc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(stalloc_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_three_calls():
+    names = _declared_functions()
+    for must in ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    import paper_2507_16274_amd as S
+    for name in _declared_functions():
+        assert hasattr(S.lib, name), f"{name} declared in include/stalloc.h but not exported"
+    assert sorted(S.EXPORTS) == _declared_functions()
+
+
+def test_status_strings():
+    import paper_2507_16274_amd as S
+    text = open(os.path.join(ROOT, "include", "stalloc.h")).read()
+    for name, value in re.findall(r"(STALLOC_[A-Z_]+)\s*=\s*(\d+)", text):
+        assert S.lib.stalloc_status_string(int(value)).decode() == name
+        assert S.STATUS[int(value)] == name
+    assert S.lib.stalloc_status_string(99).decode() == "STALLOC_UNKNOWN_STATUS"
+
+
+def test_host_side_argument_errors_need_no_gpu():
+    """NULL trace / zero sizes are rejected before any HIP call."""
+    import paper_2507_16274_amd as S
+    need = ctypes.c_size_t(0)
+    assert S.lib.stalloc_plan(None, None, 1, None, None, None, None, None, None, ctypes.byref(need), None) == 1
+    tr = S._Trace(0, 10, 1, 1, 1)
+    assert S.lib.stalloc_lower_bound(ctypes.byref(tr), None, None, None, None, ctypes.byref(need), None) == 1
+    tr = S._Trace(4, 8, 1, 1, 1)
+    assert S.lib.stalloc_validate(ctypes.byref(tr), None, 0, None, None, None, None, ctypes.byref(need), None) == 1
+    # workspace queries for lower_bound / validate need no device
+    assert S.lib.stalloc_lower_bound(ctypes.byref(tr), None, None, None, None, ctypes.byref(need), None) == 0
+    assert need.value > 0
+    assert S.lib.stalloc_validate(ctypes.byref(tr), None, 3, None, None, None, None, ctypes.byref(need), None) == 0
+    assert need.value > 0
+
+
+def test_generators_match_the_configurations():
+    from workloads import CONFIGS, make_orderings, make_trace, trace_stats
+    import numpy as np
+    want_n = {1: 96, 2: 6144, 3: 19840}
+    for cfg, n in want_n.items():
+        tr = make_trace(cfg)
+        st = trace_stats(tr)
+        assert st["n"] == n and st["T"] == 2 * n
+        assert (tr.size % 512 == 0).all() and (tr.t_alloc < tr.t_free).all()
+        assert st["distinct_sizes"] <= 32           # few distinct sizes (Sec. 2.3, spatial regularity)
+        o = make_orderings(tr, 6)
+        assert all(np.array_equal(np.sort(r), np.arange(n)) for r in o)
+        assert np.array_equal(make_orderings(tr, 6), o)      # deterministic
+        size = tr.size.astype(np.int64)
+        assert (np.diff(size[o[0]]) <= 0).all()               # row 0: descending size
+        assert (np.diff(tr.t_alloc[o[2]].astype(np.int64)) > 0).all()   # row 2: by allocation time
+    assert CONFIGS[5].n_orderings == 4096
