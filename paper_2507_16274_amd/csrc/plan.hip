@@ -11,12 +11,15 @@
 //           running maximum of their end addresses gives "first address not covered so
 //           far", and the walk stops at the first block that starts at least `size` bytes
 //           above it (lowest fitting hole) or at the end of the list;
-//   pending freshly placed blocks go to a 64-entry side buffer instead of being inserted
-//           at once.  A candidate address from the scan is checked against the side buffer;
-//           on a conflict the scan is repeated from the largest conflicting end address
-//           (every feasible address at or above the candidate must clear it), until both
-//           agree.  When the side buffer is full it is merged into the sorted list in one
-//           pass (each block moves up by the number of pending blocks below it).
+//   pending freshly placed blocks go to a small side buffer, sorted by address and held in
+//           registers by every wave (one block per lane), instead of being inserted at once.
+//           Let f(c) be the lowest address >= c at which the request clears the pending
+//           blocks that conflict with its lifetime (a short walk over those blocks).  f is
+//           monotone and idempotent, so f(max(a, b)) = max(f(a), f(b)): replacing every
+//           listed block's end address e by f(e) before the running maximum, and starting
+//           from f(0), makes the scan honour the side buffer without a second pass.  When
+//           the side buffer is full it is merged into the sorted list in one pass (each
+//           listed block moves up by the number of pending blocks at or below it).
 // The sorted list lives in LDS when it fits (small traces) and in the workspace otherwise.
 #include "host_util.h"
 #include "wave.h"
@@ -26,7 +29,7 @@ namespace stalloc {
 constexpr int kPlanThreads = 1024;
 constexpr int kPlanWaves = kPlanThreads / kWave;
 constexpr int kBatch = 256;          // requests fetched per refill
-constexpr int kPending = 64;         // side-buffer entries (one wave)
+constexpr int kPending = 16;         // side-buffer entries (at most one wave)
 constexpr int kEntryBytes = 24;      // start address, end address, (t_alloc, t_free)
 constexpr uint64_t kNoHit = ~0ull;
 
@@ -39,9 +42,6 @@ struct PlanFixedLds {
     uint32_t rq_id[kBatch];
     uint64_t wave_top[kPlanWaves];
     uint64_t wave_hit[kPlanWaves];
-    uint64_t pend_lo[kPending];
-    uint64_t pend_hi[kPending];
-    uint2 pend_tt[kPending];
     uint64_t sorted_lo[kPending];
     uint64_t sorted_hi[kPending];
     uint2 sorted_tt[kPending];
@@ -67,15 +67,49 @@ struct BlockList {
     uint2* tt;
 };
 
-// Lowest address x >= `floor_addr` such that [x, x + s) meets no listed block whose lifetime
-// conflicts with [ta, tf).  The list is sorted by start address.  All threads of the
+// The side buffer: pending block q lives in lane q of every wave, ascending start address.
+struct Pending {
+    uint64_t lo, hi;
+    uint32_t ta, tf;
+};
+
+// f(c): lowest address >= c at which [c, c + s) clears the pending blocks selected by `mask`
+// (the ones whose lifetime conflicts with the request), walked in ascending start address.
+__device__ __forceinline__ uint64_t clear_pending(uint64_t c, uint64_t s, uint64_t mask, const Pending& pd)
+{
+    while (mask) {
+        const int q = __builtin_ctzll(mask);
+        mask &= mask - 1;
+        const uint64_t lo = readlane64(pd.lo, q), hi = readlane64(pd.hi, q);
+        if (lo < c + s && hi > c) c = hi;
+    }
+    return c;
+}
+
+// Sorted insertion of a block into the register-held side buffer (every wave does the same).
+__device__ __forceinline__ void pending_insert(Pending& pd, uint32_t pending, uint64_t x, uint64_t s,
+                                               uint32_t ta, uint32_t tf)
+{
+    const int lane = lane_id();
+    const uint64_t keep = __builtin_amdgcn_ballot_w64(lane < (int)pending && pd.lo <= x);
+    const int pos = __builtin_popcountll(keep);
+    const uint64_t up_lo = wave_shift_up64(pd.lo, 0), up_hi = wave_shift_up64(pd.hi, 0);
+    const uint32_t up_ta = __builtin_amdgcn_update_dpp(0u, pd.ta, kDppWaveShr1, 0xf, 0xf, false);
+    const uint32_t up_tf = __builtin_amdgcn_update_dpp(0u, pd.tf, kDppWaveShr1, 0xf, 0xf, false);
+    if (lane > pos) { pd.lo = up_lo; pd.hi = up_hi; pd.ta = up_ta; pd.tf = up_tf; }
+    if (lane == pos) { pd.lo = x; pd.hi = x + s; pd.ta = ta; pd.tf = tf; }
+}
+
+// Lowest address x such that [x, x + s) meets neither a listed block nor a pending block whose
+// lifetime conflicts with [ta, tf).  The list is sorted by start address.  All threads of the
 // workgroup must call this together; the result is uniform.
 __device__ __forceinline__ uint64_t
-scan_sorted_list(const BlockList& list, uint32_t count, uint64_t s, uint32_t ta, uint32_t tf,
-                 uint64_t floor_addr, PlanFixedLds& sh)
+lowest_fit(const BlockList& list, uint32_t count, uint64_t s, uint32_t ta, uint32_t tf,
+           const Pending& pd, uint32_t pending, PlanFixedLds& sh)
 {
     const int lane = lane_id(), wave = wave_id();
-    uint64_t covered = floor_addr;          // first address not known to be blocked
+    const uint64_t pmask = __builtin_amdgcn_ballot_w64(lane < (int)pending && pd.ta < tf && ta < pd.tf);
+    uint64_t covered = clear_pending(0, s, pmask, pd);      // first address not known to be blocked
     for (uint32_t base = 0;; base += kPlanThreads) {
         const uint32_t k = base + threadIdx.x;
         const bool valid = k < count;
@@ -83,7 +117,9 @@ scan_sorted_list(const BlockList& list, uint32_t count, uint64_t s, uint32_t ta,
         uint2 tt = make_uint2(0, 0);
         if (valid) { lo = list.lo[k]; hi = list.hi[k]; tt = list.tt[k]; }
         const bool conflict = valid && tt.x < tf && ta < tt.y;
-        const uint64_t incl = wave_scan_max64(conflict ? hi : 0);
+        uint64_t reach = conflict ? hi : 0;
+        if (pmask) reach = clear_pending(reach, s, pmask, pd);
+        const uint64_t incl = wave_scan_max64(reach);
         const uint64_t excl = wave_shift_up64(incl, 0);
         if (lane == kWave - 1) sh.wave_top[wave] = incl;
         __syncthreads();
@@ -108,38 +144,6 @@ scan_sorted_list(const BlockList& list, uint32_t count, uint64_t s, uint32_t ta,
         if (answer != kNoHit) return answer;
         covered = all;
         if (base + kPlanThreads >= count) return covered;
-    }
-}
-
-// Largest end address among pending blocks that conflict with the request at address x
-// (0 when there is none; an end address of a conflicting block is always > x >= 0).
-__device__ __forceinline__ uint64_t
-pending_conflict(const PlanFixedLds& sh, uint32_t pending, uint64_t x, uint64_t s, uint32_t ta, uint32_t tf)
-{
-    const int lane = lane_id();
-    uint64_t hi = 0;
-    if (lane < (int)pending) {
-        uint2 tt = sh.pend_tt[lane];
-        uint64_t lo = sh.pend_lo[lane], h = sh.pend_hi[lane];
-        if (tt.x < tf && ta < tt.y && lo < x + s && h > x) hi = h;
-    }
-    return wave_max64(hi);
-}
-
-// Sorts the pending blocks by (start address, slot) into sh.sorted_*; wave 0 only.
-__device__ __forceinline__ void sort_pending(PlanFixedLds& sh, uint32_t pending)
-{
-    const int lane = lane_id();
-    if (wave_id() == 0 && lane < (int)pending) {
-        const uint64_t lo = sh.pend_lo[lane];
-        uint32_t rank = 0;
-        for (uint32_t q = 0; q < pending; ++q) {
-            uint64_t other = sh.pend_lo[q];
-            rank += (other < lo) || (other == lo && q < (uint32_t)lane);
-        }
-        sh.sorted_lo[rank] = lo;
-        sh.sorted_hi[rank] = sh.pend_hi[lane];
-        sh.sorted_tt[rank] = sh.pend_tt[lane];
     }
 }
 
@@ -196,6 +200,7 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanParams prm)
         uint64_t* out = prm.offsets ? prm.offsets + (size_t)p * n : nullptr;
         uint64_t peak = 0;
         uint32_t count = 0, pending = 0;
+        Pending pd = {0, 0, 0, 0};
 
         for (uint32_t r0 = 0; r0 < n; r0 += kBatch) {
             const uint32_t nb = n - r0 < (uint32_t)kBatch ? n - r0 : (uint32_t)kBatch;
@@ -214,26 +219,19 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanParams prm)
                 const uint64_t s = sh.rq_size[b];
                 const uint32_t ta = sh.rq_ta[b], tf = sh.rq_tf[b];
 
-                uint64_t x = scan_sorted_list(list, count, s, ta, tf, 0, sh);
-                for (;;) {
-                    const uint64_t bump = pending_conflict(sh, pending, x, s, ta, tf);
-                    if (bump == 0) break;
-                    x = scan_sorted_list(list, count, s, ta, tf, bump, sh);
-                }
-
+                const uint64_t x = lowest_fit(list, count, s, ta, tf, pd, pending, sh);
                 peak = umax64(peak, x + s);
-                if (threadIdx.x == 0) {
-                    sh.rq_addr[b] = x;
-                    sh.pend_lo[pending] = x;
-                    sh.pend_hi[pending] = x + s;
-                    sh.pend_tt[pending] = make_uint2(ta, tf);
-                }
+                if (threadIdx.x == 0) sh.rq_addr[b] = x;
+                pending_insert(pd, pending, x, s, ta, tf);
                 ++pending;
 
                 if (pending == kPending && r0 + b + 1 < n) {
                     // merge the side buffer into the sorted list
-                    __syncthreads();
-                    sort_pending(sh, pending);
+                    if (threadIdx.x < pending) {             // wave 0 publishes the (sorted) side buffer
+                        sh.sorted_lo[threadIdx.x] = pd.lo;
+                        sh.sorted_hi[threadIdx.x] = pd.hi;
+                        sh.sorted_tt[threadIdx.x] = make_uint2(pd.ta, pd.tf);
+                    }
                     __syncthreads();
                     if constexpr (kLds) {
                         constexpr int kMaxPer = 7;           // capacity <= 7 * kPlanThreads entries
