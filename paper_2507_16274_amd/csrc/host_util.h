@@ -60,7 +60,12 @@ struct Carver {
 };
 
 // Shared device-side trace check (defined in trace_check.hip).
-// acc: device uint64_t[4] scratch {sum of high halves, sum of low halves, flags, unused}.
+// acc: device uint64_t[kAccWords] scratch {sum of high halves, sum of low halves, flags,
+// OR of all sizes, mode}.  mode = log2(address granule) | kModeNarrow when 32-bit granule
+// counts can hold every address.
+constexpr int kAccWords = 8;
+constexpr int kAccMode = 4;
+constexpr uint64_t kModeNarrow = 1ull << 8;
 void launch_trace_check(const stalloc_trace& tr, uint64_t* acc, uint32_t* device_status, hipStream_t stream);
 
 }  // namespace stalloc

@@ -182,7 +182,7 @@ extern "C" int stalloc_lower_bound(const stalloc_trace* tr, uint64_t* lower_boun
     const uint32_t t_end = tr->t_end;
     const uint32_t tiles = (t_end + kLbTile - 1) / kLbTile;
     Carver cv(workspace);
-    uint64_t* acc = cv.take<uint64_t>(4);
+    uint64_t* acc = cv.take<uint64_t>(kAccWords);
     int64_t* net = cv.take<int64_t>((size_t)t_end + 1);
     int64_t* tile_sum = cv.take<int64_t>(tiles);
     LbBest* tile_best = cv.take<LbBest>(tiles);

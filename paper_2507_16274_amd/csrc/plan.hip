@@ -5,22 +5,32 @@
 // range at once.  Extent of a plan = max(a + s) (Eq. 2).
 //
 // Per plan the workgroup keeps the list of placed blocks SORTED BY ADDRESS, so that no
-// sorting is needed when a request is placed:
-//   scan    the sorted list is walked in address order, 64 blocks per wave; a ballot-free
-//           compare keeps the blocks whose lifetime conflicts with the request, a wave64
-//           running maximum of their end addresses gives "first address not covered so
-//           far", and the walk stops at the first block that starts at least `size` bytes
-//           above it (lowest fitting hole) or at the end of the list;
-//   pending freshly placed blocks go to a small side buffer, sorted by address and held in
-//           registers by every wave (one block per lane), instead of being inserted at once.
-//           Let f(c) be the lowest address >= c at which the request clears the pending
-//           blocks that conflict with its lifetime (a short walk over those blocks).  f is
-//           monotone and idempotent, so f(max(a, b)) = max(f(a), f(b)): replacing every
-//           listed block's end address e by f(e) before the running maximum, and starting
-//           from f(0), makes the scan honour the side buffer without a second pass.  When
-//           the side buffer is full it is merged into the sorted list in one pass (each
-//           listed block moves up by the number of pending blocks at or below it).
-// The sorted list lives in LDS when it fits (small traces) and in the workspace otherwise.
+// sorting is needed when a request is placed.
+//
+//   scan     Each wave owns a run of consecutive list entries and walks it 64 entries at a
+//            time.  A compare keeps the blocks whose lifetime conflicts with the request; a
+//            wave64 running maximum (DPP) of their end addresses is "first address not
+//            covered so far"; the request fits in front of the first block that starts at
+//            least `size` above that value.  Waves exchange their chunk maxima through LDS
+//            (one barrier), evaluate their candidate stops against everything below them,
+//            and publish the first hit (second barrier).
+//   pending  Freshly placed blocks go to a small side buffer, sorted by address and held in
+//            registers by every wave (one block per lane), instead of being inserted at
+//            once.  Let f(c) be the lowest address >= c at which the request clears the
+//            pending blocks that conflict with its lifetime.  f is monotone and idempotent,
+//            hence f(max(a, b)) = max(f(a), f(b)): replacing every listed block's end e by
+//            f(e) before the running maximum, and starting from f(0), makes the scan honour
+//            the side buffer exactly.  f is evaluated against "zones" -- maximal groups of
+//            conflicting pending blocks whose holes are too small for the request.
+//   merge    When the side buffer is full, one pass moves every listed block up by the
+//            number of pending blocks at or below it and drops the pending blocks in place.
+//
+// Addresses are multiples of the largest power of two dividing all sizes.  When the sum of
+// sizes, in those granules, stays below 2^31 the list holds 32-bit granule counts (half the
+// LDS bytes and single-instruction max/compare); otherwise 64-bit byte addresses.  The trace
+// check leaves that decision in device memory, both instantiations are enqueued and the one
+// that does not apply returns at once.  The list lives in LDS when it fits and in the
+// workspace otherwise.
 #include "host_util.h"
 #include "wave.h"
 
@@ -29,22 +39,25 @@ namespace stalloc {
 constexpr int kPlanThreads = 1024;
 constexpr int kPlanWaves = kPlanThreads / kWave;
 constexpr int kBatch = 256;          // requests fetched per refill
-constexpr int kPending = 16;         // side-buffer entries (at most one wave)
-constexpr int kEntryBytes = 24;      // start address, end address, (t_alloc, t_free)
-constexpr uint64_t kNoHit = ~0ull;
+constexpr int kMaxSub = 10;          // 64-entry steps one wave takes between two barriers
 
-// LDS that does not depend on the list capacity
-struct PlanFixedLds {
+template <typename Addr> struct Span { Addr lo, hi; };     // [lo, hi) in address units
+
+template <typename Addr> struct Top;
+template <> struct Top<uint32_t> { static constexpr uint32_t value = 0xffffffffu; };
+template <> struct Top<uint64_t> { static constexpr uint64_t value = ~0ull; };
+
+template <typename Addr, int kPend>
+struct PlanLds {
     uint64_t rq_size[kBatch];
     uint64_t rq_addr[kBatch];
     uint32_t rq_ta[kBatch];
     uint32_t rq_tf[kBatch];
     uint32_t rq_id[kBatch];
-    uint64_t wave_top[kPlanWaves];
-    uint64_t wave_hit[kPlanWaves];
-    uint64_t sorted_lo[kPending];
-    uint64_t sorted_hi[kPending];
-    uint2 sorted_tt[kPending];
+    Addr wave_top[kPlanWaves];
+    Addr wave_hit[kPlanWaves];
+    Span<Addr> pend_span[kPend];
+    uint2 pend_life[kPend];
 };
 
 struct PlanParams {
@@ -55,152 +68,263 @@ struct PlanParams {
     uint64_t* offsets;       // [P][n] or nullptr
     uint64_t* peaks;         // [P]
     uint32_t* status;
-    unsigned char* slabs;    // global variant: gridDim.x slabs of 2 * n * kEntryBytes
+    const uint64_t* acc;     // trace-check accumulators (mode word)
+    unsigned char* slabs;    // list in the workspace: gridDim.x slabs of 2 * n entries
     uint32_t n;
     uint32_t P;
-    uint32_t cap;            // LDS variant: list capacity in entries
 };
 
+template <typename Addr>
 struct BlockList {
-    uint64_t* lo;
-    uint64_t* hi;
-    uint2* tt;
+    Span<Addr>* span;
+    uint2* life;             // (t_alloc, t_free)
 };
+
+template <typename Addr> constexpr size_t entry_bytes() { return sizeof(Span<Addr>) + sizeof(uint2); }
 
 // The side buffer: pending block q lives in lane q of every wave, ascending start address.
+template <typename Addr>
 struct Pending {
-    uint64_t lo, hi;
+    Addr lo, hi;
     uint32_t ta, tf;
 };
 
-// f(c): lowest address >= c at which [c, c + s) clears the pending blocks selected by `mask`
-// (the ones whose lifetime conflicts with the request), walked in ascending start address.
-__device__ __forceinline__ uint64_t clear_pending(uint64_t c, uint64_t s, uint64_t mask, const Pending& pd)
+// Zones of the side buffer for one request: groups of lifetime-conflicting pending blocks.
+// A zone starts at a conflicting block that leaves a hole of at least `s` above everything
+// conflicting before it; it ends at the running maximum of end addresses.
+template <typename Addr>
+struct Zones {
+    uint64_t starts;     // lanes that open a zone
+    Addr lo;             // per lane: start address of the pending block
+    Addr reach_before;   // per lane: max end of conflicting pending blocks in lower lanes
+    Addr reach_all;      // uniform: max end of all conflicting pending blocks
+};
+
+template <typename Addr>
+__device__ __forceinline__ Zones<Addr> make_zones(const Pending<Addr>& pd, uint32_t pending, Addr s,
+                                                  uint32_t ta, uint32_t tf)
 {
-    while (mask) {
-        const int q = __builtin_ctzll(mask);
-        mask &= mask - 1;
-        const uint64_t lo = readlane64(pd.lo, q), hi = readlane64(pd.hi, q);
-        if (lo < c + s && hi > c) c = hi;
+    const int lane = lane_id();
+    const bool conflict = lane < (int)pending && pd.ta < tf && ta < pd.tf;
+    const Addr incl = wave_scan_max(conflict ? pd.hi : (Addr)0);
+    Zones<Addr> z;
+    z.lo = pd.lo;
+    z.reach_before = wave_shift_up(incl, (Addr)0);
+    z.reach_all = read_lane(incl, kWave - 1);
+    const uint64_t conflicts = __builtin_amdgcn_ballot_w64(conflict);
+    const uint64_t lower = conflicts & ((1ull << lane) - 1);
+    z.starts = __builtin_amdgcn_ballot_w64(conflict && (lower == 0 || pd.lo >= z.reach_before + s));
+    return z;
+}
+
+// f(e): lowest address >= e at which [e, e + s) clears every zone.
+template <typename Addr>
+__device__ __forceinline__ Addr clear_zones(Addr e, Addr s, const Zones<Addr>& z)
+{
+    uint64_t m = z.starts;
+    if (m == 0) return e;
+    const Addr es = e + s;
+    while (m) {
+        const int q = __builtin_ctzll(m);
+        m &= m - 1;
+        const Addr zone_lo = read_lane(z.lo, q);
+        const Addr zone_hi = m ? read_lane(z.reach_before, __builtin_ctzll(m)) : z.reach_all;
+        if (es > zone_lo && e < zone_hi) e = zone_hi;
     }
-    return c;
+    return e;
 }
 
 // Sorted insertion of a block into the register-held side buffer (every wave does the same).
-__device__ __forceinline__ void pending_insert(Pending& pd, uint32_t pending, uint64_t x, uint64_t s,
+template <typename Addr>
+__device__ __forceinline__ void pending_insert(Pending<Addr>& pd, uint32_t pending, Addr x, Addr s,
                                                uint32_t ta, uint32_t tf)
 {
     const int lane = lane_id();
     const uint64_t keep = __builtin_amdgcn_ballot_w64(lane < (int)pending && pd.lo <= x);
     const int pos = __builtin_popcountll(keep);
-    const uint64_t up_lo = wave_shift_up64(pd.lo, 0), up_hi = wave_shift_up64(pd.hi, 0);
-    const uint32_t up_ta = __builtin_amdgcn_update_dpp(0u, pd.ta, kDppWaveShr1, 0xf, 0xf, false);
-    const uint32_t up_tf = __builtin_amdgcn_update_dpp(0u, pd.tf, kDppWaveShr1, 0xf, 0xf, false);
+    const Addr up_lo = wave_shift_up(pd.lo, (Addr)0), up_hi = wave_shift_up(pd.hi, (Addr)0);
+    const uint32_t up_ta = wave_shift_up(pd.ta, 0u), up_tf = wave_shift_up(pd.tf, 0u);
     if (lane > pos) { pd.lo = up_lo; pd.hi = up_hi; pd.ta = up_ta; pd.tf = up_tf; }
     if (lane == pos) { pd.lo = x; pd.hi = x + s; pd.ta = ta; pd.tf = tf; }
 }
 
 // Lowest address x such that [x, x + s) meets neither a listed block nor a pending block whose
-// lifetime conflicts with [ta, tf).  The list is sorted by start address.  All threads of the
-// workgroup must call this together; the result is uniform.
-__device__ __forceinline__ uint64_t
-lowest_fit(const BlockList& list, uint32_t count, uint64_t s, uint32_t ta, uint32_t tf,
-           const Pending& pd, uint32_t pending, PlanFixedLds& sh)
+// lifetime conflicts with [ta, tf).  All threads of the workgroup call this together; the
+// result is uniform.
+template <typename Addr, typename Lds>
+__device__ __forceinline__ Addr lowest_fit(const BlockList<Addr>& list, uint32_t count, Addr s, uint32_t ta,
+                                           uint32_t tf, const Pending<Addr>& pd, uint32_t pending, Lds& sh)
 {
     const int lane = lane_id(), wave = wave_id();
-    const uint64_t pmask = __builtin_amdgcn_ballot_w64(lane < (int)pending && pd.ta < tf && ta < pd.tf);
-    uint64_t covered = clear_pending(0, s, pmask, pd);      // first address not known to be blocked
-    for (uint32_t base = 0;; base += kPlanThreads) {
-        const uint32_t k = base + threadIdx.x;
-        const bool valid = k < count;
-        uint64_t lo = 0, hi = 0;
-        uint2 tt = make_uint2(0, 0);
-        if (valid) { lo = list.lo[k]; hi = list.hi[k]; tt = list.tt[k]; }
-        const bool conflict = valid && tt.x < tf && ta < tt.y;
-        uint64_t reach = conflict ? hi : 0;
-        if (pmask) reach = clear_pending(reach, s, pmask, pd);
-        const uint64_t incl = wave_scan_max64(reach);
-        const uint64_t excl = wave_shift_up64(incl, 0);
-        if (lane == kWave - 1) sh.wave_top[wave] = incl;
-        __syncthreads();
-        uint64_t below = covered, all = covered;
+    const Zones<Addr> zones = make_zones(pd, pending, s, ta, tf);
+    Addr covered = clear_zones((Addr)0, s, zones);          // first address not known to be blocked
+    constexpr Addr kNoHit = Top<Addr>::value;
+
+    for (uint32_t base = 0;;) {
+        const uint32_t left = count - base;
+        uint32_t sub = (left + kPlanThreads - 1) / kPlanThreads;   // 64-entry steps per wave in this pass
+        if (sub > (uint32_t)kMaxSub) sub = kMaxSub;
+        if (sub == 0) sub = 1;
+        const uint32_t chunk0 = base + (uint32_t)wave * kWave * sub;
+
+        Addr lo_keep[kMaxSub], before_keep[kMaxSub];
+        uint32_t maybe = 0;              // steps in which some lane could be a stop
+        Addr run = 0;                    // running maximum inside this wave's chunk
 #pragma unroll
-        for (int w = 0; w < kPlanWaves; ++w) {
-            uint64_t t = sh.wave_top[w];
-            all = umax64(all, t);
-            if (w < wave) below = umax64(below, t);
+        for (int j = 0; j < kMaxSub; ++j) {
+            lo_keep[j] = 0;
+            before_keep[j] = 0;
+            if ((uint32_t)j < sub) {
+                const uint32_t k = chunk0 + j * kWave + lane;
+                const bool valid = k < count;
+                Span<Addr> sp = {0, 0};
+                uint2 lf = make_uint2(0, 0);
+                if (valid) { sp = list.span[k]; lf = list.life[k]; }
+                const bool conflict = valid && lf.x < tf && ta < lf.y;
+                const Addr reach = clear_zones(conflict ? sp.hi : (Addr)0, s, zones);
+                const Addr incl = wave_scan_max(reach);
+                const Addr before = umax(run, wave_shift_up(incl, (Addr)0));
+                lo_keep[j] = sp.lo;                   // 0 for lanes past the end: never a stop (s > 0)
+                before_keep[j] = before;
+                if (__builtin_amdgcn_ballot_w64(sp.lo >= before + s)) maybe |= 1u << j;
+                run = umax(run, read_lane(incl, kWave - 1));
+            }
         }
-        const uint64_t before = umax64(below, excl);      // covered up to here when block k is reached
-        const bool stop = valid && lo >= before + s;       // hole [before, lo) is large enough
-        const uint64_t stops = __builtin_amdgcn_ballot_w64(stop);
-        if (lane == 0) sh.wave_hit[wave] = stops ? readlane64(before, __builtin_ctzll(stops)) : kNoHit;
+        if (lane == 0) sh.wave_top[wave] = run;
         __syncthreads();
-        uint64_t answer = kNoHit;
+
+        // maxima of the chunks below this wave, and of all chunks
+        const Addr tops = row_scan_max(lane < kPlanWaves ? sh.wave_top[lane] : (Addr)0);
+        const Addr below = umax(covered, wave > 0 ? read_lane(tops, wave - 1) : (Addr)0);
+        const Addr all = umax(covered, read_lane(tops, kPlanWaves - 1));
+        Addr hit = kNoHit;
 #pragma unroll
-        for (int w = kPlanWaves - 1; w >= 0; --w) {
-            uint64_t h = sh.wave_hit[w];
-            if (h != kNoHit) answer = h;
+        for (int j = 0; j < kMaxSub; ++j) {
+            if (hit == kNoHit && (maybe & (1u << j))) {
+                const Addr before = umax(below, before_keep[j]);
+                const uint64_t stops = __builtin_amdgcn_ballot_w64(lo_keep[j] >= before + s);
+                if (stops) hit = read_lane(before, __builtin_ctzll(stops));
+            }
         }
-        if (answer != kNoHit) return answer;
+        if (lane == 0) sh.wave_hit[wave] = hit;
+        __syncthreads();
+        const Addr h = lane < kPlanWaves ? sh.wave_hit[lane] : kNoHit;
+        const uint64_t hits = __builtin_amdgcn_ballot_w64(h != kNoHit);
+        if (hits) return read_lane(h, __builtin_ctzll(hits));
         covered = all;
-        if (base + kPlanThreads >= count) return covered;
+        base += kPlanThreads * sub;
+        if (base >= count) return covered;
     }
 }
 
-// Number of sorted pending blocks with start address <= lo.
-__device__ __forceinline__ uint32_t pending_at_or_below(const PlanFixedLds& sh, uint32_t pending, uint64_t lo)
+// Number of pending blocks (sorted, one per lane) whose start address is <= lo.
+template <typename Addr>
+__device__ __forceinline__ uint32_t pending_at_or_below(const Pending<Addr>& pd, uint32_t pending, Addr lo)
 {
-    uint32_t a = 0, b = pending;
-    while (a < b) {
-        uint32_t m = (a + b) >> 1;
-        if (sh.sorted_lo[m] <= lo) a = m + 1; else b = m;
-    }
-    return a;
+    uint32_t c = 0;
+    for (uint32_t q = 0; q < pending; ++q) c += read_lane(pd.lo, (int)q) <= lo;
+    return c;
 }
 
-// Number of listed blocks with start address < lo.
-__device__ __forceinline__ uint32_t listed_below(const uint64_t* list_lo, uint32_t count, uint64_t lo)
+// Merges the side buffer into the sorted list.  Listed block k moves to k + c_k, where c_k is
+// the number of pending blocks at or below its start address; pending block q lands at
+// k + q in front of the first listed block k with c_k > q (or behind the last one).
+template <typename Addr, bool kLds, typename Lds>
+__device__ __forceinline__ void merge_pending(BlockList<Addr>& list, BlockList<Addr>& spare, uint32_t count,
+                                              const Pending<Addr>& pd, uint32_t pending, Lds& sh)
 {
-    uint32_t a = 0, b = count;
-    while (a < b) {
-        uint32_t m = (a + b) >> 1;
-        if (list_lo[m] < lo) a = m + 1; else b = m;
+    const int lane = lane_id(), wave = wave_id();
+    if (threadIdx.x < pending) {                 // wave 0 publishes the side buffer for the writers
+        sh.pend_span[threadIdx.x] = Span<Addr>{pd.lo, pd.hi};
+        sh.pend_life[threadIdx.x] = make_uint2(pd.ta, pd.tf);
     }
-    return a;
+    if constexpr (!kLds) __syncthreads();
+    BlockList<Addr>& dst = kLds ? list : spare;
+    for (uint32_t base = 0; base <= count;) {    // "<=": the position just past the end takes the tail
+        const uint32_t left = count + 1 - base;
+        uint32_t sub = (left + kPlanThreads - 1) / kPlanThreads;
+        if (sub > (uint32_t)kMaxSub) sub = kMaxSub;
+        const uint32_t chunk0 = base + (uint32_t)wave * kWave * sub;
+
+        Span<Addr> sp[kMaxSub];
+        uint2 lf[kMaxSub];
+        uint32_t c_here[kMaxSub], c_prev[kMaxSub];
+        // pending blocks at or below the entry in front of this wave's chunk
+        uint32_t carry = 0;
+        if (chunk0 > 0 && chunk0 - 1 < count) carry = pending_at_or_below(pd, pending, list.span[chunk0 - 1].lo);
+        else if (chunk0 > count) carry = pending;
+#pragma unroll
+        for (int j = 0; j < kMaxSub; ++j) {
+            sp[j] = Span<Addr>{0, 0};
+            lf[j] = make_uint2(0, 0);
+            c_here[j] = 0;
+            c_prev[j] = 0;
+            if ((uint32_t)j < sub) {
+                const uint32_t k = chunk0 + j * kWave + lane;
+                const bool valid = k < count;
+                if (valid) { sp[j] = list.span[k]; lf[j] = list.life[k]; }
+                const uint32_t c = valid ? pending_at_or_below(pd, pending, sp[j].lo) : pending;
+                c_here[j] = c;
+                c_prev[j] = wave_shift_up(c, carry);
+                carry = read_lane(c, kWave - 1);
+            }
+        }
+        if constexpr (kLds) __syncthreads();     // in place: every block is in registers before any moves
+#pragma unroll
+        for (int j = 0; j < kMaxSub; ++j) {
+            const uint32_t k = chunk0 + j * kWave + lane;
+            if ((uint32_t)j < sub && k < count && (!kLds || c_here[j] > 0)) {
+                dst.span[k + c_here[j]] = sp[j];
+                dst.life[k + c_here[j]] = lf[j];
+            }
+            if ((uint32_t)j < sub && k <= count) {
+                for (uint32_t q = c_prev[j]; q < c_here[j]; ++q) {
+                    dst.span[k + q] = sh.pend_span[q];
+                    dst.life[k + q] = sh.pend_life[q];
+                }
+            }
+        }
+        base += kPlanThreads * sub;
+    }
+    if constexpr (!kLds) { BlockList<Addr> t = list; list = spare; spare = t; }
+    __syncthreads();
 }
 
-template <bool kLds>
+template <typename Addr, bool kLds, int kPend>
 __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanParams prm)
 {
+    using Lds = PlanLds<Addr, kPend>;
     extern __shared__ __align__(16) unsigned char smem[];
-    PlanFixedLds& sh = *reinterpret_cast<PlanFixedLds*>(smem);
+    Lds& sh = *reinterpret_cast<Lds*>(smem);
     const uint32_t n = prm.n;
 
-    if (*prm.status != STALLOC_OK) return;   // malformed trace: nothing to plan (uniform exit)
+    if (*prm.status != STALLOC_OK) return;               // malformed trace: nothing to plan
+    const uint64_t mode = prm.acc[kAccMode];
+    const bool narrow = (mode & kModeNarrow) != 0;
+    if (narrow != (sizeof(Addr) == 4)) return;            // the other instantiation handles this trace
+    const uint32_t shift = sizeof(Addr) == 4 ? (uint32_t)(mode & 63) : 0;
 
-    BlockList list, spare;
+    BlockList<Addr> list, spare;
     if constexpr (kLds) {
-        unsigned char* dyn = smem + sizeof(PlanFixedLds);
-        list.lo = reinterpret_cast<uint64_t*>(dyn);
-        list.hi = list.lo + prm.cap;
-        list.tt = reinterpret_cast<uint2*>(list.hi + prm.cap);
+        unsigned char* dyn = smem + sizeof(Lds);
+        list.span = reinterpret_cast<Span<Addr>*>(dyn);
+        list.life = reinterpret_cast<uint2*>(list.span + n);
         spare = list;
     } else {
-        unsigned char* slab = prm.slabs + (size_t)blockIdx.x * 2 * (size_t)n * kEntryBytes;
-        list.lo = reinterpret_cast<uint64_t*>(slab);
-        list.hi = list.lo + n;
-        list.tt = reinterpret_cast<uint2*>(list.hi + n);
-        spare.lo = reinterpret_cast<uint64_t*>(slab + (size_t)n * kEntryBytes);
-        spare.hi = spare.lo + n;
-        spare.tt = reinterpret_cast<uint2*>(spare.hi + n);
+        unsigned char* slab = prm.slabs + (size_t)blockIdx.x * 2 * (size_t)n * entry_bytes<uint64_t>();
+        list.span = reinterpret_cast<Span<Addr>*>(slab);
+        list.life = reinterpret_cast<uint2*>(list.span + n);
+        unsigned char* slab2 = slab + (size_t)n * entry_bytes<uint64_t>();
+        spare.span = reinterpret_cast<Span<Addr>*>(slab2);
+        spare.life = reinterpret_cast<uint2*>(spare.span + n);
     }
 
     for (uint32_t p = blockIdx.x; p < prm.P; p += gridDim.x) {
         const uint32_t* order = prm.orders + (size_t)p * n;
         uint64_t* out = prm.offsets ? prm.offsets + (size_t)p * n : nullptr;
-        uint64_t peak = 0;
+        Addr peak = 0;
         uint32_t count = 0, pending = 0;
-        Pending pd = {0, 0, 0, 0};
+        Pending<Addr> pd = {0, 0, 0, 0};
 
         for (uint32_t r0 = 0; r0 < n; r0 += kBatch) {
             const uint32_t nb = n - r0 < (uint32_t)kBatch ? n - r0 : (uint32_t)kBatch;
@@ -216,73 +340,24 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanParams prm)
             __syncthreads();
 
             for (uint32_t b = 0; b < nb; ++b) {
-                const uint64_t s = sh.rq_size[b];
+                const Addr s = (Addr)(sh.rq_size[b] >> shift);
                 const uint32_t ta = sh.rq_ta[b], tf = sh.rq_tf[b];
-
-                const uint64_t x = lowest_fit(list, count, s, ta, tf, pd, pending, sh);
-                peak = umax64(peak, x + s);
-                if (threadIdx.x == 0) sh.rq_addr[b] = x;
+                const Addr x = lowest_fit(list, count, s, ta, tf, pd, pending, sh);
+                peak = umax(peak, (Addr)(x + s));
+                if (threadIdx.x == 0) sh.rq_addr[b] = (uint64_t)x << shift;
                 pending_insert(pd, pending, x, s, ta, tf);
                 ++pending;
-
-                if (pending == kPending && r0 + b + 1 < n) {
-                    // merge the side buffer into the sorted list
-                    if (threadIdx.x < pending) {             // wave 0 publishes the (sorted) side buffer
-                        sh.sorted_lo[threadIdx.x] = pd.lo;
-                        sh.sorted_hi[threadIdx.x] = pd.hi;
-                        sh.sorted_tt[threadIdx.x] = make_uint2(pd.ta, pd.tf);
-                    }
-                    __syncthreads();
-                    if constexpr (kLds) {
-                        constexpr int kMaxPer = 7;           // capacity <= 7 * kPlanThreads entries
-                        uint64_t m_lo[kMaxPer], m_hi[kMaxPer];
-                        uint2 m_tt[kMaxPer];
-                        uint32_t m_to[kMaxPer];
-#pragma unroll
-                        for (int j = 0; j < kMaxPer; ++j) {
-                            const uint32_t k = threadIdx.x + j * kPlanThreads;
-                            m_to[j] = 0xffffffffu;
-                            if (k < count) {
-                                m_lo[j] = list.lo[k];
-                                const uint32_t up = pending_at_or_below(sh, pending, m_lo[j]);
-                                if (up) { m_hi[j] = list.hi[k]; m_tt[j] = list.tt[k]; m_to[j] = k + up; }
-                            }
-                        }
-                        uint32_t p_to = 0xffffffffu;
-                        if (threadIdx.x < pending) p_to = threadIdx.x + listed_below(list.lo, count, sh.sorted_lo[threadIdx.x]);
-                        __syncthreads();
-#pragma unroll
-                        for (int j = 0; j < kMaxPer; ++j)
-                            if (m_to[j] != 0xffffffffu) { list.lo[m_to[j]] = m_lo[j]; list.hi[m_to[j]] = m_hi[j]; list.tt[m_to[j]] = m_tt[j]; }
-                        if (p_to != 0xffffffffu) {
-                            list.lo[p_to] = sh.sorted_lo[threadIdx.x];
-                            list.hi[p_to] = sh.sorted_hi[threadIdx.x];
-                            list.tt[p_to] = sh.sorted_tt[threadIdx.x];
-                        }
-                    } else {
-                        for (uint32_t k = threadIdx.x; k < count; k += kPlanThreads) {
-                            const uint64_t lo = list.lo[k];
-                            const uint32_t to = k + pending_at_or_below(sh, pending, lo);
-                            spare.lo[to] = lo; spare.hi[to] = list.hi[k]; spare.tt[to] = list.tt[k];
-                        }
-                        if (threadIdx.x < pending) {
-                            const uint32_t to = threadIdx.x + listed_below(list.lo, count, sh.sorted_lo[threadIdx.x]);
-                            spare.lo[to] = sh.sorted_lo[threadIdx.x];
-                            spare.hi[to] = sh.sorted_hi[threadIdx.x];
-                            spare.tt[to] = sh.sorted_tt[threadIdx.x];
-                        }
-                        BlockList t = list; list = spare; spare = t;
-                    }
+                if (pending == (uint32_t)kPend && r0 + b + 1 < n) {
+                    merge_pending<Addr, kLds>(list, spare, count, pd, pending, sh);
                     count += pending;
                     pending = 0;
-                    __syncthreads();
                 }
             }
             // addresses of this batch -> offsets[p][request id]
             __syncthreads();
             if (out && threadIdx.x < nb) out[sh.rq_id[threadIdx.x]] = sh.rq_addr[threadIdx.x];
         }
-        if (threadIdx.x == 0) prm.peaks[p] = peak;
+        if (threadIdx.x == 0) prm.peaks[p] = (uint64_t)peak << shift;
     }
 }
 
@@ -318,12 +393,33 @@ __global__ void __launch_bounds__(256) plan_copy_best(const uint64_t* __restrict
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) best_offsets[i] = src[i];
 }
 
+constexpr int kPendLds = 8;       // side-buffer size when the list is in LDS
+constexpr int kPendMem = 16;      // ... and when it is in the workspace (merges cost a pass over memory)
+
+template <typename Addr>
 inline uint32_t lds_capacity_entries(const DeviceInfo& di)
 {
-    if (di.lds_per_block <= sizeof(PlanFixedLds)) return 0;
-    size_t cap = (di.lds_per_block - sizeof(PlanFixedLds)) / kEntryBytes;
-    if (cap > 7u * kPlanThreads) cap = 7u * kPlanThreads;
-    return (uint32_t)cap;
+    const size_t fixed = sizeof(PlanLds<Addr, kPendLds>);
+    if (di.lds_per_block <= fixed) return 0;
+    size_t cap = (di.lds_per_block - fixed) / entry_bytes<Addr>();
+    const size_t pass = (size_t)kMaxSub * kPlanThreads - 1;     // in-place merge keeps the whole list in registers
+    return (uint32_t)(cap < pass ? cap : pass);
+}
+
+template <typename Addr, bool kLds, int kPend>
+inline bool launch_plan(const PlanParams& prm, uint32_t grid, const DeviceInfo& di, hipStream_t stream)
+{
+    auto kernel = &plan_kernel<Addr, kLds, kPend>;
+    size_t lds = sizeof(PlanLds<Addr, kPend>) + (kLds ? (size_t)prm.n * entry_bytes<Addr>() : 0);
+    static bool attr_set[64] = {};
+    if (kLds && !attr_set[di.device]) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)di.lds_per_block) != hipSuccess)
+            return false;
+        attr_set[di.device] = true;
+    }
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kPlanThreads), lds, stream, prm);
+    return true;
 }
 
 }  // namespace stalloc
@@ -334,7 +430,7 @@ extern "C" uint32_t stalloc_plan_lds_capacity(void)
 {
     DeviceInfo di;
     if (!device_info(&di)) return 0;
-    return lds_capacity_entries(di);
+    return lds_capacity_entries<uint32_t>(di);
 }
 
 extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uint32_t P, uint64_t* offsets,
@@ -345,15 +441,16 @@ extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uin
     DeviceInfo di;
     if (!device_info(&di)) return STALLOC_ERR_DEVICE;
     const uint32_t n = tr->n;
-    const uint32_t lds_cap = lds_capacity_entries(di);
-    const bool use_lds = n <= lds_cap;
-    uint32_t grid = use_lds ? (uint32_t)di.cus : (uint32_t)di.cus * 2;
-    if (grid > P) grid = P;
+    const bool lds32 = n <= lds_capacity_entries<uint32_t>(di);
+    const bool lds64 = n <= lds_capacity_entries<uint64_t>(di);
+    uint32_t grid_lds = (uint32_t)di.cus, grid_mem = (uint32_t)di.cus * 2;
+    if (grid_lds > P) grid_lds = P;
+    if (grid_mem > P) grid_mem = P;
 
     Carver cv(workspace);
-    uint64_t* acc = cv.take<uint64_t>(4);
+    uint64_t* acc = cv.take<uint64_t>(kAccWords);
     uint64_t* own_offsets = (!offsets && best_offsets) ? cv.take<uint64_t>((size_t)P * n) : nullptr;
-    unsigned char* slabs = use_lds ? nullptr : cv.take<unsigned char>((size_t)grid * 2 * n * kEntryBytes);
+    unsigned char* slabs = lds64 ? nullptr : cv.take<unsigned char>((size_t)grid_mem * 2 * n * entry_bytes<uint64_t>());
     if (!workspace) { *workspace_bytes = cv.used; return STALLOC_OK; }
     if (!orders || !peaks || !best_plan || !device_status || *workspace_bytes < cv.used ||
         (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)))
@@ -365,21 +462,15 @@ extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uin
     PlanParams prm;
     prm.size = tr->size; prm.ta = tr->t_alloc; prm.tf = tr->t_free; prm.orders = orders;
     prm.offsets = offsets ? offsets : own_offsets;
-    prm.peaks = peaks; prm.status = device_status; prm.slabs = slabs; prm.n = n; prm.P = P;
-    prm.cap = n;
-    if (use_lds) {
-        const size_t lds_bytes = sizeof(PlanFixedLds) + (size_t)n * kEntryBytes;
-        static bool attr_set[64] = {};
-        if (!attr_set[di.device]) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&plan_kernel<true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)di.lds_per_block) != hipSuccess)
-                return STALLOC_ERR_DEVICE;
-            attr_set[di.device] = true;
-        }
-        hipLaunchKernelGGL(plan_kernel<true>, dim3(grid), dim3(kPlanThreads), lds_bytes, stream, prm);
-    } else {
-        hipLaunchKernelGGL(plan_kernel<false>, dim3(grid), dim3(kPlanThreads), sizeof(PlanFixedLds), stream, prm);
-    }
+    prm.peaks = peaks; prm.status = device_status; prm.acc = acc; prm.slabs = slabs; prm.n = n; prm.P = P;
+    bool ok = true;
+    // exactly one of the two launches does the work; the trace decides which (see the mode word)
+    if (lds32) ok = ok && launch_plan<uint32_t, true, kPendLds>(prm, grid_lds, di, stream);
+    else       ok = ok && launch_plan<uint32_t, false, kPendMem>(prm, grid_mem, di, stream);
+    if (lds64) ok = ok && launch_plan<uint64_t, true, kPendLds>(prm, grid_lds, di, stream);
+    else       ok = ok && launch_plan<uint64_t, false, kPendMem>(prm, grid_mem, di, stream);
+    if (!ok) return STALLOC_ERR_DEVICE;
+
     hipLaunchKernelGGL(plan_argmin, dim3(1), dim3(256), 0, stream, peaks, P, best_plan, device_status);
     if (best_offsets) {
         uint32_t blocks = (n + 255) / 256;

@@ -1,6 +1,10 @@
 // Device-side sanity pass over a trace: sizes > 0, t_alloc < t_free <= t_end, and the
 // sum of sizes below 2^63 so that no address can wrap (requests are the events
 // m = (s, t_s, t_e) of Sec. 4).  The verdict lands in the caller's device status word.
+// The pass also derives the address granule: every address a plan can produce is a sum of
+// request sizes, hence a multiple of the largest power of two dividing all sizes; when the
+// sum of sizes counted in granules stays below 2^31 the placement kernel may keep
+// addresses as 32-bit granule counts without any loss.
 #include "host_util.h"
 #include "wave.h"
 
@@ -8,7 +12,7 @@ namespace stalloc {
 
 __global__ void trace_check_init(uint64_t* acc, uint32_t* status)
 {
-    if (threadIdx.x < 4) acc[threadIdx.x] = 0;
+    if (threadIdx.x < kAccWords) acc[threadIdx.x] = 0;
     if (threadIdx.x == 0) *status = STALLOC_OK;
 }
 
@@ -16,7 +20,7 @@ __global__ void __launch_bounds__(256)
 trace_check_scan(const uint64_t* __restrict__ size, const uint32_t* __restrict__ ta,
                  const uint32_t* __restrict__ tf, uint32_t n, uint32_t t_end, uint64_t* acc)
 {
-    uint64_t hi = 0, lo = 0;
+    uint64_t hi = 0, lo = 0, bits = 0;
     uint32_t bad = 0;
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
         uint64_t s = size[i];
@@ -24,21 +28,31 @@ trace_check_scan(const uint64_t* __restrict__ size, const uint32_t* __restrict__
         bad |= (s == 0) | (a >= f) | (f > t_end);
         hi += s >> 32;               // n < 2^31 terms below 2^32 each: cannot wrap
         lo += s & 0xffffffffull;
+        bits |= s;
     }
     hi = wave_sum64(hi);
     lo = wave_sum64(lo);
+    bits = wave_or64(bits);
     uint64_t any_bad = __builtin_amdgcn_ballot_w64(bad != 0);
     if (lane_id() == 0) {
         atomicAdd((unsigned long long*)&acc[0], (unsigned long long)hi);
         atomicAdd((unsigned long long*)&acc[1], (unsigned long long)lo);
         if (any_bad) atomicOr((unsigned long long*)&acc[2], 1ull);
+        atomicOr((unsigned long long*)&acc[3], (unsigned long long)bits);
     }
 }
 
-__global__ void trace_check_finish(const uint64_t* acc, uint32_t* status)
+__global__ void trace_check_finish(uint64_t* acc, uint32_t* status)
 {
     if (threadIdx.x != 0) return;
     uint32_t code = STALLOC_OK;
+    acc[kAccMode] = 0;
+    if (acc[0] + (acc[1] >> 32) < (1ull << 31) && acc[3] != 0) {
+        const uint64_t total = (acc[0] << 32) + acc[1];              // below 2^63 here
+        const uint32_t shift = (uint32_t)__builtin_ctzll(acc[3]);
+        const uint64_t narrow = (total >> shift) < (1ull << 31) ? kModeNarrow : 0;
+        acc[kAccMode] = shift | narrow;
+    }
     // total = acc[0] * 2^32 + acc[1]  >= 2^63  <=>  acc[0] + (acc[1] >> 32) >= 2^31
     if (acc[0] + (acc[1] >> 32) >= (1ull << 31)) code = STALLOC_ERR_OVERFLOW;
     if (acc[2] & 1ull) code = STALLOC_ERR_BAD_TRACE;

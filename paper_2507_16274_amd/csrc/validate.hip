@@ -108,7 +108,7 @@ extern "C" int stalloc_validate(const stalloc_trace* tr, const uint64_t* offsets
     const uint64_t tri = tiles * (tiles + 1) / 2;
     if (tri >= 0x7fffffffull) return STALLOC_ERR_INVALID_ARG;   // n beyond ~16.7 million requests
     Carver cv(workspace);
-    uint64_t* acc = cv.take<uint64_t>(4);
+    uint64_t* acc = cv.take<uint64_t>(kAccWords);
     uint64_t* first_key = cv.take<uint64_t>(P);
     if (!workspace) { *workspace_bytes = cv.used; return STALLOC_OK; }
     if (!offsets || !conflicts || !first_pair || !device_status || *workspace_bytes < cv.used ||

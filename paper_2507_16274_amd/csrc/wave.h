@@ -74,6 +74,17 @@ __device__ __forceinline__ uint64_t wave_sum64(uint64_t v)
     return readlane64(v, 63);
 }
 
+__device__ __forceinline__ uint64_t wave_or64(uint64_t v)
+{
+    v |= dpp64<kDppRowShr1>(0, v);
+    v |= dpp64<kDppRowShr2>(0, v);
+    v |= dpp64<kDppRowShr4>(0, v);
+    v |= dpp64<kDppRowShr8>(0, v);
+    v |= dpp64<kDppRowBcast15, 0xa>(0, v);
+    v |= dpp64<kDppRowBcast31, 0xc>(0, v);
+    return readlane64(v, 63);
+}
+
 __device__ __forceinline__ uint64_t wave_min64(uint64_t v)
 {
     const uint64_t top = ~0ull;
@@ -85,6 +96,49 @@ __device__ __forceinline__ uint64_t wave_min64(uint64_t v)
     v = umin64(v, dpp64<kDppRowBcast31, 0xc>(top, v));
     return readlane64(v, 63);
 }
+
+// Width-generic wrappers used by the placement kernel (addresses are 32- or 64-bit) ----------
+__device__ __forceinline__ uint32_t wave_scan_max(uint32_t v)
+{
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, kDppRowShr1, 0xf, 0xf, false));
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, kDppRowShr2, 0xf, 0xf, false));
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, kDppRowShr4, 0xf, 0xf, false));
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, kDppRowShr8, 0xf, 0xf, false));
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, kDppRowBcast15, 0xa, 0xf, false));
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, kDppRowBcast31, 0xc, 0xf, false));
+    return v;
+}
+__device__ __forceinline__ uint64_t wave_scan_max(uint64_t v) { return wave_scan_max64(v); }
+
+// Running maximum inside each row of 16 lanes only.
+__device__ __forceinline__ uint32_t row_scan_max(uint32_t v)
+{
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, kDppRowShr1, 0xf, 0xf, false));
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, kDppRowShr2, 0xf, 0xf, false));
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, kDppRowShr4, 0xf, 0xf, false));
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, kDppRowShr8, 0xf, 0xf, false));
+    return v;
+}
+__device__ __forceinline__ uint64_t row_scan_max(uint64_t v)
+{
+    v = umax64(v, dpp64<kDppRowShr1>(0, v));
+    v = umax64(v, dpp64<kDppRowShr2>(0, v));
+    v = umax64(v, dpp64<kDppRowShr4>(0, v));
+    v = umax64(v, dpp64<kDppRowShr8>(0, v));
+    return v;
+}
+
+__device__ __forceinline__ uint32_t wave_shift_up(uint32_t v, uint32_t fill)
+{
+    return __builtin_amdgcn_update_dpp(fill, v, kDppWaveShr1, 0xf, 0xf, false);
+}
+__device__ __forceinline__ uint64_t wave_shift_up(uint64_t v, uint64_t fill) { return wave_shift_up64(v, fill); }
+
+__device__ __forceinline__ uint32_t read_lane(uint32_t v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
+__device__ __forceinline__ uint64_t read_lane(uint64_t v, int lane) { return readlane64(v, lane); }
+
+__device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+__device__ __forceinline__ uint64_t umax(uint64_t a, uint64_t b) { return a > b ? a : b; }
 
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
 __device__ __forceinline__ int wave_id() { return (int)(threadIdx.x >> 6); }

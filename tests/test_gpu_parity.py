@@ -189,13 +189,17 @@ def test_plan_config2_all_orderings(S, oracle):
     assert np.array_equal(lean["peaks"], ext) and np.array_equal(lean["best_offsets"], got["best_offsets"])
 
 
+@pytest.mark.parametrize("wide", [False, True])
 @pytest.mark.parametrize("seed", range(12))
-def test_plan_random_traces(S, oracle, seed):
-    """Ties in timestamps, single requests, list lengths around wave / workgroup / side-buffer sizes."""
+def test_plan_random_traces(S, oracle, seed, wide):
+    """Ties in timestamps, single requests, list lengths around wave / workgroup / side-buffer sizes.
+    wide: odd byte sizes with a sum far above 2^31, which forces 64-bit addresses in the kernel."""
     rng = np.random.default_rng(900 + seed)
     n = [1, 2, 63, 64, 65, 127, 129, 1023, 1025, 2049, 700, 3000][seed]
     size, ts, te, t_end = random_trace(rng, n, t_max=max(4, n // 3), unique_times=(seed % 2 == 1))
     size = size * np.uint64(512)
+    if wide:
+        size = size * np.uint64(2 ** 31 + 12345) + np.uint64(1)
     tr = _T(size, ts, te, t_end)
     P = 9
     orders = np.stack([rng.permutation(n) for _ in range(P)]).astype(np.uint32)
@@ -230,6 +234,22 @@ def test_plan_large_list_in_workspace(S, oracle):
     got, a, ext = _compare_plans(S, oracle, tr, orders, method="lists", lists=lists)
     cnt, _ = _gpu_validate(S, tr, got["offsets"])
     assert not cnt.any()
+
+
+@pytest.mark.parametrize("wide", [False, True])
+def test_plan_list_beyond_lds(S, oracle, wide):
+    """A random trace too long for the LDS-resident list, with 32-bit and with 64-bit addresses."""
+    rng = np.random.default_rng(960 + int(wide))
+    n = 11000
+    assert n > S.lib.stalloc_plan_lds_capacity()
+    size, ts, te, t_end = random_trace(rng, n, t_max=2000, sizes=[1, 2, 3, 5, 8, 13])
+    size = size * np.uint64(4096)
+    if wide:
+        size = size * np.uint64(2 ** 31 + 7) + np.uint64(1)
+    tr = _T(size, ts, te, t_end)
+    orders = np.stack([rng.permutation(n) for _ in range(4)]).astype(np.uint32)
+    orders[0] = np.argsort(-size.astype(np.int64), kind="stable")
+    _compare_plans(S, oracle, tr, orders, method="lists")
 
 
 def test_plan_reports_malformed_inputs(S):
