@@ -24,7 +24,8 @@ def sources():
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB + f".tmp{os.getpid()}"
-    cmd = [hipcc] + HIPCC_FLAGS + sources() + ["-o", tmp]
+    extra = os.environ.get("STALLOC_DEFINES", "").split()      # e.g. "-DSTALLOC_THREADS_LDS=512"
+    cmd = [hipcc] + HIPCC_FLAGS + extra + sources() + ["-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

@@ -20,8 +20,10 @@
 //            pending blocks that conflict with its lifetime.  f is monotone and idempotent,
 //            hence f(max(a, b)) = max(f(a), f(b)): replacing every listed block's end e by
 //            f(e) before the running maximum, and starting from f(0), makes the scan honour
-//            the side buffer exactly.  f is evaluated against "zones" -- maximal groups of
-//            conflicting pending blocks whose holes are too small for the request.
+//            the side buffer exactly -- and since max f(e) = f(max e), all running maxima can
+//            stay raw and f is evaluated only where a raw candidate hole appears.  f is
+//            evaluated against "zones" -- maximal groups of conflicting pending blocks whose
+//            holes are too small for the request.
 //   merge    When the side buffer is full, one pass moves every listed block up by the
 //            number of pending blocks at or below it and drops the pending blocks in place.
 //
@@ -36,10 +38,8 @@
 
 namespace stalloc {
 
-constexpr int kPlanThreads = 1024;
-constexpr int kPlanWaves = kPlanThreads / kWave;
 constexpr int kBatch = 256;          // requests fetched per refill
-constexpr int kMaxSub = 10;          // 64-entry steps one wave takes between two barriers
+constexpr int kPassEntries = 10240;  // list entries covered between two barrier pairs
 
 template <typename Addr> struct Span { Addr lo, hi; };     // [lo, hi) in address units
 
@@ -47,17 +47,17 @@ template <typename Addr> struct Top;
 template <> struct Top<uint32_t> { static constexpr uint32_t value = 0xffffffffu; };
 template <> struct Top<uint64_t> { static constexpr uint64_t value = ~0ull; };
 
-template <typename Addr, int kPend>
+template <typename Addr, int kPend, int kThreads>
 struct PlanLds {
     uint64_t rq_size[kBatch];
     uint64_t rq_addr[kBatch];
     uint32_t rq_ta[kBatch];
     uint32_t rq_tf[kBatch];
     uint32_t rq_id[kBatch];
-    Addr wave_top[kPlanWaves];
-    Addr wave_hit[kPlanWaves];
-    Span<Addr> pend_span[kPend];
-    uint2 pend_life[kPend];
+    Addr wave_top[kThreads / kWave];
+    Addr wave_hit[kThreads / kWave];
+    Span<Addr> pend_span[2][kPend];      // side buffer, sorted; two copies alternate between steps
+    uint2 pend_life[2][kPend];
 };
 
 struct PlanParams {
@@ -82,12 +82,25 @@ struct BlockList {
 
 template <typename Addr> constexpr size_t entry_bytes() { return sizeof(Span<Addr>) + sizeof(uint2); }
 
-// The side buffer: pending block q lives in lane q of every wave, ascending start address.
+// The side buffer in registers: pending block q in lane q, ascending start address.
 template <typename Addr>
 struct Pending {
     Addr lo, hi;
     uint32_t ta, tf;
 };
+
+template <typename Addr, typename Lds>
+__device__ __forceinline__ Pending<Addr> load_pending(const Lds& sh, uint32_t pending, int copy)
+{
+    Pending<Addr> pd = {0, 0, 0, 0};
+    const int lane = lane_id();
+    if (lane < (int)pending) {
+        const Span<Addr> sp = sh.pend_span[copy][lane];
+        const uint2 lf = sh.pend_life[copy][lane];
+        pd.lo = sp.lo; pd.hi = sp.hi; pd.ta = lf.x; pd.tf = lf.y;
+    }
+    return pd;
+}
 
 // Zones of the side buffer for one request: groups of lifetime-conflicting pending blocks.
 // A zone starts at a conflicting block that leaves a hole of at least `s` above everything
@@ -134,10 +147,21 @@ __device__ __forceinline__ Addr clear_zones(Addr e, Addr s, const Zones<Addr>& z
     return e;
 }
 
-// Sorted insertion of a block into the register-held side buffer (every wave does the same).
-template <typename Addr>
-__device__ __forceinline__ void pending_insert(Pending<Addr>& pd, uint32_t pending, Addr x, Addr s,
-                                               uint32_t ta, uint32_t tf)
+// f(e) with the side buffer fetched from LDS; only called where a raw candidate shows up.
+template <typename Addr, typename Lds>
+__device__ __forceinline__ Addr clear_pending(Addr e, Addr s, uint32_t ta, uint32_t tf, const Lds& sh,
+                                              uint32_t pending, int copy)
+{
+    if (pending == 0) return e;
+    const Pending<Addr> pd = load_pending<Addr>(sh, pending, copy);
+    return clear_zones(e, s, make_zones(pd, pending, s, ta, tf));
+}
+
+// Sorted insertion of the block [x, x + s) into the side buffer: wave 0 holds the buffer in
+// registers and publishes the whole new buffer to the LDS copy the next step will read.
+template <typename Addr, typename Lds>
+__device__ __forceinline__ void pending_insert(Pending<Addr>& pd, uint32_t pending, Addr x, Addr s, uint32_t ta,
+                                               uint32_t tf, Lds& sh, int copy_out)
 {
     const int lane = lane_id();
     const uint64_t keep = __builtin_amdgcn_ballot_w64(lane < (int)pending && pd.lo <= x);
@@ -146,47 +170,68 @@ __device__ __forceinline__ void pending_insert(Pending<Addr>& pd, uint32_t pendi
     const uint32_t up_ta = wave_shift_up(pd.ta, 0u), up_tf = wave_shift_up(pd.tf, 0u);
     if (lane > pos) { pd.lo = up_lo; pd.hi = up_hi; pd.ta = up_ta; pd.tf = up_tf; }
     if (lane == pos) { pd.lo = x; pd.hi = x + s; pd.ta = ta; pd.tf = tf; }
+    if (lane <= (int)pending) {
+        sh.pend_span[copy_out][lane] = Span<Addr>{pd.lo, pd.hi};
+        sh.pend_life[copy_out][lane] = make_uint2(pd.ta, pd.tf);
+    }
 }
 
 // Lowest address x such that [x, x + s) meets neither a listed block nor a pending block whose
 // lifetime conflicts with [ta, tf).  All threads of the workgroup call this together; the
 // result is uniform.
-template <typename Addr, typename Lds>
+//
+// All running maxima are RAW (side buffer ignored).  Because f(max(a, b)) = max(f(a), f(b)),
+// "covered so far" with the side buffer is f(raw maximum), so f is only evaluated where a raw
+// candidate hole shows up, not for every listed block.
+template <typename Addr, int kThreads, typename Lds>
 __device__ __forceinline__ Addr lowest_fit(const BlockList<Addr>& list, uint32_t count, Addr s, uint32_t ta,
-                                           uint32_t tf, const Pending<Addr>& pd, uint32_t pending, Lds& sh)
+                                           uint32_t tf, uint32_t pending, int copy, Lds& sh)
 {
-    const int lane = lane_id(), wave = wave_id();
-    const Zones<Addr> zones = make_zones(pd, pending, s, ta, tf);
-    Addr covered = clear_zones((Addr)0, s, zones);          // first address not known to be blocked
+    constexpr int kWaves = kThreads / kWave;
+    constexpr int kMaxSub = kPassEntries / kThreads;
     constexpr Addr kNoHit = Top<Addr>::value;
+    const int lane = lane_id(), wave = wave_id();
+    Addr covered = 0;                    // raw: first address not blocked by listed blocks so far
+    if (count == 0) {
+        __syncthreads();                 // the side buffer written at the end of the previous step is visible
+        return clear_pending(covered, s, ta, tf, sh, pending, copy);
+    }
+    const uint32_t last = count - 1;
 
     for (uint32_t base = 0;;) {
         const uint32_t left = count - base;
-        uint32_t sub = (left + kPlanThreads - 1) / kPlanThreads;   // 64-entry steps per wave in this pass
+        uint32_t sub = (left + kThreads - 1) / kThreads;         // 64-entry steps per wave in this pass
         if (sub > (uint32_t)kMaxSub) sub = kMaxSub;
-        if (sub == 0) sub = 1;
         const uint32_t chunk0 = base + (uint32_t)wave * kWave * sub;
 
         Addr lo_keep[kMaxSub], before_keep[kMaxSub];
         uint32_t maybe = 0;              // steps in which some lane could be a stop
         Addr run = 0;                    // running maximum inside this wave's chunk
+        // entries past the end are read from the last entry and masked out afterwards
+        uint32_t k_next = chunk0 + lane;
+        Span<Addr> sp_next = list.span[k_next < last ? k_next : last];
+        uint2 lf_next = list.life[k_next < last ? k_next : last];
 #pragma unroll
         for (int j = 0; j < kMaxSub; ++j) {
             lo_keep[j] = 0;
             before_keep[j] = 0;
             if ((uint32_t)j < sub) {
-                const uint32_t k = chunk0 + j * kWave + lane;
+                const uint32_t k = k_next;
+                const Span<Addr> sp = sp_next;
+                const uint2 lf = lf_next;
+                if ((uint32_t)(j + 1) < sub) {
+                    k_next = k + kWave;
+                    sp_next = list.span[k_next < last ? k_next : last];
+                    lf_next = list.life[k_next < last ? k_next : last];
+                }
                 const bool valid = k < count;
-                Span<Addr> sp = {0, 0};
-                uint2 lf = make_uint2(0, 0);
-                if (valid) { sp = list.span[k]; lf = list.life[k]; }
                 const bool conflict = valid && lf.x < tf && ta < lf.y;
-                const Addr reach = clear_zones(conflict ? sp.hi : (Addr)0, s, zones);
-                const Addr incl = wave_scan_max(reach);
+                const Addr incl = wave_scan_max(conflict ? sp.hi : (Addr)0);
                 const Addr before = umax(run, wave_shift_up(incl, (Addr)0));
-                lo_keep[j] = sp.lo;                   // 0 for lanes past the end: never a stop (s > 0)
+                const Addr lo = valid ? sp.lo : (Addr)0;      // 0 past the end: never a stop (s > 0)
+                lo_keep[j] = lo;
                 before_keep[j] = before;
-                if (__builtin_amdgcn_ballot_w64(sp.lo >= before + s)) maybe |= 1u << j;
+                if (__builtin_amdgcn_ballot_w64(lo >= before + s)) maybe |= 1u << j;
                 run = umax(run, read_lane(incl, kWave - 1));
             }
         }
@@ -194,26 +239,29 @@ __device__ __forceinline__ Addr lowest_fit(const BlockList<Addr>& list, uint32_t
         __syncthreads();
 
         // maxima of the chunks below this wave, and of all chunks
-        const Addr tops = row_scan_max(lane < kPlanWaves ? sh.wave_top[lane] : (Addr)0);
+        const Addr tops = row_scan_max(lane < kWaves ? sh.wave_top[lane] : (Addr)0);
         const Addr below = umax(covered, wave > 0 ? read_lane(tops, wave - 1) : (Addr)0);
-        const Addr all = umax(covered, read_lane(tops, kPlanWaves - 1));
+        const Addr all = umax(covered, read_lane(tops, kWaves - 1));
         Addr hit = kNoHit;
 #pragma unroll
         for (int j = 0; j < kMaxSub; ++j) {
             if (hit == kNoHit && (maybe & (1u << j))) {
                 const Addr before = umax(below, before_keep[j]);
-                const uint64_t stops = __builtin_amdgcn_ballot_w64(lo_keep[j] >= before + s);
-                if (stops) hit = read_lane(before, __builtin_ctzll(stops));
+                if (__builtin_amdgcn_ballot_w64(lo_keep[j] >= before + s)) {      // a raw hole: now ask the side buffer
+                    const Addr cleared = clear_pending(before, s, ta, tf, sh, pending, copy);
+                    const uint64_t stops = __builtin_amdgcn_ballot_w64(lo_keep[j] >= cleared + s);
+                    if (stops) hit = read_lane(cleared, __builtin_ctzll(stops));
+                }
             }
         }
         if (lane == 0) sh.wave_hit[wave] = hit;
         __syncthreads();
-        const Addr h = lane < kPlanWaves ? sh.wave_hit[lane] : kNoHit;
+        const Addr h = lane < kWaves ? sh.wave_hit[lane] : kNoHit;
         const uint64_t hits = __builtin_amdgcn_ballot_w64(h != kNoHit);
         if (hits) return read_lane(h, __builtin_ctzll(hits));
         covered = all;
-        base += kPlanThreads * sub;
-        if (base >= count) return covered;
+        base += kThreads * sub;
+        if (base >= count) return clear_pending(covered, s, ta, tf, sh, pending, copy);
     }
 }
 
@@ -229,20 +277,18 @@ __device__ __forceinline__ uint32_t pending_at_or_below(const Pending<Addr>& pd,
 // Merges the side buffer into the sorted list.  Listed block k moves to k + c_k, where c_k is
 // the number of pending blocks at or below its start address; pending block q lands at
 // k + q in front of the first listed block k with c_k > q (or behind the last one).
-template <typename Addr, bool kLds, typename Lds>
+// The caller has synchronised the workgroup after the side buffer copy `copy` was written.
+template <typename Addr, bool kLds, int kThreads, typename Lds>
 __device__ __forceinline__ void merge_pending(BlockList<Addr>& list, BlockList<Addr>& spare, uint32_t count,
-                                              const Pending<Addr>& pd, uint32_t pending, Lds& sh)
+                                              uint32_t pending, int copy, Lds& sh)
 {
+    constexpr int kMaxSub = kPassEntries / kThreads;
     const int lane = lane_id(), wave = wave_id();
-    if (threadIdx.x < pending) {                 // wave 0 publishes the side buffer for the writers
-        sh.pend_span[threadIdx.x] = Span<Addr>{pd.lo, pd.hi};
-        sh.pend_life[threadIdx.x] = make_uint2(pd.ta, pd.tf);
-    }
-    if constexpr (!kLds) __syncthreads();
+    const Pending<Addr> pd = load_pending<Addr>(sh, pending, copy);
     BlockList<Addr>& dst = kLds ? list : spare;
     for (uint32_t base = 0; base <= count;) {    // "<=": the position just past the end takes the tail
         const uint32_t left = count + 1 - base;
-        uint32_t sub = (left + kPlanThreads - 1) / kPlanThreads;
+        uint32_t sub = (left + kThreads - 1) / kThreads;
         if (sub > (uint32_t)kMaxSub) sub = kMaxSub;
         const uint32_t chunk0 = base + (uint32_t)wave * kWave * sub;
 
@@ -279,21 +325,21 @@ __device__ __forceinline__ void merge_pending(BlockList<Addr>& list, BlockList<A
             }
             if ((uint32_t)j < sub && k <= count) {
                 for (uint32_t q = c_prev[j]; q < c_here[j]; ++q) {
-                    dst.span[k + q] = sh.pend_span[q];
-                    dst.life[k + q] = sh.pend_life[q];
+                    dst.span[k + q] = sh.pend_span[copy][q];
+                    dst.life[k + q] = sh.pend_life[copy][q];
                 }
             }
         }
-        base += kPlanThreads * sub;
+        base += kThreads * sub;
     }
     if constexpr (!kLds) { BlockList<Addr> t = list; list = spare; spare = t; }
     __syncthreads();
 }
 
-template <typename Addr, bool kLds, int kPend>
-__global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanParams prm)
+template <typename Addr, bool kLds, int kPend, int kThreads>
+__global__ void __launch_bounds__(kThreads) plan_kernel(PlanParams prm)
 {
-    using Lds = PlanLds<Addr, kPend>;
+    using Lds = PlanLds<Addr, kPend, kThreads>;
     extern __shared__ __align__(16) unsigned char smem[];
     Lds& sh = *reinterpret_cast<Lds*>(smem);
     const uint32_t n = prm.n;
@@ -324,7 +370,8 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanParams prm)
         uint64_t* out = prm.offsets ? prm.offsets + (size_t)p * n : nullptr;
         Addr peak = 0;
         uint32_t count = 0, pending = 0;
-        Pending<Addr> pd = {0, 0, 0, 0};
+        int copy = 0;                                  // side-buffer copy this step reads
+        Pending<Addr> pd = {0, 0, 0, 0};              // wave 0's register image of the side buffer
 
         for (uint32_t r0 = 0; r0 < n; r0 += kBatch) {
             const uint32_t nb = n - r0 < (uint32_t)kBatch ? n - r0 : (uint32_t)kBatch;
@@ -342,13 +389,17 @@ __global__ void __launch_bounds__(kPlanThreads) plan_kernel(PlanParams prm)
             for (uint32_t b = 0; b < nb; ++b) {
                 const Addr s = (Addr)(sh.rq_size[b] >> shift);
                 const uint32_t ta = sh.rq_ta[b], tf = sh.rq_tf[b];
-                const Addr x = lowest_fit(list, count, s, ta, tf, pd, pending, sh);
+                const Addr x = lowest_fit<Addr, kThreads>(list, count, s, ta, tf, pending, copy, sh);
                 peak = umax(peak, (Addr)(x + s));
-                if (threadIdx.x == 0) sh.rq_addr[b] = (uint64_t)x << shift;
-                pending_insert(pd, pending, x, s, ta, tf);
+                if (wave_id() == 0) {
+                    if (lane_id() == 0) sh.rq_addr[b] = (uint64_t)x << shift;
+                    pending_insert(pd, pending, x, s, ta, tf, sh, copy ^ 1);
+                }
                 ++pending;
+                copy ^= 1;
                 if (pending == (uint32_t)kPend && r0 + b + 1 < n) {
-                    merge_pending<Addr, kLds>(list, spare, count, pd, pending, sh);
+                    __syncthreads();                          // the side buffer is complete and visible
+                    merge_pending<Addr, kLds, kThreads>(list, spare, count, pending, copy, sh);
                     count += pending;
                     pending = 0;
                 }
@@ -393,24 +444,39 @@ __global__ void __launch_bounds__(256) plan_copy_best(const uint64_t* __restrict
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) best_offsets[i] = src[i];
 }
 
-constexpr int kPendLds = 8;       // side-buffer size when the list is in LDS
-constexpr int kPendMem = 16;      // ... and when it is in the workspace (merges cost a pass over memory)
+// Tuning knobs (overridable at build time with -D).
+#ifndef STALLOC_PEND_LDS
+#define STALLOC_PEND_LDS 16
+#endif
+#ifndef STALLOC_PEND_MEM
+#define STALLOC_PEND_MEM 16
+#endif
+#ifndef STALLOC_THREADS_LDS
+#define STALLOC_THREADS_LDS 1024
+#endif
+#ifndef STALLOC_THREADS_MEM
+#define STALLOC_THREADS_MEM 1024
+#endif
+constexpr int kPendLds = STALLOC_PEND_LDS;        // side-buffer size when the list is in LDS
+constexpr int kPendMem = STALLOC_PEND_MEM;        // ... and when it is in the workspace (merges cost a pass over memory)
+constexpr int kThreadsLds = STALLOC_THREADS_LDS;
+constexpr int kThreadsMem = STALLOC_THREADS_MEM;
 
 template <typename Addr>
 inline uint32_t lds_capacity_entries(const DeviceInfo& di)
 {
-    const size_t fixed = sizeof(PlanLds<Addr, kPendLds>);
+    const size_t fixed = sizeof(PlanLds<Addr, kPendLds, kThreadsLds>);
     if (di.lds_per_block <= fixed) return 0;
     size_t cap = (di.lds_per_block - fixed) / entry_bytes<Addr>();
-    const size_t pass = (size_t)kMaxSub * kPlanThreads - 1;     // in-place merge keeps the whole list in registers
+    const size_t pass = (size_t)kPassEntries - 1;               // in-place merge keeps the whole list in registers
     return (uint32_t)(cap < pass ? cap : pass);
 }
 
-template <typename Addr, bool kLds, int kPend>
+template <typename Addr, bool kLds, int kPend, int kThreads>
 inline bool launch_plan(const PlanParams& prm, uint32_t grid, const DeviceInfo& di, hipStream_t stream)
 {
-    auto kernel = &plan_kernel<Addr, kLds, kPend>;
-    size_t lds = sizeof(PlanLds<Addr, kPend>) + (kLds ? (size_t)prm.n * entry_bytes<Addr>() : 0);
+    auto kernel = &plan_kernel<Addr, kLds, kPend, kThreads>;
+    size_t lds = sizeof(PlanLds<Addr, kPend, kThreads>) + (kLds ? (size_t)prm.n * entry_bytes<Addr>() : 0);
     static bool attr_set[64] = {};
     if (kLds && !attr_set[di.device]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -418,7 +484,7 @@ inline bool launch_plan(const PlanParams& prm, uint32_t grid, const DeviceInfo& 
             return false;
         attr_set[di.device] = true;
     }
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kPlanThreads), lds, stream, prm);
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), lds, stream, prm);
     return true;
 }
 
@@ -465,10 +531,10 @@ extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uin
     prm.peaks = peaks; prm.status = device_status; prm.acc = acc; prm.slabs = slabs; prm.n = n; prm.P = P;
     bool ok = true;
     // exactly one of the two launches does the work; the trace decides which (see the mode word)
-    if (lds32) ok = ok && launch_plan<uint32_t, true, kPendLds>(prm, grid_lds, di, stream);
-    else       ok = ok && launch_plan<uint32_t, false, kPendMem>(prm, grid_mem, di, stream);
-    if (lds64) ok = ok && launch_plan<uint64_t, true, kPendLds>(prm, grid_lds, di, stream);
-    else       ok = ok && launch_plan<uint64_t, false, kPendMem>(prm, grid_mem, di, stream);
+    if (lds32) ok = ok && launch_plan<uint32_t, true, kPendLds, kThreadsLds>(prm, grid_lds, di, stream);
+    else       ok = ok && launch_plan<uint32_t, false, kPendMem, kThreadsMem>(prm, grid_mem, di, stream);
+    if (lds64) ok = ok && launch_plan<uint64_t, true, kPendLds, kThreadsLds>(prm, grid_lds, di, stream);
+    else       ok = ok && launch_plan<uint64_t, false, kPendMem, kThreadsMem>(prm, grid_mem, di, stream);
     if (!ok) return STALLOC_ERR_DEVICE;
 
     hipLaunchKernelGGL(plan_argmin, dim3(1), dim3(256), 0, stream, peaks, P, best_plan, device_status);
