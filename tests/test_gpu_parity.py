@@ -236,6 +236,39 @@ def test_plan_large_list_in_workspace(S, oracle):
     assert not cnt.any()
 
 
+def test_plan_config4_sampled_orderings(S, oracle):
+    """MoE trace (47 748 requests, 1229 distinct sizes): heuristic rows and sampled random rows."""
+    tr = make_trace(4)
+    rows = [0, 1, 2, 3, 1024, 2047]
+    orders = make_orderings(tr, CONFIGS[4].n_orderings, rows=rows)
+    lists = oracle.conflict_lists(tr.t_alloc, tr.t_free)
+    got, a, ext = _compare_plans(S, oracle, tr, orders, method="lists", lists=lists)
+    cnt, _ = _gpu_validate(S, tr, got["offsets"])
+    assert not cnt.any()
+    status, lb, _ = _gpu_lower_bound(S, tr)
+    assert (got["peaks"] >= lb).all()
+
+
+def test_plan_config5_sampled_orderings(S, oracle):
+    """Largest trace (199 748 requests, 64-bit addresses): sampled rows compared address by address,
+    the best of them validated over all n(n-1)/2 pairs, and a corrupted copy against the oracle's count."""
+    tr = make_trace(5)
+    rows = [0, 2, 3, 4094]
+    orders = make_orderings(tr, CONFIGS[5].n_orderings, rows=rows)
+    lists = oracle.conflict_lists(tr.t_alloc, tr.t_free)
+    got, a, ext = _compare_plans(S, oracle, tr, orders, method="lists", lists=lists)
+    del lists
+    best = got["best_offsets"][None, :]
+    cnt, pair = _gpu_validate(S, tr, best)
+    assert int(cnt[0]) == 0 and tuple(int(x) for x in pair[0]) == NONE_PAIR
+    rng = np.random.default_rng(555)
+    bad = best.copy()
+    for i in rng.choice(tr.n, size=5, replace=False):
+        bad[0, i] = rng.integers(0, int(best.max()))
+    cnt, pair = _gpu_validate(S, tr, bad)
+    assert (int(cnt[0]), tuple(int(x) for x in pair[0])) == oracle.validate(tr.size, tr.t_alloc, tr.t_free, bad[0])
+
+
 @pytest.mark.parametrize("wide", [False, True])
 def test_plan_list_beyond_lds(S, oracle, wide):
     """A random trace too long for the LDS-resident list, with 32-bit and with 64-bit addresses."""
