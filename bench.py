@@ -44,6 +44,8 @@ def main() -> int:
     ap.add_argument("--plans", type=int, default=0, help="override the number of orders (0 = the configuration's)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="CPU work budget of the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (reference dispatch for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (orders are independent and would be split "
@@ -88,6 +90,13 @@ def main() -> int:
         val = S.stalloc_validate(size, ta, tf, tr.t_end, plan["best_offsets"].view(1, n), workspace_cache=cache_val)
         lb = S.stalloc_lower_bound(size, ta, tf, tr.t_end, workspace_cache=cache_lb)
         return plan, val, lb
+
+    if args.copy_calibration_mib:
+        src = torch.ones(args.copy_calibration_mib * 2 ** 20 // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step(False)

@@ -5,31 +5,35 @@
 // range at once.  Extent of a plan = max(a + s) (Eq. 2).
 //
 // Per plan the workgroup keeps the list of placed blocks SORTED BY ADDRESS, so that no
-// sorting is needed when a request is placed.
+// sorting is needed when a request is placed.  Requests are handled in batches of K:
 //
-//   scan     Each wave owns a run of consecutive list entries and walks it 64 entries at a
-//            time.  A compare keeps the blocks whose lifetime conflicts with the request; a
-//            wave64 running maximum (DPP) of their end addresses is "first address not
-//            covered so far"; the request fits in front of the first block that starts at
-//            least `size` above that value.  Waves exchange their chunk maxima through LDS
-//            (one barrier), evaluate their candidate stops against everything below them,
-//            and publish the first hit (second barrier).
-//   pending  Freshly placed blocks go to a small side buffer, sorted by address and held in
-//            registers by every wave (one block per lane), instead of being inserted at
-//            once.  Let f(c) be the lowest address >= c at which the request clears the
-//            pending blocks that conflict with its lifetime.  f is monotone and idempotent,
-//            hence f(max(a, b)) = max(f(a), f(b)): replacing every listed block's end e by
-//            f(e) before the running maximum, and starting from f(0), makes the scan honour
-//            the side buffer exactly -- and since max f(e) = f(max e), all running maxima can
-//            stay raw and f is evaluated only where a raw candidate hole appears.  f is
-//            evaluated against "zones" -- maximal groups of conflicting pending blocks whose
-//            holes are too small for the request.
-//   merge    When the side buffer is full, one pass moves every listed block up by the
-//            number of pending blocks at or below it and drops the pending blocks in place.
+//   scan     One pass over the sorted list serves the whole batch, because the list only
+//            changes between batches.  Each wave owns a run of consecutive entries and walks
+//            it 64 at a time; every entry is loaded once and tested against the K requests:
+//            a compare keeps the blocks whose lifetime conflicts with request r, a wave64
+//            running maximum (DPP) of their end addresses is "covered so far", and a
+//            conflicting block that starts at least size_r above it closes a hole
+//            [covered, start) in which r could fit.  Per (wave, request) the wave publishes
+//            its chunk maximum and its first few holes (with chunk-local "covered") to LDS.
+//   resolve  After one barrier, wave 0 settles the K requests in order.  For request r the
+//            published holes of all waves sit in its 64 lanes in address order; the true
+//            "covered" of a hole is the maximum of its local value and the chunk maxima of
+//            the waves below.  The blocks already settled in this batch (the side buffer,
+//            sorted, one per lane) are honoured through f(c) = lowest address >= c that clears
+//            the side-buffer blocks conflicting with r: r takes the first hole with
+//            f(covered) + size_r <= hole end, else goes on top at f(maximum).  f is evaluated
+//            over "zones" -- maximal groups of conflicting side-buffer blocks whose holes are
+//            too small for r.  If a wave had more holes than it could publish and none of the
+//            earlier ones fits, the batch ends early and that one request takes the exact
+//            single-request path below.
+//   merge    The settled blocks are merged into the sorted list in one pass: listed block k
+//            moves up by the number of new blocks at or below its start address and the new
+//            blocks drop into the gaps (in place through registers when the list is in LDS,
+//            ping-pong between two slabs when it is in the workspace).
 //
 // Addresses are multiples of the largest power of two dividing all sizes.  When the sum of
-// sizes, in those granules, stays below 2^31 the list holds 32-bit granule counts (half the
-// LDS bytes and single-instruction max/compare); otherwise 64-bit byte addresses.  The trace
+// sizes, in those granules, stays below 2^31 the list holds 32-bit granule counts (16-byte
+// entries, single-instruction max/compare/DPP); otherwise 64-bit byte addresses.  The trace
 // check leaves that decision in device memory, both instantiations are enqueued and the one
 // that does not apply returns at once.  The list lives in LDS when it fits and in the
 // workspace otherwise.
@@ -39,7 +43,7 @@
 namespace stalloc {
 
 constexpr int kBatch = 256;          // requests fetched per refill
-constexpr int kPassEntries = 10240;  // list entries covered between two barrier pairs
+constexpr int kPassEntries = 10240;  // list entries one in-place merge pass / one fallback pass covers
 
 template <typename Addr> struct Span { Addr lo, hi; };     // [lo, hi) in address units
 
@@ -49,15 +53,25 @@ template <> struct Top<uint64_t> { static constexpr uint64_t value = ~0ull; };
 
 template <typename Addr, int kPend, int kThreads>
 struct PlanLds {
+    static constexpr int kWaves = kThreads / kWave;
+#ifdef STALLOC_HOLE_SLOTS
+    static constexpr int kSlots = STALLOC_HOLE_SLOTS;      // (test builds shrink this to exercise the exact path)
+#else
+    static constexpr int kSlots = kWave / kWaves;          // holes a wave can publish per request
+#endif
     uint64_t rq_size[kBatch];
     uint64_t rq_addr[kBatch];
     uint32_t rq_ta[kBatch];
     uint32_t rq_tf[kBatch];
     uint32_t rq_id[kBatch];
-    Addr wave_top[kThreads / kWave];
-    Addr wave_hit[kThreads / kWave];
-    Span<Addr> pend_span[2][kPend];      // side buffer, sorted; two copies alternate between steps
-    uint2 pend_life[2][kPend];
+    Addr wave_top[kWaves];                                 // single-request path
+    Addr wave_hit[kWaves];
+    Addr top[kWaves][kPend];                               // chunk maximum per (wave, request)
+    uint32_t holes[kWaves][kPend];                         // holes found per (wave, request), may exceed kSlots
+    Span<Addr> hole[kWaves][kPend][kSlots];                // {hole end, chunk-local covered}
+    Span<Addr> pend_span[kPend];                           // blocks settled in this batch, sorted
+    uint2 pend_life[kPend];
+    uint32_t settled;
 };
 
 struct PlanParams {
@@ -82,7 +96,7 @@ struct BlockList {
 
 template <typename Addr> constexpr size_t entry_bytes() { return sizeof(Span<Addr>) + sizeof(uint2); }
 
-// The side buffer in registers: pending block q in lane q, ascending start address.
+// The side buffer in registers: block q in lane q, ascending start address.
 template <typename Addr>
 struct Pending {
     Addr lo, hi;
@@ -90,13 +104,13 @@ struct Pending {
 };
 
 template <typename Addr, typename Lds>
-__device__ __forceinline__ Pending<Addr> load_pending(const Lds& sh, uint32_t pending, int copy)
+__device__ __forceinline__ Pending<Addr> load_pending(const Lds& sh, uint32_t pending)
 {
     Pending<Addr> pd = {0, 0, 0, 0};
     const int lane = lane_id();
     if (lane < (int)pending) {
-        const Span<Addr> sp = sh.pend_span[copy][lane];
-        const uint2 lf = sh.pend_life[copy][lane];
+        const Span<Addr> sp = sh.pend_span[lane];
+        const uint2 lf = sh.pend_life[lane];
         pd.lo = sp.lo; pd.hi = sp.hi; pd.ta = lf.x; pd.tf = lf.y;
     }
     return pd;
@@ -147,21 +161,10 @@ __device__ __forceinline__ Addr clear_zones(Addr e, Addr s, const Zones<Addr>& z
     return e;
 }
 
-// f(e) with the side buffer fetched from LDS; only called where a raw candidate shows up.
-template <typename Addr, typename Lds>
-__device__ __forceinline__ Addr clear_pending(Addr e, Addr s, uint32_t ta, uint32_t tf, const Lds& sh,
-                                              uint32_t pending, int copy)
-{
-    if (pending == 0) return e;
-    const Pending<Addr> pd = load_pending<Addr>(sh, pending, copy);
-    return clear_zones(e, s, make_zones(pd, pending, s, ta, tf));
-}
-
-// Sorted insertion of the block [x, x + s) into the side buffer: wave 0 holds the buffer in
-// registers and publishes the whole new buffer to the LDS copy the next step will read.
-template <typename Addr, typename Lds>
+// Sorted insertion of the block [x, x + s) into the register-held side buffer.
+template <typename Addr>
 __device__ __forceinline__ void pending_insert(Pending<Addr>& pd, uint32_t pending, Addr x, Addr s, uint32_t ta,
-                                               uint32_t tf, Lds& sh, int copy_out)
+                                               uint32_t tf)
 {
     const int lane = lane_id();
     const uint64_t keep = __builtin_amdgcn_ballot_w64(lane < (int)pending && pd.lo <= x);
@@ -170,32 +173,120 @@ __device__ __forceinline__ void pending_insert(Pending<Addr>& pd, uint32_t pendi
     const uint32_t up_ta = wave_shift_up(pd.ta, 0u), up_tf = wave_shift_up(pd.tf, 0u);
     if (lane > pos) { pd.lo = up_lo; pd.hi = up_hi; pd.ta = up_ta; pd.tf = up_tf; }
     if (lane == pos) { pd.lo = x; pd.hi = x + s; pd.ta = ta; pd.tf = tf; }
-    if (lane <= (int)pending) {
-        sh.pend_span[copy_out][lane] = Span<Addr>{pd.lo, pd.hi};
-        sh.pend_life[copy_out][lane] = make_uint2(pd.ta, pd.tf);
+}
+
+// One pass over the sorted list for the requests b0 .. b0+nb-1 of the staged batch: publishes,
+// per (wave, request), the chunk maximum of conflicting end addresses and the first holes.
+template <typename Addr, int kPend, int kThreads, typename Lds>
+__device__ __forceinline__ void scan_batch(const BlockList<Addr>& list, uint32_t count, uint32_t b0, uint32_t nb,
+                                           uint32_t shift, Lds& sh)
+{
+    constexpr int kSlots = Lds::kSlots;
+    const int lane = lane_id(), wave = wave_id();
+    // lane r holds request r of the batch; unused lanes get an empty lifetime (conflicts with nothing)
+    Addr rq_s = 0;
+    uint32_t rq_ta = 0, rq_tf = 0;
+    if (lane < (int)nb) {
+        rq_s = (Addr)(sh.rq_size[b0 + lane] >> shift);
+        rq_ta = sh.rq_ta[b0 + lane];
+        rq_tf = sh.rq_tf[b0 + lane];
+    }
+    Addr runv = 0;          // lane r: running maximum for request r inside this wave's chunk
+    uint32_t holesv = 0;    // lane r: holes found for request r
+    const uint32_t sub = (count + kThreads - 1) / kThreads;     // 64-entry steps per wave
+    uint32_t k = (uint32_t)wave * kWave * sub + lane;
+    for (uint32_t j = 0; j < sub; ++j, k += kWave) {
+        const bool valid = k < count;
+        const uint32_t kc = valid ? k : count - 1;
+        const Span<Addr> sp = list.span[kc];
+        const uint2 lf = list.life[kc];
+#pragma unroll
+        for (int r = 0; r < kPend; ++r) {
+            const uint32_t tf_r = read_lane(rq_tf, r), ta_r = read_lane(rq_ta, r);
+            const bool conflict = valid && lf.x < tf_r && ta_r < lf.y;
+            if (__builtin_amdgcn_ballot_w64(conflict)) {
+                const Addr s_r = read_lane(rq_s, r);
+                const Addr run_r = read_lane(runv, r);
+                const Addr incl = wave_scan_max(conflict ? sp.hi : (Addr)0);
+                const Addr covered = umax(run_r, wave_shift_up(incl, (Addr)0));
+                const bool closes = conflict && sp.lo >= covered + s_r;     // hole [covered, sp.lo)
+                const uint64_t closers = __builtin_amdgcn_ballot_w64(closes);
+                if (closers) {
+                    const uint32_t have = read_lane(holesv, r);
+                    const uint32_t slot = have + lanes_below(closers);
+                    if (closes && slot < (uint32_t)kSlots) sh.hole[wave][r][slot] = Span<Addr>{sp.lo, covered};
+                    holesv = write_lane(holesv, have + (uint32_t)__builtin_popcountll(closers), r);
+                }
+                runv = write_lane(runv, umax(run_r, read_lane(incl, kWave - 1)), r);
+            }
+        }
+    }
+    if (lane < kPend) {
+        sh.top[wave][lane] = runv;
+        sh.holes[wave][lane] = holesv;
     }
 }
 
-// Lowest address x such that [x, x + s) meets neither a listed block nor a pending block whose
-// lifetime conflicts with [ta, tf).  All threads of the workgroup call this together; the
-// result is uniform.
-//
-// All running maxima are RAW (side buffer ignored).  Because f(max(a, b)) = max(f(a), f(b)),
-// "covered so far" with the side buffer is f(raw maximum), so f is only evaluated where a raw
-// candidate hole shows up, not for every listed block.
+// Wave 0 settles the requests of the batch in order.  Returns how many were settled; fewer
+// than nb means request b0 + result needs the exact single-request path.
+template <typename Addr, int kPend, int kThreads, typename Lds>
+__device__ __forceinline__ uint32_t resolve_batch(uint32_t b0, uint32_t nb, uint32_t shift, Addr& peak, Lds& sh)
+{
+    constexpr int kSlots = Lds::kSlots;
+    const int lane = lane_id();
+    const int w = lane / kSlots, c = lane % kSlots;     // lanes in address order: (wave, hole slot)
+    Pending<Addr> pd = {0, 0, 0, 0};
+    uint32_t r = 0;
+    for (; r < nb; ++r) {
+        const Addr s = (Addr)(sh.rq_size[b0 + r] >> shift);
+        const uint32_t ta = sh.rq_ta[b0 + r], tf = sh.rq_tf[b0 + r];
+        const bool live = w < Lds::kWaves;                  // (always true unless kSlots was shrunk)
+        const int wc = live ? w : 0;
+        const Addr topv = live ? sh.top[wc][r] : (Addr)0;
+        const uint32_t found = live ? sh.holes[wc][r] : 0u;
+        const Span<Addr> hl = sh.hole[wc][r][c];
+        // covered below wave w = max of the chunk maxima of the waves below it
+        const Addr incl = wave_scan_max(topv);
+        const Addr below = lane_gather(wave_shift_up(incl, (Addr)0), wc * kSlots);
+        const Addr covered = umax(below, hl.hi);
+        const Zones<Addr> zones = make_zones(pd, r, s, ta, tf);
+        const Addr cleared = clear_zones(covered, s, zones);
+        const uint64_t fits = __builtin_amdgcn_ballot_w64((uint32_t)c < found && hl.lo >= cleared + s);
+        const uint64_t crowded = __builtin_amdgcn_ballot_w64(found > (uint32_t)kSlots);   // waves with unpublished holes
+        Addr x;
+        if (fits) {
+            const int h = __builtin_ctzll(fits);
+            if (crowded && __builtin_ctzll(crowded) / kSlots < h / kSlots) break;    // an unpublished hole lies lower
+            x = read_lane(cleared, h);
+        } else {
+            if (crowded) break;
+            x = read_lane(clear_zones(read_lane(incl, kWave - 1), s, zones), 0);
+        }
+        peak = umax(peak, (Addr)(x + s));
+        if (lane == 0) sh.rq_addr[b0 + r] = (uint64_t)x << shift;
+        pending_insert(pd, r, x, s, ta, tf);
+    }
+    if (lane < (int)r) {
+        sh.pend_span[lane] = Span<Addr>{pd.lo, pd.hi};
+        sh.pend_life[lane] = make_uint2(pd.ta, pd.tf);
+    }
+    if (lane == 0) sh.settled = r;
+    return r;
+}
+
+// Exact placement of one request against the sorted list alone (no side buffer): lowest
+// address x such that [x, x + s) meets no listed block whose lifetime conflicts with [ta, tf).
+// All threads of the workgroup call this together; the result is uniform.
 template <typename Addr, int kThreads, typename Lds>
 __device__ __forceinline__ Addr lowest_fit(const BlockList<Addr>& list, uint32_t count, Addr s, uint32_t ta,
-                                           uint32_t tf, uint32_t pending, int copy, Lds& sh)
+                                           uint32_t tf, Lds& sh)
 {
     constexpr int kWaves = kThreads / kWave;
     constexpr int kMaxSub = kPassEntries / kThreads;
     constexpr Addr kNoHit = Top<Addr>::value;
     const int lane = lane_id(), wave = wave_id();
-    Addr covered = 0;                    // raw: first address not blocked by listed blocks so far
-    if (count == 0) {
-        __syncthreads();                 // the side buffer written at the end of the previous step is visible
-        return clear_pending(covered, s, ta, tf, sh, pending, copy);
-    }
+    Addr covered = 0;                    // first address not blocked by listed blocks so far
+    if (count == 0) return covered;
     const uint32_t last = count - 1;
 
     for (uint32_t base = 0;;) {
@@ -203,56 +294,35 @@ __device__ __forceinline__ Addr lowest_fit(const BlockList<Addr>& list, uint32_t
         uint32_t sub = (left + kThreads - 1) / kThreads;         // 64-entry steps per wave in this pass
         if (sub > (uint32_t)kMaxSub) sub = kMaxSub;
         const uint32_t chunk0 = base + (uint32_t)wave * kWave * sub;
-
-        Addr lo_keep[kMaxSub], before_keep[kMaxSub];
-        uint32_t maybe = 0;              // steps in which some lane could be a stop
-        Addr run = 0;                    // running maximum inside this wave's chunk
-        // entries past the end are read from the last entry and masked out afterwards
-        uint32_t k_next = chunk0 + lane;
-        Span<Addr> sp_next = list.span[k_next < last ? k_next : last];
-        uint2 lf_next = list.life[k_next < last ? k_next : last];
-#pragma unroll
-        for (int j = 0; j < kMaxSub; ++j) {
-            lo_keep[j] = 0;
-            before_keep[j] = 0;
-            if ((uint32_t)j < sub) {
-                const uint32_t k = k_next;
-                const Span<Addr> sp = sp_next;
-                const uint2 lf = lf_next;
-                if ((uint32_t)(j + 1) < sub) {
-                    k_next = k + kWave;
-                    sp_next = list.span[k_next < last ? k_next : last];
-                    lf_next = list.life[k_next < last ? k_next : last];
-                }
-                const bool valid = k < count;
-                const bool conflict = valid && lf.x < tf && ta < lf.y;
-                const Addr incl = wave_scan_max(conflict ? sp.hi : (Addr)0);
-                const Addr before = umax(run, wave_shift_up(incl, (Addr)0));
-                const Addr lo = valid ? sp.lo : (Addr)0;      // 0 past the end: never a stop (s > 0)
-                lo_keep[j] = lo;
-                before_keep[j] = before;
-                if (__builtin_amdgcn_ballot_w64(lo >= before + s)) maybe |= 1u << j;
-                run = umax(run, read_lane(incl, kWave - 1));
-            }
+        Addr run = 0;
+        Addr hit = kNoHit;
+        for (uint32_t j = 0; j < sub; ++j) {
+            const uint32_t k = chunk0 + j * kWave + lane;
+            const bool valid = k < count;
+            const Span<Addr> sp = list.span[valid ? k : last];
+            const uint2 lf = list.life[valid ? k : last];
+            const bool conflict = valid && lf.x < tf && ta < lf.y;
+            const Addr incl = wave_scan_max(conflict ? sp.hi : (Addr)0);
+            run = umax(run, read_lane(incl, kWave - 1));
         }
         if (lane == 0) sh.wave_top[wave] = run;
         __syncthreads();
-
-        // maxima of the chunks below this wave, and of all chunks
         const Addr tops = row_scan_max(lane < kWaves ? sh.wave_top[lane] : (Addr)0);
         const Addr below = umax(covered, wave > 0 ? read_lane(tops, wave - 1) : (Addr)0);
         const Addr all = umax(covered, read_lane(tops, kWaves - 1));
-        Addr hit = kNoHit;
-#pragma unroll
-        for (int j = 0; j < kMaxSub; ++j) {
-            if (hit == kNoHit && (maybe & (1u << j))) {
-                const Addr before = umax(below, before_keep[j]);
-                if (__builtin_amdgcn_ballot_w64(lo_keep[j] >= before + s)) {      // a raw hole: now ask the side buffer
-                    const Addr cleared = clear_pending(before, s, ta, tf, sh, pending, copy);
-                    const uint64_t stops = __builtin_amdgcn_ballot_w64(lo_keep[j] >= cleared + s);
-                    if (stops) hit = read_lane(cleared, __builtin_ctzll(stops));
-                }
-            }
+        // second walk with everything below known: first block that starts >= s above "covered"
+        run = below;
+        for (uint32_t j = 0; j < sub && hit == kNoHit; ++j) {
+            const uint32_t k = chunk0 + j * kWave + lane;
+            const bool valid = k < count;
+            const Span<Addr> sp = list.span[valid ? k : last];
+            const uint2 lf = list.life[valid ? k : last];
+            const bool conflict = valid && lf.x < tf && ta < lf.y;
+            const Addr incl = wave_scan_max(conflict ? sp.hi : (Addr)0);
+            const Addr before = umax(run, wave_shift_up(incl, (Addr)0));
+            const uint64_t stops = __builtin_amdgcn_ballot_w64(valid && sp.lo >= before + s);
+            if (stops) hit = read_lane(before, __builtin_ctzll(stops));
+            run = umax(run, read_lane(incl, kWave - 1));
         }
         if (lane == 0) sh.wave_hit[wave] = hit;
         __syncthreads();
@@ -261,7 +331,7 @@ __device__ __forceinline__ Addr lowest_fit(const BlockList<Addr>& list, uint32_t
         if (hits) return read_lane(h, __builtin_ctzll(hits));
         covered = all;
         base += kThreads * sub;
-        if (base >= count) return clear_pending(covered, s, ta, tf, sh, pending, copy);
+        if (base >= count) return covered;
     }
 }
 
@@ -274,17 +344,17 @@ __device__ __forceinline__ uint32_t pending_at_or_below(const Pending<Addr>& pd,
     return c;
 }
 
-// Merges the side buffer into the sorted list.  Listed block k moves to k + c_k, where c_k is
-// the number of pending blocks at or below its start address; pending block q lands at
-// k + q in front of the first listed block k with c_k > q (or behind the last one).
-// The caller has synchronised the workgroup after the side buffer copy `copy` was written.
+// Merges the side buffer (sh.pend_*, sorted, `pending` blocks, already visible to the whole
+// workgroup) into the sorted list.  Listed block k moves to k + c_k, where c_k is the number
+// of pending blocks at or below its start address; pending block q lands at k + q in front of
+// the first listed block k with c_k > q (or behind the last one).
 template <typename Addr, bool kLds, int kThreads, typename Lds>
 __device__ __forceinline__ void merge_pending(BlockList<Addr>& list, BlockList<Addr>& spare, uint32_t count,
-                                              uint32_t pending, int copy, Lds& sh)
+                                              uint32_t pending, Lds& sh)
 {
     constexpr int kMaxSub = kPassEntries / kThreads;
     const int lane = lane_id(), wave = wave_id();
-    const Pending<Addr> pd = load_pending<Addr>(sh, pending, copy);
+    const Pending<Addr> pd = load_pending<Addr>(sh, pending);
     BlockList<Addr>& dst = kLds ? list : spare;
     for (uint32_t base = 0; base <= count;) {    // "<=": the position just past the end takes the tail
         const uint32_t left = count + 1 - base;
@@ -325,8 +395,8 @@ __device__ __forceinline__ void merge_pending(BlockList<Addr>& list, BlockList<A
             }
             if ((uint32_t)j < sub && k <= count) {
                 for (uint32_t q = c_prev[j]; q < c_here[j]; ++q) {
-                    dst.span[k + q] = sh.pend_span[copy][q];
-                    dst.life[k + q] = sh.pend_life[copy][q];
+                    dst.span[k + q] = sh.pend_span[q];
+                    dst.life[k + q] = sh.pend_life[q];
                 }
             }
         }
@@ -368,15 +438,13 @@ __global__ void __launch_bounds__(kThreads) plan_kernel(PlanParams prm)
     for (uint32_t p = blockIdx.x; p < prm.P; p += gridDim.x) {
         const uint32_t* order = prm.orders + (size_t)p * n;
         uint64_t* out = prm.offsets ? prm.offsets + (size_t)p * n : nullptr;
-        Addr peak = 0;
-        uint32_t count = 0, pending = 0;
-        int copy = 0;                                  // side-buffer copy this step reads
-        Pending<Addr> pd = {0, 0, 0, 0};              // wave 0's register image of the side buffer
+        Addr peak = 0;                                        // tracked by wave 0
+        uint32_t count = 0;
 
         for (uint32_t r0 = 0; r0 < n; r0 += kBatch) {
-            const uint32_t nb = n - r0 < (uint32_t)kBatch ? n - r0 : (uint32_t)kBatch;
+            const uint32_t staged = n - r0 < (uint32_t)kBatch ? n - r0 : (uint32_t)kBatch;
             __syncthreads();                                  // previous batch fully consumed
-            if (threadIdx.x < nb) {
+            if (threadIdx.x < staged) {
                 uint32_t i = order[r0 + threadIdx.x];
                 if (i >= n) { atomicMax(prm.status, (uint32_t)STALLOC_ERR_BAD_ORDER); i = 0; }
                 sh.rq_id[threadIdx.x] = i;
@@ -386,27 +454,38 @@ __global__ void __launch_bounds__(kThreads) plan_kernel(PlanParams prm)
             }
             __syncthreads();
 
-            for (uint32_t b = 0; b < nb; ++b) {
-                const Addr s = (Addr)(sh.rq_size[b] >> shift);
-                const uint32_t ta = sh.rq_ta[b], tf = sh.rq_tf[b];
-                const Addr x = lowest_fit<Addr, kThreads>(list, count, s, ta, tf, pending, copy, sh);
-                peak = umax(peak, (Addr)(x + s));
-                if (wave_id() == 0) {
-                    if (lane_id() == 0) sh.rq_addr[b] = (uint64_t)x << shift;
-                    pending_insert(pd, pending, x, s, ta, tf, sh, copy ^ 1);
-                }
-                ++pending;
-                copy ^= 1;
-                if (pending == (uint32_t)kPend && r0 + b + 1 < n) {
-                    __syncthreads();                          // the side buffer is complete and visible
-                    merge_pending<Addr, kLds, kThreads>(list, spare, count, pending, copy, sh);
-                    count += pending;
-                    pending = 0;
+            for (uint32_t b0 = 0; b0 < staged;) {
+                const uint32_t nb = staged - b0 < (uint32_t)kPend ? staged - b0 : (uint32_t)kPend;
+                scan_batch<Addr, kPend, kThreads>(list, count, b0, nb, shift, sh);
+                __syncthreads();
+                if (wave_id() == 0) resolve_batch<Addr, kPend, kThreads>(b0, nb, shift, peak, sh);
+                __syncthreads();
+                const uint32_t settled = sh.settled;
+                const bool last_of_plan = r0 + b0 + settled >= n;
+                if (settled && !last_of_plan) merge_pending<Addr, kLds, kThreads>(list, spare, count, settled, sh);
+                count += settled;
+                b0 += settled;
+                if (settled < nb) {
+                    // request b0 could not be settled from the published holes: exact path
+                    const Addr s = (Addr)(sh.rq_size[b0] >> shift);
+                    const uint32_t ta = sh.rq_ta[b0], tf = sh.rq_tf[b0];
+                    const Addr x = lowest_fit<Addr, kThreads>(list, count, s, ta, tf, sh);
+                    __syncthreads();                          // everyone has read sh.settled / pend_*
+                    if (threadIdx.x == 0) {
+                        peak = umax(peak, (Addr)(x + s));
+                        sh.rq_addr[b0] = (uint64_t)x << shift;
+                        sh.pend_span[0] = Span<Addr>{x, (Addr)(x + s)};
+                        sh.pend_life[0] = make_uint2(ta, tf);
+                    }
+                    __syncthreads();
+                    if (r0 + b0 + 1 < n) merge_pending<Addr, kLds, kThreads>(list, spare, count, 1u, sh);
+                    count += 1;
+                    b0 += 1;
                 }
             }
             // addresses of this batch -> offsets[p][request id]
             __syncthreads();
-            if (out && threadIdx.x < nb) out[sh.rq_id[threadIdx.x]] = sh.rq_addr[threadIdx.x];
+            if (out && threadIdx.x < staged) out[sh.rq_id[threadIdx.x]] = sh.rq_addr[threadIdx.x];
         }
         if (threadIdx.x == 0) prm.peaks[p] = (uint64_t)peak << shift;
     }
@@ -449,7 +528,7 @@ __global__ void __launch_bounds__(256) plan_copy_best(const uint64_t* __restrict
 #define STALLOC_PEND_LDS 16
 #endif
 #ifndef STALLOC_PEND_MEM
-#define STALLOC_PEND_MEM 16
+#define STALLOC_PEND_MEM 32
 #endif
 #ifndef STALLOC_THREADS_LDS
 #define STALLOC_THREADS_LDS 1024
@@ -457,8 +536,8 @@ __global__ void __launch_bounds__(256) plan_copy_best(const uint64_t* __restrict
 #ifndef STALLOC_THREADS_MEM
 #define STALLOC_THREADS_MEM 1024
 #endif
-constexpr int kPendLds = STALLOC_PEND_LDS;        // side-buffer size when the list is in LDS
-constexpr int kPendMem = STALLOC_PEND_MEM;        // ... and when it is in the workspace (merges cost a pass over memory)
+constexpr int kPendLds = STALLOC_PEND_LDS;        // requests per batch when the list is in LDS
+constexpr int kPendMem = STALLOC_PEND_MEM;        // ... and when it is in the workspace (every batch costs passes over memory)
 constexpr int kThreadsLds = STALLOC_THREADS_LDS;
 constexpr int kThreadsMem = STALLOC_THREADS_MEM;
 

@@ -137,6 +137,33 @@ __device__ __forceinline__ uint64_t wave_shift_up(uint64_t v, uint64_t fill) { r
 __device__ __forceinline__ uint32_t read_lane(uint32_t v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
 __device__ __forceinline__ uint64_t read_lane(uint64_t v, int lane) { return readlane64(v, lane); }
 
+// v with lane `lane` replaced by the (uniform) value.
+__device__ __forceinline__ uint32_t write_lane(uint32_t v, uint32_t value, int lane)
+{
+    return (int)(threadIdx.x & (kWave - 1)) == lane ? value : v;
+}
+__device__ __forceinline__ uint64_t write_lane(uint64_t v, uint64_t value, int lane)
+{
+    return (int)(threadIdx.x & (kWave - 1)) == lane ? value : v;
+}
+
+// Value held by lane `src` (any lane index per lane; goes through the LDS crossbar).
+__device__ __forceinline__ uint32_t lane_gather(uint32_t v, int src)
+{
+    return (uint32_t)__builtin_amdgcn_ds_bpermute(src << 2, (int)v);
+}
+__device__ __forceinline__ uint64_t lane_gather(uint64_t v, int src)
+{
+    uint32_t lo = lane_gather((uint32_t)v, src), hi = lane_gather((uint32_t)(v >> 32), src);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// Number of set bits of `mask` in lanes below the calling lane.
+__device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
 __device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
 __device__ __forceinline__ uint64_t umax(uint64_t a, uint64_t b) { return a > b ? a : b; }
 
