@@ -191,8 +191,10 @@ __device__ __forceinline__ void scan_batch(const BlockList<Addr>& list, uint32_t
         rq_ta = sh.rq_ta[b0 + lane];
         rq_tf = sh.rq_tf[b0 + lane];
     }
-    Addr runv = 0;          // lane r: running maximum for request r inside this wave's chunk
-    uint32_t holesv = 0;    // lane r: holes found for request r
+    Addr run[kPend];        // uniform: running maximum for request r inside this wave's chunk
+    uint32_t found[kPend];  // uniform: holes found for request r
+#pragma unroll
+    for (int r = 0; r < kPend; ++r) { run[r] = 0; found[r] = 0; }
     const uint32_t sub = (count + kThreads - 1) / kThreads;     // 64-entry steps per wave
     uint32_t k = (uint32_t)wave * kWave * sub + lane;
     for (uint32_t j = 0; j < sub; ++j, k += kWave) {
@@ -200,30 +202,51 @@ __device__ __forceinline__ void scan_batch(const BlockList<Addr>& list, uint32_t
         const uint32_t kc = valid ? k : count - 1;
         const Span<Addr> sp = list.span[kc];
         const uint2 lf = list.life[kc];
+        const uint64_t valid_m = __builtin_amdgcn_ballot_w64(valid);
+        // requests in groups of kGroup: their running-maximum chains are independent, so the
+        // compiler can interleave the DPP steps of one chain into the wait states of the others
+        constexpr int kGroup = 4;
 #pragma unroll
-        for (int r = 0; r < kPend; ++r) {
-            const uint32_t tf_r = read_lane(rq_tf, r), ta_r = read_lane(rq_ta, r);
-            const bool conflict = valid && lf.x < tf_r && ta_r < lf.y;
-            if (__builtin_amdgcn_ballot_w64(conflict)) {
+        for (int g = 0; g < kPend; g += kGroup) {
+            Addr incl[kGroup], covered[kGroup];
+            uint64_t conflict_m[kGroup], closers[kGroup];
+            uint64_t any_closer = 0;
+#pragma unroll
+            for (int q = 0; q < kGroup; ++q) {
+                const int r = g + q;
+                const uint32_t tf_r = read_lane(rq_tf, r), ta_r = read_lane(rq_ta, r);
+                conflict_m[q] = valid_m & lanes_lt(lf.x, tf_r) & lanes_lt(ta_r, lf.y);
+                incl[q] = wave_scan_max(keep_lanes(conflict_m[q], sp.hi));
+            }
+#pragma unroll
+            for (int q = 0; q < kGroup; ++q) {
+                const int r = g + q;
                 const Addr s_r = read_lane(rq_s, r);
-                const Addr run_r = read_lane(runv, r);
-                const Addr incl = wave_scan_max(conflict ? sp.hi : (Addr)0);
-                const Addr covered = umax(run_r, wave_shift_up(incl, (Addr)0));
-                const bool closes = conflict && sp.lo >= covered + s_r;     // hole [covered, sp.lo)
-                const uint64_t closers = __builtin_amdgcn_ballot_w64(closes);
-                if (closers) {
-                    const uint32_t have = read_lane(holesv, r);
-                    const uint32_t slot = have + lanes_below(closers);
-                    if (closes && slot < (uint32_t)kSlots) sh.hole[wave][r][slot] = Span<Addr>{sp.lo, covered};
-                    holesv = write_lane(holesv, have + (uint32_t)__builtin_popcountll(closers), r);
+                covered[q] = umax(run[r], wave_shift_up(incl[q], (Addr)0));
+                closers[q] = conflict_m[q] & lanes_ge(sp.lo, (Addr)(covered[q] + s_r));
+                any_closer |= closers[q];
+                run[r] = umax(run[r], read_lane(incl[q], kWave - 1));
+            }
+            if (any_closer) {
+#pragma unroll
+                for (int q = 0; q < kGroup; ++q) {
+                    const int r = g + q;
+                    if (closers[q]) {                            // hole [covered, sp.lo) in front of a conflicting block
+                        const uint32_t slot = found[r] + lanes_below(closers[q]);
+                        if (((closers[q] >> lane) & 1) && slot < (uint32_t)kSlots)
+                            sh.hole[wave][r][slot] = Span<Addr>{sp.lo, covered[q]};
+                        found[r] += (uint32_t)__builtin_popcountll(closers[q]);
+                    }
                 }
-                runv = write_lane(runv, umax(run_r, read_lane(incl, kWave - 1)), r);
             }
         }
     }
-    if (lane < kPend) {
-        sh.top[wave][lane] = runv;
-        sh.holes[wave][lane] = holesv;
+    if (lane == 0) {
+#pragma unroll
+        for (int r = 0; r < kPend; ++r) {
+            sh.top[wave][r] = run[r];
+            sh.holes[wave][r] = found[r];
+        }
     }
 }
 

@@ -158,6 +158,25 @@ __device__ __forceinline__ uint64_t lane_gather(uint64_t v, int src)
     return ((uint64_t)hi << 32) | lo;
 }
 
+// Lane masks straight from a vector compare (one v_cmp, no per-lane boolean in between).
+__device__ __forceinline__ uint64_t lanes_lt(uint32_t a, uint32_t b) { return __builtin_amdgcn_uicmp(a, b, 36); }
+__device__ __forceinline__ uint64_t lanes_ge(uint32_t a, uint32_t b) { return __builtin_amdgcn_uicmp(a, b, 35); }
+__device__ __forceinline__ uint64_t lanes_ge(uint64_t a, uint64_t b) { return __builtin_amdgcn_uicmpl(a, b, 35); }
+
+// Per lane: mask bit set ? v : 0.  The trailing wait states keep the result safe for a DPP
+// consumer scheduled right behind the statement (the compiler does not track hazards of
+// instructions inside an asm statement).
+__device__ __forceinline__ uint32_t keep_lanes(uint64_t mask, uint32_t v)
+{
+    uint32_t r;
+    asm("v_cndmask_b32_e64 %0, 0, %1, %2\n\ts_nop 1" : "=v"(r) : "v"(v), "s"(mask));
+    return r;
+}
+__device__ __forceinline__ uint64_t keep_lanes(uint64_t mask, uint64_t v)
+{
+    return ((uint64_t)keep_lanes(mask, (uint32_t)(v >> 32)) << 32) | keep_lanes(mask, (uint32_t)v);
+}
+
 // Number of set bits of `mask` in lanes below the calling lane.
 __device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
 {
