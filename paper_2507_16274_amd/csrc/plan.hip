@@ -15,10 +15,13 @@
 //            conflicting block that starts at least size_r above it closes a hole
 //            [covered, start) in which r could fit.  Per (wave, request) the wave publishes
 //            its chunk maximum and its first few holes (with chunk-local "covered") to LDS.
-//   resolve  After one barrier, wave 0 settles the K requests in order.  For request r the
-//            published holes of all waves sit in its 64 lanes in address order; the true
-//            "covered" of a hole is the maximum of its local value and the chunk maxima of
-//            the waves below.  The blocks already settled in this batch (the side buffer,
+//   survey   After a barrier, wave r gathers what all waves published for request r into its
+//            64 lanes in address order; the true "covered" of a hole is the maximum of its
+//            local value and the chunk maxima of the waves below.  It records the first hole
+//            that is large enough as such (or the top).
+//   resolve  After another barrier, wave 0 settles the K requests in order: if no block
+//            settled earlier in the batch gets in the way of the surveyed address, that is
+//            the answer; otherwise the holes are looked at again with those blocks honoured.  The blocks already settled in this batch (the side buffer,
 //            sorted, one per lane) are honoured through f(c) = lowest address >= c that clears
 //            the side-buffer blocks conflicting with r: r takes the first hole with
 //            f(covered) + size_r <= hole end, else goes on top at f(maximum).  f is evaluated
@@ -69,6 +72,8 @@ struct PlanLds {
     Addr top[kWaves][kPend];                               // chunk maximum per (wave, request)
     uint32_t holes[kWaves][kPend];                         // holes found per (wave, request), may exceed kSlots
     Span<Addr> hole[kWaves][kPend][kSlots];                // {hole end, chunk-local covered}
+    Addr first[kPend];                                     // survey: first raw hole (or top) per request
+    uint32_t first_open[kPend];                            // survey: 0 if an unpublished hole may lie below it
     Span<Addr> pend_span[kPend];                           // blocks settled in this batch, sorted
     uint2 pend_life[kPend];
     uint32_t settled;
@@ -193,8 +198,13 @@ __device__ __forceinline__ void scan_batch(const BlockList<Addr>& list, uint32_t
     }
     Addr run[kPend];        // uniform: running maximum for request r inside this wave's chunk
     uint32_t found[kPend];  // uniform: holes found for request r
+    Addr s_of[kPend];       // uniform copies of the request parameters
+    uint32_t ta_of[kPend], tf_of[kPend];
 #pragma unroll
-    for (int r = 0; r < kPend; ++r) { run[r] = 0; found[r] = 0; }
+    for (int r = 0; r < kPend; ++r) {
+        run[r] = 0; found[r] = 0;
+        s_of[r] = read_lane(rq_s, r); ta_of[r] = read_lane(rq_ta, r); tf_of[r] = read_lane(rq_tf, r);
+    }
     const uint32_t sub = (count + kThreads - 1) / kThreads;     // 64-entry steps per wave
     uint32_t k = (uint32_t)wave * kWave * sub + lane;
     for (uint32_t j = 0; j < sub; ++j, k += kWave) {
@@ -214,16 +224,14 @@ __device__ __forceinline__ void scan_batch(const BlockList<Addr>& list, uint32_t
 #pragma unroll
             for (int q = 0; q < kGroup; ++q) {
                 const int r = g + q;
-                const uint32_t tf_r = read_lane(rq_tf, r), ta_r = read_lane(rq_ta, r);
-                conflict_m[q] = valid_m & lanes_lt(lf.x, tf_r) & lanes_lt(ta_r, lf.y);
+                conflict_m[q] = valid_m & lanes_lt(lf.x, tf_of[r]) & lanes_lt(ta_of[r], lf.y);
                 incl[q] = wave_scan_max(keep_lanes(conflict_m[q], sp.hi));
             }
 #pragma unroll
             for (int q = 0; q < kGroup; ++q) {
                 const int r = g + q;
-                const Addr s_r = read_lane(rq_s, r);
                 covered[q] = umax(run[r], wave_shift_up(incl[q], (Addr)0));
-                closers[q] = conflict_m[q] & lanes_ge(sp.lo, (Addr)(covered[q] + s_r));
+                closers[q] = conflict_m[q] & lanes_ge(sp.lo, (Addr)(covered[q] + s_of[r]));
                 any_closer |= closers[q];
                 run[r] = umax(run[r], read_lane(incl[q], kWave - 1));
             }
@@ -231,12 +239,15 @@ __device__ __forceinline__ void scan_batch(const BlockList<Addr>& list, uint32_t
 #pragma unroll
                 for (int q = 0; q < kGroup; ++q) {
                     const int r = g + q;
-                    if (closers[q]) {                            // hole [covered, sp.lo) in front of a conflicting block
-                        const uint32_t slot = found[r] + lanes_below(closers[q]);
-                        if (((closers[q] >> lane) & 1) && slot < (uint32_t)kSlots)
-                            sh.hole[wave][r][slot] = Span<Addr>{sp.lo, covered[q]};
-                        found[r] += (uint32_t)__builtin_popcountll(closers[q]);
+                    uint64_t m = closers[q];                     // holes [covered, sp.lo) in front of conflicting blocks
+                    while (m && found[r] < (uint32_t)kSlots) {
+                        const int f = __builtin_ctzll(m);
+                        m &= m - 1;
+                        // uniform address and data: every lane stores the same record
+                        sh.hole[wave][r][found[r]] = Span<Addr>{read_lane(sp.lo, f), read_lane(covered[q], f)};
+                        ++found[r];
                     }
+                    if (m) found[r] = kSlots + 1;                // more holes than slots
                 }
             }
         }
@@ -250,40 +261,100 @@ __device__ __forceinline__ void scan_batch(const BlockList<Addr>& list, uint32_t
     }
 }
 
+// What the waves published for request r, gathered into the 64 lanes of one wave in address
+// order (lane = wave * kSlots + slot), with the true "covered" of every hole.
+template <typename Addr>
+struct HoleView {
+    Addr covered;        // per lane: covered in front of this hole (chunk maxima of lower waves included)
+    Addr end;            // per lane: address at which the hole ends
+    Addr top;            // uniform: maximum over all chunks (where the request goes if no hole fits)
+    uint64_t published;  // lanes that hold a hole
+    uint64_t crowded;    // lanes of waves that found more holes than they could publish
+};
+
+template <typename Addr, typename Lds>
+__device__ __forceinline__ HoleView<Addr> view_holes(const Lds& sh, uint32_t r)
+{
+    constexpr int kSlots = Lds::kSlots;
+    const int lane = lane_id();
+    const int w = lane / kSlots, c = lane % kSlots;
+    const bool live = w < Lds::kWaves;                  // (always true unless kSlots was shrunk)
+    const int wc = live ? w : 0;
+    const Addr topv = live ? sh.top[wc][r] : (Addr)0;
+    const uint32_t found = live ? sh.holes[wc][r] : 0u;
+    const Span<Addr> hl = sh.hole[wc][r][c];
+    const Addr incl = wave_scan_max(topv);
+    const Addr below = lane_gather(wave_shift_up(incl, (Addr)0), wc * kSlots);
+    HoleView<Addr> v;
+    v.covered = umax(below, hl.hi);
+    v.end = hl.lo;
+    v.top = read_lane(incl, kWave - 1);
+    v.published = lanes_lt((uint32_t)c, found);
+    v.crowded = __builtin_amdgcn_ballot_w64(found > (uint32_t)kSlots);
+    return v;
+}
+
+// True if a wave with unpublished holes lies below lane h (h < 0: the request would go on top).
+template <typename Lds>
+__device__ __forceinline__ bool unpublished_below(uint64_t crowded, int h)
+{
+    return crowded && (h < 0 || __builtin_ctzll(crowded) / Lds::kSlots < h / Lds::kSlots);
+}
+
+// Survey (all waves, request r handled by wave r mod #waves): the first hole that is large
+// enough as such -- or the top -- and whether an unpublished hole could lie below it.
+template <typename Addr, int kPend, int kThreads, typename Lds>
+__device__ __forceinline__ void survey_batch(uint32_t b0, uint32_t nb, uint32_t shift, Lds& sh)
+{
+    for (uint32_t r = (uint32_t)wave_id(); r < nb; r += Lds::kWaves) {
+        const Addr s = (Addr)(sh.rq_size[b0 + r] >> shift);
+        const HoleView<Addr> v = view_holes<Addr>(sh, r);
+        const uint64_t raw = v.published & lanes_ge(v.end, (Addr)(v.covered + s));
+        const int h0 = raw ? __builtin_ctzll(raw) : -1;
+        const Addr first = raw ? read_lane(v.covered, h0) : v.top;
+        if (lane_id() == 0) {
+            sh.first[r] = first;
+            sh.first_open[r] = unpublished_below<Lds>(v.crowded, h0) ? 0u : 1u;
+        }
+    }
+}
+
 // Wave 0 settles the requests of the batch in order.  Returns how many were settled; fewer
 // than nb means request b0 + result needs the exact single-request path.
 template <typename Addr, int kPend, int kThreads, typename Lds>
 __device__ __forceinline__ uint32_t resolve_batch(uint32_t b0, uint32_t nb, uint32_t shift, Addr& peak, Lds& sh)
 {
-    constexpr int kSlots = Lds::kSlots;
     const int lane = lane_id();
-    const int w = lane / kSlots, c = lane % kSlots;     // lanes in address order: (wave, hole slot)
+    // lane r holds request r of the batch and what the survey found for it
+    Addr rq_s = 0, firstv = 0;
+    uint32_t rq_ta = 0, rq_tf = 0, openv = 0;
+    if (lane < (int)nb) {
+        rq_s = (Addr)(sh.rq_size[b0 + lane] >> shift);
+        rq_ta = sh.rq_ta[b0 + lane];
+        rq_tf = sh.rq_tf[b0 + lane];
+        firstv = sh.first[lane];
+        openv = sh.first_open[lane];
+    }
     Pending<Addr> pd = {0, 0, 0, 0};
     uint32_t r = 0;
     for (; r < nb; ++r) {
-        const Addr s = (Addr)(sh.rq_size[b0 + r] >> shift);
-        const uint32_t ta = sh.rq_ta[b0 + r], tf = sh.rq_tf[b0 + r];
-        const bool live = w < Lds::kWaves;                  // (always true unless kSlots was shrunk)
-        const int wc = live ? w : 0;
-        const Addr topv = live ? sh.top[wc][r] : (Addr)0;
-        const uint32_t found = live ? sh.holes[wc][r] : 0u;
-        const Span<Addr> hl = sh.hole[wc][r][c];
-        // covered below wave w = max of the chunk maxima of the waves below it
-        const Addr incl = wave_scan_max(topv);
-        const Addr below = lane_gather(wave_shift_up(incl, (Addr)0), wc * kSlots);
-        const Addr covered = umax(below, hl.hi);
-        const Zones<Addr> zones = make_zones(pd, r, s, ta, tf);
-        const Addr cleared = clear_zones(covered, s, zones);
-        const uint64_t fits = __builtin_amdgcn_ballot_w64((uint32_t)c < found && hl.lo >= cleared + s);
-        const uint64_t crowded = __builtin_amdgcn_ballot_w64(found > (uint32_t)kSlots);   // waves with unpublished holes
+        const Addr s = read_lane(rq_s, (int)r);
+        const uint32_t ta = read_lane(rq_ta, (int)r), tf = read_lane(rq_tf, (int)r);
+        const Addr first = read_lane(firstv, (int)r);
+        // does a block settled earlier in this batch get in the way of the surveyed address?
+        const bool clash = lane < (int)r && pd.ta < tf && ta < pd.tf && pd.lo < first + s && pd.hi > first;
         Addr x;
-        if (fits) {
-            const int h = __builtin_ctzll(fits);
-            if (crowded && __builtin_ctzll(crowded) / kSlots < h / kSlots) break;    // an unpublished hole lies lower
-            x = read_lane(cleared, h);
+        if (!__builtin_amdgcn_ballot_w64(clash)) {
+            if (!read_lane(openv, (int)r)) break;             // an unpublished hole may lie lower
+            x = first;
         } else {
-            if (crowded) break;
-            x = read_lane(clear_zones(read_lane(incl, kWave - 1), s, zones), 0);
+            const HoleView<Addr> v = view_holes<Addr>(sh, r);
+            const Zones<Addr> zones = make_zones(pd, r, s, ta, tf);
+            const Addr cleared = clear_zones(v.covered, s, zones);
+            const uint64_t fits = v.published & lanes_ge(v.end, (Addr)(cleared + s));
+            const int h = fits ? __builtin_ctzll(fits) : -1;
+            if (unpublished_below<Lds>(v.crowded, h)) break;
+            x = fits ? read_lane(cleared, h) : read_lane(clear_zones(v.top, s, zones), 0);
         }
         peak = umax(peak, (Addr)(x + s));
         if (lane == 0) sh.rq_addr[b0 + r] = (uint64_t)x << shift;
@@ -378,6 +449,7 @@ __device__ __forceinline__ void merge_pending(BlockList<Addr>& list, BlockList<A
     constexpr int kMaxSub = kPassEntries / kThreads;
     const int lane = lane_id(), wave = wave_id();
     const Pending<Addr> pd = load_pending<Addr>(sh, pending);
+    const Addr p_lowest = read_lane(pd.lo, 0), p_highest = read_lane(pd.lo, (int)pending - 1);
     BlockList<Addr>& dst = kLds ? list : spare;
     for (uint32_t base = 0; base <= count;) {    // "<=": the position just past the end takes the tail
         const uint32_t left = count + 1 - base;
@@ -402,7 +474,14 @@ __device__ __forceinline__ void merge_pending(BlockList<Addr>& list, BlockList<A
                 const uint32_t k = chunk0 + j * kWave + lane;
                 const bool valid = k < count;
                 if (valid) { sp[j] = list.span[k]; lf[j] = list.life[k]; }
-                const uint32_t c = valid ? pending_at_or_below(pd, pending, sp[j].lo) : pending;
+                // most 64-entry steps lie entirely below the lowest or at/above the highest pending block
+                const uint32_t k0 = chunk0 + j * kWave;
+                uint32_t c = pending;
+                if (k0 < count) {
+                    const int last_lane = count - k0 >= (uint32_t)kWave ? kWave - 1 : (int)(count - k0 - 1);
+                    if (p_lowest > read_lane(sp[j].lo, last_lane)) c = valid ? 0u : pending;
+                    else if (p_highest > read_lane(sp[j].lo, 0)) c = valid ? pending_at_or_below(pd, pending, sp[j].lo) : pending;
+                }
                 c_here[j] = c;
                 c_prev[j] = wave_shift_up(c, carry);
                 carry = read_lane(c, kWave - 1);
@@ -480,6 +559,8 @@ __global__ void __launch_bounds__(kThreads) plan_kernel(PlanParams prm)
             for (uint32_t b0 = 0; b0 < staged;) {
                 const uint32_t nb = staged - b0 < (uint32_t)kPend ? staged - b0 : (uint32_t)kPend;
                 scan_batch<Addr, kPend, kThreads>(list, count, b0, nb, shift, sh);
+                __syncthreads();
+                survey_batch<Addr, kPend, kThreads>(b0, nb, shift, sh);
                 __syncthreads();
                 if (wave_id() == 0) resolve_batch<Addr, kPend, kThreads>(b0, nb, shift, peak, sh);
                 __syncthreads();
