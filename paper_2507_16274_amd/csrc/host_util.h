@@ -62,10 +62,11 @@ struct Carver {
 // Shared device-side trace check (defined in trace_check.hip).
 // acc: device uint64_t[kAccWords] scratch {sum of high halves, sum of low halves, flags,
 // OR of all sizes, mode}.  mode = log2(address granule) | kModeNarrow when 32-bit granule
-// counts can hold every address.
+// counts can hold every address | kModeCompact when 16-bit counts can.
 constexpr int kAccWords = 8;
 constexpr int kAccMode = 4;
 constexpr uint64_t kModeNarrow = 1ull << 8;
+constexpr uint64_t kModeCompact = 1ull << 9;   // sum of sizes in granules below 2^16 as well
 void launch_trace_check(const stalloc_trace& tr, uint64_t* acc, uint32_t* device_status, hipStream_t stream);
 
 }  // namespace stalloc

@@ -18,10 +18,11 @@
 //   survey   After a barrier, wave r gathers what all waves published for request r into its
 //            64 lanes in address order; the true "covered" of a hole is the maximum of its
 //            local value and the chunk maxima of the waves below.  It records the first hole
-//            that is large enough as such (or the top).
-//   resolve  After another barrier, wave 0 settles the K requests in order: if no block
-//            settled earlier in the batch gets in the way of the surveyed address, that is
-//            the answer; otherwise the holes are looked at again with those blocks honoured.  The blocks already settled in this batch (the side buffer,
+//            holes that are large enough as such.
+//   resolve  After another barrier, wave 0 settles the K requests in order: a request takes
+//            the first surveyed hole in which it still fits once the blocks settled earlier
+//            in the batch are cleared, else the top; if the surveyed holes run out while more
+//            were published, all published holes are looked at again with those blocks honoured.  The blocks already settled in this batch (the side buffer,
 //            sorted, one per lane) are honoured through f(c) = lowest address >= c that clears
 //            the side-buffer blocks conflicting with r: r takes the first hole with
 //            f(covered) + size_r <= hole end, else goes on top at f(maximum).  f is evaluated
@@ -72,8 +73,9 @@ struct PlanLds {
     Addr top[kWaves][kPend];                               // chunk maximum per (wave, request)
     uint32_t holes[kWaves][kPend];                         // holes found per (wave, request), may exceed kSlots
     Span<Addr> hole[kWaves][kPend][kSlots];                // {hole end, chunk-local covered}
-    Addr first[kPend];                                     // survey: first raw hole (or top) per request
-    uint32_t first_open[kPend];                            // survey: 0 if an unpublished hole may lie below it
+    Span<Addr> surveyed[kPend][4];                         // survey: first holes large enough as such {end, covered}
+    uint32_t listed[kPend];                                // survey: how many, bit 8 = more to look at behind them
+    Addr top_of[kPend];                                    // survey: maximum over all chunks
     Span<Addr> pend_span[kPend];                           // blocks settled in this batch, sorted
     uint2 pend_life[kPend];
     uint32_t settled;
@@ -91,15 +93,67 @@ struct PlanParams {
     unsigned char* slabs;    // list in the workspace: gridDim.x slabs of 2 * n entries
     uint32_t n;
     uint32_t P;
+    uint32_t compact_enqueued;   // the compact 32-bit instantiation is part of this call
 };
+
+// The sorted list of placed blocks.  Two storage layouts:
+//   wide     (lo, hi) in address units of type Addr plus (t_alloc, t_free) as 32-bit values
+//   compact  lo, hi, t_alloc, t_free as 16-bit fields of one 8-byte cell; usable when the sum of
+//            sizes in granules and the number of timestamps both stay below 2^16
+template <typename Addr, bool kCompact>
+struct BlockList;
 
 template <typename Addr>
-struct BlockList {
+struct BlockList<Addr, false> {
+    typedef Addr addr_type;
+    static constexpr size_t kEntryBytes = sizeof(Span<Addr>) + sizeof(uint2);
+    struct Entry {
+        Span<Addr> sp;
+        uint2 lf;
+        __device__ __forceinline__ Addr lo() const { return sp.lo; }
+        __device__ __forceinline__ Addr hi() const { return sp.hi; }
+        __device__ __forceinline__ uint32_t ta() const { return lf.x; }
+        __device__ __forceinline__ uint32_t tf() const { return lf.y; }
+    };
     Span<Addr>* span;
-    uint2* life;             // (t_alloc, t_free)
+    uint2* life;
+    __device__ __forceinline__ void bind(unsigned char* base, uint32_t cap)
+    {
+        span = reinterpret_cast<Span<Addr>*>(base);
+        life = reinterpret_cast<uint2*>(span + cap);
+    }
+    __device__ __forceinline__ Entry load(uint32_t k) const { return Entry{span[k], life[k]}; }
+    __device__ __forceinline__ void store(uint32_t k, const Entry& e) const { span[k] = e.sp; life[k] = e.lf; }
+    static __device__ __forceinline__ Entry make(Addr lo, Addr hi, uint32_t ta, uint32_t tf)
+    {
+        return Entry{Span<Addr>{lo, hi}, make_uint2(ta, tf)};
+    }
+    static __device__ __forceinline__ Entry none() { return make(0, 0, 0, 0); }
 };
 
-template <typename Addr> constexpr size_t entry_bytes() { return sizeof(Span<Addr>) + sizeof(uint2); }
+template <>
+struct BlockList<uint32_t, true> {
+    typedef uint32_t addr_type;
+    static constexpr size_t kEntryBytes = sizeof(uint2);
+    struct Entry {
+        uint2 c;
+        __device__ __forceinline__ uint32_t lo() const { return c.x & 0xffffu; }
+        __device__ __forceinline__ uint32_t hi() const { return c.x >> 16; }
+        __device__ __forceinline__ uint32_t ta() const { return c.y & 0xffffu; }
+        __device__ __forceinline__ uint32_t tf() const { return c.y >> 16; }
+    };
+    uint2* cell;
+    __device__ __forceinline__ void bind(unsigned char* base, uint32_t) { cell = reinterpret_cast<uint2*>(base); }
+    __device__ __forceinline__ Entry load(uint32_t k) const { return Entry{cell[k]}; }
+    __device__ __forceinline__ void store(uint32_t k, const Entry& e) const { cell[k] = e.c; }
+    static __device__ __forceinline__ Entry make(uint32_t lo, uint32_t hi, uint32_t ta, uint32_t tf)
+    {
+        return Entry{make_uint2(lo | (hi << 16), ta | (tf << 16))};
+    }
+    static __device__ __forceinline__ Entry none() { return Entry{make_uint2(0, 0)}; }
+};
+
+template <typename Addr> constexpr size_t entry_bytes() { return BlockList<Addr, false>::kEntryBytes; }
 
 // The side buffer in registers: block q in lane q, ascending start address.
 template <typename Addr>
@@ -182,8 +236,8 @@ __device__ __forceinline__ void pending_insert(Pending<Addr>& pd, uint32_t pendi
 
 // One pass over the sorted list for the requests b0 .. b0+nb-1 of the staged batch: publishes,
 // per (wave, request), the chunk maximum of conflicting end addresses and the first holes.
-template <typename Addr, int kPend, int kThreads, typename Lds>
-__device__ __forceinline__ void scan_batch(const BlockList<Addr>& list, uint32_t count, uint32_t b0, uint32_t nb,
+template <typename Addr, int kPend, int kThreads, typename List, typename Lds>
+__device__ __forceinline__ void scan_batch(const List& list, uint32_t count, uint32_t b0, uint32_t nb,
                                            uint32_t shift, Lds& sh)
 {
     constexpr int kSlots = Lds::kSlots;
@@ -210,8 +264,9 @@ __device__ __forceinline__ void scan_batch(const BlockList<Addr>& list, uint32_t
     for (uint32_t j = 0; j < sub; ++j, k += kWave) {
         const bool valid = k < count;
         const uint32_t kc = valid ? k : count - 1;
-        const Span<Addr> sp = list.span[kc];
-        const uint2 lf = list.life[kc];
+        const typename List::Entry en = list.load(kc);
+        const Span<Addr> sp = {en.lo(), en.hi()};
+        const uint2 lf = make_uint2(en.ta(), en.tf());
         const uint64_t valid_m = __builtin_amdgcn_ballot_w64(valid);
         // requests in groups of kGroup: their running-maximum chains are independent, so the
         // compiler can interleave the DPP steps of one chain into the wait states of the others
@@ -301,21 +356,43 @@ __device__ __forceinline__ bool unpublished_below(uint64_t crowded, int h)
     return crowded && (h < 0 || __builtin_ctzll(crowded) / Lds::kSlots < h / Lds::kSlots);
 }
 
-// Survey (all waves, request r handled by wave r mod #waves): the first hole that is large
-// enough as such -- or the top -- and whether an unpublished hole could lie below it.
+constexpr int kSurveyed = 4;     // holes the survey lists per request
+
+// Survey (all waves, request r handled by wave r mod #waves): lists, in address order, the
+// first holes that are large enough as such, and says what follows the list: the top of the
+// plan (every usable hole is listed) or a closer look at everything that was published.
 template <typename Addr, int kPend, int kThreads, typename Lds>
 __device__ __forceinline__ void survey_batch(uint32_t b0, uint32_t nb, uint32_t shift, Lds& sh)
 {
     for (uint32_t r = (uint32_t)wave_id(); r < nb; r += Lds::kWaves) {
         const Addr s = (Addr)(sh.rq_size[b0 + r] >> shift);
         const HoleView<Addr> v = view_holes<Addr>(sh, r);
-        const uint64_t raw = v.published & lanes_ge(v.end, (Addr)(v.covered + s));
-        const int h0 = raw ? __builtin_ctzll(raw) : -1;
-        const Addr first = raw ? read_lane(v.covered, h0) : v.top;
-        if (lane_id() == 0) {
-            sh.first[r] = first;
-            sh.first_open[r] = unpublished_below<Lds>(v.crowded, h0) ? 0u : 1u;
+        uint64_t raw = v.published & lanes_ge(v.end, (Addr)(v.covered + s));
+        uint32_t listed = 0;
+        while (raw && listed < (uint32_t)kSurveyed) {
+            const int h = __builtin_ctzll(raw);
+            if (unpublished_below<Lds>(v.crowded, h)) break;          // an unpublished hole may lie lower
+            raw &= raw - 1;
+            sh.surveyed[r][listed] = Span<Addr>{read_lane(v.end, h), read_lane(v.covered, h)};   // uniform store
+            ++listed;
         }
+        if (lane_id() == 0) {
+            sh.listed[r] = listed | ((raw || v.crowded) ? 0x100u : 0u);     // bit 8: more to look at after the list
+            sh.top_of[r] = v.top;
+        }
+    }
+}
+
+// Lowest address >= c at which [c, c + s) clears the pending blocks selected by `rivals`
+// (lanes of the side buffer whose lifetime conflicts with the request).
+template <typename Addr>
+__device__ __forceinline__ Addr clear_rivals(Addr c, Addr s, uint64_t rivals, const Pending<Addr>& pd)
+{
+    if (rivals == 0) return c;
+    for (;;) {
+        const uint64_t hit = rivals & lanes_lt(pd.lo, (Addr)(c + s)) & lanes_lt(c, pd.hi);
+        if (hit == 0) return c;
+        c = read_lane(wave_scan_max(keep_lanes(hit, pd.hi)), kWave - 1);   // every address in [c, that end) is blocked
     }
 }
 
@@ -325,36 +402,46 @@ template <typename Addr, int kPend, int kThreads, typename Lds>
 __device__ __forceinline__ uint32_t resolve_batch(uint32_t b0, uint32_t nb, uint32_t shift, Addr& peak, Lds& sh)
 {
     const int lane = lane_id();
-    // lane r holds request r of the batch and what the survey found for it
-    Addr rq_s = 0, firstv = 0;
-    uint32_t rq_ta = 0, rq_tf = 0, openv = 0;
+    // lane r holds request r of the batch
+    Addr rq_s = 0, topv = 0;
+    uint32_t rq_ta = 0, rq_tf = 0, listedv = 0;
     if (lane < (int)nb) {
         rq_s = (Addr)(sh.rq_size[b0 + lane] >> shift);
         rq_ta = sh.rq_ta[b0 + lane];
         rq_tf = sh.rq_tf[b0 + lane];
-        firstv = sh.first[lane];
-        openv = sh.first_open[lane];
+        listedv = sh.listed[lane];
+        topv = sh.top_of[lane];
     }
     Pending<Addr> pd = {0, 0, 0, 0};
+    // lane i < kSurveyed holds surveyed hole i of the current request; fetched one request ahead
+    Span<Addr> holes_next = sh.surveyed[0][lane < kSurveyed ? lane : 0];
     uint32_t r = 0;
     for (; r < nb; ++r) {
         const Addr s = read_lane(rq_s, (int)r);
         const uint32_t ta = read_lane(rq_ta, (int)r), tf = read_lane(rq_tf, (int)r);
-        const Addr first = read_lane(firstv, (int)r);
-        // does a block settled earlier in this batch get in the way of the surveyed address?
-        const bool clash = lane < (int)r && pd.ta < tf && ta < pd.tf && pd.lo < first + s && pd.hi > first;
-        Addr x;
-        if (!__builtin_amdgcn_ballot_w64(clash)) {
-            if (!read_lane(openv, (int)r)) break;             // an unpublished hole may lie lower
-            x = first;
-        } else {
-            const HoleView<Addr> v = view_holes<Addr>(sh, r);
-            const Zones<Addr> zones = make_zones(pd, r, s, ta, tf);
-            const Addr cleared = clear_zones(v.covered, s, zones);
-            const uint64_t fits = v.published & lanes_ge(v.end, (Addr)(cleared + s));
-            const int h = fits ? __builtin_ctzll(fits) : -1;
-            if (unpublished_below<Lds>(v.crowded, h)) break;
-            x = fits ? read_lane(cleared, h) : read_lane(clear_zones(v.top, s, zones), 0);
+        const uint32_t listed = read_lane(listedv, (int)r);
+        const Span<Addr> holes = holes_next;
+        if (r + 1 < nb) holes_next = sh.surveyed[r + 1][lane < kSurveyed ? lane : 0];
+        // blocks settled earlier in this batch whose lifetime conflicts with the request
+        const uint64_t rivals = __builtin_amdgcn_ballot_w64(lane < (int)r && pd.ta < tf && ta < pd.tf);
+        Addr x = 0;
+        bool placed = false;
+        for (uint32_t i = 0; i < (listed & 0xffu) && !placed; ++i) {
+            const Addr c = clear_rivals(read_lane(holes.hi, (int)i), s, rivals, pd);
+            if (c + s <= read_lane(holes.lo, (int)i)) { x = c; placed = true; }
+        }
+        if (!placed) {
+            if (!(listed & 0x100u)) {
+                x = clear_rivals(read_lane(topv, (int)r), s, rivals, pd);       // on top of everything
+            } else {
+                const HoleView<Addr> v = view_holes<Addr>(sh, r);
+                const Zones<Addr> zones = make_zones(pd, r, s, ta, tf);
+                const Addr cleared = clear_zones(v.covered, s, zones);
+                const uint64_t fits = v.published & lanes_ge(v.end, (Addr)(cleared + s));
+                const int h = fits ? __builtin_ctzll(fits) : -1;
+                if (unpublished_below<Lds>(v.crowded, h)) break;
+                x = fits ? read_lane(cleared, h) : read_lane(clear_zones(v.top, s, zones), 0);
+            }
         }
         peak = umax(peak, (Addr)(x + s));
         if (lane == 0) sh.rq_addr[b0 + r] = (uint64_t)x << shift;
@@ -371,8 +458,8 @@ __device__ __forceinline__ uint32_t resolve_batch(uint32_t b0, uint32_t nb, uint
 // Exact placement of one request against the sorted list alone (no side buffer): lowest
 // address x such that [x, x + s) meets no listed block whose lifetime conflicts with [ta, tf).
 // All threads of the workgroup call this together; the result is uniform.
-template <typename Addr, int kThreads, typename Lds>
-__device__ __forceinline__ Addr lowest_fit(const BlockList<Addr>& list, uint32_t count, Addr s, uint32_t ta,
+template <typename Addr, int kThreads, typename List, typename Lds>
+__device__ __forceinline__ Addr lowest_fit(const List& list, uint32_t count, Addr s, uint32_t ta,
                                            uint32_t tf, Lds& sh)
 {
     constexpr int kWaves = kThreads / kWave;
@@ -393,8 +480,9 @@ __device__ __forceinline__ Addr lowest_fit(const BlockList<Addr>& list, uint32_t
         for (uint32_t j = 0; j < sub; ++j) {
             const uint32_t k = chunk0 + j * kWave + lane;
             const bool valid = k < count;
-            const Span<Addr> sp = list.span[valid ? k : last];
-            const uint2 lf = list.life[valid ? k : last];
+            const typename List::Entry en = list.load(valid ? k : last);
+            const Span<Addr> sp = {en.lo(), en.hi()};
+            const uint2 lf = make_uint2(en.ta(), en.tf());
             const bool conflict = valid && lf.x < tf && ta < lf.y;
             const Addr incl = wave_scan_max(conflict ? sp.hi : (Addr)0);
             run = umax(run, read_lane(incl, kWave - 1));
@@ -409,8 +497,9 @@ __device__ __forceinline__ Addr lowest_fit(const BlockList<Addr>& list, uint32_t
         for (uint32_t j = 0; j < sub && hit == kNoHit; ++j) {
             const uint32_t k = chunk0 + j * kWave + lane;
             const bool valid = k < count;
-            const Span<Addr> sp = list.span[valid ? k : last];
-            const uint2 lf = list.life[valid ? k : last];
+            const typename List::Entry en = list.load(valid ? k : last);
+            const Span<Addr> sp = {en.lo(), en.hi()};
+            const uint2 lf = make_uint2(en.ta(), en.tf());
             const bool conflict = valid && lf.x < tf && ta < lf.y;
             const Addr incl = wave_scan_max(conflict ? sp.hi : (Addr)0);
             const Addr before = umax(run, wave_shift_up(incl, (Addr)0));
@@ -438,80 +527,102 @@ __device__ __forceinline__ uint32_t pending_at_or_below(const Pending<Addr>& pd,
     return c;
 }
 
-// Merges the side buffer (sh.pend_*, sorted, `pending` blocks, already visible to the whole
-// workgroup) into the sorted list.  Listed block k moves to k + c_k, where c_k is the number
-// of pending blocks at or below its start address; pending block q lands at k + q in front of
-// the first listed block k with c_k > q (or behind the last one).
-template <typename Addr, bool kLds, int kThreads, typename Lds>
-__device__ __forceinline__ void merge_pending(BlockList<Addr>& list, BlockList<Addr>& spare, uint32_t count,
+// One merge pass over the list entries [base, base + kThreads * kSub) and, if it falls into that
+// range, the position just past the end: listed block k moves to k + c_k, where c_k is the
+// number of pending blocks at or below its start address; pending block q lands at k + q in
+// front of the first listed block k with c_k > q (or behind the last one).  kSub is a template
+// parameter so that the per-lane copies of the entries stay in registers.
+template <typename Addr, bool kLds, int kThreads, int kSub, typename List, typename Lds>
+__device__ __forceinline__ void merge_pass(const List& list, const List& dst, uint32_t count,
+                                           uint32_t base, const Pending<Addr>& pd, uint32_t pending, Lds& sh)
+{
+    const int lane = lane_id(), wave = wave_id();
+    const Addr p_lowest = read_lane(pd.lo, 0), p_highest = read_lane(pd.lo, (int)pending - 1);
+    const uint32_t chunk0 = base + (uint32_t)wave * kWave * kSub;
+    typename List::Entry en[kSub];
+    uint32_t c_here[kSub], c_prev[kSub];
+    // pending blocks at or below the entry in front of this wave's chunk
+    uint32_t carry = 0;
+    if (chunk0 > 0 && chunk0 - 1 < count) carry = pending_at_or_below(pd, pending, (Addr)list.load(chunk0 - 1).lo());
+    else if (chunk0 > count) carry = pending;
+#pragma unroll
+    for (int j = 0; j < kSub; ++j) {
+        const uint32_t k0 = chunk0 + j * kWave;
+        const uint32_t k = k0 + lane;
+        const bool valid = k < count;
+        en[j] = List::none();
+        if (valid) en[j] = list.load(k);
+        const Addr lo_j = en[j].lo();
+        // most 64-entry steps lie entirely below the lowest or at/above the highest pending block
+        uint32_t c = pending;
+        if (k0 < count) {
+            const int last_lane = count - k0 >= (uint32_t)kWave ? kWave - 1 : (int)(count - k0 - 1);
+            if (p_lowest > read_lane(lo_j, last_lane)) c = valid ? 0u : pending;
+            else if (p_highest > read_lane(lo_j, 0)) c = valid ? pending_at_or_below(pd, pending, lo_j) : pending;
+        }
+        c_here[j] = c;
+        c_prev[j] = wave_shift_up(c, carry);
+        carry = read_lane(c, kWave - 1);
+    }
+    if constexpr (kLds) __syncthreads();     // in place: every block is in registers before any moves
+#pragma unroll
+    for (int j = 0; j < kSub; ++j) {
+        const uint32_t k = chunk0 + j * kWave + lane;
+        if (k < count && (!kLds || c_here[j] > 0)) {
+            dst.store(k + c_here[j], en[j]);
+        }
+        if (k <= count) {
+            for (uint32_t q = c_prev[j]; q < c_here[j]; ++q) {
+                const Span<Addr> ps = sh.pend_span[q];
+                const uint2 pl = sh.pend_life[q];
+                dst.store(k + q, List::make(ps.lo, ps.hi, pl.x, pl.y));
+            }
+        }
+    }
+}
+
+template <typename Addr, bool kLds, int kThreads, int kSub, typename List, typename Lds>
+struct MergeDispatch {
+    static __device__ __forceinline__ void run(uint32_t sub, const List& list, const List& dst,
+                                               uint32_t count, uint32_t base, const Pending<Addr>& pd,
+                                               uint32_t pending, Lds& sh)
+    {
+        if (sub == (uint32_t)kSub) merge_pass<Addr, kLds, kThreads, kSub>(list, dst, count, base, pd, pending, sh);
+        else MergeDispatch<Addr, kLds, kThreads, kSub - 1, List, Lds>::run(sub, list, dst, count, base, pd, pending, sh);
+    }
+};
+template <typename Addr, bool kLds, int kThreads, typename List, typename Lds>
+struct MergeDispatch<Addr, kLds, kThreads, 0, List, Lds> {
+    static __device__ __forceinline__ void run(uint32_t, const List&, const List&, uint32_t,
+                                               uint32_t, const Pending<Addr>&, uint32_t, Lds&) {}
+};
+
+// Merges the side buffer (sh.pend_*, sorted, `pending` >= 1 blocks, already visible to the whole
+// workgroup) into the sorted list: in place through registers when the list is in LDS (one
+// pass covers it), into the spare slab otherwise.
+template <typename Addr, bool kLds, int kThreads, typename List, typename Lds>
+__device__ __forceinline__ void merge_pending(List& list, List& spare, uint32_t count,
                                               uint32_t pending, Lds& sh)
 {
     constexpr int kMaxSub = kPassEntries / kThreads;
-    const int lane = lane_id(), wave = wave_id();
     const Pending<Addr> pd = load_pending<Addr>(sh, pending);
-    const Addr p_lowest = read_lane(pd.lo, 0), p_highest = read_lane(pd.lo, (int)pending - 1);
-    BlockList<Addr>& dst = kLds ? list : spare;
+    const List& dst = kLds ? list : spare;
     for (uint32_t base = 0; base <= count;) {    // "<=": the position just past the end takes the tail
         const uint32_t left = count + 1 - base;
         uint32_t sub = (left + kThreads - 1) / kThreads;
         if (sub > (uint32_t)kMaxSub) sub = kMaxSub;
-        const uint32_t chunk0 = base + (uint32_t)wave * kWave * sub;
-
-        Span<Addr> sp[kMaxSub];
-        uint2 lf[kMaxSub];
-        uint32_t c_here[kMaxSub], c_prev[kMaxSub];
-        // pending blocks at or below the entry in front of this wave's chunk
-        uint32_t carry = 0;
-        if (chunk0 > 0 && chunk0 - 1 < count) carry = pending_at_or_below(pd, pending, list.span[chunk0 - 1].lo);
-        else if (chunk0 > count) carry = pending;
-#pragma unroll
-        for (int j = 0; j < kMaxSub; ++j) {
-            sp[j] = Span<Addr>{0, 0};
-            lf[j] = make_uint2(0, 0);
-            c_here[j] = 0;
-            c_prev[j] = 0;
-            if ((uint32_t)j < sub) {
-                const uint32_t k = chunk0 + j * kWave + lane;
-                const bool valid = k < count;
-                if (valid) { sp[j] = list.span[k]; lf[j] = list.life[k]; }
-                // most 64-entry steps lie entirely below the lowest or at/above the highest pending block
-                const uint32_t k0 = chunk0 + j * kWave;
-                uint32_t c = pending;
-                if (k0 < count) {
-                    const int last_lane = count - k0 >= (uint32_t)kWave ? kWave - 1 : (int)(count - k0 - 1);
-                    if (p_lowest > read_lane(sp[j].lo, last_lane)) c = valid ? 0u : pending;
-                    else if (p_highest > read_lane(sp[j].lo, 0)) c = valid ? pending_at_or_below(pd, pending, sp[j].lo) : pending;
-                }
-                c_here[j] = c;
-                c_prev[j] = wave_shift_up(c, carry);
-                carry = read_lane(c, kWave - 1);
-            }
-        }
-        if constexpr (kLds) __syncthreads();     // in place: every block is in registers before any moves
-#pragma unroll
-        for (int j = 0; j < kMaxSub; ++j) {
-            const uint32_t k = chunk0 + j * kWave + lane;
-            if ((uint32_t)j < sub && k < count && (!kLds || c_here[j] > 0)) {
-                dst.span[k + c_here[j]] = sp[j];
-                dst.life[k + c_here[j]] = lf[j];
-            }
-            if ((uint32_t)j < sub && k <= count) {
-                for (uint32_t q = c_prev[j]; q < c_here[j]; ++q) {
-                    dst.span[k + q] = sh.pend_span[q];
-                    dst.life[k + q] = sh.pend_life[q];
-                }
-            }
-        }
+        MergeDispatch<Addr, kLds, kThreads, kMaxSub, List, Lds>::run(sub, list, dst, count, base, pd, pending, sh);
         base += kThreads * sub;
     }
-    if constexpr (!kLds) { BlockList<Addr> t = list; list = spare; spare = t; }
+    if constexpr (!kLds) { List t = list; list = spare; spare = t; }
     __syncthreads();
 }
 
-template <typename Addr, bool kLds, int kPend, int kThreads>
-__global__ void __launch_bounds__(kThreads) plan_kernel(PlanParams prm)
+template <typename Addr, bool kLds, bool kCompact, int kPend, int kThreads>
+__global__ void __launch_bounds__(kThreads, 4) plan_kernel(PlanParams prm)   // <= 128 VGPRs: 16 waves per CU
 {
     using Lds = PlanLds<Addr, kPend, kThreads>;
+    using List = BlockList<Addr, kCompact>;
     extern __shared__ __align__(16) unsigned char smem[];
     Lds& sh = *reinterpret_cast<Lds*>(smem);
     const uint32_t n = prm.n;
@@ -519,22 +630,20 @@ __global__ void __launch_bounds__(kThreads) plan_kernel(PlanParams prm)
     if (*prm.status != STALLOC_OK) return;               // malformed trace: nothing to plan
     const uint64_t mode = prm.acc[kAccMode];
     const bool narrow = (mode & kModeNarrow) != 0;
-    if (narrow != (sizeof(Addr) == 4)) return;            // the other instantiation handles this trace
+    if (narrow != (sizeof(Addr) == 4)) return;            // another instantiation handles this trace
+    // of the two 32-bit instantiations the compact one runs when it was enqueued and applies
+    const bool compact = prm.compact_enqueued && (mode & kModeCompact) != 0;
+    if (sizeof(Addr) == 4 && compact != kCompact) return;
     const uint32_t shift = sizeof(Addr) == 4 ? (uint32_t)(mode & 63) : 0;
 
-    BlockList<Addr> list, spare;
+    List list, spare;
     if constexpr (kLds) {
-        unsigned char* dyn = smem + sizeof(Lds);
-        list.span = reinterpret_cast<Span<Addr>*>(dyn);
-        list.life = reinterpret_cast<uint2*>(list.span + n);
+        list.bind(smem + sizeof(Lds), n);
         spare = list;
     } else {
         unsigned char* slab = prm.slabs + (size_t)blockIdx.x * 2 * (size_t)n * entry_bytes<uint64_t>();
-        list.span = reinterpret_cast<Span<Addr>*>(slab);
-        list.life = reinterpret_cast<uint2*>(list.span + n);
-        unsigned char* slab2 = slab + (size_t)n * entry_bytes<uint64_t>();
-        spare.span = reinterpret_cast<Span<Addr>*>(slab2);
-        spare.life = reinterpret_cast<uint2*>(spare.span + n);
+        list.bind(slab, n);
+        spare.bind(slab + (size_t)n * entry_bytes<uint64_t>(), n);
     }
 
     for (uint32_t p = blockIdx.x; p < prm.P; p += gridDim.x) {
@@ -645,21 +754,28 @@ constexpr int kPendMem = STALLOC_PEND_MEM;        // ... and when it is in the w
 constexpr int kThreadsLds = STALLOC_THREADS_LDS;
 constexpr int kThreadsMem = STALLOC_THREADS_MEM;
 
-template <typename Addr>
-inline uint32_t lds_capacity_entries(const DeviceInfo& di)
+#ifndef STALLOC_THREADS_COMPACT
+#define STALLOC_THREADS_COMPACT 512
+#endif
+constexpr int kThreadsCompact = STALLOC_THREADS_COMPACT;   // two such workgroups share one CU
+
+// Entries the LDS-resident list may hold, for a given entry size and LDS budget.
+template <typename Addr, int kThreads>
+inline uint32_t lds_capacity_entries(size_t lds_budget, size_t bytes_per_entry)
 {
-    const size_t fixed = sizeof(PlanLds<Addr, kPendLds, kThreadsLds>);
-    if (di.lds_per_block <= fixed) return 0;
-    size_t cap = (di.lds_per_block - fixed) / entry_bytes<Addr>();
+    const size_t fixed = sizeof(PlanLds<Addr, kPendLds, kThreads>);
+    if (lds_budget <= fixed) return 0;
+    size_t cap = (lds_budget - fixed) / bytes_per_entry;
     const size_t pass = (size_t)kPassEntries - 1;               // in-place merge keeps the whole list in registers
     return (uint32_t)(cap < pass ? cap : pass);
 }
 
-template <typename Addr, bool kLds, int kPend, int kThreads>
+template <typename Addr, bool kLds, bool kCompact, int kPend, int kThreads>
 inline bool launch_plan(const PlanParams& prm, uint32_t grid, const DeviceInfo& di, hipStream_t stream)
 {
-    auto kernel = &plan_kernel<Addr, kLds, kPend, kThreads>;
-    size_t lds = sizeof(PlanLds<Addr, kPend, kThreads>) + (kLds ? (size_t)prm.n * entry_bytes<Addr>() : 0);
+    auto kernel = &plan_kernel<Addr, kLds, kCompact, kPend, kThreads>;
+    size_t lds = sizeof(PlanLds<Addr, kPend, kThreads>) +
+                 (kLds ? (size_t)prm.n * BlockList<Addr, kCompact>::kEntryBytes : 0);
     static bool attr_set[64] = {};
     if (kLds && !attr_set[di.device]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -679,7 +795,7 @@ extern "C" uint32_t stalloc_plan_lds_capacity(void)
 {
     DeviceInfo di;
     if (!device_info(&di)) return 0;
-    return lds_capacity_entries<uint32_t>(di);
+    return lds_capacity_entries<uint32_t, kThreadsLds>(di.lds_per_block, entry_bytes<uint32_t>());
 }
 
 extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uint32_t P, uint64_t* offsets,
@@ -690,11 +806,15 @@ extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uin
     DeviceInfo di;
     if (!device_info(&di)) return STALLOC_ERR_DEVICE;
     const uint32_t n = tr->n;
-    const bool lds32 = n <= lds_capacity_entries<uint32_t>(di);
-    const bool lds64 = n <= lds_capacity_entries<uint64_t>(di);
-    uint32_t grid_lds = (uint32_t)di.cus, grid_mem = (uint32_t)di.cus * 2;
+    const bool lds32 = n <= lds_capacity_entries<uint32_t, kThreadsLds>(di.lds_per_block, entry_bytes<uint32_t>());
+    const bool lds64 = n <= lds_capacity_entries<uint64_t, kThreadsLds>(di.lds_per_block, entry_bytes<uint64_t>());
+    // compact list: 8-byte entries, two workgroups per CU (half the LDS each)
+    const bool compact = tr->t_end < 0x10000u &&
+                         n <= lds_capacity_entries<uint32_t, kThreadsCompact>(di.lds_per_block / 2, sizeof(uint2));
+    uint32_t grid_lds = (uint32_t)di.cus, grid_mem = (uint32_t)di.cus * 2, grid_compact = (uint32_t)di.cus * 2;
     if (grid_lds > P) grid_lds = P;
     if (grid_mem > P) grid_mem = P;
+    if (grid_compact > P) grid_compact = P;
 
     Carver cv(workspace);
     uint64_t* acc = cv.take<uint64_t>(kAccWords);
@@ -712,12 +832,14 @@ extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uin
     prm.size = tr->size; prm.ta = tr->t_alloc; prm.tf = tr->t_free; prm.orders = orders;
     prm.offsets = offsets ? offsets : own_offsets;
     prm.peaks = peaks; prm.status = device_status; prm.acc = acc; prm.slabs = slabs; prm.n = n; prm.P = P;
+    prm.compact_enqueued = compact ? 1u : 0u;
     bool ok = true;
-    // exactly one of the two launches does the work; the trace decides which (see the mode word)
-    if (lds32) ok = ok && launch_plan<uint32_t, true, kPendLds, kThreadsLds>(prm, grid_lds, di, stream);
-    else       ok = ok && launch_plan<uint32_t, false, kPendMem, kThreadsMem>(prm, grid_mem, di, stream);
-    if (lds64) ok = ok && launch_plan<uint64_t, true, kPendLds, kThreadsLds>(prm, grid_lds, di, stream);
-    else       ok = ok && launch_plan<uint64_t, false, kPendMem, kThreadsMem>(prm, grid_mem, di, stream);
+    // exactly one of the launches does the work; the trace decides which (see the mode word)
+    if (compact) ok = ok && launch_plan<uint32_t, true, true, kPendLds, kThreadsCompact>(prm, grid_compact, di, stream);
+    if (lds32) ok = ok && launch_plan<uint32_t, true, false, kPendLds, kThreadsLds>(prm, grid_lds, di, stream);
+    else       ok = ok && launch_plan<uint32_t, false, false, kPendMem, kThreadsMem>(prm, grid_mem, di, stream);
+    if (lds64) ok = ok && launch_plan<uint64_t, true, false, kPendLds, kThreadsLds>(prm, grid_lds, di, stream);
+    else       ok = ok && launch_plan<uint64_t, false, false, kPendMem, kThreadsMem>(prm, grid_mem, di, stream);
     if (!ok) return STALLOC_ERR_DEVICE;
 
     hipLaunchKernelGGL(plan_argmin, dim3(1), dim3(256), 0, stream, peaks, P, best_plan, device_status);

@@ -51,7 +51,8 @@ __global__ void trace_check_finish(uint64_t* acc, uint32_t* status)
         const uint64_t total = (acc[0] << 32) + acc[1];              // below 2^63 here
         const uint32_t shift = (uint32_t)__builtin_ctzll(acc[3]);
         const uint64_t narrow = (total >> shift) < (1ull << 31) ? kModeNarrow : 0;
-        acc[kAccMode] = shift | narrow;
+        const uint64_t compact = (total >> shift) < (1ull << 16) ? kModeCompact : 0;
+        acc[kAccMode] = shift | narrow | compact;
     }
     // total = acc[0] * 2^32 + acc[1]  >= 2^63  <=>  acc[0] + (acc[1] >> 32) >= 2^31
     if (acc[0] + (acc[1] >> 32) >= (1ull << 31)) code = STALLOC_ERR_OVERFLOW;

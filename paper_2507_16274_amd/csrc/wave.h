@@ -160,6 +160,7 @@ __device__ __forceinline__ uint64_t lane_gather(uint64_t v, int src)
 
 // Lane masks straight from a vector compare (one v_cmp, no per-lane boolean in between).
 __device__ __forceinline__ uint64_t lanes_lt(uint32_t a, uint32_t b) { return __builtin_amdgcn_uicmp(a, b, 36); }
+__device__ __forceinline__ uint64_t lanes_lt(uint64_t a, uint64_t b) { return __builtin_amdgcn_uicmpl(a, b, 36); }
 __device__ __forceinline__ uint64_t lanes_ge(uint32_t a, uint32_t b) { return __builtin_amdgcn_uicmp(a, b, 35); }
 __device__ __forceinline__ uint64_t lanes_ge(uint64_t a, uint64_t b) { return __builtin_amdgcn_uicmpl(a, b, 35); }
 

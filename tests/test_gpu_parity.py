@@ -189,16 +189,19 @@ def test_plan_config2_all_orderings(S, oracle):
     assert np.array_equal(lean["peaks"], ext) and np.array_equal(lean["best_offsets"], got["best_offsets"])
 
 
-@pytest.mark.parametrize("wide", [False, True])
+@pytest.mark.parametrize("wide", [False, "medium", True])
 @pytest.mark.parametrize("seed", range(12))
 def test_plan_random_traces(S, oracle, seed, wide):
-    """Ties in timestamps, single requests, list lengths around wave / workgroup / side-buffer sizes.
-    wide: odd byte sizes with a sum far above 2^31, which forces 64-bit addresses in the kernel."""
+    """Ties in timestamps, single requests, list lengths around wave / workgroup / batch sizes.
+    False: few granules (16-bit list cells); "medium": more than 2^16 granules (32-bit cells);
+    True: odd byte sizes with a sum far above 2^31, which forces 64-bit addresses in the kernel."""
     rng = np.random.default_rng(900 + seed)
     n = [1, 2, 63, 64, 65, 127, 129, 1023, 1025, 2049, 700, 3000][seed]
     size, ts, te, t_end = random_trace(rng, n, t_max=max(4, n // 3), unique_times=(seed % 2 == 1))
     size = size * np.uint64(512)
-    if wide:
+    if wide == "medium":
+        size = size * np.uint64(70001)
+    elif wide:
         size = size * np.uint64(2 ** 31 + 12345) + np.uint64(1)
     tr = _T(size, ts, te, t_end)
     P = 9
