@@ -9,9 +9,11 @@ orders, all inputs already resident in device memory:
 The headline value is placed requests x plans per second, n * P * steps / time.
 
 Prints ONE JSON line.  `roofline` describes the dominant kernel (the placement
-kernel): algorithmic bytes = 28 B per placement (order entry, request record,
-address written) plus one stored list entry per lifetime-overlapping pair and plan,
-divided by the kernel time measured with events on the launch stream.
+kernel).  Algorithmic work per launch: 28 B of HBM per placement (order entry,
+request record, address written); one stored list entry and 8 integer lane
+operations per lifetime-overlapping pair and plan.  The floor that takes longest
+at the chip's peak names the bound; achieved = that work / kernel time measured
+with events on the launch stream.
 `cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload on
 this machine's host cores.
 """
@@ -29,10 +31,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-ENTRY_BYTES = 24            # bytes of one placed-block list entry as stored by the kernel
 PER_PLACEMENT_BYTES = 28    # 4 B order entry + 16 B request record + 8 B address written
+OPS_PER_CANDIDATE = 8       # 2 lifetime compares, and, select, running max, add, compare, and
 LDS_PEAK_GBS = 256 * 128 * 2.4          # 256 CUs x 128 B/clk x 2.4 GHz = 78 643 GB/s
 HBM_PEAK_GBS = 8000.0
+ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12  # 256 CUs x 64 integer lanes x 2.4 GHz = 39.3 T lane-ops/s
 
 
 def main() -> int:
@@ -122,10 +125,22 @@ def main() -> int:
     ms_per_step = elapsed / args.steps * 1e3
     value = n * P * args.steps / elapsed
     plan_ms = float(np.mean([a.elapsed_time(b) for a, b in ev_pairs]))
-    algo_bytes = PER_PLACEMENT_BYTES * n * P + ENTRY_BYTES * stats["E"] * P
-    in_lds = n <= int(S.lib.stalloc_plan_lds_capacity())
-    achieved = algo_bytes / (plan_ms * 1e-3) / 1e9
-    peak = LDS_PEAK_GBS if in_lds else HBM_PEAK_GBS
+    # how the kernel stores a plan's list for this trace (same rule as on the device)
+    or_sizes = int(np.bitwise_or.reduce(tr.size))
+    shift = (or_sizes & -or_sizes).bit_length() - 1
+    granules = stats["sum_size"] >> shift
+    layout = int(S.lib.stalloc_plan_list_layout(n, tr.t_end, granules))
+    entry_bytes, in_lds = layout & 0xff, bool(layout & 0x100)
+    pairs = stats["E"] * P                       # lifetime-overlapping (earlier, later) pairs examined at least once
+    t_s = plan_ms * 1e-3
+    hbm_bytes = PER_PLACEMENT_BYTES * n * P
+    state_bytes = entry_bytes * pairs
+    algo_ops = OPS_PER_CANDIDATE * pairs
+    # the three floors: mandatory HBM stream, list-entry traffic, integer ALU work; the largest one binds
+    floors = {"hbm": hbm_bytes / (HBM_PEAK_GBS * 1e9),
+              "lds" if in_lds else "hbm_list": state_bytes / ((LDS_PEAK_GBS if in_lds else HBM_PEAK_GBS) * 1e9),
+              "alu": algo_ops / (ALU_PEAK_TOPS * 1e12)}
+    bound = max(floors, key=floors.get)
     result = {
         "metric": "placed requests x plans / s",
         "value": value,
@@ -145,11 +160,22 @@ def main() -> int:
         "quality": {"lower_bound": lower_bound, "best_peak": best_peak, "best_plan": best,
                     "lower_bound_over_peak": lower_bound / best_peak,
                     "median_lower_bound_over_peak": float(lower_bound / np.median(peaks.astype(np.float64)))},
-        "roofline": {"bound": "lds" if in_lds else "hbm", "kernel": "plan_kernel",
-                     "achieved": achieved, "peak": peak, "unit": "GB/s", "frac": achieved / peak,
-                     "traffic": None, "kernel_ms": plan_ms, "algorithmic_bytes": algo_bytes,
-                     "hbm_floor_GBs": PER_PLACEMENT_BYTES * n * P / (plan_ms * 1e-3) / 1e9},
+        "roofline": ({"bound": "alu", "kernel": "plan_kernel", "achieved": algo_ops / t_s / 1e12,
+                      "peak": ALU_PEAK_TOPS, "unit": "TOP/s", "frac": algo_ops / t_s / 1e12 / ALU_PEAK_TOPS}
+                     if bound == "alu" else
+                     {"bound": "hbm", "kernel": "plan_kernel", "achieved": (hbm_bytes + state_bytes) / t_s / 1e9,
+                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": (hbm_bytes + state_bytes) / t_s / 1e9 / HBM_PEAK_GBS}
+                     if not in_lds else
+                     {"bound": "lds", "kernel": "plan_kernel", "achieved": state_bytes / t_s / 1e9,
+                      "peak": LDS_PEAK_GBS, "unit": "GB/s", "frac": state_bytes / t_s / 1e9 / LDS_PEAK_GBS}),
     }
+
+    result["roofline"].update({
+        "traffic": None, "kernel_ms": plan_ms, "list_entry_bytes": entry_bytes, "list_in_lds": in_lds,
+        "algorithmic_ops": algo_ops, "algorithmic_list_bytes": state_bytes, "algorithmic_hbm_bytes": hbm_bytes,
+        "floor_ms": {k: v * 1e3 for k, v in floors.items()},
+        "hbm_stream_GBs": hbm_bytes / t_s / 1e9,
+        "list_GBs": state_bytes / t_s / 1e9})
 
     if not args.no_cpu_baseline:
         import oracle

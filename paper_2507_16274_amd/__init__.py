@@ -22,7 +22,7 @@ _LIB_PATH = os.path.join(_HERE, "libstalloc.so")
 STATUS = {0: "STALLOC_OK", 1: "STALLOC_ERR_INVALID_ARG", 2: "STALLOC_ERR_BAD_TRACE", 3: "STALLOC_ERR_OVERFLOW",
           4: "STALLOC_ERR_NOMEM", 5: "STALLOC_ERR_DEVICE", 6: "STALLOC_ERR_BAD_ORDER"}
 EXPORTS = ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_status_string",
-           "stalloc_plan_lds_capacity")
+           "stalloc_plan_lds_capacity", "stalloc_plan_list_layout")
 
 
 class StallocError(RuntimeError):
@@ -51,8 +51,9 @@ def _load() -> ctypes.CDLL:
         getattr(lib, name).restype = ctypes.c_int
     lib.stalloc_status_string.argtypes = [ctypes.c_int]
     lib.stalloc_status_string.restype = ctypes.c_char_p
-    lib.stalloc_plan_lds_capacity.argtypes = []
-    lib.stalloc_plan_lds_capacity.restype = ctypes.c_uint32
+    for name in ("stalloc_plan_lds_capacity", "stalloc_plan_list_layout"):
+        getattr(lib, name).argtypes = []
+        getattr(lib, name).restype = ctypes.c_uint32
     return lib
 
 

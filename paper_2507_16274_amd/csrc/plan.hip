@@ -47,7 +47,7 @@
 namespace stalloc {
 
 constexpr int kBatch = 256;          // requests fetched per refill
-constexpr int kPassEntries = 10240;  // list entries one in-place merge pass / one fallback pass covers
+constexpr int kPassEntries = 10240;  // list entries the single-request path covers between two barrier pairs
 
 template <typename Addr> struct Span { Addr lo, hi; };     // [lo, hi) in address units
 
@@ -581,39 +581,26 @@ __device__ __forceinline__ void merge_pass(const List& list, const List& dst, ui
     }
 }
 
-template <typename Addr, bool kLds, int kThreads, int kSub, typename List, typename Lds>
-struct MergeDispatch {
-    static __device__ __forceinline__ void run(uint32_t sub, const List& list, const List& dst,
-                                               uint32_t count, uint32_t base, const Pending<Addr>& pd,
-                                               uint32_t pending, Lds& sh)
-    {
-        if (sub == (uint32_t)kSub) merge_pass<Addr, kLds, kThreads, kSub>(list, dst, count, base, pd, pending, sh);
-        else MergeDispatch<Addr, kLds, kThreads, kSub - 1, List, Lds>::run(sub, list, dst, count, base, pd, pending, sh);
-    }
-};
-template <typename Addr, bool kLds, int kThreads, typename List, typename Lds>
-struct MergeDispatch<Addr, kLds, kThreads, 0, List, Lds> {
-    static __device__ __forceinline__ void run(uint32_t, const List&, const List&, uint32_t,
-                                               uint32_t, const Pending<Addr>&, uint32_t, Lds&) {}
-};
+#ifndef STALLOC_MERGE_SUB
+#define STALLOC_MERGE_SUB 4
+#endif
+constexpr int kMergeSub = STALLOC_MERGE_SUB;     // 64-entry steps one wave handles per merge segment
 
 // Merges the side buffer (sh.pend_*, sorted, `pending` >= 1 blocks, already visible to the whole
-// workgroup) into the sorted list: in place through registers when the list is in LDS (one
-// pass covers it), into the spare slab otherwise.
+// workgroup) into the sorted list.  The list is cut into segments of kThreads * kMergeSub
+// entries which are handled from the top down: blocks only move up, so a segment's writes
+// never touch entries of the segments below it, which are read later.  When the list is in LDS
+// the merge is in place (a barrier separates a segment's reads from its writes); otherwise
+// it goes into the spare slab.
 template <typename Addr, bool kLds, int kThreads, typename List, typename Lds>
-__device__ __forceinline__ void merge_pending(List& list, List& spare, uint32_t count,
-                                              uint32_t pending, Lds& sh)
+__device__ __forceinline__ void merge_pending(List& list, List& spare, uint32_t count, uint32_t pending, Lds& sh)
 {
-    constexpr int kMaxSub = kPassEntries / kThreads;
+    constexpr uint32_t kSegment = (uint32_t)kThreads * kMergeSub;
     const Pending<Addr> pd = load_pending<Addr>(sh, pending);
     const List& dst = kLds ? list : spare;
-    for (uint32_t base = 0; base <= count;) {    // "<=": the position just past the end takes the tail
-        const uint32_t left = count + 1 - base;
-        uint32_t sub = (left + kThreads - 1) / kThreads;
-        if (sub > (uint32_t)kMaxSub) sub = kMaxSub;
-        MergeDispatch<Addr, kLds, kThreads, kMaxSub, List, Lds>::run(sub, list, dst, count, base, pd, pending, sh);
-        base += kThreads * sub;
-    }
+    const uint32_t segments = count / kSegment + 1;          // the position just past the end counts too
+    for (uint32_t g = segments; g-- > 0;)
+        merge_pass<Addr, kLds, kThreads, kMergeSub>(list, dst, count, g * kSegment, pd, pending, sh);
     if constexpr (!kLds) { List t = list; list = spare; spare = t; }
     __syncthreads();
 }
@@ -765,9 +752,7 @@ inline uint32_t lds_capacity_entries(size_t lds_budget, size_t bytes_per_entry)
 {
     const size_t fixed = sizeof(PlanLds<Addr, kPendLds, kThreads>);
     if (lds_budget <= fixed) return 0;
-    size_t cap = (lds_budget - fixed) / bytes_per_entry;
-    const size_t pass = (size_t)kPassEntries - 1;               // in-place merge keeps the whole list in registers
-    return (uint32_t)(cap < pass ? cap : pass);
+    return (uint32_t)((lds_budget - fixed) / bytes_per_entry);
 }
 
 template <typename Addr, bool kLds, bool kCompact, int kPend, int kThreads>
@@ -796,6 +781,21 @@ extern "C" uint32_t stalloc_plan_lds_capacity(void)
     DeviceInfo di;
     if (!device_info(&di)) return 0;
     return lds_capacity_entries<uint32_t, kThreadsLds>(di.lds_per_block, entry_bytes<uint32_t>());
+}
+
+extern "C" uint32_t stalloc_plan_list_layout(uint32_t n, uint32_t t_end, uint64_t granules)
+{
+    DeviceInfo di;
+    if (!device_info(&di)) return 0;
+    if (granules < (1ull << 16) && t_end < 0x10000u &&
+        n <= lds_capacity_entries<uint32_t, kThreadsCompact>(di.lds_per_block / 2, sizeof(uint2)))
+        return (uint32_t)sizeof(uint2) | 0x100u;
+    if (granules < (1ull << 31)) {
+        const bool lds = n <= lds_capacity_entries<uint32_t, kThreadsLds>(di.lds_per_block, entry_bytes<uint32_t>());
+        return (uint32_t)entry_bytes<uint32_t>() | (lds ? 0x100u : 0u);
+    }
+    const bool lds = n <= lds_capacity_entries<uint64_t, kThreadsLds>(di.lds_per_block, entry_bytes<uint64_t>());
+    return (uint32_t)entry_bytes<uint64_t>() | (lds ? 0x100u : 0u);
 }
 
 extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uint32_t P, uint64_t* offsets,
