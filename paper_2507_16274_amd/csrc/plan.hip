@@ -266,8 +266,8 @@ __device__ __forceinline__ void scan_batch(const List& list, uint32_t count, uin
         const uint32_t kc = valid ? k : count - 1;
         const typename List::Entry en = list.load(kc);
         const Span<Addr> sp = {en.lo(), en.hi()};
-        const uint2 lf = make_uint2(en.ta(), en.tf());
-        const uint64_t valid_m = __builtin_amdgcn_ballot_w64(valid);
+        // lanes past the end of the list get a lifetime that conflicts with nothing
+        const uint2 lf = make_uint2(valid ? en.ta() : 0xffffffffu, valid ? en.tf() : 0u);
         // requests in groups of kGroup: their running-maximum chains are independent, so the
         // compiler can interleave the DPP steps of one chain into the wait states of the others
         constexpr int kGroup = 4;
@@ -276,12 +276,15 @@ __device__ __forceinline__ void scan_batch(const List& list, uint32_t count, uin
             Addr incl[kGroup], covered[kGroup];
             uint64_t conflict_m[kGroup], closers[kGroup];
             uint64_t any_closer = 0;
+            Addr ends[kGroup];
 #pragma unroll
             for (int q = 0; q < kGroup; ++q) {
                 const int r = g + q;
-                conflict_m[q] = valid_m & lanes_lt(lf.x, tf_of[r]) & lanes_lt(ta_of[r], lf.y);
-                incl[q] = wave_scan_max(keep_lanes(conflict_m[q], sp.hi));
+                conflict_m[q] = lanes_lt(lf.x, tf_of[r]) & lanes_lt(ta_of[r], lf.y);   // lanes past the end: see above
             }
+            keep_lanes4(conflict_m, sp.hi, ends);
+#pragma unroll
+            for (int q = 0; q < kGroup; ++q) incl[q] = wave_scan_max(ends[q]);
 #pragma unroll
             for (int q = 0; q < kGroup; ++q) {
                 const int r = g + q;

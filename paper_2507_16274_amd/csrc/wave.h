@@ -173,6 +173,22 @@ __device__ __forceinline__ uint32_t keep_lanes(uint64_t mask, uint32_t v)
     asm("v_cndmask_b32_e64 %0, 0, %1, %2\n\ts_nop 1" : "=v"(r) : "v"(v), "s"(mask));
     return r;
 }
+// Four selections at once; one pair of wait states covers all of them.
+__device__ __forceinline__ void keep_lanes4(const uint64_t (&mask)[4], uint32_t v, uint32_t (&out)[4])
+{
+    asm("v_cndmask_b32_e64 %0, 0, %4, %5\n\t"
+        "v_cndmask_b32_e64 %1, 0, %4, %6\n\t"
+        "v_cndmask_b32_e64 %2, 0, %4, %7\n\t"
+        "v_cndmask_b32_e64 %3, 0, %4, %8\n\t"
+        "s_nop 1"
+        : "=&v"(out[0]), "=&v"(out[1]), "=&v"(out[2]), "=&v"(out[3])
+        : "v"(v), "s"(mask[0]), "s"(mask[1]), "s"(mask[2]), "s"(mask[3]));
+}
+__device__ __forceinline__ void keep_lanes4(const uint64_t (&mask)[4], uint64_t v, uint64_t (&out)[4])
+{
+    for (int q = 0; q < 4; ++q) out[q] = ((uint64_t)keep_lanes(mask[q], (uint32_t)(v >> 32)) << 32) | keep_lanes(mask[q], (uint32_t)v);
+}
+
 __device__ __forceinline__ uint64_t keep_lanes(uint64_t mask, uint64_t v)
 {
     return ((uint64_t)keep_lanes(mask, (uint32_t)(v >> 32)) << 32) | keep_lanes(mask, (uint32_t)v);
