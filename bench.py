@@ -129,7 +129,7 @@ def main() -> int:
     or_sizes = int(np.bitwise_or.reduce(tr.size))
     shift = (or_sizes & -or_sizes).bit_length() - 1
     granules = stats["sum_size"] >> shift
-    layout = int(S.lib.stalloc_plan_list_layout(n, tr.t_end, granules))
+    layout = int(S.lib.stalloc_plan_list_layout(n, tr.t_end, granules, int(tr.size.max()) >> shift))
     entry_bytes, in_lds = layout & 0xff, bool(layout & 0x100)
     pairs = stats["E"] * P                       # lifetime-overlapping (earlier, later) pairs examined at least once
     t_s = plan_ms * 1e-3

@@ -113,15 +113,18 @@ int stalloc_lower_bound(const stalloc_trace *trace, uint64_t *lower_bound, uint3
 const char *stalloc_status_string(int status);
 
 /*
- * Informational: how stalloc_plan lays out each plan's list of placed blocks on the
- * current device.  `granules` = (sum of sizes) / g with g the largest power of two
- * dividing every size (all addresses are multiples of g).  Returns the bytes of one list
- * entry in the low 8 bits (8: 16-bit fields, needs granules < 2^16 and t_end < 2^16;
- * 16: 32-bit granule counts, needs granules < 2^31; 24: 64-bit byte addresses) and
- * bit 8 set when the list is kept in LDS rather than in the workspace.  0 if no device.
+ * Informational: how stalloc_plan keeps each plan's placed blocks on the current
+ * device.  `granules` = (sum of sizes) / g and `largest` = (largest size) / g, with g the
+ * largest power of two dividing every size (all addresses are multiples of g).  Returns
+ * the bytes of one stored block in the low 8 bits (4: per-request table plus per-request
+ * occupancy bitmaps, needs granules <= 32704 and largest <= 32; 8: sorted list with 16-bit
+ * fields, needs granules < 2^16 and t_end < 2^16; 16: sorted list of 32-bit granule counts,
+ * needs granules < 2^31; 24: sorted list of 64-bit byte addresses), bit 8 set when the
+ * blocks are kept in LDS rather than in the workspace, bit 9 set for the bitmap variant.
+ * 0 if no device.
  * stalloc_plan_lds_capacity: largest n for which 16-byte entries stay in LDS.
  */
-uint32_t stalloc_plan_list_layout(uint32_t n, uint32_t t_end, uint64_t granules);
+uint32_t stalloc_plan_list_layout(uint32_t n, uint32_t t_end, uint64_t granules, uint64_t largest);
 uint32_t stalloc_plan_lds_capacity(void);
 
 #ifdef __cplusplus

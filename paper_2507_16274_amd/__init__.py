@@ -51,8 +51,9 @@ def _load() -> ctypes.CDLL:
         getattr(lib, name).restype = ctypes.c_int
     lib.stalloc_status_string.argtypes = [ctypes.c_int]
     lib.stalloc_status_string.restype = ctypes.c_char_p
+    lib.stalloc_plan_lds_capacity.argtypes = []
+    lib.stalloc_plan_list_layout.argtypes = [u32, u32, ctypes.c_uint64, ctypes.c_uint64]
     for name in ("stalloc_plan_lds_capacity", "stalloc_plan_list_layout"):
-        getattr(lib, name).argtypes = []
         getattr(lib, name).restype = ctypes.c_uint32
     return lib
 

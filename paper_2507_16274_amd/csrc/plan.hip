@@ -42,6 +42,7 @@
 // that does not apply returns at once.  The list lives in LDS when it fits and in the
 // workspace otherwise.
 #include "host_util.h"
+#include "plan_params.h"
 #include "wave.h"
 
 namespace stalloc {
@@ -79,21 +80,6 @@ struct PlanLds {
     Span<Addr> pend_span[kPend];                           // blocks settled in this batch, sorted
     uint2 pend_life[kPend];
     uint32_t settled;
-};
-
-struct PlanParams {
-    const uint64_t* size;
-    const uint32_t* ta;
-    const uint32_t* tf;
-    const uint32_t* orders;
-    uint64_t* offsets;       // [P][n] or nullptr
-    uint64_t* peaks;         // [P]
-    uint32_t* status;
-    const uint64_t* acc;     // trace-check accumulators (mode word)
-    unsigned char* slabs;    // list in the workspace: gridDim.x slabs of 2 * n entries
-    uint32_t n;
-    uint32_t P;
-    uint32_t compact_enqueued;   // the compact 32-bit instantiation is part of this call
 };
 
 // The sorted list of placed blocks.  Two storage layouts:
@@ -619,6 +605,7 @@ __global__ void __launch_bounds__(kThreads, 4) plan_kernel(PlanParams prm)   // 
 
     if (*prm.status != STALLOC_OK) return;               // malformed trace: nothing to plan
     const uint64_t mode = prm.acc[kAccMode];
+    if (prm.bitmap_enqueued && (mode & kModeBitmap)) return;   // the occupancy-bitmap kernel handles this trace
     const bool narrow = (mode & kModeNarrow) != 0;
     if (narrow != (sizeof(Addr) == 4)) return;            // another instantiation handles this trace
     // of the two 32-bit instantiations the compact one runs when it was enqueued and applies
@@ -786,10 +773,12 @@ extern "C" uint32_t stalloc_plan_lds_capacity(void)
     return lds_capacity_entries<uint32_t, kThreadsLds>(di.lds_per_block, entry_bytes<uint32_t>());
 }
 
-extern "C" uint32_t stalloc_plan_list_layout(uint32_t n, uint32_t t_end, uint64_t granules)
+extern "C" uint32_t stalloc_plan_list_layout(uint32_t n, uint32_t t_end, uint64_t granules, uint64_t largest)
 {
     DeviceInfo di;
     if (!device_info(&di)) return 0;
+    if (granules <= kBitmapGranules && largest <= kBitmapMaxSize && bitmap_plan_possible(n, di))
+        return (uint32_t)sizeof(uint32_t) | 0x300u;
     if (granules < (1ull << 16) && t_end < 0x10000u &&
         n <= lds_capacity_entries<uint32_t, kThreadsCompact>(di.lds_per_block / 2, sizeof(uint2)))
         return (uint32_t)sizeof(uint2) | 0x100u;
@@ -823,6 +812,10 @@ extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uin
     uint64_t* acc = cv.take<uint64_t>(kAccWords);
     uint64_t* own_offsets = (!offsets && best_offsets) ? cv.take<uint64_t>((size_t)P * n) : nullptr;
     unsigned char* slabs = lds64 ? nullptr : cv.take<unsigned char>((size_t)grid_mem * 2 * n * entry_bytes<uint64_t>());
+    // occupancy-bitmap variant: lifetime-conflict index of the trace
+    const bool bitmap = bitmap_plan_possible(n, di);
+    uint32_t* nbr_begin = bitmap ? cv.take<uint32_t>((size_t)n + 2) : nullptr;
+    uint16_t* nbr = bitmap ? cv.take<uint16_t>(bitmap_index_entries(n)) : nullptr;
     if (!workspace) { *workspace_bytes = cv.used; return STALLOC_OK; }
     if (!orders || !peaks || !best_plan || !device_status || *workspace_bytes < cv.used ||
         (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)))
@@ -836,7 +829,9 @@ extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uin
     prm.offsets = offsets ? offsets : own_offsets;
     prm.peaks = peaks; prm.status = device_status; prm.acc = acc; prm.slabs = slabs; prm.n = n; prm.P = P;
     prm.compact_enqueued = compact ? 1u : 0u;
+    prm.nbr_begin = nbr_begin; prm.nbr = nbr; prm.bitmap_enqueued = bitmap ? 1u : 0u;
     bool ok = true;
+    if (bitmap) ok = ok && launch_plan_bitmap(prm, di, stream);
     // exactly one of the launches does the work; the trace decides which (see the mode word)
     if (compact) ok = ok && launch_plan<uint32_t, true, true, kPendLds, kThreadsCompact>(prm, grid_compact, di, stream);
     if (lds32) ok = ok && launch_plan<uint32_t, true, false, kPendLds, kThreadsLds>(prm, grid_lds, di, stream);

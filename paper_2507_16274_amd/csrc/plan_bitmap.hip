@@ -1,0 +1,299 @@
+// stalloc_plan, occupancy-bitmap variant: the same rule as the sorted-list kernel (Sec. 5.1:
+// requests in the given order, each at the lowest address where it conflicts with no earlier
+// request of the plan in lifespan and address range at once; extent = max(a + s), Eq. 2), for
+// traces whose whole address range is small when counted in granules.
+//
+// With g the largest power of two dividing all sizes, every address is a multiple of g and lies
+// below the sum of sizes.  When that sum is at most 32704 granules and no request is longer than
+// 32 granules, "which addresses are blocked for request r" fits a bitmap of one bit per granule
+// that a single wave can hold in LDS and search in a few steps:
+//
+//   index    Once per call: for every request the list of requests whose lifetime overlaps its
+//            own (the potential conflicts of Sec. 5.1 do not depend on the order), rows padded
+//            to 256 entries with a dummy request that is never placed.
+//   build    One workgroup per plan, one wave per request of a batch of K.  The wave clears its
+//            bitmap, walks the request's row of the index, looks every neighbour up in the
+//            plan's table of placed blocks (LDS, 4 bytes per request: address and size in
+//            granules, size 0 = not placed yet) and ORs the neighbour's granules into the bitmap;
+//            the first run of `size` zero bits is the lowest fit against everything placed
+//            before the batch.
+//   settle   Wave 0 takes the K requests in order.  A candidate stands unless a request settled
+//            earlier in the same batch overlaps it in lifetime and in address range; only then
+//            are those blocks ORed into the request's bitmap and the search repeated.  Adding
+//            blocks can only remove free runs, so an untouched candidate is still the lowest.
+//
+// Nothing is sorted or merged and no placement needs a second pass over a list.
+#include "host_util.h"
+#include "plan_params.h"
+#include "wave.h"
+
+namespace stalloc {
+
+constexpr int kBmBatch = 256;            // requests fetched per refill
+constexpr int kBmWords = 1056;           // 32704 / 32 words + one word per request of a batch + slack
+constexpr int kRowPad = 256;             // index rows are padded to this many entries (4 per lane)
+
+#ifndef STALLOC_BITMAP_WAVES
+#define STALLOC_BITMAP_WAVES 8
+#endif
+constexpr int kBmWaves = STALLOC_BITMAP_WAVES;     // waves per workgroup = requests per batch
+static_assert(kBmWaves >= 1 && kBmWaves <= 16, "bitmap slack covers at most 16 requests per batch");
+
+template <int kWaves>
+struct BitmapLds {
+    uint32_t rq_id[kBmBatch];
+    uint32_t rq_s[kBmBatch];             // size in granules
+    uint32_t rq_ta[kBmBatch];
+    uint32_t rq_tf[kBmBatch];
+    uint32_t rq_x[kBmBatch];             // address in granules
+    uint32_t cand[kWaves];               // lowest fit against the blocks placed before the batch
+    uint32_t top;                        // extent so far, granules
+    uint32_t pad[3];
+    uint32_t bitmap[kWaves][kBmWords];
+};
+
+// ---------------------------------------------------------------------------------------------
+// Lifetime-conflict index.  begin[i] .. begin[i + 1] are the 256-entry chunks of request i's row;
+// an entry is 4 * j for a request j != i with t_alloc_j < t_free_i and t_alloc_i < t_free_j, or
+// 4 * n (the dummy).  begin[] first holds the degrees, then their exclusive prefix sum in chunks.
+
+__device__ __forceinline__ bool index_wanted(const PlanParams& prm)
+{
+    return *prm.status == STALLOC_OK && (prm.acc[kAccMode] & kModeBitmap) != 0;
+}
+
+__global__ void __launch_bounds__(256) nbr_count(PlanParams prm)
+{
+    __shared__ uint32_t total;
+    if (!index_wanted(prm)) return;
+    const uint32_t i = blockIdx.x, n = prm.n;
+    if (threadIdx.x == 0) total = 0;
+    __syncthreads();
+    const uint32_t ta = prm.ta[i], tf = prm.tf[i];
+    uint32_t c = 0;
+    for (uint32_t j = threadIdx.x; j < n; j += 256) c += (j != i && prm.ta[j] < tf && ta < prm.tf[j]);
+    c = wave_sum32(c);
+    if (lane_id() == 0) atomicAdd(&total, c);
+    __syncthreads();
+    if (threadIdx.x == 0) prm.nbr_begin[i] = total;
+}
+
+__global__ void __launch_bounds__(1024) nbr_scan(PlanParams prm)
+{
+    __shared__ uint32_t part[1024];
+    if (!index_wanted(prm)) return;
+    const uint32_t n = prm.n;
+    const uint32_t per = (n + 1023) / 1024;
+    const uint32_t lo = threadIdx.x * per, hi = lo + per < n ? lo + per : n;
+    uint32_t sum = 0;
+    for (uint32_t i = lo; i < hi; ++i) sum += (prm.nbr_begin[i] + kRowPad - 1) / kRowPad;
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    for (uint32_t d = 1; d < 1024; d <<= 1) {            // inclusive scan of the per-thread sums
+        const uint32_t add = threadIdx.x >= d ? part[threadIdx.x - d] : 0u;
+        __syncthreads();
+        part[threadIdx.x] += add;
+        __syncthreads();
+    }
+    uint32_t run = part[threadIdx.x] - sum;
+    for (uint32_t i = lo; i < hi; ++i) {
+        const uint32_t chunks = (prm.nbr_begin[i] + kRowPad - 1) / kRowPad;
+        prm.nbr_begin[i] = run;
+        run += chunks;
+    }
+    if (threadIdx.x == 1023) prm.nbr_begin[n] = part[1023];
+}
+
+__global__ void __launch_bounds__(256) nbr_fill(PlanParams prm)
+{
+    __shared__ uint32_t cursor;
+    if (!index_wanted(prm)) return;
+    const uint32_t i = blockIdx.x, n = prm.n;
+    if (threadIdx.x == 0) cursor = 0;
+    __syncthreads();
+    const uint32_t ta = prm.ta[i], tf = prm.tf[i];
+    uint16_t* row = prm.nbr + (size_t)prm.nbr_begin[i] * kRowPad;
+    const uint32_t room = (prm.nbr_begin[i + 1] - prm.nbr_begin[i]) * kRowPad;
+    for (uint32_t j = threadIdx.x; j < n; j += 256) {
+        if (j != i && prm.ta[j] < tf && ta < prm.tf[j]) {
+            const uint32_t pos = atomicAdd(&cursor, 1u);      // any order: the bitmap is an OR over the row
+            if (pos < room) row[pos] = (uint16_t)(4 * j);
+        }
+    }
+    __syncthreads();
+    for (uint32_t pos = cursor + threadIdx.x; pos < room; pos += 256) row[pos] = (uint16_t)(4 * n);
+}
+
+// ---------------------------------------------------------------------------------------------
+
+// Marks the granules [a, a + sz) in the bitmap (sz <= 32: at most two words).
+__device__ __forceinline__ void mark_block(uint32_t* bm, uint32_t a, uint32_t sz)
+{
+    const uint64_t m = ((1ull << sz) - 1) << (a & 31);
+    const uint32_t w = a >> 5;
+    atomicOr(&bm[w], (uint32_t)m);
+    if ((uint32_t)(m >> 32)) atomicOr(&bm[w + 1], (uint32_t)(m >> 32));
+}
+
+// Lowest bit position x such that bits [x, x + s) of the bitmap are zero; words at and beyond
+// `limit` count as free.  1 <= s <= 32.  Whole wave, uniform result.
+__device__ __forceinline__ uint32_t first_fit(const uint32_t* bm, uint32_t limit, uint32_t s)
+{
+    const int lane = lane_id();
+    for (uint32_t t = 0;; t += kWave) {
+        const uint32_t w = t + lane;
+        const uint32_t here = w < limit ? bm[w] : 0u;
+        const uint32_t next = w + 1 < limit ? bm[w + 1] : 0u;
+        uint64_t free_run = ~((uint64_t)here | ((uint64_t)next << 32));     // bit b: granule 32 w + b is free
+        for (uint32_t len = 1; len < s;) {                                  // bit b: free for `len` granules from b
+            const uint32_t step = len < s - len ? len : s - len;
+            free_run &= free_run >> step;
+            len += step;
+        }
+        const uint32_t starts = (uint32_t)free_run;                         // runs that begin inside word w
+        const uint64_t any = __builtin_amdgcn_ballot_w64(starts != 0);
+        if (any) {
+            const int f = __builtin_ctzll(any);
+            return (t + (uint32_t)f) * 32 + (uint32_t)__builtin_ctz(read_lane(starts, f));
+        }
+    }
+}
+
+template <int kWaves>
+__global__ void __launch_bounds__(kWaves * kWave, 4) plan_bitmap_kernel(PlanParams prm)
+{
+    using Lds = BitmapLds<kWaves>;
+    constexpr int kThreads = kWaves * kWave;
+    extern __shared__ __align__(16) unsigned char smem[];
+    Lds& sh = *reinterpret_cast<Lds*>(smem);
+    uint32_t* cells = reinterpret_cast<uint32_t*>(smem + sizeof(Lds));     // [n + 1]: address | size << 16
+    const uint32_t n = prm.n;
+
+    if (!index_wanted(prm)) return;
+    const uint32_t shift = (uint32_t)(prm.acc[kAccMode] & 63);
+    const int lane = lane_id(), wave = wave_id();
+    uint32_t* bm = sh.bitmap[wave];
+
+    for (uint32_t p = blockIdx.x; p < prm.P; p += gridDim.x) {
+        const uint32_t* order = prm.orders + (size_t)p * n;
+        uint64_t* out = prm.offsets ? prm.offsets + (size_t)p * n : nullptr;
+        for (uint32_t i = threadIdx.x; i <= n; i += kThreads) cells[i] = 0;     // nothing placed; cell n = dummy
+        if (threadIdx.x == 0) sh.top = 0;
+
+        for (uint32_t r0 = 0; r0 < n; r0 += kBmBatch) {
+            const uint32_t staged = n - r0 < (uint32_t)kBmBatch ? n - r0 : (uint32_t)kBmBatch;
+            __syncthreads();                                  // previous refill fully consumed
+            if (threadIdx.x < staged) {
+                uint32_t i = order[r0 + threadIdx.x];
+                if (i >= n) { atomicMax(prm.status, (uint32_t)STALLOC_ERR_BAD_ORDER); i = 0; }
+                sh.rq_id[threadIdx.x] = i;
+                sh.rq_s[threadIdx.x] = (uint32_t)(prm.size[i] >> shift);
+                sh.rq_ta[threadIdx.x] = prm.ta[i];
+                sh.rq_tf[threadIdx.x] = prm.tf[i];
+            }
+            __syncthreads();
+
+            for (uint32_t b0 = 0; b0 < staged; b0 += kWaves) {
+                const uint32_t nb = staged - b0 < (uint32_t)kWaves ? staged - b0 : (uint32_t)kWaves;
+                const uint32_t top0 = sh.top;
+                // every block of the plan, this batch included, ends below word `limit`
+                const uint32_t limit = top0 / 32 + kWaves + 2;
+
+                if ((uint32_t)wave < nb) {
+                    // build: blocked granules of request b0 + wave w.r.t. everything placed so far
+                    const uint32_t i = sh.rq_id[b0 + wave], s = sh.rq_s[b0 + wave];
+                    for (uint32_t w = lane; w < limit; w += kWave) bm[w] = 0;
+                    const uint32_t c0 = prm.nbr_begin[i], c1 = prm.nbr_begin[i + 1];
+                    const uint2* row = reinterpret_cast<const uint2*>(prm.nbr) + (size_t)c0 * (kRowPad / 4) + lane;
+                    uint2 ids = c0 < c1 ? row[0] : make_uint2(0, 0);
+                    for (uint32_t c = c0; c < c1; ++c) {
+                        const uint2 cur = ids;
+                        row += kRowPad / 4;
+                        if (c + 1 < c1) ids = row[0];                       // next chunk in flight during this one
+                        const uint32_t id4[4] = {cur.x & 0xffffu, cur.x >> 16, cur.y & 0xffffu, cur.y >> 16};
+                        uint32_t cell[4];
+#pragma unroll
+                        for (int k = 0; k < 4; ++k)
+                            cell[k] = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const unsigned char*>(cells) + id4[k]);
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            const uint32_t sz = cell[k] >> 16;
+                            if (sz) mark_block(bm, cell[k] & 0xffffu, sz);
+                        }
+                    }
+                    const uint32_t x = first_fit(bm, limit, s);
+                    if (lane == 0) sh.cand[wave] = x;
+                }
+                __syncthreads();
+
+                if (wave == 0) {
+                    // settle: lane q holds request q of the batch; `mine` = its final address once settled
+                    uint32_t my_s = 0, my_ta = 0xffffffffu, my_tf = 0, my_x = 0, mine = 0;   // empty lifetime: no conflicts
+                    if (lane < (int)nb) {
+                        my_s = sh.rq_s[b0 + lane];
+                        my_ta = sh.rq_ta[b0 + lane];
+                        my_tf = sh.rq_tf[b0 + lane];
+                        my_x = sh.cand[lane];
+                    }
+                    uint32_t top = top0;
+                    for (uint32_t r = 0; r < nb; ++r) {
+                        const uint32_t s = read_lane(my_s, (int)r), ta = read_lane(my_ta, (int)r);
+                        const uint32_t tf = read_lane(my_tf, (int)r);
+                        uint32_t x = read_lane(my_x, (int)r);
+                        const bool rival = lane < (int)r && my_ta < tf && ta < my_tf;
+                        if (__builtin_amdgcn_ballot_w64(rival && mine < x + s && x < mine + my_s)) {
+                            if (rival) mark_block(sh.bitmap[r], mine, my_s);
+                            x = first_fit(sh.bitmap[r], limit, s);
+                        }
+                        if (x > kBitmapGranules) x = kBitmapGranules;      // only reachable with a malformed order row
+                        if (lane == (int)r) mine = x;
+                        top = umax(top, x + s);
+                    }
+                    if (lane < (int)nb) {
+                        cells[sh.rq_id[b0 + lane]] = mine | (my_s << 16);
+                        sh.rq_x[b0 + lane] = mine;
+                    }
+                    if (lane == 0) sh.top = top;
+                }
+                __syncthreads();
+            }
+            if (out && threadIdx.x < staged) out[sh.rq_id[threadIdx.x]] = (uint64_t)sh.rq_x[threadIdx.x] << shift;
+        }
+        if (threadIdx.x == 0) prm.peaks[p] = (uint64_t)sh.top << shift;
+        __syncthreads();                                      // sh.top read before the next plan clears it
+    }
+}
+
+bool bitmap_plan_possible(uint32_t n, const DeviceInfo& di)
+{
+    // two workgroups per CU; ids are stored as 4 * j in 16 bits
+    const size_t budget = di.lds_per_block / 2;
+    return n < 16384u && sizeof(BitmapLds<kBmWaves>) + ((size_t)n + 1) * sizeof(uint32_t) <= budget;
+}
+
+size_t bitmap_index_entries(uint32_t n)
+{
+    return (size_t)n * (((size_t)n - 1 + kRowPad - 1) / kRowPad * kRowPad);
+}
+
+bool launch_plan_bitmap(const PlanParams& prm, const DeviceInfo& di, hipStream_t stream)
+{
+    auto kernel = &plan_bitmap_kernel<kBmWaves>;
+    const size_t lds = sizeof(BitmapLds<kBmWaves>) + ((size_t)prm.n + 1) * sizeof(uint32_t);
+    static bool attr_set[64] = {};
+    if (!attr_set[di.device]) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)di.lds_per_block) != hipSuccess)
+            return false;
+        attr_set[di.device] = true;
+    }
+    hipLaunchKernelGGL(nbr_count, dim3(prm.n), dim3(256), 0, stream, prm);
+    hipLaunchKernelGGL(nbr_scan, dim3(1), dim3(1024), 0, stream, prm);
+    hipLaunchKernelGGL(nbr_fill, dim3(prm.n), dim3(256), 0, stream, prm);
+    uint32_t grid = (uint32_t)di.cus * 2;
+    if (grid > prm.P) grid = prm.P;
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kBmWaves * kWave), lds, stream, prm);
+    return true;
+}
+
+}  // namespace stalloc

@@ -20,7 +20,7 @@ __global__ void __launch_bounds__(256)
 trace_check_scan(const uint64_t* __restrict__ size, const uint32_t* __restrict__ ta,
                  const uint32_t* __restrict__ tf, uint32_t n, uint32_t t_end, uint64_t* acc)
 {
-    uint64_t hi = 0, lo = 0, bits = 0;
+    uint64_t hi = 0, lo = 0, bits = 0, largest = 0;
     uint32_t bad = 0;
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
         uint64_t s = size[i];
@@ -29,16 +29,19 @@ trace_check_scan(const uint64_t* __restrict__ size, const uint32_t* __restrict__
         hi += s >> 32;               // n < 2^31 terms below 2^32 each: cannot wrap
         lo += s & 0xffffffffull;
         bits |= s;
+        largest = umax64(largest, s);
     }
     hi = wave_sum64(hi);
     lo = wave_sum64(lo);
     bits = wave_or64(bits);
+    largest = wave_max64(largest);
     uint64_t any_bad = __builtin_amdgcn_ballot_w64(bad != 0);
     if (lane_id() == 0) {
         atomicAdd((unsigned long long*)&acc[0], (unsigned long long)hi);
         atomicAdd((unsigned long long*)&acc[1], (unsigned long long)lo);
         if (any_bad) atomicOr((unsigned long long*)&acc[2], 1ull);
         atomicOr((unsigned long long*)&acc[3], (unsigned long long)bits);
+        atomicMax((unsigned long long*)&acc[kAccMaxSize], (unsigned long long)largest);
     }
 }
 
@@ -52,7 +55,9 @@ __global__ void trace_check_finish(uint64_t* acc, uint32_t* status)
         const uint32_t shift = (uint32_t)__builtin_ctzll(acc[3]);
         const uint64_t narrow = (total >> shift) < (1ull << 31) ? kModeNarrow : 0;
         const uint64_t compact = (total >> shift) < (1ull << 16) ? kModeCompact : 0;
-        acc[kAccMode] = shift | narrow | compact;
+        const uint64_t bitmap = (total >> shift) <= kBitmapGranules && (acc[kAccMaxSize] >> shift) <= kBitmapMaxSize
+                                    ? kModeBitmap : 0;
+        acc[kAccMode] = shift | narrow | compact | bitmap;
     }
     // total = acc[0] * 2^32 + acc[1]  >= 2^63  <=>  acc[0] + (acc[1] >> 32) >= 2^31
     if (acc[0] + (acc[1] >> 32) >= (1ull << 31)) code = STALLOC_ERR_OVERFLOW;
