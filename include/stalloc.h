@@ -117,7 +117,7 @@ const char *stalloc_status_string(int status);
  * device.  `granules` = (sum of sizes) / g and `largest` = (largest size) / g, with g the
  * largest power of two dividing every size (all addresses are multiples of g).  Returns
  * the bytes of one stored block in the low 8 bits (4: per-request table plus per-request
- * occupancy bitmaps, needs granules <= 32704 and largest <= 32; 8: sorted list with 16-bit
+ * occupancy bitmaps, needs granules <= 32704 and largest <= 31; 8: sorted list with 16-bit
  * fields, needs granules < 2^16 and t_end < 2^16; 16: sorted list of 32-bit granule counts,
  * needs granules < 2^31; 24: sorted list of 64-bit byte addresses), bit 8 set when the
  * blocks are kept in LDS rather than in the workspace, bit 9 set for the bitmap variant.

@@ -71,7 +71,7 @@ constexpr uint64_t kModeNarrow = 1ull << 8;
 constexpr uint64_t kModeCompact = 1ull << 9;   // sum of sizes in granules below 2^16 as well
 constexpr uint64_t kModeBitmap = 1ull << 10;   // sum <= kBitmapGranules and every size <= kBitmapMaxSize granules
 constexpr uint32_t kBitmapGranules = 32704;    // 1022 words of 32 granules
-constexpr uint32_t kBitmapMaxSize = 32;        // a block touches at most two bitmap words
+constexpr uint32_t kBitmapMaxSize = 31;        // a block touches at most two bitmap words, its size fits 5 bits
 void launch_trace_check(const stalloc_trace& tr, uint64_t* acc, uint32_t* device_status, hipStream_t stream);
 
 }  // namespace stalloc

@@ -5,18 +5,22 @@
 //
 // With g the largest power of two dividing all sizes, every address is a multiple of g and lies
 // below the sum of sizes.  When that sum is at most 32704 granules and no request is longer than
-// 32 granules, "which addresses are blocked for request r" fits a bitmap of one bit per granule
+// 31 granules, "which addresses are blocked for request r" fits a bitmap of one bit per granule
 // that a single wave can hold in LDS and search in a few steps:
 //
 //   index    Once per call: for every request the list of requests whose lifetime overlaps its
 //            own (the potential conflicts of Sec. 5.1 do not depend on the order), rows padded
 //            to 256 entries with a dummy request that is never placed.
-//   build    One workgroup per plan, one wave per request of a batch of K.  The wave clears its
-//            bitmap, walks the request's row of the index, looks every neighbour up in the
-//            plan's table of placed blocks (LDS, 4 bytes per request: address and size in
-//            granules, size 0 = not placed yet) and ORs the neighbour's granules into the bitmap;
-//            the first run of `size` zero bits is the lowest fit against everything placed
-//            before the batch.
+//   build    One workgroup per plan, K requests per batch, one bitmap per request.  The rows of
+//            the K requests are cut into chunks of 256 entries which are dealt out to the waves
+//            round robin, so that every wave has the same amount of work whatever the row
+//            lengths.  A wave looks every neighbour of its chunk up in the plan's table of
+//            placed blocks (LDS, 4 bytes per request: address and the two word masks in a
+//            compressed form, 0 = not placed yet) and ORs the neighbour's granules into the
+//            bitmap of the request the chunk belongs to (LDS atomics: any wave may add to any
+//            bitmap).
+//   search   Wave r finds the first run of size_r zero bits in bitmap r: the lowest fit against
+//            everything placed before the batch.
 //   settle   Wave 0 takes the K requests in order.  A candidate stands unless a request settled
 //            earlier in the same batch overlaps it in lifetime and in address range; only then
 //            are those blocks ORed into the request's bitmap and the search repeated.  Adding
@@ -46,6 +50,8 @@ struct BitmapLds {
     uint32_t rq_ta[kBmBatch];
     uint32_t rq_tf[kBmBatch];
     uint32_t rq_x[kBmBatch];             // address in granules
+    uint32_t rq_row[kBmBatch];           // first chunk of the request's row of the index
+    uint32_t rq_chunks[kBmBatch];        // chunks in that row
     uint32_t cand[kWaves];               // lowest fit against the blocks placed before the batch
     uint32_t top;                        // extent so far, granules
     uint32_t pad[3];
@@ -126,17 +132,39 @@ __global__ void __launch_bounds__(256) nbr_fill(PlanParams prm)
 
 // ---------------------------------------------------------------------------------------------
 
-// Marks the granules [a, a + sz) in the bitmap (sz <= 32: at most two words).
-__device__ __forceinline__ void mark_block(uint32_t* bm, uint32_t a, uint32_t sz)
+__device__ __forceinline__ uint32_t uniform(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// A placed block as the build phase wants it: bits 0-14 address in granules (bits 0-4 = first bit
+// b in its first word, bits 5-14 = that word), bits 16-20 size in granules (1..31), bits 24-28 the
+// number of granules that spill into the next word.  0 = not placed.
+__device__ __forceinline__ uint32_t make_cell(uint32_t x, uint32_t sz)
 {
-    const uint64_t m = ((1ull << sz) - 1) << (a & 31);
-    const uint32_t w = a >> 5;
-    atomicOr(&bm[w], (uint32_t)m);
-    if ((uint32_t)(m >> 32)) atomicOr(&bm[w + 1], (uint32_t)(m >> 32));
+    const uint32_t reach = (x & 31) + sz;
+    return x | (sz << 16) | ((reach > 32 ? reach - 32 : 0u) << 24);
+}
+
+// ((1 << width) - 1) << offset with both taken modulo 32.
+__device__ __forceinline__ uint32_t bit_field_mask(uint32_t width, uint32_t offset)
+{
+    uint32_t r;
+    asm("v_bfm_b32 %0, %1, %2" : "=v"(r) : "v"(width), "v"(offset));
+    return r;
+}
+
+// ORs the block of `cell` into the bitmap; cell == 0 adds nothing.
+__device__ __forceinline__ void mark_cell(uint32_t* bm, uint32_t cell)
+{
+    if (cell) {
+        const uint32_t first = bit_field_mask(cell >> 16, cell);      // ((1 << size) - 1) << b, low 32 bits
+        const uint32_t spill = bit_field_mask(cell >> 24, 0u);        // (1 << spilled) - 1
+        uint32_t* word = bm + ((cell >> 5) & 0x3ffu);
+        atomicOr(word, first);
+        if (spill) atomicOr(word + 1, spill);
+    }
 }
 
 // Lowest bit position x such that bits [x, x + s) of the bitmap are zero; words at and beyond
-// `limit` count as free.  1 <= s <= 32.  Whole wave, uniform result.
+// `limit` count as free.  1 <= s <= 32, s and limit uniform.  Whole wave, uniform result.
 __device__ __forceinline__ uint32_t first_fit(const uint32_t* bm, uint32_t limit, uint32_t s)
 {
     const int lane = lane_id();
@@ -151,12 +179,22 @@ __device__ __forceinline__ uint32_t first_fit(const uint32_t* bm, uint32_t limit
             len += step;
         }
         const uint32_t starts = (uint32_t)free_run;                         // runs that begin inside word w
-        const uint64_t any = __builtin_amdgcn_ballot_w64(starts != 0);
+        const uint64_t any = __builtin_amdgcn_uicmp(starts, 0u, 33);        // != 0
         if (any) {
             const int f = __builtin_ctzll(any);
             return (t + (uint32_t)f) * 32 + (uint32_t)__builtin_ctz(read_lane(starts, f));
         }
     }
+}
+
+// Inclusive prefix sum inside each row of 16 lanes.
+__device__ __forceinline__ uint32_t row_scan_add(uint32_t v)
+{
+    v += __builtin_amdgcn_update_dpp(0u, v, kDppRowShr1, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0u, v, kDppRowShr2, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0u, v, kDppRowShr4, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0u, v, kDppRowShr8, 0xf, 0xf, false);
+    return v;
 }
 
 template <int kWaves>
@@ -166,13 +204,13 @@ __global__ void __launch_bounds__(kWaves * kWave, 4) plan_bitmap_kernel(PlanPara
     constexpr int kThreads = kWaves * kWave;
     extern __shared__ __align__(16) unsigned char smem[];
     Lds& sh = *reinterpret_cast<Lds*>(smem);
-    uint32_t* cells = reinterpret_cast<uint32_t*>(smem + sizeof(Lds));     // [n + 1]: address | size << 16
+    uint32_t* cells = reinterpret_cast<uint32_t*>(smem + sizeof(Lds));     // [n + 1] placed blocks, see make_cell
     const uint32_t n = prm.n;
 
     if (!index_wanted(prm)) return;
     const uint32_t shift = (uint32_t)(prm.acc[kAccMode] & 63);
-    const int lane = lane_id(), wave = wave_id();
-    uint32_t* bm = sh.bitmap[wave];
+    const int lane = lane_id(), wave = (int)uniform((uint32_t)wave_id());
+    const uint2* index = reinterpret_cast<const uint2*>(prm.nbr) + lane;   // a chunk: 64 lanes x 4 entries
 
     for (uint32_t p = blockIdx.x; p < prm.P; p += gridDim.x) {
         const uint32_t* order = prm.orders + (size_t)p * n;
@@ -190,38 +228,56 @@ __global__ void __launch_bounds__(kWaves * kWave, 4) plan_bitmap_kernel(PlanPara
                 sh.rq_s[threadIdx.x] = (uint32_t)(prm.size[i] >> shift);
                 sh.rq_ta[threadIdx.x] = prm.ta[i];
                 sh.rq_tf[threadIdx.x] = prm.tf[i];
+                const uint32_t c0 = prm.nbr_begin[i];
+                sh.rq_row[threadIdx.x] = c0;
+                sh.rq_chunks[threadIdx.x] = prm.nbr_begin[i + 1] - c0;
             }
             __syncthreads();
 
             for (uint32_t b0 = 0; b0 < staged; b0 += kWaves) {
                 const uint32_t nb = staged - b0 < (uint32_t)kWaves ? staged - b0 : (uint32_t)kWaves;
-                const uint32_t top0 = sh.top;
+                const uint32_t top0 = uniform(sh.top);
                 // every block of the plan, this batch included, ends below word `limit`
                 const uint32_t limit = top0 / 32 + kWaves + 2;
+                for (uint32_t w = lane; w < limit; w += kWave) sh.bitmap[wave][w] = 0;
+                __syncthreads();
 
-                if ((uint32_t)wave < nb) {
-                    // build: blocked granules of request b0 + wave w.r.t. everything placed so far
-                    const uint32_t i = sh.rq_id[b0 + wave], s = sh.rq_s[b0 + wave];
-                    for (uint32_t w = lane; w < limit; w += kWave) bm[w] = 0;
-                    const uint32_t c0 = prm.nbr_begin[i], c1 = prm.nbr_begin[i + 1];
-                    const uint2* row = reinterpret_cast<const uint2*>(prm.nbr) + (size_t)c0 * (kRowPad / 4) + lane;
-                    uint2 ids = c0 < c1 ? row[0] : make_uint2(0, 0);
-                    for (uint32_t c = c0; c < c1; ++c) {
+                // build: the chunks of the nb rows, numbered through, are dealt out round robin
+                {
+                    uint32_t my_row = 0, my_chunks = 0;               // lane q: row of request q of the batch
+                    if (lane < (int)nb) { my_row = sh.rq_row[b0 + lane]; my_chunks = sh.rq_chunks[b0 + lane]; }
+                    const uint32_t my_end = row_scan_add(my_chunks);  // (nb <= 16: one DPP row)
+                    const uint32_t total = read_lane(my_end, 15);
+                    // chunk f belongs to request q = number of rows that end at or before f
+                    auto locate = [&](uint32_t f, uint32_t& q) -> const uint2* {
+                        q = (uint32_t)__builtin_popcountll(lanes_ge(f, my_end) & 0xffffull);
+                        const uint32_t at = read_lane(my_row, (int)q) + f - (read_lane(my_end, (int)q) - read_lane(my_chunks, (int)q));
+                        return index + (size_t)at * (kRowPad / 4);
+                    };
+                    uint32_t q = 0, q_next = 0;
+                    uint2 ids = make_uint2(0, 0);
+                    if ((uint32_t)wave < total) ids = *locate((uint32_t)wave, q);
+                    for (uint32_t f = (uint32_t)wave; f < total; f += kWaves) {
                         const uint2 cur = ids;
-                        row += kRowPad / 4;
-                        if (c + 1 < c1) ids = row[0];                       // next chunk in flight during this one
-                        const uint32_t id4[4] = {cur.x & 0xffffu, cur.x >> 16, cur.y & 0xffffu, cur.y >> 16};
-                        uint32_t cell[4];
-#pragma unroll
-                        for (int k = 0; k < 4; ++k)
-                            cell[k] = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const unsigned char*>(cells) + id4[k]);
-#pragma unroll
-                        for (int k = 0; k < 4; ++k) {
-                            const uint32_t sz = cell[k] >> 16;
-                            if (sz) mark_block(bm, cell[k] & 0xffffu, sz);
-                        }
+                        if (f + kWaves < total) ids = *locate(f + kWaves, q_next);     // in flight during this chunk
+                        uint32_t* bm = sh.bitmap[q];
+                        const unsigned char* table = reinterpret_cast<const unsigned char*>(cells);
+                        const uint32_t c_a = *reinterpret_cast<const uint32_t*>(table + (cur.x & 0xffffu));
+                        const uint32_t c_b = *reinterpret_cast<const uint32_t*>(table + (cur.x >> 16));
+                        const uint32_t c_c = *reinterpret_cast<const uint32_t*>(table + (cur.y & 0xffffu));
+                        const uint32_t c_d = *reinterpret_cast<const uint32_t*>(table + (cur.y >> 16));
+                        mark_cell(bm, c_a);
+                        mark_cell(bm, c_b);
+                        mark_cell(bm, c_c);
+                        mark_cell(bm, c_d);
+                        q = q_next;
                     }
-                    const uint32_t x = first_fit(bm, limit, s);
+                }
+                __syncthreads();
+
+                // search: lowest fit of request b0 + wave against everything placed before the batch
+                if ((uint32_t)wave < nb) {
+                    const uint32_t x = first_fit(sh.bitmap[wave], limit, uniform(sh.rq_s[b0 + wave]));
                     if (lane == 0) sh.cand[wave] = x;
                 }
                 __syncthreads();
@@ -242,7 +298,7 @@ __global__ void __launch_bounds__(kWaves * kWave, 4) plan_bitmap_kernel(PlanPara
                         uint32_t x = read_lane(my_x, (int)r);
                         const bool rival = lane < (int)r && my_ta < tf && ta < my_tf;
                         if (__builtin_amdgcn_ballot_w64(rival && mine < x + s && x < mine + my_s)) {
-                            if (rival) mark_block(sh.bitmap[r], mine, my_s);
+                            if (rival) mark_cell(sh.bitmap[r], make_cell(mine, my_s));
                             x = first_fit(sh.bitmap[r], limit, s);
                         }
                         if (x > kBitmapGranules) x = kBitmapGranules;      // only reachable with a malformed order row
@@ -250,7 +306,7 @@ __global__ void __launch_bounds__(kWaves * kWave, 4) plan_bitmap_kernel(PlanPara
                         top = umax(top, x + s);
                     }
                     if (lane < (int)nb) {
-                        cells[sh.rq_id[b0 + lane]] = mine | (my_s << 16);
+                        cells[sh.rq_id[b0 + lane]] = make_cell(mine, my_s);
                         sh.rq_x[b0 + lane] = mine;
                     }
                     if (lane == 0) sh.top = top;
