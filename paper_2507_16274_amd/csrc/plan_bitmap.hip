@@ -135,7 +135,7 @@ __global__ void __launch_bounds__(256) nbr_fill(PlanParams prm)
 __device__ __forceinline__ uint32_t uniform(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
 
 // A placed block as the build phase wants it: bits 0-14 address in granules (bits 0-4 = first bit
-// b in its first word, bits 5-14 = that word), bits 16-20 size in granules (1..31), bits 24-28 the
+// b in its first word, bits 5-15 = that word), bits 16-20 size in granules (1..31), bits 24-28 the
 // number of granules that spill into the next word.  0 = not placed.
 __device__ __forceinline__ uint32_t make_cell(uint32_t x, uint32_t sz)
 {
@@ -154,13 +154,16 @@ __device__ __forceinline__ uint32_t bit_field_mask(uint32_t width, uint32_t offs
 // ORs the block of `cell` into the bitmap; cell == 0 adds nothing.
 __device__ __forceinline__ void mark_cell(uint32_t* bm, uint32_t cell)
 {
-    if (cell) {
-        const uint32_t first = bit_field_mask(cell >> 16, cell);      // ((1 << size) - 1) << b, low 32 bits
-        const uint32_t spill = bit_field_mask(cell >> 24, 0u);        // (1 << spilled) - 1
-        uint32_t* word = bm + ((cell >> 5) & 0x3ffu);
-        atomicOr(word, first);
-        if (spill) atomicOr(word + 1, spill);
-    }
+    if (cell == 0) return;       // (idle lanes must stay out of the LDS atomics: their cost grows with the lanes taking part)
+    // LDS address of the block's first word: two instructions (field extract, shift-add)
+    typedef __attribute__((address_space(3))) uint32_t lds_word;
+    const uint32_t base = (uint32_t)reinterpret_cast<uintptr_t>((lds_word*)bm);
+    uint32_t at;
+    asm("v_bfe_u32 %0, %1, 5, 11\n\tv_lshl_add_u32 %0, %0, 2, %2" : "=&v"(at) : "v"(cell), "s"(base));
+    lds_word* word = reinterpret_cast<lds_word*>((uintptr_t)at);
+    __hip_atomic_fetch_or(word, bit_field_mask(cell >> 16, cell), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);   // ((1 << size) - 1) << b
+    if (cell >= (1u << 24))
+        __hip_atomic_fetch_or(word + 1, bit_field_mask(cell >> 24, 0u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);   // (1 << spilled) - 1
 }
 
 // Lowest bit position x such that bits [x, x + s) of the bitmap are zero; words at and beyond
@@ -215,7 +218,7 @@ __global__ void __launch_bounds__(kWaves * kWave, 4) plan_bitmap_kernel(PlanPara
     for (uint32_t p = blockIdx.x; p < prm.P; p += gridDim.x) {
         const uint32_t* order = prm.orders + (size_t)p * n;
         uint64_t* out = prm.offsets ? prm.offsets + (size_t)p * n : nullptr;
-        for (uint32_t i = threadIdx.x; i <= n; i += kThreads) cells[i] = 0;     // nothing placed; cell n = dummy
+        for (uint32_t i = threadIdx.x; i <= n; i += kThreads) cells[i] = 0;     // nothing placed; cell n pads the rows
         if (threadIdx.x == 0) sh.top = 0;
 
         for (uint32_t r0 = 0; r0 < n; r0 += kBmBatch) {
