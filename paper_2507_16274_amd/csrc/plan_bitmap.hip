@@ -151,19 +151,51 @@ __device__ __forceinline__ uint32_t bit_field_mask(uint32_t width, uint32_t offs
     return r;
 }
 
-// ORs the block of `cell` into the bitmap; cell == 0 adds nothing.
-__device__ __forceinline__ void mark_cell(uint32_t* bm, uint32_t cell)
+typedef __attribute__((address_space(3))) uint32_t lds_word;
+
+// LDS address of the first bitmap word of the block of `cell`: field extract, shift-add.
+__device__ __forceinline__ lds_word* first_word(uint32_t* bm, uint32_t cell)
 {
-    if (cell == 0) return;       // (idle lanes must stay out of the LDS atomics: their cost grows with the lanes taking part)
-    // LDS address of the block's first word: two instructions (field extract, shift-add)
-    typedef __attribute__((address_space(3))) uint32_t lds_word;
     const uint32_t base = (uint32_t)reinterpret_cast<uintptr_t>((lds_word*)bm);
     uint32_t at;
     asm("v_bfe_u32 %0, %1, 5, 11\n\tv_lshl_add_u32 %0, %0, 2, %2" : "=&v"(at) : "v"(cell), "s"(base));
-    lds_word* word = reinterpret_cast<lds_word*>((uintptr_t)at);
-    __hip_atomic_fetch_or(word, bit_field_mask(cell >> 16, cell), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);   // ((1 << size) - 1) << b
-    if (cell >= (1u << 24))
-        __hip_atomic_fetch_or(word + 1, bit_field_mask(cell >> 24, 0u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);   // (1 << spilled) - 1
+    return reinterpret_cast<lds_word*>((uintptr_t)at);
+}
+
+// ORs the block of `cell` into the bitmap; cell == 0 adds nothing.
+__device__ __forceinline__ void mark_cell(uint32_t* bm, uint32_t cell)
+{
+    lds_word* word = first_word(bm, cell);
+    const uint32_t first = bit_field_mask(cell >> 16, cell);          // ((1 << size) - 1) << b, low 32 bits
+    const uint32_t spill = bit_field_mask(cell >> 24, 0u);            // (1 << spilled) - 1
+    if (cell) __hip_atomic_fetch_or(word, first, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    if (cell >= (1u << 24)) __hip_atomic_fetch_or(word + 1, spill, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+// The same for four cells per lane, looking before ORing.  Blocks that are alive at different
+// times share addresses (that is the point of the plan), so most blocks of a row only repeat
+// bits that are already set, and many lanes of one instruction aim at the same few words.  LDS
+// serialises atomics on one address lane by lane but broadcasts reads of one address, hence:
+// read the words, and send only the lanes that still add a bit into the atomic.  (A word read
+// just before another wave's OR merely causes a redundant OR.)  Address and masks are worked
+// out for every lane; idle lanes have empty masks and drop out with the rest.
+__device__ __forceinline__ void mark_cells(uint32_t* bm, const uint32_t (&cell)[4])
+{
+    lds_word* word[4];
+    uint32_t first[4], spill[4], seen[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        word[k] = first_word(bm, cell[k]);
+        first[k] = bit_field_mask(cell[k] >> 16, cell[k]);
+        spill[k] = bit_field_mask(cell[k] >> 24, 0u);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) seen[k] = *word[k];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        if (first[k] & ~seen[k]) __hip_atomic_fetch_or(word[k], first[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (cell[k] >= (1u << 24)) __hip_atomic_fetch_or(word[k] + 1, spill[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
 }
 
 // Lowest bit position x such that bits [x, x + s) of the bitmap are zero; words at and beyond
@@ -257,23 +289,30 @@ __global__ void __launch_bounds__(kWaves * kWave, 4) plan_bitmap_kernel(PlanPara
                         const uint32_t at = read_lane(my_row, (int)q) + f - (read_lane(my_end, (int)q) - read_lane(my_chunks, (int)q));
                         return index + (size_t)at * (kRowPad / 4);
                     };
-                    uint32_t q = 0, q_next = 0;
+                    // Two stages in flight per wave: while the cells of one chunk are turned into bitmap
+                    // bits, the table lookups of the wave's next chunk and the index entries of the one
+                    // after that are already under way.
+                    const unsigned char* table = reinterpret_cast<const unsigned char*>(cells);
+                    auto lookup = [&](const uint2& ids, uint32_t (&cell)[4]) {
+                        cell[0] = *reinterpret_cast<const uint32_t*>(table + (ids.x & 0xffffu));
+                        cell[1] = *reinterpret_cast<const uint32_t*>(table + (ids.x >> 16));
+                        cell[2] = *reinterpret_cast<const uint32_t*>(table + (ids.y & 0xffffu));
+                        cell[3] = *reinterpret_cast<const uint32_t*>(table + (ids.y >> 16));
+                    };
+                    uint32_t q = 0, q_looked = 0, q_loaded = 0;
                     uint2 ids = make_uint2(0, 0);
-                    if ((uint32_t)wave < total) ids = *locate((uint32_t)wave, q);
-                    for (uint32_t f = (uint32_t)wave; f < total; f += kWaves) {
-                        const uint2 cur = ids;
-                        if (f + kWaves < total) ids = *locate(f + kWaves, q_next);     // in flight during this chunk
+                    uint32_t cell[4] = {0, 0, 0, 0}, looked[4] = {0, 0, 0, 0};
+                    const uint32_t f0 = (uint32_t)wave;
+                    if (f0 < total) { ids = *locate(f0, q); lookup(ids, cell); }
+                    if (f0 + kWaves < total) ids = *locate(f0 + kWaves, q_loaded);
+                    for (uint32_t f = f0; f < total; f += kWaves) {
+                        if (f + kWaves < total) { lookup(ids, looked); q_looked = q_loaded; }
+                        if (f + 2 * kWaves < total) ids = *locate(f + 2 * kWaves, q_loaded);
                         uint32_t* bm = sh.bitmap[q];
-                        const unsigned char* table = reinterpret_cast<const unsigned char*>(cells);
-                        const uint32_t c_a = *reinterpret_cast<const uint32_t*>(table + (cur.x & 0xffffu));
-                        const uint32_t c_b = *reinterpret_cast<const uint32_t*>(table + (cur.x >> 16));
-                        const uint32_t c_c = *reinterpret_cast<const uint32_t*>(table + (cur.y & 0xffffu));
-                        const uint32_t c_d = *reinterpret_cast<const uint32_t*>(table + (cur.y >> 16));
-                        mark_cell(bm, c_a);
-                        mark_cell(bm, c_b);
-                        mark_cell(bm, c_c);
-                        mark_cell(bm, c_d);
-                        q = q_next;
+                        mark_cells(bm, cell);
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) cell[k] = looked[k];
+                        q = q_looked;
                     }
                 }
                 __syncthreads();
