@@ -36,6 +36,7 @@ namespace stalloc {
 constexpr int kBmBatch = 256;            // requests fetched per refill
 constexpr int kBmWords = 1056;           // 32704 / 32 words + one word per request of a batch + slack
 constexpr int kRowPad = 256;             // index rows are padded to this many entries (4 per lane)
+constexpr int kAhead = 8;                // chunks per wave and batch whose index entries are fetched ahead
 
 #ifndef STALLOC_BITMAP_WAVES
 #define STALLOC_BITMAP_WAVES 8
@@ -269,6 +270,45 @@ __global__ void __launch_bounds__(kWaves * kWave, 4) plan_bitmap_kernel(PlanPara
             }
             __syncthreads();
 
+            // The rows of a batch, cut into chunks and numbered through; chunk f goes to wave f mod
+            // kWaves.  Lane q < 16 describes the row of request q of the batch.
+            struct Rows { uint32_t row, chunks, end, total; };
+            auto rows_of = [&](uint32_t first, uint32_t count) -> Rows {
+                Rows r = {0, 0, 0, 0};
+                if (lane < (int)count) { r.row = sh.rq_row[first + lane]; r.chunks = sh.rq_chunks[first + lane]; }
+                r.end = row_scan_add(r.chunks);                   // (count <= 16: one DPP row)
+                r.total = read_lane(r.end, 15);
+                return r;
+            };
+            // chunk f belongs to request q = number of rows that end at or before f
+            auto locate = [&](const Rows& r, uint32_t f, uint32_t& q) -> const uint2* {
+                q = (uint32_t)__builtin_popcountll(lanes_ge(f, r.end) & 0xffffull);
+                const uint32_t at = read_lane(r.row, (int)q) + f - (read_lane(r.end, (int)q) - read_lane(r.chunks, (int)q));
+                return index + (size_t)at * (kRowPad / 4);
+            };
+            // The index entries of a wave's first kAhead chunks of a batch are fetched long before
+            // the batch is built (while the batch before it is searched and settled): the index is
+            // far larger than the L2 and a fetch takes about as long as a chunk takes to process.
+            uint2 ahead[kAhead];
+            uint32_t ahead_q[kAhead];
+            auto fetch_ahead = [&](const Rows& r) {
+#pragma unroll
+                for (int j = 0; j < kAhead; ++j) {
+                    const uint32_t f = (uint32_t)wave + (uint32_t)j * kWaves;
+                    ahead_q[j] = 0;
+                    if (f < r.total) ahead[j] = *locate(r, f, ahead_q[j]);
+                }
+            };
+            const unsigned char* table = reinterpret_cast<const unsigned char*>(cells);
+            auto lookup = [&](const uint2& ids, uint32_t (&cell)[4]) {
+                cell[0] = *reinterpret_cast<const uint32_t*>(table + (ids.x & 0xffffu));
+                cell[1] = *reinterpret_cast<const uint32_t*>(table + (ids.x >> 16));
+                cell[2] = *reinterpret_cast<const uint32_t*>(table + (ids.y & 0xffffu));
+                cell[3] = *reinterpret_cast<const uint32_t*>(table + (ids.y >> 16));
+            };
+            Rows rows = rows_of(0, staged < (uint32_t)kWaves ? staged : (uint32_t)kWaves);
+            fetch_ahead(rows);
+
             for (uint32_t b0 = 0; b0 < staged; b0 += kWaves) {
                 const uint32_t nb = staged - b0 < (uint32_t)kWaves ? staged - b0 : (uint32_t)kWaves;
                 const uint32_t top0 = uniform(sh.top);
@@ -277,43 +317,31 @@ __global__ void __launch_bounds__(kWaves * kWave, 4) plan_bitmap_kernel(PlanPara
                 for (uint32_t w = lane; w < limit; w += kWave) sh.bitmap[wave][w] = 0;
                 __syncthreads();
 
-                // build: the chunks of the nb rows, numbered through, are dealt out round robin
+                // build: table lookups of one chunk are in flight while the previous one is marked
                 {
-                    uint32_t my_row = 0, my_chunks = 0;               // lane q: row of request q of the batch
-                    if (lane < (int)nb) { my_row = sh.rq_row[b0 + lane]; my_chunks = sh.rq_chunks[b0 + lane]; }
-                    const uint32_t my_end = row_scan_add(my_chunks);  // (nb <= 16: one DPP row)
-                    const uint32_t total = read_lane(my_end, 15);
-                    // chunk f belongs to request q = number of rows that end at or before f
-                    auto locate = [&](uint32_t f, uint32_t& q) -> const uint2* {
-                        q = (uint32_t)__builtin_popcountll(lanes_ge(f, my_end) & 0xffffull);
-                        const uint32_t at = read_lane(my_row, (int)q) + f - (read_lane(my_end, (int)q) - read_lane(my_chunks, (int)q));
-                        return index + (size_t)at * (kRowPad / 4);
-                    };
-                    // Two stages in flight per wave: while the cells of one chunk are turned into bitmap
-                    // bits, the table lookups of the wave's next chunk and the index entries of the one
-                    // after that are already under way.
-                    const unsigned char* table = reinterpret_cast<const unsigned char*>(cells);
-                    auto lookup = [&](const uint2& ids, uint32_t (&cell)[4]) {
-                        cell[0] = *reinterpret_cast<const uint32_t*>(table + (ids.x & 0xffffu));
-                        cell[1] = *reinterpret_cast<const uint32_t*>(table + (ids.x >> 16));
-                        cell[2] = *reinterpret_cast<const uint32_t*>(table + (ids.y & 0xffffu));
-                        cell[3] = *reinterpret_cast<const uint32_t*>(table + (ids.y >> 16));
-                    };
-                    uint32_t q = 0, q_looked = 0, q_loaded = 0;
-                    uint2 ids = make_uint2(0, 0);
                     uint32_t cell[4] = {0, 0, 0, 0}, looked[4] = {0, 0, 0, 0};
-                    const uint32_t f0 = (uint32_t)wave;
-                    if (f0 < total) { ids = *locate(f0, q); lookup(ids, cell); }
-                    if (f0 + kWaves < total) ids = *locate(f0 + kWaves, q_loaded);
-                    for (uint32_t f = f0; f < total; f += kWaves) {
-                        if (f + kWaves < total) { lookup(ids, looked); q_looked = q_loaded; }
-                        if (f + 2 * kWaves < total) ids = *locate(f + 2 * kWaves, q_loaded);
-                        uint32_t* bm = sh.bitmap[q];
-                        mark_cells(bm, cell);
+                    if ((uint32_t)wave < rows.total) lookup(ahead[0], cell);
 #pragma unroll
-                        for (int k = 0; k < 4; ++k) cell[k] = looked[k];
-                        q = q_looked;
+                    for (int j = 0; j < kAhead; ++j) {
+                        const uint32_t f = (uint32_t)wave + (uint32_t)j * kWaves;
+                        if (f < rows.total) {
+                            if (j + 1 < kAhead && f + kWaves < rows.total) lookup(ahead[j + 1 < kAhead ? j + 1 : j], looked);
+                            mark_cells(sh.bitmap[ahead_q[j]], cell);
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) cell[k] = looked[k];
+                        }
                     }
+                    for (uint32_t f = (uint32_t)wave + kAhead * kWaves; f < rows.total; f += kWaves) {   // (long rows only)
+                        uint32_t q;
+                        const uint2 ids = *locate(rows, f, q);
+                        lookup(ids, cell);
+                        mark_cells(sh.bitmap[q], cell);
+                    }
+                }
+                if (b0 + kWaves < staged) {
+                    const uint32_t b1 = b0 + kWaves;
+                    rows = rows_of(b1, staged - b1 < (uint32_t)kWaves ? staged - b1 : (uint32_t)kWaves);
+                    fetch_ahead(rows);
                 }
                 __syncthreads();
 
