@@ -829,7 +829,7 @@ extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uin
     prm.offsets = offsets ? offsets : own_offsets;
     prm.peaks = peaks; prm.status = device_status; prm.acc = acc; prm.slabs = slabs; prm.n = n; prm.P = P;
     prm.compact_enqueued = compact ? 1u : 0u;
-    prm.nbr_begin = nbr_begin; prm.nbr = nbr; prm.bitmap_enqueued = bitmap ? 1u : 0u;
+    prm.nbr_begin = nbr_begin; prm.nbr = nbr; prm.bitmap_enqueued = bitmap ? 1u : 0u; prm.bitmap_pool_words = 0;
     bool ok = true;
     if (bitmap) ok = ok && launch_plan_bitmap(prm, di, stream);
     // exactly one of the launches does the work; the trace decides which (see the mode word)

@@ -33,8 +33,8 @@
 
 namespace stalloc {
 
-constexpr int kBmBatch = 256;            // requests fetched per refill
-constexpr int kBmWords = 1056;           // 32704 / 32 words + one word per request of a batch + slack
+constexpr int kBmBatch = 128;            // requests fetched per refill
+constexpr int kBmWords = 1056;           // longest bitmap: 32704 / 32 words + one word per request of a batch + slack
 constexpr int kRowPad = 256;             // index rows are padded to this many entries (4 per lane)
 constexpr int kAhead = 8;                // chunks per wave and batch whose index entries are fetched ahead
 
@@ -56,8 +56,11 @@ struct BitmapLds {
     uint32_t cand[kWaves];               // lowest fit against the blocks placed before the batch
     uint32_t top;                        // extent so far, granules
     uint32_t pad[3];
-    uint32_t bitmap[kWaves][kBmWords];
 };
+// Behind it in LDS: the plan's table of placed blocks (n + 1 words) and the pool the bitmaps of a
+// batch are carved from.  A bitmap is only as long as the plan's extent needs, so the pool
+// holds a full batch of them as long as the extent is moderate, and fewer (smaller batches)
+// beyond that; a pool of kBmWords words always holds one.
 
 // ---------------------------------------------------------------------------------------------
 // Lifetime-conflict index.  begin[i] .. begin[i + 1] are the 256-entry chunks of request i's row;
@@ -234,13 +237,15 @@ __device__ __forceinline__ uint32_t row_scan_add(uint32_t v)
 }
 
 template <int kWaves>
-__global__ void __launch_bounds__(kWaves * kWave, 4) plan_bitmap_kernel(PlanParams prm)
+// (8 waves per SIMD = 64 VGPRs at most: four workgroups of eight waves per CU)
+__global__ void __launch_bounds__(kWaves * kWave, 8) plan_bitmap_kernel(PlanParams prm)
 {
     using Lds = BitmapLds<kWaves>;
     constexpr int kThreads = kWaves * kWave;
     extern __shared__ __align__(16) unsigned char smem[];
     Lds& sh = *reinterpret_cast<Lds*>(smem);
     uint32_t* cells = reinterpret_cast<uint32_t*>(smem + sizeof(Lds));     // [n + 1] placed blocks, see make_cell
+    uint32_t* pool = cells + (prm.n + 1);
     const uint32_t n = prm.n;
 
     if (!index_wanted(prm)) return;
@@ -306,15 +311,23 @@ __global__ void __launch_bounds__(kWaves * kWave, 4) plan_bitmap_kernel(PlanPara
                 cell[2] = *reinterpret_cast<const uint32_t*>(table + (ids.y & 0xffffu));
                 cell[3] = *reinterpret_cast<const uint32_t*>(table + (ids.y >> 16));
             };
-            Rows rows = rows_of(0, staged < (uint32_t)kWaves ? staged : (uint32_t)kWaves);
-            fetch_ahead(rows);
+            Rows rows = {0, 0, 0, 0};
+            uint32_t fetched = 0;                                 // requests `rows` and `ahead` were made for
 
-            for (uint32_t b0 = 0; b0 < staged; b0 += kWaves) {
-                const uint32_t nb = staged - b0 < (uint32_t)kWaves ? staged - b0 : (uint32_t)kWaves;
+            for (uint32_t b0 = 0; b0 < staged;) {
                 const uint32_t top0 = uniform(sh.top);
                 // every block of the plan, this batch included, ends below word `limit`
                 const uint32_t limit = top0 / 32 + kWaves + 2;
-                for (uint32_t w = lane; w < limit; w += kWave) sh.bitmap[wave][w] = 0;
+                const uint32_t stride = limit | 1u;              // bitmap q of the batch: pool + q * stride
+                uint32_t fit = prm.bitmap_pool_words / stride;   // >= 1
+                if (fit > (uint32_t)kWaves) fit = kWaves;
+                const uint32_t nb = staged - b0 < fit ? staged - b0 : fit;
+                if (fetched != nb) {                              // first batch of a refill, or the pool holds fewer now
+                    rows = rows_of(b0, nb);
+                    fetch_ahead(rows);
+                }
+                if ((uint32_t)wave < nb)
+                    for (uint32_t w = lane; w < limit; w += kWave) pool[(uint32_t)wave * stride + w] = 0;
                 __syncthreads();
 
                 // build: table lookups of one chunk are in flight while the previous one is marked
@@ -326,7 +339,7 @@ __global__ void __launch_bounds__(kWaves * kWave, 4) plan_bitmap_kernel(PlanPara
                         const uint32_t f = (uint32_t)wave + (uint32_t)j * kWaves;
                         if (f < rows.total) {
                             if (j + 1 < kAhead && f + kWaves < rows.total) lookup(ahead[j + 1 < kAhead ? j + 1 : j], looked);
-                            mark_cells(sh.bitmap[ahead_q[j]], cell);
+                            mark_cells(pool + ahead_q[j] * stride, cell);
 #pragma unroll
                             for (int k = 0; k < 4; ++k) cell[k] = looked[k];
                         }
@@ -335,19 +348,21 @@ __global__ void __launch_bounds__(kWaves * kWave, 4) plan_bitmap_kernel(PlanPara
                         uint32_t q;
                         const uint2 ids = *locate(rows, f, q);
                         lookup(ids, cell);
-                        mark_cells(sh.bitmap[q], cell);
+                        mark_cells(pool + q * stride, cell);
                     }
                 }
-                if (b0 + kWaves < staged) {
-                    const uint32_t b1 = b0 + kWaves;
-                    rows = rows_of(b1, staged - b1 < (uint32_t)kWaves ? staged - b1 : (uint32_t)kWaves);
+                fetched = 0;
+                if (b0 + nb < staged) {                           // the next batch, if the pool still holds as many then
+                    const uint32_t b1 = b0 + nb;
+                    fetched = staged - b1 < fit ? staged - b1 : fit;
+                    rows = rows_of(b1, fetched);
                     fetch_ahead(rows);
                 }
                 __syncthreads();
 
                 // search: lowest fit of request b0 + wave against everything placed before the batch
                 if ((uint32_t)wave < nb) {
-                    const uint32_t x = first_fit(sh.bitmap[wave], limit, uniform(sh.rq_s[b0 + wave]));
+                    const uint32_t x = first_fit(pool + (uint32_t)wave * stride, limit, uniform(sh.rq_s[b0 + wave]));
                     if (lane == 0) sh.cand[wave] = x;
                 }
                 __syncthreads();
@@ -368,8 +383,8 @@ __global__ void __launch_bounds__(kWaves * kWave, 4) plan_bitmap_kernel(PlanPara
                         uint32_t x = read_lane(my_x, (int)r);
                         const bool rival = lane < (int)r && my_ta < tf && ta < my_tf;
                         if (__builtin_amdgcn_ballot_w64(rival && mine < x + s && x < mine + my_s)) {
-                            if (rival) mark_cell(sh.bitmap[r], make_cell(mine, my_s));
-                            x = first_fit(sh.bitmap[r], limit, s);
+                            if (rival) mark_cell(pool + r * stride, make_cell(mine, my_s));
+                            x = first_fit(pool + r * stride, limit, s);
                         }
                         if (x > kBitmapGranules) x = kBitmapGranules;      // only reachable with a malformed order row
                         if (lane == (int)r) mine = x;
@@ -382,6 +397,7 @@ __global__ void __launch_bounds__(kWaves * kWave, 4) plan_bitmap_kernel(PlanPara
                     if (lane == 0) sh.top = top;
                 }
                 __syncthreads();
+                b0 += nb;
             }
             if (out && threadIdx.x < staged) out[sh.rq_id[threadIdx.x]] = (uint64_t)sh.rq_x[threadIdx.x] << shift;
         }
@@ -390,11 +406,28 @@ __global__ void __launch_bounds__(kWaves * kWave, 4) plan_bitmap_kernel(PlanPara
     }
 }
 
+// Workgroups per CU and words of the bitmap pool for a trace of n requests: as many workgroups
+// as leave each a pool of two longest bitmaps, else as many as leave one.  0 = does not fit.
+static uint32_t bitmap_residency(uint32_t n, const DeviceInfo& di, uint32_t* pool_words)
+{
+    const size_t fixed = sizeof(BitmapLds<kBmWaves>) + ((size_t)n + 1) * sizeof(uint32_t);
+    for (uint32_t need = 2; need >= 1; --need) {
+        for (uint32_t wgs = 4; wgs >= 1; --wgs) {
+            const size_t budget = di.lds_per_block / wgs / 512 * 512;       // LDS is handed out in 512-byte pieces
+            if (budget < fixed + (size_t)need * kBmWords * sizeof(uint32_t)) continue;
+            size_t words = (budget - fixed) / sizeof(uint32_t);
+            if (words > (size_t)kBmWaves * kBmWords) words = (size_t)kBmWaves * kBmWords;
+            *pool_words = (uint32_t)words;
+            return wgs;
+        }
+    }
+    return 0;
+}
+
 bool bitmap_plan_possible(uint32_t n, const DeviceInfo& di)
 {
-    // two workgroups per CU; ids are stored as 4 * j in 16 bits
-    const size_t budget = di.lds_per_block / 2;
-    return n < 16384u && sizeof(BitmapLds<kBmWaves>) + ((size_t)n + 1) * sizeof(uint32_t) <= budget;
+    uint32_t pool_words;
+    return n < 16384u && bitmap_residency(n, di, &pool_words) != 0;         // (requests are stored as 4 * j in 16 bits)
 }
 
 size_t bitmap_index_entries(uint32_t n)
@@ -402,10 +435,13 @@ size_t bitmap_index_entries(uint32_t n)
     return (size_t)n * (((size_t)n - 1 + kRowPad - 1) / kRowPad * kRowPad);
 }
 
-bool launch_plan_bitmap(const PlanParams& prm, const DeviceInfo& di, hipStream_t stream)
+bool launch_plan_bitmap(const PlanParams& params, const DeviceInfo& di, hipStream_t stream)
 {
     auto kernel = &plan_bitmap_kernel<kBmWaves>;
-    const size_t lds = sizeof(BitmapLds<kBmWaves>) + ((size_t)prm.n + 1) * sizeof(uint32_t);
+    PlanParams prm = params;
+    const uint32_t wgs = bitmap_residency(prm.n, di, &prm.bitmap_pool_words);
+    if (wgs == 0) return false;
+    const size_t lds = sizeof(BitmapLds<kBmWaves>) + ((size_t)prm.n + 1 + prm.bitmap_pool_words) * sizeof(uint32_t);
     static bool attr_set[64] = {};
     if (!attr_set[di.device]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -416,7 +452,7 @@ bool launch_plan_bitmap(const PlanParams& prm, const DeviceInfo& di, hipStream_t
     hipLaunchKernelGGL(nbr_count, dim3(prm.n), dim3(256), 0, stream, prm);
     hipLaunchKernelGGL(nbr_scan, dim3(1), dim3(1024), 0, stream, prm);
     hipLaunchKernelGGL(nbr_fill, dim3(prm.n), dim3(256), 0, stream, prm);
-    uint32_t grid = (uint32_t)di.cus * 2;
+    uint32_t grid = (uint32_t)di.cus * wgs;
     if (grid > prm.P) grid = prm.P;
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(kBmWaves * kWave), lds, stream, prm);
     return true;

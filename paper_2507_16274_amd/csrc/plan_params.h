@@ -22,6 +22,7 @@ struct PlanParams {
     uint32_t P;
     uint32_t compact_enqueued;   // the compact 32-bit instantiation is part of this call
     uint32_t bitmap_enqueued;    // the occupancy-bitmap kernel is part of this call
+    uint32_t bitmap_pool_words;  // bitmap variant: LDS words the bitmaps of a batch are carved from
 };
 
 // True when the kernels of the bitmap variant were enqueued for this call: they do the work
