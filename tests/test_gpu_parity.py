@@ -227,6 +227,86 @@ def test_plan_closed_forms(S):
     assert not got["offsets"].any() and int(got["peaks"][0]) == int(size.max())
 
 
+def _layout(S, tr):
+    """How stalloc_plan stores a plan's blocks for this trace (same rule as on the device)."""
+    bits = int(np.bitwise_or.reduce(tr.size))
+    g = bits & -bits
+    return int(S.lib.stalloc_plan_list_layout(len(tr.size), tr.t_end, int(tr.size.sum()) // g, int(tr.size.max()) // g))
+
+
+def _nudge_to_sum(sizes, total, lo, hi, keep=()):
+    """Moves entries (not those in `keep`) one by one within [lo, hi] until the sum is `total`."""
+    sizes = sizes.copy()
+    while int(sizes.sum()) != total:
+        step = 1 if total > int(sizes.sum()) else -1
+        before = int(sizes.sum())
+        for i in range(len(sizes)):
+            if int(sizes.sum()) == total:
+                break
+            if i not in keep and lo <= sizes[i] + step <= hi:
+                sizes[i] += step
+        assert int(sizes.sum()) != before, "cannot reach the requested sum"
+    return sizes
+
+
+def test_plan_bitmap_full_address_range(S):
+    """Occupancy-bitmap variant at its limits: a clique whose extent is the whole 32704-granule
+    range (closed form: prefix sums in placement order), blocks of the longest size allowed."""
+    rng = np.random.default_rng(960)
+    g = 1 << 20
+    sizes = rng.integers(25, 31, 1200)
+    sizes = np.append(sizes[np.cumsum(sizes) <= 32704 - 31], 31)
+    sizes = _nudge_to_sum(sizes, 32704, 1, 31)
+    assert sizes.max() == 31
+    n = len(sizes)
+    size = (sizes * g).astype(np.uint64)
+    clique = _T(size, np.zeros(n, np.uint32), np.full(n, 5, np.uint32), 5)
+    assert _layout(S, clique) & 0x200, "expected the bitmap variant"
+    order = rng.permutation(n).astype(np.uint32)[None, :]
+    got = _gpu_plan(S, clique, order)
+    expect = np.zeros(n, np.uint64)
+    expect[order[0]] = np.concatenate([[0], np.cumsum(size[order[0]])[:-1]]).astype(np.uint64)
+    assert np.array_equal(got["offsets"][0], expect) and int(got["peaks"][0]) == 32704 * g
+
+
+@pytest.mark.parametrize("largest,total", [(31, 32704), (32, 32704), (31, 32705)])
+def test_plan_bitmap_applicability_limits(S, oracle, largest, total):
+    """Just inside and just outside what the bitmap variant takes (size <= 31 granules, sum <= 32704):
+    either way the plans are the oracle's."""
+    rng = np.random.default_rng(961 + largest + total)
+    n = 2500
+    sizes = rng.integers(1, 26, n)
+    sizes[7] = largest
+    sizes = _nudge_to_sum(sizes, total, 1, 30, keep=(7,))
+    assert int(sizes.sum()) == total and sizes.max() == largest
+    _, ts, te, t_end = random_trace(rng, n, t_max=400)
+    tr = _T((sizes * 4096).astype(np.uint64), ts, te, t_end)
+    assert bool(_layout(S, tr) & 0x200) == (largest <= 31 and total <= 32704)
+    orders = np.stack([rng.permutation(n) for _ in range(5)]).astype(np.uint32)
+    orders[0] = np.argsort(-sizes, kind="stable")
+    _compare_plans(S, oracle, tr, orders, method="allpairs")
+
+
+def test_plan_bitmap_tall_plans_small_pool(S, oracle):
+    """Many requests (the per-plan table leaves little LDS for bitmaps) and extents that grow to
+    ~30000 granules: the batches shrink as the bitmaps get longer."""
+    rng = np.random.default_rng(962)
+    n = 8500
+    sizes = rng.integers(1, 7, n)
+    sizes[rng.choice(n, 20, replace=False)] = 31
+    assert int(sizes.sum()) <= 32704
+    ts = rng.integers(0, 50, n)
+    te = ts + rng.integers(150, 200, n)
+    short = rng.random(n) < 0.2                         # a fifth lives briefly: holes open up under the rest
+    te[short] = ts[short] + rng.integers(1, 4, int(short.sum()))
+    tr = _T((sizes * 65536).astype(np.uint64), ts.astype(np.uint32), te.astype(np.uint32), int(te.max()))
+    assert _layout(S, tr) & 0x200, "expected the bitmap variant"
+    orders = np.stack([rng.permutation(n) for _ in range(3)]).astype(np.uint32)
+    orders[0] = np.argsort(-sizes, kind="stable")
+    got, a, ext = _compare_plans(S, oracle, tr, orders, method="allpairs")
+    assert int(ext.max()) // 65536 > 20000
+
+
 def test_plan_large_list_in_workspace(S, oracle):
     """Config 3 does not fit the LDS-resident list: sampled orders, every address compared."""
     tr = make_trace(3)
