@@ -114,24 +114,61 @@ __global__ void __launch_bounds__(1024) nbr_scan(PlanParams prm)
     if (threadIdx.x == 1023) prm.nbr_begin[n] = part[1023];
 }
 
+// Fills row i.  The order of a row's entries is free (the bitmap is an OR over the row), so it is
+// chosen for the table lookups of the build phase: one lookup instruction reads the table cells
+// of 64 consecutive entries of this order, and LDS serves them fastest when they lie in different
+// banks (cell j is in bank j mod 32).  Entries are ordered by (rank, bank), rank = how many
+// entries of the same bank come before: any 64 in a row then hold every bank about twice.
+// Within a chunk of 256, entry e belongs to lane e / 4 and lookup e mod 4, hence the transposition.
 __global__ void __launch_bounds__(256) nbr_fill(PlanParams prm)
 {
-    __shared__ uint32_t cursor;
+    constexpr uint32_t kMaxRank = 16384 / 32;           // n < 16384
+    __shared__ uint32_t per_thread[256];
+    __shared__ uint32_t in_bank[32];
+    __shared__ uint32_t before_rank[kMaxRank + 1];      // entries with a lower rank
+    __shared__ uint32_t banks_at_rank[kMaxRank + 1];    // banks that have an entry of this rank
     if (!index_wanted(prm)) return;
-    const uint32_t i = blockIdx.x, n = prm.n;
-    if (threadIdx.x == 0) cursor = 0;
-    __syncthreads();
+    const uint32_t i = blockIdx.x, n = prm.n, t = threadIdx.x;
+    const uint32_t bank = t & 31u;                      // thread t sees j = t, t + 256, ...: all in one bank
     const uint32_t ta = prm.ta[i], tf = prm.tf[i];
-    uint16_t* row = prm.nbr + (size_t)prm.nbr_begin[i] * kRowPad;
-    const uint32_t room = (prm.nbr_begin[i + 1] - prm.nbr_begin[i]) * kRowPad;
-    for (uint32_t j = threadIdx.x; j < n; j += 256) {
-        if (j != i && prm.ta[j] < tf && ta < prm.tf[j]) {
-            const uint32_t pos = atomicAdd(&cursor, 1u);      // any order: the bitmap is an OR over the row
-            if (pos < room) row[pos] = (uint16_t)(4 * j);
+    uint32_t mine = 0;
+    for (uint32_t j = t; j < n; j += 256) mine += (j != i && prm.ta[j] < tf && ta < prm.tf[j]);
+    per_thread[t] = mine;
+    __syncthreads();
+    uint32_t rank = 0, total = 0;                       // of the 8 threads of a bank, the lower ones come first
+    for (uint32_t m = 0; m < 8; ++m) {
+        const uint32_t c = per_thread[bank + 32 * m];
+        if (m < (t >> 5)) rank += c;
+        total += c;
+    }
+    if (t < 32) in_bank[t] = total;
+    __syncthreads();
+    for (uint32_t r = t; r <= kMaxRank; r += 256) {
+        uint32_t before = 0, banks = 0;
+        for (uint32_t b = 0; b < 32; ++b) {
+            const uint32_t c = in_bank[b];
+            before += c < r ? c : r;
+            banks |= (c > r ? 1u : 0u) << b;
         }
+        before_rank[r] = before;
+        banks_at_rank[r] = banks;
     }
     __syncthreads();
-    for (uint32_t pos = cursor + threadIdx.x; pos < room; pos += 256) row[pos] = (uint16_t)(4 * n);
+    uint16_t* row = prm.nbr + (size_t)prm.nbr_begin[i] * kRowPad;
+    const uint32_t room = (prm.nbr_begin[i + 1] - prm.nbr_begin[i]) * kRowPad;
+    auto slot = [](uint32_t pos) {                      // position in the order -> entry of the row
+        const uint32_t p = pos % kRowPad;
+        return pos - p + 4 * (p % kWave) + p / kWave;
+    };
+    for (uint32_t j = t; j < n; j += 256) {
+        if (j != i && prm.ta[j] < tf && ta < prm.tf[j]) {
+            const uint32_t pos = before_rank[rank] + (uint32_t)__builtin_popcount(banks_at_rank[rank] & ((1u << bank) - 1u));
+            if (pos < room) row[slot(pos)] = (uint16_t)(4 * j);
+            ++rank;
+        }
+    }
+    const uint32_t filled = before_rank[kMaxRank];      // = number of entries
+    for (uint32_t pos = filled + t; pos < room; pos += 256) row[slot(pos)] = (uint16_t)(4 * n);
 }
 
 // ---------------------------------------------------------------------------------------------
