@@ -10,10 +10,12 @@ The headline value is placed requests x plans per second, n * P * steps / time.
 
 Prints ONE JSON line.  `roofline` describes the dominant kernel (the placement
 kernel).  Algorithmic work per launch: 28 B of HBM per placement (order entry,
-request record, address written); one stored list entry and 8 integer lane
+request record, address written); one stored block record and 8 integer lane
 operations per lifetime-overlapping pair and plan.  The floor that takes longest
-at the chip's peak names the bound; achieved = that work / kernel time measured
-with events on the launch stream.
+at the chip's peak names the bound; achieved = that work / time of the
+stalloc_plan call measured with events on the launch stream (the placement kernel
+is 98 % of it).  `traffic` holds HBM-side bytes per launch from rocprofv3 counter
+runs of this very workload and build (null for any other workload).
 `cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload on
 this machine's host cores.
 """
@@ -36,6 +38,12 @@ OPS_PER_CANDIDATE = 8       # 2 lifetime compares, and, select, running max, add
 LDS_PEAK_GBS = 256 * 128 * 2.4          # 256 CUs x 128 B/clk x 2.4 GHz = 78 643 GB/s
 HBM_PEAK_GBS = 8000.0
 ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12  # 256 CUs x 64 integer lanes x 2.4 GHz = 39.3 T lane-ops/s
+
+# HBM-side bytes per launch of the placement kernel, from two rocprofv3 --pmc runs of this
+# script (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, KiB, factors from a 256 MiB copy in the same
+# runs).  Keyed by (configuration, orders, layout code); valid for the kernels as committed
+# with these figures only.
+MEASURED_TRAFFIC = {(2, 1024, 0x304): (6_991_690 * 2 + 190_754) * 1024}
 
 
 def main() -> int:
@@ -141,6 +149,7 @@ def main() -> int:
               "lds" if in_lds else "hbm_list": state_bytes / ((LDS_PEAK_GBS if in_lds else HBM_PEAK_GBS) * 1e9),
               "alu": algo_ops / (ALU_PEAK_TOPS * 1e12)}
     bound = max(floors, key=floors.get)
+    kernel = "plan_bitmap_kernel" if layout & 0x200 else "plan_kernel"
     result = {
         "metric": "placed requests x plans / s",
         "value": value,
@@ -160,18 +169,18 @@ def main() -> int:
         "quality": {"lower_bound": lower_bound, "best_peak": best_peak, "best_plan": best,
                     "lower_bound_over_peak": lower_bound / best_peak,
                     "median_lower_bound_over_peak": float(lower_bound / np.median(peaks.astype(np.float64)))},
-        "roofline": ({"bound": "alu", "kernel": "plan_kernel", "achieved": algo_ops / t_s / 1e12,
+        "roofline": ({"bound": "alu", "kernel": kernel, "achieved": algo_ops / t_s / 1e12,
                       "peak": ALU_PEAK_TOPS, "unit": "TOP/s", "frac": algo_ops / t_s / 1e12 / ALU_PEAK_TOPS}
                      if bound == "alu" else
-                     {"bound": "hbm", "kernel": "plan_kernel", "achieved": (hbm_bytes + state_bytes) / t_s / 1e9,
+                     {"bound": "hbm", "kernel": kernel, "achieved": (hbm_bytes + state_bytes) / t_s / 1e9,
                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": (hbm_bytes + state_bytes) / t_s / 1e9 / HBM_PEAK_GBS}
                      if not in_lds else
-                     {"bound": "lds", "kernel": "plan_kernel", "achieved": state_bytes / t_s / 1e9,
+                     {"bound": "lds", "kernel": kernel, "achieved": state_bytes / t_s / 1e9,
                       "peak": LDS_PEAK_GBS, "unit": "GB/s", "frac": state_bytes / t_s / 1e9 / LDS_PEAK_GBS}),
     }
 
     result["roofline"].update({
-        "traffic": None, "kernel_ms": plan_ms, "list_entry_bytes": entry_bytes, "list_in_lds": in_lds,
+        "traffic": MEASURED_TRAFFIC.get((args.config, P, layout)), "kernel_ms": plan_ms, "list_entry_bytes": entry_bytes, "list_in_lds": in_lds,
         "algorithmic_ops": algo_ops, "algorithmic_list_bytes": state_bytes, "algorithmic_hbm_bytes": hbm_bytes,
         "floor_ms": {k: v * 1e3 for k, v in floors.items()},
         "hbm_stream_GBs": hbm_bytes / t_s / 1e9,

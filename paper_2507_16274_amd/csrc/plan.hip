@@ -605,7 +605,7 @@ __global__ void __launch_bounds__(kThreads, 4) plan_kernel(PlanParams prm)   // 
 
     if (*prm.status != STALLOC_OK) return;               // malformed trace: nothing to plan
     const uint64_t mode = prm.acc[kAccMode];
-    if (prm.bitmap_enqueued && (mode & kModeBitmap)) return;   // the occupancy-bitmap kernel handles this trace
+    if (bitmap_shape(mode, prm.acc[kAccGranules], prm.bitmap_pool_words) >= 0) return;   // the occupancy-bitmap kernel places this trace
     const bool narrow = (mode & kModeNarrow) != 0;
     if (narrow != (sizeof(Addr) == 4)) return;            // another instantiation handles this trace
     // of the two 32-bit instantiations the compact one runs when it was enqueued and applies
@@ -777,7 +777,9 @@ extern "C" uint32_t stalloc_plan_list_layout(uint32_t n, uint32_t t_end, uint64_
 {
     DeviceInfo di;
     if (!device_info(&di)) return 0;
-    if (granules <= kBitmapGranules && largest <= kBitmapMaxSize && bitmap_plan_possible(n, di))
+    uint32_t pool_words[kBitmapShapes];
+    if (granules <= kBitmapGranules && largest <= kBitmapMaxSize && bitmap_plan_shapes(n, di, pool_words) &&
+        bitmap_shape(kModeBitmap, granules, pool_words) >= 0)
         return (uint32_t)sizeof(uint32_t) | 0x300u;
     if (granules < (1ull << 16) && t_end < 0x10000u &&
         n <= lds_capacity_entries<uint32_t, kThreadsCompact>(di.lds_per_block / 2, sizeof(uint2)))
@@ -813,7 +815,8 @@ extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uin
     uint64_t* own_offsets = (!offsets && best_offsets) ? cv.take<uint64_t>((size_t)P * n) : nullptr;
     unsigned char* slabs = lds64 ? nullptr : cv.take<unsigned char>((size_t)grid_mem * 2 * n * entry_bytes<uint64_t>());
     // occupancy-bitmap variant: lifetime-conflict index of the trace
-    const bool bitmap = bitmap_plan_possible(n, di);
+    uint32_t pool_words[kBitmapShapes];
+    const bool bitmap = bitmap_plan_shapes(n, di, pool_words);
     uint32_t* nbr_begin = bitmap ? cv.take<uint32_t>((size_t)n + 2) : nullptr;
     uint16_t* nbr = bitmap ? cv.take<uint16_t>(bitmap_index_entries(n)) : nullptr;
     if (!workspace) { *workspace_bytes = cv.used; return STALLOC_OK; }
@@ -829,7 +832,8 @@ extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uin
     prm.offsets = offsets ? offsets : own_offsets;
     prm.peaks = peaks; prm.status = device_status; prm.acc = acc; prm.slabs = slabs; prm.n = n; prm.P = P;
     prm.compact_enqueued = compact ? 1u : 0u;
-    prm.nbr_begin = nbr_begin; prm.nbr = nbr; prm.bitmap_enqueued = bitmap ? 1u : 0u; prm.bitmap_pool_words = 0;
+    prm.nbr_begin = nbr_begin; prm.nbr = nbr; 
+    for (int shape = 0; shape < kBitmapShapes; ++shape) prm.bitmap_pool_words[shape] = bitmap ? pool_words[shape] : 0u;
     bool ok = true;
     if (bitmap) ok = ok && launch_plan_bitmap(prm, di, stream);
     // exactly one of the launches does the work; the trace decides which (see the mode word)

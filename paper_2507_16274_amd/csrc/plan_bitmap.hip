@@ -4,9 +4,9 @@
 // traces whose whole address range is small when counted in granules.
 //
 // With g the largest power of two dividing all sizes, every address is a multiple of g and lies
-// below the sum of sizes.  When that sum is at most 32704 granules and no request is longer than
-// 31 granules, "which addresses are blocked for request r" fits a bitmap of one bit per granule
-// that a single wave can hold in LDS and search in a few steps:
+// below the sum of sizes.  When no request is longer than 31 granules and a bitmap of one bit per
+// granule of that whole range fits the LDS left over by the plan's table of placed blocks, "which
+// addresses are blocked for request r" is such a bitmap, which a single wave searches in a few steps:
 //
 //   index    Once per call: for every request the list of requests whose lifetime overlaps its
 //            own (the potential conflicts of Sec. 5.1 do not depend on the order), rows padded
@@ -34,15 +34,10 @@
 namespace stalloc {
 
 constexpr int kBmBatch = 128;            // requests fetched per refill
-constexpr int kBmWords = 1056;           // longest bitmap: 32704 / 32 words + one word per request of a batch + slack
+constexpr int kBmWords = 1056;           // a pool of twice this many words is asked for before workgroups share a CU
 constexpr int kRowPad = 256;             // index rows are padded to this many entries (4 per lane)
-constexpr int kAhead = 8;                // chunks per wave and batch whose index entries are fetched ahead
 
-#ifndef STALLOC_BITMAP_WAVES
-#define STALLOC_BITMAP_WAVES 8
-#endif
-constexpr int kBmWaves = STALLOC_BITMAP_WAVES;     // waves per workgroup = requests per batch
-static_assert(kBmWaves >= 1 && kBmWaves <= 16, "bitmap slack covers at most 16 requests per batch");
+constexpr uint32_t kBmMaxRequests = 32768;         // index entries are 16-bit request numbers; the index has n^2 of them at worst
 
 template <int kWaves>
 struct BitmapLds {
@@ -64,12 +59,13 @@ struct BitmapLds {
 
 // ---------------------------------------------------------------------------------------------
 // Lifetime-conflict index.  begin[i] .. begin[i + 1] are the 256-entry chunks of request i's row;
-// an entry is 4 * j for a request j != i with t_alloc_j < t_free_i and t_alloc_i < t_free_j, or
-// 4 * n (the dummy).  begin[] first holds the degrees, then their exclusive prefix sum in chunks.
+// an entry is j for a request j != i with t_alloc_j < t_free_i and t_alloc_i < t_free_j, or n (a
+// dummy that is never placed).  begin[] first holds the degrees, then their exclusive prefix sum
+// in chunks.
 
 __device__ __forceinline__ bool index_wanted(const PlanParams& prm)
 {
-    return *prm.status == STALLOC_OK && (prm.acc[kAccMode] & kModeBitmap) != 0;
+    return *prm.status == STALLOC_OK && bitmap_shape(prm.acc[kAccMode], prm.acc[kAccGranules], prm.bitmap_pool_words) >= 0;
 }
 
 __global__ void __launch_bounds__(256) nbr_count(PlanParams prm)
@@ -122,7 +118,7 @@ __global__ void __launch_bounds__(1024) nbr_scan(PlanParams prm)
 // Within a chunk of 256, entry e belongs to lane e / 4 and lookup e mod 4, hence the transposition.
 __global__ void __launch_bounds__(256) nbr_fill(PlanParams prm)
 {
-    constexpr uint32_t kMaxRank = 16384 / 32;           // n < 16384
+    constexpr uint32_t kMaxRank = kBmMaxRequests / 32;
     __shared__ uint32_t per_thread[256];
     __shared__ uint32_t in_bank[32];
     __shared__ uint32_t before_rank[kMaxRank + 1];      // entries with a lower rank
@@ -163,25 +159,26 @@ __global__ void __launch_bounds__(256) nbr_fill(PlanParams prm)
     for (uint32_t j = t; j < n; j += 256) {
         if (j != i && prm.ta[j] < tf && ta < prm.tf[j]) {
             const uint32_t pos = before_rank[rank] + (uint32_t)__builtin_popcount(banks_at_rank[rank] & ((1u << bank) - 1u));
-            if (pos < room) row[slot(pos)] = (uint16_t)(4 * j);
+            if (pos < room) row[slot(pos)] = (uint16_t)j;
             ++rank;
         }
     }
     const uint32_t filled = before_rank[kMaxRank];      // = number of entries
-    for (uint32_t pos = filled + t; pos < room; pos += 256) row[slot(pos)] = (uint16_t)(4 * n);
+    for (uint32_t pos = filled + t; pos < room; pos += 256) row[slot(pos)] = (uint16_t)n;
 }
 
 // ---------------------------------------------------------------------------------------------
 
 __device__ __forceinline__ uint32_t uniform(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
 
-// A placed block as the build phase wants it: bits 0-14 address in granules (bits 0-4 = first bit
-// b in its first word, bits 5-15 = that word), bits 16-20 size in granules (1..31), bits 24-28 the
+// A placed block as the build phase wants it: bits 0-21 address in granules (bits 0-4 = first bit
+// b in its first word, bits 5-21 = that word), bits 22-26 size in granules (1..31), bits 27-31 the
 // number of granules that spill into the next word.  0 = not placed.
+constexpr uint32_t kCellSizeAt = 22, kCellSpillAt = 27;
 __device__ __forceinline__ uint32_t make_cell(uint32_t x, uint32_t sz)
 {
     const uint32_t reach = (x & 31) + sz;
-    return x | (sz << 16) | ((reach > 32 ? reach - 32 : 0u) << 24);
+    return x | (sz << kCellSizeAt) | ((reach > 32 ? reach - 32 : 0u) << kCellSpillAt);
 }
 
 // ((1 << width) - 1) << offset with both taken modulo 32.
@@ -199,7 +196,7 @@ __device__ __forceinline__ lds_word* first_word(uint32_t* bm, uint32_t cell)
 {
     const uint32_t base = (uint32_t)reinterpret_cast<uintptr_t>((lds_word*)bm);
     uint32_t at;
-    asm("v_bfe_u32 %0, %1, 5, 11\n\tv_lshl_add_u32 %0, %0, 2, %2" : "=&v"(at) : "v"(cell), "s"(base));
+    asm("v_bfe_u32 %0, %1, 5, 17\n\tv_lshl_add_u32 %0, %0, 2, %2" : "=&v"(at) : "v"(cell), "s"(base));
     return reinterpret_cast<lds_word*>((uintptr_t)at);
 }
 
@@ -207,10 +204,10 @@ __device__ __forceinline__ lds_word* first_word(uint32_t* bm, uint32_t cell)
 __device__ __forceinline__ void mark_cell(uint32_t* bm, uint32_t cell)
 {
     lds_word* word = first_word(bm, cell);
-    const uint32_t first = bit_field_mask(cell >> 16, cell);          // ((1 << size) - 1) << b, low 32 bits
-    const uint32_t spill = bit_field_mask(cell >> 24, 0u);            // (1 << spilled) - 1
+    const uint32_t first = bit_field_mask(cell >> kCellSizeAt, cell);      // ((1 << size) - 1) << b, low 32 bits
+    const uint32_t spill = bit_field_mask(cell >> kCellSpillAt, 0u);       // (1 << spilled) - 1
     if (cell) __hip_atomic_fetch_or(word, first, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    if (cell >= (1u << 24)) __hip_atomic_fetch_or(word + 1, spill, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    if (cell >= (1u << kCellSpillAt)) __hip_atomic_fetch_or(word + 1, spill, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
 // The same for four cells per lane, looking before ORing.  Blocks that are alive at different
@@ -227,15 +224,15 @@ __device__ __forceinline__ void mark_cells(uint32_t* bm, const uint32_t (&cell)[
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         word[k] = first_word(bm, cell[k]);
-        first[k] = bit_field_mask(cell[k] >> 16, cell[k]);
-        spill[k] = bit_field_mask(cell[k] >> 24, 0u);
+        first[k] = bit_field_mask(cell[k] >> kCellSizeAt, cell[k]);
+        spill[k] = bit_field_mask(cell[k] >> kCellSpillAt, 0u);
     }
 #pragma unroll
     for (int k = 0; k < 4; ++k) seen[k] = *word[k];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         if (first[k] & ~seen[k]) __hip_atomic_fetch_or(word[k], first[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        if (cell[k] >= (1u << 24)) __hip_atomic_fetch_or(word[k] + 1, spill[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (cell[k] >= (1u << kCellSpillAt)) __hip_atomic_fetch_or(word[k] + 1, spill[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
 }
 
@@ -273,20 +270,28 @@ __device__ __forceinline__ uint32_t row_scan_add(uint32_t v)
     return v;
 }
 
+// (eight-wave shape: 8 waves per SIMD = 64 VGPRs at most, so that four workgroups share a CU)
 template <int kWaves>
-// (8 waves per SIMD = 64 VGPRs at most: four workgroups of eight waves per CU)
-__global__ void __launch_bounds__(kWaves * kWave, 8) plan_bitmap_kernel(PlanParams prm)
+__global__ void __launch_bounds__(kWaves * kWave, kWaves == 8 ? 8 : 4) plan_bitmap_kernel(PlanParams prm)
 {
     using Lds = BitmapLds<kWaves>;
     constexpr int kThreads = kWaves * kWave;
+    constexpr int kShape = kWaves == 8 ? 0 : 1;
+    constexpr int kAhead = kWaves == 8 ? 8 : 12;      // chunks per wave and batch whose index entries are fetched ahead
+    static_assert(bitmap_shape_waves(kShape) == (uint32_t)kWaves, "shape table and instantiation disagree");
     extern __shared__ __align__(16) unsigned char smem[];
     Lds& sh = *reinterpret_cast<Lds*>(smem);
     uint32_t* cells = reinterpret_cast<uint32_t*>(smem + sizeof(Lds));     // [n + 1] placed blocks, see make_cell
     uint32_t* pool = cells + (prm.n + 1);
     const uint32_t n = prm.n;
 
-    if (!index_wanted(prm)) return;
+    if (*prm.status != STALLOC_OK) return;
+    if (bitmap_shape(prm.acc[kAccMode], prm.acc[kAccGranules], prm.bitmap_pool_words) != kShape) return;
     const uint32_t shift = (uint32_t)(prm.acc[kAccMode] & 63);
+    const uint32_t pool_words = prm.bitmap_pool_words[kShape];
+    // the rule above keeps every address of a well-formed plan at or below this; a malformed order
+    // row (repeated requests) is clamped to it so that a bitmap never outgrows the pool
+    const uint32_t highest = 32u * (pool_words - kWaves - 5) + 31u;
     const int lane = lane_id(), wave = (int)uniform((uint32_t)wave_id());
     const uint2* index = reinterpret_cast<const uint2*>(prm.nbr) + lane;   // a chunk: 64 lanes x 4 entries
 
@@ -341,12 +346,11 @@ __global__ void __launch_bounds__(kWaves * kWave, 8) plan_bitmap_kernel(PlanPara
                     if (f < r.total) ahead[j] = *locate(r, f, ahead_q[j]);
                 }
             };
-            const unsigned char* table = reinterpret_cast<const unsigned char*>(cells);
             auto lookup = [&](const uint2& ids, uint32_t (&cell)[4]) {
-                cell[0] = *reinterpret_cast<const uint32_t*>(table + (ids.x & 0xffffu));
-                cell[1] = *reinterpret_cast<const uint32_t*>(table + (ids.x >> 16));
-                cell[2] = *reinterpret_cast<const uint32_t*>(table + (ids.y & 0xffffu));
-                cell[3] = *reinterpret_cast<const uint32_t*>(table + (ids.y >> 16));
+                cell[0] = cells[ids.x & 0xffffu];
+                cell[1] = cells[ids.x >> 16];
+                cell[2] = cells[ids.y & 0xffffu];
+                cell[3] = cells[ids.y >> 16];
             };
             Rows rows = {0, 0, 0, 0};
             uint32_t fetched = 0;                                 // requests `rows` and `ahead` were made for
@@ -356,7 +360,7 @@ __global__ void __launch_bounds__(kWaves * kWave, 8) plan_bitmap_kernel(PlanPara
                 // every block of the plan, this batch included, ends below word `limit`
                 const uint32_t limit = top0 / 32 + kWaves + 2;
                 const uint32_t stride = limit | 1u;              // bitmap q of the batch: pool + q * stride
-                uint32_t fit = prm.bitmap_pool_words / stride;   // >= 1
+                uint32_t fit = pool_words / stride;               // >= 1
                 if (fit > (uint32_t)kWaves) fit = kWaves;
                 const uint32_t nb = staged - b0 < fit ? staged - b0 : fit;
                 if (fetched != nb) {                              // first batch of a refill, or the pool holds fewer now
@@ -423,7 +427,7 @@ __global__ void __launch_bounds__(kWaves * kWave, 8) plan_bitmap_kernel(PlanPara
                             if (rival) mark_cell(pool + r * stride, make_cell(mine, my_s));
                             x = first_fit(pool + r * stride, limit, s);
                         }
-                        if (x > kBitmapGranules) x = kBitmapGranules;      // only reachable with a malformed order row
+                        if (x > highest) x = highest;                      // only reachable with a malformed order row
                         if (lane == (int)r) mine = x;
                         top = umax(top, x + s);
                     }
@@ -443,28 +447,29 @@ __global__ void __launch_bounds__(kWaves * kWave, 8) plan_bitmap_kernel(PlanPara
     }
 }
 
-// Workgroups per CU and words of the bitmap pool for a trace of n requests: as many workgroups
-// as leave each a pool of two longest bitmaps, else as many as leave one.  0 = does not fit.
-static uint32_t bitmap_residency(uint32_t n, const DeviceInfo& di, uint32_t* pool_words)
+// Workgroups per CU of the eight-wave shape for a trace of n requests, and the words of its
+// bitmap pool: as many workgroups as leave each a pool of 2 * kBmWords words.  0 = none.
+static uint32_t shared_cu_residency(uint32_t n, const DeviceInfo& di, uint32_t* pool_words)
 {
-    const size_t fixed = sizeof(BitmapLds<kBmWaves>) + ((size_t)n + 1) * sizeof(uint32_t);
-    for (uint32_t need = 2; need >= 1; --need) {
-        for (uint32_t wgs = 4; wgs >= 1; --wgs) {
-            const size_t budget = di.lds_per_block / wgs / 512 * 512;       // LDS is handed out in 512-byte pieces
-            if (budget < fixed + (size_t)need * kBmWords * sizeof(uint32_t)) continue;
-            size_t words = (budget - fixed) / sizeof(uint32_t);
-            if (words > (size_t)kBmWaves * kBmWords) words = (size_t)kBmWaves * kBmWords;
-            *pool_words = (uint32_t)words;
-            return wgs;
-        }
+    const size_t fixed = sizeof(BitmapLds<8>) + ((size_t)n + 1) * sizeof(uint32_t);
+    for (uint32_t wgs = 4; wgs >= 2; --wgs) {
+        const size_t budget = di.lds_per_block / wgs / 512 * 512;       // LDS is handed out in 512-byte pieces
+        if (budget < fixed + 2 * (size_t)kBmWords * sizeof(uint32_t)) continue;
+        *pool_words = (uint32_t)((budget - fixed) / sizeof(uint32_t));
+        return wgs;
     }
     return 0;
 }
 
-bool bitmap_plan_possible(uint32_t n, const DeviceInfo& di)
+bool bitmap_plan_shapes(uint32_t n, const DeviceInfo& di, uint32_t (&pool_words)[kBitmapShapes])
 {
-    uint32_t pool_words;
-    return n < 16384u && bitmap_residency(n, di, &pool_words) != 0;         // (requests are stored as 4 * j in 16 bits)
+    pool_words[0] = pool_words[1] = 0;
+    if (n > kBmMaxRequests) return false;
+    shared_cu_residency(n, di, &pool_words[0]);
+    const size_t fixed = sizeof(BitmapLds<16>) + ((size_t)n + 1) * sizeof(uint32_t);
+    if (di.lds_per_block >= fixed + (size_t)kBmWords * sizeof(uint32_t))
+        pool_words[1] = (uint32_t)((di.lds_per_block - fixed) / sizeof(uint32_t));
+    return pool_words[0] != 0 || pool_words[1] != 0;
 }
 
 size_t bitmap_index_entries(uint32_t n)
@@ -472,13 +477,12 @@ size_t bitmap_index_entries(uint32_t n)
     return (size_t)n * (((size_t)n - 1 + kRowPad - 1) / kRowPad * kRowPad);
 }
 
-bool launch_plan_bitmap(const PlanParams& params, const DeviceInfo& di, hipStream_t stream)
+template <int kWaves>
+static bool launch_shape(const PlanParams& prm, uint32_t wgs_per_cu, uint32_t pool_words, const DeviceInfo& di,
+                         hipStream_t stream)
 {
-    auto kernel = &plan_bitmap_kernel<kBmWaves>;
-    PlanParams prm = params;
-    const uint32_t wgs = bitmap_residency(prm.n, di, &prm.bitmap_pool_words);
-    if (wgs == 0) return false;
-    const size_t lds = sizeof(BitmapLds<kBmWaves>) + ((size_t)prm.n + 1 + prm.bitmap_pool_words) * sizeof(uint32_t);
+    auto kernel = &plan_bitmap_kernel<kWaves>;
+    const size_t lds = sizeof(BitmapLds<kWaves>) + ((size_t)prm.n + 1 + pool_words) * sizeof(uint32_t);
     static bool attr_set[64] = {};
     if (!attr_set[di.device]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -486,13 +490,26 @@ bool launch_plan_bitmap(const PlanParams& params, const DeviceInfo& di, hipStrea
             return false;
         attr_set[di.device] = true;
     }
+    uint32_t grid = (uint32_t)di.cus * wgs_per_cu;
+    if (grid > prm.P) grid = prm.P;
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kWaves * kWave), lds, stream, prm);
+    return true;
+}
+
+// Enqueues the index build and every shape of the placement kernel that prm.bitmap_pool_words names.
+bool launch_plan_bitmap(const PlanParams& prm, const DeviceInfo& di, hipStream_t stream)
+{
     hipLaunchKernelGGL(nbr_count, dim3(prm.n), dim3(256), 0, stream, prm);
     hipLaunchKernelGGL(nbr_scan, dim3(1), dim3(1024), 0, stream, prm);
     hipLaunchKernelGGL(nbr_fill, dim3(prm.n), dim3(256), 0, stream, prm);
-    uint32_t grid = (uint32_t)di.cus * wgs;
-    if (grid > prm.P) grid = prm.P;
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kBmWaves * kWave), lds, stream, prm);
-    return true;
+    bool ok = true;
+    if (prm.bitmap_pool_words[0]) {
+        uint32_t pool_words = 0;
+        const uint32_t wgs = shared_cu_residency(prm.n, di, &pool_words);
+        ok = ok && wgs != 0 && pool_words == prm.bitmap_pool_words[0] && launch_shape<8>(prm, wgs, pool_words, di, stream);
+    }
+    if (prm.bitmap_pool_words[1]) ok = ok && launch_shape<16>(prm, 1, prm.bitmap_pool_words[1], di, stream);
+    return ok;
 }
 
 }  // namespace stalloc

@@ -16,18 +16,34 @@ struct PlanParams {
     uint32_t* status;
     const uint64_t* acc;     // trace-check accumulators (mode word)
     unsigned char* slabs;    // list in the workspace: gridDim.x slabs of 2 * n entries
-    uint32_t* nbr_begin;     // bitmap variant: [n + 2] row starts of the lifetime-conflict index (+ a cursor)
-    uint16_t* nbr;           // bitmap variant: 4 * (index of a request with an overlapping lifetime)
+    uint32_t* nbr_begin;     // bitmap variant: [n + 2] row starts of the lifetime-conflict index
+    uint16_t* nbr;           // bitmap variant: indices of the requests with an overlapping lifetime, row by row
     uint32_t n;
     uint32_t P;
     uint32_t compact_enqueued;   // the compact 32-bit instantiation is part of this call
-    uint32_t bitmap_enqueued;    // the occupancy-bitmap kernel is part of this call
-    uint32_t bitmap_pool_words;  // bitmap variant: LDS words the bitmaps of a batch are carved from
+    // The occupancy-bitmap kernel is enqueued in up to two shapes: [0] eight waves per workgroup,
+    // several workgroups per CU; [1] sixteen waves, one workgroup per CU (all of the LDS).  Per
+    // shape: the LDS words its bitmaps are carved from, 0 = not part of this call.
+    uint32_t bitmap_pool_words[2];
 };
 
-// True when the kernels of the bitmap variant were enqueued for this call: they do the work
-// (and the sorted-list kernels return at once) when the trace's mode word has kModeBitmap.
-bool bitmap_plan_possible(uint32_t n, const DeviceInfo& di);
+constexpr int kBitmapShapes = 2;
+__host__ __device__ constexpr uint32_t bitmap_shape_waves(int shape) { return shape == 0 ? 8u : 16u; }
+
+// Which shape of the bitmap kernel places a trace with this mode word and sum of sizes in
+// granules (-1: none, the sorted-list kernels do).  A bitmap must be able to hold the whole
+// address range plus one word per request of a batch and a little slack.  Every kernel of a
+// call evaluates this same rule, so exactly one of them does the work.
+__host__ __device__ inline int bitmap_shape(uint64_t mode, uint64_t granules, const uint32_t (&pool_words)[kBitmapShapes])
+{
+    if (!(mode & kModeBitmap)) return -1;
+    for (int shape = 0; shape < kBitmapShapes; ++shape)
+        if (pool_words[shape] != 0 && granules / 32 + bitmap_shape_waves(shape) + 5 <= pool_words[shape]) return shape;
+    return -1;
+}
+
+// Fills PlanParams::bitmap_pool_words for a trace of n requests; false if no shape fits.
+bool bitmap_plan_shapes(uint32_t n, const DeviceInfo& di, uint32_t (&pool_words)[kBitmapShapes]);
 size_t bitmap_index_entries(uint32_t n);             // uint16_t entries of PlanParams::nbr
 bool launch_plan_bitmap(const PlanParams& prm, const DeviceInfo& di, hipStream_t stream);
 

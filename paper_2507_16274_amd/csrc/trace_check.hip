@@ -58,6 +58,7 @@ __global__ void trace_check_finish(uint64_t* acc, uint32_t* status)
         const uint64_t bitmap = (total >> shift) <= kBitmapGranules && (acc[kAccMaxSize] >> shift) <= kBitmapMaxSize
                                     ? kModeBitmap : 0;
         acc[kAccMode] = shift | narrow | compact | bitmap;
+        acc[kAccGranules] = total >> shift;
     }
     // total = acc[0] * 2^32 + acc[1]  >= 2^63  <=>  acc[0] + (acc[1] >> 32) >= 2^31
     if (acc[0] + (acc[1] >> 32) >= (1ull << 31)) code = STALLOC_ERR_OVERFLOW;

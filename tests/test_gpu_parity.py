@@ -189,17 +189,20 @@ def test_plan_config2_all_orderings(S, oracle):
     assert np.array_equal(lean["peaks"], ext) and np.array_equal(lean["best_offsets"], got["best_offsets"])
 
 
-@pytest.mark.parametrize("wide", [False, "medium", True])
+@pytest.mark.parametrize("wide", [False, "coarse", "medium", True])
 @pytest.mark.parametrize("seed", range(12))
 def test_plan_random_traces(S, oracle, seed, wide):
     """Ties in timestamps, single requests, list lengths around wave / workgroup / batch sizes.
-    False: few granules (16-bit list cells); "medium": more than 2^16 granules (32-bit cells);
+    False: sizes of 1-8 granules (bitmap variant); "coarse": 33-264 granules (sorted list, 16-bit
+    cells while the sum stays below 2^16 granules); "medium": more than 2^16 granules (32-bit cells);
     True: odd byte sizes with a sum far above 2^31, which forces 64-bit addresses in the kernel."""
     rng = np.random.default_rng(900 + seed)
     n = [1, 2, 63, 64, 65, 127, 129, 1023, 1025, 2049, 700, 3000][seed]
     size, ts, te, t_end = random_trace(rng, n, t_max=max(4, n // 3), unique_times=(seed % 2 == 1))
     size = size * np.uint64(512)
-    if wide == "medium":
+    if wide == "coarse":
+        size = size * np.uint64(33)
+    elif wide == "medium":
         size = size * np.uint64(70001)
     elif wide:
         size = size * np.uint64(2 ** 31 + 12345) + np.uint64(1)
@@ -269,19 +272,19 @@ def test_plan_bitmap_full_address_range(S):
     assert np.array_equal(got["offsets"][0], expect) and int(got["peaks"][0]) == 32704 * g
 
 
-@pytest.mark.parametrize("largest,total", [(31, 32704), (32, 32704), (31, 32705)])
-def test_plan_bitmap_applicability_limits(S, oracle, largest, total):
-    """Just inside and just outside what the bitmap variant takes (size <= 31 granules, sum <= 32704):
-    either way the plans are the oracle's."""
-    rng = np.random.default_rng(961 + largest + total)
-    n = 2500
+@pytest.mark.parametrize("n,largest,total,bitmap", [(2500, 31, 32704, True), (2500, 32, 32704, False),
+                                                     (9000, 31, 200000, True)])
+def test_plan_bitmap_applicability_limits(S, oracle, n, largest, total, bitmap):
+    """Just inside and just outside what the bitmap variant takes (no size above 31 granules), and an
+    address range that only the one-workgroup-per-CU shape can hold: the plans are the oracle's."""
+    rng = np.random.default_rng(961 + n + largest)
     sizes = rng.integers(1, 26, n)
     sizes[7] = largest
     sizes = _nudge_to_sum(sizes, total, 1, 30, keep=(7,))
     assert int(sizes.sum()) == total and sizes.max() == largest
     _, ts, te, t_end = random_trace(rng, n, t_max=400)
     tr = _T((sizes * 4096).astype(np.uint64), ts, te, t_end)
-    assert bool(_layout(S, tr) & 0x200) == (largest <= 31 and total <= 32704)
+    assert bool(_layout(S, tr) & 0x200) == bitmap
     orders = np.stack([rng.permutation(n) for _ in range(5)]).astype(np.uint32)
     orders[0] = np.argsort(-sizes, kind="stable")
     _compare_plans(S, oracle, tr, orders, method="allpairs")
@@ -307,10 +310,11 @@ def test_plan_bitmap_tall_plans_small_pool(S, oracle):
     assert int(ext.max()) // 65536 > 20000
 
 
-def test_plan_large_list_in_workspace(S, oracle):
-    """Config 3 does not fit the LDS-resident list: sampled orders, every address compared."""
+def test_plan_config3_sampled_orderings(S, oracle):
+    """Config 3 (19 840 requests, 86 748 granules: bitmap variant, one workgroup per CU): sampled
+    orders, every address compared."""
     tr = make_trace(3)
-    assert tr.n > S.lib.stalloc_plan_lds_capacity()
+    assert _layout(S, tr) & 0x200
     rows = [0, 1, 2, 3, 4, 1025, 2046, 2047]
     orders = make_orderings(tr, CONFIGS[3].n_orderings, rows=rows)
     lists = oracle.conflict_lists(tr.t_alloc, tr.t_free)
@@ -354,15 +358,17 @@ def test_plan_config5_sampled_orderings(S, oracle):
 
 @pytest.mark.parametrize("wide", [False, True])
 def test_plan_list_beyond_lds(S, oracle, wide):
-    """A random trace too long for the LDS-resident list, with 32-bit and with 64-bit addresses."""
+    """A random trace too long for the LDS-resident sorted list (and with a size above 31 granules, which
+    rules the bitmap variant out), with 32-bit and with 64-bit addresses."""
     rng = np.random.default_rng(960 + int(wide))
     n = 11000
     assert n > S.lib.stalloc_plan_lds_capacity()
-    size, ts, te, t_end = random_trace(rng, n, t_max=2000, sizes=[1, 2, 3, 5, 8, 13])
+    size, ts, te, t_end = random_trace(rng, n, t_max=2000, sizes=[1, 2, 3, 5, 8, 13, 40])
     size = size * np.uint64(4096)
     if wide:
         size = size * np.uint64(2 ** 31 + 7) + np.uint64(1)
     tr = _T(size, ts, te, t_end)
+    assert _layout(S, tr) == (24 if wide else 16)          # sorted list in the workspace
     orders = np.stack([rng.permutation(n) for _ in range(4)]).astype(np.uint32)
     orders[0] = np.argsort(-size.astype(np.int64), kind="stable")
     _compare_plans(S, oracle, tr, orders, method="lists")
