@@ -60,8 +60,11 @@ struct BitmapLds {
 // ---------------------------------------------------------------------------------------------
 // Lifetime-conflict index.  begin[i] .. begin[i + 1] are the 256-entry chunks of request i's row;
 // an entry is j for a request j != i with t_alloc_j < t_free_i and t_alloc_i < t_free_j, or n (a
-// dummy that is never placed).  begin[] first holds the degrees, then their exclusive prefix sum
-// in chunks.
+// dummy that is never placed) -- stored as 4 * j, the byte offset into the plan's table, while
+// 4 * n fits 16 bits (the build phase then needs one instruction less per lookup).  begin[] first
+// holds the degrees, then their exclusive prefix sum in chunks.
+constexpr uint32_t kScaledEntriesBelow = 16384;      // n below this: entries are 4 * j
+__host__ __device__ inline uint32_t entry_shift(uint32_t n) { return n < kScaledEntriesBelow ? 2u : 0u; }
 
 __device__ __forceinline__ bool index_wanted(const PlanParams& prm)
 {
@@ -159,12 +162,12 @@ __global__ void __launch_bounds__(256) nbr_fill(PlanParams prm)
     for (uint32_t j = t; j < n; j += 256) {
         if (j != i && prm.ta[j] < tf && ta < prm.tf[j]) {
             const uint32_t pos = before_rank[rank] + (uint32_t)__builtin_popcount(banks_at_rank[rank] & ((1u << bank) - 1u));
-            if (pos < room) row[slot(pos)] = (uint16_t)j;
+            if (pos < room) row[slot(pos)] = (uint16_t)(j << entry_shift(n));
             ++rank;
         }
     }
     const uint32_t filled = before_rank[kMaxRank];      // = number of entries
-    for (uint32_t pos = filled + t; pos < room; pos += 256) row[slot(pos)] = (uint16_t)n;
+    for (uint32_t pos = filled + t; pos < room; pos += 256) row[slot(pos)] = (uint16_t)(n << entry_shift(n));
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -271,7 +274,7 @@ __device__ __forceinline__ uint32_t row_scan_add(uint32_t v)
 }
 
 // (eight-wave shape: 8 waves per SIMD = 64 VGPRs at most, so that four workgroups share a CU)
-template <int kWaves>
+template <int kWaves, bool kScaledEntries>
 __global__ void __launch_bounds__(kWaves * kWave, kWaves == 8 ? 8 : 4) plan_bitmap_kernel(PlanParams prm)
 {
     using Lds = BitmapLds<kWaves>;
@@ -347,10 +350,11 @@ __global__ void __launch_bounds__(kWaves * kWave, kWaves == 8 ? 8 : 4) plan_bitm
                 }
             };
             auto lookup = [&](const uint2& ids, uint32_t (&cell)[4]) {
-                cell[0] = cells[ids.x & 0xffffu];
-                cell[1] = cells[ids.x >> 16];
-                cell[2] = cells[ids.y & 0xffffu];
-                cell[3] = cells[ids.y >> 16];
+                const uint32_t e[4] = {ids.x & 0xffffu, ids.x >> 16, ids.y & 0xffffu, ids.y >> 16};
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    cell[k] = kScaledEntries ? *reinterpret_cast<const uint32_t*>(reinterpret_cast<const unsigned char*>(cells) + e[k])
+                                             : cells[e[k]];
             };
             Rows rows = {0, 0, 0, 0};
             uint32_t fetched = 0;                                 // requests `rows` and `ahead` were made for
@@ -481,14 +485,14 @@ template <int kWaves>
 static bool launch_shape(const PlanParams& prm, uint32_t wgs_per_cu, uint32_t pool_words, const DeviceInfo& di,
                          hipStream_t stream)
 {
-    auto kernel = &plan_bitmap_kernel<kWaves>;
+    auto kernel = entry_shift(prm.n) ? &plan_bitmap_kernel<kWaves, true> : &plan_bitmap_kernel<kWaves, false>;
     const size_t lds = sizeof(BitmapLds<kWaves>) + ((size_t)prm.n + 1 + pool_words) * sizeof(uint32_t);
-    static bool attr_set[64] = {};
-    if (!attr_set[di.device]) {
+    static bool attr_set[64][2] = {};
+    if (!attr_set[di.device][entry_shift(prm.n) ? 1 : 0]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)di.lds_per_block) != hipSuccess)
             return false;
-        attr_set[di.device] = true;
+        attr_set[di.device][entry_shift(prm.n) ? 1 : 0] = true;
     }
     uint32_t grid = (uint32_t)di.cus * wgs_per_cu;
     if (grid > prm.P) grid = prm.P;
