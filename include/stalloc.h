@@ -78,6 +78,11 @@ typedef struct stalloc_trace {
  *   best_offsets  device [n], addresses of the best plan; may be NULL.
  *   best_plan     device [1], index of the smallest extent, lowest index among equals.
  *   device_status device [1], see above; must not be NULL.
+ *   workspace     sized for whatever the trace may turn out to need, which only the device
+ *                 learns: for n <= 32768 this includes an index of the request pairs with
+ *                 overlapping lifetimes at its upper bound of about 2 n^2 bytes (76 MB for
+ *                 n = 6144, 0.8 GB for n = 19840); plus (P x n) x 8 bytes when best_offsets
+ *                 is wanted without offsets.
  */
 int stalloc_plan(const stalloc_trace *trace, const uint32_t *orders, uint32_t P,
                  uint64_t *offsets, uint64_t *peaks, uint64_t *best_offsets,
@@ -116,12 +121,12 @@ const char *stalloc_status_string(int status);
  * Informational: how stalloc_plan keeps each plan's placed blocks on the current
  * device.  `granules` = (sum of sizes) / g and `largest` = (largest size) / g, with g the
  * largest power of two dividing every size (all addresses are multiples of g).  Returns
- * the bytes of one stored block in the low 8 bits (4: per-request table plus per-request
- * occupancy bitmaps, needs granules <= 32704 and largest <= 31; 8: sorted list with 16-bit
- * fields, needs granules < 2^16 and t_end < 2^16; 16: sorted list of 32-bit granule counts,
- * needs granules < 2^31; 24: sorted list of 64-bit byte addresses), bit 8 set when the
- * blocks are kept in LDS rather than in the workspace, bit 9 set for the bitmap variant.
- * 0 if no device.
+ * the bytes of one stored block in the low 8 bits (4: per-plan table of placed blocks plus
+ * per-request occupancy bitmaps, needs largest <= 31, n <= 32768 and an LDS bitmap of
+ * granules bits beside the table; 8: sorted list with 16-bit fields, needs granules < 2^16
+ * and t_end < 2^16; 16: sorted list of 32-bit granule counts, needs granules < 2^31; 24:
+ * sorted list of 64-bit byte addresses), bit 8 set when the blocks are kept in LDS rather
+ * than in the workspace, bit 9 set for the bitmap variant.  0 if no device.
  * stalloc_plan_lds_capacity: largest n for which 16-byte entries stay in LDS.
  */
 uint32_t stalloc_plan_list_layout(uint32_t n, uint32_t t_end, uint64_t granules, uint64_t largest);
