@@ -61,10 +61,11 @@ def _bind(path: str):
     lib.oracle_lower_bound_sweep.argtypes = [u32, u32, p, p, p, p, p]
     lib.oracle_best_over_all_orders.argtypes = [u32, p, p, p, p, p]
     lib.oracle_exact_optimum.argtypes = [u32, p, p, p, p, p]
+    lib.oracle_reusable_space.argtypes = [u32, p, p, p, p, u32, u32, u64, p, p, p]
     for name in ("oracle_check_trace", "oracle_plan_allpairs", "oracle_conflict_lists",
                  "oracle_plan_lists", "oracle_best_plan", "oracle_validate",
                  "oracle_lower_bound_definition", "oracle_lower_bound_sweep",
-                 "oracle_best_over_all_orders", "oracle_exact_optimum"):
+                 "oracle_best_over_all_orders", "oracle_exact_optimum", "oracle_reusable_space"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -202,3 +203,15 @@ def exact_optimum(size, t_s, t_e) -> Tuple[int, np.ndarray]:
     a = np.zeros(len(size), dtype=np.uint64)
     _check(_load().oracle_exact_optimum(len(size), _ptr(size), _ptr(t_s), _ptr(t_e), _ptr(ext), _ptr(a)))
     return int(ext[0]), a
+
+
+def reusable_space(size, t_s, t_e, a, window: Tuple[int, int], cap: Optional[int] = None) -> Tuple[np.ndarray, int, int]:
+    """Idle address intervals of plan `a` throughout the window [w_lo, w_hi): (ranges [c][2], count, idle bytes)."""
+    size, t_s, t_e, a = _c(size, np.uint64), _c(t_s, np.uint32), _c(t_e, np.uint32), _c(a, np.uint64)
+    cap = len(size) + 1 if cap is None else int(cap)       # k met decisions leave at most k + 1 intervals
+    ranges = np.zeros((cap, 2), dtype=np.uint64)
+    count = np.zeros(1, dtype=np.uint64)
+    idle = np.zeros(1, dtype=np.uint64)
+    _check(_load().oracle_reusable_space(len(size), _ptr(size), _ptr(t_s), _ptr(t_e), _ptr(a), int(window[0]),
+                                         int(window[1]), cap, _ptr(ranges), _ptr(count), _ptr(idle)))
+    return ranges[:min(cap, int(count[0]))], int(count[0]), int(idle[0])

@@ -34,6 +34,10 @@
  * re-derivation, and hand-worked examples under tests/golden/.
  * No value printed in the paper exists for a placement (its worked figures are
  * images), so parity with printed values is unpinned.
+ *
+ * Dynamic reusable space (Sec. 5.2): oracle_reusable_space, pinned by a
+ * byte-by-byte occupancy map on small pools, closed forms and a hand-worked
+ * example (tests/test_oracle_reusable.py); no printed values exist for it either.
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -341,5 +345,52 @@ int oracle_exact_optimum(uint32_t n, const uint64_t *size, const uint32_t *t_s,
     exact_search(&st, 0, 0);
     *opt_extent = st.best;
     if (opt_a) memcpy(opt_a, st.best_a, n * sizeof(uint64_t));
+    return ORC_OK;
+}
+
+/*
+ * Dynamic reusable space of a plan for one time window (Sec. 5.2).
+ * The occupied addresses A_o of the window are the union of the address ranges
+ * R_s(d) of the decisions whose lifespan R_t(d) meets the window; the pool A
+ * runs from the lowest start address to the highest end address of the whole
+ * plan; the reusable space A_i is A without A_o.  It is returned as its maximal
+ * intervals [lo, hi) in ascending order: ranges[2c], ranges[2c+1] for the first
+ * `cap` of them, *count = how many there are, *idle = their total length.
+ * Readings: the window [w_lo, w_hi) is half-open like the lifespans (the paper
+ * prints both closed), so a decision meets it iff t_s < w_hi and w_lo < t_e.
+ */
+int oracle_reusable_space(uint32_t n, const uint64_t *size, const uint32_t *t_s,
+                          const uint32_t *t_e, const uint64_t *a, uint32_t w_lo, uint32_t w_hi,
+                          uint64_t cap, uint64_t *ranges, uint64_t *count, uint64_t *idle)
+{
+    if (n == 0 || !size || !t_s || !t_e || !a || !count || !idle || (cap && !ranges)) return ORC_INVALID_ARG;
+    if (w_lo >= w_hi) return ORC_INVALID_ARG;
+    span_t *met = (span_t *)malloc((size_t)n * sizeof(span_t));
+    if (!met) return ORC_NOMEM;
+    uint64_t pool_lo = a[0], pool_hi = a[0] + size[0];
+    size_t k = 0;
+    for (uint32_t i = 0; i < n; ++i) {
+        if (a[i] < pool_lo) pool_lo = a[i];
+        if (a[i] + size[i] > pool_hi) pool_hi = a[i] + size[i];
+        if (lifetimes_conflict(t_s[i], t_e[i], w_lo, w_hi)) {
+            met[k].a = a[i];
+            met[k].end = a[i] + size[i];
+            ++k;
+        }
+    }
+    qsort(met, k, sizeof(span_t), span_by_address);
+    uint64_t found = 0, total = 0, reach = pool_lo;      /* everything below `reach` is accounted for */
+    for (size_t c = 0; c <= k; ++c) {
+        const uint64_t next = c < k ? met[c].a : pool_hi;
+        if (next > reach) {                               /* [reach, next) is idle throughout the window */
+            if (found < cap) { ranges[2 * found] = reach; ranges[2 * found + 1] = next; }
+            ++found;
+            total += next - reach;
+        }
+        if (c < k && met[c].end > reach) reach = met[c].end;
+    }
+    free(met);
+    *count = found;
+    *idle = total;
     return ORC_OK;
 }

@@ -7,6 +7,7 @@ import numpy as np
 import pytest
 
 import test_oracle_pins as pins
+import test_oracle_reusable as reusable
 
 MUTATIONS = {
     "closed_lifetimes": ("return ts_a < te_b && ts_b < te_a;", "return ts_a <= te_b && ts_b <= te_a;"),
@@ -21,6 +22,12 @@ MUTATIONS = {
                                  "for (uint32_t j = i + 2; j < n; ++j)\n            if (lifetimes_conflict(t_s[i], t_e[i], t_s[j], t_e[j]) &&"),
     "best_plan_last_of_equals": ("if (extent[p] < extent[b]) b = p;", "if (extent[p] <= extent[b]) b = p;"),
     "sort_descending": ("if (x->a != y->a) return x->a < y->a ? -1 : 1;", "if (x->a != y->a) return x->a < y->a ? 1 : -1;"),
+    "window_closed": ("if (lifetimes_conflict(t_s[i], t_e[i], w_lo, w_hi)) {", "if (t_s[i] <= w_hi && w_lo <= t_e[i]) {"),
+    "idle_reach_not_max": ("if (c < k && met[c].end > reach) reach = met[c].end;", "if (c < k) reach = met[c].end;"),
+    "idle_pool_from_zero": ("uint64_t pool_lo = a[0], pool_hi = a[0] + size[0];", "uint64_t pool_lo = 0, pool_hi = a[0] + size[0];"),
+    "idle_no_tail_interval": ("for (size_t c = 0; c <= k; ++c) {", "for (size_t c = 0; c < k; ++c) {"),
+    "idle_count_capped": ("            ++found;\n            total += next - reach;", "            if (found < cap) ++found;\n            total += next - reach;"),
+    "idle_needs_gap_of_two": ("if (next > reach) {", "if (next > reach + 1) {"),
     "extent_forgets_size": ("if (a[i] + size[i] > top) top = a[i] + size[i];\n    }\n    free(spans);\n    *extent",
                             "if (a[i] > top) top = a[i];\n    }\n    free(spans);\n    *extent"),
 }
@@ -40,6 +47,11 @@ def _battery(oracle):
         pins.test_validate_counts_planted_conflicts(oracle, seed)
     pins.test_validate_known_single_conflict(oracle)
     pins.test_best_plan_prefers_lowest_index(oracle)
+    reusable.test_hand_worked_windows(oracle)
+    reusable.test_closed_forms(oracle)
+    for seed in range(6):
+        reusable.test_matches_byte_map(oracle, seed)
+    reusable.test_lowest_fit_plans_have_no_idle_space_over_the_whole_iteration(oracle, 0)
 
 
 def test_battery_passes_on_the_real_oracle(oracle):
