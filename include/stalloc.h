@@ -22,7 +22,7 @@
  *   - Return value: a stalloc_status for everything the host can see (NULL
  *     pointers, n == 0, P == 0, workspace too small, launch failure).  Defects only
  *     visible on the device (size 0, t_alloc >= t_free, t_free > t_end, sum of sizes
- *     >= 2^63, an order entry >= n) are written as a stalloc_status to
+ *     >= 2^63, an order entry >= n, an empty time window) are written as a stalloc_status to
  *     `device_status[0]` (0 when clean); when it is non-zero every other output of
  *     that call is unspecified, but all kernels still terminate normally.
  *   - Lifetimes and address ranges are half-open; no alignment is applied; byte
@@ -46,7 +46,8 @@ typedef enum stalloc_status {
     STALLOC_ERR_OVERFLOW = 3,    /* sum of sizes >= 2^63: addresses could wrap                    */
     STALLOC_ERR_NOMEM = 4,       /* reserved                                                      */
     STALLOC_ERR_DEVICE = 5,      /* a HIP call failed                                             */
-    STALLOC_ERR_BAD_ORDER = 6    /* an entry of `orders` is >= n                                  */
+    STALLOC_ERR_BAD_ORDER = 6,   /* an entry of `orders` is >= n                                  */
+    STALLOC_ERR_BAD_WINDOW = 7   /* a time window with w_lo >= w_hi                               */
 } stalloc_status;
 
 /* Structure-of-arrays trace (Sec. 4: s, t_s, t_e of every request event). */
@@ -113,6 +114,31 @@ int stalloc_validate(const stalloc_trace *trace, const uint64_t *offsets, uint32
 int stalloc_lower_bound(const stalloc_trace *trace, uint64_t *lower_bound, uint32_t *t_at_max,
                         uint32_t *device_status,
                         void *workspace, size_t *workspace_bytes, void *hip_stream);
+
+/*
+ * Dynamic reusable space of one plan (Sec. 5.2): for each of k time windows
+ * T = [w_lo, w_hi) the address intervals of the pool that stay idle throughout T, so
+ * that requests living inside T can be served from them without touching any planned
+ * decision.  With D the plan's decisions: A_o(T) is the union of the address ranges
+ * R_s(d) of the d in D whose lifespan R_t(d) meets T; A = [min d.a, max (d.a + d.s));
+ * the result is A_i(T) = A minus A_o(T), as its maximal intervals in ascending order.
+ * Windows are half-open like lifespans: d meets T iff t_alloc < w_hi and w_lo < t_free.
+ *
+ *   offsets     device [n], the plan (for instance best_offsets of stalloc_plan); it need
+ *               not be conflict-free, but offsets[i] + size[i] must not wrap
+ *   windows     device [k][2] uint32 {w_lo, w_hi}; w_lo >= w_hi sets device_status to
+ *               STALLOC_ERR_BAD_WINDOW
+ *   max_ranges  capacity of one row of `ranges` (n + 1 always suffices)
+ *   ranges      device [k][max_ranges][2] {lo, hi}: the first max_ranges intervals of each
+ *               window; may be NULL when max_ranges == 0
+ *   counts      device [k], number of intervals of each window (may exceed max_ranges)
+ *   idle_bytes  device [k], total length of all intervals of each window; may be NULL
+ */
+int stalloc_reusable_space(const stalloc_trace *trace, const uint64_t *offsets,
+                           const uint32_t *windows, uint32_t k, uint32_t max_ranges,
+                           uint64_t *ranges, uint32_t *counts, uint64_t *idle_bytes,
+                           uint32_t *device_status,
+                           void *workspace, size_t *workspace_bytes, void *hip_stream);
 
 /* Human-readable name of a stalloc_status; never NULL.  Host memory, static storage. */
 const char *stalloc_status_string(int status);

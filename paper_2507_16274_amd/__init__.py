@@ -20,9 +20,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libstalloc.so")
 
 STATUS = {0: "STALLOC_OK", 1: "STALLOC_ERR_INVALID_ARG", 2: "STALLOC_ERR_BAD_TRACE", 3: "STALLOC_ERR_OVERFLOW",
-          4: "STALLOC_ERR_NOMEM", 5: "STALLOC_ERR_DEVICE", 6: "STALLOC_ERR_BAD_ORDER"}
-EXPORTS = ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_status_string",
-           "stalloc_plan_lds_capacity", "stalloc_plan_list_layout")
+          4: "STALLOC_ERR_NOMEM", 5: "STALLOC_ERR_DEVICE", 6: "STALLOC_ERR_BAD_ORDER", 7: "STALLOC_ERR_BAD_WINDOW"}
+EXPORTS = ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_reusable_space",
+           "stalloc_status_string", "stalloc_plan_lds_capacity", "stalloc_plan_list_layout")
 
 
 class StallocError(RuntimeError):
@@ -47,7 +47,8 @@ def _load() -> ctypes.CDLL:
     lib.stalloc_plan.argtypes = [tp, vp, u32, vp, vp, vp, vp, vp, vp, szp, vp]
     lib.stalloc_validate.argtypes = [tp, vp, u32, vp, vp, vp, vp, szp, vp]
     lib.stalloc_lower_bound.argtypes = [tp, vp, vp, vp, vp, szp, vp]
-    for name in ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound"):
+    lib.stalloc_reusable_space.argtypes = [tp, vp, vp, u32, u32, vp, vp, vp, vp, vp, szp, vp]
+    for name in ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_reusable_space"):
         getattr(lib, name).restype = ctypes.c_int
     lib.stalloc_status_string.argtypes = [ctypes.c_int]
     lib.stalloc_status_string.restype = ctypes.c_char_p
@@ -172,6 +173,32 @@ def stalloc_lower_bound(size, t_alloc, t_free, t_end: int, *, stream=None,
     ws = _workspace(need.value, dev, workspace_cache)
     have = ctypes.c_size_t(ws.numel())
     _check(lib.stalloc_lower_bound(*args, ws.data_ptr(), ctypes.byref(have), _stream(stream)), "stalloc_lower_bound")
+    out["workspace"] = ws
+    return out
+
+
+def stalloc_reusable_space(size, t_alloc, t_free, t_end: int, offsets, windows, max_ranges: int, *, stream=None,
+                           workspace_cache: Optional[Dict] = None) -> Dict[str, torch.Tensor]:
+    """offsets int64 [n], windows int32 [k][2] -> ranges int64 [k][max_ranges][2], counts int32 [k],
+    idle_bytes int64 [k], status int32 [1]."""
+    tr = _trace(size, t_alloc, t_free, t_end)
+    if offsets.dim() != 1 or offsets.numel() != tr.n:
+        raise ValueError("offsets must be [n]")
+    if windows.dim() != 2 or windows.shape[1] != 2:
+        raise ValueError("windows must be [k][2]")
+    k, dev = windows.shape[0], size.device
+    out = {"ranges": torch.empty((k, max_ranges, 2), dtype=torch.int64, device=dev) if max_ranges else None,
+           "counts": torch.empty(k, dtype=torch.int32, device=dev),
+           "idle_bytes": torch.empty(k, dtype=torch.int64, device=dev),
+           "status": torch.empty(1, dtype=torch.int32, device=dev)}
+    args = (ctypes.byref(tr), _dev(offsets, torch.int64, "offsets"), _dev(windows, torch.int32, "windows"), k,
+            int(max_ranges), out["ranges"].data_ptr() if max_ranges else None, out["counts"].data_ptr(),
+            out["idle_bytes"].data_ptr(), out["status"].data_ptr())
+    need = ctypes.c_size_t(0)
+    _check(lib.stalloc_reusable_space(*args, None, ctypes.byref(need), None), "stalloc_reusable_space(workspace query)")
+    ws = _workspace(need.value, dev, workspace_cache)
+    have = ctypes.c_size_t(ws.numel())
+    _check(lib.stalloc_reusable_space(*args, ws.data_ptr(), ctypes.byref(have), _stream(stream)), "stalloc_reusable_space")
     out["workspace"] = ws
     return out
 

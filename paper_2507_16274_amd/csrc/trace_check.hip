@@ -88,6 +88,7 @@ extern "C" const char* stalloc_status_string(int status)
         case STALLOC_ERR_NOMEM: return "STALLOC_ERR_NOMEM";
         case STALLOC_ERR_DEVICE: return "STALLOC_ERR_DEVICE";
         case STALLOC_ERR_BAD_ORDER: return "STALLOC_ERR_BAD_ORDER";
+        case STALLOC_ERR_BAD_WINDOW: return "STALLOC_ERR_BAD_WINDOW";
         default: return "STALLOC_UNKNOWN_STATUS";
     }
 }
