@@ -55,6 +55,8 @@ def main() -> int:
     ap.add_argument("--plans", type=int, default=0, help="override the number of orders (0 = the configuration's)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="CPU work budget of the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--reusable", type=int, default=0, metavar="K",
+                    help="also time stalloc_reusable_space for K windows over the best plan (reported beside the step)")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference dispatch for HBM byte counters)")
     args = ap.parse_args()
@@ -185,6 +187,53 @@ def main() -> int:
         "floor_ms": {k: v * 1e3 for k, v in floors.items()},
         "hbm_stream_GBs": hbm_bytes / t_s / 1e9,
         "list_GBs": state_bytes / t_s / 1e9})
+
+    if args.reusable:
+        # Dynamic reusable space of the best plan (Sec. 5.2) for K layer-like windows: its own timed
+        # region.  Algorithmic work: every window looks at every decision once, 24 B (address range,
+        # lifespan) and 8 lane operations (two compares, select, 64-bit running maximum, compare).
+        from workloads import make_windows
+        K = args.reusable
+        windows_np = make_windows(tr, K, seed=7000 + args.config)
+        windows = torch.from_numpy(windows_np.view(np.int32)).cuda()
+        cap, cache_rs = 64, {}
+        best_offsets = plan["best_offsets"].clone()
+        for _ in range(args.warmup):
+            S.stalloc_reusable_space(size, ta, tf, tr.t_end, best_offsets, windows, cap, workspace_cache=cache_rs)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            rs = S.stalloc_reusable_space(size, ta, tf, tr.t_end, best_offsets, windows, cap, workspace_cache=cache_rs)
+        e1.record()
+        torch.cuda.synchronize()
+        S.check_status(rs, "stalloc_reusable_space")
+        rs_ms = e0.elapsed_time(e1) / args.steps
+        rs_bytes, rs_ops = 24 * n * K, 8 * n * K
+        # the byte floor (at the HBM rate) is the larger of the two for any n and K
+        result["reusable_space"] = {
+            "windows": K, "ms_per_call": rs_ms, "windows_per_s": K / (rs_ms * 1e-3),
+            "mean_intervals": float(rs["counts"].float().mean().item()),
+            "roofline": {"bound": "hbm", "kernel": "rs_sweep (+ rs_rank, rs_scatter)", "achieved": rs_bytes / (rs_ms * 1e-3) / 1e9,
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": rs_bytes / (rs_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "traffic": None, "algorithmic_bytes": rs_bytes,
+                         "floor_ms": {"hbm": rs_bytes / (HBM_PEAK_GBS * 1e9) * 1e3, "alu": rs_ops / (ALU_PEAK_TOPS * 1e12) * 1e3}}}
+        if not args.no_cpu_baseline:
+            import oracle
+            oracle.build()
+            sample = min(K, 64)
+            t1 = time.perf_counter()
+            best_np = best_offsets.cpu().numpy().view(np.uint64)
+            counts = rs["counts"].cpu().numpy()
+            for w in range(sample):
+                _, c, _ = oracle.reusable_space(tr.size, tr.t_alloc, tr.t_free, best_np,
+                                                (int(windows_np[w, 0]), int(windows_np[w, 1])), cap=cap)
+                if c != int(counts[w]):
+                    print("bench.py: reusable-space counts differ from the oracle", file=sys.stderr)
+                    return 1
+            wall = time.perf_counter() - t1
+            result["reusable_space"]["cpu_baseline"] = {"value": sample / wall, "unit": "windows/s", "cores": 1,
+                                                        "kind": "oracle", "sample": f"first {sample} windows"}
 
     if not args.no_cpu_baseline:
         import oracle

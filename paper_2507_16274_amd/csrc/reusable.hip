@@ -5,11 +5,12 @@
 // the highest end address of the whole plan; the reusable space is A_i = A \ A_o.  It is returned
 // as its maximal intervals in ascending address order.  Windows are half-open like lifespans.
 //
-//   rank     The decisions are sorted by start address once per call.  Their rank is counted
-//            directly -- rank_i = #{j : (a_j, j) < (a_i, i)} -- over tiles of 256 x 256 pairs: a
-//            thread keeps its own decision in registers and walks a tile that sits in LDS and is
-//            read as broadcasts.  n^2 compares are cheap next to the windows that follow, need no
-//            scratch passes and no tuning, and ties are broken by request number.
+//   rank     The decisions are sorted by (start address, request number) once per call: tiles of
+//            256 are sorted in LDS (bitonic network); the rank of a decision is then its position
+//            in its own tile plus, for every other tile, the number of that tile's decisions
+//            that sort before it -- a binary search in the tile, staged in LDS.  n^2 / 32 steps
+//            in all, no scratch passes, nothing to tune, no dependence on how the addresses are
+//            distributed.
 //   scatter  (start, end, lifespan) of every decision go to their rank.
 //   sweep    One workgroup per window over the address-sorted decisions, each wave a contiguous
 //            part, 64 decisions a step.  A decision counts if its lifespan meets the window; a
@@ -36,38 +37,79 @@ __global__ void rs_init(uint32_t* rank, uint32_t n, RsPool* pool)
     if (blockIdx.x == 0 && threadIdx.x == 0) { pool->lo = ~0ull; pool->hi = 0; }
 }
 
-// grid (tiles of i, slices of j): rank[i] += number of decisions of the slice that sort before i.
+// (address, request number), ordered lexicographically
+struct RsKey { uint64_t a; uint32_t id; };
+__device__ __forceinline__ bool before(const RsKey& x, const RsKey& y) { return x.a < y.a || (x.a == y.a && x.id < y.id); }
+
+// One tile of 256 decisions per workgroup: sorted in LDS, written to t_a / t_id; past-the-end
+// slots hold (~0, ~0) and sort last.  Also the pool's bounds.
 __global__ void __launch_bounds__(kRsTile)
-rs_rank(const uint64_t* __restrict__ size, const uint64_t* __restrict__ offsets, uint32_t n, uint32_t tiles_per_slice,
-        uint32_t* rank, RsPool* pool, const uint32_t* status)
+rs_sort_tiles(const uint64_t* __restrict__ size, const uint64_t* __restrict__ offsets, uint32_t n, uint64_t* t_a,
+              uint32_t* t_id, RsPool* pool, const uint32_t* status)
 {
-    __shared__ uint64_t j_lo[kRsTile];
+    __shared__ uint64_t k_a[kRsTile];
+    __shared__ uint32_t k_id[kRsTile];
     if (*status != STALLOC_OK) return;
-    const uint32_t i = blockIdx.x * kRsTile + threadIdx.x;
-    const bool i_ok = i < n;
-    const uint64_t i_lo = i_ok ? offsets[i] : ~0ull;
-    uint32_t before = 0;
-    const uint32_t tile0 = blockIdx.y * tiles_per_slice;
-    for (uint32_t t = tile0; t < tile0 + tiles_per_slice && t * kRsTile < n; ++t) {
-        const uint32_t j0 = t * kRsTile;
-        __syncthreads();
-        j_lo[threadIdx.x] = j0 + threadIdx.x < n ? offsets[j0 + threadIdx.x] : ~0ull;
-        __syncthreads();
-        const uint32_t in_tile = n - j0 < (uint32_t)kRsTile ? n - j0 : (uint32_t)kRsTile;
-        // j sorts before i if its address is lower, or equal with a lower request number
-        const uint32_t ties_before = i < j0 ? 0u : (i - j0 < in_tile ? i - j0 : in_tile);    // j in the tile with j < i
-#pragma unroll 8
-        for (uint32_t q = 0; q < in_tile; ++q) before += j_lo[q] < i_lo || (j_lo[q] == i_lo && q < ties_before);
-    }
-    if (i_ok && before) atomicAdd(&rank[i], before);
-    if (blockIdx.y == 0) {
-        const uint64_t lo = wave_min64(i_lo);                                    // (lanes past n hold ~0)
-        const uint64_t hi = wave_max64(i_ok ? i_lo + size[i] : 0ull);
+    const uint32_t t = threadIdx.x, i = blockIdx.x * kRsTile + t;
+    const bool ok = i < n;
+    const uint64_t a = ok ? offsets[i] : ~0ull;
+    k_a[t] = a;
+    k_id[t] = ok ? i : ~0u;
+    {
+        const uint64_t lo = wave_min64(a);                                       // (slots past n hold ~0)
+        const uint64_t hi = wave_max64(ok ? a + size[i] : 0ull);
         if (lane_id() == 0) {
             atomicMin((unsigned long long*)&pool->lo, (unsigned long long)lo);
             atomicMax((unsigned long long*)&pool->hi, (unsigned long long)hi);
         }
     }
+    for (uint32_t span = 2; span <= (uint32_t)kRsTile; span <<= 1) {
+        for (uint32_t gap = span >> 1; gap > 0; gap >>= 1) {
+            __syncthreads();
+            const uint32_t other = t ^ gap;
+            if (other > t) {
+                const RsKey x = {k_a[t], k_id[t]}, y = {k_a[other], k_id[other]};
+                const bool ascending = (t & span) == 0;
+                if (before(y, x) == ascending) {
+                    k_a[t] = y.a; k_id[t] = y.id;
+                    k_a[other] = x.a; k_id[other] = x.id;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    t_a[blockIdx.x * kRsTile + t] = k_a[t];
+    t_id[blockIdx.x * kRsTile + t] = k_id[t];
+}
+
+// grid (tiles, slices of the tile range): thread p of workgroup b holds the decision at position p
+// of sorted tile b and adds, to its rank, how many decisions of the slice's tiles sort before it.
+__global__ void __launch_bounds__(kRsTile)
+rs_rank(const uint64_t* __restrict__ t_a, const uint32_t* __restrict__ t_id, uint32_t n, uint32_t tiles,
+        uint32_t tiles_per_slice, uint32_t* rank, const uint32_t* status)
+{
+    __shared__ uint64_t k_a[kRsTile];
+    __shared__ uint32_t k_id[kRsTile];
+    if (*status != STALLOC_OK) return;
+    const uint32_t p = threadIdx.x, own = blockIdx.x;
+    const RsKey me = {t_a[own * kRsTile + p], t_id[own * kRsTile + p]};
+    uint32_t count = 0;
+    const uint32_t tile0 = blockIdx.y * tiles_per_slice;
+    for (uint32_t t = tile0; t < tile0 + tiles_per_slice && t < tiles; ++t) {
+        if (t == own) { count += p; continue; }                                  // (uniform)
+        __syncthreads();
+        k_a[p] = t_a[t * kRsTile + p];
+        k_id[p] = t_id[t * kRsTile + p];
+        __syncthreads();
+        uint32_t lo = 0;                                                          // first position not before `me`
+        for (uint32_t half = kRsTile / 2; half > 0; half >>= 1) {
+            const RsKey probe = {k_a[lo + half - 1], k_id[lo + half - 1]};
+            if (before(probe, me)) lo += half;
+        }
+        const RsKey last = {k_a[lo], k_id[lo]};                                   // lo <= 255 here
+        count += lo + (before(last, me) ? 1u : 0u);
+    }
+    if (me.id < n && count) atomicAdd(&rank[me.id], count);
 }
 
 __global__ void __launch_bounds__(256)
@@ -209,6 +251,9 @@ extern "C" int stalloc_reusable_space(const stalloc_trace* tr, const uint64_t* o
     uint64_t* acc = cv.take<uint64_t>(kAccWords);
     RsPool* pool = cv.take<RsPool>(1);
     uint32_t* rank = cv.take<uint32_t>(n);
+    const uint32_t tiles = (n + kRsTile - 1) / kRsTile;
+    uint64_t* t_a = cv.take<uint64_t>((size_t)tiles * kRsTile);
+    uint32_t* t_id = cv.take<uint32_t>((size_t)tiles * kRsTile);
     uint64_t* s_lo = cv.take<uint64_t>(n);
     uint64_t* s_hi = cv.take<uint64_t>(n);
     uint2* s_life = cv.take<uint2>(n);
@@ -222,15 +267,16 @@ extern "C" int stalloc_reusable_space(const stalloc_trace* tr, const uint64_t* o
 
     uint32_t blocks = (n + 255) / 256;
     hipLaunchKernelGGL(rs_init, dim3(blocks > 1024 ? 1024 : blocks), dim3(256), 0, stream, rank, n, pool);
-    const uint32_t tiles = (n + kRsTile - 1) / kRsTile;
-    // enough slices of the j range to fill the chip, at least 8 tiles each
+    hipLaunchKernelGGL(rs_sort_tiles, dim3(tiles), dim3(kRsTile), 0, stream, tr->size, offsets, n, t_a, t_id, pool,
+                       device_status);
+    // enough slices of the tile range to fill the chip, at least 8 tiles each
     uint32_t slices = (uint32_t)di.cus * 8 / tiles;
     if (slices < 1) slices = 1;
     if (slices > (tiles + 7) / 8) slices = (tiles + 7) / 8;
     const uint32_t tiles_per_slice = (tiles + slices - 1) / slices;
     slices = (tiles + tiles_per_slice - 1) / tiles_per_slice;
-    hipLaunchKernelGGL(rs_rank, dim3(tiles, slices), dim3(kRsTile), 0, stream, tr->size, offsets, n, tiles_per_slice, rank,
-                       pool, device_status);
+    hipLaunchKernelGGL(rs_rank, dim3(tiles, slices), dim3(kRsTile), 0, stream, t_a, t_id, n, tiles, tiles_per_slice, rank,
+                       device_status);
     hipLaunchKernelGGL(rs_scatter, dim3(blocks > 1024 ? 1024 : blocks), dim3(256), 0, stream, tr->size, tr->t_alloc,
                        tr->t_free, offsets, rank, n, s_lo, s_hi, s_life, device_status);
     RsArgs g;
