@@ -374,6 +374,20 @@ def test_plan_list_beyond_lds(S, oracle, wide):
     _compare_plans(S, oracle, tr, orders, method="lists")
 
 
+@pytest.mark.parametrize("sizes", [[1, 2, 3, 4], [1, 2, 3, 40]])
+def test_plan_more_orders_than_resident_workgroups(S, oracle, sizes):
+    """5000 orders of a small trace: every workgroup places several plans in a row (per-plan state
+    must start clean), in the bitmap kernel (sizes up to 4 granules) and in the sorted-list kernel."""
+    rng = np.random.default_rng(970)
+    n = 150
+    size, ts, te, t_end = random_trace(rng, n, t_max=60, sizes=sizes)
+    tr = _T(size * np.uint64(1024), ts, te, t_end)
+    assert bool(_layout(S, tr) & 0x200) == (max(sizes) <= 31)
+    P = 5000
+    orders = np.stack([rng.permutation(n) for _ in range(P)]).astype(np.uint32)
+    _compare_plans(S, oracle, tr, orders, method="allpairs")
+
+
 def test_plan_reports_malformed_inputs(S):
     g = load_golden("gap_fit.txt")
     orders = np.asarray([g["cases"][0]["order"]], np.uint32)
