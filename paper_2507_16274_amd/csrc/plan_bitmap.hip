@@ -33,7 +33,14 @@
 
 namespace stalloc {
 
-constexpr int kBmBatch = 128;            // requests fetched per refill
+#ifndef STALLOC_BITMAP_REFILL
+#define STALLOC_BITMAP_REFILL 128
+#endif
+#ifndef STALLOC_BITMAP_SHARES
+#define STALLOC_BITMAP_SHARES 2
+#endif
+constexpr int kBmBatch = STALLOC_BITMAP_REFILL;    // requests fetched per refill
+constexpr uint32_t kShares = STALLOC_BITMAP_SHARES; // chunks a building wave takes for every one wave 0 takes
 constexpr int kBmWords = 1056;           // a pool of twice this many words is asked for before workgroups share a CU
 constexpr int kRowPad = 256;             // index rows are padded to this many entries (4 per lane)
 
@@ -294,7 +301,8 @@ __global__ void __launch_bounds__(kWaves * kWave, kWaves == 8 ? 8 : 4) plan_bitm
     const uint32_t pool_words = prm.bitmap_pool_words[kShape];
     // the rule above keeps every address of a well-formed plan at or below this; a malformed order
     // row (repeated requests) is clamped to it so that a bitmap never outgrows the pool
-    const uint32_t highest = 32u * (pool_words - kWaves - 5) + 31u;
+    const uint32_t half_words = pool_words / 2;        // two batches are in flight, each in its half of the pool
+    const uint32_t highest = 32u * (half_words - 2 * kWaves - 5) + 31u;
     const int lane = lane_id(), wave = (int)uniform((uint32_t)wave_id());
     const uint2* index = reinterpret_cast<const uint2*>(prm.nbr) + lane;   // a chunk: 64 lanes x 4 entries
 
@@ -320,13 +328,28 @@ __global__ void __launch_bounds__(kWaves * kWave, kWaves == 8 ? 8 : 4) plan_bitm
             }
             __syncthreads();
 
-            // The rows of a batch, cut into chunks and numbered through; chunk f goes to wave f mod
-            // kWaves.  Lane q < 16 describes the row of request q of the batch.
+            // A batch: requests first .. first + nb - 1 of the refill, their bitmaps `stride` words apart
+            // and `limit` words long in one half of the pool.  A batch is sized when its half is cleared:
+            // two batches are in flight, so every block that can exist while it is in use ends below
+            // the extent at that moment plus 2 * kWaves of the longest requests.
+            struct Batch { uint32_t first, nb, limit, stride; };
+            auto size_batch = [&](uint32_t first) -> Batch {
+                Batch b;
+                b.first = first;
+                b.limit = uniform(sh.top) / 32 + 2 * kWaves + 2;
+                b.stride = b.limit | 1u;
+                uint32_t fit = half_words / b.stride;             // >= 1
+                if (fit > (uint32_t)kWaves) fit = kWaves;
+                b.nb = first >= staged ? 0u : (staged - first < fit ? staged - first : fit);
+                return b;
+            };
+            // The rows of a batch, cut into chunks and numbered through.  Lane q < 16 describes the row
+            // of request q of the batch.
             struct Rows { uint32_t row, chunks, end, total; };
-            auto rows_of = [&](uint32_t first, uint32_t count) -> Rows {
+            auto rows_of = [&](const Batch& b) -> Rows {
                 Rows r = {0, 0, 0, 0};
-                if (lane < (int)count) { r.row = sh.rq_row[first + lane]; r.chunks = sh.rq_chunks[first + lane]; }
-                r.end = row_scan_add(r.chunks);                   // (count <= 16: one DPP row)
+                if (lane < (int)b.nb) { r.row = sh.rq_row[b.first + lane]; r.chunks = sh.rq_chunks[b.first + lane]; }
+                r.end = row_scan_add(r.chunks);                   // (nb <= 16: one DPP row)
                 r.total = read_lane(r.end, 15);
                 return r;
             };
@@ -336,15 +359,23 @@ __global__ void __launch_bounds__(kWaves * kWave, kWaves == 8 ? 8 : 4) plan_bitm
                 const uint32_t at = read_lane(r.row, (int)q) + f - (read_lane(r.end, (int)q) - read_lane(r.chunks, (int)q));
                 return index + (size_t)at * (kRowPad / 4);
             };
-            // The index entries of a wave's first kAhead chunks of a batch are fetched long before
-            // the batch is built (while the batch before it is searched and settled): the index is
-            // far larger than the L2 and a fetch takes about as long as a chunk takes to process.
+            // Which chunks a wave takes: wave 0 settles the previous batch while the others already
+            // build, so it gets a smaller share -- of every kShares * (kWaves - 1) + 1 chunks, kShares
+            // go to each of the waves 1 .. kWaves - 1 and the last one to wave 0.
+            auto chunk_of = [&](uint32_t j) -> uint32_t {
+                constexpr uint32_t kPeriod = kShares * (kWaves - 1) + 1;
+                return wave == 0 ? j * kPeriod + (kPeriod - 1)
+                                 : (j / kShares) * kPeriod + (j % kShares) * (kWaves - 1) + (uint32_t)(wave - 1);
+            };
+            // The index entries of a wave's first kAhead chunks of a batch are fetched when the batch is
+            // sized, a whole batch before they are used: the index is far larger than the L2 and a
+            // fetch takes about as long as a chunk takes to process.
             uint2 ahead[kAhead];
             uint32_t ahead_q[kAhead];
             auto fetch_ahead = [&](const Rows& r) {
 #pragma unroll
                 for (int j = 0; j < kAhead; ++j) {
-                    const uint32_t f = (uint32_t)wave + (uint32_t)j * kWaves;
+                    const uint32_t f = chunk_of((uint32_t)j);
                     ahead_q[j] = 0;
                     if (f < r.total) ahead[j] = *locate(r, f, ahead_q[j]);
                 }
@@ -356,93 +387,116 @@ __global__ void __launch_bounds__(kWaves * kWave, kWaves == 8 ? 8 : 4) plan_bitm
                     cell[k] = kScaledEntries ? *reinterpret_cast<const uint32_t*>(reinterpret_cast<const unsigned char*>(cells) + e[k])
                                              : cells[e[k]];
             };
-            Rows rows = {0, 0, 0, 0};
-            uint32_t fetched = 0;                                 // requests `rows` and `ahead` were made for
-
-            for (uint32_t b0 = 0; b0 < staged;) {
-                const uint32_t top0 = uniform(sh.top);
-                // every block of the plan, this batch included, ends below word `limit`
-                const uint32_t limit = top0 / 32 + kWaves + 2;
-                const uint32_t stride = limit | 1u;              // bitmap q of the batch: pool + q * stride
-                uint32_t fit = pool_words / stride;               // >= 1
-                if (fit > (uint32_t)kWaves) fit = kWaves;
-                const uint32_t nb = staged - b0 < fit ? staged - b0 : fit;
-                if (fetched != nb) {                              // first batch of a refill, or the pool holds fewer now
-                    rows = rows_of(b0, nb);
-                    fetch_ahead(rows);
-                }
-                if ((uint32_t)wave < nb)
-                    for (uint32_t w = lane; w < limit; w += kWave) pool[(uint32_t)wave * stride + w] = 0;
-                __syncthreads();
-
-                // build: table lookups of one chunk are in flight while the previous one is marked
-                {
-                    uint32_t cell[4] = {0, 0, 0, 0}, looked[4] = {0, 0, 0, 0};
-                    if ((uint32_t)wave < rows.total) lookup(ahead[0], cell);
+            auto clear = [&](uint32_t* bitmaps, const Batch& b) {
+                if ((uint32_t)wave < b.nb)
+                    for (uint32_t w = lane; w < b.limit; w += kWave) bitmaps[(uint32_t)wave * b.stride + w] = 0;
+            };
+            // build: table lookups of one chunk are in flight while the previous one is marked
+            auto build = [&](uint32_t* bitmaps, const Batch& b, const Rows& rows) {
+                uint32_t cell[4] = {0, 0, 0, 0}, looked[4] = {0, 0, 0, 0};
+                if (chunk_of(0) < rows.total) lookup(ahead[0], cell);
 #pragma unroll
-                    for (int j = 0; j < kAhead; ++j) {
-                        const uint32_t f = (uint32_t)wave + (uint32_t)j * kWaves;
-                        if (f < rows.total) {
-                            if (j + 1 < kAhead && f + kWaves < rows.total) lookup(ahead[j + 1 < kAhead ? j + 1 : j], looked);
-                            mark_cells(pool + ahead_q[j] * stride, cell);
+                for (int j = 0; j < kAhead; ++j) {
+                    if (chunk_of((uint32_t)j) < rows.total) {
+                        if (j + 1 < kAhead && chunk_of((uint32_t)j + 1) < rows.total) lookup(ahead[j + 1 < kAhead ? j + 1 : j], looked);
+                        mark_cells(bitmaps + ahead_q[j] * b.stride, cell);
 #pragma unroll
-                            for (int k = 0; k < 4; ++k) cell[k] = looked[k];
-                        }
-                    }
-                    for (uint32_t f = (uint32_t)wave + kAhead * kWaves; f < rows.total; f += kWaves) {   // (long rows only)
-                        uint32_t q;
-                        const uint2 ids = *locate(rows, f, q);
-                        lookup(ids, cell);
-                        mark_cells(pool + q * stride, cell);
+                        for (int k = 0; k < 4; ++k) cell[k] = looked[k];
                     }
                 }
-                fetched = 0;
-                if (b0 + nb < staged) {                           // the next batch, if the pool still holds as many then
-                    const uint32_t b1 = b0 + nb;
-                    fetched = staged - b1 < fit ? staged - b1 : fit;
-                    rows = rows_of(b1, fetched);
-                    fetch_ahead(rows);
+                for (uint32_t j = kAhead; chunk_of(j) < rows.total; ++j) {                // (long rows only)
+                    uint32_t q;
+                    const uint2 ids = *locate(rows, chunk_of(j), q);
+                    lookup(ids, cell);
+                    mark_cells(bitmaps + q * b.stride, cell);
                 }
-                __syncthreads();
-
-                // search: lowest fit of request b0 + wave against everything placed before the batch
-                if ((uint32_t)wave < nb) {
-                    const uint32_t x = first_fit(pool + (uint32_t)wave * stride, limit, uniform(sh.rq_s[b0 + wave]));
+            };
+            // search: lowest fit of request q of the batch against what its bitmap holds
+            auto search = [&](uint32_t* bitmaps, const Batch& b) {
+                if ((uint32_t)wave < b.nb) {
+                    const uint32_t x = first_fit(bitmaps + (uint32_t)wave * b.stride, b.limit, uniform(sh.rq_s[b.first + wave]));
                     if (lane == 0) sh.cand[wave] = x;
                 }
-                __syncthreads();
-
-                if (wave == 0) {
-                    // settle: lane q holds request q of the batch; `mine` = its final address once settled
-                    uint32_t my_s = 0, my_ta = 0xffffffffu, my_tf = 0, my_x = 0, mine = 0;   // empty lifetime: no conflicts
-                    if (lane < (int)nb) {
-                        my_s = sh.rq_s[b0 + lane];
-                        my_ta = sh.rq_ta[b0 + lane];
-                        my_tf = sh.rq_tf[b0 + lane];
-                        my_x = sh.cand[lane];
-                    }
-                    uint32_t top = top0;
-                    for (uint32_t r = 0; r < nb; ++r) {
-                        const uint32_t s = read_lane(my_s, (int)r), ta = read_lane(my_ta, (int)r);
-                        const uint32_t tf = read_lane(my_tf, (int)r);
-                        uint32_t x = read_lane(my_x, (int)r);
-                        const bool rival = lane < (int)r && my_ta < tf && ta < my_tf;
-                        if (__builtin_amdgcn_ballot_w64(rival && mine < x + s && x < mine + my_s)) {
-                            if (rival) mark_cell(pool + r * stride, make_cell(mine, my_s));
-                            x = first_fit(pool + r * stride, limit, s);
-                        }
-                        if (x > highest) x = highest;                      // only reachable with a malformed order row
-                        if (lane == (int)r) mine = x;
-                        top = umax(top, x + s);
-                    }
-                    if (lane < (int)nb) {
-                        cells[sh.rq_id[b0 + lane]] = make_cell(mine, my_s);
-                        sh.rq_x[b0 + lane] = mine;
-                    }
-                    if (lane == 0) sh.top = top;
+            };
+            // settle (one wave): the requests of the batch in order.  The bitmaps hold every block
+            // placed before the batch except possibly those of the batch just before it (they were
+            // being settled while these bitmaps were built).  A candidate stands unless one of those,
+            // or a request settled earlier in this batch, overlaps it in lifetime and in address
+            // range; only then are those blocks ORed into the request's bitmap and the search
+            // repeated (adding blocks only removes free runs; ORing a block twice changes nothing).
+            // Lanes 0 .. kWaves-1: the batch before (settled); lanes kWaves .. : this batch.
+            auto settle = [&](uint32_t* bitmaps, const Batch& b, uint32_t nb_prev) {
+                uint32_t my_s = 0, my_ta = 0xffffffffu, my_tf = 0, mine = 0;     // empty lifetime: conflicts with nothing
+                const bool prev = lane < kWaves && (uint32_t)(kWaves - lane) <= nb_prev;    // request first - (kWaves - lane)
+                const bool cur = lane >= kWaves && (uint32_t)(lane - kWaves) < b.nb;
+                if (prev || cur) {
+                    const uint32_t at = b.first + (uint32_t)lane - kWaves;
+                    my_s = sh.rq_s[at];
+                    my_ta = sh.rq_ta[at];
+                    my_tf = sh.rq_tf[at];
+                    mine = prev ? sh.rq_x[at] : sh.cand[lane - kWaves];
                 }
+                uint32_t top = sh.top;
+                for (uint32_t r = 0; r < b.nb; ++r) {
+                    const int at = kWaves + (int)r;
+                    const uint32_t s = read_lane(my_s, at), ta = read_lane(my_ta, at), tf = read_lane(my_tf, at);
+                    uint32_t x = read_lane(mine, at);
+                    const bool rival = lane < at && my_ta < tf && ta < my_tf;
+                    if (__builtin_amdgcn_ballot_w64(rival && mine < x + s && x < mine + my_s)) {
+                        if (rival) mark_cell(bitmaps + r * b.stride, make_cell(mine, my_s));
+                        x = first_fit(bitmaps + r * b.stride, b.limit, s);
+                    }
+                    if (x > highest) x = highest;                          // only reachable with a malformed order row
+                    if (lane == at) mine = x;
+                    top = umax(top, x + s);
+                }
+                if (cur) {
+                    cells[sh.rq_id[b.first + lane - kWaves]] = make_cell(mine, my_s);
+                    sh.rq_x[b.first + lane - kWaves] = mine;
+                }
+                if (lane == 0) sh.top = top;
+            };
+
+            // Software pipeline over the batches of the refill: while wave 0 settles batch B in one
+            // half of the pool, all waves (wave 0 once it is done) build the bitmaps of batch B + 1 in
+            // the other half; then B + 1 is searched, and the half of B is cleared for B + 2.
+            uint32_t* half[2] = {pool, pool + half_words};
+            int h = 0;
+            Batch cur = size_batch(0);
+            Rows rows = rows_of(cur);
+            fetch_ahead(rows);
+            clear(half[0], cur);
+            __syncthreads();
+            build(half[0], cur, rows);
+            Batch nxt = size_batch(cur.nb);
+            if (nxt.nb) {
+                rows = rows_of(nxt);
+                fetch_ahead(rows);
+                clear(half[1], nxt);
+            }
+            __syncthreads();
+            search(half[0], cur);
+            __syncthreads();
+            uint32_t nb_prev = 0;
+            while (cur.nb) {
+                if (wave == 0) settle(half[h], cur, nb_prev);
+                if (nxt.nb) build(half[h ^ 1], nxt, rows);
                 __syncthreads();
-                b0 += nb;
+                Batch after = {0, 0, 0, 0};
+                if (nxt.nb) {
+                    search(half[h ^ 1], nxt);
+                    after = size_batch(nxt.first + nxt.nb);
+                    if (after.nb) {
+                        rows = rows_of(after);
+                        fetch_ahead(rows);
+                        clear(half[h], after);
+                    }
+                    __syncthreads();
+                }
+                nb_prev = cur.nb;
+                cur = nxt;
+                nxt = after;
+                h ^= 1;
             }
             if (out && threadIdx.x < staged) out[sh.rq_id[threadIdx.x]] = (uint64_t)sh.rq_x[threadIdx.x] << shift;
         }

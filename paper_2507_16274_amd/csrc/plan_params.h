@@ -31,14 +31,15 @@ constexpr int kBitmapShapes = 2;
 __host__ __device__ constexpr uint32_t bitmap_shape_waves(int shape) { return shape == 0 ? 8u : 16u; }
 
 // Which shape of the bitmap kernel places a trace with this mode word and sum of sizes in
-// granules (-1: none, the sorted-list kernels do).  A bitmap must be able to hold the whole
-// address range plus one word per request of a batch and a little slack.  Every kernel of a
-// call evaluates this same rule, so exactly one of them does the work.
+// granules (-1: none, the sorted-list kernels do).  Half of the pool (two batches are in
+// flight) must be able to hold one bitmap of the whole address range plus one word per
+// request of two batches and a little slack.  Every kernel of a call evaluates this same
+// rule, so exactly one of them does the work.
 __host__ __device__ inline int bitmap_shape(uint64_t mode, uint64_t granules, const uint32_t (&pool_words)[kBitmapShapes])
 {
     if (!(mode & kModeBitmap)) return -1;
     for (int shape = 0; shape < kBitmapShapes; ++shape)
-        if (pool_words[shape] != 0 && granules / 32 + bitmap_shape_waves(shape) + 5 <= pool_words[shape]) return shape;
+        if (pool_words[shape] != 0 && granules / 32 + 2 * bitmap_shape_waves(shape) + 5 <= pool_words[shape] / 2) return shape;
     return -1;
 }
 
