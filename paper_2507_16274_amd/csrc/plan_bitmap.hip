@@ -1,7 +1,7 @@
 // stalloc_plan, occupancy-bitmap variant: the same rule as the sorted-list kernel (Sec. 5.1:
 // requests in the given order, each at the lowest address where it conflicts with no earlier
 // request of the plan in lifespan and address range at once; extent = max(a + s), Eq. 2), for
-// traces whose whole address range is small when counted in granules.
+// traces whose requests are short when counted in granules.
 //
 // With g the largest power of two dividing all sizes, every address is a multiple of g and lies
 // below the sum of sizes.  When no request is longer than 31 granules and a bitmap of one bit per
@@ -12,21 +12,22 @@
 //            own (the potential conflicts of Sec. 5.1 do not depend on the order), rows padded
 //            to 256 entries with a dummy request that is never placed.
 //   build    One workgroup per plan, K requests per batch, one bitmap per request.  The rows of
-//            the K requests are cut into chunks of 256 entries which are dealt out to the waves
-//            round robin, so that every wave has the same amount of work whatever the row
-//            lengths.  A wave looks every neighbour of its chunk up in the plan's table of
-//            placed blocks (LDS, 4 bytes per request: address and the two word masks in a
-//            compressed form, 0 = not placed yet) and ORs the neighbour's granules into the
-//            bitmap of the request the chunk belongs to (LDS atomics: any wave may add to any
-//            bitmap).
+//            the K requests are cut into chunks of 256 entries which are dealt out to the waves,
+//            so that every wave has the same amount of work whatever the row lengths.  A wave
+//            looks every neighbour of its chunk up in the plan's table of placed blocks (LDS,
+//            4 bytes per request: address and the two word masks in a compressed form, 0 = not
+//            placed yet) and ORs the neighbour's granules into the bitmap of the request the
+//            chunk belongs to (LDS atomics: any wave may add to any bitmap).
 //   search   Wave r finds the first run of size_r zero bits in bitmap r: the lowest fit against
-//            everything placed before the batch.
-//   settle   Wave 0 takes the K requests in order.  A candidate stands unless a request settled
-//            earlier in the same batch overlaps it in lifetime and in address range; only then
-//            are those blocks ORed into the request's bitmap and the search repeated.  Adding
-//            blocks can only remove free runs, so an untouched candidate is still the lowest.
+//            what the bitmap holds.
+//   settle   Wave 0 takes the K requests in order.  A candidate stands unless a block the bitmap
+//            may have missed -- one of the batch before, or one settled earlier in the same
+//            batch -- overlaps it in lifetime and in address range; only then are those blocks
+//            ORed into the request's bitmap and the search repeated.  Adding blocks can only
+//            remove free runs, so an untouched candidate is still the lowest.
 //
-// Nothing is sorted or merged and no placement needs a second pass over a list.
+// Batches are software-pipelined over two halves of the bitmap pool: batch B is settled while
+// batch B + 1 is built.  Nothing is sorted or merged and no placement needs a second pass.
 #include "host_util.h"
 #include "plan_params.h"
 #include "wave.h"
