@@ -35,12 +35,12 @@
 namespace stalloc {
 
 #ifndef STALLOC_BITMAP_REFILL
-#define STALLOC_BITMAP_REFILL 128
+#define STALLOC_BITMAP_REFILL 16      // requests fetched per refill, per wave of the workgroup
 #endif
 #ifndef STALLOC_BITMAP_SHARES
 #define STALLOC_BITMAP_SHARES 2
 #endif
-constexpr int kBmBatch = STALLOC_BITMAP_REFILL;    // requests fetched per refill
+constexpr int kRefillPerWave = STALLOC_BITMAP_REFILL;   // (the pipeline of batches drains at every refill)
 constexpr uint32_t kShares = STALLOC_BITMAP_SHARES; // chunks a building wave takes for every one wave 0 takes
 constexpr int kBmWords = 1056;           // a pool of twice this many words is asked for before workgroups share a CU
 constexpr int kRowPad = 256;             // index rows are padded to this many entries (4 per lane)
@@ -49,6 +49,7 @@ constexpr uint32_t kBmMaxRequests = 32768;         // index entries are 16-bit r
 
 template <int kWaves>
 struct BitmapLds {
+    static constexpr int kBmBatch = kRefillPerWave * kWaves;     // 128 requests with eight waves, 256 with sixteen
     uint32_t rq_id[kBmBatch];
     uint32_t rq_s[kBmBatch];             // size in granules
     uint32_t rq_ta[kBmBatch];
@@ -313,8 +314,8 @@ __global__ void __launch_bounds__(kWaves * kWave, kWaves == 8 ? 8 : 4) plan_bitm
         for (uint32_t i = threadIdx.x; i <= n; i += kThreads) cells[i] = 0;     // nothing placed; cell n pads the rows
         if (threadIdx.x == 0) sh.top = 0;
 
-        for (uint32_t r0 = 0; r0 < n; r0 += kBmBatch) {
-            const uint32_t staged = n - r0 < (uint32_t)kBmBatch ? n - r0 : (uint32_t)kBmBatch;
+        for (uint32_t r0 = 0; r0 < n; r0 += Lds::kBmBatch) {
+            const uint32_t staged = n - r0 < (uint32_t)Lds::kBmBatch ? n - r0 : (uint32_t)Lds::kBmBatch;
             __syncthreads();                                  // previous refill fully consumed
             if (threadIdx.x < staged) {
                 uint32_t i = order[r0 + threadIdx.x];
