@@ -1,4 +1,5 @@
-// stalloc_plan: batched greedy placement, one workgroup per candidate placement order.
+// stalloc_plan: batched greedy placement, one workgroup per candidate placement order; the
+// entry point, and the placement kernel for traces the occupancy-bitmap kernel does not take.
 //
 // Rule (Sec. 5.1): requests are taken in the given order; each gets the lowest address at
 // which it conflicts with no earlier request of the same plan in lifespan and address
@@ -17,19 +18,18 @@
 //            its chunk maximum and its first few holes (with chunk-local "covered") to LDS.
 //   survey   After a barrier, wave r gathers what all waves published for request r into its
 //            64 lanes in address order; the true "covered" of a hole is the maximum of its
-//            local value and the chunk maxima of the waves below.  It records the first hole
-//            holes that are large enough as such.
-//   resolve  After another barrier, wave 0 settles the K requests in order: a request takes
-//            the first surveyed hole in which it still fits once the blocks settled earlier
-//            in the batch are cleared, else the top; if the surveyed holes run out while more
-//            were published, all published holes are looked at again with those blocks honoured.  The blocks already settled in this batch (the side buffer,
-//            sorted, one per lane) are honoured through f(c) = lowest address >= c that clears
-//            the side-buffer blocks conflicting with r: r takes the first hole with
-//            f(covered) + size_r <= hole end, else goes on top at f(maximum).  f is evaluated
-//            over "zones" -- maximal groups of conflicting side-buffer blocks whose holes are
-//            too small for r.  If a wave had more holes than it could publish and none of the
-//            earlier ones fits, the batch ends early and that one request takes the exact
-//            single-request path below.
+//            local value and the chunk maxima of the waves below.  It lists the first holes
+//            that are large enough as such.
+//   resolve  After another barrier, wave 0 settles the K requests in order.  The blocks
+//            settled earlier in the batch (the side buffer, sorted, one per lane) are honoured
+//            through f(c) = lowest address >= c that clears the side-buffer blocks conflicting
+//            with r: r takes the first surveyed hole with f(covered) + size_r <= hole end, else
+//            goes on top at f(maximum).  If the surveyed holes run out while more were
+//            published, all published holes are looked at with f evaluated over "zones" --
+//            maximal groups of conflicting side-buffer blocks whose holes are too small for r.
+//            If a wave had more holes than it could publish and none of the earlier ones
+//            fits, the batch ends early and that one request takes the exact single-request
+//            path below.
 //   merge    The settled blocks are merged into the sorted list in one pass: listed block k
 //            moves up by the number of new blocks at or below its start address and the new
 //            blocks drop into the gaps (in place through registers when the list is in LDS,
@@ -37,10 +37,11 @@
 //
 // Addresses are multiples of the largest power of two dividing all sizes.  When the sum of
 // sizes, in those granules, stays below 2^31 the list holds 32-bit granule counts (16-byte
-// entries, single-instruction max/compare/DPP); otherwise 64-bit byte addresses.  The trace
-// check leaves that decision in device memory, both instantiations are enqueued and the one
-// that does not apply returns at once.  The list lives in LDS when it fits and in the
-// workspace otherwise.
+// entries, single-instruction max/compare/DPP), below 2^16 (and with 16-bit timestamps) 8-byte
+// cells; otherwise 64-bit byte addresses.  Only the device knows which applies (the trace
+// check leaves it in the mode word), so every instantiation that could apply is enqueued and
+// all but one return at once.  The list lives in LDS when it fits and in the workspace
+// otherwise.
 #include "host_util.h"
 #include "plan_params.h"
 #include "wave.h"
@@ -832,7 +833,7 @@ extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uin
     prm.offsets = offsets ? offsets : own_offsets;
     prm.peaks = peaks; prm.status = device_status; prm.acc = acc; prm.slabs = slabs; prm.n = n; prm.P = P;
     prm.compact_enqueued = compact ? 1u : 0u;
-    prm.nbr_begin = nbr_begin; prm.nbr = nbr; 
+    prm.nbr_begin = nbr_begin; prm.nbr = nbr;
     for (int shape = 0; shape < kBitmapShapes; ++shape) prm.bitmap_pool_words[shape] = bitmap ? pool_words[shape] : 0u;
     bool ok = true;
     if (bitmap) ok = ok && launch_plan_bitmap(prm, di, stream);

@@ -48,6 +48,10 @@ def test_host_side_argument_errors_need_no_gpu():
     assert need.value > 0
     assert S.lib.stalloc_validate(ctypes.byref(tr), None, 3, None, None, None, None, ctypes.byref(need), None) == 0
     assert need.value > 0
+    # no trace, or no window at all
+    assert S.lib.stalloc_reusable_space(None, None, None, 1, 0, None, None, None, None, None, ctypes.byref(need), None) == 1
+    assert S.lib.stalloc_reusable_space(ctypes.byref(tr), None, None, 0, 0, None, None, None, None, None,
+                                        ctypes.byref(need), None) == 1
 
 
 def test_generators_match_the_configurations():
@@ -67,3 +71,8 @@ def test_generators_match_the_configurations():
         assert (np.diff(size[o[0]]) <= 0).all()               # row 0: descending size
         assert (np.diff(tr.t_alloc[o[2]].astype(np.int64)) > 0).all()   # row 2: by allocation time
     assert CONFIGS[5].n_orderings == 4096
+    from workloads import make_windows
+    tr = make_trace(2)
+    w = make_windows(tr, 1000)
+    assert w.shape == (1000, 2) and (w[:, 0] < w[:, 1]).all() and int(w[:, 1].max()) <= tr.t_end
+    assert np.array_equal(w, make_windows(tr, 1000)) and np.median(w[:, 1] - w[:, 0]) < tr.t_end // 20
