@@ -27,7 +27,8 @@
  *     that call is unspecified, but all kernels still terminate normally.
  *   - Lifetimes and address ranges are half-open; no alignment is applied; byte
  *     quantities are uint64_t; timestamps are uint32_t event ranks below t_end.
- *   - Calls that share a workspace or outputs must be ordered by the caller.
+ *   - Calls that share a workspace or outputs must be ordered by the caller; otherwise the
+ *     entry points may be called from several host threads at once.
  */
 #ifndef STALLOC_H
 #define STALLOC_H

@@ -6,6 +6,9 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+#include <mutex>
+
 #include "../../include/stalloc.h"
 
 namespace stalloc {
@@ -20,12 +23,14 @@ struct DeviceInfo {
     size_t lds_per_block = 0;   // largest LDS allocation one workgroup may use
 };
 
-// Properties of the current device (queried once per device).
+// Properties of the current device (queried once per device; callable from several host threads).
 inline bool device_info(DeviceInfo* out)
 {
     static DeviceInfo cache[64];
+    static std::mutex guard;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+    std::lock_guard<std::mutex> lock(guard);
     DeviceInfo& c = cache[dev];
     if (c.device != dev) {
         int cus = 0, lds = 0;

@@ -752,7 +752,7 @@ inline bool launch_plan(const PlanParams& prm, uint32_t grid, const DeviceInfo& 
     auto kernel = &plan_kernel<Addr, kLds, kCompact, kPend, kThreads>;
     size_t lds = sizeof(PlanLds<Addr, kPend, kThreads>) +
                  (kLds ? (size_t)prm.n * BlockList<Addr, kCompact>::kEntryBytes : 0);
-    static bool attr_set[64] = {};
+    static std::atomic<bool> attr_set[64] = {};        // (set twice at worst when threads race)
     if (kLds && !attr_set[di.device]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)di.lds_per_block) != hipSuccess)

@@ -543,7 +543,7 @@ static bool launch_shape(const PlanParams& prm, uint32_t wgs_per_cu, uint32_t po
 {
     auto kernel = entry_shift(prm.n) ? &plan_bitmap_kernel<kWaves, true> : &plan_bitmap_kernel<kWaves, false>;
     const size_t lds = sizeof(BitmapLds<kWaves>) + ((size_t)prm.n + 1 + pool_words) * sizeof(uint32_t);
-    static bool attr_set[64][2] = {};
+    static std::atomic<bool> attr_set[64][2] = {};     // (set twice at worst when threads race)
     if (!attr_set[di.device][entry_shift(prm.n) ? 1 : 0]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)di.lds_per_block) != hipSuccess)
