@@ -61,7 +61,7 @@ def main() -> int:
                     help="also run one plain device copy of this many MiB (reference dispatch for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (orders are independent and would be split "
+        print("bench.py: exactly one GPU is supported (orders are independent and would be split "
               "across GPUs, but no multi-GPU path exists); use --gpus 1", file=sys.stderr)
         return 2
 
