@@ -99,6 +99,19 @@ def test_large_configs_sampled_windows(S, oracle, cfg):
     _compare(S, oracle, tr.size, tr.t_alloc, tr.t_free, tr.t_end, a, windows, cap=4096, sample=range(0, 512, 16))
 
 
+def test_more_windows_than_resident_workgroups(S, oracle):
+    """6000 windows over a small plan: every workgroup answers several windows in a row."""
+    tr = make_trace(1)
+    order = make_orderings(tr, CONFIGS[1].n_orderings, rows=[1])[0]
+    a, _ = oracle.plan_allpairs(tr.size, tr.t_alloc, tr.t_free, order)
+    rng = np.random.default_rng(4100)
+    lo = rng.integers(0, tr.t_end, 6000)
+    hi = np.minimum(lo + rng.integers(1, 40, 6000), tr.t_end)
+    lo = np.minimum(lo, hi - 1)
+    windows = np.stack([lo, hi], axis=1).astype(np.uint32)
+    _compare(S, oracle, tr.size, tr.t_alloc, tr.t_free, tr.t_end, a, windows, cap=16)
+
+
 def test_reports_malformed_inputs(S):
     size, ts, te, a, windows = load_reusable_golden()
     status, *_ = _gpu(S, size, ts, te, int(te.max()), a, np.array([[0, 3], [4, 4]], np.uint32), 4)
