@@ -345,14 +345,30 @@ __global__ void __launch_bounds__(kWaves * kWave, kWaves == 8 ? 8 : 4) plan_bitm
                 b.nb = first >= staged ? 0u : (staged - first < fit ? staged - first : fit);
                 return b;
             };
+            // Which chunks a wave takes: wave 0 settles the previous batch while the others already
+            // build, so it gets a smaller share -- of every kShares * (kWaves - 1) + 1 chunks, kShares
+            // go to each of the waves 1 .. kWaves - 1 and the last one to wave 0.
+            constexpr uint32_t kPeriod = kShares * (kWaves - 1) + 1;
+            auto chunk_of = [&](uint32_t j) -> uint32_t {          // the wave's j-th chunk (ascending in j)
+                return wave == 0 ? j * kPeriod + (kPeriod - 1)
+                                 : (j / kShares) * kPeriod + (j % kShares) * (kWaves - 1) + (uint32_t)(wave - 1);
+            };
+            auto chunks_of_wave = [&](uint32_t total) -> uint32_t { // how many of `total` chunks are the wave's
+                const uint32_t full = total / kPeriod, rest = total % kPeriod;
+                if (wave == 0) return full;
+                uint32_t c = full * kShares;
+                for (uint32_t k = 0; k < kShares; ++k) c += k * (kWaves - 1) + (uint32_t)(wave - 1) < rest ? 1u : 0u;
+                return c;
+            };
             // The rows of a batch, cut into chunks and numbered through.  Lane q < 16 describes the row
-            // of request q of the batch.
-            struct Rows { uint32_t row, chunks, end, total; };
+            // of request q of the batch; `mine` = how many of the chunks are this wave's.
+            struct Rows { uint32_t row, chunks, end, total, mine; };
             auto rows_of = [&](const Batch& b) -> Rows {
-                Rows r = {0, 0, 0, 0};
+                Rows r = {0, 0, 0, 0, 0};
                 if (lane < (int)b.nb) { r.row = sh.rq_row[b.first + lane]; r.chunks = sh.rq_chunks[b.first + lane]; }
                 r.end = row_scan_add(r.chunks);                   // (nb <= 16: one DPP row)
                 r.total = read_lane(r.end, 15);
+                r.mine = chunks_of_wave(r.total);
                 return r;
             };
             // chunk f belongs to request q = number of rows that end at or before f
@@ -360,14 +376,6 @@ __global__ void __launch_bounds__(kWaves * kWave, kWaves == 8 ? 8 : 4) plan_bitm
                 q = (uint32_t)__builtin_popcountll(lanes_ge(f, r.end) & 0xffffull);
                 const uint32_t at = read_lane(r.row, (int)q) + f - (read_lane(r.end, (int)q) - read_lane(r.chunks, (int)q));
                 return index + (size_t)at * (kRowPad / 4);
-            };
-            // Which chunks a wave takes: wave 0 settles the previous batch while the others already
-            // build, so it gets a smaller share -- of every kShares * (kWaves - 1) + 1 chunks, kShares
-            // go to each of the waves 1 .. kWaves - 1 and the last one to wave 0.
-            auto chunk_of = [&](uint32_t j) -> uint32_t {
-                constexpr uint32_t kPeriod = kShares * (kWaves - 1) + 1;
-                return wave == 0 ? j * kPeriod + (kPeriod - 1)
-                                 : (j / kShares) * kPeriod + (j % kShares) * (kWaves - 1) + (uint32_t)(wave - 1);
             };
             // The index entries of a wave's first kAhead chunks of a batch are fetched when the batch is
             // sized, a whole batch before they are used: the index is far larger than the L2 and a
@@ -377,9 +385,8 @@ __global__ void __launch_bounds__(kWaves * kWave, kWaves == 8 ? 8 : 4) plan_bitm
             auto fetch_ahead = [&](const Rows& r) {
 #pragma unroll
                 for (int j = 0; j < kAhead; ++j) {
-                    const uint32_t f = chunk_of((uint32_t)j);
                     ahead_q[j] = 0;
-                    if (f < r.total) ahead[j] = *locate(r, f, ahead_q[j]);
+                    if ((uint32_t)j < r.mine) ahead[j] = *locate(r, chunk_of((uint32_t)j), ahead_q[j]);
                 }
             };
             auto lookup = [&](const uint2& ids, uint32_t (&cell)[4]) {
@@ -396,17 +403,17 @@ __global__ void __launch_bounds__(kWaves * kWave, kWaves == 8 ? 8 : 4) plan_bitm
             // build: table lookups of one chunk are in flight while the previous one is marked
             auto build = [&](uint32_t* bitmaps, const Batch& b, const Rows& rows) {
                 uint32_t cell[4] = {0, 0, 0, 0}, looked[4] = {0, 0, 0, 0};
-                if (chunk_of(0) < rows.total) lookup(ahead[0], cell);
+                if (rows.mine) lookup(ahead[0], cell);
 #pragma unroll
                 for (int j = 0; j < kAhead; ++j) {
-                    if (chunk_of((uint32_t)j) < rows.total) {
-                        if (j + 1 < kAhead && chunk_of((uint32_t)j + 1) < rows.total) lookup(ahead[j + 1 < kAhead ? j + 1 : j], looked);
+                    if ((uint32_t)j < rows.mine) {
+                        if (j + 1 < kAhead && (uint32_t)j + 1 < rows.mine) lookup(ahead[j + 1 < kAhead ? j + 1 : j], looked);
                         mark_cells(bitmaps + ahead_q[j] * b.stride, cell);
 #pragma unroll
                         for (int k = 0; k < 4; ++k) cell[k] = looked[k];
                     }
                 }
-                for (uint32_t j = kAhead; chunk_of(j) < rows.total; ++j) {                // (long rows only)
+                for (uint32_t j = kAhead; j < rows.mine; ++j) {                           // (long rows only)
                     uint32_t q;
                     const uint2 ids = *locate(rows, chunk_of(j), q);
                     lookup(ids, cell);
