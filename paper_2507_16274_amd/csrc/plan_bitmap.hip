@@ -57,14 +57,14 @@ struct BitmapLds {
     uint32_t rq_x[kBmBatch];             // address in granules
     uint32_t rq_row[kBmBatch];           // first chunk of the request's row of the index
     uint32_t rq_chunks[kBmBatch];        // chunks in that row
-    uint32_t cand[kWaves];               // lowest fit against the blocks placed before the batch
+    uint32_t cand[kWaves];               // lowest fit of each request of the batch against what its bitmap holds
     uint32_t top;                        // extent so far, granules
     uint32_t pad[3];
 };
-// Behind it in LDS: the plan's table of placed blocks (n + 1 words) and the pool the bitmaps of a
-// batch are carved from.  A bitmap is only as long as the plan's extent needs, so the pool
-// holds a full batch of them as long as the extent is moderate, and fewer (smaller batches)
-// beyond that; a pool of kBmWords words always holds one.
+// Behind it in LDS: the plan's table of placed blocks (n + 1 words) and the pool the bitmaps are
+// carved from, one half per batch in flight.  A bitmap is only as long as the plan's extent
+// needs, so a half holds a full batch of them as long as the extent is moderate, and fewer
+// (smaller batches) beyond that; the rule that admits a trace makes sure it always holds one.
 
 // ---------------------------------------------------------------------------------------------
 // Lifetime-conflict index.  begin[i] .. begin[i + 1] are the 256-entry chunks of request i's row;
@@ -301,9 +301,9 @@ __global__ void __launch_bounds__(kWaves * kWave, kWaves == 8 ? 8 : 4) plan_bitm
     if (bitmap_shape(prm.acc[kAccMode], prm.acc[kAccGranules], prm.bitmap_pool_words) != kShape) return;
     const uint32_t shift = (uint32_t)(prm.acc[kAccMode] & 63);
     const uint32_t pool_words = prm.bitmap_pool_words[kShape];
-    // the rule above keeps every address of a well-formed plan at or below this; a malformed order
-    // row (repeated requests) is clamped to it so that a bitmap never outgrows the pool
     const uint32_t half_words = pool_words / 2;        // two batches are in flight, each in its half of the pool
+    // the rule above keeps every address of a well-formed plan at or below `highest`; a malformed
+    // order row (repeated requests) is clamped to it so that a bitmap never outgrows its half
     const uint32_t highest = 32u * (half_words - 2 * kWaves - 5) + 31u;
     const int lane = lane_id(), wave = (int)uniform((uint32_t)wave_id());
     const uint2* index = reinterpret_cast<const uint2*>(prm.nbr) + lane;   // a chunk: 64 lanes x 4 entries
