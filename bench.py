@@ -57,6 +57,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--reusable", type=int, default=0, metavar="K",
                     help="also time stalloc_reusable_space for K windows over the best plan (reported beside the step)")
+    ap.add_argument("--checks", action="store_true",
+                    help="also time stalloc_validate (all plans; the best plan alone) and stalloc_lower_bound in timed "
+                         "regions of their own (reported beside the step)")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference dispatch for HBM byte counters)")
     args = ap.parse_args()
@@ -234,6 +237,51 @@ def main() -> int:
             wall = time.perf_counter() - t1
             result["reusable_space"]["cpu_baseline"] = {"value": sample / wall, "unit": "windows/s", "cores": 1,
                                                         "kind": "oracle", "sample": f"first {sample} windows"}
+
+    if args.checks:
+        # The two checking calls in timed regions of their own.  stalloc_validate tests every unordered
+        # pair of a plan: 4 compares, 3 ands and a count = 8 lane operations per pair; its bytes (24 per
+        # request and tile pass) are negligible.  stalloc_lower_bound streams the trace (16 B per request),
+        # scatters two 8-byte sums per request and passes twice over 8 B per timestamp.
+        def timed(fn):
+            for _ in range(max(args.warmup, 1)):
+                fn()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(args.steps):
+                out = fn()
+            b.record()
+            torch.cuda.synchronize()
+            return out, a.elapsed_time(b) / args.steps
+
+        def pair_roofline(plans, ms):
+            ops = 8 * (n * (n - 1) // 2) * plans
+            return {"plans": plans, "ms_per_call": ms, "pairs_per_s": ops / 8 / (ms * 1e-3),
+                    "roofline": {"bound": "alu", "kernel": "val_pairs", "achieved": ops / (ms * 1e-3) / 1e12,
+                                 "peak": ALU_PEAK_TOPS, "unit": "TOP/s", "frac": ops / (ms * 1e-3) / 1e12 / ALU_PEAK_TOPS,
+                                 "traffic": None, "algorithmic_ops": ops}}
+
+        cache_all, cache_one, cache_l = {}, {}, {}
+        best_row = plan["best_offsets"].clone().view(1, n)
+        all_rows = plan["offsets"].clone()
+        v_all, ms_all = timed(lambda: S.stalloc_validate(size, ta, tf, tr.t_end, all_rows, workspace_cache=cache_all))
+        v_one, ms_one = timed(lambda: S.stalloc_validate(size, ta, tf, tr.t_end, best_row, workspace_cache=cache_one))
+        l_out, ms_lb = timed(lambda: S.stalloc_lower_bound(size, ta, tf, tr.t_end, workspace_cache=cache_l))
+        S.check_status(v_all, "stalloc_validate")
+        S.check_status(v_one, "stalloc_validate")
+        S.check_status(l_out, "stalloc_lower_bound")
+        if int(v_all["conflicts"].sum().item()) != 0 or int(v_one["conflicts"].item()) != 0:
+            print("bench.py: a plan has conflicts", file=sys.stderr)
+            return 1
+        lb_bytes = 32 * n + 16 * stats["T"]
+        result["checks"] = {
+            "validate_all_plans": pair_roofline(P, ms_all),
+            "validate_best_plan": pair_roofline(1, ms_one),
+            "lower_bound": {"ms_per_call": ms_lb,
+                            "roofline": {"bound": "hbm", "kernel": "lb_* (6 launches)", "achieved": lb_bytes / (ms_lb * 1e-3) / 1e9,
+                                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": lb_bytes / (ms_lb * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                         "traffic": None, "algorithmic_bytes": lb_bytes}}}
 
     if not args.no_cpu_baseline:
         import oracle

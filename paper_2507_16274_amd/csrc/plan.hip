@@ -9,13 +9,17 @@
 // sorting is needed when a request is placed.  Requests are handled in batches of K:
 //
 //   scan     One pass over the sorted list serves the whole batch, because the list only
-//            changes between batches.  Each wave owns a run of consecutive entries and walks
-//            it 64 at a time; every entry is loaded once and tested against the K requests:
-//            a compare keeps the blocks whose lifetime conflicts with request r, a wave64
-//            running maximum (DPP) of their end addresses is "covered so far", and a
-//            conflicting block that starts at least size_r above it closes a hole
-//            [covered, start) in which r could fit.  Per (wave, request) the wave publishes
-//            its chunk maximum and its first few holes (with chunk-local "covered") to LDS.
+//            changes between batches.  Each wave owns a run of consecutive entries (its
+//            chunk); every entry is loaded once and tested against the K requests: two
+//            compares keep the blocks whose lifetime conflicts with request r, the running
+//            maximum of their end addresses is "covered so far", and a conflicting block that
+//            starts at least size_r above it closes a hole [covered, start) in which r could
+//            fit.  Per (wave, request) the wave publishes its chunk maximum and its first
+//            few holes (with chunk-local "covered") to LDS.  Two forms: with the list in LDS
+//            (K = 16) a lane holds a listed block and the running maximum is a wave64 DPP
+//            scan per request; with the list in the workspace (K = 64) a lane holds a
+//            request and the blocks are taken one by one as wave-uniform values, which needs
+//            no cross-lane step at all.
 //   survey   After a barrier, wave r gathers what all waves published for request r into its
 //            64 lanes in address order; the true "covered" of a hole is the maximum of its
 //            local value and the chunk maxima of the waves below.  It lists the first holes
@@ -28,8 +32,8 @@
 //            published, all published holes are looked at with f evaluated over "zones" --
 //            maximal groups of conflicting side-buffer blocks whose holes are too small for r.
 //            If a wave had more holes than it could publish and none of the earlier ones
-//            fits, the batch ends early and that one request takes the exact single-request
-//            path below.
+//            fits, wave 0 walks that wave's chunk again for this one request, with
+//            everything below the chunk known, and takes the chunk's first hole that fits.
 //   merge    The settled blocks are merged into the sorted list in one pass: listed block k
 //            moves up by the number of new blocks at or below its start address and the new
 //            blocks drop into the gaps (in place through registers when the list is in LDS,
@@ -49,7 +53,6 @@
 namespace stalloc {
 
 constexpr int kBatch = 256;          // requests fetched per refill
-constexpr int kPassEntries = 10240;  // list entries the single-request path covers between two barrier pairs
 
 template <typename Addr> struct Span { Addr lo, hi; };     // [lo, hi) in address units
 
@@ -61,17 +64,17 @@ template <typename Addr, int kPend, int kThreads>
 struct PlanLds {
     static constexpr int kWaves = kThreads / kWave;
 #ifdef STALLOC_HOLE_SLOTS
-    static constexpr int kSlots = STALLOC_HOLE_SLOTS;      // (test builds shrink this to exercise the exact path)
+    static constexpr int kSlots = STALLOC_HOLE_SLOTS;      // (test builds shrink this to exercise the second walk of a chunk)
 #else
-    static constexpr int kSlots = kWave / kWaves;          // holes a wave can publish per request
+    // holes a wave can publish per request; three when 64 requests with 64-bit addresses share
+    // a pass, so that two workgroups still fit the LDS of a CU
+    static constexpr int kSlots = (sizeof(Addr) == 8 && kPend > 32 && kWaves == 16) ? 3 : kWave / kWaves;
 #endif
     uint64_t rq_size[kBatch];
     uint64_t rq_addr[kBatch];
     uint32_t rq_ta[kBatch];
     uint32_t rq_tf[kBatch];
     uint32_t rq_id[kBatch];
-    Addr wave_top[kWaves];                                 // single-request path
-    Addr wave_hit[kWaves];
     Addr top[kWaves][kPend];                               // chunk maximum per (wave, request)
     uint32_t holes[kWaves][kPend];                         // holes found per (wave, request), may exceed kSlots
     Span<Addr> hole[kWaves][kPend][kSlots];                // {hole end, chunk-local covered}
@@ -306,6 +309,59 @@ __device__ __forceinline__ void scan_batch(const List& list, uint32_t count, uin
     }
 }
 
+// The same pass with the roles of lanes and loop exchanged, for lists in the workspace: lane r
+// holds request r of the batch (up to 64 of them) and the listed blocks of the wave's chunk
+// are taken one at a time, in address order, as wave-uniform values.  A block costs two
+// lifetime compares, an add and two address compares for all requests at once -- no
+// cross-lane running maximum, which is what the lane-per-block form spends its time on when
+// one pass serves many requests.  What is published per (wave, request) is identical.
+template <typename Addr, int kPend, int kThreads, typename List, typename Lds>
+__device__ __forceinline__ void scan_batch_by_request(const List& list, uint32_t count, uint32_t b0, uint32_t nb,
+                                                      uint32_t shift, Lds& sh)
+{
+    constexpr int kSlots = Lds::kSlots;
+    static_assert(kPend <= kWave, "one lane per request of the batch");
+    const int lane = lane_id(), wave = wave_id();
+    // unused lanes get an empty lifetime (conflicts with nothing)
+    Addr rq_s = 0;
+    uint32_t rq_ta = 0, rq_tf = 0;
+    if (lane < (int)nb) {
+        rq_s = (Addr)(sh.rq_size[b0 + lane] >> shift);
+        rq_ta = sh.rq_ta[b0 + lane];
+        rq_tf = sh.rq_tf[b0 + lane];
+    }
+    Addr covered = 0;        // per request: maximum end of the conflicting blocks of this chunk so far
+    uint32_t found = 0;      // per request: holes found in this chunk
+    const uint32_t sub = (count + kThreads - 1) / kThreads;     // 64-entry steps per wave
+    const uint32_t chunk0 = (uint32_t)wave * kWave * sub;
+    for (uint32_t j = 0; j < sub; ++j) {
+        const uint32_t k0 = chunk0 + j * kWave;
+        if (k0 >= count) break;                                  // (uniform)
+        const uint32_t k = k0 + lane;
+        const bool valid = k < count;
+        const typename List::Entry en = list.load(valid ? k : count - 1);
+        const Addr e_lo = en.lo(), e_hi = en.hi();
+        // lanes past the end of the list get a lifetime that conflicts with nothing
+        const uint32_t e_ta = valid ? en.ta() : 0xffffffffu, e_tf = valid ? en.tf() : 0u;
+#pragma unroll
+        for (int q = 0; q < kWave; ++q) {
+            const uint32_t ta_q = read_lane(e_ta, q), tf_q = read_lane(e_tf, q);
+            const Addr lo_q = read_lane(e_lo, q), hi_q = read_lane(e_hi, q);
+            const bool conflict = ta_q < rq_tf && rq_ta < tf_q;
+            if (conflict && lo_q >= (Addr)(covered + rq_s)) {    // a hole [covered, lo_q) in front of this block
+                if (found < (uint32_t)kSlots) sh.hole[wave][lane][found] = Span<Addr>{lo_q, covered};
+                found = found < (uint32_t)kSlots ? found + 1 : (uint32_t)kSlots + 1;   // kSlots + 1: more holes than slots
+            }
+            const Addr reach = umax(covered, hi_q);
+            covered = conflict ? reach : covered;
+        }
+    }
+    if (lane < kPend) {
+        sh.top[wave][lane] = covered;
+        sh.holes[wave][lane] = found;
+    }
+}
+
 // What the waves published for request r, gathered into the 64 lanes of one wave in address
 // order (lane = wave * kSlots + slot), with the true "covered" of every hole.
 template <typename Addr>
@@ -313,6 +369,7 @@ struct HoleView {
     Addr covered;        // per lane: covered in front of this hole (chunk maxima of lower waves included)
     Addr end;            // per lane: address at which the hole ends
     Addr top;            // uniform: maximum over all chunks (where the request goes if no hole fits)
+    Addr below;          // per lane: maximum over the chunks of the waves below this lane's wave
     uint64_t published;  // lanes that hold a hole
     uint64_t crowded;    // lanes of waves that found more holes than they could publish
 };
@@ -332,6 +389,7 @@ __device__ __forceinline__ HoleView<Addr> view_holes(const Lds& sh, uint32_t r)
     const Addr below = lane_gather(wave_shift_up(incl, (Addr)0), wc * kSlots);
     HoleView<Addr> v;
     v.covered = umax(below, hl.hi);
+    v.below = below;
     v.end = hl.lo;
     v.top = read_lane(incl, kWave - 1);
     v.published = lanes_lt((uint32_t)c, found);
@@ -386,10 +444,46 @@ __device__ __forceinline__ Addr clear_rivals(Addr c, Addr s, uint64_t rivals, co
     }
 }
 
-// Wave 0 settles the requests of the batch in order.  Returns how many were settled; fewer
-// than nb means request b0 + result needs the exact single-request path.
-template <typename Addr, int kPend, int kThreads, typename Lds>
-__device__ __forceinline__ uint32_t resolve_batch(uint32_t b0, uint32_t nb, uint32_t shift, Addr& peak, Lds& sh)
+// One wave walks the chunk of the list that wave `w` scanned, for one request, with everything
+// below the chunk known (`below` = maximum end of the conflicting blocks of all lower chunks):
+// the first hole of the chunk that takes the request once the zones of the side buffer are
+// cleared.  Returns true and the address if there is one.  This is what a wave could not
+// publish when its chunk held more holes than it has slots.
+template <typename Addr, int kThreads, typename List>
+__device__ __forceinline__ bool chunk_lowest_fit(const List& list, uint32_t count, int w, Addr below, Addr s,
+                                                 uint32_t ta, uint32_t tf, const Zones<Addr>& zones, Addr& x)
+{
+    const int lane = lane_id();
+    const uint32_t sub = (count + kThreads - 1) / kThreads;     // 64-entry steps per wave, as in the scan
+    const uint32_t chunk0 = (uint32_t)w * kWave * sub;
+    Addr run = below;
+    typename List::Entry ahead = List::none();
+    if (chunk0 + lane < count) ahead = list.load(chunk0 + lane);
+    for (uint32_t j = 0; j < sub; ++j) {
+        const uint32_t k0 = chunk0 + j * kWave;
+        if (k0 >= count) break;                                  // (uniform)
+        const typename List::Entry en = ahead;
+        const bool valid = k0 + lane < count;
+        if (j + 1 < sub && k0 + kWave + lane < count) ahead = list.load(k0 + kWave + lane);
+        const Addr e_lo = en.lo();
+        const bool conflict = valid && en.ta() < tf && ta < en.tf();
+        const Addr incl = wave_scan_max(conflict ? (Addr)en.hi() : (Addr)0);
+        const Addr before = umax(run, wave_shift_up(incl, (Addr)0));
+        const bool opens = conflict && e_lo >= (Addr)(before + s);            // a hole [before, e_lo) large enough as such
+        if (__builtin_amdgcn_ballot_w64(opens)) {
+            const Addr cleared = clear_zones(before, s, zones);
+            const uint64_t fits = __builtin_amdgcn_ballot_w64(opens && e_lo >= (Addr)(cleared + s));
+            if (fits) { x = read_lane(cleared, __builtin_ctzll(fits)); return true; }
+        }
+        run = umax(run, read_lane(incl, kWave - 1));
+    }
+    return false;
+}
+
+// Wave 0 settles the requests of the batch in order.  Returns how many were settled (all).
+template <typename Addr, int kPend, int kThreads, typename List, typename Lds>
+__device__ __forceinline__ uint32_t resolve_batch(const List& list, uint32_t count, uint32_t b0, uint32_t nb,
+                                                  uint32_t shift, Addr& peak, Lds& sh)
 {
     const int lane = lane_id();
     // lane r holds request r of the batch
@@ -429,8 +523,17 @@ __device__ __forceinline__ uint32_t resolve_batch(uint32_t b0, uint32_t nb, uint
                 const Addr cleared = clear_zones(v.covered, s, zones);
                 const uint64_t fits = v.published & lanes_ge(v.end, (Addr)(cleared + s));
                 const int h = fits ? __builtin_ctzll(fits) : -1;
-                if (unpublished_below<Lds>(v.crowded, h)) break;
-                x = fits ? read_lane(cleared, h) : read_lane(clear_zones(v.top, s, zones), 0);
+                // chunks with more holes than their wave could publish, lowest first, as long as
+                // they lie below the chunk of hole h: the lowest fit may be one of those
+                bool lower = false;
+                for (uint64_t crowded = v.crowded; unpublished_below<Lds>(crowded, h);) {
+                    const int first = __builtin_ctzll(crowded);
+                    const int w = first / Lds::kSlots;
+                    lower = chunk_lowest_fit<Addr, kThreads>(list, count, w, read_lane(v.below, first), s, ta, tf, zones, x);
+                    if (lower) break;
+                    for (int c = 0; c < Lds::kSlots; ++c) crowded &= ~(1ull << (w * Lds::kSlots + c));
+                }
+                if (!lower) x = fits ? read_lane(cleared, h) : read_lane(clear_zones(v.top, s, zones), 0);
             }
         }
         peak = umax(peak, (Addr)(x + s));
@@ -443,69 +546,6 @@ __device__ __forceinline__ uint32_t resolve_batch(uint32_t b0, uint32_t nb, uint
     }
     if (lane == 0) sh.settled = r;
     return r;
-}
-
-// Exact placement of one request against the sorted list alone (no side buffer): lowest
-// address x such that [x, x + s) meets no listed block whose lifetime conflicts with [ta, tf).
-// All threads of the workgroup call this together; the result is uniform.
-template <typename Addr, int kThreads, typename List, typename Lds>
-__device__ __forceinline__ Addr lowest_fit(const List& list, uint32_t count, Addr s, uint32_t ta,
-                                           uint32_t tf, Lds& sh)
-{
-    constexpr int kWaves = kThreads / kWave;
-    constexpr int kMaxSub = kPassEntries / kThreads;
-    constexpr Addr kNoHit = Top<Addr>::value;
-    const int lane = lane_id(), wave = wave_id();
-    Addr covered = 0;                    // first address not blocked by listed blocks so far
-    if (count == 0) return covered;
-    const uint32_t last = count - 1;
-
-    for (uint32_t base = 0;;) {
-        const uint32_t left = count - base;
-        uint32_t sub = (left + kThreads - 1) / kThreads;         // 64-entry steps per wave in this pass
-        if (sub > (uint32_t)kMaxSub) sub = kMaxSub;
-        const uint32_t chunk0 = base + (uint32_t)wave * kWave * sub;
-        Addr run = 0;
-        Addr hit = kNoHit;
-        for (uint32_t j = 0; j < sub; ++j) {
-            const uint32_t k = chunk0 + j * kWave + lane;
-            const bool valid = k < count;
-            const typename List::Entry en = list.load(valid ? k : last);
-            const Span<Addr> sp = {en.lo(), en.hi()};
-            const uint2 lf = make_uint2(en.ta(), en.tf());
-            const bool conflict = valid && lf.x < tf && ta < lf.y;
-            const Addr incl = wave_scan_max(conflict ? sp.hi : (Addr)0);
-            run = umax(run, read_lane(incl, kWave - 1));
-        }
-        if (lane == 0) sh.wave_top[wave] = run;
-        __syncthreads();
-        const Addr tops = row_scan_max(lane < kWaves ? sh.wave_top[lane] : (Addr)0);
-        const Addr below = umax(covered, wave > 0 ? read_lane(tops, wave - 1) : (Addr)0);
-        const Addr all = umax(covered, read_lane(tops, kWaves - 1));
-        // second walk with everything below known: first block that starts >= s above "covered"
-        run = below;
-        for (uint32_t j = 0; j < sub && hit == kNoHit; ++j) {
-            const uint32_t k = chunk0 + j * kWave + lane;
-            const bool valid = k < count;
-            const typename List::Entry en = list.load(valid ? k : last);
-            const Span<Addr> sp = {en.lo(), en.hi()};
-            const uint2 lf = make_uint2(en.ta(), en.tf());
-            const bool conflict = valid && lf.x < tf && ta < lf.y;
-            const Addr incl = wave_scan_max(conflict ? sp.hi : (Addr)0);
-            const Addr before = umax(run, wave_shift_up(incl, (Addr)0));
-            const uint64_t stops = __builtin_amdgcn_ballot_w64(valid && sp.lo >= before + s);
-            if (stops) hit = read_lane(before, __builtin_ctzll(stops));
-            run = umax(run, read_lane(incl, kWave - 1));
-        }
-        if (lane == 0) sh.wave_hit[wave] = hit;
-        __syncthreads();
-        const Addr h = lane < kWaves ? sh.wave_hit[lane] : kNoHit;
-        const uint64_t hits = __builtin_amdgcn_ballot_w64(h != kNoHit);
-        if (hits) return read_lane(h, __builtin_ctzll(hits));
-        covered = all;
-        base += kThreads * sub;
-        if (base >= count) return covered;
-    }
 }
 
 // Number of pending blocks (sorted, one per lane) whose start address is <= lo.
@@ -645,34 +685,18 @@ __global__ void __launch_bounds__(kThreads, 4) plan_kernel(PlanParams prm)   // 
 
             for (uint32_t b0 = 0; b0 < staged;) {
                 const uint32_t nb = staged - b0 < (uint32_t)kPend ? staged - b0 : (uint32_t)kPend;
-                scan_batch<Addr, kPend, kThreads>(list, count, b0, nb, shift, sh);
+                if constexpr (kLds) scan_batch<Addr, kPend, kThreads>(list, count, b0, nb, shift, sh);
+                else scan_batch_by_request<Addr, kPend, kThreads>(list, count, b0, nb, shift, sh);
                 __syncthreads();
                 survey_batch<Addr, kPend, kThreads>(b0, nb, shift, sh);
                 __syncthreads();
-                if (wave_id() == 0) resolve_batch<Addr, kPend, kThreads>(b0, nb, shift, peak, sh);
+                if (wave_id() == 0) resolve_batch<Addr, kPend, kThreads>(list, count, b0, nb, shift, peak, sh);
                 __syncthreads();
                 const uint32_t settled = sh.settled;
                 const bool last_of_plan = r0 + b0 + settled >= n;
                 if (settled && !last_of_plan) merge_pending<Addr, kLds, kThreads>(list, spare, count, settled, sh);
                 count += settled;
                 b0 += settled;
-                if (settled < nb) {
-                    // request b0 could not be settled from the published holes: exact path
-                    const Addr s = (Addr)(sh.rq_size[b0] >> shift);
-                    const uint32_t ta = sh.rq_ta[b0], tf = sh.rq_tf[b0];
-                    const Addr x = lowest_fit<Addr, kThreads>(list, count, s, ta, tf, sh);
-                    __syncthreads();                          // everyone has read sh.settled / pend_*
-                    if (threadIdx.x == 0) {
-                        peak = umax(peak, (Addr)(x + s));
-                        sh.rq_addr[b0] = (uint64_t)x << shift;
-                        sh.pend_span[0] = Span<Addr>{x, (Addr)(x + s)};
-                        sh.pend_life[0] = make_uint2(ta, tf);
-                    }
-                    __syncthreads();
-                    if (r0 + b0 + 1 < n) merge_pending<Addr, kLds, kThreads>(list, spare, count, 1u, sh);
-                    count += 1;
-                    b0 += 1;
-                }
             }
             // addresses of this batch -> offsets[p][request id]
             __syncthreads();
@@ -719,7 +743,7 @@ __global__ void __launch_bounds__(256) plan_copy_best(const uint64_t* __restrict
 #define STALLOC_PEND_LDS 16
 #endif
 #ifndef STALLOC_PEND_MEM
-#define STALLOC_PEND_MEM 32
+#define STALLOC_PEND_MEM 64
 #endif
 #ifndef STALLOC_THREADS_LDS
 #define STALLOC_THREADS_LDS 1024
@@ -753,7 +777,7 @@ inline bool launch_plan(const PlanParams& prm, uint32_t grid, const DeviceInfo& 
     size_t lds = sizeof(PlanLds<Addr, kPend, kThreads>) +
                  (kLds ? (size_t)prm.n * BlockList<Addr, kCompact>::kEntryBytes : 0);
     static std::atomic<bool> attr_set[64] = {};        // (set twice at worst when threads race)
-    if (kLds && !attr_set[di.device]) {
+    if (!attr_set[di.device]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)di.lds_per_block) != hipSuccess)
             return false;
