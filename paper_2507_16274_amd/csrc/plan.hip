@@ -346,8 +346,9 @@ __device__ __forceinline__ void scan_batch_by_request(const List& list, uint32_t
 #pragma unroll
         for (int q = 0; q < kWave; ++q) {
             const uint32_t ta_q = read_lane(e_ta, q), tf_q = read_lane(e_tf, q);
-            const Addr lo_q = read_lane(e_lo, q), hi_q = read_lane(e_hi, q);
             const bool conflict = ta_q < rq_tf && rq_ta < tf_q;
+            if (__builtin_amdgcn_ballot_w64(conflict) == 0) continue;   // (uniform) the block concerns no request of the batch
+            const Addr lo_q = read_lane(e_lo, q), hi_q = read_lane(e_hi, q);
             if (conflict && lo_q >= (Addr)(covered + rq_s)) {    // a hole [covered, lo_q) in front of this block
                 if (found < (uint32_t)kSlots) sh.hole[wave][lane][found] = Span<Addr>{lo_q, covered};
                 found = found < (uint32_t)kSlots ? found + 1 : (uint32_t)kSlots + 1;   // kSlots + 1: more holes than slots
@@ -548,13 +549,14 @@ __device__ __forceinline__ uint32_t resolve_batch(const List& list, uint32_t cou
     return r;
 }
 
-// Number of pending blocks (sorted, one per lane) whose start address is <= lo.
+// Number of pending blocks (sorted by start address, one per lane) whose start address is
+// <= lo, for a wave-uniform lo; `from` of them are already known to be.
 template <typename Addr>
-__device__ __forceinline__ uint32_t pending_at_or_below(const Pending<Addr>& pd, uint32_t pending, Addr lo)
+__device__ __forceinline__ uint32_t pending_at_or_below(const Pending<Addr>& pd, uint32_t pending, Addr lo, uint32_t from)
 {
-    uint32_t c = 0;
-    for (uint32_t q = 0; q < pending; ++q) c += read_lane(pd.lo, (int)q) <= lo;
-    return c;
+    uint32_t q = from;
+    while (q < pending && read_lane(pd.lo, (int)q) <= lo) ++q;
+    return q;
 }
 
 // One merge pass over the list entries [base, base + kThreads * kSub) and, if it falls into that
@@ -567,14 +569,19 @@ __device__ __forceinline__ void merge_pass(const List& list, const List& dst, ui
                                            uint32_t base, const Pending<Addr>& pd, uint32_t pending, Lds& sh)
 {
     const int lane = lane_id(), wave = wave_id();
-    const Addr p_lowest = read_lane(pd.lo, 0), p_highest = read_lane(pd.lo, (int)pending - 1);
     const uint32_t chunk0 = base + (uint32_t)wave * kWave * kSub;
     typename List::Entry en[kSub];
     uint32_t c_here[kSub], c_prev[kSub];
     // pending blocks at or below the entry in front of this wave's chunk
     uint32_t carry = 0;
-    if (chunk0 > 0 && chunk0 - 1 < count) carry = pending_at_or_below(pd, pending, (Addr)list.load(chunk0 - 1).lo());
-    else if (chunk0 > count) carry = pending;
+    if (chunk0 > 0 && chunk0 - 1 < count) {
+        const Addr lo_before = read_lane((Addr)list.load(chunk0 - 1).lo(), 0);
+        for (uint32_t step = 32; step > 0; step >>= 1)           // (the one place without a known starting point)
+            if (carry + step <= pending && read_lane(pd.lo, (int)(carry + step - 1)) <= lo_before) carry += step;
+        if (carry < pending && read_lane(pd.lo, (int)carry) <= lo_before) ++carry;
+    } else if (chunk0 > count) {
+        carry = pending;
+    }
 #pragma unroll
     for (int j = 0; j < kSub; ++j) {
         const uint32_t k0 = chunk0 + j * kWave;
@@ -583,12 +590,17 @@ __device__ __forceinline__ void merge_pass(const List& list, const List& dst, ui
         en[j] = List::none();
         if (valid) en[j] = list.load(k);
         const Addr lo_j = en[j].lo();
-        // most 64-entry steps lie entirely below the lowest or at/above the highest pending block
+        // Both sequences ascend, so the counts of a step lie between those of its first and last
+        // block, and the first one starts from the previous step's last: the pending blocks are
+        // walked once per chunk, and only the few that fall inside a step are compared per lane.
         uint32_t c = pending;
         if (k0 < count) {
             const int last_lane = count - k0 >= (uint32_t)kWave ? kWave - 1 : (int)(count - k0 - 1);
-            if (p_lowest > read_lane(lo_j, last_lane)) c = valid ? 0u : pending;
-            else if (p_highest > read_lane(lo_j, 0)) c = valid ? pending_at_or_below(pd, pending, lo_j) : pending;
+            const uint32_t c_first = pending_at_or_below(pd, pending, read_lane(lo_j, 0), carry);
+            const uint32_t c_last = pending_at_or_below(pd, pending, read_lane(lo_j, last_lane), c_first);
+            uint32_t mine = c_first;
+            for (uint32_t q = c_first; q < c_last; ++q) mine += read_lane(pd.lo, (int)q) <= lo_j;
+            c = valid ? mine : pending;
         }
         c_here[j] = c;
         c_prev[j] = wave_shift_up(c, carry);
