@@ -20,6 +20,7 @@ __global__ void __launch_bounds__(256)
 trace_check_scan(const uint64_t* __restrict__ size, const uint32_t* __restrict__ ta,
                  const uint32_t* __restrict__ tf, uint32_t n, uint32_t t_end, uint64_t* acc)
 {
+    __shared__ uint64_t part[4][5];                  // per wave: hi, lo, bad, bits, largest
     uint64_t hi = 0, lo = 0, bits = 0, largest = 0;
     uint32_t bad = 0;
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
@@ -36,7 +37,17 @@ trace_check_scan(const uint64_t* __restrict__ size, const uint32_t* __restrict__
     bits = wave_or64(bits);
     largest = wave_max64(largest);
     uint64_t any_bad = __builtin_amdgcn_ballot_w64(bad != 0);
+    // one set of atomics per workgroup: thousands of waves on five words would queue up
     if (lane_id() == 0) {
+        uint64_t* mine = part[wave_id()];
+        mine[0] = hi; mine[1] = lo; mine[2] = any_bad ? 1 : 0; mine[3] = bits; mine[4] = largest;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w) {
+            hi += part[w][0]; lo += part[w][1]; any_bad |= part[w][2]; bits |= part[w][3];
+            largest = umax64(largest, part[w][4]);
+        }
         atomicAdd((unsigned long long*)&acc[0], (unsigned long long)hi);
         atomicAdd((unsigned long long*)&acc[1], (unsigned long long)lo);
         if (any_bad) atomicOr((unsigned long long*)&acc[2], 1ull);
@@ -70,7 +81,7 @@ void launch_trace_check(const stalloc_trace& tr, uint64_t* acc, uint32_t* device
 {
     hipLaunchKernelGGL(trace_check_init, dim3(1), dim3(64), 0, stream, acc, device_status);
     uint32_t blocks = (tr.n + 255) / 256;
-    if (blocks > 1024) blocks = 1024;
+    if (blocks > 256) blocks = 256;
     hipLaunchKernelGGL(trace_check_scan, dim3(blocks), dim3(256), 0, stream, tr.size, tr.t_alloc, tr.t_free,
                        tr.n, tr.t_end, acc);
     hipLaunchKernelGGL(trace_check_finish, dim3(1), dim3(64), 0, stream, acc, device_status);
