@@ -193,8 +193,10 @@ def main() -> int:
 
     if args.reusable:
         # Dynamic reusable space of the best plan (Sec. 5.2) for K layer-like windows: its own timed
-        # region.  Algorithmic work: every window looks at every decision once, 24 B (address range,
-        # lifespan) and 8 lane operations (two compares, select, 64-bit running maximum, compare).
+        # region.  Algorithmic work: every window looks at every decision once: 8 lane operations (two
+        # compares, select, 64-bit running maximum, compare).  The 24 B of a decision (address range,
+        # lifespan) serve many windows at once, so the bytes that must move are the plan, the windows
+        # and the answers only; the figure for one read per window is kept for comparison.
         from workloads import make_windows
         K = args.reusable
         windows_np = make_windows(tr, K, seed=7000 + args.config)
@@ -213,14 +215,17 @@ def main() -> int:
         S.check_status(rs, "stalloc_reusable_space")
         rs_ms = e0.elapsed_time(e1) / args.steps
         rs_bytes, rs_ops = 24 * n * K, 8 * n * K
-        # the byte floor (at the HBM rate) is the larger of the two for any n and K
+        mean_intervals = float(rs["counts"].float().mean().item())
+        must_move = 24 * n + 8 * K + K * (12 + 16 * min(mean_intervals, cap))
         result["reusable_space"] = {
             "windows": K, "ms_per_call": rs_ms, "windows_per_s": K / (rs_ms * 1e-3),
-            "mean_intervals": float(rs["counts"].float().mean().item()),
-            "roofline": {"bound": "hbm", "kernel": "rs_sweep (+ rs_rank, rs_scatter)", "achieved": rs_bytes / (rs_ms * 1e-3) / 1e9,
-                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": rs_bytes / (rs_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                         "traffic": None, "algorithmic_bytes": rs_bytes,
-                         "floor_ms": {"hbm": rs_bytes / (HBM_PEAK_GBS * 1e9) * 1e3, "alu": rs_ops / (ALU_PEAK_TOPS * 1e12) * 1e3}}}
+            "mean_intervals": mean_intervals,
+            "roofline": {"bound": "alu", "kernel": "rs_sweep / rs_sweep_by_window (+ rs_rank, rs_scatter)",
+                         "achieved": rs_ops / (rs_ms * 1e-3) / 1e12, "peak": ALU_PEAK_TOPS, "unit": "TOP/s",
+                         "frac": rs_ops / (rs_ms * 1e-3) / 1e12 / ALU_PEAK_TOPS,
+                         "traffic": None, "algorithmic_ops": rs_ops, "algorithmic_bytes": must_move,
+                         "one_read_per_window_GBs": rs_bytes / (rs_ms * 1e-3) / 1e9,
+                         "floor_ms": {"hbm": must_move / (HBM_PEAK_GBS * 1e9) * 1e3, "alu": rs_ops / (ALU_PEAK_TOPS * 1e12) * 1e3}}}
         if not args.no_cpu_baseline:
             import oracle
             oracle.build()

@@ -134,6 +134,8 @@ int stalloc_lower_bound(const stalloc_trace *trace, uint64_t *lower_bound, uint3
  *               window; may be NULL when max_ranges == 0
  *   counts      device [k], number of intervals of each window (may exceed max_ranges)
  *   idle_bytes  device [k], total length of all intervals of each window; may be NULL
+ *
+ * The workspace size depends on n and k: query it with the k of the call.
  */
 int stalloc_reusable_space(const stalloc_trace *trace, const uint64_t *offsets,
                            const uint32_t *windows, uint32_t k, uint32_t max_ranges,

@@ -20,6 +20,12 @@
 //            "covered" it starts from; (2) the number of intervals per wave, which gives every wave
 //            its place in the output; (3) the intervals themselves.  What lies between the last
 //            covered address and the end of the pool is the final interval.
+//            With thousands of windows the roles are exchanged: a workgroup takes 64 windows, one
+//            per lane, each of its 16 waves a contiguous part of the sorted decisions, which
+//            are taken one at a time as wave-uniform values -- two compares per decision tell
+//            for all 64 windows whether it counts (most decisions count for none and are done
+//            with), and "covered so far" is a per-lane maximum without any cross-lane step.  The
+//            same three walks, at a fraction of the instructions per decision and window.
 #include "host_util.h"
 #include "wave.h"
 
@@ -233,6 +239,116 @@ __global__ void __launch_bounds__(kRsThreads) rs_sweep(RsArgs g)
     }
 }
 
+#ifndef STALLOC_RS_WIDE_FROM
+#define STALLOC_RS_WIDE_FROM (1ull << 23)
+#endif
+// A lane takes a window from this many decisions x windows on (three launches and per-part
+// prefixes cost more than they save below it), given at least half a wave of windows.
+constexpr uint64_t kRsWideFrom = STALLOC_RS_WIDE_FROM;
+__host__ inline bool rs_window_per_lane(uint32_t n, uint32_t k) { return k >= 32 && (uint64_t)n * k >= kRsWideFrom; }
+constexpr uint32_t kRsMaxParts = 256;                    // parts the sorted plan is cut into, at most
+
+// Scratch of the window-per-lane sweep, [group of 64 windows][part][lane].
+struct RsParts {
+    uint64_t* reach;        // walk 1: maximum end of the counting decisions of the part
+    uint64_t* idle;         // walk 2: bytes of the idle intervals closed inside the part
+    uint32_t* found;        //         and their number
+    uint32_t parts;         // parts per group; one wave each
+    uint32_t steps;         // 64-decision steps per part
+};
+
+// One wave = 64 windows (one per lane) x one part of the sorted plan.  kWalk = 1, 2, 3: the
+// three walks, one launch each (a part needs the results of all lower parts of the walk before).
+template <int kWalk>
+__global__ void __launch_bounds__(kRsThreads) rs_sweep_by_window(RsArgs g, RsParts sc)
+{
+    if (*g.status != STALLOC_OK) return;
+    const int lane = lane_id();
+    const uint32_t groups = (g.k + kWave - 1) / kWave;
+    const uint32_t waves = groups * sc.parts;
+    for (uint32_t unit = blockIdx.x * kRsWaves + (uint32_t)wave_id(); unit < waves; unit += gridDim.x * kRsWaves) {
+        const uint32_t grp = unit / sc.parts, part = unit % sc.parts;
+        const uint32_t w = grp * kWave + lane;
+        // lanes without a window, and malformed windows, get bounds that no lifespan meets
+        uint32_t w_lo = 1, w_hi = 0;
+        bool live = false;
+        if (w < g.k) {
+            const uint32_t lo = g.windows[2 * w], hi = g.windows[2 * w + 1];
+            if (lo < hi) { w_lo = lo; w_hi = hi; live = true; }
+            else if (kWalk == 1 && part == 0) atomicMax(g.status, (uint32_t)STALLOC_ERR_BAD_WINDOW);
+        }
+        const size_t row = ((size_t)grp * sc.parts) * kWave + lane;        // [grp][0][lane]; next part: + kWave
+        const uint32_t first = part * sc.steps * kWave;
+        // body(start, end, counts): called for every decision of this part that counts for at
+        // least one window, in address order, with wave-uniform start and end
+        auto walk = [&](auto&& body) {
+            for (uint32_t s = 0; s < sc.steps; ++s) {
+                const uint32_t k0 = first + s * kWave;
+                if (k0 >= g.n) break;                                     // (uniform)
+                const uint32_t at = k0 + lane;
+                const bool valid = at < g.n;
+                const uint2 life = valid ? g.s_life[at] : make_uint2(0xffffffffu, 0u);   // past the end: meets no window
+                const uint64_t lo = valid ? g.s_lo[at] : 0, hi = valid ? g.s_hi[at] : 0;
+#pragma unroll 8
+                for (int q = 0; q < kWave; ++q) {
+                    const uint32_t ts_q = __builtin_amdgcn_readlane(life.x, q), te_q = __builtin_amdgcn_readlane(life.y, q);
+                    const bool counts = ts_q < w_hi && w_lo < te_q;
+                    if (__builtin_amdgcn_ballot_w64(counts) == 0) continue;           // (uniform)
+                    body(readlane64(lo, q), readlane64(hi, q), counts);
+                }
+            }
+        };
+
+        if constexpr (kWalk == 1) {          // how far the decisions of each part reach
+            uint64_t covered = 0;
+            walk([&](uint64_t, uint64_t end, bool counts) { covered = counts ? umax64(covered, end) : covered; });
+            sc.reach[row + (size_t)part * kWave] = covered;
+        } else {
+            uint64_t covered = g.pool->lo;       // covered before this part
+            for (uint32_t v = 0; v < part; ++v) covered = umax64(covered, sc.reach[row + (size_t)v * kWave]);
+            if constexpr (kWalk == 2) {      // idle intervals closed inside each part
+                uint32_t count = 0;
+                uint64_t idle = 0;
+                walk([&](uint64_t start, uint64_t end, bool counts) {
+                    if (counts && start > covered) { ++count; idle += start - covered; }
+                    covered = counts ? umax64(covered, end) : covered;
+                });
+                sc.found[row + (size_t)part * kWave] = count;
+                sc.idle[row + (size_t)part * kWave] = idle;
+            } else {                         // write them; the last part adds the tail of the pool and the totals
+                uint32_t place = 0;
+                for (uint32_t v = 0; v < part; ++v) place += sc.found[row + (size_t)v * kWave];
+                uint64_t* out = (g.ranges && live) ? g.ranges + (size_t)w * g.max_ranges * 2 : nullptr;
+                const uint64_t covered0 = covered;
+                if (g.ranges) {                                           // (uniform; lanes without a window count nothing)
+                    walk([&](uint64_t start, uint64_t end, bool counts) {
+                        if (counts && start > covered) {
+                            if (place < g.max_ranges) { out[2 * place] = covered; out[2 * place + 1] = start; }
+                            ++place;
+                        }
+                        covered = counts ? umax64(covered, end) : covered;
+                    });
+                }
+                if (part + 1 == sc.parts && live) {
+                    const size_t mine = row + (size_t)part * kWave;
+                    const uint64_t covered_all = umax64(covered0, sc.reach[mine]);
+                    uint32_t total = sc.found[mine];
+                    uint64_t idle_total = sc.idle[mine];
+                    for (uint32_t v = 0; v < part; ++v) { total += sc.found[row + (size_t)v * kWave]; idle_total += sc.idle[row + (size_t)v * kWave]; }
+                    const uint64_t pool_hi = g.pool->hi;
+                    if (covered_all < pool_hi) {                          // from the last covered address to the end of the pool
+                        if (out && total < g.max_ranges) { out[2 * total] = covered_all; out[2 * total + 1] = pool_hi; }
+                        idle_total += pool_hi - covered_all;
+                        ++total;
+                    }
+                    g.counts[w] = total;
+                    if (g.idle_bytes) g.idle_bytes[w] = idle_total;
+                }
+            }
+        }
+    }
+}
+
 }  // namespace stalloc
 
 using namespace stalloc;
@@ -257,6 +373,21 @@ extern "C" int stalloc_reusable_space(const stalloc_trace* tr, const uint64_t* o
     uint64_t* s_lo = cv.take<uint64_t>(n);
     uint64_t* s_hi = cv.take<uint64_t>(n);
     uint2* s_life = cv.take<uint2>(n);
+    // window-per-lane sweep: enough (group of 64 windows) x (part of the plan) waves to fill the chip
+    RsParts sc = {nullptr, nullptr, nullptr, 0, 0};
+    const uint32_t groups = (k + kWave - 1) / kWave;
+    if (rs_window_per_lane(n, k)) {
+        const uint32_t all_steps = (n + kWave - 1) / kWave;
+        uint32_t parts = ((uint32_t)di.cus * 16 + groups - 1) / groups;
+        if (parts > kRsMaxParts) parts = kRsMaxParts;
+        if (parts > (all_steps + 1) / 2) parts = (all_steps + 1) / 2;     // at least two steps to a part
+        sc.steps = (all_steps + parts - 1) / parts;
+        sc.parts = (all_steps + sc.steps - 1) / sc.steps;
+        const size_t cells = (size_t)groups * sc.parts * kWave;
+        sc.reach = cv.take<uint64_t>(cells);
+        sc.idle = cv.take<uint64_t>(cells);
+        sc.found = cv.take<uint32_t>(cells);
+    }
     if (!workspace) { *workspace_bytes = cv.used; return STALLOC_OK; }
     if (!offsets || !windows || !counts || !device_status || (max_ranges != 0 && !ranges) ||
         *workspace_bytes < cv.used || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)))
@@ -283,8 +414,17 @@ extern "C" int stalloc_reusable_space(const stalloc_trace* tr, const uint64_t* o
     g.s_lo = s_lo; g.s_hi = s_hi; g.s_life = s_life; g.pool = pool; g.windows = windows;
     g.ranges = max_ranges ? ranges : nullptr; g.counts = counts; g.idle_bytes = idle_bytes; g.status = device_status;
     g.n = n; g.k = k; g.max_ranges = max_ranges;
-    uint32_t grid = (uint32_t)di.cus * 8;
-    if (grid > k) grid = k;
-    hipLaunchKernelGGL(rs_sweep, dim3(grid), dim3(kRsThreads), 0, stream, g);
+    if (rs_window_per_lane(n, k)) {
+        const uint64_t waves = (uint64_t)groups * sc.parts;
+        uint32_t grid = (uint32_t)di.cus * 8;
+        if (grid > (waves + kRsWaves - 1) / kRsWaves) grid = (uint32_t)((waves + kRsWaves - 1) / kRsWaves);
+        hipLaunchKernelGGL(rs_sweep_by_window<1>, dim3(grid), dim3(kRsThreads), 0, stream, g, sc);
+        hipLaunchKernelGGL(rs_sweep_by_window<2>, dim3(grid), dim3(kRsThreads), 0, stream, g, sc);
+        hipLaunchKernelGGL(rs_sweep_by_window<3>, dim3(grid), dim3(kRsThreads), 0, stream, g, sc);
+    } else {
+        uint32_t grid = (uint32_t)di.cus * 8;
+        if (grid > k) grid = k;
+        hipLaunchKernelGGL(rs_sweep, dim3(grid), dim3(kRsThreads), 0, stream, g);
+    }
     return hipGetLastError() == hipSuccess ? STALLOC_OK : STALLOC_ERR_DEVICE;
 }

@@ -112,6 +112,55 @@ def test_more_windows_than_resident_workgroups(S, oracle):
     _compare(S, oracle, tr.size, tr.t_alloc, tr.t_free, tr.t_end, a, windows, cap=16)
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_thousands_of_windows(S, oracle, seed):
+    """From 2^23 decisions x windows on, a lane takes a window and a wave 64 of them over a part of the
+    sorted plan: ragged last groups and parts, tied and unique times, truncated rows."""
+    rng = np.random.default_rng(4200 + seed)
+    n = [131, 300, 1025, 4099, 5000, 20000][seed]
+    k = [64100, 28001, 8200, 2049, 2560, 2050][seed]
+    size, ts, te, t_end = random_trace(rng, n, t_max=max(4, n // 2), unique_times=(seed % 2 == 1))
+    if seed % 3 == 0:
+        size = size * np.uint64(1 << 37)
+    a = (rng.integers(0, max(2, 4 * n), n).astype(np.uint64)) * (size.max() if seed % 3 == 0 else np.uint64(1))
+    lo = rng.integers(0, t_end, k)
+    hi = np.minimum(lo + np.exp(rng.uniform(0, np.log(max(2, t_end // 2)), k)).astype(np.int64), t_end + 3)
+    windows = np.stack([lo, np.maximum(hi, lo + 1)], axis=1).astype(np.uint32)
+    sample = None if k <= 3000 and n <= 5000 else range(seed, k, max(1, k // 1500))
+    _compare(S, oracle, size, ts, te, t_end, a, windows, cap=64, sample=sample)
+    _compare(S, oracle, size, ts, te, t_end, a, windows, cap=2, sample=range(0, k, max(5, k // 500)))
+    status, ranges, counts, idle = _gpu(S, size, ts, te, t_end, a, windows, 0)       # counts and idle bytes only
+    assert status == 0 and ranges is None
+    for w in range(0, k, max(11, k // 500)):
+        _, c, i = oracle.reusable_space(size, ts, te, a, (int(windows[w][0]), int(windows[w][1])), cap=1)
+        assert int(counts[w]) == c and int(idle[w]) == i
+
+
+def test_config2_best_plan_4096_windows(S, oracle):
+    tr = make_trace(2)
+    order = make_orderings(tr, CONFIGS[2].n_orderings, rows=[0])[0]
+    a, _ = oracle.plan_allpairs(tr.size, tr.t_alloc, tr.t_free, order)
+    windows = make_windows(tr, 4096, seed=7002)
+    _compare(S, oracle, tr.size, tr.t_alloc, tr.t_free, tr.t_end, a, windows, cap=64)
+
+
+def test_more_window_groups_than_waves(S, oracle):
+    """300 000 windows over a short plan: every wave answers several (group of 64 windows, part) units in
+    a row; one malformed window in the middle is reported."""
+    rng = np.random.default_rng(4300)
+    n, k = 131, 300000
+    size, ts, te, t_end = random_trace(rng, n, t_max=200, unique_times=False)
+    a = rng.integers(0, 4 * n, n).astype(np.uint64)
+    lo = rng.integers(0, t_end, k)
+    hi = np.minimum(lo + rng.integers(1, 60, k), t_end)
+    lo = np.minimum(lo, hi - 1)
+    windows = np.stack([lo, hi], axis=1).astype(np.uint32)
+    _compare(S, oracle, size, ts, te, t_end, a, windows, cap=16, sample=range(0, k, 211))
+    windows[200001] = (5, 5)
+    status, *_ = _gpu(S, size, ts, te, t_end, a, windows, 16)
+    assert status == 7                                                   # STALLOC_ERR_BAD_WINDOW
+
+
 def test_reports_malformed_inputs(S):
     size, ts, te, a, windows = load_reusable_golden()
     status, *_ = _gpu(S, size, ts, te, int(te.max()), a, np.array([[0, 3], [4, 4]], np.uint32), 4)
