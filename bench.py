@@ -51,7 +51,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=2, help="trace configuration 1..5 (default: 2)")
+    ap.add_argument("--config", type=int, default=2, help="trace configuration 1..5, or 6..7 for the second kind of workload (default: 2)")
     ap.add_argument("--plans", type=int, default=0, help="override the number of orders (0 = the configuration's)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="CPU work budget of the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -168,7 +168,8 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "u64",
         "data": "synthetic",
-        "config": {"workload": f"configs[{args.config - 1}] {cfg.name}: {cfg.description}", "n": n, "P": P,
+        "config": {"workload": (f"configs[{args.config - 1}] " if args.config <= 5 else "second workload ") +
+                               f"{cfg.name}: {cfg.description}", "n": n, "P": P,
                    "T": stats["T"], "E": stats["E"], "distinct_sizes": stats["distinct_sizes"],
                    "step": "stalloc_plan(all orders) + stalloc_validate(best plan) + stalloc_lower_bound"},
         "quality": {"lower_bound": lower_bound, "best_peak": best_peak, "best_plan": best,

@@ -336,6 +336,24 @@ def test_plan_config4_sampled_orderings(S, oracle):
     assert (got["peaks"] >= lb).all()
 
 
+def test_plan_second_workload_sampled_orderings(S, oracle):
+    """Iterations back to back, persistent tensors that overlap every request, a coarse clock with
+    thousands of tied timestamps: two iterations of config 2 (occupancy-bitmap kernel) and the MoE
+    stage (sorted-list kernel)."""
+    for cfg, rows in ((6, [0, 1, 2, 3, 4, 511, 1022, 1023]), (7, [0, 3, 2046])):
+        tr = make_trace(cfg)
+        orders = make_orderings(tr, CONFIGS[cfg].n_orderings, rows=rows)
+        lists = oracle.conflict_lists(tr.t_alloc, tr.t_free)
+        got, a, ext = _compare_plans(S, oracle, tr, orders, method="lists", lists=lists)
+        del lists
+        assert (_layout(S, tr) & 0x200 != 0) == (cfg == 6)
+        cnt, _ = _gpu_validate(S, tr, got["offsets"])
+        assert not cnt.any()
+        status, lb, t_at = _gpu_lower_bound(S, tr)
+        assert status == 0 and (got["peaks"] >= lb).all()
+        assert (int(lb), int(t_at)) == oracle.lower_bound(tr.size, tr.t_alloc, tr.t_free, tr.t_end)
+
+
 def test_plan_config5_sampled_orderings(S, oracle):
     """Largest trace (199 748 requests, 64-bit addresses): sampled rows compared address by address,
     the best of them validated over all n(n-1)/2 pairs, and a corrupted copy against the oracle's count."""

@@ -71,6 +71,15 @@ def test_generators_match_the_configurations():
         assert (np.diff(size[o[0]]) <= 0).all()               # row 0: descending size
         assert (np.diff(tr.t_alloc[o[2]].astype(np.int64)) > 0).all()   # row 2: by allocation time
     assert CONFIGS[5].n_orderings == 4096
+    # second kind of workload: iterations back to back, persistent tensors, coarse clock
+    base, tr = make_trace(2), make_trace(6)
+    c = CONFIGS[6]
+    assert tr.n == c.iterations * base.n + c.persistent and (tr.t_alloc < tr.t_free).all()
+    assert int(tr.t_free.max()) == tr.t_end and len(np.unique(tr.t_alloc)) < tr.n // 2        # many ties
+    pers = (tr.t_alloc < c.persistent // c.quantum + 1) & (tr.t_free > tr.t_end - c.persistent // c.quantum - 1)
+    assert int(pers.sum()) >= c.persistent
+    assert np.array_equal(np.sort(tr.size[c.persistent:c.persistent + base.n]), np.sort(base.size))
+    assert trace_stats(tr)["max_degree"] == tr.n - 1                     # a persistent tensor overlaps every request
     from workloads import make_windows
     tr = make_trace(2)
     w = make_windows(tr, 1000)

@@ -18,6 +18,12 @@ Every allocation and every release takes the next integer timestamp, so all
 timestamps are distinct and the number of events is t_end = 2 n.  Lifetimes
 are half-open, [t_alloc, t_free).
 
+Configurations 6 and 7 are a second kind of workload derived from 2 and 4: several
+iterations back to back, persistent tensors that live through all of them
+(Sec. 2.3 names persistent tensors as the third lifetime class) and coarse
+timestamps, as a profiler with a slower clock would record them, so that many
+requests start and end at the same instant.
+
 Only inputs are produced here; nothing in this file places, validates or
 bounds anything.
 """
@@ -181,6 +187,10 @@ class _Cfg:
     experts: int = 0
     tokens_per_mb: int = 0
     small_per_pass: int = 0
+    base: int = 0                 # kind "multi": the configuration whose iteration is repeated
+    iterations: int = 1
+    persistent: int = 0           # tensors alive from the first to the last event
+    quantum: int = 1              # events per recorded timestamp
 
 
 CONFIGS: Dict[int, _Cfg] = {
@@ -194,6 +204,10 @@ CONFIGS: Dict[int, _Cfg] = {
             2048, 16, 1, 8, 4096, 8192, kind="moe", experts=64, tokens_per_mb=8192),
     5: _Cfg("cfg5_interleaved", "interleaved 1F1B, 4 chunks x 16 layers, 8 micro-batches, h=8192, s=8192",
             4096, 16, 4, 8, 8192, 8192, kind="interleaved", small_per_pass=183),
+    6: _Cfg("cfg6_two_iterations", "two iterations of the 32-layer 1F1B stage, 256 persistent tensors, 4 events per timestamp",
+            1024, 32, 1, 8, 4096, 4096, kind="multi", base=2, iterations=2, persistent=256, quantum=4),
+    7: _Cfg("cfg7_moe_coarse_clock", "the MoE stage with 128 persistent tensors, 8 events per timestamp",
+            2048, 16, 1, 8, 4096, 8192, kind="multi", base=4, iterations=1, persistent=128, quantum=8),
 }
 
 _SMALL_SIZES = (512, 1024, 1536, 2048, 3072, 4096, 6144, 8192, 12288, 16384,
@@ -206,9 +220,37 @@ def _free_interleaved(em: _Emitter, scoped: List[int]) -> None:
         em.free(scoped.pop())
 
 
-def make_trace(cfg_id: int) -> Trace:
-    """Build the trace of configuration `cfg_id` (1..5); fully determined by the id."""
+def _make_multi(cfg_id: int) -> Trace:
+    """Iterations of a base configuration back to back, persistent tensors around them, coarse clock."""
     c = CONFIGS[cfg_id]
+    base = make_trace(c.base)
+    rng = np.random.Generator(np.random.PCG64(BASE_SEED + cfg_id))
+    act = c.s * c.h * 2
+    pers_size = np.asarray([_round_up(act * int(rng.choice(c.k_choices))) for _ in range(c.persistent)], dtype=np.uint64)
+    # events: the persistent allocations, then the iterations, then the persistent releases
+    t0 = c.persistent
+    span = base.t_end
+    size = [pers_size]
+    ta = [np.arange(c.persistent, dtype=np.int64)]
+    tf = [t0 + c.iterations * span + np.arange(c.persistent, dtype=np.int64)[::-1]]
+    for it in range(c.iterations):
+        size.append(base.size)
+        ta.append(base.t_alloc.astype(np.int64) + t0 + it * span)
+        tf.append(base.t_free.astype(np.int64) + t0 + it * span)
+    size = np.concatenate(size)
+    ta = np.concatenate(ta) // c.quantum
+    tf = np.concatenate(tf) // c.quantum
+    tf = np.maximum(tf, ta + 1)                 # a lifetime shorter than the clock's tick still holds its memory for one
+    meta = {"cfg": cfg_id, "description": c.description, "n_orderings": c.n_orderings, "seed": BASE_SEED + cfg_id}
+    return Trace(name=c.name, size=size, t_alloc=ta.astype(np.uint32), t_free=tf.astype(np.uint32),
+                 t_end=int(tf.max()), meta=meta)
+
+
+def make_trace(cfg_id: int) -> Trace:
+    """Build the trace of configuration `cfg_id` (1..7); fully determined by the id."""
+    c = CONFIGS[cfg_id]
+    if c.kind == "multi":
+        return _make_multi(cfg_id)
     rng = np.random.Generator(np.random.PCG64(BASE_SEED + cfg_id))
     em = _Emitter()
     act = c.s * c.h * 2  # one bf16 activation of s x h
