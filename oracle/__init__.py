@@ -62,10 +62,12 @@ def _bind(path: str):
     lib.oracle_best_over_all_orders.argtypes = [u32, p, p, p, p, p]
     lib.oracle_exact_optimum.argtypes = [u32, p, p, p, p, p]
     lib.oracle_reusable_space.argtypes = [u32, p, p, p, p, u32, u32, u64, p, p, p]
+    lib.oracle_memory_layers.argtypes = [u32, p, p, p, p, p, p, p, p]
     for name in ("oracle_check_trace", "oracle_plan_allpairs", "oracle_conflict_lists",
                  "oracle_plan_lists", "oracle_best_plan", "oracle_validate",
                  "oracle_lower_bound_definition", "oracle_lower_bound_sweep",
-                 "oracle_best_over_all_orders", "oracle_exact_optimum", "oracle_reusable_space"):
+                 "oracle_best_over_all_orders", "oracle_exact_optimum", "oracle_reusable_space",
+                 "oracle_memory_layers"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -215,3 +217,18 @@ def reusable_space(size, t_s, t_e, a, window: Tuple[int, int], cap: Optional[int
     _check(_load().oracle_reusable_space(len(size), _ptr(size), _ptr(t_s), _ptr(t_e), _ptr(a), int(window[0]),
                                          int(window[1]), cap, _ptr(ranges), _ptr(count), _ptr(idle)))
     return ranges[:min(cap, int(count[0]))], int(count[0]), int(idle[0])
+
+
+def memory_layers(size, t_s, t_e):
+    """Algorithm 1 for every HomoSize group: (layer_of [n], layer_size [L], layer_t_s [L], layer_t_e [L])."""
+    size, t_s, t_e = _c(size, np.uint64), _c(t_s, np.uint32), _c(t_e, np.uint32)
+    n = len(size)
+    layer_of = np.zeros(n, dtype=np.uint32)
+    count = np.zeros(1, dtype=np.uint32)
+    l_size = np.zeros(n, dtype=np.uint64)
+    l_ts = np.zeros(n, dtype=np.uint32)
+    l_te = np.zeros(n, dtype=np.uint32)
+    _check(_load().oracle_memory_layers(n, _ptr(size), _ptr(t_s), _ptr(t_e), _ptr(layer_of), _ptr(count),
+                                        _ptr(l_size), _ptr(l_ts), _ptr(l_te)))
+    L = int(count[0])
+    return layer_of, l_size[:L].copy(), l_ts[:L].copy(), l_te[:L].copy()

@@ -38,6 +38,11 @@
  * Dynamic reusable space (Sec. 5.2): oracle_reusable_space, pinned by a
  * byte-by-byte occupancy map on small pools, closed forms and a hand-worked
  * example (tests/test_oracle_reusable.py); no printed values exist for it either.
+ *
+ * Memory-layer construction (Sec. 5.1, Algorithm 1): oracle_memory_layers, pinned by a
+ * hand-worked example, the optimum of interval partitioning (as many layers as
+ * requests of the size are ever alive at once), structural invariants, closed forms
+ * and the validity of the plan that the layers expand to (tests/test_oracle_layers.py).
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -392,5 +397,68 @@ int oracle_reusable_space(uint32_t n, const uint64_t *size, const uint32_t *t_s,
     free(met);
     *count = found;
     *idle = total;
+    return ORC_OK;
+}
+
+/*
+ * Memory-layer construction for the HomoSize groups of a trace (Sec. 5.1,
+ * HomoSize Group Planning, Algorithm 1).  A HomoSize group M_s holds the requests of
+ * one size S; requests of a group whose lifetimes do not overlap can share one
+ * range of S bytes, a memory-layer.  The group's requests are taken by allocation
+ * time; each goes to the layer whose last request ends latest among the layers that
+ * are free at its allocation time, so that the layer idles least; if no layer is
+ * free a new one is opened.  The request becomes the layer's last one and the
+ * layer's end becomes its free time.
+ *
+ * Output: layer_of[i] = layer of request i.  Layers are numbered group by group in
+ * descending size (the order in which the global plan takes the groups) and, inside
+ * a group, in the order in which they were opened.  For every layer: its size, the
+ * allocation time of its first request and the free time of its last one -- the
+ * rectangle the layer occupies when it is planned as one request (as the local plan
+ * of a group is, Sec. 5.1).  *n_layers = number of layers.
+ *
+ * Readings: lifetimes are half-open, so a layer whose last request is released at t
+ * is free for a request allocated at t (the listing prints a strict comparison for
+ * closed lifetimes); requests with equal allocation times are taken by request
+ * number; among free layers with equal ends the one opened first is taken.
+ */
+typedef struct { uint64_t size; uint32_t t_s; uint32_t id; } layer_key_t;
+
+static int by_size_desc_then_start(const void *pa, const void *pb)
+{
+    const layer_key_t *x = (const layer_key_t *)pa, *y = (const layer_key_t *)pb;
+    if (x->size != y->size) return x->size > y->size ? -1 : 1;
+    if (x->t_s != y->t_s) return x->t_s < y->t_s ? -1 : 1;
+    return x->id < y->id ? -1 : (x->id > y->id ? 1 : 0);
+}
+
+int oracle_memory_layers(uint32_t n, const uint64_t *size, const uint32_t *t_s,
+                         const uint32_t *t_e, uint32_t *layer_of, uint32_t *n_layers,
+                         uint64_t *layer_size, uint32_t *layer_t_s, uint32_t *layer_t_e)
+{
+    if (n == 0 || !size || !t_s || !t_e || !layer_of || !n_layers || !layer_size || !layer_t_s || !layer_t_e)
+        return ORC_INVALID_ARG;
+    layer_key_t *m = (layer_key_t *)malloc((size_t)n * sizeof(layer_key_t));
+    if (!m) return ORC_NOMEM;
+    for (uint32_t i = 0; i < n; ++i) { m[i].size = size[i]; m[i].t_s = t_s[i]; m[i].id = i; }
+    qsort(m, n, sizeof(layer_key_t), by_size_desc_then_start);
+    uint32_t layers = 0;                       /* layers opened so far, over all groups */
+    uint32_t group_first = 0;                  /* first layer of the current group */
+    for (uint32_t k = 0; k < n; ++k) {
+        if (k > 0 && m[k].size != m[k - 1].size) group_first = layers;      /* next HomoSize group */
+        const uint32_t i = m[k].id;
+        int64_t best = -1;
+        for (uint32_t l = group_first; l < layers; ++l)
+            if (layer_t_e[l] <= t_s[i] && (best < 0 || layer_t_e[l] > layer_t_e[best])) best = l;
+        if (best < 0) {
+            best = layers++;
+            layer_size[best] = size[i];
+            layer_t_s[best] = t_s[i];
+        }
+        layer_of[i] = (uint32_t)best;
+        layer_t_e[best] = t_e[i];
+    }
+    free(m);
+    *n_layers = layers;
     return ORC_OK;
 }

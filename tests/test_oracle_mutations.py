@@ -8,6 +8,7 @@ import pytest
 
 import test_oracle_pins as pins
 import test_oracle_reusable as reusable
+import test_oracle_layers as layers
 
 MUTATIONS = {
     "closed_lifetimes": ("return ts_a < te_b && ts_b < te_a;", "return ts_a <= te_b && ts_b <= te_a;"),
@@ -28,6 +29,12 @@ MUTATIONS = {
     "idle_no_tail_interval": ("for (size_t c = 0; c <= k; ++c) {", "for (size_t c = 0; c < k; ++c) {"),
     "idle_count_capped": ("            ++found;\n            total += next - reach;", "            if (found < cap) ++found;\n            total += next - reach;"),
     "idle_needs_gap_of_two": ("if (next > reach) {", "if (next > reach + 1) {"),
+    "layer_first_free_not_latest": ("(best < 0 || layer_t_e[l] > layer_t_e[best])) best = l;", "best < 0) best = l;"),
+    "layer_needs_idle_tick": ("if (layer_t_e[l] <= t_s[i] &&", "if (layer_t_e[l] < t_s[i] &&"),
+    "layer_shared_across_groups": ("if (k > 0 && m[k].size != m[k - 1].size) group_first = layers;", "if (0) group_first = layers;"),
+    "layer_end_not_updated": ("        layer_t_e[best] = t_e[i];\n    }\n    free(m);", "        if (layer_t_e[best] < t_e[i]) layer_t_e[best] = t_e[i] - 1;\n    }\n    free(m);"),
+    "layer_groups_ascending": ("if (x->size != y->size) return x->size > y->size ? -1 : 1;", "if (x->size != y->size) return x->size > y->size ? 1 : -1;"),
+    "layer_by_number_not_start": ("if (x->t_s != y->t_s) return x->t_s < y->t_s ? -1 : 1;\n    return x->id < y->id", "return x->id < y->id"),
     "extent_forgets_size": ("if (a[i] + size[i] > top) top = a[i] + size[i];\n    }\n    free(spans);\n    *extent",
                             "if (a[i] > top) top = a[i];\n    }\n    free(spans);\n    *extent"),
 }
@@ -52,6 +59,11 @@ def _battery(oracle):
     for seed in range(6):
         reusable.test_matches_byte_map(oracle, seed)
     reusable.test_lowest_fit_plans_have_no_idle_space_over_the_whole_iteration(oracle, 0)
+    layers.test_hand_worked_example(oracle)
+    layers.test_closed_forms(oracle)
+    for seed in range(4):
+        layers.test_random_traces_structure_and_minimum(oracle, seed)
+        layers.test_layers_planned_as_requests_expand_to_a_valid_plan(oracle, seed)
 
 
 def test_battery_passes_on_the_real_oracle(oracle):
