@@ -48,7 +48,8 @@ typedef enum stalloc_status {
     STALLOC_ERR_NOMEM = 4,       /* reserved                                                      */
     STALLOC_ERR_DEVICE = 5,      /* a HIP call failed                                             */
     STALLOC_ERR_BAD_ORDER = 6,   /* an entry of `orders` is >= n                                  */
-    STALLOC_ERR_BAD_WINDOW = 7   /* a time window with w_lo >= w_hi                               */
+    STALLOC_ERR_BAD_WINDOW = 7,  /* a time window with w_lo >= w_hi                               */
+    STALLOC_ERR_BAD_LAYER = 8    /* an entry of `layer_of` is >= n_layers                         */
 } stalloc_status;
 
 /* Structure-of-arrays trace (Sec. 4: s, t_s, t_e of every request event). */
@@ -142,6 +143,54 @@ int stalloc_reusable_space(const stalloc_trace *trace, const uint64_t *offsets,
                            uint64_t *ranges, uint32_t *counts, uint64_t *idle_bytes,
                            uint32_t *device_status,
                            void *workspace, size_t *workspace_bytes, void *hip_stream);
+
+/*
+ * Memory-layer construction for every HomoSize group of the trace (Sec. 5.1, HomoSize
+ * Group Planning, Algorithm 1).  A HomoSize group holds the requests of one size;
+ * requests of a group whose lifetimes do not overlap can share one range of that
+ * size, a memory-layer.  The requests of a group are taken by allocation time
+ * (request number among equals); each joins, as its last request, the layer that is
+ * free at its allocation time and whose last request was released latest (the layer
+ * opened first among equals), so that the layer idles least; if no layer is free a
+ * new one is opened.  Lifetimes are half-open: a layer whose last request is released
+ * at t is free for a request allocated at t.  A group gets as few layers as any
+ * assignment can have.
+ *
+ * Layers are numbered group by group in descending size and, inside a group, in the
+ * order in which they were opened.  A layer planned as one request of its size from
+ * the allocation of its first request to the release of its last one (the local plan
+ * of the group becomes part of the global plan, Sec. 5.1) gives all its requests one
+ * address: (layer_size, layer_t_alloc, layer_t_free) is a trace of *n_layers requests
+ * that stalloc_plan accepts, with t_end of the original trace.
+ *
+ *   layer_of       device [n], layer of every request
+ *   n_layers       device [1]
+ *   layer_size     device [n], the first *n_layers entries are written
+ *   layer_t_alloc  device [n], likewise
+ *   layer_t_free   device [n], likewise
+ */
+int stalloc_memory_layers(const stalloc_trace *trace, uint32_t *layer_of, uint32_t *n_layers,
+                          uint64_t *layer_size, uint32_t *layer_t_alloc, uint32_t *layer_t_free,
+                          uint32_t *device_status,
+                          void *workspace, size_t *workspace_bytes, void *hip_stream);
+
+/*
+ * Plans of the layers back to plans of the requests: every request takes the address of
+ * its layer, offsets[p][i] = layer_offsets[p][layer_of[i]].  Plans that are free of
+ * conflicts for the layer trace are free of conflicts for the requests and have the
+ * same extent.
+ *
+ *   layer_of       device [n], as written by stalloc_memory_layers
+ *   layer_offsets  device [P][n_layers], for instance `offsets` of stalloc_plan on the
+ *                  layer trace
+ *   n_layers       host value (read back from stalloc_memory_layers); an entry of
+ *                  layer_of that is >= n_layers sets device_status to STALLOC_ERR_BAD_LAYER
+ *   offsets        device [P][n]
+ *   device_status  device [1], written (STALLOC_OK or the error); no workspace is needed
+ */
+int stalloc_expand_layers(uint32_t n, uint32_t P, const uint32_t *layer_of,
+                          const uint64_t *layer_offsets, uint32_t n_layers, uint64_t *offsets,
+                          uint32_t *device_status, void *hip_stream);
 
 /* Human-readable name of a stalloc_status; never NULL.  Host memory, static storage. */
 const char *stalloc_status_string(int status);

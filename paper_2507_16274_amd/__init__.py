@@ -20,8 +20,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libstalloc.so")
 
 STATUS = {0: "STALLOC_OK", 1: "STALLOC_ERR_INVALID_ARG", 2: "STALLOC_ERR_BAD_TRACE", 3: "STALLOC_ERR_OVERFLOW",
-          4: "STALLOC_ERR_NOMEM", 5: "STALLOC_ERR_DEVICE", 6: "STALLOC_ERR_BAD_ORDER", 7: "STALLOC_ERR_BAD_WINDOW"}
+          4: "STALLOC_ERR_NOMEM", 5: "STALLOC_ERR_DEVICE", 6: "STALLOC_ERR_BAD_ORDER", 7: "STALLOC_ERR_BAD_WINDOW",
+          8: "STALLOC_ERR_BAD_LAYER"}
 EXPORTS = ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_reusable_space",
+           "stalloc_memory_layers", "stalloc_expand_layers",
            "stalloc_status_string", "stalloc_plan_lds_capacity", "stalloc_plan_list_layout")
 
 
@@ -48,7 +50,10 @@ def _load() -> ctypes.CDLL:
     lib.stalloc_validate.argtypes = [tp, vp, u32, vp, vp, vp, vp, szp, vp]
     lib.stalloc_lower_bound.argtypes = [tp, vp, vp, vp, vp, szp, vp]
     lib.stalloc_reusable_space.argtypes = [tp, vp, vp, u32, u32, vp, vp, vp, vp, vp, szp, vp]
-    for name in ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_reusable_space"):
+    lib.stalloc_memory_layers.argtypes = [tp, vp, vp, vp, vp, vp, vp, vp, szp, vp]
+    lib.stalloc_expand_layers.argtypes = [u32, u32, vp, vp, u32, vp, vp, vp]
+    for name in ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_reusable_space",
+                 "stalloc_memory_layers", "stalloc_expand_layers"):
         getattr(lib, name).restype = ctypes.c_int
     lib.stalloc_status_string.argtypes = [ctypes.c_int]
     lib.stalloc_status_string.restype = ctypes.c_char_p
@@ -217,3 +222,40 @@ def trace_to_device(trace, device="cuda"):
     ta = torch.from_numpy(np.ascontiguousarray(trace.t_alloc).view(np.int32)).to(device)
     tf = torch.from_numpy(np.ascontiguousarray(trace.t_free).view(np.int32)).to(device)
     return size, ta, tf
+
+
+def stalloc_memory_layers(size, t_alloc, t_free, t_end: int, *, stream=None,
+                          workspace_cache: Optional[Dict] = None) -> Dict[str, torch.Tensor]:
+    """-> layer_of int32 [n], n_layers int32 [1], layer_size int64 [n], layer_t_alloc / layer_t_free int32 [n]
+    (the first n_layers entries are written), status int32 [1]."""
+    tr = _trace(size, t_alloc, t_free, t_end)
+    dev, n = size.device, tr.n
+    out = {"layer_of": torch.empty(n, dtype=torch.int32, device=dev),
+           "n_layers": torch.empty(1, dtype=torch.int32, device=dev),
+           "layer_size": torch.empty(n, dtype=torch.int64, device=dev),
+           "layer_t_alloc": torch.empty(n, dtype=torch.int32, device=dev),
+           "layer_t_free": torch.empty(n, dtype=torch.int32, device=dev),
+           "status": torch.empty(1, dtype=torch.int32, device=dev)}
+    args = (ctypes.byref(tr), out["layer_of"].data_ptr(), out["n_layers"].data_ptr(), out["layer_size"].data_ptr(),
+            out["layer_t_alloc"].data_ptr(), out["layer_t_free"].data_ptr(), out["status"].data_ptr())
+    need = ctypes.c_size_t(0)
+    _check(lib.stalloc_memory_layers(*args, None, ctypes.byref(need), None), "stalloc_memory_layers(workspace query)")
+    ws = _workspace(need.value, dev, workspace_cache)
+    have = ctypes.c_size_t(ws.numel())
+    _check(lib.stalloc_memory_layers(*args, ws.data_ptr(), ctypes.byref(have), _stream(stream)), "stalloc_memory_layers")
+    out["workspace"] = ws
+    return out
+
+
+def stalloc_expand_layers(layer_of, layer_offsets, *, stream=None) -> Dict[str, torch.Tensor]:
+    """layer_of int32 [n], layer_offsets int64 [P][n_layers] -> offsets int64 [P][n], status int32 [1]."""
+    if layer_of.dim() != 1 or layer_offsets.dim() != 2:
+        raise ValueError("layer_of must be [n] and layer_offsets [P][n_layers]")
+    n, (P, n_layers), dev = layer_of.numel(), layer_offsets.shape, layer_of.device
+    out = {"offsets": torch.empty((P, n), dtype=torch.int64, device=dev),
+           "status": torch.empty(1, dtype=torch.int32, device=dev)}
+    _check(lib.stalloc_expand_layers(n, P, _dev(layer_of, torch.int32, "layer_of"),
+                                     _dev(layer_offsets, torch.int64, "layer_offsets"), n_layers,
+                                     out["offsets"].data_ptr(), out["status"].data_ptr(), _stream(stream)),
+           "stalloc_expand_layers")
+    return out

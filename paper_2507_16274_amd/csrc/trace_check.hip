@@ -100,6 +100,7 @@ extern "C" const char* stalloc_status_string(int status)
         case STALLOC_ERR_DEVICE: return "STALLOC_ERR_DEVICE";
         case STALLOC_ERR_BAD_ORDER: return "STALLOC_ERR_BAD_ORDER";
         case STALLOC_ERR_BAD_WINDOW: return "STALLOC_ERR_BAD_WINDOW";
+        case STALLOC_ERR_BAD_LAYER: return "STALLOC_ERR_BAD_LAYER";
         default: return "STALLOC_UNKNOWN_STATUS";
     }
 }

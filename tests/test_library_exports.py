@@ -54,6 +54,18 @@ def test_host_side_argument_errors_need_no_gpu():
                                         ctypes.byref(need), None) == 1
 
 
+def test_layer_calls_reject_bad_host_arguments():
+    import paper_2507_16274_amd as S
+    need = ctypes.c_size_t(0)
+    assert S.lib.stalloc_memory_layers(None, None, None, None, None, None, None, None, ctypes.byref(need), None) == 1
+    tr = S._Trace(0, 10, 1, 1, 1)
+    assert S.lib.stalloc_memory_layers(ctypes.byref(tr), None, None, None, None, None, None, None, ctypes.byref(need), None) == 1
+    assert S.lib.stalloc_expand_layers(0, 1, 1, 1, 1, 1, 1, None) == 1          # n == 0
+    assert S.lib.stalloc_expand_layers(4, 0, 1, 1, 1, 1, 1, None) == 1          # P == 0
+    assert S.lib.stalloc_expand_layers(4, 1, 1, 1, 0, 1, 1, None) == 1          # no layers
+    assert S.lib.stalloc_expand_layers(4, 1, None, 1, 2, 1, 1, None) == 1       # NULL layer_of
+
+
 def test_generators_match_the_configurations():
     from workloads import CONFIGS, make_orderings, make_trace, trace_stats
     import numpy as np
