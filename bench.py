@@ -60,6 +60,9 @@ def main() -> int:
     ap.add_argument("--checks", action="store_true",
                     help="also time stalloc_validate (all plans; the best plan alone) and stalloc_lower_bound in timed "
                          "regions of their own (reported beside the step)")
+    ap.add_argument("--layers", action="store_true",
+                    help="also build the memory-layers of the trace (Algorithm 1), plan the layers under as many "
+                         "orders and expand the plans to the requests, in a timed region of its own")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference dispatch for HBM byte counters)")
     args = ap.parse_args()
@@ -243,6 +246,61 @@ def main() -> int:
             wall = time.perf_counter() - t1
             result["reusable_space"]["cpu_baseline"] = {"value": sample / wall, "unit": "windows/s", "cores": 1,
                                                         "kind": "oracle", "sample": f"first {sample} windows"}
+
+    if args.layers:
+        # HomoSize groups -> memory-layers (Sec. 5.1, Algorithm 1), each layer planned as one request under
+        # P orders of the layers, the plans expanded to the requests and the best one validated.  The
+        # construction is sequential inside a group (one wave per group), so it is bound by the chain of
+        # dependent steps of the longest group, not by bytes or lane operations.
+        from workloads import Trace
+        cache_ly, cache_lp, cache_lv = {}, {}, {}
+        ly = S.stalloc_memory_layers(size, ta, tf, tr.t_end, workspace_cache=cache_ly)
+        torch.cuda.synchronize()
+        S.check_status(ly, "stalloc_memory_layers")
+        L = int(ly["n_layers"].item())
+        l_size, l_ta, l_tf = ly["layer_size"][:L].clone(), ly["layer_t_alloc"][:L].clone(), ly["layer_t_free"][:L].clone()
+        ltr = Trace(name="layers", size=l_size.cpu().numpy().view(np.uint64), t_alloc=l_ta.cpu().numpy().view(np.uint32),
+                    t_free=l_tf.cpu().numpy().view(np.uint32), t_end=tr.t_end)
+        l_orders = torch.from_numpy(make_orderings(ltr, P).view(np.int32)).cuda()
+
+        def layer_family():
+            a = S.stalloc_memory_layers(size, ta, tf, tr.t_end, workspace_cache=cache_ly)
+            b = S.stalloc_plan(l_size, l_ta, l_tf, tr.t_end, l_orders, workspace_cache=cache_lp)
+            c = S.stalloc_expand_layers(a["layer_of"], b["offsets"])
+            return a, b, c
+
+        for _ in range(max(args.warmup, 1)):
+            layer_family()
+        torch.cuda.synchronize()
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        evs[0].record()
+        for _ in range(args.steps):
+            a = S.stalloc_memory_layers(size, ta, tf, tr.t_end, workspace_cache=cache_ly)
+        evs[1].record()
+        for _ in range(args.steps):
+            b = S.stalloc_plan(l_size, l_ta, l_tf, tr.t_end, l_orders, workspace_cache=cache_lp)
+        evs[2].record()
+        for _ in range(args.steps):
+            c = S.stalloc_expand_layers(a["layer_of"], b["offsets"])
+        evs[3].record()
+        torch.cuda.synchronize()
+        S.check_status(b, "stalloc_plan(layers)")
+        S.check_status(c, "stalloc_expand_layers")
+        l_peaks = b["peaks"].cpu().numpy().view(np.uint64)
+        l_best = int(b["best_plan"].item())
+        v = S.stalloc_validate(size, ta, tf, tr.t_end, c["offsets"][l_best].view(1, n).contiguous(), workspace_cache=cache_lv)
+        torch.cuda.synchronize()
+        if int(v["conflicts"].item()) != 0 or int(l_peaks[l_best]) < lower_bound:
+            print("bench.py: the expanded layer plan is not a valid plan", file=sys.stderr)
+            return 1
+        ms = [evs[i].elapsed_time(evs[i + 1]) / args.steps for i in range(3)]
+        result["layers"] = {
+            "n_layers": L, "orders": P,
+            "ms_memory_layers": ms[0], "requests_per_s": n / (ms[0] * 1e-3),
+            "ms_plan_layers": ms[1], "layer_plans_per_s": L * P / (ms[1] * 1e-3),
+            "ms_expand": ms[2], "expand_GBs": (12 * n * P) / (ms[2] * 1e-3) / 1e9,
+            "best_peak": int(l_peaks[l_best]), "lower_bound_over_peak": lower_bound / int(l_peaks[l_best]),
+            "per_request_best_lower_bound_over_peak": lower_bound / best_peak}
 
     if args.checks:
         # The two checking calls in timed regions of their own.  stalloc_validate tests every unordered

@@ -245,7 +245,8 @@ __global__ void __launch_bounds__(256) ly_build(LyBuild g)
                 // latest end among the free layers (an end is a free time, hence >= 1)
                 uint32_t latest = 0;
 #pragma unroll
-                for (int r = 0; r < kLyRegs; ++r) latest = umax(latest, end_of[r] <= ts ? end_of[r] : 0u);
+                for (int r = 0; r < kLyRegs; ++r)
+                    if ((uint32_t)r * kWave < layers) latest = umax(latest, end_of[r] <= ts ? end_of[r] : 0u);   // (uniform)
                 const uint32_t in_regs = __builtin_amdgcn_readlane(wave_scan_max(latest), kWave - 1);
                 uint32_t in_mem = 0;
                 for (uint32_t l0 = kLyRegs * kWave; l0 < layers; l0 += kWave) {    // (only groups with more than 512 layers)
@@ -260,8 +261,9 @@ __global__ void __launch_bounds__(256) ly_build(LyBuild g)
                     if (in_regs == best) {
 #pragma unroll
                         for (int r = 0; r < kLyRegs; ++r) {
+                            if (found || (uint32_t)r * kWave >= layers) continue;                      // (uniform)
                             const uint64_t hit = __builtin_amdgcn_ballot_w64(end_of[r] == best);
-                            if (!found && hit) { layer = (uint32_t)r * kWave + (uint32_t)__builtin_ctzll(hit); found = true; }
+                            if (hit) { layer = (uint32_t)r * kWave + (uint32_t)__builtin_ctzll(hit); found = true; }
                         }
                     }
                     for (uint32_t l0 = kLyRegs * kWave; !found && l0 < layers; l0 += kWave) {
@@ -278,7 +280,7 @@ __global__ void __launch_bounds__(256) ly_build(LyBuild g)
                 if (layer < (uint32_t)(kLyRegs * kWave)) {
 #pragma unroll
                     for (int r = 0; r < kLyRegs; ++r)
-                        if ((uint32_t)r == layer / kWave && (uint32_t)lane == layer % kWave) end_of[r] = te;
+                        if ((uint32_t)r == layer / kWave) end_of[r] = (uint32_t)lane == layer % kWave ? te : end_of[r];   // (uniform test)
                 } else if (lane == 0) {
                     __hip_atomic_store(&g.ends[s + layer], te, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
