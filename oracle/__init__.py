@@ -232,3 +232,14 @@ def memory_layers(size, t_s, t_e):
                                         _ptr(l_size), _ptr(l_ts), _ptr(l_te)))
     L = int(count[0])
     return layer_of, l_size[:L].copy(), l_ts[:L].copy(), l_te[:L].copy()
+
+
+def tmp(size, t_s, t_e, a) -> float:
+    """Time-memory product of a plan (Eq. 2, with the whole plan as the group D_g): the memory-time the
+    requests use, sum of s * (t_e - t_s), over the memory-time the plan reserves, its extent max(a + s)
+    times its span max(t_e) - min(t_s).  Exact integers, one rounding to double at the end."""
+    from fractions import Fraction
+    used = sum(int(s) * (int(e) - int(b)) for s, b, e in zip(size, t_s, t_e))
+    extent = max(int(x) + int(s) for x, s in zip(a, size))
+    span = max(int(e) for e in t_e) - min(int(b) for b in t_s)
+    return float(Fraction(used, extent * span))

@@ -43,6 +43,10 @@
  * hand-worked example, the optimum of interval partitioning (as many layers as
  * requests of the size are ever alive at once), structural invariants, closed forms
  * and the validity of the plan that the layers expand to (tests/test_oracle_layers.py).
+ *
+ * The time-memory product of a plan (Eq. 2) is a ratio of exact integers and lives in
+ * the Python part of the oracle (oracle/__init__.py, tmp), pinned by closed forms, the
+ * area bound, unit invariances and an instant-by-instant count (tests/test_oracle_tmp.py).
  */
 #include <stdint.h>
 #include <stdlib.h>
