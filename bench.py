@@ -332,6 +332,10 @@ def main() -> int:
         v_all, ms_all = timed(lambda: S.stalloc_validate(size, ta, tf, tr.t_end, all_rows, workspace_cache=cache_all))
         v_one, ms_one = timed(lambda: S.stalloc_validate(size, ta, tf, tr.t_end, best_row, workspace_cache=cache_one))
         l_out, ms_lb = timed(lambda: S.stalloc_lower_bound(size, ta, tf, tr.t_end, workspace_cache=cache_l))
+        cache_t = {}
+        t_out, ms_tmp = timed(lambda: S.stalloc_tmp(size, ta, tf, tr.t_end, plan["peaks"], workspace_cache=cache_t))
+        S.check_status(t_out, "stalloc_tmp")
+        tmp_all = t_out["tmp"].cpu().numpy()
         S.check_status(v_all, "stalloc_validate")
         S.check_status(v_one, "stalloc_validate")
         S.check_status(l_out, "stalloc_lower_bound")
@@ -339,7 +343,10 @@ def main() -> int:
             print("bench.py: a plan has conflicts", file=sys.stderr)
             return 1
         lb_bytes = 32 * n + 16 * stats["T"]
+        result["quality"]["tmp_best_plan"] = float(tmp_all[best])          # Eq. 2 over the whole plan
+        result["quality"]["tmp_median"] = float(np.median(tmp_all))
         result["checks"] = {
+            "tmp_all_plans": {"ms_per_call": ms_tmp, "algorithmic_bytes": 16 * n + 16 * P},
             "validate_all_plans": pair_roofline(P, ms_all),
             "validate_best_plan": pair_roofline(1, ms_one),
             "lower_bound": {"ms_per_call": ms_lb,

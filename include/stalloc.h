@@ -192,6 +192,21 @@ int stalloc_expand_layers(uint32_t n, uint32_t P, const uint32_t *layer_of,
                           const uint64_t *layer_offsets, uint32_t n_layers, uint64_t *offsets,
                           uint32_t *device_status, void *hip_stream);
 
+/*
+ * Time-memory product of Eq. 2 for P plans of one trace, the whole plan taken as the
+ * group: the memory-time the requests use, sum of size * (t_free - t_alloc), over the
+ * memory-time the plan reserves, extent * (max t_free - min t_alloc).  1 means no
+ * spatio-temporal bubble; plans of one trace differ in their extent only.
+ *
+ *   extents  device [P], extent max(a + s) of every plan (`peaks` of stalloc_plan);
+ *            an extent of 0 yields infinity
+ *   tmp      device [P], double precision; the numerator is summed exactly, the result
+ *            is within 10 * 2^-53 (relative) of the exact ratio
+ */
+int stalloc_tmp(const stalloc_trace *trace, const uint64_t *extents, uint32_t P, double *tmp,
+                uint32_t *device_status,
+                void *workspace, size_t *workspace_bytes, void *hip_stream);
+
 /* Human-readable name of a stalloc_status; never NULL.  Host memory, static storage. */
 const char *stalloc_status_string(int status);
 

@@ -23,7 +23,7 @@ STATUS = {0: "STALLOC_OK", 1: "STALLOC_ERR_INVALID_ARG", 2: "STALLOC_ERR_BAD_TRA
           4: "STALLOC_ERR_NOMEM", 5: "STALLOC_ERR_DEVICE", 6: "STALLOC_ERR_BAD_ORDER", 7: "STALLOC_ERR_BAD_WINDOW",
           8: "STALLOC_ERR_BAD_LAYER"}
 EXPORTS = ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_reusable_space",
-           "stalloc_memory_layers", "stalloc_expand_layers",
+           "stalloc_memory_layers", "stalloc_expand_layers", "stalloc_tmp",
            "stalloc_status_string", "stalloc_plan_lds_capacity", "stalloc_plan_list_layout")
 
 
@@ -52,8 +52,9 @@ def _load() -> ctypes.CDLL:
     lib.stalloc_reusable_space.argtypes = [tp, vp, vp, u32, u32, vp, vp, vp, vp, vp, szp, vp]
     lib.stalloc_memory_layers.argtypes = [tp, vp, vp, vp, vp, vp, vp, vp, szp, vp]
     lib.stalloc_expand_layers.argtypes = [u32, u32, vp, vp, u32, vp, vp, vp]
+    lib.stalloc_tmp.argtypes = [tp, vp, u32, vp, vp, vp, szp, vp]
     for name in ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_reusable_space",
-                 "stalloc_memory_layers", "stalloc_expand_layers"):
+                 "stalloc_memory_layers", "stalloc_expand_layers", "stalloc_tmp"):
         getattr(lib, name).restype = ctypes.c_int
     lib.stalloc_status_string.argtypes = [ctypes.c_int]
     lib.stalloc_status_string.restype = ctypes.c_char_p
@@ -258,4 +259,23 @@ def stalloc_expand_layers(layer_of, layer_offsets, *, stream=None) -> Dict[str, 
                                      _dev(layer_offsets, torch.int64, "layer_offsets"), n_layers,
                                      out["offsets"].data_ptr(), out["status"].data_ptr(), _stream(stream)),
            "stalloc_expand_layers")
+    return out
+
+
+def stalloc_tmp(size, t_alloc, t_free, t_end: int, extents, *, stream=None,
+                workspace_cache: Optional[Dict] = None) -> Dict[str, torch.Tensor]:
+    """extents int64 [P] (`peaks` of stalloc_plan) -> tmp float64 [P], status int32 [1]."""
+    tr = _trace(size, t_alloc, t_free, t_end)
+    if extents.dim() != 1:
+        raise ValueError("extents must be [P]")
+    P, dev = extents.numel(), size.device
+    out = {"tmp": torch.empty(P, dtype=torch.float64, device=dev),
+           "status": torch.empty(1, dtype=torch.int32, device=dev)}
+    args = (ctypes.byref(tr), _dev(extents, torch.int64, "extents"), P, out["tmp"].data_ptr(), out["status"].data_ptr())
+    need = ctypes.c_size_t(0)
+    _check(lib.stalloc_tmp(*args, None, ctypes.byref(need), None), "stalloc_tmp(workspace query)")
+    ws = _workspace(need.value, dev, workspace_cache)
+    have = ctypes.c_size_t(ws.numel())
+    _check(lib.stalloc_tmp(*args, ws.data_ptr(), ctypes.byref(have), _stream(stream)), "stalloc_tmp")
+    out["workspace"] = ws
     return out
