@@ -63,11 +63,14 @@ def _bind(path: str):
     lib.oracle_exact_optimum.argtypes = [u32, p, p, p, p, p]
     lib.oracle_reusable_space.argtypes = [u32, p, p, p, p, u32, u32, u64, p, p, p]
     lib.oracle_memory_layers.argtypes = [u32, p, p, p, p, p, p, p, p]
+    lib.oracle_make_orders.argtypes = [u32, p, p, p, u32, u32, u64, p]
+    lib.oracle_splitmix64.argtypes = [u64]
+    lib.oracle_splitmix64.restype = u64
     for name in ("oracle_check_trace", "oracle_plan_allpairs", "oracle_conflict_lists",
                  "oracle_plan_lists", "oracle_best_plan", "oracle_validate",
                  "oracle_lower_bound_definition", "oracle_lower_bound_sweep",
                  "oracle_best_over_all_orders", "oracle_exact_optimum", "oracle_reusable_space",
-                 "oracle_memory_layers"):
+                 "oracle_memory_layers", "oracle_make_orders"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -243,3 +246,17 @@ def tmp(size, t_s, t_e, a) -> float:
     extent = max(int(x) + int(s) for x, s in zip(a, size))
     span = max(int(e) for e in t_e) - min(int(b) for b in t_s)
     return float(Fraction(used, extent * span))
+
+
+def splitmix64(x: int) -> int:
+    """Output of the SplitMix64 generator whose state before the step is x."""
+    return int(_load().oracle_splitmix64(int(x) & 0xFFFFFFFFFFFFFFFF))
+
+
+def make_orders(size, t_s, t_e, P: int, seed: int = 1000, first_plan: int = 0) -> np.ndarray:
+    """Candidate placement orders first_plan .. first_plan + P - 1 as uint32 [P][n]."""
+    size, t_s, t_e = _c(size, np.uint64), _c(t_s, np.uint32), _c(t_e, np.uint32)
+    orders = np.zeros((P, len(size)), dtype=np.uint32)
+    _check(_load().oracle_make_orders(len(size), _ptr(size), _ptr(t_s), _ptr(t_e), int(first_plan), int(P), int(seed),
+                                      _ptr(orders)))
+    return orders

@@ -44,6 +44,11 @@
  * requests of the size are ever alive at once), structural invariants, closed forms
  * and the validity of the plan that the layers expand to (tests/test_oracle_layers.py).
  *
+ * Candidate placement orders: oracle_make_orders, pinned by the published outputs of
+ * SplitMix64, the sorting rules checked on the result, agreement with the numpy input
+ * generator of workloads/ and the statistics of the two random families
+ * (tests/test_oracle_orders.py).
+ *
  * The time-memory product of a plan (Eq. 2) is a ratio of exact integers and lives in
  * the Python part of the oracle (oracle/__init__.py, tmp), pinned by closed forms, the
  * area bound, unit invariances and an instant-by-instant count (tests/test_oracle_tmp.py).
@@ -464,5 +469,89 @@ int oracle_memory_layers(uint32_t n, const uint64_t *size, const uint32_t *t_s,
     }
     free(m);
     *n_layers = layers;
+    return ORC_OK;
+}
+
+/*
+ * Candidate placement orders.  Row p is a permutation of the request numbers:
+ *   p = 0          by size descending, then allocation time, then number -- large
+ *                  requests first, so that smaller ones fill the intervals they leave
+ *                  (Sec. 5.1, Global Planning);
+ *   p = 1          by lifetime descending, then size descending, then number;
+ *   p = 2          by allocation time, then number (the order Algorithm 1 takes);
+ *   p >= 3, odd    by a 64-bit pseudo-random key k(p, i), then number: a uniform
+ *                  random permutation;
+ *   p >= 4, even   by (c(i) + 1) * 2^32 + (k(p, i) >> 31), then number, where c(i) is
+ *                  the number of distinct sizes larger than request i's: size
+ *                  descending, with a random order inside each size and a shift of up
+ *                  to one size to either side.
+ * k(p, i) = mix(i * 0xD1342543DE82EF95 + mix(seed + p)), all modulo 2^64, where mix(x)
+ * is the output of the SplitMix64 generator (Steele, Lea, Flood: "Fast splittable
+ * pseudorandom number generators", OOPSLA 2014; constants of Vigna's public-domain
+ * splitmix64.c) whose state before the step is x: so any row, and any key, can be
+ * produced on its own from (seed, p, i).
+ * Writes rows first_plan .. first_plan + P - 1 to orders[P][n].
+ */
+uint64_t oracle_splitmix64(uint64_t x)
+{
+    uint64_t z = x + 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+typedef struct { uint64_t k0, k1; uint32_t k2; uint32_t id; } order_key_t;
+
+static int order_key_cmp(const void *pa, const void *pb)
+{
+    const order_key_t *x = (const order_key_t *)pa, *y = (const order_key_t *)pb;
+    if (x->k0 != y->k0) return x->k0 < y->k0 ? -1 : 1;
+    if (x->k1 != y->k1) return x->k1 < y->k1 ? -1 : 1;
+    if (x->k2 != y->k2) return x->k2 < y->k2 ? -1 : 1;
+    return x->id < y->id ? -1 : (x->id > y->id ? 1 : 0);
+}
+
+static int u64_desc(const void *pa, const void *pb)
+{
+    const uint64_t x = *(const uint64_t *)pa, y = *(const uint64_t *)pb;
+    return x > y ? -1 : (x < y ? 1 : 0);
+}
+
+int oracle_make_orders(uint32_t n, const uint64_t *size, const uint32_t *t_s, const uint32_t *t_e,
+                       uint32_t first_plan, uint32_t P, uint64_t seed, uint32_t *orders)
+{
+    if (n == 0 || P == 0 || !size || !t_s || !t_e || !orders) return ORC_INVALID_ARG;
+    order_key_t *m = (order_key_t *)malloc((size_t)n * sizeof(order_key_t));
+    uint64_t *distinct = (uint64_t *)malloc((size_t)n * sizeof(uint64_t));
+    uint32_t *larger = (uint32_t *)malloc((size_t)n * sizeof(uint32_t));
+    if (!m || !distinct || !larger) { free(m); free(distinct); free(larger); return ORC_NOMEM; }
+    /* c(i): number of distinct sizes larger than size[i] */
+    memcpy(distinct, size, (size_t)n * sizeof(uint64_t));
+    qsort(distinct, n, sizeof(uint64_t), u64_desc);
+    uint32_t d = 0;
+    for (uint32_t k = 0; k < n; ++k)
+        if (k == 0 || distinct[k] != distinct[k - 1]) distinct[d++] = distinct[k];
+    for (uint32_t i = 0; i < n; ++i) {
+        uint32_t c = 0;
+        while (distinct[c] != size[i]) ++c;
+        larger[i] = c;
+    }
+    for (uint32_t r = 0; r < P; ++r) {
+        const uint64_t p = (uint64_t)first_plan + r;
+        const uint64_t stream = oracle_splitmix64(seed + p);
+        for (uint32_t i = 0; i < n; ++i) {
+            const uint64_t k = oracle_splitmix64((uint64_t)i * 0xD1342543DE82EF95ull + stream);
+            m[i].id = i;
+            m[i].k0 = 0; m[i].k1 = 0; m[i].k2 = 0;
+            if (p == 0)          { m[i].k0 = ~size[i]; m[i].k2 = t_s[i]; }
+            else if (p == 1)     { m[i].k0 = ~(uint64_t)(t_e[i] - t_s[i]); m[i].k1 = ~size[i]; }
+            else if (p == 2)     { m[i].k2 = t_s[i]; }
+            else if (p % 2 == 1) { m[i].k0 = k; }
+            else                 { m[i].k0 = (((uint64_t)larger[i] + 1) << 32) + (k >> 31); }
+        }
+        qsort(m, n, sizeof(order_key_t), order_key_cmp);
+        for (uint32_t q = 0; q < n; ++q) orders[(size_t)r * n + q] = m[q].id;
+    }
+    free(m); free(distinct); free(larger);
     return ORC_OK;
 }

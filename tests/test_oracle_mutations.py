@@ -9,6 +9,7 @@ import pytest
 import test_oracle_pins as pins
 import test_oracle_reusable as reusable
 import test_oracle_layers as layers
+import test_oracle_orders as orders
 
 MUTATIONS = {
     "closed_lifetimes": ("return ts_a < te_b && ts_b < te_a;", "return ts_a <= te_b && ts_b <= te_a;"),
@@ -35,6 +36,12 @@ MUTATIONS = {
     "layer_end_not_updated": ("        layer_t_e[best] = t_e[i];\n    }\n    free(m);", "        if (layer_t_e[best] < t_e[i]) layer_t_e[best] = t_e[i] - 1;\n    }\n    free(m);"),
     "layer_groups_ascending": ("if (x->size != y->size) return x->size > y->size ? -1 : 1;", "if (x->size != y->size) return x->size > y->size ? 1 : -1;"),
     "layer_by_number_not_start": ("if (x->t_s != y->t_s) return x->t_s < y->t_s ? -1 : 1;\n    return x->id < y->id", "return x->id < y->id"),
+    "orders_jitter_one_bit_short": ("<< 32) + (k >> 31); }", "<< 32) + (k >> 32); }"),
+    "orders_lifetime_row_by_size_first": ("{ m[i].k0 = ~(uint64_t)(t_e[i] - t_s[i]); m[i].k1 = ~size[i]; }",
+                                          "{ m[i].k1 = ~(uint64_t)(t_e[i] - t_s[i]); m[i].k0 = ~size[i]; }"),
+    "orders_generator_shift": ("z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;", "z = (z ^ (z >> 28)) * 0x94D049BB133111EBull;"),
+    "orders_counter_not_spread": ("(uint64_t)i * 0xD1342543DE82EF95ull + stream", "(uint64_t)i + stream"),
+    "orders_classes_ascending": ("return x > y ? -1 : (x < y ? 1 : 0);", "return x > y ? 1 : (x < y ? -1 : 0);"),
     "extent_forgets_size": ("if (a[i] + size[i] > top) top = a[i] + size[i];\n    }\n    free(spans);\n    *extent",
                             "if (a[i] > top) top = a[i];\n    }\n    free(spans);\n    *extent"),
 }
@@ -59,6 +66,10 @@ def _battery(oracle):
     for seed in range(6):
         reusable.test_matches_byte_map(oracle, seed)
     reusable.test_lowest_fit_plans_have_no_idle_space_over_the_whole_iteration(oracle, 0)
+    orders.test_splitmix64_published_outputs(oracle)
+    orders.test_rows_are_permutations_and_heuristic_rows_follow_their_rules(oracle, 0)
+    orders.test_matches_the_input_generator(oracle, 1)
+    orders.test_random_families_have_the_intended_statistics(oracle)
     layers.test_hand_worked_example(oracle)
     layers.test_closed_forms(oracle)
     for seed in range(4):
