@@ -207,6 +207,29 @@ int stalloc_tmp(const stalloc_trace *trace, const uint64_t *extents, uint32_t P,
                 uint32_t *device_status,
                 void *workspace, size_t *workspace_bytes, void *hip_stream);
 
+/*
+ * Candidate placement orders, produced on the device: rows first_plan .. first_plan + P - 1
+ * of the family below, each a permutation of 0 .. n-1 (the stable sort of the requests by the
+ * row's key), ready for stalloc_plan.
+ *   row 0          size descending, then allocation time: large requests first, so that
+ *                  smaller ones fill the intervals they leave (Sec. 5.1, Global Planning)
+ *   row 1          lifetime descending, then size descending
+ *   row 2          allocation time (the order in which Algorithm 1 takes a group's requests)
+ *   rows >= 3, odd   a 64-bit pseudo-random key k(p, i): a uniform random permutation
+ *   rows >= 4, even  (c(i) + 1) * 2^32 + (k(p, i) >> 31), c(i) = number of distinct sizes larger
+ *                  than request i's: size descending, with a random order inside each size
+ *                  and a shift of up to one size to either side
+ * k(p, i) = mix(i * 0xD1342543DE82EF95 + mix(seed + p)) modulo 2^64, where mix(x) is the output
+ * of the SplitMix64 generator (Steele, Lea, Flood, OOPSLA 2014) whose state before the step is
+ * x.  Any window of rows can be produced on its own.
+ *
+ *   orders   device [P][n]
+ * The workspace holds the sort buffers of up to 1 GiB worth of rows at a time.
+ */
+int stalloc_make_orders(const stalloc_trace *trace, uint32_t first_plan, uint32_t P, uint64_t seed,
+                        uint32_t *orders, uint32_t *device_status,
+                        void *workspace, size_t *workspace_bytes, void *hip_stream);
+
 /* Human-readable name of a stalloc_status; never NULL.  Host memory, static storage. */
 const char *stalloc_status_string(int status);
 

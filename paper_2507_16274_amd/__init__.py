@@ -23,7 +23,7 @@ STATUS = {0: "STALLOC_OK", 1: "STALLOC_ERR_INVALID_ARG", 2: "STALLOC_ERR_BAD_TRA
           4: "STALLOC_ERR_NOMEM", 5: "STALLOC_ERR_DEVICE", 6: "STALLOC_ERR_BAD_ORDER", 7: "STALLOC_ERR_BAD_WINDOW",
           8: "STALLOC_ERR_BAD_LAYER"}
 EXPORTS = ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_reusable_space",
-           "stalloc_memory_layers", "stalloc_expand_layers", "stalloc_tmp",
+           "stalloc_memory_layers", "stalloc_expand_layers", "stalloc_tmp", "stalloc_make_orders",
            "stalloc_status_string", "stalloc_plan_lds_capacity", "stalloc_plan_list_layout")
 
 
@@ -53,8 +53,10 @@ def _load() -> ctypes.CDLL:
     lib.stalloc_memory_layers.argtypes = [tp, vp, vp, vp, vp, vp, vp, vp, szp, vp]
     lib.stalloc_expand_layers.argtypes = [u32, u32, vp, vp, u32, vp, vp, vp]
     lib.stalloc_tmp.argtypes = [tp, vp, u32, vp, vp, vp, szp, vp]
+    lib.stalloc_make_orders.argtypes = [tp, u32, u32, ctypes.c_uint64, vp, vp, vp, szp, vp]
     for name in ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_reusable_space",
-                 "stalloc_memory_layers", "stalloc_expand_layers", "stalloc_tmp"):
+                 "stalloc_memory_layers", "stalloc_expand_layers", "stalloc_tmp",
+                 "stalloc_make_orders"):
         getattr(lib, name).restype = ctypes.c_int
     lib.stalloc_status_string.argtypes = [ctypes.c_int]
     lib.stalloc_status_string.restype = ctypes.c_char_p
@@ -277,5 +279,22 @@ def stalloc_tmp(size, t_alloc, t_free, t_end: int, extents, *, stream=None,
     ws = _workspace(need.value, dev, workspace_cache)
     have = ctypes.c_size_t(ws.numel())
     _check(lib.stalloc_tmp(*args, ws.data_ptr(), ctypes.byref(have), _stream(stream)), "stalloc_tmp")
+    out["workspace"] = ws
+    return out
+
+
+def stalloc_make_orders(size, t_alloc, t_free, t_end: int, P: int, *, seed: int = 1000, first_plan: int = 0,
+                        stream=None, workspace_cache: Optional[Dict] = None) -> Dict[str, torch.Tensor]:
+    """-> orders int32 [P][n] (rows first_plan .. first_plan + P - 1), status int32 [1]."""
+    tr = _trace(size, t_alloc, t_free, t_end)
+    dev = size.device
+    out = {"orders": torch.empty((P, tr.n), dtype=torch.int32, device=dev),
+           "status": torch.empty(1, dtype=torch.int32, device=dev)}
+    args = (ctypes.byref(tr), int(first_plan), int(P), int(seed), out["orders"].data_ptr(), out["status"].data_ptr())
+    need = ctypes.c_size_t(0)
+    _check(lib.stalloc_make_orders(*args, None, ctypes.byref(need), None), "stalloc_make_orders(workspace query)")
+    ws = _workspace(need.value, dev, workspace_cache)
+    have = ctypes.c_size_t(ws.numel())
+    _check(lib.stalloc_make_orders(*args, ws.data_ptr(), ctypes.byref(have), _stream(stream)), "stalloc_make_orders")
     out["workspace"] = ws
     return out

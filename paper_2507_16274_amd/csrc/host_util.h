@@ -80,4 +80,9 @@ constexpr uint32_t kBitmapGranules = 1u << 21; // a placed block's address has 2
 constexpr uint32_t kBitmapMaxSize = 31;        // a block touches at most two bitmap words, its size fits 5 bits
 void launch_trace_check(const stalloc_trace& tr, uint64_t* acc, uint32_t* device_status, hipStream_t stream);
 
+// Exclusive sums of in[0..m) into out (defined in layers.hip): three launches; chunk_sum needs
+// (m + 1023) / 1024 words; total[0] receives the sum of all; nothing happens unless *status is OK.
+void launch_scan(const uint32_t* in, uint32_t m, uint32_t* out, uint32_t* chunk_sum, uint32_t* total,
+                 const uint32_t* status, hipStream_t stream);
+
 }  // namespace stalloc

@@ -353,8 +353,8 @@ ly_expand(const uint32_t* __restrict__ layer_of, const uint64_t* __restrict__ la
 }
 
 // Exclusive sums of in[0..m) into out; total[0] = sum.  chunk_sum: (m + 1023) / 1024 words.
-static void launch_scan(const uint32_t* in, uint32_t m, uint32_t* out, uint32_t* chunk_sum, uint32_t* total,
-                        const uint32_t* status, hipStream_t stream)
+void launch_scan(const uint32_t* in, uint32_t m, uint32_t* out, uint32_t* chunk_sum, uint32_t* total,
+                 const uint32_t* status, hipStream_t stream)
 {
     const uint32_t chunks = (m + kScanChunk - 1) / kScanChunk;
     hipLaunchKernelGGL(scan_chunk_sums, dim3(chunks), dim3(256), 0, stream, in, m, chunk_sum, status);

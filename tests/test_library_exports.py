@@ -65,6 +65,11 @@ def test_layer_calls_reject_bad_host_arguments():
     assert S.lib.stalloc_expand_layers(4, 1, 1, 1, 0, 1, 1, None) == 1          # no layers
     assert S.lib.stalloc_expand_layers(4, 1, None, 1, 2, 1, 1, None) == 1       # NULL layer_of
     assert S.lib.stalloc_tmp(None, None, 1, None, None, None, ctypes.byref(need), None) == 1
+    assert S.lib.stalloc_make_orders(None, 0, 1, 5, None, None, None, ctypes.byref(need), None) == 1
+    tr = S._Trace(4, 8, 1, 1, 1)
+    assert S.lib.stalloc_make_orders(ctypes.byref(tr), 0, 0, 5, None, None, None, ctypes.byref(need), None) == 1      # P == 0
+    assert S.lib.stalloc_make_orders(ctypes.byref(tr), 0xfffffff0, 32, 5, None, None, None, ctypes.byref(need), None) == 1
+    assert S.lib.stalloc_make_orders(ctypes.byref(tr), 7, 9, 5, None, None, None, ctypes.byref(need), None) == 0 and need.value > 0
     tr = S._Trace(4, 8, 1, 1, 1)
     assert S.lib.stalloc_tmp(ctypes.byref(tr), None, 0, None, None, None, ctypes.byref(need), None) == 1   # P == 0
     assert S.lib.stalloc_tmp(ctypes.byref(tr), None, 3, None, None, None, ctypes.byref(need), None) == 0 and need.value > 0
