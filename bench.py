@@ -60,6 +60,9 @@ def main() -> int:
     ap.add_argument("--checks", action="store_true",
                     help="also time stalloc_validate (all plans; the best plan alone) and stalloc_lower_bound in timed "
                          "regions of their own (reported beside the step)")
+    ap.add_argument("--make-orders", action="store_true",
+                    help="also produce the run's orders on the device (stalloc_make_orders) in a timed region of its "
+                         "own and compare them with the host's arrays")
     ap.add_argument("--layers", action="store_true",
                     help="also build the memory-layers of the trace (Algorithm 1), plan the layers under as many "
                          "orders and expand the plans to the requests, in a timed region of its own")
@@ -246,6 +249,33 @@ def main() -> int:
             wall = time.perf_counter() - t1
             result["reusable_space"]["cpu_baseline"] = {"value": sample / wall, "unit": "windows/s", "cores": 1,
                                                         "kind": "oracle", "sample": f"first {sample} windows"}
+
+    if args.make_orders:
+        # The orders of this run produced on the device: P rows of n keys sorted.  What must move is the
+        # result (4 B per entry); the sort itself writes 16-byte keys once per pass (log2(n / 256) + 1 passes).
+        cache_o = {}
+        for _ in range(max(args.warmup, 1)):
+            made = S.stalloc_make_orders(size, ta, tf, tr.t_end, P, workspace_cache=cache_o)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            made = S.stalloc_make_orders(size, ta, tf, tr.t_end, P, workspace_cache=cache_o)
+        e1.record()
+        torch.cuda.synchronize()
+        S.check_status(made, "stalloc_make_orders")
+        if not torch.equal(made["orders"], orders):
+            print("bench.py: orders made on the device differ from the host's", file=sys.stderr)
+            return 1
+        mo_ms = e0.elapsed_time(e1) / args.steps
+        passes = 1 + max(0, int(np.ceil(np.log2(max(1, -(-n // 256))))))
+        result["make_orders"] = {
+            "ms_per_call": mo_ms, "keys_per_s": n * P / (mo_ms * 1e-3), "sort_passes": passes,
+            "roofline": {"bound": "hbm", "kernel": "or_sort_tiles + or_merge passes + or_emit",
+                         "achieved": 4 * n * P / (mo_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": 4 * n * P / (mo_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                         "algorithmic_bytes": 4 * n * P,
+                         "sort_buffer_GBs": (32 * passes + 4) * n * P / (mo_ms * 1e-3) / 1e9}}
 
     if args.layers:
         # HomoSize groups -> memory-layers (Sec. 5.1, Algorithm 1), each layer planned as one request under
