@@ -27,6 +27,7 @@ namespace stalloc {
 
 constexpr int kLyTile = 256;
 constexpr int kLyRegs = 8;                       // 64 layers per register: 512 layers of a group in registers
+static_assert(kLyRegs == 8, "ly_build dispatches on one to eight registers in use");
 
 // (size descending, allocation time, request number) as two ascending 64-bit words
 struct LyKey { uint64_t a, b; };
@@ -218,6 +219,31 @@ struct LyBuild {
     uint32_t n;
 };
 
+// One request of a group whose layers all sit in the first kRegs registers (a layer it opens
+// included): returns its layer and makes the request the layer's last one.  `layers` is uniform.
+template <int kRegs>
+__device__ __forceinline__ uint32_t take_layer(uint32_t (&end_of)[kLyRegs], uint32_t ts, uint32_t te, uint32_t layers)
+{
+    const uint32_t lane = (uint32_t)lane_id();
+    // latest end among the free layers (an end is a free time, hence >= 1; 0 = not opened)
+    uint32_t latest = 0;
+#pragma unroll
+    for (int r = 0; r < kRegs; ++r) latest = umax(latest, end_of[r] <= ts ? end_of[r] : 0u);
+    const uint32_t best = __builtin_amdgcn_readlane(wave_scan_max(latest), kWave - 1);
+    uint32_t layer = layers;                                              // a new one unless a free layer is found
+    if (best != 0) {
+        bool found = false;
+#pragma unroll
+        for (int r = 0; r < kRegs; ++r) {
+            const uint64_t hit = __builtin_amdgcn_ballot_w64(end_of[r] == best);
+            if (!found && hit) { layer = (uint32_t)r * kWave + (uint32_t)__builtin_ctzll(hit); found = true; }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kRegs; ++r) end_of[r] = ((uint32_t)r == layer / kWave && lane == layer % kWave) ? te : end_of[r];
+    return layer;
+}
+
 __global__ void __launch_bounds__(256) ly_build(LyBuild g)
 {
     if (*g.status != STALLOC_OK) return;
@@ -242,7 +268,28 @@ __global__ void __launch_bounds__(256) ly_build(LyBuild g)
             const int members = e - base < (uint32_t)kWave ? (int)(e - base) : kWave;
             for (int q = 0; q < members; ++q) {
                 const uint32_t ts = __builtin_amdgcn_readlane(ts_k, q), te = __builtin_amdgcn_readlane(te_k, q);
-                // latest end among the free layers (an end is a free time, hence >= 1)
+                layers = __builtin_amdgcn_readfirstlane(layers);
+                if (layers < (uint32_t)(kLyRegs * kWave)) {
+                    // the usual case: everything in registers, code specialised for the registers in use
+                    uint32_t layer;
+                    switch (layers / kWave) {
+                        case 0: layer = take_layer<1>(end_of, ts, te, layers); break;
+                        case 1: layer = take_layer<2>(end_of, ts, te, layers); break;
+                        case 2: layer = take_layer<3>(end_of, ts, te, layers); break;
+                        case 3: layer = take_layer<4>(end_of, ts, te, layers); break;
+                        case 4: layer = take_layer<5>(end_of, ts, te, layers); break;
+                        case 5: layer = take_layer<6>(end_of, ts, te, layers); break;
+                        case 6: layer = take_layer<7>(end_of, ts, te, layers); break;
+                        default: layer = take_layer<8>(end_of, ts, te, layers); break;
+                    }
+                    if (layer == layers) {
+                        if (lane == 0) g.first_ts[s + layers] = ts;
+                        ++layers;
+                    }
+                    if (lane == q) mine = layer;
+                    continue;
+                }
+                // a group with 512 layers or more: the further ones are kept in memory
                 uint32_t latest = 0;
 #pragma unroll
                 for (int r = 0; r < kLyRegs; ++r)
