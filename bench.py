@@ -43,7 +43,8 @@ ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12  # 256 CUs x 64 integer lanes x 2.4 GHz 
 # script (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, KiB, factors from a 256 MiB copy in the same
 # runs).  Keyed by (configuration, orders, layout code); valid for the kernels as committed
 # with these figures only.
-MEASURED_TRAFFIC = {(2, 1024, 0x304): (7_164_610 * 2 + 190_749) * 1024}
+MEASURED_TRAFFIC = {(2, 1024, 0x304): (7_164_610 * 2 + 190_749) * 1024,
+                    (4, 512, 0x010): (145_172_818 * 2 + 143_083_633) * 1024}
 
 
 def main() -> int:
