@@ -61,6 +61,9 @@ def main() -> int:
     ap.add_argument("--checks", action="store_true",
                     help="also time stalloc_validate (all plans; the best plan alone) and stalloc_lower_bound in timed "
                          "regions of their own (reported beside the step)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also capture one step in a graph and time its replays (the calls allocate nothing and use "
+                         "the caller's stream only)")
     ap.add_argument("--make-orders", action="store_true",
                     help="also produce the run's orders on the device (stalloc_make_orders) in a timed region of its "
                          "own and compare them with the host's arrays")
@@ -250,6 +253,31 @@ def main() -> int:
             wall = time.perf_counter() - t1
             result["reusable_space"]["cpu_baseline"] = {"value": sample / wall, "unit": "windows/s", "cores": 1,
                                                         "kind": "oracle", "sample": f"first {sample} windows"}
+
+    if args.graph:
+        # One step captured once and replayed: the ~30 launches of a step cost no host time any more.
+        g_stream = torch.cuda.Stream()
+        g_stream.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(g_stream):
+            step(False)
+            g_stream.synchronize()
+            with torch.cuda.graph(graph, stream=g_stream):
+                g_plan, g_val, g_lb = step(False)
+        torch.cuda.current_stream().wait_stream(g_stream)
+        for _ in range(max(args.warmup, 1)):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        g_elapsed = time.perf_counter() - t1
+        if not torch.equal(g_plan["peaks"], plan["peaks"]) or int(g_val["conflicts"].item()) != 0 or \
+                int(g_lb["lower_bound"].item()) != lower_bound:
+            print("bench.py: the replayed step differs from the eager one", file=sys.stderr)
+            return 1
+        result["graph"] = {"ms_per_step": g_elapsed / args.steps * 1e3, "value": n * P * args.steps / g_elapsed}
 
     if args.make_orders:
         # The orders of this run produced on the device: P rows of n keys sorted.  What must move is the
