@@ -323,6 +323,52 @@ def test_plan_config3_sampled_orderings(S, oracle):
     assert not cnt.any()
 
 
+def test_plan_config3_full_launch_every_eighth_ordering(S, oracle):
+    """All 2048 orders of config 3 in one call, as the benchmark launches them (more orders than resident
+    workgroups); every eighth plan compared address by address, and all extents are at least the lower
+    bound.  (All 2048 were compared once by hand: equal.)"""
+    import torch
+    tr = make_trace(3)
+    P = CONFIGS[3].n_orderings
+    orders = make_orderings(tr, P)
+    got = _gpu_plan(S, tr, orders)
+    assert got["status"] == 0
+    rows = np.arange(0, P, 8)
+    lists = oracle.conflict_lists(tr.t_alloc, tr.t_free)
+    a, ext = oracle.plan_many(tr.size, tr.t_alloc, tr.t_free, orders[rows], threads=THREADS, method="lists", lists=lists)
+    assert np.array_equal(got["peaks"][rows], ext)
+    assert np.array_equal(got["offsets"][rows], a)
+    status, lb, _ = _gpu_lower_bound(S, tr)
+    assert status == 0 and (got["peaks"] >= lb).all()
+    assert int(got["best_plan"]) == int(np.argmin(got["peaks"]))
+
+
+@pytest.mark.parametrize("cfg,P,rows", [(4, 2048, [5, 2040]), (5, 512, [1, 510])])
+def test_plan_large_configs_full_launches(S, oracle, cfg, P, rows):
+    """Config 4 with all its 2048 orders and config 5 with 512 (every resident workgroup busy, several
+    orders per workgroup on config 4), the orders made on the device: sampled plans compared address by
+    address, every plan checked for conflicts over all pairs, every extent at least the lower bound."""
+    import torch
+    tr = make_trace(cfg)
+    size, ta, tf = S.trace_to_device(tr)
+    made = S.stalloc_make_orders(size, ta, tf, tr.t_end, P)
+    plan = S.stalloc_plan(size, ta, tf, tr.t_end, made["orders"], want_best_offsets=False)
+    val = S.stalloc_validate(size, ta, tf, tr.t_end, plan["offsets"])
+    lb = S.stalloc_lower_bound(size, ta, tf, tr.t_end)
+    torch.cuda.synchronize()
+    assert [int(x["status"].item()) for x in (made, plan, val, lb)] == [0, 0, 0, 0]
+    assert not val["conflicts"].cpu().numpy().any()
+    peaks = plan["peaks"].cpu().numpy().view(np.uint64)
+    assert (peaks >= np.uint64(int(lb["lower_bound"].item()))).all()
+    assert int(plan["best_plan"].item()) == int(np.argmin(peaks))
+    orders = made["orders"][rows].cpu().numpy().view(np.uint32)
+    assert np.array_equal(orders, make_orderings(tr, CONFIGS[cfg].n_orderings, rows=rows))
+    lists = oracle.conflict_lists(tr.t_alloc, tr.t_free)
+    a, ext = oracle.plan_many(tr.size, tr.t_alloc, tr.t_free, orders, threads=THREADS, method="lists", lists=lists)
+    assert np.array_equal(peaks[rows], ext)
+    assert np.array_equal(plan["offsets"][rows].cpu().numpy().view(np.uint64), a)
+
+
 def test_plan_config4_sampled_orderings(S, oracle):
     """MoE trace (47 748 requests, 1229 distinct sizes): heuristic rows and sampled random rows."""
     tr = make_trace(4)
