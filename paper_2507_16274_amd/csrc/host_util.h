@@ -85,4 +85,11 @@ void launch_trace_check(const stalloc_trace& tr, uint64_t* acc, uint32_t* device
 void launch_scan(const uint32_t* in, uint32_t m, uint32_t* out, uint32_t* chunk_sum, uint32_t* total,
                  const uint32_t* status, hipStream_t stream);
 
+// Rows of n_pad two-word keys (n_pad a multiple of 256, all keys of a row distinct, compared word
+// by word), every tile of 256 already sorted: merges the tiles of each row (defined in orders.hip),
+// one launch per doubling of the run length, `keys` and `spare` in turn; returns the one that
+// holds the sorted rows.
+ulonglong2* launch_merge_tiles(ulonglong2* keys, ulonglong2* spare, uint32_t n_pad, uint32_t rows, const uint32_t* status,
+                               hipStream_t stream);
+
 }  // namespace stalloc

@@ -8,9 +8,10 @@
 // free a new layer is opened.  Layers are numbered group by group in descending size, inside
 // a group in the order in which they were opened.
 //
-//   sort     Requests are ranked by (size descending, allocation time, request number): tiles
-//            of 256 keys sorted in LDS (bitonic network), then every key is located in every
-//            other sorted tile by binary search -- n^2 / 32 steps, no scratch passes.
+//   sort     Requests are sorted by (size descending, allocation time, request number): tiles
+//            of 256 keys sorted in LDS (bitonic network), merged in log2(n / 256) passes (an
+//            element's place is its place in its own run plus the number of elements of the
+//            partner run that sort before it, found by binary search).
 //   groups   A group starts where the size changes in the sorted sequence; exclusive sums of
 //            the start flags number the groups.
 //   build    One wave per group walks its requests in order -- the construction is
@@ -29,83 +30,48 @@ constexpr int kLyTile = 256;
 constexpr int kLyRegs = 8;                       // 64 layers per register: 512 layers of a group in registers
 static_assert(kLyRegs == 8, "ly_build dispatches on one to eight registers in use");
 
-// (size descending, allocation time, request number) as two ascending 64-bit words
-struct LyKey { uint64_t a, b; };
-__device__ __forceinline__ bool before(const LyKey& x, const LyKey& y) { return x.a < y.a || (x.a == y.a && x.b < y.b); }
+// Keys (size descending, allocation time, request number) as two ascending 64-bit words.
+__device__ __forceinline__ bool before(const ulonglong2& x, const ulonglong2& y) { return x.x < y.x || (x.x == y.x && x.y < y.y); }
 
-__global__ void ly_init(uint32_t* rank, uint32_t n)
+__global__ void ly_init(uint32_t* v, uint32_t n)
 {
-    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) rank[i] = 0;
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) v[i] = 0;
 }
 
-// One tile of 256 requests per workgroup, sorted in LDS; past-the-end slots hold (~0, ~0) and sort last.
+// One tile of 256 requests per workgroup, sorted in LDS; slot e past the end holds a key behind
+// every real one, (~0, ~0 << 32 | e) (sizes are > 0, so no real key starts with ~0).
 __global__ void __launch_bounds__(kLyTile)
-ly_sort_tiles(const uint64_t* __restrict__ size, const uint32_t* __restrict__ ta, uint32_t n, uint64_t* t_a, uint64_t* t_b,
+ly_sort_tiles(const uint64_t* __restrict__ size, const uint32_t* __restrict__ ta, uint32_t n, ulonglong2* keys,
               const uint32_t* status)
 {
-    __shared__ uint64_t k_a[kLyTile];
-    __shared__ uint64_t k_b[kLyTile];
+    __shared__ ulonglong2 k[kLyTile];
     if (*status != STALLOC_OK) return;
     const uint32_t t = threadIdx.x, i = blockIdx.x * kLyTile + t;
-    const bool ok = i < n;
-    k_a[t] = ok ? ~size[i] : ~0ull;                   // sizes are > 0, so a real key never equals the filler
-    k_b[t] = ok ? ((uint64_t)ta[i] << 32) | i : ~0ull;
+    k[t] = i < n ? make_ulonglong2(~size[i], ((uint64_t)ta[i] << 32) | i) : make_ulonglong2(~0ull, 0xffffffff00000000ull | i);
     for (uint32_t span = 2; span <= (uint32_t)kLyTile; span <<= 1) {
         for (uint32_t gap = span >> 1; gap > 0; gap >>= 1) {
             __syncthreads();
             const uint32_t other = t ^ gap;
             if (other > t) {
-                const LyKey x = {k_a[t], k_b[t]}, y = {k_a[other], k_b[other]};
+                const ulonglong2 x = k[t], y = k[other];
                 const bool ascending = (t & span) == 0;
-                if (before(y, x) == ascending) {
-                    k_a[t] = y.a; k_b[t] = y.b;
-                    k_a[other] = x.a; k_b[other] = x.b;
-                }
+                if (before(y, x) == ascending) { k[t] = y; k[other] = x; }
             }
         }
     }
     __syncthreads();
-    t_a[blockIdx.x * kLyTile + t] = k_a[t];
-    t_b[blockIdx.x * kLyTile + t] = k_b[t];
+    keys[blockIdx.x * kLyTile + t] = k[t];
 }
 
-// grid (tiles, slices of the tile range): thread p of workgroup b holds the key at position p of
-// sorted tile b and adds, to its request's rank, how many keys of the slice's tiles sort before it.
-__global__ void __launch_bounds__(kLyTile)
-ly_rank(const uint64_t* __restrict__ t_a, const uint64_t* __restrict__ t_b, uint32_t n, uint32_t tiles,
-        uint32_t tiles_per_slice, uint32_t* rank, const uint32_t* status)
-{
-    __shared__ uint64_t k_a[kLyTile];
-    __shared__ uint64_t k_b[kLyTile];
-    if (*status != STALLOC_OK) return;
-    const uint32_t p = threadIdx.x, own = blockIdx.x;
-    const LyKey me = {t_a[own * kLyTile + p], t_b[own * kLyTile + p]};
-    uint32_t count = 0;
-    const uint32_t tile0 = blockIdx.y * tiles_per_slice;
-    for (uint32_t t = tile0; t < tile0 + tiles_per_slice && t < tiles; ++t) {
-        if (t == own) { count += p; continue; }                                  // (uniform)
-        __syncthreads();
-        k_a[p] = t_a[t * kLyTile + p];
-        k_b[p] = t_b[t * kLyTile + p];
-        __syncthreads();
-        uint32_t lo = 0;                                                          // first position not before `me`
-        for (uint32_t half = kLyTile / 2; half > 0; half >>= 1) {
-            const LyKey probe = {k_a[lo + half - 1], k_b[lo + half - 1]};
-            if (before(probe, me)) lo += half;
-        }
-        const LyKey last = {k_a[lo], k_b[lo]};                                    // lo <= 255 here
-        count += lo + (before(last, me) ? 1u : 0u);
-    }
-    const uint32_t id = (uint32_t)me.b;
-    if (me.a != ~0ull && id < n && count) atomicAdd(&rank[id], count);
-}
-
-// sorted[rank of i] = i
+// sorted[k] = request at sorted position k
 __global__ void __launch_bounds__(256)
-ly_scatter(const uint32_t* __restrict__ rank, uint32_t n, uint32_t* sorted, const uint32_t* status)
+ly_ids(const ulonglong2* __restrict__ keys, uint32_t n, uint32_t* sorted, const uint32_t* status)
 {
     if (*status != STALLOC_OK) return;
-    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) sorted[rank[i]] = i;
+    for (uint32_t k = blockIdx.x * blockDim.x + threadIdx.x; k < n; k += gridDim.x * blockDim.x) {
+        const uint32_t i = (uint32_t)keys[k].y;
+        sorted[k] = i < n ? i : 0u;                           // (the first n sorted keys are the real ones)
+    }
 }
 
 __global__ void __launch_bounds__(256)
@@ -427,9 +393,8 @@ extern "C" int stalloc_memory_layers(const stalloc_trace* tr, uint32_t* layer_of
 
     Carver cv(workspace);
     uint64_t* acc = cv.take<uint64_t>(kAccWords);
-    uint32_t* rank = cv.take<uint32_t>(n);
-    uint64_t* t_a = cv.take<uint64_t>((size_t)tiles * kLyTile);
-    uint64_t* t_b = cv.take<uint64_t>((size_t)tiles * kLyTile);
+    ulonglong2* keys = cv.take<ulonglong2>((size_t)tiles * kLyTile);
+    ulonglong2* spare = cv.take<ulonglong2>((size_t)tiles * kLyTile);
     uint32_t* sorted = cv.take<uint32_t>(n);
     uint32_t* flag = cv.take<uint32_t>(n);
     uint32_t* flags_before = cv.take<uint32_t>(n);
@@ -451,18 +416,9 @@ extern "C" int stalloc_memory_layers(const stalloc_trace* tr, uint32_t* layer_of
 
     uint32_t blocks = (n + 255) / 256;
     if (blocks > 1024) blocks = 1024;
-    hipLaunchKernelGGL(ly_init, dim3(blocks), dim3(256), 0, stream, rank, n);
-    hipLaunchKernelGGL(ly_sort_tiles, dim3(tiles), dim3(kLyTile), 0, stream, tr->size, tr->t_alloc, n, t_a, t_b,
-                       device_status);
-    // enough slices of the tile range to fill the chip, at least 8 tiles each
-    uint32_t slices = (uint32_t)di.cus * 8 / tiles;
-    if (slices < 1) slices = 1;
-    if (slices > (tiles + 7) / 8) slices = (tiles + 7) / 8;
-    const uint32_t tiles_per_slice = (tiles + slices - 1) / slices;
-    slices = (tiles + tiles_per_slice - 1) / tiles_per_slice;
-    hipLaunchKernelGGL(ly_rank, dim3(tiles, slices), dim3(kLyTile), 0, stream, t_a, t_b, n, tiles, tiles_per_slice, rank,
-                       device_status);
-    hipLaunchKernelGGL(ly_scatter, dim3(blocks), dim3(256), 0, stream, rank, n, sorted, device_status);
+    hipLaunchKernelGGL(ly_sort_tiles, dim3(tiles), dim3(kLyTile), 0, stream, tr->size, tr->t_alloc, n, keys, device_status);
+    const ulonglong2* by_key = launch_merge_tiles(keys, spare, tiles * kLyTile, 1, device_status, stream);
+    hipLaunchKernelGGL(ly_ids, dim3(blocks), dim3(256), 0, stream, by_key, n, sorted, device_status);
     hipLaunchKernelGGL(ly_flags, dim3(blocks), dim3(256), 0, stream, tr->size, sorted, n, flag, device_status);
     launch_scan(flag, n, flags_before, chunk_sum, n_groups, device_status, stream);
     hipLaunchKernelGGL(ly_group_starts, dim3(blocks), dim3(256), 0, stream, flag, flags_before, n, group_start,

@@ -94,6 +94,20 @@ or_sort_tiles(OrTrace t, uint64_t first_plan, uint64_t seed, uint32_t n_pad, ulo
     keys[(size_t)blockIdx.y * n_pad + e] = k[th];
 }
 
+// Element e of a row whose runs of `run` keys are merged in pairs: where it goes.
+__device__ __forceinline__ uint32_t merged_place(const ulonglong2* row, uint32_t n_pad, uint32_t run, uint32_t e,
+                                                 const ulonglong2& me)
+{
+    const uint32_t mine = e / run;                              // my run; its partner is the other one of the pair
+    const uint32_t other0 = (mine ^ 1u) * run;
+    uint32_t lo = 0, hi = other0 < n_pad ? (n_pad - other0 < run ? n_pad - other0 : run) : 0u;
+    while (lo < hi) {                                           // keys of the partner that sort before mine
+        const uint32_t mid = (lo + hi) >> 1;
+        if (key_before(row[other0 + mid], me)) lo = mid + 1; else hi = mid;
+    }
+    return (mine & ~1u) * run + (e - mine * run) + lo;
+}
+
 // grid (tiles, rows): runs of `run` keys merged in pairs, src -> dst.
 __global__ void __launch_bounds__(kOrTile)
 or_merge(const ulonglong2* __restrict__ src, ulonglong2* dst, uint32_t n_pad, uint32_t run, const uint32_t* status)
@@ -102,15 +116,33 @@ or_merge(const ulonglong2* __restrict__ src, ulonglong2* dst, uint32_t n_pad, ui
     const uint32_t e = blockIdx.x * kOrTile + threadIdx.x;
     const ulonglong2* row = src + (size_t)blockIdx.y * n_pad;
     const ulonglong2 me = row[e];
-    const uint32_t mine = e / run;                              // my run; its partner is the other one of the pair
-    const uint32_t other0 = (mine ^ 1u) * run;
-    uint32_t lo = 0, hi = other0 < n_pad ? (n_pad - other0 < run ? n_pad - other0 : run) : 0u;
-    while (lo < hi) {                                           // keys of the partner that sort before mine
-        const uint32_t mid = (lo + hi) >> 1;
-        if (key_before(row[other0 + mid], me)) lo = mid + 1; else hi = mid;
+    dst[(size_t)blockIdx.y * n_pad + merged_place(row, n_pad, run, e, me)] = me;
+}
+
+// Short rows in one launch, grid (tiles, rows): thread p of workgroup b holds the key at position p
+// of sorted tile b; its place in the row is p plus, for every other tile (staged in LDS), the
+// number of that tile's keys that sort before it.
+constexpr uint32_t kOrShortRow = 8192;
+__global__ void __launch_bounds__(kOrTile)
+or_place_short(const ulonglong2* __restrict__ src, ulonglong2* dst, uint32_t n_pad, const uint32_t* status)
+{
+    __shared__ ulonglong2 k[kOrTile];
+    if (*status != STALLOC_OK) return;
+    const uint32_t p = threadIdx.x, own = blockIdx.x, tiles = n_pad / kOrTile;
+    const ulonglong2* row = src + (size_t)blockIdx.y * n_pad;
+    const ulonglong2 me = row[own * kOrTile + p];
+    uint32_t place = p;
+    for (uint32_t t = 0; t < tiles; ++t) {
+        if (t == own) continue;                                  // (uniform)
+        __syncthreads();
+        k[p] = row[t * kOrTile + p];
+        __syncthreads();
+        uint32_t lo = 0;                                         // first position of the tile not before `me`
+        for (uint32_t half = kOrTile / 2; half > 0; half >>= 1)
+            if (key_before(k[lo + half - 1], me)) lo += half;
+        place += lo + (key_before(k[lo], me) ? 1u : 0u);         // lo <= 255 here
     }
-    const uint32_t pair0 = (mine & ~1u) * run;
-    dst[(size_t)blockIdx.y * n_pad + pair0 + (e - mine * run) + lo] = me;
+    dst[(size_t)blockIdx.y * n_pad + place] = me;
 }
 
 __global__ void __launch_bounds__(256)
@@ -141,18 +173,30 @@ or_size_classes(const ulonglong2* __restrict__ keys, const uint32_t* __restrict_
         larger[(uint32_t)keys[k].y] = flags_before[k] + flag[k];
 }
 
-// Sorts `rows` rows starting at plan first_plan; returns the buffer that holds the result.
-static ulonglong2* sort_rows(const OrTrace& t, uint64_t first_plan, uint32_t rows, uint64_t seed, uint32_t n_pad,
-                             ulonglong2* buf_a, ulonglong2* buf_b, const uint32_t* status, hipStream_t stream)
+ulonglong2* launch_merge_tiles(ulonglong2* keys, ulonglong2* spare, uint32_t n_pad, uint32_t rows, const uint32_t* status,
+                               hipStream_t stream)
 {
     const uint32_t tiles = n_pad / kOrTile;
-    hipLaunchKernelGGL(or_sort_tiles, dim3(tiles, rows), dim3(kOrTile), 0, stream, t, first_plan, seed, n_pad, buf_a, status);
-    ulonglong2 *src = buf_a, *dst = buf_b;
+    ulonglong2 *src = keys, *dst = spare;
+    if (n_pad <= kOrShortRow) {
+        if (tiles == 1) return keys;
+        hipLaunchKernelGGL(or_place_short, dim3(tiles, rows), dim3(kOrTile), 0, stream, keys, spare, n_pad, status);
+        return spare;
+    }
     for (uint64_t run = kOrTile; run < n_pad; run <<= 1) {
         hipLaunchKernelGGL(or_merge, dim3(tiles, rows), dim3(kOrTile), 0, stream, src, dst, n_pad, (uint32_t)run, status);
         ulonglong2* s = src; src = dst; dst = s;
     }
     return src;
+}
+
+// Sorts `rows` rows starting at plan first_plan; returns the buffer that holds the result.
+static ulonglong2* sort_rows(const OrTrace& t, uint64_t first_plan, uint32_t rows, uint64_t seed, uint32_t n_pad,
+                             ulonglong2* buf_a, ulonglong2* buf_b, const uint32_t* status, hipStream_t stream)
+{
+    hipLaunchKernelGGL(or_sort_tiles, dim3(n_pad / kOrTile, rows), dim3(kOrTile), 0, stream, t, first_plan, seed, n_pad, buf_a,
+                       status);
+    return launch_merge_tiles(buf_a, buf_b, n_pad, rows, status, stream);
 }
 
 }  // namespace stalloc

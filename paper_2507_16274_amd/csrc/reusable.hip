@@ -5,13 +5,15 @@
 // the highest end address of the whole plan; the reusable space is A_i = A \ A_o.  It is returned
 // as its maximal intervals in ascending address order.  Windows are half-open like lifespans.
 //
-//   rank     The decisions are sorted by (start address, request number) once per call: tiles of
-//            256 are sorted in LDS (bitonic network); the rank of a decision is then its position
-//            in its own tile plus, for every other tile, the number of that tile's decisions
-//            that sort before it -- a binary search in the tile, staged in LDS.  n^2 / 32 steps
-//            in all, no scratch passes, nothing to tune, no dependence on how the addresses are
-//            distributed.
-//   scatter  (start, end, lifespan) of every decision go to their rank.
+//   sort     The decisions are sorted by (start address, request number) once per call: tiles of
+//            256 keys are sorted in LDS (bitonic network) and merged in log2(n / 256) passes,
+//            an element's place being its place in its own run plus the number of elements
+//            of the partner run that sort before it (binary search); nothing depends on how
+//            the addresses are distributed.
+//   gather   (start, end, lifespan) of the decisions in that order; the unit of the pool's
+//            addresses (largest power of two dividing every start and end relative to the
+//            pool's start): when 32-bit counts of it cover the pool, the sweep below runs on
+//            such counts.
 //   sweep    One workgroup per window over the address-sorted decisions, each wave a contiguous
 //            part, 64 decisions a step.  A decision counts if its lifespan meets the window; a
 //            wave64 running maximum (DPP) of the ends of those before it is "covered so far", and a
@@ -20,12 +22,13 @@
 //            "covered" it starts from; (2) the number of intervals per wave, which gives every wave
 //            its place in the output; (3) the intervals themselves.  What lies between the last
 //            covered address and the end of the pool is the final interval.
-//            With thousands of windows the roles are exchanged: a workgroup takes 64 windows, one
-//            per lane, each of its 16 waves a contiguous part of the sorted decisions, which
+//            With thousands of windows the roles are exchanged: a wave takes 64 windows, one
+//            per lane, and a contiguous part of the sorted decisions, which
 //            are taken one at a time as wave-uniform values -- two compares per decision tell
 //            for all 64 windows whether it counts (most decisions count for none and are done
 //            with), and "covered so far" is a per-lane maximum without any cross-lane step.  The
-//            same three walks, at a fraction of the instructions per decision and window.
+//            same three walks (one launch each, a wave per group of windows and part of the
+//            plan), at a fraction of the instructions per decision and window.
 #include "host_util.h"
 #include "wave.h"
 
@@ -35,32 +38,30 @@ constexpr int kRsTile = 256;
 constexpr int kRsThreads = 256;
 constexpr int kRsWaves = kRsThreads / kWave;
 
-struct RsPool { uint64_t lo, hi; };      // A = [lo, hi)
+// A = [lo, hi).  Every start and end address, taken relative to lo, is a multiple of 2^shift
+// (the largest such power); `narrow` says that the pool counted in those units fits 32 bits.
+struct RsPool { uint64_t lo, hi, bits; uint32_t shift, narrow; };
 
-__global__ void rs_init(uint32_t* rank, uint32_t n, RsPool* pool)
+__global__ void rs_init(RsPool* pool)
 {
-    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) rank[i] = 0;
-    if (blockIdx.x == 0 && threadIdx.x == 0) { pool->lo = ~0ull; pool->hi = 0; }
+    if (threadIdx.x == 0) { pool->lo = ~0ull; pool->hi = 0; pool->bits = 0; pool->shift = 0; pool->narrow = 0; }
 }
 
-// (address, request number), ordered lexicographically
-struct RsKey { uint64_t a; uint32_t id; };
-__device__ __forceinline__ bool before(const RsKey& x, const RsKey& y) { return x.a < y.a || (x.a == y.a && x.id < y.id); }
+// Keys (address, request number), compared word by word.
+__device__ __forceinline__ bool before(const ulonglong2& x, const ulonglong2& y) { return x.x < y.x || (x.x == y.x && x.y < y.y); }
 
-// One tile of 256 decisions per workgroup: sorted in LDS, written to t_a / t_id; past-the-end
-// slots hold (~0, ~0) and sort last.  Also the pool's bounds.
+// One tile of 256 decisions per workgroup, sorted in LDS; slot e past the end holds a key behind
+// every real one, (~0, ~0 << 32 | e).  Also the pool's bounds.
 __global__ void __launch_bounds__(kRsTile)
-rs_sort_tiles(const uint64_t* __restrict__ size, const uint64_t* __restrict__ offsets, uint32_t n, uint64_t* t_a,
-              uint32_t* t_id, RsPool* pool, const uint32_t* status)
+rs_sort_tiles(const uint64_t* __restrict__ size, const uint64_t* __restrict__ offsets, uint32_t n, ulonglong2* keys,
+              RsPool* pool, const uint32_t* status)
 {
-    __shared__ uint64_t k_a[kRsTile];
-    __shared__ uint32_t k_id[kRsTile];
+    __shared__ ulonglong2 k[kRsTile];
     if (*status != STALLOC_OK) return;
     const uint32_t t = threadIdx.x, i = blockIdx.x * kRsTile + t;
     const bool ok = i < n;
     const uint64_t a = ok ? offsets[i] : ~0ull;
-    k_a[t] = a;
-    k_id[t] = ok ? i : ~0u;
+    k[t] = ok ? make_ulonglong2(a, i) : make_ulonglong2(~0ull, 0xffffffff00000000ull | i);
     {
         const uint64_t lo = wave_min64(a);                                       // (slots past n hold ~0)
         const uint64_t hi = wave_max64(ok ? a + size[i] : 0ull);
@@ -74,65 +75,72 @@ rs_sort_tiles(const uint64_t* __restrict__ size, const uint64_t* __restrict__ of
             __syncthreads();
             const uint32_t other = t ^ gap;
             if (other > t) {
-                const RsKey x = {k_a[t], k_id[t]}, y = {k_a[other], k_id[other]};
+                const ulonglong2 x = k[t], y = k[other];
                 const bool ascending = (t & span) == 0;
-                if (before(y, x) == ascending) {
-                    k_a[t] = y.a; k_id[t] = y.id;
-                    k_a[other] = x.a; k_id[other] = x.id;
-                }
+                if (before(y, x) == ascending) { k[t] = y; k[other] = x; }
             }
         }
     }
     __syncthreads();
-    t_a[blockIdx.x * kRsTile + t] = k_a[t];
-    t_id[blockIdx.x * kRsTile + t] = k_id[t];
+    keys[blockIdx.x * kRsTile + t] = k[t];
 }
 
-// grid (tiles, slices of the tile range): thread p of workgroup b holds the decision at position p
-// of sorted tile b and adds, to its rank, how many decisions of the slice's tiles sort before it.
-__global__ void __launch_bounds__(kRsTile)
-rs_rank(const uint64_t* __restrict__ t_a, const uint32_t* __restrict__ t_id, uint32_t n, uint32_t tiles,
-        uint32_t tiles_per_slice, uint32_t* rank, const uint32_t* status)
-{
-    __shared__ uint64_t k_a[kRsTile];
-    __shared__ uint32_t k_id[kRsTile];
-    if (*status != STALLOC_OK) return;
-    const uint32_t p = threadIdx.x, own = blockIdx.x;
-    const RsKey me = {t_a[own * kRsTile + p], t_id[own * kRsTile + p]};
-    uint32_t count = 0;
-    const uint32_t tile0 = blockIdx.y * tiles_per_slice;
-    for (uint32_t t = tile0; t < tile0 + tiles_per_slice && t < tiles; ++t) {
-        if (t == own) { count += p; continue; }                                  // (uniform)
-        __syncthreads();
-        k_a[p] = t_a[t * kRsTile + p];
-        k_id[p] = t_id[t * kRsTile + p];
-        __syncthreads();
-        uint32_t lo = 0;                                                          // first position not before `me`
-        for (uint32_t half = kRsTile / 2; half > 0; half >>= 1) {
-            const RsKey probe = {k_a[lo + half - 1], k_id[lo + half - 1]};
-            if (before(probe, me)) lo += half;
-        }
-        const RsKey last = {k_a[lo], k_id[lo]};                                   // lo <= 255 here
-        count += lo + (before(last, me) ? 1u : 0u);
-    }
-    if (me.id < n && count) atomicAdd(&rank[me.id], count);
-}
-
+// (start, end, lifespan) of the decisions in address order; the bits set in any start or end
+// address relative to the pool's start.
 __global__ void __launch_bounds__(256)
-rs_scatter(const uint64_t* __restrict__ size, const uint32_t* __restrict__ ta, const uint32_t* __restrict__ tf,
-           const uint64_t* __restrict__ offsets, const uint32_t* __restrict__ rank, uint32_t n,
-           uint64_t* s_lo, uint64_t* s_hi, uint2* s_life, const uint32_t* status)
+rs_gather(const uint64_t* __restrict__ size, const uint32_t* __restrict__ ta, const uint32_t* __restrict__ tf,
+          const uint64_t* __restrict__ offsets, const ulonglong2* __restrict__ sorted, uint32_t n,
+          uint64_t* s_lo, uint64_t* s_hi, uint2* s_life, RsPool* pool, const uint32_t* status)
 {
+    __shared__ uint64_t part[4];
     if (*status != STALLOC_OK) return;
-    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
-        const uint32_t r = rank[i];
-        s_lo[r] = offsets[i];
-        s_hi[r] = offsets[i] + size[i];
+    const uint64_t pool_lo = pool->lo;
+    uint64_t bits = 0;
+    for (uint32_t r = blockIdx.x * blockDim.x + threadIdx.x; r < n; r += gridDim.x * blockDim.x) {
+        uint32_t i = (uint32_t)sorted[r].y;
+        if (i >= n) i = 0;                                   // (cannot happen: the first n sorted keys are the real ones)
+        const uint64_t lo = offsets[i], hi = lo + size[i];
+        s_lo[r] = lo;
+        s_hi[r] = hi;
         s_life[r] = make_uint2(ta[i], tf[i]);
+        bits |= (lo - pool_lo) | (hi - pool_lo);
+    }
+    bits = wave_or64(bits);
+    if (lane_id() == 0) part[wave_id()] = bits;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        bits = part[0] | part[1] | part[2] | part[3];
+        if (bits) atomicOr((unsigned long long*)&pool->bits, (unsigned long long)bits);
+    }
+}
+
+// The unit of the pool's addresses and whether 32-bit counts of it cover the pool.
+__global__ void rs_units(RsPool* pool, const uint32_t* status)
+{
+    if (*status != STALLOC_OK || threadIdx.x != 0) return;
+    const uint64_t span = pool->hi - pool->lo;                  // > 0: sizes are
+    const uint32_t shift = (uint32_t)__builtin_ctzll(pool->bits | span);
+    pool->shift = shift;
+    pool->narrow = (span >> shift) <= 0xffffffffull ? 1u : 0u;
+}
+
+// Start and end of every sorted decision in units of the pool, relative to its start.
+__global__ void __launch_bounds__(256)
+rs_compress(const uint64_t* __restrict__ s_lo, const uint64_t* __restrict__ s_hi, uint32_t n, const RsPool* pool,
+            uint32_t* c_lo, uint32_t* c_hi, const uint32_t* status)
+{
+    if (*status != STALLOC_OK || !pool->narrow) return;
+    const uint64_t pool_lo = pool->lo;
+    const uint32_t shift = pool->shift;
+    for (uint32_t r = blockIdx.x * blockDim.x + threadIdx.x; r < n; r += gridDim.x * blockDim.x) {
+        c_lo[r] = (uint32_t)((s_lo[r] - pool_lo) >> shift);
+        c_hi[r] = (uint32_t)((s_hi[r] - pool_lo) >> shift);
     }
 }
 
 struct RsArgs {
+    const uint32_t* c_lo;        // sorted decisions in 32-bit units of the pool (valid when the pool is narrow)
+    const uint32_t* c_hi;
     const uint64_t* s_lo;
     const uint64_t* s_hi;
     const uint2* s_life;
@@ -259,11 +267,19 @@ struct RsParts {
 
 // One wave = 64 windows (one per lane) x one part of the sorted plan.  kWalk = 1, 2, 3: the
 // three walks, one launch each (a part needs the results of all lower parts of the walk before).
-template <int kWalk>
-__global__ void __launch_bounds__(kRsThreads) rs_sweep_by_window(RsArgs g, RsParts sc)
+__device__ __forceinline__ uint32_t read_lane_addr(uint32_t v, int q) { return __builtin_amdgcn_readlane(v, q); }
+__device__ __forceinline__ uint64_t read_lane_addr(uint64_t v, int q) { return readlane64(v, q); }
+
+// Addr = uint32_t: addresses in units of the pool relative to its start (a narrow pool: half the
+// registers, single-instruction compares and maxima); Addr = uint64_t: byte addresses.
+template <int kWalk, typename Addr>
+__device__ __forceinline__ void sweep_by_window(const RsArgs& g, const RsParts& sc)
 {
-    if (*g.status != STALLOC_OK) return;
+    constexpr bool kNarrow = sizeof(Addr) == 4;
     const int lane = lane_id();
+    const uint64_t pool_lo = g.pool->lo;
+    const uint32_t shift = kNarrow ? g.pool->shift : 0u;
+    auto bytes = [&](Addr v) -> uint64_t { return kNarrow ? pool_lo + ((uint64_t)v << shift) : (uint64_t)v; };
     const uint32_t groups = (g.k + kWave - 1) / kWave;
     const uint32_t waves = groups * sc.parts;
     for (uint32_t unit = blockIdx.x * kRsWaves + (uint32_t)wave_id(); unit < waves; unit += gridDim.x * kRsWaves) {
@@ -288,30 +304,34 @@ __global__ void __launch_bounds__(kRsThreads) rs_sweep_by_window(RsArgs g, RsPar
                 const uint32_t at = k0 + lane;
                 const bool valid = at < g.n;
                 const uint2 life = valid ? g.s_life[at] : make_uint2(0xffffffffu, 0u);   // past the end: meets no window
-                const uint64_t lo = valid ? g.s_lo[at] : 0, hi = valid ? g.s_hi[at] : 0;
+                Addr lo = 0, hi = 0;
+                if (valid) {
+                    if constexpr (kNarrow) { lo = g.c_lo[at]; hi = g.c_hi[at]; }
+                    else { lo = g.s_lo[at]; hi = g.s_hi[at]; }
+                }
 #pragma unroll 8
                 for (int q = 0; q < kWave; ++q) {
                     const uint32_t ts_q = __builtin_amdgcn_readlane(life.x, q), te_q = __builtin_amdgcn_readlane(life.y, q);
                     const bool counts = ts_q < w_hi && w_lo < te_q;
                     if (__builtin_amdgcn_ballot_w64(counts) == 0) continue;           // (uniform)
-                    body(readlane64(lo, q), readlane64(hi, q), counts);
+                    body(read_lane_addr(lo, q), read_lane_addr(hi, q), counts);
                 }
             }
         };
 
         if constexpr (kWalk == 1) {          // how far the decisions of each part reach
-            uint64_t covered = 0;
-            walk([&](uint64_t, uint64_t end, bool counts) { covered = counts ? umax64(covered, end) : covered; });
+            Addr covered = 0;
+            walk([&](Addr, Addr end, bool counts) { covered = counts ? umax(covered, end) : covered; });
             sc.reach[row + (size_t)part * kWave] = covered;
         } else {
-            uint64_t covered = g.pool->lo;       // covered before this part
-            for (uint32_t v = 0; v < part; ++v) covered = umax64(covered, sc.reach[row + (size_t)v * kWave]);
+            Addr covered = kNarrow ? (Addr)0 : (Addr)pool_lo;       // covered before this part
+            for (uint32_t v = 0; v < part; ++v) covered = umax(covered, (Addr)sc.reach[row + (size_t)v * kWave]);
             if constexpr (kWalk == 2) {      // idle intervals closed inside each part
                 uint32_t count = 0;
-                uint64_t idle = 0;
-                walk([&](uint64_t start, uint64_t end, bool counts) {
+                Addr idle = 0;               // (disjoint intervals of the pool: fits the address type)
+                walk([&](Addr start, Addr end, bool counts) {
                     if (counts && start > covered) { ++count; idle += start - covered; }
-                    covered = counts ? umax64(covered, end) : covered;
+                    covered = counts ? umax(covered, end) : covered;
                 });
                 sc.found[row + (size_t)part * kWave] = count;
                 sc.idle[row + (size_t)part * kWave] = idle;
@@ -319,22 +339,23 @@ __global__ void __launch_bounds__(kRsThreads) rs_sweep_by_window(RsArgs g, RsPar
                 uint32_t place = 0;
                 for (uint32_t v = 0; v < part; ++v) place += sc.found[row + (size_t)v * kWave];
                 uint64_t* out = (g.ranges && live) ? g.ranges + (size_t)w * g.max_ranges * 2 : nullptr;
-                const uint64_t covered0 = covered;
+                const Addr covered0 = covered;
                 if (g.ranges) {                                           // (uniform; lanes without a window count nothing)
-                    walk([&](uint64_t start, uint64_t end, bool counts) {
+                    walk([&](Addr start, Addr end, bool counts) {
                         if (counts && start > covered) {
-                            if (place < g.max_ranges) { out[2 * place] = covered; out[2 * place + 1] = start; }
+                            if (place < g.max_ranges) { out[2 * place] = bytes(covered); out[2 * place + 1] = bytes(start); }
                             ++place;
                         }
-                        covered = counts ? umax64(covered, end) : covered;
+                        covered = counts ? umax(covered, end) : covered;
                     });
                 }
                 if (part + 1 == sc.parts && live) {
                     const size_t mine = row + (size_t)part * kWave;
-                    const uint64_t covered_all = umax64(covered0, sc.reach[mine]);
+                    const uint64_t covered_all = bytes(umax(covered0, (Addr)sc.reach[mine]));
                     uint32_t total = sc.found[mine];
                     uint64_t idle_total = sc.idle[mine];
                     for (uint32_t v = 0; v < part; ++v) { total += sc.found[row + (size_t)v * kWave]; idle_total += sc.idle[row + (size_t)v * kWave]; }
+                    idle_total <<= shift;                                 // units of the pool -> bytes
                     const uint64_t pool_hi = g.pool->hi;
                     if (covered_all < pool_hi) {                          // from the last covered address to the end of the pool
                         if (out && total < g.max_ranges) { out[2 * total] = covered_all; out[2 * total + 1] = pool_hi; }
@@ -347,6 +368,14 @@ __global__ void __launch_bounds__(kRsThreads) rs_sweep_by_window(RsArgs g, RsPar
             }
         }
     }
+}
+
+template <int kWalk>
+__global__ void __launch_bounds__(kRsThreads) rs_sweep_by_window(RsArgs g, RsParts sc)
+{
+    if (*g.status != STALLOC_OK) return;
+    if (g.pool->narrow) sweep_by_window<kWalk, uint32_t>(g, sc);       // (uniform)
+    else sweep_by_window<kWalk, uint64_t>(g, sc);
 }
 
 }  // namespace stalloc
@@ -366,13 +395,14 @@ extern "C" int stalloc_reusable_space(const stalloc_trace* tr, const uint64_t* o
     Carver cv(workspace);
     uint64_t* acc = cv.take<uint64_t>(kAccWords);
     RsPool* pool = cv.take<RsPool>(1);
-    uint32_t* rank = cv.take<uint32_t>(n);
     const uint32_t tiles = (n + kRsTile - 1) / kRsTile;
-    uint64_t* t_a = cv.take<uint64_t>((size_t)tiles * kRsTile);
-    uint32_t* t_id = cv.take<uint32_t>((size_t)tiles * kRsTile);
+    ulonglong2* keys = cv.take<ulonglong2>((size_t)tiles * kRsTile);
+    ulonglong2* spare = cv.take<ulonglong2>((size_t)tiles * kRsTile);
     uint64_t* s_lo = cv.take<uint64_t>(n);
     uint64_t* s_hi = cv.take<uint64_t>(n);
     uint2* s_life = cv.take<uint2>(n);
+    uint32_t* c_lo = cv.take<uint32_t>(n);
+    uint32_t* c_hi = cv.take<uint32_t>(n);
     // window-per-lane sweep: enough (group of 64 windows) x (part of the plan) waves to fill the chip
     RsParts sc = {nullptr, nullptr, nullptr, 0, 0};
     const uint32_t groups = (k + kWave - 1) / kWave;
@@ -397,24 +427,21 @@ extern "C" int stalloc_reusable_space(const stalloc_trace* tr, const uint64_t* o
     launch_trace_check(*tr, acc, device_status, stream);
 
     uint32_t blocks = (n + 255) / 256;
-    hipLaunchKernelGGL(rs_init, dim3(blocks > 1024 ? 1024 : blocks), dim3(256), 0, stream, rank, n, pool);
-    hipLaunchKernelGGL(rs_sort_tiles, dim3(tiles), dim3(kRsTile), 0, stream, tr->size, offsets, n, t_a, t_id, pool,
-                       device_status);
-    // enough slices of the tile range to fill the chip, at least 8 tiles each
-    uint32_t slices = (uint32_t)di.cus * 8 / tiles;
-    if (slices < 1) slices = 1;
-    if (slices > (tiles + 7) / 8) slices = (tiles + 7) / 8;
-    const uint32_t tiles_per_slice = (tiles + slices - 1) / slices;
-    slices = (tiles + tiles_per_slice - 1) / tiles_per_slice;
-    hipLaunchKernelGGL(rs_rank, dim3(tiles, slices), dim3(kRsTile), 0, stream, t_a, t_id, n, tiles, tiles_per_slice, rank,
-                       device_status);
-    hipLaunchKernelGGL(rs_scatter, dim3(blocks > 1024 ? 1024 : blocks), dim3(256), 0, stream, tr->size, tr->t_alloc,
-                       tr->t_free, offsets, rank, n, s_lo, s_hi, s_life, device_status);
+    if (blocks > 256) blocks = 256;
+    hipLaunchKernelGGL(rs_init, dim3(1), dim3(64), 0, stream, pool);
+    hipLaunchKernelGGL(rs_sort_tiles, dim3(tiles), dim3(kRsTile), 0, stream, tr->size, offsets, n, keys, pool, device_status);
+    const ulonglong2* sorted = launch_merge_tiles(keys, spare, tiles * kRsTile, 1, device_status, stream);
+    hipLaunchKernelGGL(rs_gather, dim3(blocks), dim3(256), 0, stream, tr->size, tr->t_alloc, tr->t_free, offsets, sorted, n,
+                       s_lo, s_hi, s_life, pool, device_status);
     RsArgs g;
+    g.c_lo = c_lo; g.c_hi = c_hi;
     g.s_lo = s_lo; g.s_hi = s_hi; g.s_life = s_life; g.pool = pool; g.windows = windows;
     g.ranges = max_ranges ? ranges : nullptr; g.counts = counts; g.idle_bytes = idle_bytes; g.status = device_status;
     g.n = n; g.k = k; g.max_ranges = max_ranges;
     if (rs_window_per_lane(n, k)) {
+        hipLaunchKernelGGL(rs_units, dim3(1), dim3(64), 0, stream, pool, device_status);
+        hipLaunchKernelGGL(rs_compress, dim3(blocks), dim3(256), 0, stream, s_lo, s_hi, n, pool, c_lo,
+                           c_hi, device_status);
         const uint64_t waves = (uint64_t)groups * sc.parts;
         uint32_t grid = (uint32_t)di.cus * 8;
         if (grid > (waves + kRsWaves - 1) / kRsWaves) grid = (uint32_t)((waves + kRsWaves - 1) / kRsWaves);

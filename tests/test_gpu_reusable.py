@@ -115,7 +115,8 @@ def test_more_windows_than_resident_workgroups(S, oracle):
 @pytest.mark.parametrize("seed", range(6))
 def test_thousands_of_windows(S, oracle, seed):
     """From 2^23 decisions x windows on, a lane takes a window and a wave 64 of them over a part of the
-    sorted plan: ragged last groups and parts, tied and unique times, truncated rows."""
+    sorted plan: ragged last groups and parts, tied and unique times, truncated rows; pools that 32-bit
+    counts of their address unit cover (the usual case) and pools that need 64-bit byte addresses."""
     rng = np.random.default_rng(4200 + seed)
     n = [131, 300, 1025, 4099, 5000, 20000][seed]
     k = [64100, 28001, 8200, 2049, 2560, 2050][seed]
@@ -123,6 +124,8 @@ def test_thousands_of_windows(S, oracle, seed):
     if seed % 3 == 0:
         size = size * np.uint64(1 << 37)
     a = (rng.integers(0, max(2, 4 * n), n).astype(np.uint64)) * (size.max() if seed % 3 == 0 else np.uint64(1))
+    if seed in (1, 4):                                   # odd byte addresses over 2 TB: no 32-bit unit covers the pool
+        a = rng.integers(0, 1 << 41, n).astype(np.uint64) | np.uint64(1)
     lo = rng.integers(0, t_end, k)
     hi = np.minimum(lo + np.exp(rng.uniform(0, np.log(max(2, t_end // 2)), k)).astype(np.int64), t_end + 3)
     windows = np.stack([lo, np.maximum(hi, lo + 1)], axis=1).astype(np.uint32)
