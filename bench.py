@@ -231,7 +231,7 @@ def main() -> int:
         result["reusable_space"] = {
             "windows": K, "ms_per_call": rs_ms, "windows_per_s": K / (rs_ms * 1e-3),
             "mean_intervals": mean_intervals,
-            "roofline": {"bound": "alu", "kernel": "rs_sweep / rs_sweep_by_window (+ rs_rank, rs_scatter)",
+            "roofline": {"bound": "alu", "kernel": "rs_sweep / rs_sweep_by_window (+ sort, rs_gather)",
                          "achieved": rs_ops / (rs_ms * 1e-3) / 1e12, "peak": ALU_PEAK_TOPS, "unit": "TOP/s",
                          "frac": rs_ops / (rs_ms * 1e-3) / 1e12 / ALU_PEAK_TOPS,
                          "traffic": None, "algorithmic_ops": rs_ops, "algorithmic_bytes": must_move,

@@ -119,7 +119,7 @@ or_merge(const ulonglong2* __restrict__ src, ulonglong2* dst, uint32_t n_pad, ui
     dst[(size_t)blockIdx.y * n_pad + merged_place(row, n_pad, run, e, me)] = me;
 }
 
-// Short rows in one launch, grid (tiles, rows): thread p of workgroup b holds the key at position p
+// A few short rows in one launch (n^2 / 32 steps a row instead of n log n, but no launch per pass), grid (tiles, rows): thread p of workgroup b holds the key at position p
 // of sorted tile b; its place in the row is p plus, for every other tile (staged in LDS), the
 // number of that tile's keys that sort before it.
 constexpr uint32_t kOrShortRow = 8192;
@@ -178,8 +178,8 @@ ulonglong2* launch_merge_tiles(ulonglong2* keys, ulonglong2* spare, uint32_t n_p
 {
     const uint32_t tiles = n_pad / kOrTile;
     ulonglong2 *src = keys, *dst = spare;
-    if (n_pad <= kOrShortRow) {
-        if (tiles == 1) return keys;
+    if (tiles == 1) return keys;
+    if (n_pad <= kOrShortRow && (uint64_t)rows * tiles <= 2048) {       // few short rows: launches are what costs
         hipLaunchKernelGGL(or_place_short, dim3(tiles, rows), dim3(kOrTile), 0, stream, keys, spare, n_pad, status);
         return spare;
     }
