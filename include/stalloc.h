@@ -22,7 +22,8 @@
  *   - Return value: a stalloc_status for everything the host can see (NULL
  *     pointers, n == 0, P == 0, workspace too small, launch failure).  Defects only
  *     visible on the device (size 0, t_alloc >= t_free, t_free > t_end, sum of sizes
- *     >= 2^63, an order entry >= n, an empty time window) are written as a stalloc_status to
+ *     >= 2^63, an order entry >= n, an empty time window, a layer number that does not
+ *     exist) are written as a stalloc_status to
  *     `device_status[0]` (0 when clean); when it is non-zero every other output of
  *     that call is unspecified, but all kernels still terminate normally.
  *   - Lifetimes and address ranges are half-open; no alignment is applied; byte
