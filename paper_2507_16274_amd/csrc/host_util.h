@@ -68,14 +68,16 @@ struct Carver {
 // acc: device uint64_t[kAccWords] scratch {sum of high halves, sum of low halves, flags,
 // OR of all sizes, mode, largest size, sum of sizes in granules}.  mode = log2(address granule)
 // | kModeNarrow when 32-bit granule counts can hold every address | kModeCompact when 16-bit
-// counts can | kModeBitmap when the sizes suit one-bit-per-granule occupancy bitmaps.
+// counts can | kModeBitmap when the sizes suit one-bit-per-granule occupancy bitmaps | kModeTry32
+// when only plans that stack nearly everything would overflow 32-bit counts.
 constexpr int kAccWords = 8;
 constexpr int kAccMode = 4;
 constexpr int kAccMaxSize = 5;
-constexpr int kAccGranules = 6;                // valid with kModeNarrow
+constexpr int kAccGranules = 6;                // sum of sizes in granules
 constexpr uint64_t kModeNarrow = 1ull << 8;
 constexpr uint64_t kModeCompact = 1ull << 9;   // sum of sizes in granules below 2^16 as well
 constexpr uint64_t kModeBitmap = 1ull << 10;   // sum <= kBitmapGranules and every size <= kBitmapMaxSize granules
+constexpr uint64_t kModeTry32 = 1ull << 11;    // not narrow, but every size < 2^30 granules: 32-bit counts are tried plan by plan
 constexpr uint32_t kBitmapGranules = 1u << 21; // a placed block's address has 22 bits in the kernel's table
 constexpr uint32_t kBitmapMaxSize = 31;        // a block touches at most two bitmap words, its size fits 5 bits
 void launch_trace_check(const stalloc_trace& tr, uint64_t* acc, uint32_t* device_status, hipStream_t stream);

@@ -84,6 +84,7 @@ struct PlanLds {
     Span<Addr> pend_span[kPend];                           // blocks settled in this batch, sorted
     uint2 pend_life[kPend];
     uint32_t settled;
+    Addr extent_now;                                       // extent of the plan after the last settled batch
 };
 
 // The sorted list of placed blocks.  Two storage layouts:
@@ -660,7 +661,11 @@ __global__ void __launch_bounds__(kThreads, 4) plan_kernel(PlanParams prm)   // 
     const uint64_t mode = prm.acc[kAccMode];
     if (bitmap_shape(mode, prm.acc[kAccGranules], prm.bitmap_pool_words) >= 0) return;   // the occupancy-bitmap kernel places this trace
     const bool narrow = (mode & kModeNarrow) != 0;
-    if (narrow != (sizeof(Addr) == 4)) return;            // another instantiation handles this trace
+    // Not narrow, but no request is large: the 32-bit instantiation takes every plan as far as
+    // 32-bit granule counts certainly hold its addresses and marks the plans that outgrow them;
+    // the 64-bit instantiation (enqueued behind it) places those from scratch.
+    const bool try32 = (mode & kModeTry32) != 0;
+    if (sizeof(Addr) == 4 ? !(narrow || try32) : narrow) return;     // another instantiation handles this trace
     // of the two 32-bit instantiations the compact one runs when it was enqueued and applies
     const bool compact = prm.compact_enqueued && (mode & kModeCompact) != 0;
     if (sizeof(Addr) == 4 && compact != kCompact) return;
@@ -677,10 +682,14 @@ __global__ void __launch_bounds__(kThreads, 4) plan_kernel(PlanParams prm)   // 
     }
 
     for (uint32_t p = blockIdx.x; p < prm.P; p += gridDim.x) {
+        if (sizeof(Addr) == 8 && try32 && !prm.wide_plans[p]) continue;   // (uniform) placed with 32-bit counts already
         const uint32_t* order = prm.orders + (size_t)p * n;
         uint64_t* out = prm.offsets ? prm.offsets + (size_t)p * n : nullptr;
         Addr peak = 0;                                        // tracked by wave 0
         uint32_t count = 0;
+        bool outgrown = false;                                // (uniform) 32-bit counts may not hold the next batch
+        __syncthreads();                                      // (every wave has taken its decisions about the plan before)
+        if (threadIdx.x == 0) sh.extent_now = 0;
 
         for (uint32_t r0 = 0; r0 < n; r0 += kBatch) {
             const uint32_t staged = n - r0 < (uint32_t)kBatch ? n - r0 : (uint32_t)kBatch;
@@ -697,12 +706,21 @@ __global__ void __launch_bounds__(kThreads, 4) plan_kernel(PlanParams prm)   // 
 
             for (uint32_t b0 = 0; b0 < staged;) {
                 const uint32_t nb = staged - b0 < (uint32_t)kPend ? staged - b0 : (uint32_t)kPend;
+                if (sizeof(Addr) == 4 && try32) {
+                    // no address of this batch exceeds the extent so far plus the sizes of the batch
+                    const int lane = lane_id();
+                    const uint64_t growth = wave_sum64(lane < (int)nb ? sh.rq_size[b0 + lane] >> shift : 0ull);
+                    if ((uint64_t)sh.extent_now + growth > 0xffffffffull) { outgrown = true; break; }
+                }
                 if constexpr (kLds) scan_batch<Addr, kPend, kThreads>(list, count, b0, nb, shift, sh);
                 else scan_batch_by_request<Addr, kPend, kThreads>(list, count, b0, nb, shift, sh);
                 __syncthreads();
                 survey_batch<Addr, kPend, kThreads>(b0, nb, shift, sh);
                 __syncthreads();
-                if (wave_id() == 0) resolve_batch<Addr, kPend, kThreads>(list, count, b0, nb, shift, peak, sh);
+                if (wave_id() == 0) {
+                    resolve_batch<Addr, kPend, kThreads>(list, count, b0, nb, shift, peak, sh);
+                    if (lane_id() == 0) sh.extent_now = peak;
+                }
                 __syncthreads();
                 const uint32_t settled = sh.settled;
                 const bool last_of_plan = r0 + b0 + settled >= n;
@@ -710,12 +728,22 @@ __global__ void __launch_bounds__(kThreads, 4) plan_kernel(PlanParams prm)   // 
                 count += settled;
                 b0 += settled;
             }
+            if (outgrown) break;
             // addresses of this batch -> offsets[p][request id]
             __syncthreads();
             if (out && threadIdx.x < staged) out[sh.rq_id[threadIdx.x]] = sh.rq_addr[threadIdx.x];
         }
+        if (outgrown) {
+            if (threadIdx.x == 0) prm.wide_plans[p] = 1;
+            continue;
+        }
         if (threadIdx.x == 0) prm.peaks[p] = (uint64_t)peak << shift;
     }
+}
+
+__global__ void plan_clear_marks(uint32_t* wide_plans, uint32_t P)
+{
+    for (uint32_t p = blockIdx.x * blockDim.x + threadIdx.x; p < P; p += gridDim.x * blockDim.x) wide_plans[p] = 0;
 }
 
 // best_plan = index of the smallest extent (lowest index among equals); one workgroup.
@@ -821,9 +849,9 @@ extern "C" uint32_t stalloc_plan_list_layout(uint32_t n, uint32_t t_end, uint64_
     if (granules < (1ull << 16) && t_end < 0x10000u &&
         n <= lds_capacity_entries<uint32_t, kThreadsCompact>(di.lds_per_block / 2, sizeof(uint2)))
         return (uint32_t)sizeof(uint2) | 0x100u;
-    if (granules < (1ull << 31)) {
+    if (granules < (1ull << 31) || largest < (1ull << 30)) {      // (the latter: tried plan by plan)
         const bool lds = n <= lds_capacity_entries<uint32_t, kThreadsLds>(di.lds_per_block, entry_bytes<uint32_t>());
-        return (uint32_t)entry_bytes<uint32_t>() | (lds ? 0x100u : 0u);
+        return (uint32_t)entry_bytes<uint32_t>() | (lds ? 0x100u : 0u) | (granules < (1ull << 31) ? 0u : 0x400u);
     }
     const bool lds = n <= lds_capacity_entries<uint64_t, kThreadsLds>(di.lds_per_block, entry_bytes<uint64_t>());
     return (uint32_t)entry_bytes<uint64_t>() | (lds ? 0x100u : 0u);
@@ -851,6 +879,7 @@ extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uin
     uint64_t* acc = cv.take<uint64_t>(kAccWords);
     uint64_t* own_offsets = (!offsets && best_offsets) ? cv.take<uint64_t>((size_t)P * n) : nullptr;
     unsigned char* slabs = lds64 ? nullptr : cv.take<unsigned char>((size_t)grid_mem * 2 * n * entry_bytes<uint64_t>());
+    uint32_t* wide_plans = cv.take<uint32_t>(P);
     // occupancy-bitmap variant: lifetime-conflict index of the trace
     uint32_t pool_words[kBitmapShapes];
     const bool bitmap = bitmap_plan_shapes(n, di, pool_words);
@@ -869,7 +898,12 @@ extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uin
     prm.offsets = offsets ? offsets : own_offsets;
     prm.peaks = peaks; prm.status = device_status; prm.acc = acc; prm.slabs = slabs; prm.n = n; prm.P = P;
     prm.compact_enqueued = compact ? 1u : 0u;
-    prm.nbr_begin = nbr_begin; prm.nbr = nbr;
+    prm.nbr_begin = nbr_begin; prm.nbr = nbr; prm.wide_plans = wide_plans;
+    {
+        uint32_t pb = (P + 255) / 256;
+        if (pb > 256) pb = 256;
+        hipLaunchKernelGGL(plan_clear_marks, dim3(pb), dim3(256), 0, stream, wide_plans, P);
+    }
     for (int shape = 0; shape < kBitmapShapes; ++shape) prm.bitmap_pool_words[shape] = bitmap ? pool_words[shape] : 0u;
     bool ok = true;
     if (bitmap) ok = ok && launch_plan_bitmap(prm, di, stream);

@@ -16,6 +16,7 @@ struct PlanParams {
     uint32_t* status;
     const uint64_t* acc;     // trace-check accumulators (mode word)
     unsigned char* slabs;    // list in the workspace: gridDim.x slabs of 2 * n entries
+    uint32_t* wide_plans;    // [P] list variant: 1 = the plan outgrew 32-bit granule counts, the 64-bit kernel places it
     uint32_t* nbr_begin;     // bitmap variant: [n + 2] row starts of the lifetime-conflict index
     uint16_t* nbr;           // bitmap variant: indices of the requests with an overlapping lifetime, row by row
     uint32_t n;

@@ -68,7 +68,11 @@ __global__ void trace_check_finish(uint64_t* acc, uint32_t* status)
         const uint64_t compact = (total >> shift) < (1ull << 16) ? kModeCompact : 0;
         const uint64_t bitmap = (total >> shift) <= kBitmapGranules && (acc[kAccMaxSize] >> shift) <= kBitmapMaxSize
                                     ? kModeBitmap : 0;
-        acc[kAccMode] = shift | narrow | compact | bitmap;
+        // The sum of sizes bounds every address, but plans worth having end far below it: when the
+        // sum is too large for 32-bit granule counts and no single request is, the 32-bit placement
+        // kernel takes each plan as far as its extent allows and hands the rest to the 64-bit one.
+        const uint64_t try32 = (!narrow && (acc[kAccMaxSize] >> shift) < (1ull << 30)) ? kModeTry32 : 0;
+        acc[kAccMode] = shift | narrow | compact | bitmap | try32;
         acc[kAccGranules] = total >> shift;
     }
     // total = acc[0] * 2^32 + acc[1]  >= 2^63  <=>  acc[0] + (acc[1] >> 32) >= 2^31

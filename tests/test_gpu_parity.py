@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 from helpers import count_conflicts_fast, load_golden, random_trace
-from workloads import CONFIGS, make_orderings, make_trace
+from workloads import CONFIGS, Trace, make_orderings, make_trace
 
 pytestmark = pytest.mark.gpu
 
@@ -367,6 +367,35 @@ def test_plan_large_configs_full_launches(S, oracle, cfg, P, rows):
     a, ext = oracle.plan_many(tr.size, tr.t_alloc, tr.t_free, orders, threads=THREADS, method="lists", lists=lists)
     assert np.array_equal(peaks[rows], ext)
     assert np.array_equal(plan["offsets"][rows].cpu().numpy().view(np.uint64), a)
+
+
+@pytest.mark.parametrize("n_clique,n_extra,unit,fill", [(230, 70, 1 << 24, 0.80), (230, 70, 1 << 24, 0.875),
+                                                         (230, 70, 1 << 24, 0.885), (9000, 1500, 1 << 18, 0.970),
+                                                         (9000, 1500, 1 << 18, 0.9711), (9000, 1500, 1 << 18, 0.972)])
+def test_plan_32_bit_counts_tried_plan_by_plan(S, oracle, n_clique, n_extra, unit, fill):
+    """Odd byte sizes whose sum exceeds 2^32 while no request is large: the 32-bit list kernel takes every
+    plan as far as its extent certainly fits 32 bits and leaves the others to the 64-bit kernel.  The
+    traces stack a clique of `fill` x 2^32 bytes plus shorter-lived requests, so that, from one case to
+    the next, none, some or all of the plans end above 2^32 (list in LDS for 300 requests, in the
+    workspace for 10 500)."""
+    rng = np.random.default_rng(5)
+    size = np.concatenate([rng.integers(unit // 2, unit * 3 // 2, n_clique),
+                           rng.integers(unit // 4, unit * 2, n_extra)]).astype(np.uint64) | np.uint64(1)
+    scale = fill * 2 ** 32 / int(size[:n_clique].sum())
+    size[:n_clique] = (size[:n_clique].astype(np.float64) * scale).astype(np.uint64) | np.uint64(1)
+    ts = np.concatenate([np.zeros(n_clique, np.int64), rng.integers(0, 90, n_extra)])
+    te = np.concatenate([np.full(n_clique, 100, np.int64), ts[n_clique:] + rng.integers(1, 40, n_extra)])
+    n = n_clique + n_extra
+    tr = Trace(name="near 2^32", size=size, t_alloc=ts.astype(np.uint32), t_free=te.astype(np.uint32), t_end=int(te.max()))
+    layout = _layout(S, tr)
+    assert layout & 0xff == 16 and layout & 0x400 and bool(layout & 0x100) == (n < 5000)
+    rng = np.random.default_rng(9)
+    orders = np.stack([rng.permutation(n) for _ in range(12 if n < 5000 else 6)]).astype(np.uint32)
+    got, a, ext = _compare_plans(S, oracle, tr, orders, method="allpairs")
+    above = int((ext > np.uint64(2 ** 32)).sum())
+    assert (fill < 0.87 and above == 0) or (fill > 0.88 and above > 0) or 0.87 <= fill <= 0.88 or n > 5000
+    cnt, _ = _gpu_validate(S, tr, got["offsets"])
+    assert not cnt.any()
 
 
 def test_plan_config4_sampled_orderings(S, oracle):
