@@ -243,7 +243,9 @@ const char *stalloc_status_string(int status);
  * granules bits beside the table; 8: sorted list with 16-bit fields, needs granules < 2^16
  * and t_end < 2^16; 16: sorted list of 32-bit granule counts, needs granules < 2^31; 24:
  * sorted list of 64-bit byte addresses), bit 8 set when the blocks are kept in LDS rather
- * than in the workspace, bit 9 set for the bitmap variant.  0 if no device.
+ * than in the workspace, bit 9 set for the bitmap variant, bit 10 set when 32-bit granule
+ * counts are only tried plan by plan (granules >= 2^31 but largest < 2^30: a plan whose
+ * extent approaches 2^32 granules is placed with 64-bit addresses instead).  0 if no device.
  * stalloc_plan_lds_capacity: largest n for which 16-byte entries stay in LDS.
  */
 uint32_t stalloc_plan_list_layout(uint32_t n, uint32_t t_end, uint64_t granules, uint64_t largest);
