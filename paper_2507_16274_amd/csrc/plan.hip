@@ -42,10 +42,14 @@
 // Addresses are multiples of the largest power of two dividing all sizes.  When the sum of
 // sizes, in those granules, stays below 2^31 the list holds 32-bit granule counts (16-byte
 // entries, single-instruction max/compare/DPP), below 2^16 (and with 16-bit timestamps) 8-byte
-// cells; otherwise 64-bit byte addresses.  Only the device knows which applies (the trace
+// cells; otherwise 64-bit byte addresses.  The sum of sizes is a bound no sensible plan comes
+// near, so when only the sum is too large (no single size reaches 2^30 granules) the 32-bit
+// instantiation still takes every plan, as far as the extent so far plus the sizes of the next
+// batch stays below 2^32 granules, and marks the plans that fail the check for the 64-bit
+// instantiation enqueued behind it.  Only the device knows which case applies (the trace
 // check leaves it in the mode word), so every instantiation that could apply is enqueued and
-// all but one return at once.  The list lives in LDS when it fits and in the workspace
-// otherwise.
+// those with nothing to do return at once.  The list lives in LDS when it fits and in the
+// workspace otherwise.
 #include "host_util.h"
 #include "plan_params.h"
 #include "wave.h"
