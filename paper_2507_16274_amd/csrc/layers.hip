@@ -22,16 +22,14 @@
 //   number   Exclusive sums of the groups' layer counts give every group its first layer.
 //   emit     layer_of per request; size, first allocation and last release per layer.
 #include "host_util.h"
+#include "sort_keys.h"
 #include "wave.h"
 
 namespace stalloc {
 
-constexpr int kLyTile = 256;
+constexpr int kLyTile = kSortTile;
 constexpr int kLyRegs = 8;                       // 64 layers per register: 512 layers of a group in registers
 static_assert(kLyRegs == 8, "ly_build dispatches on one to eight registers in use");
-
-// Keys (size descending, allocation time, request number) as two ascending 64-bit words.
-__device__ __forceinline__ bool before(const ulonglong2& x, const ulonglong2& y) { return x.x < y.x || (x.x == y.x && x.y < y.y); }
 
 __global__ void ly_init(uint32_t* v, uint32_t n)
 {
@@ -47,19 +45,9 @@ ly_sort_tiles(const uint64_t* __restrict__ size, const uint32_t* __restrict__ ta
     __shared__ ulonglong2 k[kLyTile];
     if (*status != STALLOC_OK) return;
     const uint32_t t = threadIdx.x, i = blockIdx.x * kLyTile + t;
-    k[t] = i < n ? make_ulonglong2(~size[i], ((uint64_t)ta[i] << 32) | i) : make_ulonglong2(~0ull, 0xffffffff00000000ull | i);
-    for (uint32_t span = 2; span <= (uint32_t)kLyTile; span <<= 1) {
-        for (uint32_t gap = span >> 1; gap > 0; gap >>= 1) {
-            __syncthreads();
-            const uint32_t other = t ^ gap;
-            if (other > t) {
-                const ulonglong2 x = k[t], y = k[other];
-                const bool ascending = (t & span) == 0;
-                if (before(y, x) == ascending) { k[t] = y; k[other] = x; }
-            }
-        }
-    }
-    __syncthreads();
+    // (size descending, allocation time, request number) as two ascending 64-bit words
+    k[t] = i < n ? make_ulonglong2(~size[i], ((uint64_t)ta[i] << 32) | i) : filler_key(i);
+    sort_tile(k);
     keys[blockIdx.x * kLyTile + t] = k[t];
 }
 

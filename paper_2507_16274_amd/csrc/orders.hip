@@ -19,11 +19,12 @@
 // elements of the other run that sort before it, found by binary search.  log2(n / 256) passes,
 // all rows of a batch side by side in every launch.
 #include "host_util.h"
+#include "sort_keys.h"
 #include "wave.h"
 
 namespace stalloc {
 
-constexpr int kOrTile = 256;
+constexpr int kOrTile = kSortTile;
 
 __device__ __forceinline__ uint64_t splitmix64_out(uint64_t x)
 {
@@ -31,11 +32,6 @@ __device__ __forceinline__ uint64_t splitmix64_out(uint64_t x)
     z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
     z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
     return z ^ (z >> 31);
-}
-
-__device__ __forceinline__ bool key_before(const ulonglong2& x, const ulonglong2& y)
-{
-    return x.x < y.x || (x.x == y.x && x.y < y.y);
 }
 
 struct OrTrace {
@@ -50,7 +46,7 @@ struct OrTrace {
 __device__ __forceinline__ ulonglong2 order_key(const OrTrace& t, uint64_t p, uint64_t stream, uint32_t i, uint32_t e)
 {
     ulonglong2 k;
-    if (i >= t.n) { k.x = ~0ull; k.y = 0xffffffff00000000ull | e; return k; }
+    if (i >= t.n) return filler_key(e);
     if (p == 0) {
         k.x = ~t.size[i];
         k.y = ((uint64_t)t.ta[i] << 32) | i;
@@ -79,18 +75,7 @@ or_sort_tiles(OrTrace t, uint64_t first_plan, uint64_t seed, uint32_t n_pad, ulo
     const uint32_t th = threadIdx.x, e = blockIdx.x * kOrTile + th;
     const uint64_t p = first_plan + blockIdx.y;
     k[th] = order_key(t, p, splitmix64_out(seed + p), e, e);
-    for (uint32_t span = 2; span <= (uint32_t)kOrTile; span <<= 1) {
-        for (uint32_t gap = span >> 1; gap > 0; gap >>= 1) {
-            __syncthreads();
-            const uint32_t other = th ^ gap;
-            if (other > th) {
-                const ulonglong2 x = k[th], y = k[other];
-                const bool ascending = (th & span) == 0;
-                if (key_before(y, x) == ascending) { k[th] = y; k[other] = x; }
-            }
-        }
-    }
-    __syncthreads();
+    sort_tile(k);
     keys[(size_t)blockIdx.y * n_pad + e] = k[th];
 }
 

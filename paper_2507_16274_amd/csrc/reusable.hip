@@ -30,11 +30,12 @@
 //            same three walks (one launch each, a wave per group of windows and part of the
 //            plan), at a fraction of the instructions per decision and window.
 #include "host_util.h"
+#include "sort_keys.h"
 #include "wave.h"
 
 namespace stalloc {
 
-constexpr int kRsTile = 256;
+constexpr int kRsTile = kSortTile;
 constexpr int kRsThreads = 256;
 constexpr int kRsWaves = kRsThreads / kWave;
 
@@ -47,9 +48,6 @@ __global__ void rs_init(RsPool* pool)
     if (threadIdx.x == 0) { pool->lo = ~0ull; pool->hi = 0; pool->bits = 0; pool->shift = 0; pool->narrow = 0; }
 }
 
-// Keys (address, request number), compared word by word.
-__device__ __forceinline__ bool before(const ulonglong2& x, const ulonglong2& y) { return x.x < y.x || (x.x == y.x && x.y < y.y); }
-
 // One tile of 256 decisions per workgroup, sorted in LDS; slot e past the end holds a key behind
 // every real one, (~0, ~0 << 32 | e).  Also the pool's bounds.
 __global__ void __launch_bounds__(kRsTile)
@@ -61,7 +59,7 @@ rs_sort_tiles(const uint64_t* __restrict__ size, const uint64_t* __restrict__ of
     const uint32_t t = threadIdx.x, i = blockIdx.x * kRsTile + t;
     const bool ok = i < n;
     const uint64_t a = ok ? offsets[i] : ~0ull;
-    k[t] = ok ? make_ulonglong2(a, i) : make_ulonglong2(~0ull, 0xffffffff00000000ull | i);
+    k[t] = ok ? make_ulonglong2(a, i) : filler_key(i);          // keys (address, request number)
     {
         const uint64_t lo = wave_min64(a);                                       // (slots past n hold ~0)
         const uint64_t hi = wave_max64(ok ? a + size[i] : 0ull);
@@ -70,18 +68,7 @@ rs_sort_tiles(const uint64_t* __restrict__ size, const uint64_t* __restrict__ of
             atomicMax((unsigned long long*)&pool->hi, (unsigned long long)hi);
         }
     }
-    for (uint32_t span = 2; span <= (uint32_t)kRsTile; span <<= 1) {
-        for (uint32_t gap = span >> 1; gap > 0; gap >>= 1) {
-            __syncthreads();
-            const uint32_t other = t ^ gap;
-            if (other > t) {
-                const ulonglong2 x = k[t], y = k[other];
-                const bool ascending = (t & span) == 0;
-                if (before(y, x) == ascending) { k[t] = y; k[other] = x; }
-            }
-        }
-    }
-    __syncthreads();
+    sort_tile(k);
     keys[blockIdx.x * kRsTile + t] = k[t];
 }
 
