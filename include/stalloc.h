@@ -50,7 +50,8 @@ typedef enum stalloc_status {
     STALLOC_ERR_DEVICE = 5,      /* a HIP call failed                                             */
     STALLOC_ERR_BAD_ORDER = 6,   /* an entry of `orders` is >= n                                  */
     STALLOC_ERR_BAD_WINDOW = 7,  /* a time window with w_lo >= w_hi                               */
-    STALLOC_ERR_BAD_LAYER = 8    /* an entry of `layer_of` is >= n_layers                         */
+    STALLOC_ERR_BAD_LAYER = 8,   /* an entry of `layer_of` is >= n_layers                         */
+    STALLOC_ERR_TOO_LARGE = 9    /* the trace exceeds what an entry point without workspace holds */
 } stalloc_status;
 
 /* Structure-of-arrays trace (Sec. 4: s, t_s, t_e of every request event). */
@@ -117,6 +118,24 @@ int stalloc_validate(const stalloc_trace *trace, const uint64_t *offsets, uint32
 int stalloc_lower_bound(const stalloc_trace *trace, uint64_t *lower_bound, uint32_t *t_at_max,
                         uint32_t *device_status,
                         void *workspace, size_t *workspace_bytes, void *hip_stream);
+
+/*
+ * stalloc_lower_bound for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same outputs as
+ * stalloc_lower_bound, no workspace argument: the net-change array and the partial results
+ * live in a fixed buffer inside the library (STALLOC_STATIC_MAX_T_END + 1 64-bit words plus
+ * about 3 KB, 4 MiB in all, resident on every GPU the library runs on until the process
+ * ends).  Neither this call nor anything it calls allocates or frees memory.
+ *
+ *   trace->t_end above STALLOC_STATIC_MAX_T_END returns STALLOC_ERR_TOO_LARGE; nothing is
+ *   enqueued then.
+ *   All calls on one GPU share that GPU's buffer: calls that can overlap in time on one GPU
+ *   (different streams, several host threads) race and must be ordered by the caller.  The
+ *   buffer keeps the previous call's contents between calls; every call rewrites what it reads.
+ */
+#define STALLOC_STATIC_MAX_T_END 524288u
+int stalloc_lower_bound_static(const stalloc_trace *trace, uint64_t *lower_bound, uint32_t *t_at_max,
+                               uint32_t *device_status, void *hip_stream);
 
 /*
  * Dynamic reusable space of one plan (Sec. 5.2): for each of k time windows

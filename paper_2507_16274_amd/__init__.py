@@ -21,8 +21,10 @@ _LIB_PATH = os.path.join(_HERE, "libstalloc.so")
 
 STATUS = {0: "STALLOC_OK", 1: "STALLOC_ERR_INVALID_ARG", 2: "STALLOC_ERR_BAD_TRACE", 3: "STALLOC_ERR_OVERFLOW",
           4: "STALLOC_ERR_NOMEM", 5: "STALLOC_ERR_DEVICE", 6: "STALLOC_ERR_BAD_ORDER", 7: "STALLOC_ERR_BAD_WINDOW",
-          8: "STALLOC_ERR_BAD_LAYER"}
-EXPORTS = ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_reusable_space",
+          8: "STALLOC_ERR_BAD_LAYER", 9: "STALLOC_ERR_TOO_LARGE"}
+STATIC_MAX_T_END = 524288        # STALLOC_STATIC_MAX_T_END of include/stalloc.h
+EXPORTS = ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_lower_bound_static",
+           "stalloc_reusable_space",
            "stalloc_memory_layers", "stalloc_expand_layers", "stalloc_tmp", "stalloc_make_orders",
            "stalloc_status_string", "stalloc_plan_lds_capacity", "stalloc_plan_list_layout")
 
@@ -49,13 +51,14 @@ def _load() -> ctypes.CDLL:
     lib.stalloc_plan.argtypes = [tp, vp, u32, vp, vp, vp, vp, vp, vp, szp, vp]
     lib.stalloc_validate.argtypes = [tp, vp, u32, vp, vp, vp, vp, szp, vp]
     lib.stalloc_lower_bound.argtypes = [tp, vp, vp, vp, vp, szp, vp]
+    lib.stalloc_lower_bound_static.argtypes = [tp, vp, vp, vp, vp]
     lib.stalloc_reusable_space.argtypes = [tp, vp, vp, u32, u32, vp, vp, vp, vp, vp, szp, vp]
     lib.stalloc_memory_layers.argtypes = [tp, vp, vp, vp, vp, vp, vp, vp, szp, vp]
     lib.stalloc_expand_layers.argtypes = [u32, u32, vp, vp, u32, vp, vp, vp]
     lib.stalloc_tmp.argtypes = [tp, vp, u32, vp, vp, vp, szp, vp]
     lib.stalloc_make_orders.argtypes = [tp, u32, u32, ctypes.c_uint64, vp, vp, vp, szp, vp]
-    for name in ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_reusable_space",
-                 "stalloc_memory_layers", "stalloc_expand_layers", "stalloc_tmp",
+    for name in ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_lower_bound_static",
+                 "stalloc_reusable_space", "stalloc_memory_layers", "stalloc_expand_layers", "stalloc_tmp",
                  "stalloc_make_orders"):
         getattr(lib, name).restype = ctypes.c_int
     lib.stalloc_status_string.argtypes = [ctypes.c_int]
@@ -182,6 +185,18 @@ def stalloc_lower_bound(size, t_alloc, t_free, t_end: int, *, stream=None,
     have = ctypes.c_size_t(ws.numel())
     _check(lib.stalloc_lower_bound(*args, ws.data_ptr(), ctypes.byref(have), _stream(stream)), "stalloc_lower_bound")
     out["workspace"] = ws
+    return out
+
+
+def stalloc_lower_bound_static(size, t_alloc, t_free, t_end: int, *, out: Dict[str, torch.Tensor],
+                               stream=None) -> Dict[str, torch.Tensor]:
+    """stalloc_lower_bound without a workspace; `out` carries the preallocated outputs
+    (lower_bound int64 [1], t_at_max int32 [1], status int32 [1]), so nothing is allocated here either."""
+    tr = _trace(size, t_alloc, t_free, t_end)
+    _check(lib.stalloc_lower_bound_static(ctypes.byref(tr), _dev(out["lower_bound"], torch.int64, "lower_bound"),
+                                          _dev(out["t_at_max"], torch.int32, "t_at_max"),
+                                          _dev(out["status"], torch.int32, "status"), _stream(stream)),
+           "stalloc_lower_bound_static")
     return out
 
 

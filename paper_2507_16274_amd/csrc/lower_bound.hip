@@ -170,6 +170,71 @@ lb_final(const LbBest* __restrict__ tile_best, uint32_t tiles, uint64_t* lower_b
     }
 }
 
+// Pieces of the scratch memory one call needs, carved from `base` (nullptr: sizes only).
+struct LbScratch {
+    uint64_t* acc;
+    int64_t* net;
+    int64_t* tile_sum;
+    LbBest* tile_best;
+    uint32_t tiles;
+    size_t bytes;
+    LbScratch(void* base, uint32_t t_end)
+    {
+        tiles = (t_end + kLbTile - 1) / kLbTile;
+        Carver cv(base);
+        acc = cv.take<uint64_t>(kAccWords);
+        net = cv.take<int64_t>((size_t)t_end + 1);
+        tile_sum = cv.take<int64_t>(tiles);
+        tile_best = cv.take<LbBest>(tiles);
+        bytes = cv.used;
+    }
+};
+
+static int enqueue_lower_bound(const stalloc_trace& tr, uint64_t* lower_bound, uint32_t* t_at_max,
+                               uint32_t* device_status, const LbScratch& sc, hipStream_t stream)
+{
+    const uint32_t t_end = tr.t_end;
+    launch_trace_check(tr, sc.acc, device_status, stream);
+    uint32_t clear_blocks = (t_end + 1 + kLbThreads - 1) / kLbThreads;
+    if (clear_blocks > 4096) clear_blocks = 4096;
+    hipLaunchKernelGGL(lb_clear, dim3(clear_blocks), dim3(kLbThreads), 0, stream, sc.net, t_end + 1);
+    uint32_t sc_blocks = (tr.n + kLbThreads - 1) / kLbThreads;
+    if (sc_blocks > 4096) sc_blocks = 4096;
+    hipLaunchKernelGGL(lb_scatter, dim3(sc_blocks), dim3(kLbThreads), 0, stream, tr.size, tr.t_alloc, tr.t_free,
+                       tr.n, t_end, sc.net);
+    hipLaunchKernelGGL(lb_tile_sums, dim3(sc.tiles), dim3(kLbThreads), 0, stream, sc.net, t_end, sc.tile_sum);
+    hipLaunchKernelGGL(lb_scan_tiles, dim3(1), dim3(kLbThreads), 0, stream, sc.tile_sum, sc.tiles);
+    hipLaunchKernelGGL(lb_tile_max, dim3(sc.tiles), dim3(kLbThreads), 0, stream, sc.net, t_end, sc.tile_sum,
+                       sc.tile_best);
+    hipLaunchKernelGGL(lb_final, dim3(1), dim3(kLbThreads), 0, stream, sc.tile_best, sc.tiles, lower_bound, t_at_max);
+    return hipGetLastError() == hipSuccess ? STALLOC_OK : STALLOC_ERR_DEVICE;
+}
+
+// Scratch memory of stalloc_lower_bound_static: one copy per GPU, resident from the moment the
+// library is loaded on that GPU until the process ends.  Host code never uses this name as an
+// address; it asks the runtime for the device address once per device (static_scratch()).
+constexpr uint32_t kStaticMaxTEnd = STALLOC_STATIC_MAX_T_END;
+constexpr size_t kStaticScratchBytes =
+    kAlign * 4 + sizeof(uint64_t) * kAccWords + sizeof(int64_t) * ((size_t)kStaticMaxTEnd + 1) +
+    (sizeof(int64_t) + sizeof(LbBest)) * ((kStaticMaxTEnd + kLbTile - 1) / kLbTile);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on the current device (nullptr if the runtime refuses).
+static void* static_scratch()
+{
+    static void* ptr[64] = {};
+    static std::mutex guard;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    std::lock_guard<std::mutex> lock(guard);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        ptr[dev] = p;
+    }
+    return ptr[dev];
+}
+
 }  // namespace stalloc
 
 using namespace stalloc;
@@ -179,30 +244,24 @@ extern "C" int stalloc_lower_bound(const stalloc_trace* tr, uint64_t* lower_boun
                                    void* hip_stream)
 {
     if (!trace_args_ok(tr) || !workspace_bytes) return STALLOC_ERR_INVALID_ARG;
-    const uint32_t t_end = tr->t_end;
-    const uint32_t tiles = (t_end + kLbTile - 1) / kLbTile;
-    Carver cv(workspace);
-    uint64_t* acc = cv.take<uint64_t>(kAccWords);
-    int64_t* net = cv.take<int64_t>((size_t)t_end + 1);
-    int64_t* tile_sum = cv.take<int64_t>(tiles);
-    LbBest* tile_best = cv.take<LbBest>(tiles);
-    if (!workspace) { *workspace_bytes = cv.used; return STALLOC_OK; }
-    if (!lower_bound || !device_status || *workspace_bytes < cv.used ||
+    const LbScratch sc(workspace, tr->t_end);
+    if (!workspace) { *workspace_bytes = sc.bytes; return STALLOC_OK; }
+    if (!lower_bound || !device_status || *workspace_bytes < sc.bytes ||
         (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)))
         return STALLOC_ERR_INVALID_ARG;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    return enqueue_lower_bound(*tr, lower_bound, t_at_max, device_status, sc, static_cast<hipStream_t>(hip_stream));
+}
 
-    launch_trace_check(*tr, acc, device_status, stream);
-    uint32_t clear_blocks = (t_end + 1 + kLbThreads - 1) / kLbThreads;
-    if (clear_blocks > 4096) clear_blocks = 4096;
-    hipLaunchKernelGGL(lb_clear, dim3(clear_blocks), dim3(kLbThreads), 0, stream, net, t_end + 1);
-    uint32_t sc_blocks = (tr->n + kLbThreads - 1) / kLbThreads;
-    if (sc_blocks > 4096) sc_blocks = 4096;
-    hipLaunchKernelGGL(lb_scatter, dim3(sc_blocks), dim3(kLbThreads), 0, stream, tr->size, tr->t_alloc, tr->t_free,
-                       tr->n, t_end, net);
-    hipLaunchKernelGGL(lb_tile_sums, dim3(tiles), dim3(kLbThreads), 0, stream, net, t_end, tile_sum);
-    hipLaunchKernelGGL(lb_scan_tiles, dim3(1), dim3(kLbThreads), 0, stream, tile_sum, tiles);
-    hipLaunchKernelGGL(lb_tile_max, dim3(tiles), dim3(kLbThreads), 0, stream, net, t_end, tile_sum, tile_best);
-    hipLaunchKernelGGL(lb_final, dim3(1), dim3(kLbThreads), 0, stream, tile_best, tiles, lower_bound, t_at_max);
-    return hipGetLastError() == hipSuccess ? STALLOC_OK : STALLOC_ERR_DEVICE;
+extern "C" int stalloc_lower_bound_static(const stalloc_trace* tr, uint64_t* lower_bound, uint32_t* t_at_max,
+                                          uint32_t* device_status, void* hip_stream)
+{
+    if (!trace_args_ok(tr) || !lower_bound || !device_status) return STALLOC_ERR_INVALID_ARG;
+    if (tr->t_end > kStaticMaxTEnd) return STALLOC_ERR_TOO_LARGE;
+    void* base = static_scratch();
+    if (!base) return STALLOC_ERR_DEVICE;
+    const LbScratch sc(base, tr->t_end);
+    if (sc.bytes > kStaticScratchBytes) return STALLOC_ERR_TOO_LARGE;
+    // every word of the scratch memory a call reads is written by that call first (the trace
+    // check resets its accumulators, lb_clear the net changes), so what the last call left is harmless
+    return enqueue_lower_bound(*tr, lower_bound, t_at_max, device_status, sc, static_cast<hipStream_t>(hip_stream));
 }

@@ -105,6 +105,7 @@ extern "C" const char* stalloc_status_string(int status)
         case STALLOC_ERR_BAD_ORDER: return "STALLOC_ERR_BAD_ORDER";
         case STALLOC_ERR_BAD_WINDOW: return "STALLOC_ERR_BAD_WINDOW";
         case STALLOC_ERR_BAD_LAYER: return "STALLOC_ERR_BAD_LAYER";
+        case STALLOC_ERR_TOO_LARGE: return "STALLOC_ERR_TOO_LARGE";
         default: return "STALLOC_UNKNOWN_STATUS";
     }
 }
