@@ -74,6 +74,8 @@ constexpr int kAccWords = 8;
 constexpr int kAccMode = 4;
 constexpr int kAccMaxSize = 5;
 constexpr int kAccGranules = 6;                // sum of sizes in granules
+constexpr int kAccSplit = 7;                   // bit 0: the kernel that keeps only long-lived blocks in its list places the
+                                               // trace; bits 8..31: its lifetime threshold; bits 32..63: long-lived requests
 constexpr uint64_t kModeNarrow = 1ull << 8;
 constexpr uint64_t kModeCompact = 1ull << 9;   // sum of sizes in granules below 2^16 as well
 constexpr uint64_t kModeBitmap = 1ull << 10;   // sum <= kBitmapGranules and every size <= kBitmapMaxSize granules

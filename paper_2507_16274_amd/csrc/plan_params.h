@@ -44,6 +44,26 @@ __host__ __device__ inline int bitmap_shape(uint64_t mode, uint64_t granules, co
     return -1;
 }
 
+// The variant that keeps only long-lived blocks in its sorted list (plan_split.hip): pieces of
+// the workspace, their sizes, and the launcher of its preparation and placement kernels.  The
+// preparation decides on the device whether the variant places the trace (acc[kAccSplit]).
+struct SplitWorkspace {
+    uint32_t* hist;
+    uint32_t* gate;
+    ulonglong2* keys;
+    ulonglong2* spare;
+    uint4* by_rank;
+    uint32_t* size_by_rank;
+    uint32_t* rank_of;
+    uint2* window;
+    uint32_t* addr;
+    uint64_t* group_bins;
+    uint64_t* region_bins;
+    uint32_t slots, n_pad, grid;
+};
+size_t split_workspace(uint32_t n, const DeviceInfo& di, Carver& cv, SplitWorkspace* ws);
+bool launch_plan_split(const PlanParams& prm, const SplitWorkspace& ws, const DeviceInfo& di, hipStream_t stream);
+
 // Fills PlanParams::bitmap_pool_words for a trace of n requests; false if no shape fits.
 bool bitmap_plan_shapes(uint32_t n, const DeviceInfo& di, uint32_t (&pool_words)[kBitmapShapes]);
 size_t bitmap_index_entries(uint32_t n);             // uint16_t entries of PlanParams::nbr

@@ -1,0 +1,675 @@
+// stalloc_plan, placement kernel for long traces in which few requests live long: one
+// workgroup per candidate placement order, the rule of Sec. 5.1 (every request gets the lowest
+// address at which it conflicts with no earlier request of the plan in lifespan and address
+// range at once).
+//
+// Training traces hold a few thousand long-lived tensors (activations kept from a forward to
+// its backward pass) among hundreds of thousands that live for a handful of events (Sec. 2.3,
+// Fig. 4).  A request's lifetime-conflicting blocks are then (a) long-lived blocks, of which
+// there are few in all, and (b) short-lived blocks that started shortly before it or during
+// its own lifetime, which in the order of allocation times form one contiguous range.  The
+// kernel keeps the two kinds apart:
+//
+//   long blocks   (lifetime > theta) in a list sorted by address, in LDS, as the sorted-list
+//                 kernel keeps all blocks.  Any request walks this list once, 64 blocks a step:
+//                 two compares keep the blocks whose lifetime conflicts, a running maximum of
+//                 their end addresses is "covered so far", a conflicting block that starts at
+//                 least `size` above it closes a hole the request could take.
+//   short blocks  (lifetime <= theta) in a per-plan table of addresses indexed by the request's
+//                 rank in allocation-time order.  The short blocks that can conflict with a
+//                 request are the placed entries of a window of that table, fixed per request
+//                 and independent of the order: allocation times in (t_alloc - theta, t_free).
+//                 A short-lived request reads its window (a few dozen entries) into the lanes
+//                 of the wave.  A long-lived request, whose window spans thousands of entries,
+//                 consults per-64-entry summaries (lowest start, highest end address of the
+//                 placed blocks) and opens only the groups that can meet the range it tries.
+//
+// A hole of the long-block list takes the request if, after moving up past every other
+// conflicting block that reaches into it (those of the window and those settled earlier in the
+// same batch), the request still ends below the hole's end; the first such hole, else the top.
+// Moving up: all addresses from c to the highest end of the blocks meeting [c, c + size) are
+// blocked, so c jumps there, until nothing meets the range.
+//
+// Requests are settled in batches of 64 of the order.  Inside a batch a request waits only for
+// the earlier requests of the batch whose lifetime conflicts with its own; everything that is
+// ready is settled at once, one request per wave, so that a batch takes as many rounds as its
+// longest chain of conflicts (mostly one or two).  The long blocks of a batch are merged into
+// the sorted list when the batch is done.
+//
+// theta is the smallest 2^c - 1 that leaves no more long requests than the LDS list holds; the
+// kernel takes the trace only if those are at most an eighth of all requests (else the
+// sorted-list kernel does).  Addresses are 32-bit granule counts, with the same plan-by-plan
+// hand-over to the 64-bit sorted-list kernel as there.
+#include "host_util.h"
+#include "plan_list.h"
+#include "plan_params.h"
+#include "sort_keys.h"
+#include "wave.h"
+
+namespace stalloc {
+
+constexpr int kSpThreads = 512;                  // two workgroups share a CU
+constexpr int kSpBatch = 64;                     // requests between two merges; dependency masks have 64 bits
+constexpr int kSpRefill = 128;                   // requests fetched per refill
+constexpr int kSpPool = 640;                     // short blocks the windows of one batch may hold in LDS
+constexpr uint32_t kSpRefetch = 0xffffffffu;     // (a window whose blocks did not fit the pool is read when its request is settled)
+constexpr uint32_t kSpUnplaced = 0xffffffffu;
+constexpr uint32_t kSpLongFlag = 0x80000000u;
+constexpr int kSpMaxThetaBits = 12;              // theta < 2^12 events
+// Which addresses the placed short blocks of 64 ranks (a group) or of a region touch, as bitmaps
+// of 64 address bins at several resolutions: bin width 2^(8 + 3 l) granules at level l, the last
+// bin of a level taking everything above.  A request that tries [c, c + s) looks at the finest
+// level whose first 63 bins reach c + s: bins between 1/512 and 1/64 of that address wide.
+constexpr int kSpLevels = 8;
+__host__ __device__ constexpr uint32_t sp_level_shift(int level) { return 8u + 3u * (uint32_t)level; }
+
+// Bins of one level that the addresses lo .. last (inclusive) fall into.
+__device__ __forceinline__ uint64_t sp_bins(uint32_t lo, uint32_t last, int level)
+{
+    uint32_t a = lo >> sp_level_shift(level), b = last >> sp_level_shift(level);
+    a = a < 63u ? a : 63u;
+    b = b < 63u ? b : 63u;
+    return (b == 63u ? ~0ull : (2ull << b) - 1) & ~((1ull << a) - 1);
+}
+
+using SpList = BlockList<uint32_t, false>;
+
+struct SplitLds {
+    uint32_t rq_id[kSpRefill];
+    uint32_t rq_size[kSpRefill];                 // granules
+    uint32_t rq_ta[kSpRefill];
+    uint32_t rq_tf[kSpRefill];
+    uint32_t rq_rank[kSpRefill];                 // rank in allocation-time order | kSpLongFlag
+    uint32_t rq_wlo[kSpRefill];                  // window of that order holding the short requests that can conflict
+    uint32_t rq_whi[kSpRefill];
+    uint32_t rq_addr[kSpRefill];                 // granules
+    uint64_t dep[kSpBatch];                      // earlier requests of the batch with a conflicting lifetime
+    Span<uint32_t> pend_span[kSpBatch];          // long blocks of the batch, sorted by address, for the merge
+    uint2 pend_life[kSpBatch];
+    Span<uint32_t> pool[kSpPool];                // conflicting short blocks of the windows of the batch's requests
+    uint32_t pool_used;
+    uint32_t win_first[kSpBatch];                // per request of the batch: its part of the pool
+    uint32_t win_count[kSpBatch];
+    uint32_t region_min[kWave];                  // lowest start / highest end address of the placed short blocks of a
+    uint32_t region_max[kWave];                  // region of ranks (64 regions cover the table)
+    uint32_t reach[3];                           // window_reach: what the waves found, three calls in rotation
+    uint32_t extent_now;                         // extent after the last finished batch
+    uint32_t peak;                               // running extent
+};
+
+__host__ __device__ inline uint32_t split_list_capacity(size_t lds_per_workgroup)
+{
+    return lds_per_workgroup > sizeof(SplitLds) + 1024 ? (uint32_t)((lds_per_workgroup - sizeof(SplitLds)) / SpList::kEntryBytes) : 0u;
+}
+
+// ------------------------------------------------------------------------------------------
+// Once per call: lifetime classes, allocation-time order, windows.
+
+// hist[c] = requests whose lifetime lies in [2^c, 2^(c+1)).
+__global__ void __launch_bounds__(256)
+sp_histogram(const uint32_t* __restrict__ ta, const uint32_t* __restrict__ tf, uint32_t n, uint32_t* hist,
+             const uint32_t* status)
+{
+    __shared__ uint32_t local[32];
+    if (*status != STALLOC_OK) return;
+    if (threadIdx.x < 32) local[threadIdx.x] = 0;
+    __syncthreads();
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+        const uint32_t life = tf[i] - ta[i];                       // >= 1 in a sound trace
+        atomicAdd(&local[life ? 31 - __builtin_clz(life) : 0], 1u);
+    }
+    __syncthreads();
+    if (threadIdx.x < 32 && local[threadIdx.x]) atomicAdd(&hist[threadIdx.x], local[threadIdx.x]);
+}
+
+__global__ void sp_clear_histogram(uint32_t* hist, uint32_t* gate)
+{
+    if (threadIdx.x < 32) hist[threadIdx.x] = 0;
+    if (threadIdx.x == 0) *gate = 1;                                // closed until sp_decide opens it
+}
+
+// Decides whether this kernel places the trace, and with which theta; acc[kAccSplit] = 1 |
+// theta << 8 | long requests << 32 (0: another kernel does), gate[0] = 0 when it does (the
+// kernels that prepare its tables read the gate like a status word).
+__global__ void sp_decide(uint64_t* acc, const uint32_t* hist, uint32_t n, uint32_t list_cap,
+                          PlanParams prm, uint32_t* gate, const uint32_t* status)
+{
+    if (threadIdx.x != 0) return;
+    acc[kAccSplit] = 0;
+    if (*status != STALLOC_OK) return;
+    const uint64_t mode = acc[kAccMode];
+    if (!(mode & (kModeNarrow | kModeTry32))) return;
+    if (bitmap_shape(mode, acc[kAccGranules], prm.bitmap_pool_words) >= 0) return;
+    if ((mode & kModeCompact) && prm.compact_enqueued) return;
+    uint32_t longs = 0;
+    int c_sel = -1;
+    for (int c = 31; c >= 0; --c) {                                 // smallest c with #(lifetime >= 2^c) <= list_cap
+        if (longs + hist[c] > list_cap) break;
+        longs += hist[c];
+        c_sel = c;
+    }
+    if (c_sel < 1 || c_sel > kSpMaxThetaBits || (uint64_t)longs * 8 > n) return;
+    const uint64_t theta = (1ull << c_sel) - 1;
+    acc[kAccSplit] = 1ull | (theta << 8) | ((uint64_t)longs << 32);
+    *gate = 0;
+}
+
+// Keys (t_alloc, request) of one tile, sorted in LDS.
+__global__ void __launch_bounds__(kSortTile)
+sp_sort_tiles(const uint32_t* __restrict__ ta, uint32_t n, ulonglong2* keys, const uint32_t* gate)
+{
+    __shared__ ulonglong2 k[kSortTile];
+    if (*gate != 0) return;
+    const uint32_t e = blockIdx.x * kSortTile + threadIdx.x;
+    k[threadIdx.x] = e < n ? make_ulonglong2((uint64_t)ta[e], (uint64_t)e) : filler_key(e);
+    sort_tile(k);
+    keys[e] = k[threadIdx.x];
+}
+
+// Per rank k of the allocation-time order: (size in granules, t_alloc, t_free, request); the
+// slots past the end conflict with nothing.  Per request: its rank, flagged when it is long.
+__global__ void __launch_bounds__(256)
+sp_tables(const ulonglong2* __restrict__ sorted, const uint64_t* __restrict__ size, const uint32_t* __restrict__ ta,
+          const uint32_t* __restrict__ tf, uint32_t n, uint32_t slots, const uint64_t* acc, uint4* by_rank,
+          uint32_t* size_by_rank, uint32_t* rank_of, const uint32_t* gate)
+{
+    if (*gate != 0) return;
+    const uint32_t shift = (uint32_t)(acc[kAccMode] & 63);
+    const uint32_t theta = (uint32_t)((acc[kAccSplit] >> 8) & 0xffffffu);
+    for (uint32_t k = blockIdx.x * blockDim.x + threadIdx.x; k < slots; k += gridDim.x * blockDim.x) {
+        if (k >= n) { by_rank[k] = make_uint4(0u, 0xffffffffu, 0u, 0xffffffffu); size_by_rank[k] = 0u; continue; }
+        const uint32_t i = (uint32_t)sorted[k].y;
+        const uint32_t a = ta[i], f = tf[i];
+        by_rank[k] = make_uint4((uint32_t)(size[i] >> shift), a, f, i);
+        size_by_rank[k] = (uint32_t)(size[i] >> shift);
+        rank_of[i] = k | (f - a > theta ? kSpLongFlag : 0u);
+    }
+}
+
+// First rank whose allocation time is >= t.
+__device__ __forceinline__ uint32_t first_rank_at(const uint4* __restrict__ by_rank, uint32_t n, uint32_t t)
+{
+    uint32_t lo = 0, hi = n;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (by_rank[mid].y < t) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+// Window of request i: ranks of the requests allocated in (t_alloc - theta, t_free).  A short
+// request j (lifetime <= theta) whose lifetime conflicts with i's has t_alloc_j < t_free_i and
+// t_alloc_j >= t_free_j - theta > t_alloc_i - theta, so it lies in the window.
+__global__ void __launch_bounds__(256)
+sp_windows(const uint4* __restrict__ by_rank, const uint32_t* __restrict__ ta, const uint32_t* __restrict__ tf, uint32_t n,
+           const uint64_t* acc, uint2* window, const uint32_t* gate)
+{
+    if (*gate != 0) return;
+    const uint32_t theta = (uint32_t)((acc[kAccSplit] >> 8) & 0xffffffu);
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+        const uint32_t a = ta[i];
+        const uint32_t from = a + 1 > theta ? a + 1 - theta : 0u;
+        window[i] = make_uint2(first_rank_at(by_rank, n, from), first_rank_at(by_rank, n, tf[i]));
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// The placement kernel.
+
+struct SplitTables {
+    const uint4* by_rank;        // [slots] (size, t_alloc, t_free, request) in allocation-time order
+    const uint32_t* size_by_rank;// [slots] the sizes once more, on their own
+    const uint32_t* rank_of;     // [n]
+    const uint2* window;         // [n]
+    uint32_t* addr;              // per resident workgroup: [slots] address of the short block at each rank
+    uint64_t* group_bins;        // per resident workgroup: [groups][kSpLevels] address bins of the placed short blocks of 64 ranks
+    uint64_t* region_bins;       // per resident workgroup: [64][kSpLevels] the same per region
+    uint32_t slots;              // n rounded up to 64, plus 64
+    uint32_t groups;             // slots / 64
+    uint32_t list_cap;           // entries of the LDS list
+    uint32_t region_shift;       // 2^region_shift ranks share one summary in LDS; at most 64 regions cover all slots
+};
+
+// What one wave knows about the request it settles.
+struct SpRequest {
+    uint32_t s, ta, tf;
+    uint32_t wlo, whi;
+    // blocks settled earlier in the batch (lane = position in the batch)
+    uint64_t rivals_in;
+    uint32_t in_lo, in_hi;
+    // short blocks of the window (lane = rank - wlo), when it fits the wave
+    uint64_t rivals_w;
+    uint32_t w_lo, w_hi;
+};
+
+__device__ __forceinline__ uint32_t load_coherent(const uint32_t* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// The table of short blocks of the plan a workgroup is working on.
+struct SpTable {
+    uint32_t* addr;
+    uint64_t* group_bins;
+    uint64_t* region_bins;
+};
+
+__device__ __forceinline__ uint64_t load_coherent(const uint64_t* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Highest end address of the placed short blocks of the window that conflict with the request
+// in lifetime and meet [c, c + s); 0 if none does.  Called by ALL waves of the workgroup with the
+// same arguments; every wave returns the same value.  Regions first (lowest start / highest end
+// in LDS, then their address bins), then the groups of 64 ranks of a region (address bins), then
+// the blocks of a group.  The regions that are left are dealt out to the waves; `turn` counts the
+// calls of the workgroup (the results of three consecutive calls use different LDS words, so
+// that one barrier per call suffices).
+template <int kWaves, typename Lds>
+__device__ __forceinline__ uint32_t window_reach(const SpRequest& rq, uint32_t own_rank, uint32_t c, const SplitTables& tb,
+                                                 const SpTable& pt, uint32_t& turn, Lds& sh)
+{
+    const int lane = lane_id(), wave = wave_id();
+    const uint32_t cs = c + rq.s;
+    const uint32_t g_begin = rq.wlo / kWave, g_end = (rq.whi + kWave - 1) / kWave;     // groups of the window
+    const uint32_t per_region = 1u << (tb.region_shift - 6);                            // groups per region
+    const uint32_t r_begin = g_begin / per_region, r_end = (g_end + per_region - 1) / per_region;   // <= 64
+    uint64_t regions = __builtin_amdgcn_ballot_w64((uint32_t)lane >= r_begin && (uint32_t)lane < r_end &&
+                                                   sh.region_max[lane] > c && sh.region_min[lane] < cs);
+    if (regions == 0) return 0;                                                         // (the same in every wave)
+    int level = 0;
+    while (((cs - 1) >> sp_level_shift(level)) > 62u) ++level;                          // (level 7 always ends the search)
+    const uint64_t wanted = sp_bins(c, cs - 1, level);
+    {
+        const uint64_t bins = ((regions >> lane) & 1) ? load_coherent(pt.region_bins + lane * kSpLevels + level) : 0ull;
+        regions = __builtin_amdgcn_ballot_w64((bins & wanted) != 0);
+    }
+    if (regions == 0) return 0;
+    const uint32_t slot = turn % 3;
+    ++turn;
+    if (threadIdx.x == 0) sh.reach[(slot + 1) % 3] = 0;                                 // for the call after this one
+    uint32_t reach = 0;
+    uint32_t share = 0;
+    for (; regions; regions &= regions - 1, ++share) {
+        if (share % kWaves != (uint32_t)wave) continue;                                 // (uniform) another wave's region
+        const uint32_t first = (uint32_t)__builtin_ctzll(regions) * per_region;
+        for (uint32_t g0 = first; g0 < first + per_region; g0 += kWave) {
+            const uint32_t g = g0 + lane;
+            const bool valid = g >= g_begin && g < g_end && g < first + per_region;
+            const uint64_t bins = valid ? load_coherent(pt.group_bins + (size_t)g * kSpLevels + level) : 0ull;
+            uint64_t open = __builtin_amdgcn_ballot_w64((bins & wanted) != 0);
+            // two groups at a time, so that the reads of the second are under way while the first is looked at
+            while (open) {
+                const uint32_t k0 = (g0 + (uint32_t)__builtin_ctzll(open)) * kWave + lane;    // < slots
+                open &= open - 1;
+                const bool two = open != 0;
+                const uint32_t k1 = two ? (g0 + (uint32_t)__builtin_ctzll(open)) * kWave + lane : k0;
+                open &= open - 1;
+                const uint32_t a0 = pt.addr[k0], s0 = tb.size_by_rank[k0];
+                const uint32_t a1 = pt.addr[k1], s1 = tb.size_by_rank[k1];
+                // ranks above the request's own started during its lifetime; the few below need a look at their release time
+                bool live0 = k0 >= rq.wlo && k0 < rq.whi && a0 != kSpUnplaced, live1 = two && k1 < rq.whi && a1 != kSpUnplaced;
+                if (k0 - lane <= own_rank) live0 = live0 && tb.by_rank[k0].z > rq.ta;
+                if (k1 - lane <= own_rank) live1 = live1 && k1 >= rq.wlo && tb.by_rank[k1].z > rq.ta;
+                reach = umax(reach, (live0 && a0 < cs && a0 + s0 > c) ? a0 + s0 : 0u);
+                reach = umax(reach, (live1 && a1 < cs && a1 + s1 > c) ? a1 + s1 : 0u);
+            }
+        }
+    }
+    reach = read_lane(wave_scan_max(reach), kWave - 1);
+    if (lane == 0 && reach) atomicMax(&sh.reach[slot], reach);
+    __syncthreads();
+    return sh.reach[slot];
+}
+
+// Lowest address >= c at which [c, c + s) meets no conflicting block other than the long blocks
+// of the list; gives up (returns something > limit - s) once the request cannot end by `limit`.
+// kWide: the request's window is looked up in the table itself, by the whole workgroup.
+template <bool kWide, int kWaves, typename Lds>
+__device__ __forceinline__ uint32_t clear_others(const SpRequest& rq, uint32_t own_rank, uint32_t c, uint32_t limit,
+                                                 const SplitTables& tb, const SpTable& pt, uint32_t& turn, Lds& sh)
+{
+    for (;;) {
+        if (c > limit || limit - c < rq.s) return c;                              // (uniform)
+        const uint32_t cs = c + rq.s;
+        const uint64_t hit_in = rq.rivals_in & lanes_lt(rq.in_lo, cs) & lanes_lt(c, rq.in_hi);
+        const uint64_t hit_w = rq.rivals_w & lanes_lt(rq.w_lo, cs) & lanes_lt(c, rq.w_hi);
+        if (hit_in | hit_w) {
+            const uint32_t ends = umax(keep_lanes(hit_in, rq.in_hi), keep_lanes(hit_w, rq.w_hi));
+            c = read_lane(wave_scan_max(ends), kWave - 1);
+            continue;
+        }
+        if constexpr (!kWide) {
+            return c;
+        } else {
+            const uint32_t reach = window_reach<kWaves>(rq, own_rank, c, tb, pt, turn, sh);
+            if (reach == 0) return c;
+            c = reach;
+        }
+    }
+}
+
+// Settles request q of the batch: the lowest address at which it conflicts with nothing placed
+// before it.  A request whose window fits the lanes of a wave (kWide false) is settled by one
+// wave; one with a wider window by all waves of the workgroup together, every wave taking the
+// same steps (they read the same LDS) and sharing only the look-ups in the table.
+template <bool kWide, int kWaves, typename Lds>
+__device__ __forceinline__ uint32_t settle_request(const SpList& list, uint32_t count, uint32_t b0, uint32_t q,
+                                                   uint64_t dep_q, const SplitTables& tb, const SpTable& pt,
+                                                   uint32_t& turn, Lds& sh)
+{
+    const int lane = lane_id();
+    SpRequest rq;
+    rq.s = sh.rq_size[b0 + q]; rq.ta = sh.rq_ta[b0 + q]; rq.tf = sh.rq_tf[b0 + q];
+    rq.wlo = sh.rq_wlo[b0 + q]; rq.whi = sh.rq_whi[b0 + q];
+    const uint32_t own_rank = sh.rq_rank[b0 + q] & ~kSpLongFlag;
+    // earlier requests of the batch with a conflicting lifetime: all settled by now
+    rq.rivals_in = dep_q;
+    rq.in_lo = sh.rq_addr[b0 + lane];
+    rq.in_hi = rq.in_lo + sh.rq_size[b0 + lane];
+    rq.rivals_w = 0; rq.w_lo = 0; rq.w_hi = 0;
+    if constexpr (!kWide) {
+        // conflicting short blocks of its window, as gathered when the batch began
+        const uint32_t in_pool = __builtin_amdgcn_readfirstlane(sh.win_count[q]);
+        if (in_pool != kSpRefetch) {
+            Span<uint32_t> sp = {0u, 0u};
+            if ((uint32_t)lane < in_pool) sp = sh.pool[sh.win_first[q] + lane];
+            rq.rivals_w = in_pool >= (uint32_t)kWave ? ~0ull : (1ull << in_pool) - 1;
+            rq.w_lo = sp.lo;
+            rq.w_hi = sp.hi;
+        } else {
+            const uint32_t k = rq.wlo + lane;                       // < slots
+            const uint32_t a = pt.addr[k];
+            const uint4 rec = tb.by_rank[k];
+            rq.rivals_w = __builtin_amdgcn_ballot_w64(k < rq.whi && a != kSpUnplaced && rec.z > rq.ta && rec.y < rq.tf);
+            rq.w_lo = a;
+            rq.w_hi = a + rec.x;
+        }
+    }
+    // walk over the long blocks, in address order
+    uint32_t run = 0;
+    for (uint32_t k0 = 0; k0 < count; k0 += kWave) {
+        const uint32_t k = k0 + lane;
+        const bool valid = k < count;
+        const SpList::Entry en = list.load(valid ? k : count - 1);
+        const bool conflict = valid && en.ta() < rq.tf && rq.ta < en.tf();
+        const uint32_t incl = wave_scan_max(conflict ? en.hi() : 0u);
+        const uint32_t before = umax(run, wave_shift_up(incl, 0u));
+        // a hole [before, lo) in front of a conflicting block, large enough as such
+        uint64_t opens = __builtin_amdgcn_ballot_w64(conflict && en.lo() >= before && en.lo() - before >= rq.s);
+        while (opens) {
+            const int f = __builtin_ctzll(opens);
+            opens &= opens - 1;
+            const uint32_t limit = read_lane(en.lo(), f);
+            const uint32_t c = clear_others<kWide, kWaves>(rq, own_rank, read_lane(before, f), limit, tb, pt, turn, sh);
+            if (c <= limit && limit - c >= rq.s) return c;
+        }
+        run = umax(run, read_lane(incl, kWave - 1));
+    }
+    return clear_others<kWide, kWaves>(rq, own_rank, run, 0xffffffffu, tb, pt, turn, sh);     // on top of every conflicting long block
+}
+
+template <int kThreads>
+__global__ void __launch_bounds__(kThreads, 2) plan_split_kernel(PlanParams prm, SplitTables tb)
+{
+    constexpr int kWaves = kThreads / kWave;
+    extern __shared__ __align__(16) unsigned char smem[];
+    SplitLds& sh = *reinterpret_cast<SplitLds*>(smem);
+    const uint32_t n = prm.n;
+    if (*prm.status != STALLOC_OK) return;
+    if (!(prm.acc[kAccSplit] & 1)) return;                            // another kernel places this trace
+    const uint64_t mode = prm.acc[kAccMode];
+    const bool try32 = (mode & kModeTry32) != 0;
+    const uint32_t shift = (uint32_t)(mode & 63);
+    const int lane = lane_id(), wave = wave_id();
+    // the requests of a batch this wave settles: positions wave, wave + kWaves, ...
+    uint64_t stripe = 0;
+    for (int e = wave; e < kSpBatch; e += kWaves) stripe |= 1ull << e;
+
+    SpList list, spare;
+    list.bind(smem + sizeof(SplitLds), tb.list_cap);
+    spare = list;
+    SpTable pt;
+    pt.addr = tb.addr + (size_t)blockIdx.x * tb.slots;
+    pt.group_bins = tb.group_bins + (size_t)blockIdx.x * tb.groups * kSpLevels;
+    pt.region_bins = tb.region_bins + (size_t)blockIdx.x * kWave * kSpLevels;
+    uint32_t* addr = pt.addr;
+
+    for (uint32_t p = blockIdx.x; p < prm.P; p += gridDim.x) {
+        const uint32_t* order = prm.orders + (size_t)p * n;
+        uint64_t* out = prm.offsets ? prm.offsets + (size_t)p * n : nullptr;
+        uint32_t count = 0;
+        bool outgrown = false;                                        // (uniform) 32-bit counts may not hold the next batch
+        __syncthreads();                                              // every wave is done with the previous plan
+        for (uint32_t k = threadIdx.x; k < tb.slots; k += kThreads) addr[k] = kSpUnplaced;
+        for (uint32_t g = threadIdx.x; g < tb.groups * kSpLevels; g += kThreads) pt.group_bins[g] = 0ull;
+        for (uint32_t g = threadIdx.x; g < (uint32_t)(kWave * kSpLevels); g += kThreads) pt.region_bins[g] = 0ull;
+        if (threadIdx.x < kWave) { sh.region_min[threadIdx.x] = 0xffffffffu; sh.region_max[threadIdx.x] = 0u; }
+        if (threadIdx.x == 0) { sh.extent_now = 0; sh.peak = 0; sh.pool_used = 0; sh.reach[0] = 0; }
+        uint32_t turn = 0;                                            // calls of window_reach: slot 0 is clear
+
+        for (uint32_t r0 = 0; r0 < n; r0 += kSpRefill) {
+            const uint32_t staged = n - r0 < (uint32_t)kSpRefill ? n - r0 : (uint32_t)kSpRefill;
+            __syncthreads();                                          // previous refill fully consumed
+            if (threadIdx.x < staged) {
+                uint32_t i = order[r0 + threadIdx.x];
+                if (i >= n) { atomicMax(prm.status, (uint32_t)STALLOC_ERR_BAD_ORDER); i = 0; }
+                const uint2 w = tb.window[i];
+                sh.rq_id[threadIdx.x] = i;
+                sh.rq_size[threadIdx.x] = (uint32_t)(prm.size[i] >> shift);
+                sh.rq_ta[threadIdx.x] = prm.ta[i];
+                sh.rq_tf[threadIdx.x] = prm.tf[i];
+                sh.rq_rank[threadIdx.x] = tb.rank_of[i];
+                sh.rq_wlo[threadIdx.x] = w.x;
+                sh.rq_whi[threadIdx.x] = w.y;
+            }
+            if (threadIdx.x < kSpBatch) sh.dep[threadIdx.x] = 0;
+            __syncthreads();
+
+            for (uint32_t b0 = 0; b0 < staged; b0 += kSpBatch) {
+                const uint32_t nb = staged - b0 < (uint32_t)kSpBatch ? staged - b0 : (uint32_t)kSpBatch;
+                const bool mine = lane < (int)nb;
+                const uint32_t my_size = mine ? sh.rq_size[b0 + lane] : 0u;
+                const uint32_t my_ta = mine ? sh.rq_ta[b0 + lane] : 0xffffffffu;      // an empty lifetime otherwise
+                const uint32_t my_tf = mine ? sh.rq_tf[b0 + lane] : 0u;
+                const uint32_t my_rank = mine ? sh.rq_rank[b0 + lane] : 0u;
+                const uint32_t my_wlo = mine ? sh.rq_wlo[b0 + lane] : 0u;
+                const uint32_t my_whi = mine ? sh.rq_whi[b0 + lane] : 0u;
+                if (try32) {
+                    // no address of this batch exceeds the extent so far plus the sizes of the batch
+                    const uint64_t growth = wave_sum64((uint64_t)my_size);
+                    if ((uint64_t)sh.extent_now + growth > 0xffffffffull) { outgrown = true; break; }
+                }
+                // The windows of the requests this wave settles (positions wave, wave + kWaves, ... of
+                // the batch): the reads go out now and are looked at after the next step.  What the
+                // batch itself adds to the table concerns them through `dep` instead.
+                constexpr int kMine = kSpBatch / kWaves;
+                uint32_t f_addr[kMine];
+                uint4 f_rec[kMine];
+#pragma unroll
+                for (int j = 0; j < kMine; ++j) {
+                    const uint32_t k = read_lane(my_wlo, wave + j * kWaves) + lane;     // < slots
+                    f_addr[j] = addr[k];
+                    f_rec[j] = tb.by_rank[k];
+                }
+                // which earlier requests of the batch each request has to wait for: wave w looks at
+                // the requests 64 / kWaves * w .. of the batch, for all 64 lanes
+                {
+                    uint64_t part = 0;
+                    for (int j = 0; j < kSpBatch / kWaves; ++j) {
+                        const int e = wave * (kSpBatch / kWaves) + j;
+                        const uint32_t e_ta = read_lane(my_ta, e), e_tf = read_lane(my_tf, e);
+                        if (e < lane && e_ta < my_tf && my_ta < e_tf) part |= 1ull << e;
+                    }
+                    if (part) atomicOr((unsigned long long*)&sh.dep[lane], (unsigned long long)part);
+                }
+                // the placed short blocks of each window that conflict in lifetime, packed into the pool
+#pragma unroll
+                for (int j = 0; j < kMine; ++j) {
+                    const int q = wave + j * kWaves;
+                    const uint32_t wlo = read_lane(my_wlo, q), whi = read_lane(my_whi, q);
+                    const uint32_t q_ta = read_lane(my_ta, q), q_tf = read_lane(my_tf, q);
+                    const bool rival = whi - wlo <= (uint32_t)kWave && wlo + lane < whi && f_addr[j] != kSpUnplaced &&
+                                       f_rec[j].z > q_ta && f_rec[j].y < q_tf;
+                    const uint64_t rivals = __builtin_amdgcn_ballot_w64(rival);
+                    const uint32_t found = (uint32_t)__builtin_popcountll(rivals);
+                    uint32_t first = 0;
+                    if (found) {                                               // (uniform)
+                        if (lane == 0) first = atomicAdd(&sh.pool_used, found);
+                        first = read_lane(first, 0);
+                    }
+                    const bool fits = first + found <= (uint32_t)kSpPool;
+                    if (rival && fits) sh.pool[first + lanes_below(rivals)] = Span<uint32_t>{f_addr[j], f_addr[j] + f_rec[j].x};
+                    if (lane == 0) {
+                        sh.win_first[q] = first;
+                        sh.win_count[q] = fits ? found : kSpRefetch;
+                    }
+                }
+                __syncthreads();
+                const uint64_t dep = sh.dep[lane];
+                const uint64_t all = nb == (uint32_t)kSpBatch ? ~0ull : (1ull << nb) - 1;
+                uint64_t done = 0;
+                const uint64_t wide = __builtin_amdgcn_ballot_w64(mine && my_whi - my_wlo > (uint32_t)kWave);
+                while (done != all) {
+                    // settled: bit set in `done`; ready: everything it waits for is settled.  (What is ready
+                    // together does not conflict with each other, so the order inside a round is free.)
+                    const uint64_t ready = __builtin_amdgcn_ballot_w64(mine && !((done >> lane) & 1) && (dep & ~done) == 0);
+                    for (uint64_t todo = ready & stripe & ~wide; todo; todo &= todo - 1) {
+                        const int q = __builtin_ctzll(todo);
+                        const uint32_t x = settle_request<false, kWaves>(list, count, b0, (uint32_t)q, readlane64(dep, q), tb, pt,
+                                                                         turn, sh);
+                        if (lane == 0) {
+                            sh.rq_addr[b0 + q] = x;
+                            atomicMax(&sh.peak, x + read_lane(my_size, q));
+                        }
+                    }
+                    for (uint64_t todo = ready & wide; todo; todo &= todo - 1) {
+                        const int q = __builtin_ctzll(todo);
+                        const uint32_t x = settle_request<true, kWaves>(list, count, b0, (uint32_t)q, readlane64(dep, q), tb, pt,
+                                                                        turn, sh);
+                        if (threadIdx.x == 0) {
+                            sh.rq_addr[b0 + q] = x;
+                            atomicMax(&sh.peak, x + read_lane(my_size, q));
+                        }
+                    }
+                    __syncthreads();
+                    done |= ready;
+                }
+                // the short blocks of the batch enter the table and its summaries
+                if (wave == 1 % kWaves && mine && !(my_rank & kSpLongFlag)) {
+                    const uint32_t x = sh.rq_addr[b0 + lane];
+                    addr[my_rank] = x;
+                    for (int level = 0; level < kSpLevels; ++level) {
+                        const uint64_t bins = sp_bins(x, x + my_size - 1, level);
+                        atomicOr((unsigned long long*)(pt.group_bins + (size_t)(my_rank / kWave) * kSpLevels + level),
+                                 (unsigned long long)bins);
+                        atomicOr((unsigned long long*)(pt.region_bins + (my_rank >> tb.region_shift) * kSpLevels + level),
+                                 (unsigned long long)bins);
+                    }
+                    atomicMin(&sh.region_min[my_rank >> tb.region_shift], x);
+                    atomicMax(&sh.region_max[my_rank >> tb.region_shift], x + my_size);
+                }
+                // the long blocks of the batch, sorted by address, go into the list
+                const uint64_t longs = __builtin_amdgcn_ballot_w64(mine && (my_rank & kSpLongFlag));
+                uint32_t pending = (uint32_t)__builtin_popcountll(longs);
+                if (count + pending > tb.list_cap) pending = 0;          // (an order that repeats requests; result unspecified)
+                if (wave == 0) {
+                    const uint32_t x = mine ? sh.rq_addr[b0 + lane] : 0u;
+                    uint32_t place = 0;
+                    for (uint64_t m = longs; m; m &= m - 1) {
+                        const int e = __builtin_ctzll(m);
+                        const uint32_t e_x = read_lane(x, e);
+                        place += (e_x < x || (e_x == x && e < lane)) ? 1u : 0u;
+                    }
+                    if (pending && ((longs >> lane) & 1)) {
+                        sh.pend_span[place] = Span<uint32_t>{x, x + my_size};
+                        sh.pend_life[place] = make_uint2(my_ta, my_tf);
+                    }
+                    if (lane == 0) { sh.extent_now = sh.peak; sh.pool_used = 0; }
+                    if (lane < kSpBatch) sh.dep[lane] = 0;
+                }
+                __syncthreads();
+                if (pending) {
+                    merge_pending<uint32_t, true, kThreads>(list, spare, count, pending, sh);
+                    count += pending;
+                }
+            }
+            if (outgrown) break;
+            // addresses of this refill -> offsets[p][request]
+            __syncthreads();
+            if (out && threadIdx.x < staged) out[sh.rq_id[threadIdx.x]] = (uint64_t)sh.rq_addr[threadIdx.x] << shift;
+        }
+        __syncthreads();
+        if (outgrown) {
+            if (threadIdx.x == 0) prm.wide_plans[p] = 1;
+            continue;
+        }
+        if (threadIdx.x == 0) prm.peaks[p] = (uint64_t)sh.peak << shift;
+    }
+}
+
+size_t split_workspace(uint32_t n, const DeviceInfo& di, Carver& cv, SplitWorkspace* ws)
+{
+    const uint32_t n_pad = (n + kSortTile - 1) / kSortTile * kSortTile;
+    const uint32_t slots = (n + kWave - 1) / kWave * kWave + kWave;
+    uint32_t grid = (uint32_t)di.cus * 2;
+    ws->hist = cv.take<uint32_t>(32);
+    ws->gate = cv.take<uint32_t>(1);
+    ws->keys = cv.take<ulonglong2>(n_pad);
+    ws->spare = cv.take<ulonglong2>(n_pad);
+    ws->by_rank = cv.take<uint4>(slots);
+    ws->size_by_rank = cv.take<uint32_t>(slots);
+    ws->rank_of = cv.take<uint32_t>(n);
+    ws->window = cv.take<uint2>(n);
+    ws->addr = cv.take<uint32_t>((size_t)grid * slots);
+    ws->group_bins = cv.take<uint64_t>((size_t)grid * (slots / kWave) * kSpLevels);
+    ws->region_bins = cv.take<uint64_t>((size_t)grid * kWave * kSpLevels);
+    ws->slots = slots;
+    ws->n_pad = n_pad;
+    ws->grid = grid;
+    return cv.used;
+}
+
+bool launch_plan_split(const PlanParams& prm, const SplitWorkspace& ws, const DeviceInfo& di, hipStream_t stream)
+{
+    const uint32_t n = prm.n;
+    const size_t lds = di.lds_per_block / 2;                          // two workgroups per CU
+    const uint32_t list_cap = split_list_capacity(lds);
+    uint32_t blocks = (n + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    uint64_t* acc = const_cast<uint64_t*>(prm.acc);
+
+    hipLaunchKernelGGL(sp_clear_histogram, dim3(1), dim3(64), 0, stream, ws.hist, ws.gate);
+    hipLaunchKernelGGL(sp_histogram, dim3(blocks > 256 ? 256 : blocks), dim3(256), 0, stream, prm.ta, prm.tf, n, ws.hist,
+                       prm.status);
+    hipLaunchKernelGGL(sp_decide, dim3(1), dim3(64), 0, stream, acc, ws.hist, n, list_cap, prm, ws.gate, prm.status);
+    hipLaunchKernelGGL(sp_sort_tiles, dim3(ws.n_pad / kSortTile), dim3(kSortTile), 0, stream, prm.ta, n, ws.keys, ws.gate);
+    const ulonglong2* sorted = launch_merge_tiles(ws.keys, ws.spare, ws.n_pad, 1, ws.gate, stream);
+    hipLaunchKernelGGL(sp_tables, dim3(blocks), dim3(256), 0, stream, sorted, prm.size, prm.ta, prm.tf, n, ws.slots, prm.acc,
+                       ws.by_rank, ws.size_by_rank, ws.rank_of, ws.gate);
+    hipLaunchKernelGGL(sp_windows, dim3(blocks), dim3(256), 0, stream, ws.by_rank, prm.ta, prm.tf, n, prm.acc, ws.window,
+                       ws.gate);
+
+    SplitTables tb;
+    tb.by_rank = ws.by_rank; tb.size_by_rank = ws.size_by_rank; tb.rank_of = ws.rank_of; tb.window = ws.window;
+    tb.addr = ws.addr; tb.group_bins = ws.group_bins; tb.region_bins = ws.region_bins;
+    tb.slots = ws.slots; tb.groups = ws.slots / kWave; tb.list_cap = list_cap;
+    tb.region_shift = 6;
+    while (((uint64_t)ws.slots + (1ull << tb.region_shift) - 1) >> tb.region_shift > (uint64_t)kWave) ++tb.region_shift;
+    auto kernel = &plan_split_kernel<kSpThreads>;
+    static std::atomic<bool> attr_set[64] = {};        // (set twice at worst when threads race)
+    if (!attr_set[di.device]) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)di.lds_per_block) != hipSuccess)
+            return false;
+        attr_set[di.device] = true;
+    }
+    uint32_t grid = ws.grid;
+    if (grid > prm.P) grid = prm.P;
+    const size_t lds_bytes = sizeof(SplitLds) + (size_t)list_cap * SpList::kEntryBytes;
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kSpThreads), lds_bytes, stream, prm, tb);
+    return true;
+}
+
+}  // namespace stalloc
