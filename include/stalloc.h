@@ -250,24 +250,69 @@ int stalloc_make_orders(const stalloc_trace *trace, uint32_t first_plan, uint32_
                         uint32_t *orders, uint32_t *device_status,
                         void *workspace, size_t *workspace_bytes, void *hip_stream);
 
+/*
+ * Informational: what the stalloc_plan call that last used `workspace` did with its trace.
+ * Synchronises `hip_stream` (the stream of that call) and reads a few words back; `info` is HOST
+ * memory.  Which kernel places a trace is decided on the device, from the trace alone:
+ *   STALLOC_KERNEL_BITMAP       per-plan table of placed blocks plus per-request occupancy bitmaps
+ *                               in LDS (every size at most 31 granules, n <= 32768, few granules)
+ *   STALLOC_KERNEL_LIST_LDS     list of all placed blocks sorted by address, in LDS
+ *   STALLOC_KERNEL_LIST_MEMORY  the same list in the workspace (traces too long for LDS)
+ *   STALLOC_KERNEL_LONG_LIST    sorted list of the long-lived blocks in LDS, short-lived blocks in
+ *                               a per-plan table ordered by allocation time (long traces in which
+ *                               at most an eighth of the requests outlive `lifetime_threshold`)
+ * granule_log2: addresses are multiples of 2^granule_log2 bytes (the largest power of two that
+ * divides every size); granules: sum of sizes in that unit.  plans_64bit: plans whose extent
+ * approached 2^32 granules and that were therefore placed again with 64-bit byte addresses.
+ */
+typedef enum stalloc_plan_kernel {
+    STALLOC_KERNEL_NONE = 0,
+    STALLOC_KERNEL_BITMAP = 1,
+    STALLOC_KERNEL_LIST_LDS = 2,
+    STALLOC_KERNEL_LIST_MEMORY = 3,
+    STALLOC_KERNEL_LONG_LIST = 4
+} stalloc_plan_kernel;
+
+typedef struct stalloc_plan_info {
+    uint32_t kernel;             /* a stalloc_plan_kernel                                        */
+    uint32_t granule_log2;
+    uint64_t granules;
+    uint32_t plans_64bit;
+    uint32_t lifetime_threshold; /* STALLOC_KERNEL_LONG_LIST: requests living longer are "long"   */
+    uint32_t long_requests;      /* ... and how many there are                                    */
+    uint32_t address_bits;       /* width of the addresses the kernel keeps per placed block: 16, 22, 32 (counts of
+                                    granules) or 64 (bytes)                                       */
+} stalloc_plan_info;
+
+int stalloc_plan_report(const void *workspace, stalloc_plan_info *info, void *hip_stream);
+
+/*
+ * Measurement aid: enqueues one plain kernel that exercises one resource of the chip, so that the
+ * rates of the planning kernels can be set against what the device delivers (the caller times it
+ * with events on `hip_stream`).
+ *   STALLOC_PROBE_COPY      copies the first half of `buffer` to its second half (16-byte words);
+ *                           work_done = bytes read + bytes written
+ *   STALLOC_PROBE_LDS_READ  2 workgroups of 1024 threads per CU, every thread reads 16 bytes of LDS
+ *                           `iters` times; work_done = bytes read from LDS
+ *   STALLOC_PROBE_INT_ALU   32 workgroups of 256 threads per CU, 8 independent 32-bit integer
+ *                           operations per thread and step, `iters` steps; work_done = lane operations
+ * buffer: device memory, 16-byte aligned; the last two kinds write 4 bytes per thread into it
+ * (8 KiB resp. 32 KiB per CU).  work_done: HOST memory.
+ */
+typedef enum stalloc_probe_kind {
+    STALLOC_PROBE_COPY = 0,
+    STALLOC_PROBE_LDS_READ = 1,
+    STALLOC_PROBE_INT_ALU = 2
+} stalloc_probe_kind;
+
+int stalloc_probe(uint32_t what, void *buffer, size_t buffer_bytes, uint32_t iters, uint64_t *work_done,
+                  void *hip_stream);
+
 /* Human-readable name of a stalloc_status; never NULL.  Host memory, static storage. */
 const char *stalloc_status_string(int status);
 
-/*
- * Informational: how stalloc_plan keeps each plan's placed blocks on the current
- * device.  `granules` = (sum of sizes) / g and `largest` = (largest size) / g, with g the
- * largest power of two dividing every size (all addresses are multiples of g).  Returns
- * the bytes of one stored block in the low 8 bits (4: per-plan table of placed blocks plus
- * per-request occupancy bitmaps, needs largest <= 31, n <= 32768 and an LDS bitmap of
- * granules bits beside the table; 8: sorted list with 16-bit fields, needs granules < 2^16
- * and t_end < 2^16; 16: sorted list of 32-bit granule counts, needs granules < 2^31; 24:
- * sorted list of 64-bit byte addresses), bit 8 set when the blocks are kept in LDS rather
- * than in the workspace, bit 9 set for the bitmap variant, bit 10 set when 32-bit granule
- * counts are only tried plan by plan (granules >= 2^31 but largest < 2^30: a plan whose
- * extent approaches 2^32 granules is placed with 64-bit addresses instead).  0 if no device.
- * stalloc_plan_lds_capacity: largest n for which 16-byte entries stay in LDS.
- */
-uint32_t stalloc_plan_list_layout(uint32_t n, uint32_t t_end, uint64_t granules, uint64_t largest);
+/* Informational: the largest n for which stalloc_plan keeps 16-byte list entries (32-bit granule
+ * counts) of all placed blocks in LDS on the current device; 0 if there is no device. */
 uint32_t stalloc_plan_lds_capacity(void);
 
 #ifdef __cplusplus

@@ -26,7 +26,8 @@ STATIC_MAX_T_END = 524288        # STALLOC_STATIC_MAX_T_END of include/stalloc.h
 EXPORTS = ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_lower_bound_static",
            "stalloc_reusable_space",
            "stalloc_memory_layers", "stalloc_expand_layers", "stalloc_tmp", "stalloc_make_orders",
-           "stalloc_status_string", "stalloc_plan_lds_capacity", "stalloc_plan_list_layout")
+           "stalloc_status_string", "stalloc_plan_lds_capacity", "stalloc_plan_report", "stalloc_probe")
+KERNELS = {0: "none", 1: "bitmap", 2: "list_lds", 3: "list_memory", 4: "long_list"}
 
 
 class StallocError(RuntimeError):
@@ -38,6 +39,12 @@ class StallocError(RuntimeError):
 class _Trace(ctypes.Structure):
     _fields_ = [("n", ctypes.c_uint32), ("t_end", ctypes.c_uint32), ("size", ctypes.c_void_p),
                 ("t_alloc", ctypes.c_void_p), ("t_free", ctypes.c_void_p)]
+
+
+class _PlanInfo(ctypes.Structure):
+    _fields_ = [("kernel", ctypes.c_uint32), ("granule_log2", ctypes.c_uint32), ("granules", ctypes.c_uint64),
+                ("plans_64bit", ctypes.c_uint32), ("lifetime_threshold", ctypes.c_uint32),
+                ("long_requests", ctypes.c_uint32), ("address_bits", ctypes.c_uint32)]
 
 
 def _load() -> ctypes.CDLL:
@@ -61,12 +68,14 @@ def _load() -> ctypes.CDLL:
                  "stalloc_reusable_space", "stalloc_memory_layers", "stalloc_expand_layers", "stalloc_tmp",
                  "stalloc_make_orders"):
         getattr(lib, name).restype = ctypes.c_int
+    lib.stalloc_plan_report.argtypes = [vp, ctypes.POINTER(_PlanInfo), vp]
+    lib.stalloc_plan_report.restype = ctypes.c_int
+    lib.stalloc_probe.argtypes = [u32, vp, ctypes.c_size_t, u32, ctypes.POINTER(ctypes.c_uint64), vp]
+    lib.stalloc_probe.restype = ctypes.c_int
     lib.stalloc_status_string.argtypes = [ctypes.c_int]
     lib.stalloc_status_string.restype = ctypes.c_char_p
     lib.stalloc_plan_lds_capacity.argtypes = []
-    lib.stalloc_plan_list_layout.argtypes = [u32, u32, ctypes.c_uint64, ctypes.c_uint64]
-    for name in ("stalloc_plan_lds_capacity", "stalloc_plan_list_layout"):
-        getattr(lib, name).restype = ctypes.c_uint32
+    lib.stalloc_plan_lds_capacity.restype = ctypes.c_uint32
     return lib
 
 
@@ -147,6 +156,24 @@ def stalloc_plan(size, t_alloc, t_free, t_end: int, orders, *, want_offsets: boo
     _check(lib.stalloc_plan(*args, ws.data_ptr(), ctypes.byref(have), _stream(stream)), "stalloc_plan")
     out["workspace"] = ws
     return out
+
+
+def stalloc_plan_report(plan: Dict[str, torch.Tensor], *, stream=None) -> Dict[str, int]:
+    """What the stalloc_plan call that produced `plan` did (synchronises): kernel name, address granule, ..."""
+    info = _PlanInfo()
+    _check(lib.stalloc_plan_report(plan["workspace"].data_ptr(), ctypes.byref(info), _stream(stream)), "stalloc_plan_report")
+    return {"kernel": KERNELS.get(info.kernel, str(info.kernel)), "granule_log2": info.granule_log2,
+            "granules": info.granules, "plans_64bit": info.plans_64bit,
+            "lifetime_threshold": info.lifetime_threshold, "long_requests": info.long_requests,
+            "address_bits": info.address_bits}
+
+
+def stalloc_probe(what: int, buffer: torch.Tensor, iters: int = 0, *, stream=None) -> int:
+    """Enqueue one probe kernel (0 copy, 1 LDS read, 2 integer ALU) on `buffer` (uint8); returns its work."""
+    done = ctypes.c_uint64(0)
+    _check(lib.stalloc_probe(int(what), _dev(buffer, torch.uint8, "buffer"), buffer.numel(), int(iters),
+                             ctypes.byref(done), _stream(stream)), "stalloc_probe")
+    return int(done.value)
 
 
 def stalloc_validate(size, t_alloc, t_free, t_end: int, offsets, *, stream=None,

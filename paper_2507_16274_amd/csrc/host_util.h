@@ -70,12 +70,14 @@ struct Carver {
 // | kModeNarrow when 32-bit granule counts can hold every address | kModeCompact when 16-bit
 // counts can | kModeBitmap when the sizes suit one-bit-per-granule occupancy bitmaps | kModeTry32
 // when only plans that stack nearly everything would overflow 32-bit counts.
-constexpr int kAccWords = 8;
+constexpr int kAccWords = 16;
 constexpr int kAccMode = 4;
 constexpr int kAccMaxSize = 5;
 constexpr int kAccGranules = 6;                // sum of sizes in granules
 constexpr int kAccSplit = 7;                   // bit 0: the kernel that keeps only long-lived blocks in its list places the
                                                // trace; bits 8..31: its lifetime threshold; bits 32..63: long-lived requests
+constexpr int kAccKernel = 8;                  // which placement kernel took the trace (stalloc_plan_kernel in stalloc.h)
+constexpr int kAccWidePlans = 9;               // plans that outgrew 32-bit granule counts and were placed with 64-bit addresses
 constexpr uint64_t kModeNarrow = 1ull << 8;
 constexpr uint64_t kModeCompact = 1ull << 9;   // sum of sizes in granules below 2^16 as well
 constexpr uint64_t kModeBitmap = 1ull << 10;   // sum <= kBitmapGranules and every size <= kBitmapMaxSize granules

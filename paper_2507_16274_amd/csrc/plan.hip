@@ -495,6 +495,9 @@ __global__ void __launch_bounds__(kThreads, 4) plan_kernel(PlanParams prm)   // 
     const bool compact = prm.compact_enqueued && (mode & kModeCompact) != 0;
     if (sizeof(Addr) == 4 && compact != kCompact) return;
     const uint32_t shift = sizeof(Addr) == 4 ? (uint32_t)(mode & 63) : 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0 && !(sizeof(Addr) == 8 && try32))
+        const_cast<uint64_t*>(prm.acc)[kAccKernel] = (kLds ? STALLOC_KERNEL_LIST_LDS : STALLOC_KERNEL_LIST_MEMORY) |
+                                                     ((kCompact ? 16u : 8u * (uint32_t)sizeof(Addr)) << 8);
 
     List list, spare;
     if constexpr (kLds) {
@@ -508,6 +511,8 @@ __global__ void __launch_bounds__(kThreads, 4) plan_kernel(PlanParams prm)   // 
 
     for (uint32_t p = blockIdx.x; p < prm.P; p += gridDim.x) {
         if (sizeof(Addr) == 8 && try32 && !prm.wide_plans[p]) continue;   // (uniform) placed with 32-bit counts already
+        if (sizeof(Addr) == 8 && try32 && threadIdx.x == 0)
+            atomicAdd((unsigned long long*)&const_cast<uint64_t*>(prm.acc)[kAccWidePlans], 1ull);
         const uint32_t* order = prm.orders + (size_t)p * n;
         uint64_t* out = prm.offsets ? prm.offsets + (size_t)p * n : nullptr;
         Addr peak = 0;                                        // tracked by wave 0
@@ -656,30 +661,29 @@ inline bool launch_plan(const PlanParams& prm, uint32_t grid, const DeviceInfo& 
 
 using namespace stalloc;
 
+extern "C" int stalloc_plan_report(const void* workspace, stalloc_plan_info* info, void* hip_stream)
+{
+    if (!workspace || !info) return STALLOC_ERR_INVALID_ARG;
+    uint64_t acc[kAccWords];
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (hipMemcpyAsync(acc, workspace, sizeof(acc), hipMemcpyDeviceToHost, stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess)
+        return STALLOC_ERR_DEVICE;
+    info->kernel = (uint32_t)(acc[kAccKernel] & 0xffu);
+    info->address_bits = (uint32_t)((acc[kAccKernel] >> 8) & 0xffu);
+    info->granule_log2 = (uint32_t)(acc[kAccMode] & 63);
+    info->granules = acc[kAccGranules];
+    info->plans_64bit = (uint32_t)acc[kAccWidePlans];
+    info->lifetime_threshold = (acc[kAccSplit] & 1) ? (uint32_t)((acc[kAccSplit] >> 8) & 0xffffffu) : 0u;
+    info->long_requests = (acc[kAccSplit] & 1) ? (uint32_t)(acc[kAccSplit] >> 32) : 0u;
+    return STALLOC_OK;
+}
+
 extern "C" uint32_t stalloc_plan_lds_capacity(void)
 {
     DeviceInfo di;
     if (!device_info(&di)) return 0;
     return lds_capacity_entries<uint32_t, kThreadsLds>(di.lds_per_block, entry_bytes<uint32_t>());
-}
-
-extern "C" uint32_t stalloc_plan_list_layout(uint32_t n, uint32_t t_end, uint64_t granules, uint64_t largest)
-{
-    DeviceInfo di;
-    if (!device_info(&di)) return 0;
-    uint32_t pool_words[kBitmapShapes];
-    if (granules <= kBitmapGranules && largest <= kBitmapMaxSize && bitmap_plan_shapes(n, di, pool_words) &&
-        bitmap_shape(kModeBitmap, granules, pool_words) >= 0)
-        return (uint32_t)sizeof(uint32_t) | 0x300u;
-    if (granules < (1ull << 16) && t_end < 0x10000u &&
-        n <= lds_capacity_entries<uint32_t, kThreadsCompact>(di.lds_per_block / 2, sizeof(uint2)))
-        return (uint32_t)sizeof(uint2) | 0x100u;
-    if (granules < (1ull << 31) || largest < (1ull << 30)) {      // (the latter: tried plan by plan)
-        const bool lds = n <= lds_capacity_entries<uint32_t, kThreadsLds>(di.lds_per_block, entry_bytes<uint32_t>());
-        return (uint32_t)entry_bytes<uint32_t>() | (lds ? 0x100u : 0u) | (granules < (1ull << 31) ? 0u : 0x400u);
-    }
-    const bool lds = n <= lds_capacity_entries<uint64_t, kThreadsLds>(di.lds_per_block, entry_bytes<uint64_t>());
-    return (uint32_t)entry_bytes<uint64_t>() | (lds ? 0x100u : 0u);
 }
 
 extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uint32_t P, uint64_t* offsets,
@@ -735,7 +739,7 @@ extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uin
     }
     for (int shape = 0; shape < kBitmapShapes; ++shape) prm.bitmap_pool_words[shape] = bitmap ? pool_words[shape] : 0u;
     bool ok = true;
-    if (split) ok = ok && launch_plan_split(prm, sw, di, stream);
+    if (split) ok = ok && launch_plan_split(prm, tr->t_end, sw, di, stream);
     if (bitmap) ok = ok && launch_plan_bitmap(prm, di, stream);
     // exactly one of the launches does the work; the trace decides which (see the mode word)
     if (compact) ok = ok && launch_plan<uint32_t, true, true, kPendLds, kThreadsCompact>(prm, grid_compact, di, stream);

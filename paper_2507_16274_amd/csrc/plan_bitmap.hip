@@ -300,6 +300,7 @@ __global__ void __launch_bounds__(kWaves * kWave, kWaves == 8 ? 8 : 4) plan_bitm
     if (*prm.status != STALLOC_OK) return;
     if (bitmap_shape(prm.acc[kAccMode], prm.acc[kAccGranules], prm.bitmap_pool_words) != kShape) return;
     const uint32_t shift = (uint32_t)(prm.acc[kAccMode] & 63);
+    if (blockIdx.x == 0 && threadIdx.x == 0) const_cast<uint64_t*>(prm.acc)[kAccKernel] = STALLOC_KERNEL_BITMAP | (22u << 8);
     const uint32_t pool_words = prm.bitmap_pool_words[kShape];
     const uint32_t half_words = pool_words / 2;        // two batches are in flight, each in its half of the pool
     // the rule above keeps every address of a well-formed plan at or below `highest`; a malformed

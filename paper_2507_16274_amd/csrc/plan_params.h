@@ -62,7 +62,7 @@ struct SplitWorkspace {
     uint32_t slots, n_pad, grid;
 };
 size_t split_workspace(uint32_t n, const DeviceInfo& di, Carver& cv, SplitWorkspace* ws);
-bool launch_plan_split(const PlanParams& prm, const SplitWorkspace& ws, const DeviceInfo& di, hipStream_t stream);
+bool launch_plan_split(const PlanParams& prm, uint32_t t_end, const SplitWorkspace& ws, const DeviceInfo& di, hipStream_t stream);
 
 // Fills PlanParams::bitmap_pool_words for a trace of n requests; false if no shape fits.
 bool bitmap_plan_shapes(uint32_t n, const DeviceInfo& di, uint32_t (&pool_words)[kBitmapShapes]);

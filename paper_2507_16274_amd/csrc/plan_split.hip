@@ -36,9 +36,10 @@
 // longest chain of conflicts (mostly one or two).  The long blocks of a batch are merged into
 // the sorted list when the batch is done.
 //
-// theta is the smallest 2^c - 1 that leaves no more long requests than the LDS list holds; the
-// kernel takes the trace only if those are at most an eighth of all requests (else the
-// sorted-list kernel does).  Addresses are 32-bit granule counts, with the same plan-by-plan
+// theta = 2^c - 1 is chosen so that the long requests fit the LDS list and are at most an eighth
+// of all requests while the windows of the short ones stay narrow (sp_decide); traces for which
+// no such theta exists, or in which many short requests have wide windows all the same (dense or
+// tied timestamps), are left to the sorted-list kernel.  Addresses are 32-bit granule counts, with the same plan-by-plan
 // hand-over to the 64-bit sorted-list kernel as there.
 #include "host_util.h"
 #include "plan_list.h"
@@ -122,16 +123,26 @@ sp_histogram(const uint32_t* __restrict__ ta, const uint32_t* __restrict__ tf, u
     if (threadIdx.x < 32 && local[threadIdx.x]) atomicAdd(&hist[threadIdx.x], local[threadIdx.x]);
 }
 
+constexpr int kSpHistWords = 40;                 // 32 lifetime classes, then [32]: requests with a wide window
+constexpr int kSpHistWide = 32;
+
 __global__ void sp_clear_histogram(uint32_t* hist, uint32_t* gate)
 {
-    if (threadIdx.x < 32) hist[threadIdx.x] = 0;
+    if (threadIdx.x < kSpHistWords) hist[threadIdx.x] = 0;
     if (threadIdx.x == 0) *gate = 1;                                // closed until sp_decide opens it
 }
 
 // Decides whether this kernel places the trace, and with which theta; acc[kAccSplit] = 1 |
 // theta << 8 | long requests << 32 (0: another kernel does), gate[0] = 0 when it does (the
 // kernels that prepare its tables read the gate like a status word).
-__global__ void sp_decide(uint64_t* acc, const uint32_t* hist, uint32_t n, uint32_t list_cap,
+//
+// theta = 2^c - 1.  Fewer long-lived requests mean a shorter list, but a larger theta widens the
+// windows of the short-lived ones, which should fit the 64 lanes of a wave: with n allocations on
+// t_end timestamps a window of up to 2 theta timestamps holds about 2 theta n / t_end ranks, and c
+// is admissible while that stays below 48.  Among the admissible c that leave at most
+// min(list_cap, n / 8) long requests, the one with the fewest long requests is taken, and of
+// several such the smallest.
+__global__ void sp_decide(uint64_t* acc, const uint32_t* hist, uint32_t n, uint32_t t_end, uint32_t list_cap,
                           PlanParams prm, uint32_t* gate, const uint32_t* status)
 {
     if (threadIdx.x != 0) return;
@@ -141,16 +152,20 @@ __global__ void sp_decide(uint64_t* acc, const uint32_t* hist, uint32_t n, uint3
     if (!(mode & (kModeNarrow | kModeTry32))) return;
     if (bitmap_shape(mode, acc[kAccGranules], prm.bitmap_pool_words) >= 0) return;
     if ((mode & kModeCompact) && prm.compact_enqueued) return;
-    uint32_t longs = 0;
-    int c_sel = -1;
-    for (int c = 31; c >= 0; --c) {                                 // smallest c with #(lifetime >= 2^c) <= list_cap
-        if (longs + hist[c] > list_cap) break;
-        longs += hist[c];
-        c_sel = c;
-    }
-    if (c_sel < 1 || c_sel > kSpMaxThetaBits || (uint64_t)longs * 8 > n) return;
+    uint32_t at_least[33];                                          // requests with lifetime >= 2^c
+    at_least[32] = 0;
+    for (int c = 31; c >= 0; --c) at_least[c] = at_least[c + 1] + hist[c];
+    const uint32_t most = list_cap < n / 8 ? list_cap : n / 8;
+    int c_min = 1;
+    while (c_min <= kSpMaxThetaBits && at_least[c_min] > most) ++c_min;
+    if (c_min > kSpMaxThetaBits) return;
+    int c_best = c_min;
+    for (int c = c_min + 1; c <= kSpMaxThetaBits; ++c)
+        if (((1ull << c) - 1) * 2 * n <= 48ull * t_end) c_best = c;
+    int c_sel = c_best;
+    while (c_sel > c_min && at_least[c_sel - 1] == at_least[c_best]) --c_sel;
     const uint64_t theta = (1ull << c_sel) - 1;
-    acc[kAccSplit] = 1ull | (theta << 8) | ((uint64_t)longs << 32);
+    acc[kAccSplit] = 1ull | (theta << 8) | ((uint64_t)at_least[c_sel] << 32);
     *gate = 0;
 }
 
@@ -202,14 +217,33 @@ __device__ __forceinline__ uint32_t first_rank_at(const uint4* __restrict__ by_r
 // t_alloc_j >= t_free_j - theta > t_alloc_i - theta, so it lies in the window.
 __global__ void __launch_bounds__(256)
 sp_windows(const uint4* __restrict__ by_rank, const uint32_t* __restrict__ ta, const uint32_t* __restrict__ tf, uint32_t n,
-           const uint64_t* acc, uint2* window, const uint32_t* gate)
+           const uint64_t* acc, uint2* window, uint32_t* hist, const uint32_t* gate)
 {
     if (*gate != 0) return;
     const uint32_t theta = (uint32_t)((acc[kAccSplit] >> 8) & 0xffffffu);
+    uint32_t wide = 0;
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
         const uint32_t a = ta[i];
         const uint32_t from = a + 1 > theta ? a + 1 - theta : 0u;
-        window[i] = make_uint2(first_rank_at(by_rank, n, from), first_rank_at(by_rank, n, tf[i]));
+        const uint2 w = make_uint2(first_rank_at(by_rank, n, from), first_rank_at(by_rank, n, tf[i]));
+        window[i] = w;
+        wide += w.y - w.x > (uint32_t)kWave ? 1u : 0u;
+    }
+    wide = wave_sum32(wide);
+    if (lane_id() == 0 && wide) atomicAdd(&hist[kSpHistWide], wide);
+}
+
+// A request whose window is wider than a wave is settled by the whole workgroup, with look-ups
+// in the table for every step it moves up: affordable for the few long-lived requests this
+// kernel is meant for, not when timestamps are so dense (or tied) that short-lived requests
+// have such windows too.  Then the sorted-list kernel places the trace after all.
+__global__ void sp_confirm(uint64_t* acc, const uint32_t* hist, uint32_t n, uint32_t* gate)
+{
+    if (threadIdx.x != 0 || *gate != 0) return;
+    const uint32_t longs = (uint32_t)(acc[kAccSplit] >> 32);
+    if ((uint64_t)hist[kSpHistWide] > 2ull * longs + 64 || (uint64_t)hist[kSpHistWide] * 8 > n) {
+        acc[kAccSplit] = 0;
+        *gate = 1;
     }
 }
 
@@ -423,6 +457,7 @@ __global__ void __launch_bounds__(kThreads, 2) plan_split_kernel(PlanParams prm,
     const bool try32 = (mode & kModeTry32) != 0;
     const uint32_t shift = (uint32_t)(mode & 63);
     const int lane = lane_id(), wave = wave_id();
+    if (blockIdx.x == 0 && threadIdx.x == 0) const_cast<uint64_t*>(prm.acc)[kAccKernel] = STALLOC_KERNEL_LONG_LIST | (32u << 8);
     // the requests of a batch this wave settles: positions wave, wave + kWaves, ...
     uint64_t stripe = 0;
     for (int e = wave; e < kSpBatch; e += kWaves) stripe |= 1ull << e;
@@ -614,7 +649,7 @@ size_t split_workspace(uint32_t n, const DeviceInfo& di, Carver& cv, SplitWorksp
     const uint32_t n_pad = (n + kSortTile - 1) / kSortTile * kSortTile;
     const uint32_t slots = (n + kWave - 1) / kWave * kWave + kWave;
     uint32_t grid = (uint32_t)di.cus * 2;
-    ws->hist = cv.take<uint32_t>(32);
+    ws->hist = cv.take<uint32_t>(kSpHistWords);
     ws->gate = cv.take<uint32_t>(1);
     ws->keys = cv.take<ulonglong2>(n_pad);
     ws->spare = cv.take<ulonglong2>(n_pad);
@@ -631,7 +666,7 @@ size_t split_workspace(uint32_t n, const DeviceInfo& di, Carver& cv, SplitWorksp
     return cv.used;
 }
 
-bool launch_plan_split(const PlanParams& prm, const SplitWorkspace& ws, const DeviceInfo& di, hipStream_t stream)
+bool launch_plan_split(const PlanParams& prm, uint32_t t_end, const SplitWorkspace& ws, const DeviceInfo& di, hipStream_t stream)
 {
     const uint32_t n = prm.n;
     const size_t lds = di.lds_per_block / 2;                          // two workgroups per CU
@@ -643,13 +678,14 @@ bool launch_plan_split(const PlanParams& prm, const SplitWorkspace& ws, const De
     hipLaunchKernelGGL(sp_clear_histogram, dim3(1), dim3(64), 0, stream, ws.hist, ws.gate);
     hipLaunchKernelGGL(sp_histogram, dim3(blocks > 256 ? 256 : blocks), dim3(256), 0, stream, prm.ta, prm.tf, n, ws.hist,
                        prm.status);
-    hipLaunchKernelGGL(sp_decide, dim3(1), dim3(64), 0, stream, acc, ws.hist, n, list_cap, prm, ws.gate, prm.status);
+    hipLaunchKernelGGL(sp_decide, dim3(1), dim3(64), 0, stream, acc, ws.hist, n, t_end, list_cap, prm, ws.gate, prm.status);
     hipLaunchKernelGGL(sp_sort_tiles, dim3(ws.n_pad / kSortTile), dim3(kSortTile), 0, stream, prm.ta, n, ws.keys, ws.gate);
     const ulonglong2* sorted = launch_merge_tiles(ws.keys, ws.spare, ws.n_pad, 1, ws.gate, stream);
     hipLaunchKernelGGL(sp_tables, dim3(blocks), dim3(256), 0, stream, sorted, prm.size, prm.ta, prm.tf, n, ws.slots, prm.acc,
                        ws.by_rank, ws.size_by_rank, ws.rank_of, ws.gate);
     hipLaunchKernelGGL(sp_windows, dim3(blocks), dim3(256), 0, stream, ws.by_rank, prm.ta, prm.tf, n, prm.acc, ws.window,
-                       ws.gate);
+                       ws.hist, ws.gate);
+    hipLaunchKernelGGL(sp_confirm, dim3(1), dim3(64), 0, stream, acc, ws.hist, n, ws.gate);
 
     SplitTables tb;
     tb.by_rank = ws.by_rank; tb.size_by_rank = ws.size_by_rank; tb.rank_of = ws.rank_of; tb.window = ws.window;

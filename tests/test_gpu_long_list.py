@@ -1,0 +1,192 @@
+"""Parity of the placement kernel that keeps only long-lived blocks in its sorted list (long traces
+with few long-lived requests) with the CPU oracle, through the C ABI: every address, bit by bit."""
+import os
+
+import numpy as np
+import pytest
+
+from workloads import Trace
+
+pytestmark = pytest.mark.gpu
+
+THREADS = min(16, os.cpu_count() or 1)
+
+
+@pytest.fixture(scope="module")
+def S():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2507_16274_amd as S
+    return S
+
+
+def _plan(S, tr, orders):
+    import torch
+    size, ta, tf = S.trace_to_device(tr)
+    o = torch.from_numpy(np.ascontiguousarray(orders).view(np.int32)).cuda()
+    out = S.stalloc_plan(size, ta, tf, tr.t_end, o)
+    torch.cuda.synchronize()
+    info = S.stalloc_plan_report(out)
+    return {"status": int(out["status"].item()), "offsets": out["offsets"].cpu().numpy().view(np.uint64),
+            "peaks": out["peaks"].cpu().numpy().view(np.uint64), "best_plan": int(out["best_plan"].item()),
+            "best_offsets": out["best_offsets"].cpu().numpy().view(np.uint64), "info": info, "raw": out}
+
+
+def _validate(S, tr, offsets_dev):
+    import torch
+    size, ta, tf = S.trace_to_device(tr)
+    out = S.stalloc_validate(size, ta, tf, tr.t_end, offsets_dev)
+    torch.cuda.synchronize()
+    assert int(out["status"].item()) == 0
+    return out["conflicts"].cpu().numpy().view(np.uint64)
+
+
+def two_kinds(rng, n, n_long, short_life, sizes_long, sizes_short, quantum=1, long_span=(8, 2)):
+    """n requests on 2n distinct timestamps; n_long of them live for an eighth to a half of the trace, the
+    others for 1..short_life timestamps; `quantum` timestamps share one recorded instant."""
+    T = 2 * n
+    ts = rng.permutation(T)[:n].astype(np.int64)
+    life = rng.integers(1, short_life + 1, n)
+    long_ids = rng.choice(n, n_long, replace=False)
+    life[long_ids] = rng.integers(T // long_span[0], T // long_span[1], n_long)
+    te = np.minimum(ts + life, T)
+    size = rng.choice(np.asarray(sizes_short, dtype=np.uint64), n)
+    size[long_ids] = rng.choice(np.asarray(sizes_long, dtype=np.uint64), n_long)
+    ts //= quantum
+    te = np.maximum(te // quantum, ts + 1)
+    return Trace(name="two kinds", size=size, t_alloc=ts.astype(np.uint32), t_free=te.astype(np.uint32),
+                 t_end=int(te.max()))
+
+
+def _orders(rng, tr, random_rows):
+    n = tr.n
+    rows = [np.argsort(-tr.size.astype(np.int64), kind="stable"),                      # all long blocks first
+            np.lexsort((np.arange(n), tr.t_alloc)),                                      # by time: one long chain of waits
+            np.lexsort((np.arange(n), -(tr.t_free.astype(np.int64) - tr.t_alloc)))]
+    rows += [rng.permutation(n) for _ in range(random_rows)]
+    return np.stack(rows).astype(np.uint32)
+
+
+def _compare(S, oracle, tr, orders, want_kernel="long_list", method="allpairs", lists=None):
+    got = _plan(S, tr, orders)
+    assert got["status"] == 0
+    assert got["info"]["kernel"] == want_kernel, got["info"]
+    a, ext = oracle.plan_many(tr.size, tr.t_alloc, tr.t_free, orders, threads=THREADS, method=method, lists=lists)
+    assert np.array_equal(got["peaks"], ext), "extents differ"
+    bad = np.nonzero((got["offsets"] != a).any(axis=1))[0]
+    assert bad.size == 0, f"addresses differ in plans {bad[:8]}"
+    assert got["best_plan"] == oracle.best_plan(ext)
+    assert np.array_equal(got["best_offsets"], a[got["best_plan"]])
+    return got, a, ext
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_traces_of_two_kinds(S, oracle, seed):
+    """Sizes in 512-byte units and odd byte sizes (32-bit granule counts tried plan by plan), with and
+    without tied timestamps, lifetime thresholds from 1 to 31, 50 to 1100 long-lived requests."""
+    rng = np.random.default_rng(8800 + seed)
+    n = int(rng.integers(9500, 14000))
+    assert n > S.lib.stalloc_plan_lds_capacity()
+    odd = seed % 4 == 3
+    sizes_long = [1 << 20, 3 << 20, 5 << 19] if not odd else [1048577, 3145731, 2621443]
+    sizes_short = [512, 1024, 4096, 1 << 16, 3 << 9] if not odd else [513, 1025, 4099, 65537, 1537, 999_999]
+    quantum = int(rng.choice([1, 1, 2]))
+    short_life = int(rng.choice([3, 7, 15, 31] if quantum == 1 else [3, 7, 15]))     # windows of short requests fit a wave
+    n_long = int(rng.integers(50, 1100))
+    tr = two_kinds(rng, n, n_long, short_life, sizes_long, sizes_short, quantum=quantum)
+    got, a, ext = _compare(S, oracle, tr, _orders(rng, tr, 3))
+    assert got["info"]["lifetime_threshold"] in (1, 3, 7, 15, 31) and n_long - 8 <= got["info"]["long_requests"] <= n_long      # (a lifetime cut at the end of the trace may be short)
+    assert got["info"]["granule_log2"] == (0 if odd else 9)
+
+
+def test_crowded_short_lived_requests_overflow_the_window_pool(S, oracle):
+    """Short lifetimes of up to 31 timestamps: late in an order a request finds some twenty placed
+    short blocks in its window, more than the LDS pool of a batch holds for all 64 requests; the windows
+    that do not fit are read again when their request is settled."""
+    rng = np.random.default_rng(31)
+    tr = two_kinds(rng, 10240, 400, 31, [1 << 22, 1 << 23], [512, 1536, 2048, 8192])
+    _compare(S, oracle, tr, _orders(rng, tr, 2))
+
+
+def test_bursts_give_some_short_lived_requests_wide_windows(S, oracle):
+    """Ninety short-lived requests allocated at one instant, twice: their windows hold more ranks than
+    a wave has lanes, so they are settled by the whole workgroup like the long-lived ones."""
+    rng = np.random.default_rng(77)
+    tr = two_kinds(rng, 9800, 300, 7, [1 << 21, 3 << 20], [512, 1024, 2560])
+    ts, te = tr.t_alloc.astype(np.int64), tr.t_free.astype(np.int64)
+    short = np.nonzero(te - ts <= 7)[0]
+    for burst, at in ((short[:90], 5000), (short[90:180], 12001)):
+        life = te[burst] - ts[burst]
+        ts[burst] = at
+        te[burst] = at + life
+    tr = Trace(name="bursts", size=tr.size, t_alloc=ts.astype(np.uint32), t_free=te.astype(np.uint32), t_end=int(te.max()))
+    _compare(S, oracle, tr, _orders(rng, tr, 3))
+
+
+def test_more_orders_than_resident_workgroups(S, oracle):
+    """1100 orders (two workgroups per CU are resident): sampled plans address by address, every plan
+    free of conflicts, every extent at least the lower bound."""
+    import torch
+    rng = np.random.default_rng(5)
+    tr = two_kinds(rng, 9600, 250, 15, [1 << 20, 1 << 21], [512, 1024, 16384])
+    P = 1100
+    orders = np.stack([rng.permutation(tr.n) for _ in range(P)]).astype(np.uint32)
+    got = _plan(S, tr, orders)
+    assert got["status"] == 0 and got["info"]["kernel"] == "long_list"
+    rows = np.r_[0, 1, 2, np.arange(17, P, 64), P - 1]
+    lists = oracle.conflict_lists(tr.t_alloc, tr.t_free)
+    a, ext = oracle.plan_many(tr.size, tr.t_alloc, tr.t_free, orders[rows], threads=THREADS, method="lists", lists=lists)
+    assert np.array_equal(got["peaks"][rows], ext) and np.array_equal(got["offsets"][rows], a)
+    assert not _validate(S, tr, got["raw"]["offsets"]).any()
+    lb = oracle.lower_bound(tr.size, tr.t_alloc, tr.t_free, tr.t_end)[0]
+    assert (got["peaks"] >= lb).all() and got["best_plan"] == int(np.argmin(got["peaks"]))
+
+
+@pytest.mark.parametrize("fill", [0.80, 0.97, 1.04])
+def test_plans_that_outgrow_32_bit_counts_are_placed_again(S, oracle, fill):
+    """Odd byte sizes, 300 long-lived requests that all overlap and stack up to `fill` x 2^32 bytes, and
+    ten thousand short-lived ones: depending on `fill` none, some or all plans come too close to 2^32
+    granules and are handed to the kernel with 64-bit addresses."""
+    rng = np.random.default_rng(2032)
+    n_long, n = 300, 10300
+    tr = two_kinds(rng, n, n_long, 15, [1], [1537, 4099, 70001], long_span=(3, 2))
+    size = tr.size.copy()
+    ts, te = tr.t_alloc.astype(np.int64), tr.t_free.astype(np.int64)
+    long_ids = np.nonzero(te - ts > 15)[0]
+    ts[long_ids] = rng.integers(0, 1000, n_long)                     # all long-lived requests overlap around the middle
+    te[long_ids] = tr.t_end - rng.integers(0, 1000, n_long)
+    raw = rng.integers(1 << 22, 3 << 22, n_long).astype(np.float64)
+    size[long_ids] = (raw * (fill * 2 ** 32 / raw.sum())).astype(np.uint64) | np.uint64(1)
+    tr = Trace(name="near 2^32", size=size, t_alloc=ts.astype(np.uint32), t_free=te.astype(np.uint32), t_end=tr.t_end)
+    orders = np.stack([rng.permutation(n) for _ in range(6)]).astype(np.uint32)
+    got, a, ext = _compare(S, oracle, tr, orders)
+    assert got["info"]["granule_log2"] == 0
+    redone = got["info"]["plans_64bit"]
+    assert (fill < 0.9 and redone == 0) or (0.9 < fill < 1.0) or (fill > 1.0 and redone == 6), redone
+    assert bool((ext > np.uint64(2 ** 32)).all()) == (fill > 1.0)
+
+
+def test_traces_the_kernel_leaves_to_the_sorted_list(S, oracle):
+    """Too many long-lived requests for the LDS list, and timestamps so coarse that every window is
+    wide: the sorted-list kernel places these; results equal the oracle's all the same."""
+    rng = np.random.default_rng(404)
+    many_long = two_kinds(rng, 10000, 4000, 15, [1 << 20], [512, 4096])
+    coarse = two_kinds(rng, 10000, 200, 15, [1 << 20], [512, 4096], quantum=400)
+    for tr in (many_long, coarse):
+        _compare(S, oracle, tr, _orders(rng, tr, 1)[[0, 3]], want_kernel="list_memory")
+
+
+def test_malformed_orders_end_normally(S):
+    """An entry beyond n is reported; a row that repeats requests gives an unspecified plan, but the
+    call ends and stays inside its buffers."""
+    rng = np.random.default_rng(9)
+    tr = two_kinds(rng, 9700, 200, 15, [1 << 20], [512, 4096])
+    orders = np.stack([rng.permutation(tr.n) for _ in range(2)]).astype(np.uint32)
+    bad = orders.copy()
+    bad[1, 100] = tr.n + 7
+    assert _plan(S, tr, bad)["status"] == 6
+    repeated = orders.copy()
+    long_ids = np.nonzero(tr.t_free.astype(np.int64) - tr.t_alloc > 15)[0]
+    repeated[0, :] = np.resize(long_ids, tr.n)                         # 9700 long blocks for a list of a few thousand
+    got = _plan(S, tr, repeated)
+    assert got["status"] == 0 and got["info"]["kernel"] == "long_list"

@@ -33,7 +33,7 @@ def _gpu_plan(S, tr, orders, **kw):
     o = torch.from_numpy(np.ascontiguousarray(orders).view(np.int32)).cuda()
     out = S.stalloc_plan(size, ta, tf, tr.t_end, o, **kw)
     torch.cuda.synchronize()
-    res = {"status": int(out["status"].item())}
+    res = {"status": int(out["status"].item()), "info": S.stalloc_plan_report(out)}
     if res["status"] == 0:
         res["peaks"] = out["peaks"].cpu().numpy().view(np.uint64)
         res["best_plan"] = int(out["best_plan"].item())
@@ -230,13 +230,6 @@ def test_plan_closed_forms(S):
     assert not got["offsets"].any() and int(got["peaks"][0]) == int(size.max())
 
 
-def _layout(S, tr):
-    """How stalloc_plan stores a plan's blocks for this trace (same rule as on the device)."""
-    bits = int(np.bitwise_or.reduce(tr.size))
-    g = bits & -bits
-    return int(S.lib.stalloc_plan_list_layout(len(tr.size), tr.t_end, int(tr.size.sum()) // g, int(tr.size.max()) // g))
-
-
 def _nudge_to_sum(sizes, total, lo, hi, keep=()):
     """Moves entries (not those in `keep`) one by one within [lo, hi] until the sum is `total`."""
     sizes = sizes.copy()
@@ -264,9 +257,9 @@ def test_plan_bitmap_full_address_range(S):
     n = len(sizes)
     size = (sizes * g).astype(np.uint64)
     clique = _T(size, np.zeros(n, np.uint32), np.full(n, 5, np.uint32), 5)
-    assert _layout(S, clique) & 0x200, "expected the bitmap variant"
     order = rng.permutation(n).astype(np.uint32)[None, :]
     got = _gpu_plan(S, clique, order)
+    assert got["info"]["kernel"] == "bitmap"
     expect = np.zeros(n, np.uint64)
     expect[order[0]] = np.concatenate([[0], np.cumsum(size[order[0]])[:-1]]).astype(np.uint64)
     assert np.array_equal(got["offsets"][0], expect) and int(got["peaks"][0]) == 32704 * g
@@ -284,10 +277,10 @@ def test_plan_bitmap_applicability_limits(S, oracle, n, largest, total, bitmap):
     assert int(sizes.sum()) == total and sizes.max() == largest
     _, ts, te, t_end = random_trace(rng, n, t_max=400)
     tr = _T((sizes * 4096).astype(np.uint64), ts, te, t_end)
-    assert bool(_layout(S, tr) & 0x200) == bitmap
     orders = np.stack([rng.permutation(n) for _ in range(5)]).astype(np.uint32)
     orders[0] = np.argsort(-sizes, kind="stable")
-    _compare_plans(S, oracle, tr, orders, method="allpairs")
+    got, _, _ = _compare_plans(S, oracle, tr, orders, method="allpairs")
+    assert (got["info"]["kernel"] == "bitmap") == bitmap
 
 
 def test_plan_bitmap_tall_plans_small_pool(S, oracle):
@@ -303,10 +296,10 @@ def test_plan_bitmap_tall_plans_small_pool(S, oracle):
     short = rng.random(n) < 0.2                         # a fifth lives briefly: holes open up under the rest
     te[short] = ts[short] + rng.integers(1, 4, int(short.sum()))
     tr = _T((sizes * 65536).astype(np.uint64), ts.astype(np.uint32), te.astype(np.uint32), int(te.max()))
-    assert _layout(S, tr) & 0x200, "expected the bitmap variant"
     orders = np.stack([rng.permutation(n) for _ in range(3)]).astype(np.uint32)
     orders[0] = np.argsort(-sizes, kind="stable")
     got, a, ext = _compare_plans(S, oracle, tr, orders, method="allpairs")
+    assert got["info"]["kernel"] == "bitmap"
     assert int(ext.max()) // 65536 > 20000
 
 
@@ -314,42 +307,27 @@ def test_plan_config3_sampled_orderings(S, oracle):
     """Config 3 (19 840 requests, 86 748 granules: bitmap variant, one workgroup per CU): sampled
     orders, every address compared."""
     tr = make_trace(3)
-    assert _layout(S, tr) & 0x200
     rows = [0, 1, 2, 3, 4, 1025, 2046, 2047]
     orders = make_orderings(tr, CONFIGS[3].n_orderings, rows=rows)
     lists = oracle.conflict_lists(tr.t_alloc, tr.t_free)
     got, a, ext = _compare_plans(S, oracle, tr, orders, method="lists", lists=lists)
+    assert got["info"]["kernel"] == "bitmap"
     cnt, _ = _gpu_validate(S, tr, got["offsets"])
     assert not cnt.any()
 
 
-def test_plan_config3_full_launch_every_eighth_ordering(S, oracle):
-    """All 2048 orders of config 3 in one call, as the benchmark launches them (more orders than resident
-    workgroups); every eighth plan compared address by address, and all extents are at least the lower
-    bound.  (All 2048 were compared once by hand: equal.)"""
-    import torch
-    tr = make_trace(3)
-    P = CONFIGS[3].n_orderings
-    orders = make_orderings(tr, P)
-    got = _gpu_plan(S, tr, orders)
-    assert got["status"] == 0
-    rows = np.arange(0, P, 8)
-    lists = oracle.conflict_lists(tr.t_alloc, tr.t_free)
-    a, ext = oracle.plan_many(tr.size, tr.t_alloc, tr.t_free, orders[rows], threads=THREADS, method="lists", lists=lists)
-    assert np.array_equal(got["peaks"][rows], ext)
-    assert np.array_equal(got["offsets"][rows], a)
-    status, lb, _ = _gpu_lower_bound(S, tr)
-    assert status == 0 and (got["peaks"] >= lb).all()
-    assert int(got["best_plan"]) == int(np.argmin(got["peaks"]))
+_FULL = {}       # configuration -> what its full launch gave (kept between the parts of a test)
 
 
-@pytest.mark.parametrize("cfg,P,rows", [(4, 2048, [5, 2040]), (5, 512, [1, 510])])
-def test_plan_large_configs_full_launches(S, oracle, cfg, P, rows):
-    """Config 4 with all its 2048 orders and config 5 with 512 (every resident workgroup busy, several
-    orders per workgroup on config 4), the orders made on the device: sampled plans compared address by
-    address, every plan checked for conflicts over all pairs, every extent at least the lower bound."""
+def _full_launch(S, cfg):
+    """All orders of a configuration in one call, as the benchmark launches them: the orders made on the
+    device, every plan checked over all pairs by stalloc_validate, the lower bound beside them."""
     import torch
+    if cfg in _FULL:
+        return _FULL[cfg]
+    _FULL.clear()                                             # one configuration's arrays at a time
     tr = make_trace(cfg)
+    P = CONFIGS[cfg].n_orderings
     size, ta, tf = S.trace_to_device(tr)
     made = S.stalloc_make_orders(size, ta, tf, tr.t_end, P)
     plan = S.stalloc_plan(size, ta, tf, tr.t_end, made["orders"], want_best_offsets=False)
@@ -357,16 +335,60 @@ def test_plan_large_configs_full_launches(S, oracle, cfg, P, rows):
     lb = S.stalloc_lower_bound(size, ta, tf, tr.t_end)
     torch.cuda.synchronize()
     assert [int(x["status"].item()) for x in (made, plan, val, lb)] == [0, 0, 0, 0]
-    assert not val["conflicts"].cpu().numpy().any()
-    peaks = plan["peaks"].cpu().numpy().view(np.uint64)
-    assert (peaks >= np.uint64(int(lb["lower_bound"].item()))).all()
-    assert int(plan["best_plan"].item()) == int(np.argmin(peaks))
-    orders = made["orders"][rows].cpu().numpy().view(np.uint32)
-    assert np.array_equal(orders, make_orderings(tr, CONFIGS[cfg].n_orderings, rows=rows))
+    res = {"tr": tr, "P": P, "made": made, "plan": plan, "info": S.stalloc_plan_report(plan),
+           "conflicts": val["conflicts"].cpu().numpy().view(np.uint64),
+           "peaks": plan["peaks"].cpu().numpy().view(np.uint64), "best_plan": int(plan["best_plan"].item()),
+           "lower_bound": int(lb["lower_bound"].item())}
+    _FULL[cfg] = res
+    return res
+
+
+def _compare_rows_of_full_launch(S, oracle, cfg, rows):
+    full = _full_launch(S, cfg)
+    tr, P = full["tr"], full["P"]
+    assert not full["conflicts"].any()
+    assert (full["peaks"] >= np.uint64(full["lower_bound"])).all()
+    assert full["best_plan"] == int(np.argmin(full["peaks"]))
+    rows = np.asarray(rows)
+    orders = full["made"]["orders"][rows].cpu().numpy().view(np.uint32)
+    assert np.array_equal(orders[:4], make_orderings(tr, P, rows=rows[:4]))       # the rows the host would make
     lists = oracle.conflict_lists(tr.t_alloc, tr.t_free)
     a, ext = oracle.plan_many(tr.size, tr.t_alloc, tr.t_free, orders, threads=THREADS, method="lists", lists=lists)
-    assert np.array_equal(peaks[rows], ext)
-    assert np.array_equal(plan["offsets"][rows].cpu().numpy().view(np.uint64), a)
+    assert np.array_equal(full["peaks"][rows], ext)
+    got = full["plan"]["offsets"][rows].cpu().numpy().view(np.uint64)
+    bad = np.nonzero((got != a).any(axis=1))[0]
+    assert bad.size == 0, f"addresses differ in plans {rows[bad][:8]}"
+    return full
+
+
+@pytest.mark.parametrize("part", range(4))
+def test_plan_config3_full_launch_every_ordering(S, oracle, part):
+    """All 2048 orders of config 3 in one call (more orders than resident workgroups), every plan
+    compared with the oracle address by address, 512 plans per part of this test."""
+    full = _compare_rows_of_full_launch(S, oracle, 3, np.arange(512 * part, 512 * (part + 1)))
+    assert full["info"]["kernel"] == "bitmap"
+
+
+def _stratified(P):
+    """Rows 0, 1, 2 and every ceil(P / 64)-th row."""
+    return np.unique(np.r_[0, 1, 2, np.arange(0, P, -(-P // 64))])
+
+
+def test_plan_config4_full_launch_stratified_orderings(S, oracle):
+    """Config 4 (47 748 requests, 1229 distinct sizes) with all its 2048 orders: rows 0-2 and every 32nd
+    row compared address by address, every plan of the launch checked for conflicts over all pairs."""
+    full = _compare_rows_of_full_launch(S, oracle, 4, _stratified(2048))
+    assert full["info"]["kernel"] == "list_memory" and full["info"]["plans_64bit"] == 0
+
+
+@pytest.mark.parametrize("half", range(2))
+def test_plan_config5_full_launch_stratified_orderings(S, oracle, half):
+    """Config 5 (199 748 requests) with all its 4096 orders in one call: rows 0-2 and every 64th row
+    compared address by address (in two halves), all 4096 plans checked over all n(n-1)/2 pairs."""
+    rows = _stratified(4096)
+    full = _compare_rows_of_full_launch(S, oracle, 5, rows[half::2])
+    assert full["info"]["kernel"] == "long_list" and full["info"]["plans_64bit"] == 0
+    assert full["info"]["lifetime_threshold"] == 15 and full["info"]["long_requests"] == 4271
 
 
 @pytest.mark.parametrize("n_clique,n_extra,unit,fill", [(230, 70, 1 << 24, 0.80), (230, 70, 1 << 24, 0.875),
@@ -387,28 +409,16 @@ def test_plan_32_bit_counts_tried_plan_by_plan(S, oracle, n_clique, n_extra, uni
     te = np.concatenate([np.full(n_clique, 100, np.int64), ts[n_clique:] + rng.integers(1, 40, n_extra)])
     n = n_clique + n_extra
     tr = Trace(name="near 2^32", size=size, t_alloc=ts.astype(np.uint32), t_free=te.astype(np.uint32), t_end=int(te.max()))
-    layout = _layout(S, tr)
-    assert layout & 0xff == 16 and layout & 0x400 and bool(layout & 0x100) == (n < 5000)
     rng = np.random.default_rng(9)
     orders = np.stack([rng.permutation(n) for _ in range(12 if n < 5000 else 6)]).astype(np.uint32)
     got, a, ext = _compare_plans(S, oracle, tr, orders, method="allpairs")
+    info = got["info"]
+    assert info["kernel"] == ("list_lds" if n < 5000 else "list_memory") and info["address_bits"] == 32
+    assert info["granule_log2"] == 0 and info["granules"] >= 2 ** 31          # 32-bit counts are tried plan by plan
     above = int((ext > np.uint64(2 ** 32)).sum())
     assert (fill < 0.87 and above == 0) or (fill > 0.88 and above > 0) or 0.87 <= fill <= 0.88 or n > 5000
     cnt, _ = _gpu_validate(S, tr, got["offsets"])
     assert not cnt.any()
-
-
-def test_plan_config4_sampled_orderings(S, oracle):
-    """MoE trace (47 748 requests, 1229 distinct sizes): heuristic rows and sampled random rows."""
-    tr = make_trace(4)
-    rows = [0, 1, 2, 3, 1024, 2047]
-    orders = make_orderings(tr, CONFIGS[4].n_orderings, rows=rows)
-    lists = oracle.conflict_lists(tr.t_alloc, tr.t_free)
-    got, a, ext = _compare_plans(S, oracle, tr, orders, method="lists", lists=lists)
-    cnt, _ = _gpu_validate(S, tr, got["offsets"])
-    assert not cnt.any()
-    status, lb, _ = _gpu_lower_bound(S, tr)
-    assert (got["peaks"] >= lb).all()
 
 
 def test_plan_second_workload_sampled_orderings(S, oracle):
@@ -421,7 +431,7 @@ def test_plan_second_workload_sampled_orderings(S, oracle):
         lists = oracle.conflict_lists(tr.t_alloc, tr.t_free)
         got, a, ext = _compare_plans(S, oracle, tr, orders, method="lists", lists=lists)
         del lists
-        assert (_layout(S, tr) & 0x200 != 0) == (cfg == 6)
+        assert got["info"]["kernel"] == ("bitmap" if cfg == 6 else "list_memory")
         cnt, _ = _gpu_validate(S, tr, got["offsets"])
         assert not cnt.any()
         status, lb, t_at = _gpu_lower_bound(S, tr)
@@ -429,15 +439,14 @@ def test_plan_second_workload_sampled_orderings(S, oracle):
         assert (int(lb), int(t_at)) == oracle.lower_bound(tr.size, tr.t_alloc, tr.t_free, tr.t_end)
 
 
-def test_plan_config5_sampled_orderings(S, oracle):
-    """Largest trace (199 748 requests, 64-bit addresses): sampled rows compared address by address,
-    the best of them validated over all n(n-1)/2 pairs, and a corrupted copy against the oracle's count."""
+def test_validate_config5_best_plan_and_a_corrupted_copy(S, oracle):
+    """Largest trace: the best of a few plans validated over all n(n-1)/2 pairs, and a corrupted copy
+    against the oracle's count and first pair."""
     tr = make_trace(5)
-    rows = [0, 2, 3, 4094]
+    rows = [0, 3]
     orders = make_orderings(tr, CONFIGS[5].n_orderings, rows=rows)
-    lists = oracle.conflict_lists(tr.t_alloc, tr.t_free)
-    got, a, ext = _compare_plans(S, oracle, tr, orders, method="lists", lists=lists)
-    del lists
+    got = _gpu_plan(S, tr, orders)
+    assert got["status"] == 0
     best = got["best_offsets"][None, :]
     cnt, pair = _gpu_validate(S, tr, best)
     assert int(cnt[0]) == 0 and tuple(int(x) for x in pair[0]) == NONE_PAIR
@@ -461,10 +470,10 @@ def test_plan_list_beyond_lds(S, oracle, wide):
     if wide:
         size = size * np.uint64(2 ** 31 + 7) + np.uint64(1)
     tr = _T(size, ts, te, t_end)
-    assert _layout(S, tr) == (24 if wide else 16)          # sorted list in the workspace
     orders = np.stack([rng.permutation(n) for _ in range(4)]).astype(np.uint32)
     orders[0] = np.argsort(-size.astype(np.int64), kind="stable")
-    _compare_plans(S, oracle, tr, orders, method="lists")
+    got, _, _ = _compare_plans(S, oracle, tr, orders, method="lists")
+    assert got["info"]["kernel"] == "list_memory" and got["info"]["address_bits"] == (64 if wide else 32)
 
 
 @pytest.mark.parametrize("sizes", [[1, 2, 3, 4], [1, 2, 3, 40]])
@@ -475,10 +484,10 @@ def test_plan_more_orders_than_resident_workgroups(S, oracle, sizes):
     n = 150
     size, ts, te, t_end = random_trace(rng, n, t_max=60, sizes=sizes)
     tr = _T(size * np.uint64(1024), ts, te, t_end)
-    assert bool(_layout(S, tr) & 0x200) == (max(sizes) <= 31)
     P = 5000
     orders = np.stack([rng.permutation(n) for _ in range(P)]).astype(np.uint32)
-    _compare_plans(S, oracle, tr, orders, method="allpairs")
+    got, _, _ = _compare_plans(S, oracle, tr, orders, method="allpairs")
+    assert (got["info"]["kernel"] == "bitmap") == (max(sizes) <= 31)
 
 
 def test_plan_reports_malformed_inputs(S):

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 def test_status_strings():
     import paper_2507_16274_amd as S
     text = open(os.path.join(ROOT, "include", "stalloc.h")).read()
-    for name, value in re.findall(r"(STALLOC_[A-Z_]+)\s*=\s*(\d+)", text):
+    for name, value in re.findall(r"(STALLOC_(?:OK|ERR_[A-Z_]+))\s*=\s*(\d+)", text):
         assert S.lib.stalloc_status_string(int(value)).decode() == name
         assert S.STATUS[int(value)] == name
     assert S.lib.stalloc_status_string(99).decode() == "STALLOC_UNKNOWN_STATUS"

@@ -2,6 +2,7 @@
 hand-worked fixtures, closed forms, Algorithm 1's layer count, exhaustive and
 exact searches on tiny traces, and re-derivations written with numpy only."""
 import itertools
+import os
 
 import numpy as np
 import pytest
@@ -228,8 +229,27 @@ def test_lists_equal_allpairs_on_configs(oracle):
     rows = [0, 1, 2, 3, 4, 513, 1022, 1023]
     orders = make_orderings(tr, 1024, rows=rows)
     a1, e1 = oracle.plan_many(tr.size, tr.t_alloc, tr.t_free, orders, threads=4, method="allpairs")
-    a2, e2 = oracle.plan_many(tr.size, tr.t_alloc, tr.t_free, orders, threads=4, method="lists")
-    assert np.array_equal(a1, a2) and np.array_equal(e1, e2)
     for k in range(len(rows)):
         assert count_conflicts_fast(tr.size, tr.t_alloc, tr.t_free, a1[k]) == 0
         assert int(e1[k]) == int((a1[k] + tr.size).max())
+
+
+def test_lists_equal_allpairs_on_every_order_of_config_2_and_sampled_orders_of_config_3(oracle):
+    """The conflict-list oracle, which the comparisons on the larger configurations rest on, against the
+    all-pairs oracle: all 1024 orders of config 2, and eight orders of config 3 (the three heuristic
+    rows, uniform permutations and rows sorted by size with jitter)."""
+    threads = min(8, os.cpu_count() or 1)
+    tr = make_trace(2)
+    orders = make_orderings(tr, 1024)
+    lists = oracle.conflict_lists(tr.t_alloc, tr.t_free)
+    for r0 in range(0, 1024, 256):                      # in four parts: 50 MB of addresses at a time
+        part = orders[r0:r0 + 256]
+        a1, e1 = oracle.plan_many(tr.size, tr.t_alloc, tr.t_free, part, threads=threads, method="allpairs")
+        a2, e2 = oracle.plan_many(tr.size, tr.t_alloc, tr.t_free, part, threads=threads, method="lists", lists=lists)
+        assert np.array_equal(a1, a2) and np.array_equal(e1, e2), f"rows {r0}..{r0 + 255}"
+    tr = make_trace(3)
+    rows = [0, 1, 2, 3, 4, 1025, 2046, 2047]
+    orders = make_orderings(tr, 2048, rows=rows)
+    a1, e1 = oracle.plan_many(tr.size, tr.t_alloc, tr.t_free, orders, threads=threads, method="allpairs")
+    a2, e2 = oracle.plan_many(tr.size, tr.t_alloc, tr.t_free, orders, threads=threads, method="lists")
+    assert np.array_equal(a1, a2) and np.array_equal(e1, e2)
