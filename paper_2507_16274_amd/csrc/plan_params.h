@@ -59,6 +59,7 @@ struct SplitWorkspace {
     uint32_t* addr;
     uint64_t* group_bins;
     uint64_t* region_bins;
+    uint32_t* group_top;
     uint32_t slots, n_pad, grid;
 };
 size_t split_workspace(uint32_t n, const DeviceInfo& di, Carver& cv, SplitWorkspace* ws);

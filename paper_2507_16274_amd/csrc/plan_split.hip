@@ -53,6 +53,7 @@ constexpr int kSpThreads = 512;                  // two workgroups share a CU
 constexpr int kSpBatch = 64;                     // requests between two merges; dependency masks have 64 bits
 constexpr int kSpRefill = 128;                   // requests fetched per refill
 constexpr int kSpPool = 640;                     // short blocks the windows of one batch may hold in LDS
+constexpr int kSpWideHoles = 24;                 // holes of the list that one wave writes down for a request the workgroup settles together
 constexpr uint32_t kSpRefetch = 0xffffffffu;     // (a window whose blocks did not fit the pool is read when its request is settled)
 constexpr uint32_t kSpUnplaced = 0xffffffffu;
 constexpr uint32_t kSpLongFlag = 0x80000000u;
@@ -94,6 +95,10 @@ struct SplitLds {
     uint32_t region_min[kWave];                  // lowest start / highest end address of the placed short blocks of a
     uint32_t region_max[kWave];                  // region of ranks (64 regions cover the table)
     uint32_t reach[3];                           // window_reach: what the waves found, three calls in rotation
+    Span<uint32_t> wide_hole[kSpWideHoles];      // request with a wide window: holes of the list {end, covered}, in address order
+    uint32_t wide_holes;                         // how many there are (may exceed what is stored)
+    uint32_t wide_top;                           // highest end of the conflicting long blocks
+    uint32_t next_plan;                          // the plan this workgroup takes next
     uint32_t extent_now;                         // extent after the last finished batch
     uint32_t peak;                               // running extent
 };
@@ -125,6 +130,7 @@ sp_histogram(const uint32_t* __restrict__ ta, const uint32_t* __restrict__ tf, u
 
 constexpr int kSpHistWords = 40;                 // 32 lifetime classes, then [32]: requests with a wide window
 constexpr int kSpHistWide = 32;
+constexpr int kSpHistNextPlan = 33;              // (the counter that hands out plans lives behind the histogram)
 
 __global__ void sp_clear_histogram(uint32_t* hist, uint32_t* gate)
 {
@@ -258,10 +264,12 @@ struct SplitTables {
     uint32_t* addr;              // per resident workgroup: [slots] address of the short block at each rank
     uint64_t* group_bins;        // per resident workgroup: [groups][kSpLevels] address bins of the placed short blocks of 64 ranks
     uint64_t* region_bins;       // per resident workgroup: [64][kSpLevels] the same per region
+    uint32_t* group_top;         // per resident workgroup: [groups] highest end address of the placed short blocks of 64 ranks
     uint32_t slots;              // n rounded up to 64, plus 64
     uint32_t groups;             // slots / 64
     uint32_t list_cap;           // entries of the LDS list
     uint32_t region_shift;       // 2^region_shift ranks share one summary in LDS; at most 64 regions cover all slots
+    uint32_t* next_plan;         // [1] plans handed out so far
 };
 
 // What one wave knows about the request it settles.
@@ -286,7 +294,13 @@ struct SpTable {
     uint32_t* addr;
     uint64_t* group_bins;
     uint64_t* region_bins;
+    uint32_t* group_top;
 };
+
+__device__ __forceinline__ uint32_t load_coherent32(const uint32_t* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 __device__ __forceinline__ uint64_t load_coherent(const uint64_t* p)
 {
@@ -332,7 +346,17 @@ __device__ __forceinline__ uint32_t window_reach(const SpRequest& rq, uint32_t o
             const uint32_t g = g0 + lane;
             const bool valid = g >= g_begin && g < g_end && g < first + per_region;
             const uint64_t bins = valid ? load_coherent(pt.group_bins + (size_t)g * kSpLevels + level) : 0ull;
-            uint64_t open = __builtin_amdgcn_ballot_w64((bins & wanted) != 0);
+            const uint32_t top = valid ? load_coherent32(pt.group_top + g) : 0u;
+            // nothing of the group in the bins of [c, c + s), or nothing that ends above c: not concerned
+            bool look = (bins & wanted) != 0 && top > c;
+            // every block of the group ends by c + s, so all of them start below it, and the highest end
+            // is that of a block meeting [c, c + s): no need to read the blocks.  (Only for groups whose
+            // ranks all lie in the window and above the request's own: those started during its lifetime.)
+            if (look && top <= cs && g * kWave > own_rank && (g + 1) * kWave <= rq.whi) {
+                reach = umax(reach, top);
+                look = false;
+            }
+            uint64_t open = __builtin_amdgcn_ballot_w64(look);
             // two groups at a time, so that the reads of the second are under way while the first is looked at
             while (open) {
                 const uint32_t k0 = (g0 + (uint32_t)__builtin_ctzll(open)) * kWave + lane;    // < slots
@@ -444,6 +468,53 @@ __device__ __forceinline__ uint32_t settle_request(const SpList& list, uint32_t 
     return clear_others<kWide, kWaves>(rq, own_rank, run, 0xffffffffu, tb, pt, turn, sh);     // on top of every conflicting long block
 }
 
+// A request with a wide window, settled by the whole workgroup: one wave walks the list of long
+// blocks and writes down the holes that are large enough as such; then all waves try them in
+// order, sharing the look-ups in the table of short blocks.  Called by all waves.
+template <int kWaves, typename Lds>
+__device__ __forceinline__ uint32_t settle_wide(const SpList& list, uint32_t count, uint32_t b0, uint32_t q, uint64_t dep_q,
+                                                const SplitTables& tb, const SpTable& pt, uint32_t& turn, Lds& sh)
+{
+    const int lane = lane_id();
+    SpRequest rq;
+    rq.s = sh.rq_size[b0 + q]; rq.ta = sh.rq_ta[b0 + q]; rq.tf = sh.rq_tf[b0 + q];
+    rq.wlo = sh.rq_wlo[b0 + q]; rq.whi = sh.rq_whi[b0 + q];
+    const uint32_t own_rank = sh.rq_rank[b0 + q] & ~kSpLongFlag;
+    rq.rivals_in = dep_q;
+    rq.in_lo = sh.rq_addr[b0 + lane];
+    rq.in_hi = rq.in_lo + sh.rq_size[b0 + lane];
+    rq.rivals_w = 0; rq.w_lo = 0; rq.w_hi = 0;
+    __syncthreads();                                              // the holes of the previous such request are no longer read
+    if (wave_id() == 0) {
+        uint32_t run = 0, found = 0;
+        for (uint32_t k0 = 0; k0 < count; k0 += kWave) {
+            const uint32_t k = k0 + lane;
+            const bool valid = k < count;
+            const SpList::Entry en = list.load(valid ? k : count - 1);
+            const bool conflict = valid && en.ta() < rq.tf && rq.ta < en.tf();
+            const uint32_t incl = wave_scan_max(conflict ? en.hi() : 0u);
+            const uint32_t before = umax(run, wave_shift_up(incl, 0u));
+            const uint64_t opens = __builtin_amdgcn_ballot_w64(conflict && en.lo() >= before && en.lo() - before >= rq.s);
+            const uint32_t at = found + lanes_below(opens);
+            if (((opens >> lane) & 1) && at < (uint32_t)kSpWideHoles) sh.wide_hole[at] = Span<uint32_t>{en.lo(), before};
+            found += (uint32_t)__builtin_popcountll(opens);
+            run = umax(run, read_lane(incl, kWave - 1));
+        }
+        if (lane == 0) { sh.wide_holes = found; sh.wide_top = run; }
+    }
+    __syncthreads();
+    const uint32_t found = sh.wide_holes;
+    const uint32_t listed = found < (uint32_t)kSpWideHoles ? found : (uint32_t)kSpWideHoles;
+    for (uint32_t i = 0; i < listed; ++i) {
+        const Span<uint32_t> hole = sh.wide_hole[i];                  // {end, covered}
+        const uint32_t c = clear_others<true, kWaves>(rq, own_rank, hole.hi, hole.lo, tb, pt, turn, sh);
+        if (c <= hole.lo && hole.lo - c >= rq.s) return c;
+    }
+    // more holes than were written down and none of those took the request: every wave walks the list
+    if (found > listed) return settle_request<true, kWaves>(list, count, b0, q, dep_q, tb, pt, turn, sh);
+    return clear_others<true, kWaves>(rq, own_rank, sh.wide_top, 0xffffffffu, tb, pt, turn, sh);
+}
+
 template <int kThreads>
 __global__ void __launch_bounds__(kThreads, 2) plan_split_kernel(PlanParams prm, SplitTables tb)
 {
@@ -469,16 +540,24 @@ __global__ void __launch_bounds__(kThreads, 2) plan_split_kernel(PlanParams prm,
     pt.addr = tb.addr + (size_t)blockIdx.x * tb.slots;
     pt.group_bins = tb.group_bins + (size_t)blockIdx.x * tb.groups * kSpLevels;
     pt.region_bins = tb.region_bins + (size_t)blockIdx.x * kWave * kSpLevels;
+    pt.group_top = tb.group_top + (size_t)blockIdx.x * tb.groups;
     uint32_t* addr = pt.addr;
 
-    for (uint32_t p = blockIdx.x; p < prm.P; p += gridDim.x) {
+    // Plans are handed out one by one (a counter in the workspace): some orders take several times
+    // longer than others (long chains of requests that wait for each other), and the first rows are such.
+    for (;;) {
+        __syncthreads();                                              // every wave is done with the previous plan
+        if (threadIdx.x == 0) sh.next_plan = atomicAdd(tb.next_plan, 1u);
+        __syncthreads();
+        const uint32_t p = sh.next_plan;
+        if (p >= prm.P) break;                                        // (uniform)
         const uint32_t* order = prm.orders + (size_t)p * n;
         uint64_t* out = prm.offsets ? prm.offsets + (size_t)p * n : nullptr;
         uint32_t count = 0;
         bool outgrown = false;                                        // (uniform) 32-bit counts may not hold the next batch
-        __syncthreads();                                              // every wave is done with the previous plan
         for (uint32_t k = threadIdx.x; k < tb.slots; k += kThreads) addr[k] = kSpUnplaced;
         for (uint32_t g = threadIdx.x; g < tb.groups * kSpLevels; g += kThreads) pt.group_bins[g] = 0ull;
+        for (uint32_t g = threadIdx.x; g < tb.groups; g += kThreads) pt.group_top[g] = 0u;
         for (uint32_t g = threadIdx.x; g < (uint32_t)(kWave * kSpLevels); g += kThreads) pt.region_bins[g] = 0ull;
         if (threadIdx.x < kWave) { sh.region_min[threadIdx.x] = 0xffffffffu; sh.region_max[threadIdx.x] = 0u; }
         if (threadIdx.x == 0) { sh.extent_now = 0; sh.peak = 0; sh.pool_used = 0; sh.reach[0] = 0; }
@@ -570,6 +649,7 @@ __global__ void __launch_bounds__(kThreads, 2) plan_split_kernel(PlanParams prm,
                     // settled: bit set in `done`; ready: everything it waits for is settled.  (What is ready
                     // together does not conflict with each other, so the order inside a round is free.)
                     const uint64_t ready = __builtin_amdgcn_ballot_w64(mine && !((done >> lane) & 1) && (dep & ~done) == 0);
+                    // the waves share the requests with narrow windows, a request each ...
                     for (uint64_t todo = ready & stripe & ~wide; todo; todo &= todo - 1) {
                         const int q = __builtin_ctzll(todo);
                         const uint32_t x = settle_request<false, kWaves>(list, count, b0, (uint32_t)q, readlane64(dep, q), tb, pt,
@@ -579,10 +659,10 @@ __global__ void __launch_bounds__(kThreads, 2) plan_split_kernel(PlanParams prm,
                             atomicMax(&sh.peak, x + read_lane(my_size, q));
                         }
                     }
+                    // ... and the workgroup as a whole takes the requests with wide windows one by one
                     for (uint64_t todo = ready & wide; todo; todo &= todo - 1) {
                         const int q = __builtin_ctzll(todo);
-                        const uint32_t x = settle_request<true, kWaves>(list, count, b0, (uint32_t)q, readlane64(dep, q), tb, pt,
-                                                                        turn, sh);
+                        const uint32_t x = settle_wide<kWaves>(list, count, b0, (uint32_t)q, readlane64(dep, q), tb, pt, turn, sh);
                         if (threadIdx.x == 0) {
                             sh.rq_addr[b0 + q] = x;
                             atomicMax(&sh.peak, x + read_lane(my_size, q));
@@ -595,6 +675,7 @@ __global__ void __launch_bounds__(kThreads, 2) plan_split_kernel(PlanParams prm,
                 if (wave == 1 % kWaves && mine && !(my_rank & kSpLongFlag)) {
                     const uint32_t x = sh.rq_addr[b0 + lane];
                     addr[my_rank] = x;
+                    atomicMax(pt.group_top + my_rank / kWave, x + my_size);
                     for (int level = 0; level < kSpLevels; ++level) {
                         const uint64_t bins = sp_bins(x, x + my_size - 1, level);
                         atomicOr((unsigned long long*)(pt.group_bins + (size_t)(my_rank / kWave) * kSpLevels + level),
@@ -660,6 +741,7 @@ size_t split_workspace(uint32_t n, const DeviceInfo& di, Carver& cv, SplitWorksp
     ws->addr = cv.take<uint32_t>((size_t)grid * slots);
     ws->group_bins = cv.take<uint64_t>((size_t)grid * (slots / kWave) * kSpLevels);
     ws->region_bins = cv.take<uint64_t>((size_t)grid * kWave * kSpLevels);
+    ws->group_top = cv.take<uint32_t>((size_t)grid * (slots / kWave));
     ws->slots = slots;
     ws->n_pad = n_pad;
     ws->grid = grid;
@@ -689,8 +771,9 @@ bool launch_plan_split(const PlanParams& prm, uint32_t t_end, const SplitWorkspa
 
     SplitTables tb;
     tb.by_rank = ws.by_rank; tb.size_by_rank = ws.size_by_rank; tb.rank_of = ws.rank_of; tb.window = ws.window;
-    tb.addr = ws.addr; tb.group_bins = ws.group_bins; tb.region_bins = ws.region_bins;
+    tb.addr = ws.addr; tb.group_bins = ws.group_bins; tb.region_bins = ws.region_bins; tb.group_top = ws.group_top;
     tb.slots = ws.slots; tb.groups = ws.slots / kWave; tb.list_cap = list_cap;
+    tb.next_plan = ws.hist + kSpHistNextPlan;
     tb.region_shift = 6;
     while (((uint64_t)ws.slots + (1ull << tb.region_shift) - 1) >> tb.region_shift > (uint64_t)kWave) ++tb.region_shift;
     auto kernel = &plan_split_kernel<kSpThreads>;
