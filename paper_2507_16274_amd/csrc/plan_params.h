@@ -55,7 +55,8 @@ struct SplitWorkspace {
     uint4* by_rank;
     uint32_t* size_by_rank;
     uint32_t* rank_of;
-    uint2* window;
+    uint4* record;
+    uint2* fit_by_rank;
     uint32_t* addr;
     uint64_t* group_bins;
     uint64_t* region_bins;

@@ -90,8 +90,6 @@ struct SplitLds {
     uint2 pend_life[kSpBatch];
     Span<uint32_t> pool[kSpPool];                // conflicting short blocks of the windows of the batch's requests
     uint32_t pool_used;
-    uint32_t win_first[kSpBatch];                // per request of the batch: its part of the pool
-    uint32_t win_count[kSpBatch];
     uint32_t region_min[kWave];                  // lowest start / highest end address of the placed short blocks of a
     uint32_t region_max[kWave];                  // region of ranks (64 regions cover the table)
     uint32_t reach[3];                           // window_reach: what the waves found, three calls in rotation
@@ -192,17 +190,23 @@ sp_sort_tiles(const uint32_t* __restrict__ ta, uint32_t n, ulonglong2* keys, con
 __global__ void __launch_bounds__(256)
 sp_tables(const ulonglong2* __restrict__ sorted, const uint64_t* __restrict__ size, const uint32_t* __restrict__ ta,
           const uint32_t* __restrict__ tf, uint32_t n, uint32_t slots, const uint64_t* acc, uint4* by_rank,
-          uint32_t* size_by_rank, uint32_t* rank_of, const uint32_t* gate)
+          uint32_t* size_by_rank, uint2* fit_by_rank, uint32_t* rank_of, const uint32_t* gate)
 {
     if (*gate != 0) return;
     const uint32_t shift = (uint32_t)(acc[kAccMode] & 63);
     const uint32_t theta = (uint32_t)((acc[kAccSplit] >> 8) & 0xffffffu);
     for (uint32_t k = blockIdx.x * blockDim.x + threadIdx.x; k < slots; k += gridDim.x * blockDim.x) {
-        if (k >= n) { by_rank[k] = make_uint4(0u, 0xffffffffu, 0u, 0xffffffffu); size_by_rank[k] = 0u; continue; }
+        if (k >= n) {
+            by_rank[k] = make_uint4(0u, 0xffffffffu, 0u, 0xffffffffu);
+            size_by_rank[k] = 0u;
+            fit_by_rank[k] = make_uint2(0u, 0u);
+            continue;
+        }
         const uint32_t i = (uint32_t)sorted[k].y;
         const uint32_t a = ta[i], f = tf[i];
         by_rank[k] = make_uint4((uint32_t)(size[i] >> shift), a, f, i);
         size_by_rank[k] = (uint32_t)(size[i] >> shift);
+        fit_by_rank[k] = make_uint2((uint32_t)(size[i] >> shift), f);
         rank_of[i] = k | (f - a > theta ? kSpLongFlag : 0u);
     }
 }
@@ -223,7 +227,8 @@ __device__ __forceinline__ uint32_t first_rank_at(const uint4* __restrict__ by_r
 // t_alloc_j >= t_free_j - theta > t_alloc_i - theta, so it lies in the window.
 __global__ void __launch_bounds__(256)
 sp_windows(const uint4* __restrict__ by_rank, const uint32_t* __restrict__ ta, const uint32_t* __restrict__ tf, uint32_t n,
-           const uint64_t* acc, uint2* window, uint32_t* hist, const uint32_t* gate)
+           const uint64_t* acc, const uint64_t* __restrict__ size, const uint32_t* __restrict__ rank_of, uint4* record,
+           uint32_t* hist, const uint32_t* gate)
 {
     if (*gate != 0) return;
     const uint32_t theta = (uint32_t)((acc[kAccSplit] >> 8) & 0xffffffu);
@@ -232,7 +237,8 @@ sp_windows(const uint4* __restrict__ by_rank, const uint32_t* __restrict__ ta, c
         const uint32_t a = ta[i];
         const uint32_t from = a + 1 > theta ? a + 1 - theta : 0u;
         const uint2 w = make_uint2(first_rank_at(by_rank, n, from), first_rank_at(by_rank, n, tf[i]));
-        window[i] = w;
+        record[2 * i] = make_uint4((uint32_t)(size[i] >> (acc[kAccMode] & 63)), a, tf[i], rank_of[i]);
+        record[2 * i + 1] = make_uint4(w.x, w.y, 0u, 0u);
         wide += w.y - w.x > (uint32_t)kWave ? 1u : 0u;
     }
     wide = wave_sum32(wide);
@@ -259,8 +265,8 @@ __global__ void sp_confirm(uint64_t* acc, const uint32_t* hist, uint32_t n, uint
 struct SplitTables {
     const uint4* by_rank;        // [slots] (size, t_alloc, t_free, request) in allocation-time order
     const uint32_t* size_by_rank;// [slots] the sizes once more, on their own
-    const uint32_t* rank_of;     // [n]
-    const uint2* window;         // [n]
+    const uint2* fit_by_rank;    // [slots] (size, t_free): what a request needs to know of the short blocks of its window
+    const uint4* record;         // [n] per request: (size, t_alloc, t_free, rank | long flag), then (window start, window end, -, -)
     uint32_t* addr;              // per resident workgroup: [slots] address of the short block at each rank
     uint64_t* group_bins;        // per resident workgroup: [groups][kSpLevels] address bins of the placed short blocks of 64 ranks
     uint64_t* region_bins;       // per resident workgroup: [64][kSpLevels] the same per region
@@ -408,34 +414,43 @@ __device__ __forceinline__ uint32_t clear_others(const SpRequest& rq, uint32_t o
     }
 }
 
+// The requests of the batch as the lanes of a wave hold them (lane = position in the batch).
+struct SpBatch {
+    uint32_t size, ta, tf, rank, wlo, whi;
+};
+
 // Settles request q of the batch: the lowest address at which it conflicts with nothing placed
 // before it.  A request whose window fits the lanes of a wave (kWide false) is settled by one
 // wave; one with a wider window by all waves of the workgroup together, every wave taking the
 // same steps (they read the same LDS) and sharing only the look-ups in the table.
 template <bool kWide, int kWaves, typename Lds>
 __device__ __forceinline__ uint32_t settle_request(const SpList& list, uint32_t count, uint32_t b0, uint32_t q,
-                                                   uint64_t dep_q, const SplitTables& tb, const SpTable& pt,
-                                                   uint32_t& turn, Lds& sh)
+                                                   uint64_t dep_q, const SpBatch& bt, uint32_t pool_first, uint32_t in_pool,
+                                                   const SplitTables& tb, const SpTable& pt, uint32_t& turn, Lds& sh)
 {
     const int lane = lane_id();
     SpRequest rq;
-    rq.s = sh.rq_size[b0 + q]; rq.ta = sh.rq_ta[b0 + q]; rq.tf = sh.rq_tf[b0 + q];
-    rq.wlo = sh.rq_wlo[b0 + q]; rq.whi = sh.rq_whi[b0 + q];
-    const uint32_t own_rank = sh.rq_rank[b0 + q] & ~kSpLongFlag;
+    rq.s = read_lane(bt.size, (int)q); rq.ta = read_lane(bt.ta, (int)q); rq.tf = read_lane(bt.tf, (int)q);
+    rq.wlo = read_lane(bt.wlo, (int)q); rq.whi = read_lane(bt.whi, (int)q);
+    const uint32_t own_rank = read_lane(bt.rank, (int)q) & ~kSpLongFlag;
     // earlier requests of the batch with a conflicting lifetime: all settled by now
     rq.rivals_in = dep_q;
-    rq.in_lo = sh.rq_addr[b0 + lane];
-    rq.in_hi = rq.in_lo + sh.rq_size[b0 + lane];
+    rq.in_lo = 0; rq.in_hi = 0;
+    if (dep_q) {                                                    // (uniform)
+        rq.in_lo = sh.rq_addr[b0 + lane];
+        rq.in_hi = rq.in_lo + bt.size;
+    }
     rq.rivals_w = 0; rq.w_lo = 0; rq.w_hi = 0;
     if constexpr (!kWide) {
         // conflicting short blocks of its window, as gathered when the batch began
-        const uint32_t in_pool = __builtin_amdgcn_readfirstlane(sh.win_count[q]);
         if (in_pool != kSpRefetch) {
-            Span<uint32_t> sp = {0u, 0u};
-            if ((uint32_t)lane < in_pool) sp = sh.pool[sh.win_first[q] + lane];
-            rq.rivals_w = in_pool >= (uint32_t)kWave ? ~0ull : (1ull << in_pool) - 1;
-            rq.w_lo = sp.lo;
-            rq.w_hi = sp.hi;
+            if (in_pool) {                                          // (uniform)
+                Span<uint32_t> sp = {0u, 0u};
+                if ((uint32_t)lane < in_pool) sp = sh.pool[pool_first + lane];
+                rq.rivals_w = in_pool >= (uint32_t)kWave ? ~0ull : (1ull << in_pool) - 1;
+                rq.w_lo = sp.lo;
+                rq.w_hi = sp.hi;
+            }
         } else {
             const uint32_t k = rq.wlo + lane;                       // < slots
             const uint32_t a = pt.addr[k];
@@ -473,16 +488,17 @@ __device__ __forceinline__ uint32_t settle_request(const SpList& list, uint32_t 
 // order, sharing the look-ups in the table of short blocks.  Called by all waves.
 template <int kWaves, typename Lds>
 __device__ __forceinline__ uint32_t settle_wide(const SpList& list, uint32_t count, uint32_t b0, uint32_t q, uint64_t dep_q,
-                                                const SplitTables& tb, const SpTable& pt, uint32_t& turn, Lds& sh)
+                                                const SpBatch& bt, const SplitTables& tb, const SpTable& pt, uint32_t& turn,
+                                                Lds& sh)
 {
     const int lane = lane_id();
     SpRequest rq;
-    rq.s = sh.rq_size[b0 + q]; rq.ta = sh.rq_ta[b0 + q]; rq.tf = sh.rq_tf[b0 + q];
-    rq.wlo = sh.rq_wlo[b0 + q]; rq.whi = sh.rq_whi[b0 + q];
-    const uint32_t own_rank = sh.rq_rank[b0 + q] & ~kSpLongFlag;
+    rq.s = read_lane(bt.size, (int)q); rq.ta = read_lane(bt.ta, (int)q); rq.tf = read_lane(bt.tf, (int)q);
+    rq.wlo = read_lane(bt.wlo, (int)q); rq.whi = read_lane(bt.whi, (int)q);
+    const uint32_t own_rank = read_lane(bt.rank, (int)q) & ~kSpLongFlag;
     rq.rivals_in = dep_q;
     rq.in_lo = sh.rq_addr[b0 + lane];
-    rq.in_hi = rq.in_lo + sh.rq_size[b0 + lane];
+    rq.in_hi = rq.in_lo + bt.size;
     rq.rivals_w = 0; rq.w_lo = 0; rq.w_hi = 0;
     __syncthreads();                                              // the holes of the previous such request are no longer read
     if (wave_id() == 0) {
@@ -511,7 +527,7 @@ __device__ __forceinline__ uint32_t settle_wide(const SpList& list, uint32_t cou
         if (c <= hole.lo && hole.lo - c >= rq.s) return c;
     }
     // more holes than were written down and none of those took the request: every wave walks the list
-    if (found > listed) return settle_request<true, kWaves>(list, count, b0, q, dep_q, tb, pt, turn, sh);
+    if (found > listed) return settle_request<true, kWaves>(list, count, b0, q, dep_q, bt, 0u, 0u, tb, pt, turn, sh);
     return clear_others<true, kWaves>(rq, own_rank, sh.wide_top, 0xffffffffu, tb, pt, turn, sh);
 }
 
@@ -569,14 +585,14 @@ __global__ void __launch_bounds__(kThreads, 2) plan_split_kernel(PlanParams prm,
             if (threadIdx.x < staged) {
                 uint32_t i = order[r0 + threadIdx.x];
                 if (i >= n) { atomicMax(prm.status, (uint32_t)STALLOC_ERR_BAD_ORDER); i = 0; }
-                const uint2 w = tb.window[i];
+                const uint4 r0 = tb.record[2 * (size_t)i], r1 = tb.record[2 * (size_t)i + 1];    // one 32-byte read
                 sh.rq_id[threadIdx.x] = i;
-                sh.rq_size[threadIdx.x] = (uint32_t)(prm.size[i] >> shift);
-                sh.rq_ta[threadIdx.x] = prm.ta[i];
-                sh.rq_tf[threadIdx.x] = prm.tf[i];
-                sh.rq_rank[threadIdx.x] = tb.rank_of[i];
-                sh.rq_wlo[threadIdx.x] = w.x;
-                sh.rq_whi[threadIdx.x] = w.y;
+                sh.rq_size[threadIdx.x] = r0.x;
+                sh.rq_ta[threadIdx.x] = r0.y;
+                sh.rq_tf[threadIdx.x] = r0.z;
+                sh.rq_rank[threadIdx.x] = r0.w;
+                sh.rq_wlo[threadIdx.x] = r1.x;
+                sh.rq_whi[threadIdx.x] = r1.y;
             }
             if (threadIdx.x < kSpBatch) sh.dep[threadIdx.x] = 0;
             __syncthreads();
@@ -590,6 +606,7 @@ __global__ void __launch_bounds__(kThreads, 2) plan_split_kernel(PlanParams prm,
                 const uint32_t my_rank = mine ? sh.rq_rank[b0 + lane] : 0u;
                 const uint32_t my_wlo = mine ? sh.rq_wlo[b0 + lane] : 0u;
                 const uint32_t my_whi = mine ? sh.rq_whi[b0 + lane] : 0u;
+                const SpBatch bt = {my_size, my_ta, my_tf, my_rank, my_wlo, my_whi};
                 if (try32) {
                     // no address of this batch exceeds the extent so far plus the sizes of the batch
                     const uint64_t growth = wave_sum64((uint64_t)my_size);
@@ -600,12 +617,13 @@ __global__ void __launch_bounds__(kThreads, 2) plan_split_kernel(PlanParams prm,
                 // batch itself adds to the table concerns them through `dep` instead.
                 constexpr int kMine = kSpBatch / kWaves;
                 uint32_t f_addr[kMine];
-                uint4 f_rec[kMine];
+                uint2 f_fit[kMine];
 #pragma unroll
                 for (int j = 0; j < kMine; ++j) {
                     const uint32_t k = read_lane(my_wlo, wave + j * kWaves) + lane;     // < slots
-                    f_addr[j] = addr[k];
-                    f_rec[j] = tb.by_rank[k];
+                    const bool inside = k < read_lane(my_whi, wave + j * kWaves);       // (nothing is read past the window)
+                    f_addr[j] = inside ? addr[k] : kSpUnplaced;
+                    f_fit[j] = inside ? tb.fit_by_rank[k] : make_uint2(0u, 0u);
                 }
                 // which earlier requests of the batch each request has to wait for: wave w looks at
                 // the requests 64 / kWaves * w .. of the batch, for all 64 lanes
@@ -618,14 +636,18 @@ __global__ void __launch_bounds__(kThreads, 2) plan_split_kernel(PlanParams prm,
                     }
                     if (part) atomicOr((unsigned long long*)&sh.dep[lane], (unsigned long long)part);
                 }
-                // the placed short blocks of each window that conflict in lifetime, packed into the pool
+                // the placed short blocks of each window that conflict in lifetime, packed into the pool; this
+                // wave settles these very requests, so it keeps their parts of the pool to itself (lane j:
+                // request wave + j * kWaves)
+                uint32_t part_first = 0, part_count = 0;
 #pragma unroll
                 for (int j = 0; j < kMine; ++j) {
                     const int q = wave + j * kWaves;
                     const uint32_t wlo = read_lane(my_wlo, q), whi = read_lane(my_whi, q);
-                    const uint32_t q_ta = read_lane(my_ta, q), q_tf = read_lane(my_tf, q);
+                    // (a block of the window was allocated before the request is released: only its release counts)
+                    const uint32_t q_ta = read_lane(my_ta, q);
                     const bool rival = whi - wlo <= (uint32_t)kWave && wlo + lane < whi && f_addr[j] != kSpUnplaced &&
-                                       f_rec[j].z > q_ta && f_rec[j].y < q_tf;
+                                       f_fit[j].y > q_ta;
                     const uint64_t rivals = __builtin_amdgcn_ballot_w64(rival);
                     const uint32_t found = (uint32_t)__builtin_popcountll(rivals);
                     uint32_t first = 0;
@@ -634,11 +656,9 @@ __global__ void __launch_bounds__(kThreads, 2) plan_split_kernel(PlanParams prm,
                         first = read_lane(first, 0);
                     }
                     const bool fits = first + found <= (uint32_t)kSpPool;
-                    if (rival && fits) sh.pool[first + lanes_below(rivals)] = Span<uint32_t>{f_addr[j], f_addr[j] + f_rec[j].x};
-                    if (lane == 0) {
-                        sh.win_first[q] = first;
-                        sh.win_count[q] = fits ? found : kSpRefetch;
-                    }
+                    if (rival && fits) sh.pool[first + lanes_below(rivals)] = Span<uint32_t>{f_addr[j], f_addr[j] + f_fit[j].x};
+                    part_first = write_lane(part_first, first, j);
+                    part_count = write_lane(part_count, fits ? found : kSpRefetch, j);
                 }
                 __syncthreads();
                 const uint64_t dep = sh.dep[lane];
@@ -652,8 +672,9 @@ __global__ void __launch_bounds__(kThreads, 2) plan_split_kernel(PlanParams prm,
                     // the waves share the requests with narrow windows, a request each ...
                     for (uint64_t todo = ready & stripe & ~wide; todo; todo &= todo - 1) {
                         const int q = __builtin_ctzll(todo);
-                        const uint32_t x = settle_request<false, kWaves>(list, count, b0, (uint32_t)q, readlane64(dep, q), tb, pt,
-                                                                         turn, sh);
+                        const uint32_t x = settle_request<false, kWaves>(list, count, b0, (uint32_t)q, readlane64(dep, q), bt,
+                                                                         read_lane(part_first, q / kWaves),
+                                                                         read_lane(part_count, q / kWaves), tb, pt, turn, sh);
                         if (lane == 0) {
                             sh.rq_addr[b0 + q] = x;
                             atomicMax(&sh.peak, x + read_lane(my_size, q));
@@ -662,7 +683,7 @@ __global__ void __launch_bounds__(kThreads, 2) plan_split_kernel(PlanParams prm,
                     // ... and the workgroup as a whole takes the requests with wide windows one by one
                     for (uint64_t todo = ready & wide; todo; todo &= todo - 1) {
                         const int q = __builtin_ctzll(todo);
-                        const uint32_t x = settle_wide<kWaves>(list, count, b0, (uint32_t)q, readlane64(dep, q), tb, pt, turn, sh);
+                        const uint32_t x = settle_wide<kWaves>(list, count, b0, (uint32_t)q, readlane64(dep, q), bt, tb, pt, turn, sh);
                         if (threadIdx.x == 0) {
                             sh.rq_addr[b0 + q] = x;
                             atomicMax(&sh.peak, x + read_lane(my_size, q));
@@ -737,7 +758,8 @@ size_t split_workspace(uint32_t n, const DeviceInfo& di, Carver& cv, SplitWorksp
     ws->by_rank = cv.take<uint4>(slots);
     ws->size_by_rank = cv.take<uint32_t>(slots);
     ws->rank_of = cv.take<uint32_t>(n);
-    ws->window = cv.take<uint2>(n);
+    ws->record = cv.take<uint4>(2 * (size_t)n);
+    ws->fit_by_rank = cv.take<uint2>(slots);
     ws->addr = cv.take<uint32_t>((size_t)grid * slots);
     ws->group_bins = cv.take<uint64_t>((size_t)grid * (slots / kWave) * kSpLevels);
     ws->region_bins = cv.take<uint64_t>((size_t)grid * kWave * kSpLevels);
@@ -764,13 +786,13 @@ bool launch_plan_split(const PlanParams& prm, uint32_t t_end, const SplitWorkspa
     hipLaunchKernelGGL(sp_sort_tiles, dim3(ws.n_pad / kSortTile), dim3(kSortTile), 0, stream, prm.ta, n, ws.keys, ws.gate);
     const ulonglong2* sorted = launch_merge_tiles(ws.keys, ws.spare, ws.n_pad, 1, ws.gate, stream);
     hipLaunchKernelGGL(sp_tables, dim3(blocks), dim3(256), 0, stream, sorted, prm.size, prm.ta, prm.tf, n, ws.slots, prm.acc,
-                       ws.by_rank, ws.size_by_rank, ws.rank_of, ws.gate);
-    hipLaunchKernelGGL(sp_windows, dim3(blocks), dim3(256), 0, stream, ws.by_rank, prm.ta, prm.tf, n, prm.acc, ws.window,
-                       ws.hist, ws.gate);
+                       ws.by_rank, ws.size_by_rank, ws.fit_by_rank, ws.rank_of, ws.gate);
+    hipLaunchKernelGGL(sp_windows, dim3(blocks), dim3(256), 0, stream, ws.by_rank, prm.ta, prm.tf, n, prm.acc, prm.size,
+                       ws.rank_of, ws.record, ws.hist, ws.gate);
     hipLaunchKernelGGL(sp_confirm, dim3(1), dim3(64), 0, stream, acc, ws.hist, n, ws.gate);
 
     SplitTables tb;
-    tb.by_rank = ws.by_rank; tb.size_by_rank = ws.size_by_rank; tb.rank_of = ws.rank_of; tb.window = ws.window;
+    tb.by_rank = ws.by_rank; tb.size_by_rank = ws.size_by_rank; tb.fit_by_rank = ws.fit_by_rank; tb.record = ws.record;
     tb.addr = ws.addr; tb.group_bins = ws.group_bins; tb.region_bins = ws.region_bins; tb.group_top = ws.group_top;
     tb.slots = ws.slots; tb.groups = ws.slots / kWave; tb.list_cap = list_cap;
     tb.next_plan = ws.hist + kSpHistNextPlan;
