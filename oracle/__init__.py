@@ -56,6 +56,7 @@ def _bind(path: str):
     lib.oracle_conflict_lists.argtypes = [u32, p, p, p, p]
     lib.oracle_plan_lists.argtypes = [u32, p, p, p, p, p, p]
     lib.oracle_best_plan.argtypes = [u32, p, p]
+    lib.oracle_fuse_groups.argtypes = [u32, p, p, p, u32, p, u32, p, p, p, p, p, p]
     lib.oracle_validate.argtypes = [u32, p, p, p, p, p, p]
     lib.oracle_lower_bound_definition.argtypes = [u32, u32, p, p, p, p, p]
     lib.oracle_lower_bound_sweep.argtypes = [u32, u32, p, p, p, p, p]
@@ -246,6 +247,22 @@ def tmp(size, t_s, t_e, a) -> float:
     extent = max(int(x) + int(s) for x, s in zip(a, size))
     span = max(int(e) for e in t_e) - min(int(b) for b in t_s)
     return float(Fraction(used, extent * span))
+
+
+def fuse_groups(size, t_s, t_e, members1, members2):
+    """Fusion of two HomoPhase groups (Sec. 5.1): -> dict with `order` (request numbers: the larger group's in
+    packing order, then the smaller group's by allocation time), `a` (their addresses in the fused plan),
+    `extent` [3] and `span` [3][2] of plan 1, plan 2 and the fused plan, `accepted` (bool)."""
+    size, t_s, t_e = _c(size, np.uint64), _c(t_s, np.uint32), _c(t_e, np.uint32)
+    m1, m2 = _c(members1, np.uint32), _c(members2, np.uint32)
+    order = np.zeros(len(m1) + len(m2), dtype=np.uint32)
+    a = np.zeros(len(m1) + len(m2), dtype=np.uint64)
+    extent = np.zeros(3, dtype=np.uint64)
+    span = np.zeros((3, 2), dtype=np.uint32)
+    accepted = np.zeros(1, dtype=np.uint32)
+    _check(_load().oracle_fuse_groups(len(size), _ptr(size), _ptr(t_s), _ptr(t_e), len(m1), _ptr(m1), len(m2), _ptr(m2),
+                                      _ptr(order), _ptr(a), _ptr(extent), _ptr(span), _ptr(accepted)))
+    return {"order": order, "a": a, "extent": extent, "span": span, "accepted": bool(accepted[0])}
 
 
 def splitmix64(x: int) -> int:

@@ -49,6 +49,13 @@
  * generator of workloads/ and the statistics of the two random families
  * (tests/test_oracle_orders.py).
  *
+ * Fusion of two HomoPhase groups (Sec. 5.1, HomoPhase Group Planning): oracle_fuse_groups,
+ * pinned by a hand-worked example with an accepted and a rejected fusion, closed forms
+ * (disjoint lifetimes: the smaller plan disappears inside the larger; one common lifetime:
+ * the plans end up stacked and the fusion is rejected), the no-conflict invariant, the
+ * equivalence of its integer accept test with the TMP values of Eq. 2, and planted mistakes
+ * (tests/test_oracle_fusion.py).  The paper's worked figure is an image: unpinned by printed values.
+ *
  * The time-memory product of a plan (Eq. 2) is a ratio of exact integers and lives in
  * the Python part of the oracle (oracle/__init__.py, tmp), pinned by closed forms, the
  * area bound, unit invariances and an instant-by-instant count (tests/test_oracle_tmp.py).
@@ -553,5 +560,149 @@ int oracle_make_orders(uint32_t n, const uint64_t *size, const uint32_t *t_s, co
         for (uint32_t q = 0; q < n; ++q) orders[(size_t)r * n + q] = m[q].id;
     }
     free(m); free(distinct); free(larger);
+    return ORC_OK;
+}
+
+
+/* ---------------------------------------------------------------------------------------
+ * Fusion of two HomoPhase groups (Sec. 5.1, HomoPhase Group Planning).
+ *
+ * A HomoPhase group holds the requests allocated in one computation phase and released in
+ * one (other) phase; its local plan packs them contiguously, so its extent is the sum of
+ * their sizes.  Two such plans are fused by inserting the smaller into the larger:
+ *   - the larger plan's requests are packed from 0 in descending order of release time
+ *     (request number among equals);
+ *   - addr starts at the lowest start address of the larger plan; the requests of the smaller
+ *     plan are tried in order of allocation time (request number among equals): the first
+ *     one that conflicts with nothing placed so far when put at addr is placed there and
+ *     addr moves up by its size; if none fits, addr moves to the next higher start address
+ *     of the larger plan; when there is none, the requests still left are packed on top of
+ *     everything placed, in the same order (the text does not say; they have to go somewhere);
+ *   - the fusion is accepted only if its time-memory product (Eq. 2) exceeds the weighted
+ *     average of the two plans' products, the weights being the memory-time each plan reserves
+ *     (its extent times its span): the weighted average is then (used_1 + used_2) /
+ *     (reserved_1 + reserved_2) and, the used memory-time being the same on both sides, the
+ *     test is  reserved_fused < reserved_1 + reserved_2  in exact integers.
+ *
+ * members1 / members2: request numbers of the two groups.  order_out / addr_out [n1 + n2]: the
+ * fused plan, the larger group's requests first (in packing order), then the smaller group's in
+ * order of allocation time.  extent_out[3], span_out[3][2]: extent and (first allocation,
+ * last release) of plan 1, plan 2 and the fused plan.  accepted_out[1].
+ */
+typedef struct { uint32_t id; uint32_t key; } fuse_key_t;
+
+static int fuse_by_release_desc(const void *pa, const void *pb)
+{
+    const fuse_key_t *a = (const fuse_key_t *)pa, *b = (const fuse_key_t *)pb;
+    if (a->key != b->key) return a->key > b->key ? -1 : 1;
+    return a->id < b->id ? -1 : (a->id > b->id ? 1 : 0);
+}
+
+static int fuse_by_start_asc(const void *pa, const void *pb)
+{
+    const fuse_key_t *a = (const fuse_key_t *)pa, *b = (const fuse_key_t *)pb;
+    if (a->key != b->key) return a->key < b->key ? -1 : 1;
+    return a->id < b->id ? -1 : (a->id > b->id ? 1 : 0);
+}
+
+int oracle_fuse_groups(uint32_t n, const uint64_t *size, const uint32_t *t_s, const uint32_t *t_e,
+                       uint32_t n1, const uint32_t *members1, uint32_t n2, const uint32_t *members2,
+                       uint32_t *order_out, uint64_t *addr_out, uint64_t *extent_out, uint32_t *span_out,
+                       uint32_t *accepted_out)
+{
+    if (!size || !t_s || !t_e || !members1 || !members2 || n1 == 0 || n2 == 0 || !order_out || !addr_out ||
+        !extent_out || !span_out || !accepted_out)
+        return ORC_INVALID_ARG;
+    for (uint32_t k = 0; k < n1; ++k) if (members1[k] >= n) return ORC_INVALID_ARG;
+    for (uint32_t k = 0; k < n2; ++k) if (members2[k] >= n) return ORC_INVALID_ARG;
+    /* the two local plans: extent = sum of sizes, span = first allocation .. last release */
+    uint64_t ext[2] = {0, 0};
+    uint32_t lo[2] = {0xffffffffu, 0xffffffffu}, hi[2] = {0, 0};
+    for (uint32_t k = 0; k < n1; ++k) {
+        uint32_t i = members1[k];
+        ext[0] += size[i];
+        if (t_s[i] < lo[0]) lo[0] = t_s[i];
+        if (t_e[i] > hi[0]) hi[0] = t_e[i];
+    }
+    for (uint32_t k = 0; k < n2; ++k) {
+        uint32_t i = members2[k];
+        ext[1] += size[i];
+        if (t_s[i] < lo[1]) lo[1] = t_s[i];
+        if (t_e[i] > hi[1]) hi[1] = t_e[i];
+    }
+    const int first_is_larger = ext[0] >= ext[1];
+    const uint32_t nl = first_is_larger ? n1 : n2, ns = first_is_larger ? n2 : n1;
+    const uint32_t *larger = first_is_larger ? members1 : members2, *smaller = first_is_larger ? members2 : members1;
+    fuse_key_t *kl = (fuse_key_t *)malloc(sizeof(fuse_key_t) * nl), *ks = (fuse_key_t *)malloc(sizeof(fuse_key_t) * ns);
+    unsigned char *placed = (unsigned char *)calloc(ns, 1);
+    if (!kl || !ks || !placed) { free(kl); free(ks); free(placed); return ORC_NOMEM; }
+    for (uint32_t k = 0; k < nl; ++k) { kl[k].id = larger[k]; kl[k].key = t_e[larger[k]]; }
+    for (uint32_t k = 0; k < ns; ++k) { ks[k].id = smaller[k]; ks[k].key = t_s[smaller[k]]; }
+    qsort(kl, nl, sizeof(fuse_key_t), fuse_by_release_desc);
+    qsort(ks, ns, sizeof(fuse_key_t), fuse_by_start_asc);
+    /* the larger plan, packed from 0 */
+    uint64_t top = 0;
+    for (uint32_t k = 0; k < nl; ++k) {
+        order_out[k] = kl[k].id;
+        addr_out[k] = top;
+        top += size[kl[k].id];
+    }
+    for (uint32_t k = 0; k < ns; ++k) order_out[nl + k] = ks[k].id;
+    /* insertion of the smaller plan */
+    uint64_t addr = addr_out[0];                 /* the lowest start address of the larger plan */
+    uint32_t left = ns;
+    for (;;) {
+        if (left == 0) break;
+        uint32_t fit = ns;
+        for (uint32_t k = 0; k < ns && fit == ns; ++k) {
+            if (placed[k]) continue;
+            const uint32_t j = ks[k].id;
+            int clash = 0;
+            for (uint32_t q = 0; q < nl + ns && !clash; ++q) {
+                if (q >= nl && !placed[q - nl]) continue;
+                const uint32_t i = order_out[q];
+                clash = lifetimes_conflict(t_s[i], t_e[i], t_s[j], t_e[j]) &&
+                        ranges_conflict(addr_out[q], size[i], addr, size[j]);
+            }
+            if (!clash) fit = k;
+        }
+        if (fit < ns) {
+            placed[fit] = 1;
+            addr_out[nl + fit] = addr;
+            addr += size[ks[fit].id];
+            --left;
+            continue;
+        }
+        /* nothing fits here: on to the next higher start address of the larger plan */
+        uint64_t next = 0;
+        int have = 0;
+        for (uint32_t k = 0; k < nl; ++k)
+            if (addr_out[k] > addr && (!have || addr_out[k] < next)) { next = addr_out[k]; have = 1; }
+        if (!have) break;
+        addr = next;
+    }
+    /* what is left goes on top of everything placed */
+    for (uint32_t q = 0; q < nl + ns; ++q) {
+        if (q >= nl && !placed[q - nl]) continue;
+        const uint64_t end = addr_out[q] + size[order_out[q]];
+        if (end > top) top = end;
+    }
+    for (uint32_t k = 0; k < ns; ++k) {
+        if (placed[k]) continue;
+        addr_out[nl + k] = top;
+        top += size[ks[k].id];
+    }
+    extent_out[0] = ext[0];
+    extent_out[1] = ext[1];
+    extent_out[2] = top;
+    span_out[0] = lo[0]; span_out[1] = hi[0];
+    span_out[2] = lo[1]; span_out[3] = hi[1];
+    span_out[4] = lo[0] < lo[1] ? lo[0] : lo[1];
+    span_out[5] = hi[0] > hi[1] ? hi[0] : hi[1];
+    const unsigned __int128 r1 = (unsigned __int128)ext[0] * (hi[0] - lo[0]);
+    const unsigned __int128 r2 = (unsigned __int128)ext[1] * (hi[1] - lo[1]);
+    const unsigned __int128 rf = (unsigned __int128)top * (span_out[5] - span_out[4]);
+    *accepted_out = rf < r1 + r2 ? 1u : 0u;
+    free(kl); free(ks); free(placed);
     return ORC_OK;
 }

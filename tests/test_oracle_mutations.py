@@ -10,6 +10,7 @@ import test_oracle_pins as pins
 import test_oracle_reusable as reusable
 import test_oracle_layers as layers
 import test_oracle_orders as orders
+import test_oracle_fusion as fusion
 
 MUTATIONS = {
     "closed_lifetimes": ("return ts_a < te_b && ts_b < te_a;", "return ts_a <= te_b && ts_b <= te_a;"),
@@ -42,6 +43,13 @@ MUTATIONS = {
     "orders_generator_shift": ("z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;", "z = (z ^ (z >> 28)) * 0x94D049BB133111EBull;"),
     "orders_counter_not_spread": ("(uint64_t)i * 0xD1342543DE82EF95ull + stream", "(uint64_t)i + stream"),
     "orders_classes_ascending": ("return x > y ? -1 : (x < y ? 1 : 0);", "return x > y ? 1 : (x < y ? -1 : 0);"),
+    "fusion_larger_plan_by_earliest_release": ("if (a->key != b->key) return a->key > b->key ? -1 : 1;", "if (a->key != b->key) return a->key > b->key ? 1 : -1;"),
+    "fusion_latest_request_first": ("if (a->key != b->key) return a->key < b->key ? -1 : 1;\n    return a->id < b->id ? -1 : (a->id > b->id ? 1 : 0);\n}\n\nint oracle_fuse_groups",
+                                    "if (a->key != b->key) return a->key < b->key ? 1 : -1;\n    return a->id < b->id ? -1 : (a->id > b->id ? 1 : 0);\n}\n\nint oracle_fuse_groups"),
+    "fusion_accepts_equal_product": ("*accepted_out = rf < r1 + r2 ? 1u : 0u;", "*accepted_out = rf <= r1 + r2 ? 1u : 0u;"),
+    "fusion_jumps_to_the_highest_address": ("if (addr_out[k] > addr && (!have || addr_out[k] < next))", "if (addr_out[k] > addr && (!have || addr_out[k] > next))"),
+    "fusion_addr_not_advanced": ("            addr += size[ks[fit].id];\n", "            addr += 0;\n"),
+    "fusion_leftovers_at_the_larger_plans_top": ("        if (end > top) top = end;\n    }\n    for (uint32_t k = 0; k < ns; ++k) {\n        if (placed[k]) continue;", "        if (end > top && q < nl) top = end;\n    }\n    for (uint32_t k = 0; k < ns; ++k) {\n        if (placed[k]) continue;"),
     "extent_forgets_size": ("if (a[i] + size[i] > top) top = a[i] + size[i];\n    }\n    free(spans);\n    *extent",
                             "if (a[i] > top) top = a[i];\n    }\n    free(spans);\n    *extent"),
 }
@@ -75,6 +83,11 @@ def _battery(oracle):
     for seed in range(4):
         layers.test_random_traces_structure_and_minimum(oracle, seed)
         layers.test_layers_planned_as_requests_expand_to_a_valid_plan(oracle, seed)
+    fusion.test_hand_worked_fusions(oracle)
+    fusion.test_closed_forms(oracle)
+    fusion.test_first_placement_is_the_earliest_request_that_fits_at_the_lowest_start_address(oracle)
+    for seed in range(12):
+        fusion.test_fused_plans_are_valid_and_the_accept_test_is_the_tmp_test(oracle, seed)
 
 
 def test_battery_passes_on_the_real_oracle(oracle):

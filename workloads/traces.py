@@ -46,6 +46,8 @@ class Trace:
     t_free: np.ndarray    # uint32 [n], t_alloc < t_free <= t_end
     t_end: int
     meta: Dict = field(default_factory=dict)
+    p_alloc: np.ndarray = None   # uint32 [n], computation phase (forward / backward pass of a micro-batch, optimizer
+    p_free: np.ndarray = None    # step, in schedule order) in which the request is allocated / released (Sec. 4: p_s, p_e)
 
     @property
     def n(self) -> int:
@@ -64,11 +66,15 @@ class _Emitter:
         self.ta: List[int] = []
         self.tf: List[int] = []
         self.t = 0
+        self.phase = 0                       # the computation phase the events that follow belong to
+        self.ps: List[int] = []
+        self.pe: List[int] = []
         self._pending: List[List[int]] = []  # [remaining further allocations, id]
 
     def free(self, rid: int) -> None:
         assert self.tf[rid] < 0
         self.tf[rid] = self.t
+        self.pe[rid] = self.phase
         self.t += 1
 
     def _age_pending(self) -> None:
@@ -89,6 +95,8 @@ class _Emitter:
         self.size.append(_round_up(size))
         self.ta.append(self.t)
         self.tf.append(-1)
+        self.ps.append(self.phase)
+        self.pe.append(-1)
         self.t += 1
         return rid
 
@@ -115,6 +123,8 @@ class _Emitter:
             t_free=np.asarray(self.tf, dtype=np.uint32),
             t_end=self.t,
             meta=meta,
+            p_alloc=np.asarray(self.ps, dtype=np.uint32),
+            p_free=np.asarray(self.pe, dtype=np.uint32),
         )
 
 
@@ -242,8 +252,14 @@ def _make_multi(cfg_id: int) -> Trace:
     tf = np.concatenate(tf) // c.quantum
     tf = np.maximum(tf, ta + 1)                 # a lifetime shorter than the clock's tick still holds its memory for one
     meta = {"cfg": cfg_id, "description": c.description, "n_orderings": c.n_orderings, "seed": BASE_SEED + cfg_id}
+    # phases: 0 = before the first iteration, then the base trace's phases once per iteration, then one for the end
+    per_it = int(base.p_free.max()) + 1
+    ps = [np.zeros(c.persistent, np.int64)] + [base.p_alloc.astype(np.int64) + 1 + it * per_it for it in range(c.iterations)]
+    pe = [np.full(c.persistent, 1 + c.iterations * per_it, np.int64)] + \
+         [base.p_free.astype(np.int64) + 1 + it * per_it for it in range(c.iterations)]
     return Trace(name=c.name, size=size, t_alloc=ta.astype(np.uint32), t_free=tf.astype(np.uint32),
-                 t_end=int(tf.max()), meta=meta)
+                 t_end=int(tf.max()), meta=meta, p_alloc=np.concatenate(ps).astype(np.uint32),
+                 p_free=np.concatenate(pe).astype(np.uint32))
 
 
 def make_trace(cfg_id: int) -> Trace:
@@ -364,6 +380,7 @@ def make_trace(cfg_id: int) -> Trace:
             last_backward_of_chunk[ch] = idx
 
     for idx, (ph, mb, ch) in enumerate(schedule):
+        em.phase = idx                               # one phase per forward / backward pass of the schedule
         layers = range(ch * c.layers_per_chunk, (ch + 1) * c.layers_per_chunk)
         if ph == "F":
             for layer in layers:
@@ -375,6 +392,7 @@ def make_trace(cfg_id: int) -> Trace:
                 persistent_until_end.append(em.alloc(25 * 2 ** 20))   # gradient bucket
 
     # optimizer step
+    em.phase = len(schedule)
     if c.kind == "tiny":
         for _layer in range(c.layers_per_chunk):
             for _ in range(12):
