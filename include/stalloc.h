@@ -69,7 +69,7 @@ typedef struct stalloc_trace {
  *
  * For plan p the requests are taken in the order orders[p][0..n-1]; each one gets
  * the lowest address at which it conflicts with no request placed before it in
- * that plan ("lowest available address", Sec. 5.1; large-first orders let small
+ * that plan (the lowest-fit rule of Sec. 5.1; large-first orders let small
  * requests fill the unused intervals of larger ones, Sec. 5.1 Global Planning).
  * For a given trace and order the result is unique.
  *
@@ -248,6 +248,48 @@ int stalloc_tmp(const stalloc_trace *trace, const uint64_t *extents, uint32_t P,
  */
 int stalloc_make_orders(const stalloc_trace *trace, uint32_t first_plan, uint32_t P, uint64_t seed,
                         uint32_t *orders, uint32_t *device_status,
+                        void *workspace, size_t *workspace_bytes, void *hip_stream);
+
+/*
+ * Candidate fusions of HomoPhase groups, k of them at once (Sec. 5.1, HomoPhase Group Planning;
+ * the accept test compares time-memory products, Eq. 2).
+ *
+ * A HomoPhase group holds the requests that are allocated in one computation phase and released
+ * in one other phase; its local plan packs them contiguously, so that plan's extent is the sum
+ * of their sizes.  Two plans are fused by inserting the smaller (by extent; the second if equal)
+ * into the larger: the larger plan's requests are packed from address 0 in descending order of
+ * release time (request number among equals); an address pointer starts at the lowest start
+ * address of the larger plan; the smaller plan's requests are tried in order of allocation time
+ * (request number among equals), the first that conflicts with nothing placed so far when put at
+ * the pointer is placed there and the pointer moves up by its size; if none fits, the pointer
+ * moves to the next higher start address of the larger plan; when there is none, the requests
+ * still left are packed on top of everything placed, in the same order.  The fusion is accepted
+ * when the fused plan's time-memory product exceeds the average of the two plans' products
+ * weighted by the memory-time each reserves (extent times span from first allocation to last
+ * release), which is the case exactly if the fused plan reserves less memory-time than the two
+ * plans together; the comparison is made in exact integers.
+ *
+ *   members       device [m]: the request numbers of all pairs, pair after pair; pair p owns
+ *                 members[pair_begin[p] .. pair_begin[p+1]), its first group's requests first.
+ *                 The requests of one pair must be distinct (not detected: the result is then
+ *                 unspecified, but memory-safe); an entry >= n sets device_status to
+ *                 STALLOC_ERR_BAD_ORDER.
+ *   pair_begin    device [k+1], ascending, pair_begin[0] = 0.
+ *   count1        device [k]: how many of pair p's requests belong to its first group; both
+ *                 groups must be non-empty (else device_status = STALLOC_ERR_INVALID_ARG).
+ *   largest_pair  the largest pair_begin[p+1] - pair_begin[p]; a pair lives in one workgroup's
+ *                 LDS (32 bytes per request): beyond about 5000 requests the call returns
+ *                 STALLOC_ERR_TOO_LARGE; a pair larger than largest_pair sets device_status to it.
+ *   order         device [m]: per pair, the request numbers in the fused plan's order: the larger
+ *                 group's in packing order, then the smaller group's by allocation time.
+ *   addr          device [m]: the addresses of those requests in the fused plan.
+ *   extents       device [k][3]: extent of plan 1, of plan 2, of the fused plan.
+ *   accepted      device [k]: 1 if the fusion is accepted, else 0.
+ * Outputs of a pair are written only when device_status stays STALLOC_OK up to its turn.
+ */
+int stalloc_fuse_groups(const stalloc_trace *trace, const uint32_t *members, const uint32_t *pair_begin,
+                        const uint32_t *count1, uint32_t k, uint32_t largest_pair, uint32_t *order,
+                        uint64_t *addr, uint64_t *extents, uint32_t *accepted, uint32_t *device_status,
                         void *workspace, size_t *workspace_bytes, void *hip_stream);
 
 /*

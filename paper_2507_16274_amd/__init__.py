@@ -26,7 +26,8 @@ STATIC_MAX_T_END = 524288        # STALLOC_STATIC_MAX_T_END of include/stalloc.h
 EXPORTS = ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_lower_bound_static",
            "stalloc_reusable_space",
            "stalloc_memory_layers", "stalloc_expand_layers", "stalloc_tmp", "stalloc_make_orders",
-           "stalloc_status_string", "stalloc_plan_lds_capacity", "stalloc_plan_report", "stalloc_probe")
+           "stalloc_status_string", "stalloc_plan_lds_capacity", "stalloc_plan_report", "stalloc_probe",
+           "stalloc_fuse_groups")
 KERNELS = {0: "none", 1: "bitmap", 2: "list_lds", 3: "list_memory", 4: "long_list"}
 
 
@@ -64,9 +65,10 @@ def _load() -> ctypes.CDLL:
     lib.stalloc_expand_layers.argtypes = [u32, u32, vp, vp, u32, vp, vp, vp]
     lib.stalloc_tmp.argtypes = [tp, vp, u32, vp, vp, vp, szp, vp]
     lib.stalloc_make_orders.argtypes = [tp, u32, u32, ctypes.c_uint64, vp, vp, vp, szp, vp]
+    lib.stalloc_fuse_groups.argtypes = [tp, vp, vp, vp, u32, u32, vp, vp, vp, vp, vp, vp, szp, vp]
     for name in ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_lower_bound_static",
                  "stalloc_reusable_space", "stalloc_memory_layers", "stalloc_expand_layers", "stalloc_tmp",
-                 "stalloc_make_orders"):
+                 "stalloc_make_orders", "stalloc_fuse_groups"):
         getattr(lib, name).restype = ctypes.c_int
     lib.stalloc_plan_report.argtypes = [vp, ctypes.POINTER(_PlanInfo), vp]
     lib.stalloc_plan_report.restype = ctypes.c_int
@@ -321,6 +323,30 @@ def stalloc_tmp(size, t_alloc, t_free, t_end: int, extents, *, stream=None,
     ws = _workspace(need.value, dev, workspace_cache)
     have = ctypes.c_size_t(ws.numel())
     _check(lib.stalloc_tmp(*args, ws.data_ptr(), ctypes.byref(have), _stream(stream)), "stalloc_tmp")
+    out["workspace"] = ws
+    return out
+
+
+def stalloc_fuse_groups(size, t_alloc, t_free, t_end: int, members, pair_begin, count1, largest_pair: int, *,
+                        stream=None, workspace_cache: Optional[Dict] = None) -> Dict[str, torch.Tensor]:
+    """members int32 [m], pair_begin int32 [k+1], count1 int32 [k], largest_pair = the largest pair's size ->
+    order int32 [m], addr int64 [m], extents int64 [k][3], accepted int32 [k], status int32 [1]."""
+    tr = _trace(size, t_alloc, t_free, t_end)
+    k, m, dev = count1.numel(), members.numel(), size.device
+    if pair_begin.numel() != k + 1:
+        raise ValueError("pair_begin must hold k + 1 entries")
+    out = {"order": torch.empty(m, dtype=torch.int32, device=dev), "addr": torch.empty(m, dtype=torch.int64, device=dev),
+           "extents": torch.empty((k, 3), dtype=torch.int64, device=dev),
+           "accepted": torch.empty(k, dtype=torch.int32, device=dev),
+           "status": torch.empty(1, dtype=torch.int32, device=dev)}
+    args = (ctypes.byref(tr), _dev(members, torch.int32, "members"), _dev(pair_begin, torch.int32, "pair_begin"),
+            _dev(count1, torch.int32, "count1"), k, int(largest_pair), out["order"].data_ptr(), out["addr"].data_ptr(),
+            out["extents"].data_ptr(), out["accepted"].data_ptr(), out["status"].data_ptr())
+    need = ctypes.c_size_t(0)
+    _check(lib.stalloc_fuse_groups(*args, None, ctypes.byref(need), None), "stalloc_fuse_groups(workspace query)")
+    ws = _workspace(need.value, dev, workspace_cache)
+    have = ctypes.c_size_t(ws.numel())
+    _check(lib.stalloc_fuse_groups(*args, ws.data_ptr(), ctypes.byref(have), _stream(stream)), "stalloc_fuse_groups")
     out["workspace"] = ws
     return out
 
