@@ -97,7 +97,9 @@ int stalloc_plan(const stalloc_trace *trace, const uint32_t *orders, uint32_t P,
 /*
  * Pairwise check of the constraint of Sec. 5.1 for P plans of one trace.
  *
- *   offsets     device [P][n]
+ *   offsets     device [P][n].  offsets + size must stay below 2^64 for every request of every
+ *               plan: a range that would wrap sets device_status to STALLOC_ERR_OVERFLOW (it is
+ *               then counted as reaching up to 2^64 - 1)
  *   conflicts   device [P], number of unordered pairs (i, j) whose lifetimes
  *               overlap and whose address ranges overlap
  *   first_pair  device [P][2], the lexicographically first such pair with i < j,

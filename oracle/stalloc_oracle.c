@@ -420,11 +420,16 @@ int oracle_reusable_space(uint32_t n, const uint64_t *size, const uint32_t *t_s,
  * Memory-layer construction for the HomoSize groups of a trace (Sec. 5.1,
  * HomoSize Group Planning, Algorithm 1).  A HomoSize group M_s holds the requests of
  * one size S; requests of a group whose lifetimes do not overlap can share one
- * range of S bytes, a memory-layer.  The group's requests are taken by allocation
- * time; each goes to the layer whose last request ends latest among the layers that
- * are free at its allocation time, so that the layer idles least; if no layer is
- * free a new one is opened.  The request becomes the layer's last one and the
- * layer's end becomes its free time.
+ * range of S bytes, a memory-layer.  The rule of Algorithm 1: a group's requests are
+ * taken by allocation time; each goes, among the layers that are free at its allocation
+ * time, to the one that became free last, so that the layer idles least; if no layer is
+ * free a new one is opened.
+ *
+ * Written here as a sweep over the group's events in time order instead of a search over
+ * the layers per request: a layer becomes free when the request it holds is released, so
+ * the free layers, kept in the order in which they became free, form a pile whose top is
+ * "the free layer with the latest end"; a release puts its layer on the pile, an
+ * allocation takes the top or opens a new layer when the pile is empty.
  *
  * Output: layer_of[i] = layer of request i.  Layers are numbered group by group in
  * descending size (the order in which the global plan takes the groups) and, inside
@@ -433,19 +438,34 @@ int oracle_reusable_space(uint32_t n, const uint64_t *size, const uint32_t *t_s,
  * rectangle the layer occupies when it is planned as one request (as the local plan
  * of a group is, Sec. 5.1).  *n_layers = number of layers.
  *
- * Readings: lifetimes are half-open, so a layer whose last request is released at t
- * is free for a request allocated at t (the listing prints a strict comparison for
- * closed lifetimes); requests with equal allocation times are taken by request
- * number; among free layers with equal ends the one opened first is taken.
+ * Readings: lifetimes are half-open, so a layer whose request is released at t is free
+ * for a request allocated at t (releases at t come before allocations at t; the listing
+ * prints a strict comparison for closed lifetimes); requests with equal allocation times
+ * are taken by request number; of layers that become free at the same time the one
+ * opened first is taken first.
  */
-typedef struct { uint64_t size; uint32_t t_s; uint32_t id; } layer_key_t;
+typedef struct { uint64_t size; uint32_t id; } layer_member_t;
+typedef struct { uint32_t t; uint32_t is_alloc; uint32_t id; } layer_event_t;
 
-static int by_size_desc_then_start(const void *pa, const void *pb)
+static int by_size_desc(const void *pa, const void *pb)
 {
-    const layer_key_t *x = (const layer_key_t *)pa, *y = (const layer_key_t *)pb;
+    const layer_member_t *x = (const layer_member_t *)pa, *y = (const layer_member_t *)pb;
     if (x->size != y->size) return x->size > y->size ? -1 : 1;
-    if (x->t_s != y->t_s) return x->t_s < y->t_s ? -1 : 1;
     return x->id < y->id ? -1 : (x->id > y->id ? 1 : 0);
+}
+
+static int by_time_release_first(const void *pa, const void *pb)
+{
+    const layer_event_t *x = (const layer_event_t *)pa, *y = (const layer_event_t *)pb;
+    if (x->t != y->t) return x->t < y->t ? -1 : 1;
+    if (x->is_alloc != y->is_alloc) return x->is_alloc < y->is_alloc ? -1 : 1;
+    return x->id < y->id ? -1 : (x->id > y->id ? 1 : 0);
+}
+
+static int descending_u32(const void *pa, const void *pb)
+{
+    const uint32_t x = *(const uint32_t *)pa, y = *(const uint32_t *)pb;
+    return (x < y) - (x > y);
 }
 
 int oracle_memory_layers(uint32_t n, const uint64_t *size, const uint32_t *t_s,
@@ -454,27 +474,50 @@ int oracle_memory_layers(uint32_t n, const uint64_t *size, const uint32_t *t_s,
 {
     if (n == 0 || !size || !t_s || !t_e || !layer_of || !n_layers || !layer_size || !layer_t_s || !layer_t_e)
         return ORC_INVALID_ARG;
-    layer_key_t *m = (layer_key_t *)malloc((size_t)n * sizeof(layer_key_t));
-    if (!m) return ORC_NOMEM;
-    for (uint32_t i = 0; i < n; ++i) { m[i].size = size[i]; m[i].t_s = t_s[i]; m[i].id = i; }
-    qsort(m, n, sizeof(layer_key_t), by_size_desc_then_start);
+    layer_member_t *m = (layer_member_t *)malloc((size_t)n * sizeof(layer_member_t));
+    layer_event_t *ev = (layer_event_t *)malloc((size_t)n * 2 * sizeof(layer_event_t));
+    uint32_t *pile = (uint32_t *)malloc((size_t)n * sizeof(uint32_t));      /* free layers, freed last on top */
+    uint32_t *freed = (uint32_t *)malloc((size_t)n * sizeof(uint32_t));     /* layers freed at the current time */
+    if (!m || !ev || !pile || !freed) { free(m); free(ev); free(pile); free(freed); return ORC_NOMEM; }
+    for (uint32_t i = 0; i < n; ++i) { m[i].size = size[i]; m[i].id = i; }
+    qsort(m, n, sizeof(layer_member_t), by_size_desc);
     uint32_t layers = 0;                       /* layers opened so far, over all groups */
-    uint32_t group_first = 0;                  /* first layer of the current group */
-    for (uint32_t k = 0; k < n; ++k) {
-        if (k > 0 && m[k].size != m[k - 1].size) group_first = layers;      /* next HomoSize group */
-        const uint32_t i = m[k].id;
-        int64_t best = -1;
-        for (uint32_t l = group_first; l < layers; ++l)
-            if (layer_t_e[l] <= t_s[i] && (best < 0 || layer_t_e[l] > layer_t_e[best])) best = l;
-        if (best < 0) {
-            best = layers++;
-            layer_size[best] = size[i];
-            layer_t_s[best] = t_s[i];
+    for (uint32_t g0 = 0; g0 < n; ) {
+        uint32_t g1 = g0;                      /* the HomoSize group m[g0 .. g1) */
+        while (g1 < n && m[g1].size == m[g0].size) ++g1;
+        const uint32_t members = g1 - g0;
+        for (uint32_t k = 0; k < members; ++k) {
+            const uint32_t i = m[g0 + k].id;
+            ev[2 * k].t = t_s[i]; ev[2 * k].is_alloc = 1; ev[2 * k].id = i;
+            ev[2 * k + 1].t = t_e[i]; ev[2 * k + 1].is_alloc = 0; ev[2 * k + 1].id = i;
         }
-        layer_of[i] = (uint32_t)best;
-        layer_t_e[best] = t_e[i];
+        qsort(ev, 2 * (size_t)members, sizeof(layer_event_t), by_time_release_first);
+        uint32_t on_pile = 0;                  /* every group starts with no layer */
+        for (uint32_t e = 0; e < 2 * members; ) {
+            /* the releases of this instant: their layers go on the pile, the one opened first on top */
+            uint32_t k = 0;
+            const uint32_t now = ev[e].t;
+            while (e < 2 * members && ev[e].t == now && !ev[e].is_alloc) freed[k++] = layer_of[ev[e++].id];
+            qsort(freed, k, sizeof(uint32_t), descending_u32);
+            for (uint32_t q = 0; q < k; ++q) pile[on_pile++] = freed[q];
+            /* the allocations of this instant, by request number */
+            while (e < 2 * members && ev[e].t == now && ev[e].is_alloc) {
+                const uint32_t i = ev[e++].id;
+                uint32_t l;
+                if (on_pile > 0) {
+                    l = pile[--on_pile];
+                } else {
+                    l = layers++;
+                    layer_size[l] = size[i];
+                    layer_t_s[l] = t_s[i];
+                }
+                layer_of[i] = l;
+                layer_t_e[l] = t_e[i];
+            }
+        }
+        g0 = g1;
     }
-    free(m);
+    free(m); free(ev); free(pile); free(freed);
     *n_layers = layers;
     return ORC_OK;
 }

@@ -5,9 +5,10 @@
 // alive at each timestamp (half-open lifetimes: a release at t is already gone at t);
 // the answer is the maximum and the earliest timestamp reaching it.
 //
-// Kernels: clear -> scatter (64-bit atomics, integer adds commute so the result is
-// exact) -> per-tile sums -> scan of tile sums (one workgroup) -> per-tile running
-// sum + maximum -> final reduction (one workgroup).
+// Three launches: lb_clear (net changes, accumulators, status) -> lb_scatter (64-bit atomics,
+// integer adds commute so the result is exact; the sanity pass over the trace rides along) ->
+// lb_tiles (per tile of timestamps: sum, and maximum of the running sum counted from the tile's
+// start; the workgroup that finishes last adds the tiles up and writes the answer and the status).
 #include "host_util.h"
 #include "wave.h"
 
@@ -16,6 +17,7 @@ namespace stalloc {
 constexpr int kLbThreads = 256;
 constexpr int kLbPerThread = 16;
 constexpr int kLbTile = kLbThreads * kLbPerThread;
+constexpr int kLbAccDone = 10;                 // word of the accumulators that counts finished tiles
 
 struct LbBest {
     int64_t live;
@@ -28,91 +30,49 @@ __device__ __forceinline__ bool lb_better(int64_t live_a, uint32_t t_a, int64_t 
     return live_a > live_b || (live_a == live_b && t_a < t_b);
 }
 
-__global__ void __launch_bounds__(kLbThreads) lb_clear(int64_t* net, uint32_t len)
+__global__ void __launch_bounds__(kLbThreads) lb_clear(int64_t* net, uint32_t len, uint64_t* acc, uint32_t* status)
 {
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < len; i += gridDim.x * blockDim.x) net[i] = 0;
+    if (blockIdx.x == 0 && threadIdx.x < kAccWords) acc[threadIdx.x] = 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) *status = STALLOC_OK;
 }
 
+// Net changes per timestamp, and the trace's sanity on the way: acc[0], acc[1] = sums of the high
+// and low halves of the sizes, acc[2] = 1 if a request is malformed.
 __global__ void __launch_bounds__(kLbThreads)
 lb_scatter(const uint64_t* __restrict__ size, const uint32_t* __restrict__ ta, const uint32_t* __restrict__ tf,
-           uint32_t n, uint32_t t_end, int64_t* net)
+           uint32_t n, uint32_t t_end, int64_t* net, uint64_t* acc)
 {
+    __shared__ uint64_t part[kLbThreads / kWave][3];
+    uint64_t hi = 0, lo = 0;
+    uint32_t bad = 0;
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
         uint64_t s = size[i];
         uint32_t a = ta[i], f = tf[i];
-        if (a < f && f <= t_end) {   // malformed requests are reported by the trace check; never index out of range
+        bad |= (s == 0) | (a >= f) | (f > t_end);
+        hi += s >> 32;               // n < 2^31 terms below 2^32 each: cannot wrap
+        lo += s & 0xffffffffull;
+        if (a < f && f <= t_end) {   // malformed requests are reported; never index out of range
             atomicAdd((unsigned long long*)&net[a], (unsigned long long)s);
             atomicAdd((unsigned long long*)&net[f], (unsigned long long)(0 - s));
         }
     }
-}
-
-// Block-wide sum of one int64 per thread; result valid in every thread.
-__device__ __forceinline__ int64_t block_sum(int64_t v, int64_t* lds)
-{
-    int64_t w = (int64_t)wave_sum64((uint64_t)v);
+    hi = wave_sum64(hi);
+    lo = wave_sum64(lo);
+    uint64_t any_bad = __builtin_amdgcn_ballot_w64(bad != 0);
+    if (lane_id() == 0) { part[wave_id()][0] = hi; part[wave_id()][1] = lo; part[wave_id()][2] = any_bad ? 1 : 0; }
     __syncthreads();
-    if (lane_id() == 0) lds[wave_id()] = w;
-    __syncthreads();
-    int64_t tot = 0;
-    for (int k = 0; k < kLbThreads / kWave; ++k) tot += lds[k];
-    return tot;
-}
-
-__global__ void __launch_bounds__(kLbThreads)
-lb_tile_sums(const int64_t* __restrict__ net, uint32_t t_end, int64_t* tile_sum)
-{
-    __shared__ int64_t lds[kLbThreads / kWave];
-    uint32_t base = blockIdx.x * kLbTile;
-    int64_t acc = 0;
-    for (int j = 0; j < kLbPerThread; ++j) {
-        uint32_t t = base + j * kLbThreads + threadIdx.x;
-        if (t < t_end) acc += net[t];
-    }
-    int64_t tot = block_sum(acc, lds);
-    if (threadIdx.x == 0) tile_sum[blockIdx.x] = tot;
-}
-
-// Exclusive scan of the tile sums, in place, by one workgroup.
-__global__ void __launch_bounds__(kLbThreads) lb_scan_tiles(int64_t* tile_sum, uint32_t tiles)
-{
-    __shared__ int64_t lds[kLbThreads];
-    int64_t carry = 0;
-    for (uint32_t base = 0; base < tiles; base += kLbThreads) {
-        uint32_t k = base + threadIdx.x;
-        int64_t v = k < tiles ? tile_sum[k] : 0;
-        lds[threadIdx.x] = v;
-        __syncthreads();
-        for (int d = 1; d < kLbThreads; d <<= 1) {
-            int64_t add = threadIdx.x >= (uint32_t)d ? lds[threadIdx.x - d] : 0;
-            __syncthreads();
-            lds[threadIdx.x] += add;
-            __syncthreads();
-        }
-        int64_t incl = lds[threadIdx.x];
-        int64_t total = lds[kLbThreads - 1];
-        if (k < tiles) tile_sum[k] = carry + incl - v;
-        carry += total;
-        __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kLbThreads / kWave; ++w) { hi += part[w][0]; lo += part[w][1]; any_bad |= part[w][2]; }
+        atomicAdd((unsigned long long*)&acc[0], (unsigned long long)hi);
+        atomicAdd((unsigned long long*)&acc[1], (unsigned long long)lo);
+        if (any_bad) atomicOr((unsigned long long*)&acc[2], 1ull);
     }
 }
 
-__global__ void __launch_bounds__(kLbThreads)
-lb_tile_max(const int64_t* __restrict__ net, uint32_t t_end, const int64_t* __restrict__ tile_prefix, LbBest* tile_best)
+// Inclusive sums over the workgroup's threads, in place in lds[kLbThreads].
+__device__ __forceinline__ void block_scan(int64_t* lds)
 {
-    __shared__ int64_t lds[kLbThreads];
-    __shared__ LbBest best_lds[kLbThreads / kWave];
-    // thread owns kLbPerThread consecutive timestamps
-    uint32_t t0 = blockIdx.x * kLbTile + threadIdx.x * kLbPerThread;
-    int64_t v[kLbPerThread];
-    int64_t mine = 0;
-#pragma unroll
-    for (int j = 0; j < kLbPerThread; ++j) {
-        uint32_t t = t0 + j;
-        v[j] = t < t_end ? net[t] : 0;
-        mine += v[j];
-    }
-    lds[threadIdx.x] = mine;
     __syncthreads();
     for (int d = 1; d < kLbThreads; d <<= 1) {
         int64_t add = threadIdx.x >= (uint32_t)d ? lds[threadIdx.x - d] : 0;
@@ -120,53 +80,97 @@ lb_tile_max(const int64_t* __restrict__ net, uint32_t t_end, const int64_t* __re
         lds[threadIdx.x] += add;
         __syncthreads();
     }
-    int64_t live = tile_prefix[blockIdx.x] + lds[threadIdx.x] - mine;   // bytes alive just before t0
-    int64_t best = -1;
-    uint32_t best_t = 0xffffffffu;
-#pragma unroll
-    for (int j = 0; j < kLbPerThread; ++j) {
-        uint32_t t = t0 + j;
-        live += v[j];
-        if (t < t_end && lb_better(live, t, best, best_t)) { best = live; best_t = t; }
-    }
-    // reduce (best, best_t) over the block: pack-free two-step (max live, then min t among holders)
-    uint64_t wmax = wave_max64((uint64_t)(best + 1));                 // best >= -1, so best + 1 >= 0
-    uint64_t cand_t = ((uint64_t)(best + 1) == wmax) ? (uint64_t)best_t : ~0ull;
-    uint64_t wt = wave_min64(cand_t);
-    if (lane_id() == 0) { best_lds[wave_id()].live = (int64_t)wmax - 1; best_lds[wave_id()].t = (uint32_t)wt; }
+}
+
+// The best (live, t) over the workgroup (largest live, earliest t among equals), valid in thread 0.
+__device__ __forceinline__ LbBest block_best(int64_t best, uint32_t best_t, LbBest* best_lds)
+{
+    const uint64_t key = (uint64_t)best ^ (1ull << 63);               // order of int64 as unsigned
+    const uint64_t wmax = wave_max64(key);
+    const uint64_t wt = wave_min64(key == wmax ? (uint64_t)best_t : ~0ull);
+    if (lane_id() == 0) { best_lds[wave_id()].live = (int64_t)(wmax ^ (1ull << 63)); best_lds[wave_id()].t = (uint32_t)wt; }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        LbBest b = best_lds[0];
-        for (int k = 1; k < kLbThreads / kWave; ++k)
-            if (lb_better(best_lds[k].live, best_lds[k].t, b.live, b.t)) b = best_lds[k];
-        b.pad = 0;
-        tile_best[blockIdx.x] = b;
-    }
+    LbBest b = best_lds[0];
+    for (int k = 1; k < kLbThreads / kWave; ++k)
+        if (lb_better(best_lds[k].live, best_lds[k].t, b.live, b.t)) b = best_lds[k];
+    b.pad = 0;
+    return b;
+}
+
+__device__ __forceinline__ int64_t load_coherent(const int64_t* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __global__ void __launch_bounds__(kLbThreads)
-lb_final(const LbBest* __restrict__ tile_best, uint32_t tiles, uint64_t* lower_bound, uint32_t* t_at_max)
+lb_tiles(const int64_t* __restrict__ net, uint32_t t_end, int64_t* tile_sum, LbBest* tile_best, uint64_t* acc,
+         uint64_t* lower_bound, uint32_t* t_at_max, uint32_t* status)
 {
+    __shared__ int64_t lds[kLbThreads];
     __shared__ LbBest best_lds[kLbThreads / kWave];
-    int64_t best = -1;
-    uint32_t best_t = 0xffffffffu;
-    for (uint32_t k = threadIdx.x; k < tiles; k += kLbThreads) {
-        LbBest b = tile_best[k];
-        if (lb_better(b.live, b.t, best, best_t)) { best = b.live; best_t = b.t; }
+    __shared__ uint32_t finished_before;
+    // thread owns kLbPerThread consecutive timestamps
+    const uint32_t t0 = blockIdx.x * kLbTile + threadIdx.x * kLbPerThread;
+    int64_t v[kLbPerThread];
+    int64_t mine = 0;
+#pragma unroll
+    for (int j = 0; j < kLbPerThread; ++j) {
+        const uint32_t t = t0 + j;
+        v[j] = t < t_end ? net[t] : 0;
+        mine += v[j];
     }
-    uint64_t wmax = wave_max64((uint64_t)(best + 1));
-    uint64_t cand_t = ((uint64_t)(best + 1) == wmax) ? (uint64_t)best_t : ~0ull;
-    uint64_t wt = wave_min64(cand_t);
-    if (lane_id() == 0) { best_lds[wave_id()].live = (int64_t)wmax - 1; best_lds[wave_id()].t = (uint32_t)wt; }
-    __syncthreads();
+    lds[threadIdx.x] = mine;
+    block_scan(lds);
+    int64_t live = lds[threadIdx.x] - mine;                            // running sum from the tile's start, before t0
+    const int64_t tile_total = lds[kLbThreads - 1];
+    int64_t best = INT64_MIN;
+    uint32_t best_t = 0xffffffffu;
+#pragma unroll
+    for (int j = 0; j < kLbPerThread; ++j) {
+        const uint32_t t = t0 + j;
+        live += v[j];
+        if (t < t_end && lb_better(live, t, best, best_t)) { best = live; best_t = t; }
+    }
+    const LbBest b = block_best(best, best_t, best_lds);
     if (threadIdx.x == 0) {
-        LbBest b = best_lds[0];
-        for (int k = 1; k < kLbThreads / kWave; ++k)
-            if (lb_better(best_lds[k].live, best_lds[k].t, b.live, b.t)) b = best_lds[k];
+        tile_sum[blockIdx.x] = tile_total;
+        tile_best[blockIdx.x] = b;
+        __threadfence();
+        finished_before = (uint32_t)atomicAdd((unsigned long long*)&acc[kLbAccDone], 1ull);
+    }
+    __syncthreads();
+    if (finished_before != gridDim.x - 1) return;
+    // the last tile to finish: bytes alive at a tile's start = sum of the tiles before it
+    __threadfence();
+    int64_t carry = 0;
+    best = INT64_MIN;
+    best_t = 0xffffffffu;
+    for (uint32_t base = 0; base < gridDim.x; base += kLbThreads) {
+        const uint32_t k = base + threadIdx.x;
+        const int64_t sum = k < gridDim.x ? load_coherent(&tile_sum[k]) : 0;
+        __syncthreads();
+        lds[threadIdx.x] = sum;
+        block_scan(lds);
+        if (k < gridDim.x) {
+            const int64_t cand = carry + lds[threadIdx.x] - sum + load_coherent(&tile_best[k].live);
+            const uint32_t cand_t = __hip_atomic_load(&tile_best[k].t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (lb_better(cand, cand_t, best, best_t)) { best = cand; best_t = cand_t; }
+        }
+        carry += lds[kLbThreads - 1];
+    }
+    __syncthreads();
+    LbBest all = block_best(best, best_t, best_lds);
+    if (threadIdx.x == 0) {
         // a maximum of zero live bytes is reported at t = 0
-        if (b.live <= 0) { b.live = 0; b.t = 0; }
-        *lower_bound = (uint64_t)b.live;
-        if (t_at_max) *t_at_max = b.t;
+        if (all.live <= 0) { all.live = 0; all.t = 0; }
+        *lower_bound = (uint64_t)all.live;
+        if (t_at_max) *t_at_max = all.t;
+        // total = acc[0] * 2^32 + acc[1]  >= 2^63  <=>  acc[0] + (acc[1] >> 32) >= 2^31
+        const uint64_t hi = acc[0], lo = acc[1];
+        uint32_t code = STALLOC_OK;
+        if (hi + (lo >> 32) >= (1ull << 31)) code = STALLOC_ERR_OVERFLOW;
+        if (acc[2] & 1ull) code = STALLOC_ERR_BAD_TRACE;
+        if (code != STALLOC_OK) atomicMax(status, code);
     }
 }
 
@@ -194,19 +198,15 @@ static int enqueue_lower_bound(const stalloc_trace& tr, uint64_t* lower_bound, u
                                uint32_t* device_status, const LbScratch& sc, hipStream_t stream)
 {
     const uint32_t t_end = tr.t_end;
-    launch_trace_check(tr, sc.acc, device_status, stream);
     uint32_t clear_blocks = (t_end + 1 + kLbThreads - 1) / kLbThreads;
     if (clear_blocks > 4096) clear_blocks = 4096;
-    hipLaunchKernelGGL(lb_clear, dim3(clear_blocks), dim3(kLbThreads), 0, stream, sc.net, t_end + 1);
+    hipLaunchKernelGGL(lb_clear, dim3(clear_blocks), dim3(kLbThreads), 0, stream, sc.net, t_end + 1, sc.acc, device_status);
     uint32_t sc_blocks = (tr.n + kLbThreads - 1) / kLbThreads;
     if (sc_blocks > 4096) sc_blocks = 4096;
     hipLaunchKernelGGL(lb_scatter, dim3(sc_blocks), dim3(kLbThreads), 0, stream, tr.size, tr.t_alloc, tr.t_free,
-                       tr.n, t_end, sc.net);
-    hipLaunchKernelGGL(lb_tile_sums, dim3(sc.tiles), dim3(kLbThreads), 0, stream, sc.net, t_end, sc.tile_sum);
-    hipLaunchKernelGGL(lb_scan_tiles, dim3(1), dim3(kLbThreads), 0, stream, sc.tile_sum, sc.tiles);
-    hipLaunchKernelGGL(lb_tile_max, dim3(sc.tiles), dim3(kLbThreads), 0, stream, sc.net, t_end, sc.tile_sum,
-                       sc.tile_best);
-    hipLaunchKernelGGL(lb_final, dim3(1), dim3(kLbThreads), 0, stream, sc.tile_best, sc.tiles, lower_bound, t_at_max);
+                       tr.n, t_end, sc.net, sc.acc);
+    hipLaunchKernelGGL(lb_tiles, dim3(sc.tiles), dim3(kLbThreads), 0, stream, sc.net, t_end, sc.tile_sum, sc.tile_best,
+                       sc.acc, lower_bound, t_at_max, device_status);
     return hipGetLastError() == hipSuccess ? STALLOC_OK : STALLOC_ERR_DEVICE;
 }
 
@@ -261,7 +261,7 @@ extern "C" int stalloc_lower_bound_static(const stalloc_trace* tr, uint64_t* low
     if (!base) return STALLOC_ERR_DEVICE;
     const LbScratch sc(base, tr->t_end);
     if (sc.bytes > kStaticScratchBytes) return STALLOC_ERR_TOO_LARGE;
-    // every word of the scratch memory a call reads is written by that call first (the trace
-    // check resets its accumulators, lb_clear the net changes), so what the last call left is harmless
+    // every word of the scratch memory a call reads is written by that call first (lb_clear resets
+    // the net changes and the accumulators), so what the last call left is harmless
     return enqueue_lower_bound(*tr, lower_bound, t_at_max, device_status, sc, static_cast<hipStream_t>(hip_stream));
 }

@@ -53,7 +53,8 @@ constexpr int kSpThreads = 512;                  // two workgroups share a CU
 constexpr int kSpBatch = 64;                     // requests between two merges; dependency masks have 64 bits
 constexpr int kSpRefill = 128;                   // requests fetched per refill
 constexpr int kSpPool = 640;                     // short blocks the windows of one batch may hold in LDS
-constexpr int kSpWideHoles = 24;                 // holes of the list that one wave writes down for a request the workgroup settles together
+constexpr int kSpWideHoles = 6;                  // holes of its part of the list that a wave writes down for a request the workgroup settles together
+constexpr int kSpMaxWaves = 8;
 constexpr uint32_t kSpRefetch = 0xffffffffu;     // (a window whose blocks did not fit the pool is read when its request is settled)
 constexpr uint32_t kSpUnplaced = 0xffffffffu;
 constexpr uint32_t kSpLongFlag = 0x80000000u;
@@ -93,9 +94,10 @@ struct SplitLds {
     uint32_t region_min[kWave];                  // lowest start / highest end address of the placed short blocks of a
     uint32_t region_max[kWave];                  // region of ranks (64 regions cover the table)
     uint32_t reach[3];                           // window_reach: what the waves found, three calls in rotation
-    Span<uint32_t> wide_hole[kSpWideHoles];      // request with a wide window: holes of the list {end, covered}, in address order
-    uint32_t wide_holes;                         // how many there are (may exceed what is stored)
-    uint32_t wide_top;                           // highest end of the conflicting long blocks
+    // request with a wide window: every wave walks one part of the list
+    Span<uint32_t> wide_hole[kSpMaxWaves][kSpWideHoles];   // holes of that part {end, covered}, in address order
+    uint32_t wide_holes[kSpMaxWaves];            // how many there are (may exceed what is stored)
+    uint32_t wide_part_top[kSpMaxWaves];         // highest end of the conflicting long blocks of that part
     uint32_t next_plan;                          // the plan this workgroup takes next
     uint32_t extent_now;                         // extent after the last finished batch
     uint32_t peak;                               // running extent
@@ -363,21 +365,25 @@ __device__ __forceinline__ uint32_t window_reach(const SpRequest& rq, uint32_t o
                 look = false;
             }
             uint64_t open = __builtin_amdgcn_ballot_w64(look);
-            // two groups at a time, so that the reads of the second are under way while the first is looked at
+            // four groups at a time, so that the reads of the others are under way while one is looked at
             while (open) {
-                const uint32_t k0 = (g0 + (uint32_t)__builtin_ctzll(open)) * kWave + lane;    // < slots
-                open &= open - 1;
-                const bool two = open != 0;
-                const uint32_t k1 = two ? (g0 + (uint32_t)__builtin_ctzll(open)) * kWave + lane : k0;
-                open &= open - 1;
-                const uint32_t a0 = pt.addr[k0], s0 = tb.size_by_rank[k0];
-                const uint32_t a1 = pt.addr[k1], s1 = tb.size_by_rank[k1];
-                // ranks above the request's own started during its lifetime; the few below need a look at their release time
-                bool live0 = k0 >= rq.wlo && k0 < rq.whi && a0 != kSpUnplaced, live1 = two && k1 < rq.whi && a1 != kSpUnplaced;
-                if (k0 - lane <= own_rank) live0 = live0 && tb.by_rank[k0].z > rq.ta;
-                if (k1 - lane <= own_rank) live1 = live1 && k1 >= rq.wlo && tb.by_rank[k1].z > rq.ta;
-                reach = umax(reach, (live0 && a0 < cs && a0 + s0 > c) ? a0 + s0 : 0u);
-                reach = umax(reach, (live1 && a1 < cs && a1 + s1 > c) ? a1 + s1 : 0u);
+                uint32_t k[4], a[4], sz[4];
+                bool on[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    on[u] = open != 0;
+                    k[u] = on[u] ? (g0 + (uint32_t)__builtin_ctzll(open)) * kWave + lane : k[0];      // < slots
+                    open &= open - 1;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) { a[u] = pt.addr[k[u]]; sz[u] = tb.size_by_rank[k[u]]; }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    // ranks above the request's own started during its lifetime; the few below need a look at their release time
+                    bool live = on[u] && k[u] >= rq.wlo && k[u] < rq.whi && a[u] != kSpUnplaced;
+                    if (k[u] - lane <= own_rank) live = live && tb.by_rank[k[u]].z > rq.ta;
+                    reach = umax(reach, (live && a[u] < cs && a[u] + sz[u] > c) ? a[u] + sz[u] : 0u);
+                }
             }
         }
     }
@@ -483,9 +489,10 @@ __device__ __forceinline__ uint32_t settle_request(const SpList& list, uint32_t 
     return clear_others<kWide, kWaves>(rq, own_rank, run, 0xffffffffu, tb, pt, turn, sh);     // on top of every conflicting long block
 }
 
-// A request with a wide window, settled by the whole workgroup: one wave walks the list of long
-// blocks and writes down the holes that are large enough as such; then all waves try them in
-// order, sharing the look-ups in the table of short blocks.  Called by all waves.
+// A request with a wide window, settled by the whole workgroup: the waves walk one part of the
+// list of long blocks each and write down the holes that are large enough as such; then all
+// waves try them in address order, sharing the look-ups in the table of short blocks.  Called by
+// all waves.
 template <int kWaves, typename Lds>
 __device__ __forceinline__ uint32_t settle_wide(const SpList& list, uint32_t count, uint32_t b0, uint32_t q, uint64_t dep_q,
                                                 const SpBatch& bt, const SplitTables& tb, const SpTable& pt, uint32_t& turn,
@@ -501,39 +508,61 @@ __device__ __forceinline__ uint32_t settle_wide(const SpList& list, uint32_t cou
     rq.in_hi = rq.in_lo + bt.size;
     rq.rivals_w = 0; rq.w_lo = 0; rq.w_hi = 0;
     __syncthreads();                                              // the holes of the previous such request are no longer read
-    if (wave_id() == 0) {
-        uint32_t run = 0, found = 0;
-        for (uint32_t k0 = 0; k0 < count; k0 += kWave) {
+    // every wave takes one part of the list: first the highest end of its conflicting blocks ...
+    const int wave = wave_id();
+    const uint32_t steps = (count + kWave - 1) / kWave, per_wave = (steps + kWaves - 1) / kWaves;
+    const uint32_t k_begin = umin(count, (uint32_t)wave * per_wave * kWave), k_end = umin(count, k_begin + per_wave * kWave);
+    {
+        uint32_t top = 0;
+        for (uint32_t k0 = k_begin; k0 < k_end; k0 += kWave) {
             const uint32_t k = k0 + lane;
-            const bool valid = k < count;
-            const SpList::Entry en = list.load(valid ? k : count - 1);
+            const SpList::Entry en = list.load(k < k_end ? k : k_end - 1);
+            top = umax(top, (k < k_end && en.ta() < rq.tf && rq.ta < en.tf()) ? en.hi() : 0u);
+        }
+        top = read_lane(wave_scan_max(top), kWave - 1);
+        if (lane == 0) sh.wide_part_top[wave] = top;
+    }
+    __syncthreads();
+    // ... then, knowing what the parts below cover, the holes of its part that are large enough as such
+    {
+        uint32_t run = 0, found = 0;
+        for (int w = 0; w < wave; ++w) run = umax(run, sh.wide_part_top[w]);
+        for (uint32_t k0 = k_begin; k0 < k_end; k0 += kWave) {
+            const uint32_t k = k0 + lane;
+            const bool valid = k < k_end;
+            const SpList::Entry en = list.load(valid ? k : k_end - 1);
             const bool conflict = valid && en.ta() < rq.tf && rq.ta < en.tf();
             const uint32_t incl = wave_scan_max(conflict ? en.hi() : 0u);
             const uint32_t before = umax(run, wave_shift_up(incl, 0u));
             const uint64_t opens = __builtin_amdgcn_ballot_w64(conflict && en.lo() >= before && en.lo() - before >= rq.s);
             const uint32_t at = found + lanes_below(opens);
-            if (((opens >> lane) & 1) && at < (uint32_t)kSpWideHoles) sh.wide_hole[at] = Span<uint32_t>{en.lo(), before};
+            if (((opens >> lane) & 1) && at < (uint32_t)kSpWideHoles) sh.wide_hole[wave][at] = Span<uint32_t>{en.lo(), before};
             found += (uint32_t)__builtin_popcountll(opens);
             run = umax(run, read_lane(incl, kWave - 1));
         }
-        if (lane == 0) { sh.wide_holes = found; sh.wide_top = run; }
+        if (lane == 0) sh.wide_holes[wave] = found;
     }
     __syncthreads();
-    const uint32_t found = sh.wide_holes;
-    const uint32_t listed = found < (uint32_t)kSpWideHoles ? found : (uint32_t)kSpWideHoles;
-    for (uint32_t i = 0; i < listed; ++i) {
-        const Span<uint32_t> hole = sh.wide_hole[i];                  // {end, covered}
-        const uint32_t c = clear_others<true, kWaves>(rq, own_rank, hole.hi, hole.lo, tb, pt, turn, sh);
-        if (c <= hole.lo && hole.lo - c >= rq.s) return c;
+    uint32_t top = 0;
+    for (int w = 0; w < kWaves; ++w) {
+        const uint32_t found = sh.wide_holes[w];
+        const uint32_t listed = found < (uint32_t)kSpWideHoles ? found : (uint32_t)kSpWideHoles;
+        for (uint32_t i = 0; i < listed; ++i) {
+            const Span<uint32_t> hole = sh.wide_hole[w][i];           // {end, covered}
+            const uint32_t c = clear_others<true, kWaves>(rq, own_rank, hole.hi, hole.lo, tb, pt, turn, sh);
+            if (c <= hole.lo && hole.lo - c >= rq.s) return c;
+        }
+        // more holes in this part than were written down and none so far took the request: every wave walks the list
+        if (found > listed) return settle_request<true, kWaves>(list, count, b0, q, dep_q, bt, 0u, 0u, tb, pt, turn, sh);
+        top = umax(top, sh.wide_part_top[w]);
     }
-    // more holes than were written down and none of those took the request: every wave walks the list
-    if (found > listed) return settle_request<true, kWaves>(list, count, b0, q, dep_q, bt, 0u, 0u, tb, pt, turn, sh);
-    return clear_others<true, kWaves>(rq, own_rank, sh.wide_top, 0xffffffffu, tb, pt, turn, sh);
+    return clear_others<true, kWaves>(rq, own_rank, top, 0xffffffffu, tb, pt, turn, sh);
 }
 
 template <int kThreads>
 __global__ void __launch_bounds__(kThreads, 2) plan_split_kernel(PlanParams prm, SplitTables tb)
 {
+    static_assert(kThreads / kWave <= kSpMaxWaves, "a wave's part of the list has its own LDS words");
     constexpr int kWaves = kThreads / kWave;
     extern __shared__ __align__(16) unsigned char smem[];
     SplitLds& sh = *reinterpret_cast<SplitLds*>(smem);

@@ -25,7 +25,7 @@ __global__ void val_init(uint64_t* conflicts, uint64_t* first_key, uint32_t P)
 __global__ void __launch_bounds__(kValTile)
 val_pairs(const uint64_t* __restrict__ size, const uint32_t* __restrict__ ta, const uint32_t* __restrict__ tf,
           const uint64_t* __restrict__ offsets, uint32_t n, uint32_t tiles, uint32_t plan0,
-          uint64_t* conflicts, uint64_t* first_key)
+          uint64_t* conflicts, uint64_t* first_key, uint32_t* status)
 {
     __shared__ uint64_t j_lo[kValTile];
     __shared__ uint64_t j_hi[kValTile];
@@ -51,6 +51,9 @@ val_pairs(const uint64_t* __restrict__ size, const uint32_t* __restrict__ ta, co
         uint32_t j = j0 + threadIdx.x;
         bool ok = j < n;
         uint64_t o = ok ? off[j] : 0, s = ok ? size[j] : 0;
+        // an address range that would run past 2^64 is reported, and kept from wrapping so that
+        // what it covers still counts
+        if (o + s < o) { atomicMax(status, (uint32_t)STALLOC_ERR_OVERFLOW); s = ~o; }
         j_lo[threadIdx.x] = o;
         j_hi[threadIdx.x] = o + s;
         j_ta[threadIdx.x] = ok ? ta[j] : 0;
@@ -59,7 +62,8 @@ val_pairs(const uint64_t* __restrict__ size, const uint32_t* __restrict__ ta, co
     const uint32_t i = ti * kValTile + threadIdx.x;
     const bool i_ok = i < n;
     const uint64_t i_lo = i_ok ? off[i] : 0;
-    const uint64_t i_hi = i_lo + (i_ok ? size[i] : 0);
+    const uint64_t i_size = i_ok ? size[i] : 0;
+    const uint64_t i_hi = i_lo + i_size < i_lo ? ~0ull : i_lo + i_size;
     const uint32_t i_ta = i_ok ? ta[i] : 0;
     const uint32_t i_tf = i_ok ? tf[i] : 0;
     __syncthreads();
@@ -123,7 +127,8 @@ extern "C" int stalloc_validate(const stalloc_trace* tr, const uint64_t* offsets
     for (uint32_t p0 = 0; p0 < P; p0 += 32768) {          // grid.y is limited to 65535
         uint32_t py = P - p0 < 32768 ? P - p0 : 32768;
         hipLaunchKernelGGL(val_pairs, dim3((uint32_t)tri, py), dim3(kValTile), 0, stream, tr->size, tr->t_alloc,
-                           tr->t_free, offsets, tr->n, (uint32_t)tiles, p0, conflicts, first_key);
+                           tr->t_free, offsets, tr->n, (uint32_t)tiles, p0, conflicts, first_key,
+                           device_status);
     }
     hipLaunchKernelGGL(val_finish, dim3(pb), dim3(256), 0, stream, first_key, first_pair, P);
     return hipGetLastError() == hipSuccess ? STALLOC_OK : STALLOC_ERR_DEVICE;

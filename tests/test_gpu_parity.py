@@ -44,13 +44,13 @@ def _gpu_plan(S, tr, orders, **kw):
     return res
 
 
-def _gpu_validate(S, tr, offsets):
+def _gpu_validate(S, tr, offsets, want_status=0):
     import torch
     size, ta, tf = S.trace_to_device(tr)
     off = torch.from_numpy(np.ascontiguousarray(offsets).view(np.int64)).cuda()
     out = S.stalloc_validate(size, ta, tf, tr.t_end, off)
     torch.cuda.synchronize()
-    assert int(out["status"].item()) == 0
+    assert int(out["status"].item()) == want_status
     return (out["conflicts"].cpu().numpy().view(np.uint64),
             out["first_pair"].cpu().numpy().view(np.uint32))
 
@@ -150,6 +150,28 @@ def test_validate_ragged_tile_sizes(S, oracle):
         for p in range(3):
             want = oracle.validate(size, ts, te, offs[p])
             assert (int(cnt[p]), tuple(int(x) for x in pair[p])) == want
+
+
+def test_validate_reports_an_address_range_that_would_wrap(S, oracle):
+    """A corrupted plan with an address near 2^64: offset + size wraps to a small number and the block
+    would look disjoint from everything.  The call reports it and still counts what the block covers."""
+    rng = np.random.default_rng(811)
+    n = 700
+    size, ts, te, t_end = random_trace(rng, n, t_max=40, sizes=[4, 8, 12])
+    tr = _T(size, ts, te, t_end)
+    a, _ = oracle.plan_many(size, ts, te, np.arange(n, dtype=np.uint32)[None, :], threads=1, method="lists")
+    cnt, pair = _gpu_validate(S, tr, a)
+    assert int(cnt[0]) == 0
+    for victim in (0, 300, n - 1):
+        bad = np.concatenate([a, a])
+        bad[1, victim] = np.uint64(2 ** 64 - 1) - size[victim] + np.uint64(1)      # ends exactly at 2^64: wraps to 0
+        cnt, pair = _gpu_validate(S, tr, bad, want_status=3)
+        assert int(cnt[0]) == 0
+        # up to 2^64 - 1 the range is still counted: a second block planted inside it conflicts with it
+        other = int(np.flatnonzero((ts < te[victim]) & (ts[victim] < te) & (np.arange(n) != victim))[0])
+        bad[1, other] = np.uint64(2 ** 64 - 2) - size[other]
+        cnt, pair = _gpu_validate(S, tr, bad, want_status=3)
+        assert int(cnt[1]) == 1 and tuple(int(x) for x in pair[1]) == (min(victim, other), max(victim, other))
 
 
 # --------------------------------------------------------------------------- plan

@@ -96,6 +96,10 @@ def test_closed_forms(oracle):
     ts, te = np.asarray([0, 0, 5, 5], np.uint32), np.asarray([1, 3, 6, 6], np.uint32)
     layer_of, *_ = oracle.memory_layers(size, ts, te)
     assert layer_of.tolist() == [0, 1, 1, 0]
+    # two layers released at the same instant: the one opened first is taken first
+    ts, te = np.asarray([0, 0, 5, 5], np.uint32), np.asarray([3, 3, 6, 6], np.uint32)
+    layer_of, *_ = oracle.memory_layers(size, ts, te)
+    assert layer_of.tolist() == [0, 1, 0, 1]
 
 
 @pytest.mark.parametrize("seed", range(6))

@@ -31,12 +31,18 @@ MUTATIONS = {
     "idle_no_tail_interval": ("for (size_t c = 0; c <= k; ++c) {", "for (size_t c = 0; c < k; ++c) {"),
     "idle_count_capped": ("            ++found;\n            total += next - reach;", "            if (found < cap) ++found;\n            total += next - reach;"),
     "idle_needs_gap_of_two": ("if (next > reach) {", "if (next > reach + 1) {"),
-    "layer_first_free_not_latest": ("(best < 0 || layer_t_e[l] > layer_t_e[best])) best = l;", "best < 0) best = l;"),
-    "layer_needs_idle_tick": ("if (layer_t_e[l] <= t_s[i] &&", "if (layer_t_e[l] < t_s[i] &&"),
-    "layer_shared_across_groups": ("if (k > 0 && m[k].size != m[k - 1].size) group_first = layers;", "if (0) group_first = layers;"),
-    "layer_end_not_updated": ("        layer_t_e[best] = t_e[i];\n    }\n    free(m);", "        if (layer_t_e[best] < t_e[i]) layer_t_e[best] = t_e[i] - 1;\n    }\n    free(m);"),
-    "layer_groups_ascending": ("if (x->size != y->size) return x->size > y->size ? -1 : 1;", "if (x->size != y->size) return x->size > y->size ? 1 : -1;"),
-    "layer_by_number_not_start": ("if (x->t_s != y->t_s) return x->t_s < y->t_s ? -1 : 1;\n    return x->id < y->id", "return x->id < y->id"),
+    "layer_first_free_not_latest": ("l = pile[--on_pile];", "l = pile[0]; pile[0] = pile[--on_pile];"),
+    "layer_needs_idle_tick": ("if (x->is_alloc != y->is_alloc) return x->is_alloc < y->is_alloc ? -1 : 1;",
+                              "if (x->is_alloc != y->is_alloc) return x->is_alloc > y->is_alloc ? -1 : 1;"),
+    "layer_shared_across_groups": ("uint32_t on_pile = 0;                  /* every group starts with no layer */",
+                                   "static uint32_t on_pile; if (g0 == 0) on_pile = 0;"),
+    "layer_end_not_updated": ("                layer_of[i] = l;\n                layer_t_e[l] = t_e[i];",
+                              "                layer_of[i] = l;\n                if (l + 1 == layers) layer_t_e[l] = t_e[i];"),
+    "layer_groups_ascending": ("if (x->size != y->size) return x->size > y->size ? -1 : 1;\n    return x->id < y->id ? -1 : (x->id > y->id ? 1 : 0);\n}\n\nstatic int by_time_release_first",
+                               "if (x->size != y->size) return x->size > y->size ? 1 : -1;\n    return x->id < y->id ? -1 : (x->id > y->id ? 1 : 0);\n}\n\nstatic int by_time_release_first"),
+    "layer_equal_starts_by_highest_number": ("    return x->id < y->id ? -1 : (x->id > y->id ? 1 : 0);\n}\n\nstatic int descending_u32",
+                                             "    return x->id > y->id ? -1 : (x->id < y->id ? 1 : 0);\n}\n\nstatic int descending_u32"),
+    "layer_equal_ends_opened_last_first": ("return (x < y) - (x > y);", "return (x > y) - (x < y);"),
     "orders_jitter_one_bit_short": ("<< 32) + (k >> 31); }", "<< 32) + (k >> 32); }"),
     "orders_lifetime_row_by_size_first": ("{ m[i].k0 = ~(uint64_t)(t_e[i] - t_s[i]); m[i].k1 = ~size[i]; }",
                                           "{ m[i].k1 = ~(uint64_t)(t_e[i] - t_s[i]); m[i].k0 = ~size[i]; }"),
