@@ -59,7 +59,6 @@ struct SplitWorkspace {
     uint2* fit_by_rank;
     uint32_t* addr;
     uint64_t* group_bins;
-    uint64_t* region_bins;
     uint32_t* group_top;
     uint32_t slots, n_pad, grid;
 };

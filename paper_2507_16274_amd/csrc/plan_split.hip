@@ -95,7 +95,7 @@ struct SplitLds {
     uint32_t region_max[kWave];                  // region of ranks (64 regions cover the table)
     uint32_t reach[3];                           // window_reach: what the waves found, three calls in rotation
     // request with a wide window: every wave walks one part of the list
-    Span<uint32_t> wide_hole[kSpMaxWaves][kSpWideHoles];   // holes of that part {end, covered}, in address order
+    Span<uint32_t> wide_hole[kSpMaxWaves][kSpWideHoles];   // candidate holes of that part {end, covered within the part}, in address order
     uint32_t wide_holes[kSpMaxWaves];            // how many there are (may exceed what is stored)
     uint32_t wide_part_top[kSpMaxWaves];         // highest end of the conflicting long blocks of that part
     uint32_t next_plan;                          // the plan this workgroup takes next
@@ -271,7 +271,6 @@ struct SplitTables {
     const uint4* record;         // [n] per request: (size, t_alloc, t_free, rank | long flag), then (window start, window end, -, -)
     uint32_t* addr;              // per resident workgroup: [slots] address of the short block at each rank
     uint64_t* group_bins;        // per resident workgroup: [groups][kSpLevels] address bins of the placed short blocks of 64 ranks
-    uint64_t* region_bins;       // per resident workgroup: [64][kSpLevels] the same per region
     uint32_t* group_top;         // per resident workgroup: [groups] highest end address of the placed short blocks of 64 ranks
     uint32_t slots;              // n rounded up to 64, plus 64
     uint32_t groups;             // slots / 64
@@ -301,7 +300,6 @@ __device__ __forceinline__ uint32_t load_coherent(const uint32_t* p)
 struct SpTable {
     uint32_t* addr;
     uint64_t* group_bins;
-    uint64_t* region_bins;
     uint32_t* group_top;
 };
 
@@ -317,11 +315,11 @@ __device__ __forceinline__ uint64_t load_coherent(const uint64_t* p)
 
 // Highest end address of the placed short blocks of the window that conflict with the request
 // in lifetime and meet [c, c + s); 0 if none does.  Called by ALL waves of the workgroup with the
-// same arguments; every wave returns the same value.  Regions first (lowest start / highest end
-// in LDS, then their address bins), then the groups of 64 ranks of a region (address bins), then
-// the blocks of a group.  The regions that are left are dealt out to the waves; `turn` counts the
-// calls of the workgroup (the results of three consecutive calls use different LDS words, so
-// that one barrier per call suffices).
+// same arguments; every wave returns the same value.  Regions of ranks first (lowest start /
+// highest end in LDS), then the groups of 64 ranks of the regions that are left (address bins and
+// highest end), then the blocks of a group.  The groups of the window are dealt out to the waves
+// in equal parts; `turn` counts the calls of the workgroup (the results of three consecutive calls
+// use different LDS words, so that one barrier per call suffices).
 template <int kWaves, typename Lds>
 __device__ __forceinline__ uint32_t window_reach(const SpRequest& rq, uint32_t own_rank, uint32_t c, const SplitTables& tb,
                                                  const SpTable& pt, uint32_t& turn, Lds& sh)
@@ -329,61 +327,54 @@ __device__ __forceinline__ uint32_t window_reach(const SpRequest& rq, uint32_t o
     const int lane = lane_id(), wave = wave_id();
     const uint32_t cs = c + rq.s;
     const uint32_t g_begin = rq.wlo / kWave, g_end = (rq.whi + kWave - 1) / kWave;     // groups of the window
-    const uint32_t per_region = 1u << (tb.region_shift - 6);                            // groups per region
-    const uint32_t r_begin = g_begin / per_region, r_end = (g_end + per_region - 1) / per_region;   // <= 64
-    uint64_t regions = __builtin_amdgcn_ballot_w64((uint32_t)lane >= r_begin && (uint32_t)lane < r_end &&
-                                                   sh.region_max[lane] > c && sh.region_min[lane] < cs);
+    const uint32_t region_of_group = tb.region_shift - 6;                               // 2^that groups per region
+    const uint32_t r_begin = g_begin >> region_of_group, r_end = ((g_end - 1) >> region_of_group) + 1;   // <= 64
+    const uint64_t regions = __builtin_amdgcn_ballot_w64((uint32_t)lane >= r_begin && (uint32_t)lane < r_end &&
+                                                         sh.region_max[lane] > c && sh.region_min[lane] < cs);
     if (regions == 0) return 0;                                                         // (the same in every wave)
     int level = 0;
     while (((cs - 1) >> sp_level_shift(level)) > 62u) ++level;                          // (level 7 always ends the search)
     const uint64_t wanted = sp_bins(c, cs - 1, level);
-    {
-        const uint64_t bins = ((regions >> lane) & 1) ? load_coherent(pt.region_bins + lane * kSpLevels + level) : 0ull;
-        regions = __builtin_amdgcn_ballot_w64((bins & wanted) != 0);
-    }
-    if (regions == 0) return 0;
     const uint32_t slot = turn % 3;
     ++turn;
     if (threadIdx.x == 0) sh.reach[(slot + 1) % 3] = 0;                                 // for the call after this one
     uint32_t reach = 0;
-    uint32_t share = 0;
-    for (; regions; regions &= regions - 1, ++share) {
-        if (share % kWaves != (uint32_t)wave) continue;                                 // (uniform) another wave's region
-        const uint32_t first = (uint32_t)__builtin_ctzll(regions) * per_region;
-        for (uint32_t g0 = first; g0 < first + per_region; g0 += kWave) {
-            const uint32_t g = g0 + lane;
-            const bool valid = g >= g_begin && g < g_end && g < first + per_region;
-            const uint64_t bins = valid ? load_coherent(pt.group_bins + (size_t)g * kSpLevels + level) : 0ull;
-            const uint32_t top = valid ? load_coherent32(pt.group_top + g) : 0u;
-            // nothing of the group in the bins of [c, c + s), or nothing that ends above c: not concerned
-            bool look = (bins & wanted) != 0 && top > c;
-            // every block of the group ends by c + s, so all of them start below it, and the highest end
-            // is that of a block meeting [c, c + s): no need to read the blocks.  (Only for groups whose
-            // ranks all lie in the window and above the request's own: those started during its lifetime.)
-            if (look && top <= cs && g * kWave > own_rank && (g + 1) * kWave <= rq.whi) {
-                reach = umax(reach, top);
-                look = false;
+    const uint32_t share = (g_end - g_begin + kWaves - 1) / kWaves;                     // groups per wave
+    const uint32_t my_begin = g_begin + (uint32_t)wave * share, my_end = umin(g_end, my_begin + share);
+    for (uint32_t g0 = my_begin; g0 < my_end; g0 += kWave) {
+        const uint32_t g = g0 + lane;
+        const bool valid = g < my_end && ((regions >> umin(g >> region_of_group, 63u)) & 1);
+        const uint64_t bins = valid ? load_coherent(pt.group_bins + (size_t)g * kSpLevels + level) : 0ull;
+        const uint32_t top = valid ? load_coherent32(pt.group_top + g) : 0u;
+        // nothing of the group in the bins of [c, c + s), or nothing that ends above c: not concerned
+        bool look = (bins & wanted) != 0 && top > c;
+        // every block of the group ends by c + s, so all of them start below it, and the highest end
+        // is that of a block meeting [c, c + s): no need to read the blocks.  (Only for groups whose
+        // ranks all lie in the window and above the request's own: those started during its lifetime.)
+        if (look && top <= cs && g * kWave > own_rank && (g + 1) * kWave <= rq.whi) {
+            reach = umax(reach, top);
+            look = false;
+        }
+        uint64_t open = __builtin_amdgcn_ballot_w64(look);
+        // six groups at a time, so that the reads of the others are under way while one is looked at
+        while (open) {
+            constexpr int kFlight = 6;
+            uint32_t k[kFlight], a[kFlight], sz[kFlight];
+            bool on[kFlight];
+#pragma unroll
+            for (int u = 0; u < kFlight; ++u) {
+                on[u] = open != 0;
+                k[u] = on[u] ? (g0 + (uint32_t)__builtin_ctzll(open)) * kWave + lane : k[0];      // < slots
+                open &= open - 1;
             }
-            uint64_t open = __builtin_amdgcn_ballot_w64(look);
-            // four groups at a time, so that the reads of the others are under way while one is looked at
-            while (open) {
-                uint32_t k[4], a[4], sz[4];
-                bool on[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    on[u] = open != 0;
-                    k[u] = on[u] ? (g0 + (uint32_t)__builtin_ctzll(open)) * kWave + lane : k[0];      // < slots
-                    open &= open - 1;
-                }
+            for (int u = 0; u < kFlight; ++u) { a[u] = pt.addr[k[u]]; sz[u] = tb.size_by_rank[k[u]]; }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) { a[u] = pt.addr[k[u]]; sz[u] = tb.size_by_rank[k[u]]; }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    // ranks above the request's own started during its lifetime; the few below need a look at their release time
-                    bool live = on[u] && k[u] >= rq.wlo && k[u] < rq.whi && a[u] != kSpUnplaced;
-                    if (k[u] - lane <= own_rank) live = live && tb.by_rank[k[u]].z > rq.ta;
-                    reach = umax(reach, (live && a[u] < cs && a[u] + sz[u] > c) ? a[u] + sz[u] : 0u);
-                }
+            for (int u = 0; u < kFlight; ++u) {
+                // ranks above the request's own started during its lifetime; the few below need a look at their release time
+                bool live = on[u] && k[u] >= rq.wlo && k[u] < rq.whi && a[u] != kSpUnplaced;
+                if (k[u] - lane <= own_rank) live = live && tb.by_rank[k[u]].z > rq.ta;
+                reach = umax(reach, (live && a[u] < cs && a[u] + sz[u] > c) ? a[u] + sz[u] : 0u);
             }
         }
     }
@@ -508,25 +499,14 @@ __device__ __forceinline__ uint32_t settle_wide(const SpList& list, uint32_t cou
     rq.in_hi = rq.in_lo + bt.size;
     rq.rivals_w = 0; rq.w_lo = 0; rq.w_hi = 0;
     __syncthreads();                                              // the holes of the previous such request are no longer read
-    // every wave takes one part of the list: first the highest end of its conflicting blocks ...
+    // Every wave takes one part of the list and writes down what may be a hole large enough as such,
+    // as seen from the part's start, and the highest end of the part's conflicting blocks; what the
+    // parts below cover is known once all waves are done, and decides which of them are holes.
     const int wave = wave_id();
     const uint32_t steps = (count + kWave - 1) / kWave, per_wave = (steps + kWaves - 1) / kWaves;
     const uint32_t k_begin = umin(count, (uint32_t)wave * per_wave * kWave), k_end = umin(count, k_begin + per_wave * kWave);
     {
-        uint32_t top = 0;
-        for (uint32_t k0 = k_begin; k0 < k_end; k0 += kWave) {
-            const uint32_t k = k0 + lane;
-            const SpList::Entry en = list.load(k < k_end ? k : k_end - 1);
-            top = umax(top, (k < k_end && en.ta() < rq.tf && rq.ta < en.tf()) ? en.hi() : 0u);
-        }
-        top = read_lane(wave_scan_max(top), kWave - 1);
-        if (lane == 0) sh.wide_part_top[wave] = top;
-    }
-    __syncthreads();
-    // ... then, knowing what the parts below cover, the holes of its part that are large enough as such
-    {
         uint32_t run = 0, found = 0;
-        for (int w = 0; w < wave; ++w) run = umax(run, sh.wide_part_top[w]);
         for (uint32_t k0 = k_begin; k0 < k_end; k0 += kWave) {
             const uint32_t k = k0 + lane;
             const bool valid = k < k_end;
@@ -540,19 +520,21 @@ __device__ __forceinline__ uint32_t settle_wide(const SpList& list, uint32_t cou
             found += (uint32_t)__builtin_popcountll(opens);
             run = umax(run, read_lane(incl, kWave - 1));
         }
-        if (lane == 0) sh.wide_holes[wave] = found;
+        if (lane == 0) { sh.wide_holes[wave] = found; sh.wide_part_top[wave] = run; }
     }
     __syncthreads();
-    uint32_t top = 0;
+    uint32_t top = 0;                                                 // highest end of the conflicting blocks of the parts below
     for (int w = 0; w < kWaves; ++w) {
         const uint32_t found = sh.wide_holes[w];
         const uint32_t listed = found < (uint32_t)kSpWideHoles ? found : (uint32_t)kSpWideHoles;
         for (uint32_t i = 0; i < listed; ++i) {
-            const Span<uint32_t> hole = sh.wide_hole[w][i];           // {end, covered}
-            const uint32_t c = clear_others<true, kWaves>(rq, own_rank, hole.hi, hole.lo, tb, pt, turn, sh);
+            const Span<uint32_t> hole = sh.wide_hole[w][i];           // {end, covered within the part}
+            const uint32_t covered = umax(hole.hi, top);
+            if (hole.lo < covered || hole.lo - covered < rq.s) continue;
+            const uint32_t c = clear_others<true, kWaves>(rq, own_rank, covered, hole.lo, tb, pt, turn, sh);
             if (c <= hole.lo && hole.lo - c >= rq.s) return c;
         }
-        // more holes in this part than were written down and none so far took the request: every wave walks the list
+        // more candidates in this part than were written down and none so far took the request: every wave walks the list
         if (found > listed) return settle_request<true, kWaves>(list, count, b0, q, dep_q, bt, 0u, 0u, tb, pt, turn, sh);
         top = umax(top, sh.wide_part_top[w]);
     }
@@ -560,7 +542,7 @@ __device__ __forceinline__ uint32_t settle_wide(const SpList& list, uint32_t cou
 }
 
 template <int kThreads>
-__global__ void __launch_bounds__(kThreads, 2) plan_split_kernel(PlanParams prm, SplitTables tb)
+__global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm, SplitTables tb)
 {
     static_assert(kThreads / kWave <= kSpMaxWaves, "a wave's part of the list has its own LDS words");
     constexpr int kWaves = kThreads / kWave;
@@ -584,7 +566,6 @@ __global__ void __launch_bounds__(kThreads, 2) plan_split_kernel(PlanParams prm,
     SpTable pt;
     pt.addr = tb.addr + (size_t)blockIdx.x * tb.slots;
     pt.group_bins = tb.group_bins + (size_t)blockIdx.x * tb.groups * kSpLevels;
-    pt.region_bins = tb.region_bins + (size_t)blockIdx.x * kWave * kSpLevels;
     pt.group_top = tb.group_top + (size_t)blockIdx.x * tb.groups;
     uint32_t* addr = pt.addr;
 
@@ -603,7 +584,6 @@ __global__ void __launch_bounds__(kThreads, 2) plan_split_kernel(PlanParams prm,
         for (uint32_t k = threadIdx.x; k < tb.slots; k += kThreads) addr[k] = kSpUnplaced;
         for (uint32_t g = threadIdx.x; g < tb.groups * kSpLevels; g += kThreads) pt.group_bins[g] = 0ull;
         for (uint32_t g = threadIdx.x; g < tb.groups; g += kThreads) pt.group_top[g] = 0u;
-        for (uint32_t g = threadIdx.x; g < (uint32_t)(kWave * kSpLevels); g += kThreads) pt.region_bins[g] = 0ull;
         if (threadIdx.x < kWave) { sh.region_min[threadIdx.x] = 0xffffffffu; sh.region_max[threadIdx.x] = 0u; }
         if (threadIdx.x == 0) { sh.extent_now = 0; sh.peak = 0; sh.pool_used = 0; sh.reach[0] = 0; }
         uint32_t turn = 0;                                            // calls of window_reach: slot 0 is clear
@@ -730,8 +710,6 @@ __global__ void __launch_bounds__(kThreads, 2) plan_split_kernel(PlanParams prm,
                         const uint64_t bins = sp_bins(x, x + my_size - 1, level);
                         atomicOr((unsigned long long*)(pt.group_bins + (size_t)(my_rank / kWave) * kSpLevels + level),
                                  (unsigned long long)bins);
-                        atomicOr((unsigned long long*)(pt.region_bins + (my_rank >> tb.region_shift) * kSpLevels + level),
-                                 (unsigned long long)bins);
                     }
                     atomicMin(&sh.region_min[my_rank >> tb.region_shift], x);
                     atomicMax(&sh.region_max[my_rank >> tb.region_shift], x + my_size);
@@ -791,7 +769,6 @@ size_t split_workspace(uint32_t n, const DeviceInfo& di, Carver& cv, SplitWorksp
     ws->fit_by_rank = cv.take<uint2>(slots);
     ws->addr = cv.take<uint32_t>((size_t)grid * slots);
     ws->group_bins = cv.take<uint64_t>((size_t)grid * (slots / kWave) * kSpLevels);
-    ws->region_bins = cv.take<uint64_t>((size_t)grid * kWave * kSpLevels);
     ws->group_top = cv.take<uint32_t>((size_t)grid * (slots / kWave));
     ws->slots = slots;
     ws->n_pad = n_pad;
@@ -822,7 +799,7 @@ bool launch_plan_split(const PlanParams& prm, uint32_t t_end, const SplitWorkspa
 
     SplitTables tb;
     tb.by_rank = ws.by_rank; tb.size_by_rank = ws.size_by_rank; tb.fit_by_rank = ws.fit_by_rank; tb.record = ws.record;
-    tb.addr = ws.addr; tb.group_bins = ws.group_bins; tb.region_bins = ws.region_bins; tb.group_top = ws.group_top;
+    tb.addr = ws.addr; tb.group_bins = ws.group_bins; tb.group_top = ws.group_top;
     tb.slots = ws.slots; tb.groups = ws.slots / kWave; tb.list_cap = list_cap;
     tb.next_plan = ws.hist + kSpHistNextPlan;
     tb.region_shift = 6;
