@@ -58,9 +58,14 @@ struct SplitWorkspace {
     uint4* record;
     uint2* fit_by_rank;
     uint32_t* addr;
-    uint64_t* group_bins;
-    uint32_t* group_top;
-    uint32_t slots, n_pad, grid;
+    uint2* group_span;
+    uint32_t* is_large;
+    uint32_t* large_before;
+    uint32_t* scan_chunks;
+    uint32_t* scan_total;
+    uint2* large_fit;
+    uint32_t* large_addr;
+    uint32_t slots, large_slots, n_pad, grid;
 };
 size_t split_workspace(uint32_t n, const DeviceInfo& di, Carver& cv, SplitWorkspace* ws);
 bool launch_plan_split(const PlanParams& prm, uint32_t t_end, const SplitWorkspace& ws, const DeviceInfo& di, hipStream_t stream);

@@ -57,24 +57,10 @@ constexpr int kSpWideHoles = 6;                  // holes of its part of the lis
 constexpr int kSpMaxWaves = 8;
 constexpr uint32_t kSpRefetch = 0xffffffffu;     // (a window whose blocks did not fit the pool is read when its request is settled)
 constexpr uint32_t kSpUnplaced = 0xffffffffu;
-constexpr uint32_t kSpLongFlag = 0x80000000u;
+constexpr uint32_t kSpLongFlag = 0x80000000u;      // in a request's rank word: lives longer than theta
+constexpr uint32_t kSpLargeFlag = 0x40000000u;     // short-lived, and at least sigma granules large
+constexpr uint32_t kSpRankMask = 0x3fffffffu;
 constexpr int kSpMaxThetaBits = 12;              // theta < 2^12 events
-// Which addresses the placed short blocks of 64 ranks (a group) or of a region touch, as bitmaps
-// of 64 address bins at several resolutions: bin width 2^(8 + 3 l) granules at level l, the last
-// bin of a level taking everything above.  A request that tries [c, c + s) looks at the finest
-// level whose first 63 bins reach c + s: bins between 1/512 and 1/64 of that address wide.
-constexpr int kSpLevels = 8;
-__host__ __device__ constexpr uint32_t sp_level_shift(int level) { return 8u + 3u * (uint32_t)level; }
-
-// Bins of one level that the addresses lo .. last (inclusive) fall into.
-__device__ __forceinline__ uint64_t sp_bins(uint32_t lo, uint32_t last, int level)
-{
-    uint32_t a = lo >> sp_level_shift(level), b = last >> sp_level_shift(level);
-    a = a < 63u ? a : 63u;
-    b = b < 63u ? b : 63u;
-    return (b == 63u ? ~0ull : (2ull << b) - 1) & ~((1ull << a) - 1);
-}
-
 using SpList = BlockList<uint32_t, false>;
 
 struct SplitLds {
@@ -91,8 +77,9 @@ struct SplitLds {
     uint2 pend_life[kSpBatch];
     Span<uint32_t> pool[kSpPool];                // conflicting short blocks of the windows of the batch's requests
     uint32_t pool_used;
-    uint32_t region_min[kWave];                  // lowest start / highest end address of the placed short blocks of a
+    uint32_t region_min[kWave];                  // lowest start / highest end address of the placed small short blocks of a
     uint32_t region_max[kWave];                  // region of ranks (64 regions cover the table)
+    uint32_t large_min, large_max;               // the same over all placed large short blocks
     uint32_t reach[3];                           // window_reach: what the waves found, three calls in rotation
     // request with a wide window: every wave walks one part of the list
     Span<uint32_t> wide_hole[kSpMaxWaves][kSpWideHoles];   // candidate holes of that part {end, covered within the part}, in address order
@@ -128,13 +115,15 @@ sp_histogram(const uint32_t* __restrict__ ta, const uint32_t* __restrict__ tf, u
     if (threadIdx.x < 32 && local[threadIdx.x]) atomicAdd(&hist[threadIdx.x], local[threadIdx.x]);
 }
 
-constexpr int kSpHistWords = 40;                 // 32 lifetime classes, then [32]: requests with a wide window
+constexpr int kSpHistWords = 80;                 // 32 lifetime classes, then [32]: requests with a wide window
 constexpr int kSpHistWide = 32;
 constexpr int kSpHistNextPlan = 33;              // (the counter that hands out plans lives behind the histogram)
+constexpr int kSpHistSigma = 34;                 // sizes of at least this many granules count as large among the short-lived
+constexpr int kSpHistSizes = 40;                 // 32 size classes of the short-lived requests
 
 __global__ void sp_clear_histogram(uint32_t* hist, uint32_t* gate)
 {
-    if (threadIdx.x < kSpHistWords) hist[threadIdx.x] = 0;
+    for (int k = threadIdx.x; k < kSpHistWords; k += blockDim.x) hist[k] = 0;
     if (threadIdx.x == 0) *gate = 1;                                // closed until sp_decide opens it
 }
 
@@ -156,6 +145,7 @@ __global__ void sp_decide(uint64_t* acc, const uint32_t* hist, uint32_t n, uint3
     if (*status != STALLOC_OK) return;
     const uint64_t mode = acc[kAccMode];
     if (!(mode & (kModeNarrow | kModeTry32))) return;
+    if (n > kSpRankMask) return;                                    // (a rank word keeps two bits for flags)
     if (bitmap_shape(mode, acc[kAccGranules], prm.bitmap_pool_words) >= 0) return;
     if ((mode & kModeCompact) && prm.compact_enqueued) return;
     uint32_t at_least[33];                                          // requests with lifetime >= 2^c
@@ -175,6 +165,50 @@ __global__ void sp_decide(uint64_t* acc, const uint32_t* hist, uint32_t n, uint3
     *gate = 0;
 }
 
+// hist[kSpHistSizes + c] = short-lived requests whose size lies in [2^c, 2^(c+1)) granules.
+__global__ void __launch_bounds__(256)
+sp_size_histogram(const uint64_t* __restrict__ size, const uint32_t* __restrict__ ta, const uint32_t* __restrict__ tf,
+                  uint32_t n, const uint64_t* acc, uint32_t* hist, const uint32_t* gate)
+{
+    __shared__ uint32_t local[32];
+    if (*gate != 0) return;
+    const uint32_t shift = (uint32_t)(acc[kAccMode] & 63);
+    const uint32_t theta = (uint32_t)((acc[kAccSplit] >> 8) & 0xffffffu);
+    if (threadIdx.x < 32) local[threadIdx.x] = 0;
+    __syncthreads();
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+        const uint32_t s = (uint32_t)(size[i] >> shift);             // >= 1
+        if (tf[i] - ta[i] <= theta) atomicAdd(&local[s ? 31 - __builtin_clz(s) : 0], 1u);
+    }
+    __syncthreads();
+    if (threadIdx.x < 32 && local[threadIdx.x]) atomicAdd(&hist[kSpHistSizes + threadIdx.x], local[threadIdx.x]);
+}
+
+// Short-lived blocks come in two kinds in a training trace: many small ones that settle low in
+// the address space, and few large ones that end up anywhere (Sec. 2.3).  A long-lived request
+// that looks for room high up is stopped by the large ones only, so those are also kept in a
+// table of their own, which such a request reads whole.  sigma = 2^c with at most an eighth of the
+// short-lived requests of at least that size (and at least one); of those c, the one with the
+// most empty size classes right below it (the gap between the two kinds), the smallest of several
+// such; none are large if even the largest occupied class holds more than an eighth.
+__global__ void sp_sigma(uint32_t* hist, const uint32_t* gate)
+{
+    if (threadIdx.x != 0 || *gate != 0) return;
+    uint32_t total = 0;
+    for (int c = 0; c < 32; ++c) total += hist[kSpHistSizes + c];
+    uint32_t above = 0, sigma = 0xffffffffu;
+    int widest = -1;
+    for (int c = 31; c >= 1; --c) {
+        above += hist[kSpHistSizes + c];
+        if (above > total / 8) break;
+        if (above == 0) continue;
+        int gap = 0;
+        while (c - 1 - gap >= 0 && hist[kSpHistSizes + c - 1 - gap] == 0) ++gap;
+        if (gap >= widest) { widest = gap; sigma = 1u << c; }
+    }
+    hist[kSpHistSigma] = sigma;
+}
+
 // Keys (t_alloc, request) of one tile, sorted in LDS.
 __global__ void __launch_bounds__(kSortTile)
 sp_sort_tiles(const uint32_t* __restrict__ ta, uint32_t n, ulonglong2* keys, const uint32_t* gate)
@@ -192,24 +226,30 @@ sp_sort_tiles(const uint32_t* __restrict__ ta, uint32_t n, ulonglong2* keys, con
 __global__ void __launch_bounds__(256)
 sp_tables(const ulonglong2* __restrict__ sorted, const uint64_t* __restrict__ size, const uint32_t* __restrict__ ta,
           const uint32_t* __restrict__ tf, uint32_t n, uint32_t slots, const uint64_t* acc, uint4* by_rank,
-          uint32_t* size_by_rank, uint2* fit_by_rank, uint32_t* rank_of, const uint32_t* gate)
+          uint32_t* size_by_rank, uint2* fit_by_rank, uint32_t* rank_of, uint32_t* is_large, const uint32_t* hist,
+          const uint32_t* gate)
 {
     if (*gate != 0) return;
     const uint32_t shift = (uint32_t)(acc[kAccMode] & 63);
     const uint32_t theta = (uint32_t)((acc[kAccSplit] >> 8) & 0xffffffu);
+    const uint32_t sigma = hist[kSpHistSigma];
     for (uint32_t k = blockIdx.x * blockDim.x + threadIdx.x; k < slots; k += gridDim.x * blockDim.x) {
         if (k >= n) {
             by_rank[k] = make_uint4(0u, 0xffffffffu, 0u, 0xffffffffu);
             size_by_rank[k] = 0u;
             fit_by_rank[k] = make_uint2(0u, 0u);
+            is_large[k] = 0u;
             continue;
         }
         const uint32_t i = (uint32_t)sorted[k].y;
         const uint32_t a = ta[i], f = tf[i];
-        by_rank[k] = make_uint4((uint32_t)(size[i] >> shift), a, f, i);
-        size_by_rank[k] = (uint32_t)(size[i] >> shift);
-        fit_by_rank[k] = make_uint2((uint32_t)(size[i] >> shift), f);
-        rank_of[i] = k | (f - a > theta ? kSpLongFlag : 0u);
+        const uint32_t s = (uint32_t)(size[i] >> shift);
+        const bool lives_long = f - a > theta, large = !lives_long && s >= sigma;
+        by_rank[k] = make_uint4(s, a, f, i);
+        size_by_rank[k] = s;
+        fit_by_rank[k] = make_uint2(s, f);
+        is_large[k] = large ? 1u : 0u;
+        rank_of[i] = k | (lives_long ? kSpLongFlag : 0u) | (large ? kSpLargeFlag : 0u);
     }
 }
 
@@ -224,13 +264,15 @@ __device__ __forceinline__ uint32_t first_rank_at(const uint4* __restrict__ by_r
     return lo;
 }
 
+// Second word of a request's record: (window start, window end, for a large short block its place
+// among the large short blocks in allocation-time order, -).
 // Window of request i: ranks of the requests allocated in (t_alloc - theta, t_free).  A short
 // request j (lifetime <= theta) whose lifetime conflicts with i's has t_alloc_j < t_free_i and
 // t_alloc_j >= t_free_j - theta > t_alloc_i - theta, so it lies in the window.
 __global__ void __launch_bounds__(256)
 sp_windows(const uint4* __restrict__ by_rank, const uint32_t* __restrict__ ta, const uint32_t* __restrict__ tf, uint32_t n,
-           const uint64_t* acc, const uint64_t* __restrict__ size, const uint32_t* __restrict__ rank_of, uint4* record,
-           uint32_t* hist, const uint32_t* gate)
+           const uint64_t* acc, const uint64_t* __restrict__ size, const uint32_t* __restrict__ rank_of,
+           const uint32_t* __restrict__ large_before, uint4* record, uint2* large_fit, uint32_t* hist, const uint32_t* gate)
 {
     if (*gate != 0) return;
     const uint32_t theta = (uint32_t)((acc[kAccSplit] >> 8) & 0xffffffu);
@@ -240,7 +282,12 @@ sp_windows(const uint4* __restrict__ by_rank, const uint32_t* __restrict__ ta, c
         const uint32_t from = a + 1 > theta ? a + 1 - theta : 0u;
         const uint2 w = make_uint2(first_rank_at(by_rank, n, from), first_rank_at(by_rank, n, tf[i]));
         record[2 * i] = make_uint4((uint32_t)(size[i] >> (acc[kAccMode] & 63)), a, tf[i], rank_of[i]);
-        record[2 * i + 1] = make_uint4(w.x, w.y, 0u, 0u);
+        // large_before[k] = large short blocks among the ranks below k: a large short block's place in
+        // the table of those
+        const bool large = (rank_of[i] & kSpLargeFlag) != 0;
+        const uint32_t place = large ? large_before[rank_of[i] & kSpRankMask] : 0u;
+        record[2 * i + 1] = make_uint4(w.x, w.y, place, 0u);
+        if (large) large_fit[place] = make_uint2((uint32_t)(size[i] >> (acc[kAccMode] & 63)), tf[i]);
         wide += w.y - w.x > (uint32_t)kWave ? 1u : 0u;
     }
     wide = wave_sum32(wide);
@@ -269,9 +316,12 @@ struct SplitTables {
     const uint32_t* size_by_rank;// [slots] the sizes once more, on their own
     const uint2* fit_by_rank;    // [slots] (size, t_free): what a request needs to know of the short blocks of its window
     const uint4* record;         // [n] per request: (size, t_alloc, t_free, rank | long flag), then (window start, window end, -, -)
+    const uint32_t* large_before;// [slots] large short blocks among the ranks below
+    const uint2* large_fit;      // [large_slots] (size, t_free) of the large short blocks in allocation-time order
     uint32_t* addr;              // per resident workgroup: [slots] address of the short block at each rank
-    uint64_t* group_bins;        // per resident workgroup: [groups][kSpLevels] address bins of the placed short blocks of 64 ranks
-    uint32_t* group_top;         // per resident workgroup: [groups] highest end address of the placed short blocks of 64 ranks
+    uint2* group_span;           // per resident workgroup: [groups] lowest start, highest end address of the placed small short blocks of 64 ranks
+    uint32_t* large_addr;        // per resident workgroup: [large_slots] addresses of the large short blocks
+    uint32_t large_slots;        // a multiple of 64
     uint32_t slots;              // n rounded up to 64, plus 64
     uint32_t groups;             // slots / 64
     uint32_t list_cap;           // entries of the LDS list
@@ -283,6 +333,7 @@ struct SplitTables {
 struct SpRequest {
     uint32_t s, ta, tf;
     uint32_t wlo, whi;
+    uint32_t large_lo, large_hi;     // the window in the table of large short blocks (wide windows only)
     // blocks settled earlier in the batch (lane = position in the batch)
     uint64_t rivals_in;
     uint32_t in_lo, in_hi;
@@ -291,35 +342,28 @@ struct SpRequest {
     uint32_t w_lo, w_hi;
 };
 
-__device__ __forceinline__ uint32_t load_coherent(const uint32_t* p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
 // The table of short blocks of the plan a workgroup is working on.
 struct SpTable {
     uint32_t* addr;
-    uint64_t* group_bins;
-    uint32_t* group_top;
+    uint2* group_span;
+    uint32_t* large_addr;
 };
 
-__device__ __forceinline__ uint32_t load_coherent32(const uint32_t* p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-__device__ __forceinline__ uint64_t load_coherent(const uint64_t* p)
+// (changed with atomic operations by one wave of the workgroup, read by all after a barrier)
+__device__ __forceinline__ uint32_t load_coherent(const uint32_t* p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Highest end address of the placed short blocks of the window that conflict with the request
 // in lifetime and meet [c, c + s); 0 if none does.  Called by ALL waves of the workgroup with the
-// same arguments; every wave returns the same value.  Regions of ranks first (lowest start /
-// highest end in LDS), then the groups of 64 ranks of the regions that are left (address bins and
-// highest end), then the blocks of a group.  The groups of the window are dealt out to the waves
-// in equal parts; `turn` counts the calls of the workgroup (the results of three consecutive calls
-// use different LDS words, so that one barrier per call suffices).
+// same arguments; every wave returns the same value.
+//   small blocks: regions of ranks first (lowest start / highest end in LDS), then the groups of 64
+//                 ranks of the regions that are left (lowest start / highest end), then the blocks
+//                 of a group;
+//   large blocks: all of the window, from the table of their own.
+// Groups are dealt out to the waves in turn; `turn` counts the calls of the workgroup (the results
+// of three consecutive calls use different LDS words, so that one barrier per call suffices).
 template <int kWaves, typename Lds>
 __device__ __forceinline__ uint32_t window_reach(const SpRequest& rq, uint32_t own_rank, uint32_t c, const SplitTables& tb,
                                                  const SpTable& pt, uint32_t& turn, Lds& sh)
@@ -331,40 +375,60 @@ __device__ __forceinline__ uint32_t window_reach(const SpRequest& rq, uint32_t o
     const uint32_t r_begin = g_begin >> region_of_group, r_end = ((g_end - 1) >> region_of_group) + 1;   // <= 64
     const uint64_t regions = __builtin_amdgcn_ballot_w64((uint32_t)lane >= r_begin && (uint32_t)lane < r_end &&
                                                          sh.region_max[lane] > c && sh.region_min[lane] < cs);
-    if (regions == 0) return 0;                                                         // (the same in every wave)
-    int level = 0;
-    while (((cs - 1) >> sp_level_shift(level)) > 62u) ++level;                          // (level 7 always ends the search)
-    const uint64_t wanted = sp_bins(c, cs - 1, level);
+    const bool large = rq.large_lo < rq.large_hi && sh.large_max > c && sh.large_min < cs;
+    if (regions == 0 && !large) return 0;                                               // (the same in every wave)
     const uint32_t slot = turn % 3;
     ++turn;
     if (threadIdx.x == 0) sh.reach[(slot + 1) % 3] = 0;                                 // for the call after this one
     uint32_t reach = 0;
-    const uint32_t share = (g_end - g_begin + kWaves - 1) / kWaves;                     // groups per wave
-    const uint32_t my_begin = g_begin + (uint32_t)wave * share, my_end = umin(g_end, my_begin + share);
-    for (uint32_t g0 = my_begin; g0 < my_end; g0 += kWave) {
-        const uint32_t g = g0 + lane;
-        const bool valid = g < my_end && ((regions >> umin(g >> region_of_group, 63u)) & 1);
-        const uint64_t bins = valid ? load_coherent(pt.group_bins + (size_t)g * kSpLevels + level) : 0ull;
-        const uint32_t top = valid ? load_coherent32(pt.group_top + g) : 0u;
-        // nothing of the group in the bins of [c, c + s), or nothing that ends above c: not concerned
-        bool look = (bins & wanted) != 0 && top > c;
+    constexpr int kFlight = 6;                                                          // groups whose reads are under way together
+    if (large) {
+        const uint32_t l_begin = rq.large_lo / kWave, l_end = (rq.large_hi + kWave - 1) / kWave;
+        for (uint32_t g0 = l_begin + (uint32_t)wave; g0 < l_end; g0 += kFlight * kWaves) {
+            uint32_t a[kFlight];
+            uint2 fit[kFlight];
+#pragma unroll
+            for (int u = 0; u < kFlight; ++u) {
+                const uint32_t k = umin(g0 + (uint32_t)u * kWaves, l_end - 1) * kWave + lane;      // < large_slots
+                a[u] = pt.large_addr[k];
+                fit[u] = tb.large_fit[k];
+            }
+#pragma unroll
+            for (int u = 0; u < kFlight; ++u) {
+                const uint32_t k = (g0 + (uint32_t)u * kWaves) * kWave + lane;
+                // (a block of the window was allocated before the request is released: only its release counts)
+                const bool live = k >= rq.large_lo && k < rq.large_hi && a[u] != kSpUnplaced && fit[u].y > rq.ta;
+                reach = umax(reach, (live && a[u] < cs && a[u] + fit[u].x > c) ? a[u] + fit[u].x : 0u);
+            }
+        }
+    }
+    // wave w takes the groups g_begin + w, g_begin + w + kWaves, ...: neighbouring groups hold blocks of
+    // the same phase of the trace and tend to be busy together
+    for (uint32_t g0 = g_begin + (uint32_t)wave; regions != 0 && g0 < g_end; g0 += kWave * kWaves) {
+        const uint32_t g = g0 + (uint32_t)lane * kWaves;
+        const bool valid = g < g_end && ((regions >> umin(g >> region_of_group, 63u)) & 1);
+        uint2 span = make_uint2(0xffffffffu, 0u);
+        if (valid) {
+            span.x = load_coherent(&pt.group_span[g].x);
+            span.y = load_coherent(&pt.group_span[g].y);
+        }
+        // nothing of the group reaches into [c, c + s): not concerned
+        bool look = span.y > c && span.x < cs;
         // every block of the group ends by c + s, so all of them start below it, and the highest end
         // is that of a block meeting [c, c + s): no need to read the blocks.  (Only for groups whose
         // ranks all lie in the window and above the request's own: those started during its lifetime.)
-        if (look && top <= cs && g * kWave > own_rank && (g + 1) * kWave <= rq.whi) {
-            reach = umax(reach, top);
+        if (look && span.y <= cs && g * kWave > own_rank && (g + 1) * kWave <= rq.whi) {
+            reach = umax(reach, span.y);
             look = false;
         }
         uint64_t open = __builtin_amdgcn_ballot_w64(look);
-        // six groups at a time, so that the reads of the others are under way while one is looked at
         while (open) {
-            constexpr int kFlight = 6;
             uint32_t k[kFlight], a[kFlight], sz[kFlight];
             bool on[kFlight];
 #pragma unroll
             for (int u = 0; u < kFlight; ++u) {
                 on[u] = open != 0;
-                k[u] = on[u] ? (g0 + (uint32_t)__builtin_ctzll(open)) * kWave + lane : k[0];      // < slots
+                k[u] = on[u] ? (g0 + (uint32_t)__builtin_ctzll(open) * kWaves) * kWave + lane : k[0];      // < slots
                 open &= open - 1;
             }
 #pragma unroll
@@ -429,7 +493,7 @@ __device__ __forceinline__ uint32_t settle_request(const SpList& list, uint32_t 
     SpRequest rq;
     rq.s = read_lane(bt.size, (int)q); rq.ta = read_lane(bt.ta, (int)q); rq.tf = read_lane(bt.tf, (int)q);
     rq.wlo = read_lane(bt.wlo, (int)q); rq.whi = read_lane(bt.whi, (int)q);
-    const uint32_t own_rank = read_lane(bt.rank, (int)q) & ~kSpLongFlag;
+    const uint32_t own_rank = read_lane(bt.rank, (int)q) & kSpRankMask;
     // earlier requests of the batch with a conflicting lifetime: all settled by now
     rq.rivals_in = dep_q;
     rq.in_lo = 0; rq.in_hi = 0;
@@ -438,6 +502,11 @@ __device__ __forceinline__ uint32_t settle_request(const SpList& list, uint32_t 
         rq.in_hi = rq.in_lo + bt.size;
     }
     rq.rivals_w = 0; rq.w_lo = 0; rq.w_hi = 0;
+    rq.large_lo = 0; rq.large_hi = 0;
+    if constexpr (kWide) {
+        rq.large_lo = tb.large_before[rq.wlo];
+        rq.large_hi = tb.large_before[rq.whi];
+    }
     if constexpr (!kWide) {
         // conflicting short blocks of its window, as gathered when the batch began
         if (in_pool != kSpRefetch) {
@@ -493,11 +562,13 @@ __device__ __forceinline__ uint32_t settle_wide(const SpList& list, uint32_t cou
     SpRequest rq;
     rq.s = read_lane(bt.size, (int)q); rq.ta = read_lane(bt.ta, (int)q); rq.tf = read_lane(bt.tf, (int)q);
     rq.wlo = read_lane(bt.wlo, (int)q); rq.whi = read_lane(bt.whi, (int)q);
-    const uint32_t own_rank = read_lane(bt.rank, (int)q) & ~kSpLongFlag;
+    const uint32_t own_rank = read_lane(bt.rank, (int)q) & kSpRankMask;
     rq.rivals_in = dep_q;
     rq.in_lo = sh.rq_addr[b0 + lane];
     rq.in_hi = rq.in_lo + bt.size;
     rq.rivals_w = 0; rq.w_lo = 0; rq.w_hi = 0;
+    rq.large_lo = tb.large_before[rq.wlo];                        // (looked at after the walk over the list)
+    rq.large_hi = tb.large_before[rq.whi];
     __syncthreads();                                              // the holes of the previous such request are no longer read
     // Every wave takes one part of the list and writes down what may be a hole large enough as such,
     // as seen from the part's start, and the highest end of the part's conflicting blocks; what the
@@ -565,8 +636,8 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
     spare = list;
     SpTable pt;
     pt.addr = tb.addr + (size_t)blockIdx.x * tb.slots;
-    pt.group_bins = tb.group_bins + (size_t)blockIdx.x * tb.groups * kSpLevels;
-    pt.group_top = tb.group_top + (size_t)blockIdx.x * tb.groups;
+    pt.group_span = tb.group_span + (size_t)blockIdx.x * tb.groups;
+    pt.large_addr = tb.large_addr + (size_t)blockIdx.x * tb.large_slots;
     uint32_t* addr = pt.addr;
 
     // Plans are handed out one by one (a counter in the workspace): some orders take several times
@@ -582,10 +653,10 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
         uint32_t count = 0;
         bool outgrown = false;                                        // (uniform) 32-bit counts may not hold the next batch
         for (uint32_t k = threadIdx.x; k < tb.slots; k += kThreads) addr[k] = kSpUnplaced;
-        for (uint32_t g = threadIdx.x; g < tb.groups * kSpLevels; g += kThreads) pt.group_bins[g] = 0ull;
-        for (uint32_t g = threadIdx.x; g < tb.groups; g += kThreads) pt.group_top[g] = 0u;
+        for (uint32_t k = threadIdx.x; k < tb.large_slots; k += kThreads) pt.large_addr[k] = kSpUnplaced;
+        for (uint32_t g = threadIdx.x; g < tb.groups; g += kThreads) pt.group_span[g] = make_uint2(0xffffffffu, 0u);
         if (threadIdx.x < kWave) { sh.region_min[threadIdx.x] = 0xffffffffu; sh.region_max[threadIdx.x] = 0u; }
-        if (threadIdx.x == 0) { sh.extent_now = 0; sh.peak = 0; sh.pool_used = 0; sh.reach[0] = 0; }
+        if (threadIdx.x == 0) { sh.extent_now = 0; sh.peak = 0; sh.pool_used = 0; sh.reach[0] = 0; sh.large_min = 0xffffffffu; sh.large_max = 0u; }
         uint32_t turn = 0;                                            // calls of window_reach: slot 0 is clear
 
         for (uint32_t r0 = 0; r0 < n; r0 += kSpRefill) {
@@ -704,15 +775,18 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
                 // the short blocks of the batch enter the table and its summaries
                 if (wave == 1 % kWaves && mine && !(my_rank & kSpLongFlag)) {
                     const uint32_t x = sh.rq_addr[b0 + lane];
-                    addr[my_rank] = x;
-                    atomicMax(pt.group_top + my_rank / kWave, x + my_size);
-                    for (int level = 0; level < kSpLevels; ++level) {
-                        const uint64_t bins = sp_bins(x, x + my_size - 1, level);
-                        atomicOr((unsigned long long*)(pt.group_bins + (size_t)(my_rank / kWave) * kSpLevels + level),
-                                 (unsigned long long)bins);
+                    const uint32_t rank = my_rank & kSpRankMask;
+                    addr[rank] = x;
+                    if (my_rank & kSpLargeFlag) {
+                        pt.large_addr[tb.record[2 * (size_t)sh.rq_id[b0 + lane] + 1].z] = x;
+                        atomicMin(&sh.large_min, x);
+                        atomicMax(&sh.large_max, x + my_size);
+                    } else {
+                        atomicMin(&pt.group_span[rank / kWave].x, x);
+                        atomicMax(&pt.group_span[rank / kWave].y, x + my_size);
+                        atomicMin(&sh.region_min[rank >> tb.region_shift], x);
+                        atomicMax(&sh.region_max[rank >> tb.region_shift], x + my_size);
                     }
-                    atomicMin(&sh.region_min[my_rank >> tb.region_shift], x);
-                    atomicMax(&sh.region_max[my_rank >> tb.region_shift], x + my_size);
                 }
                 // the long blocks of the batch, sorted by address, go into the list
                 const uint64_t longs = __builtin_amdgcn_ballot_w64(mine && (my_rank & kSpLongFlag));
@@ -768,9 +842,17 @@ size_t split_workspace(uint32_t n, const DeviceInfo& di, Carver& cv, SplitWorksp
     ws->record = cv.take<uint4>(2 * (size_t)n);
     ws->fit_by_rank = cv.take<uint2>(slots);
     ws->addr = cv.take<uint32_t>((size_t)grid * slots);
-    ws->group_bins = cv.take<uint64_t>((size_t)grid * (slots / kWave) * kSpLevels);
-    ws->group_top = cv.take<uint32_t>((size_t)grid * (slots / kWave));
+    // at most an eighth of the short-lived requests count as large (sp_sigma)
+    const uint32_t large_slots = (n / 8 + kWave - 1) / kWave * kWave + kWave;
+    ws->group_span = cv.take<uint2>((size_t)grid * (slots / kWave));
+    ws->is_large = cv.take<uint32_t>(slots);
+    ws->large_before = cv.take<uint32_t>(slots);
+    ws->scan_chunks = cv.take<uint32_t>((slots + 1023) / 1024);
+    ws->scan_total = cv.take<uint32_t>(1);
+    ws->large_fit = cv.take<uint2>(large_slots);
+    ws->large_addr = cv.take<uint32_t>((size_t)grid * large_slots);
     ws->slots = slots;
+    ws->large_slots = large_slots;
     ws->n_pad = n_pad;
     ws->grid = grid;
     return cv.used;
@@ -789,17 +871,22 @@ bool launch_plan_split(const PlanParams& prm, uint32_t t_end, const SplitWorkspa
     hipLaunchKernelGGL(sp_histogram, dim3(blocks > 256 ? 256 : blocks), dim3(256), 0, stream, prm.ta, prm.tf, n, ws.hist,
                        prm.status);
     hipLaunchKernelGGL(sp_decide, dim3(1), dim3(64), 0, stream, acc, ws.hist, n, t_end, list_cap, prm, ws.gate, prm.status);
+    hipLaunchKernelGGL(sp_size_histogram, dim3(blocks > 256 ? 256 : blocks), dim3(256), 0, stream, prm.size, prm.ta, prm.tf, n,
+                       prm.acc, ws.hist, ws.gate);
+    hipLaunchKernelGGL(sp_sigma, dim3(1), dim3(64), 0, stream, ws.hist, ws.gate);
     hipLaunchKernelGGL(sp_sort_tiles, dim3(ws.n_pad / kSortTile), dim3(kSortTile), 0, stream, prm.ta, n, ws.keys, ws.gate);
     const ulonglong2* sorted = launch_merge_tiles(ws.keys, ws.spare, ws.n_pad, 1, ws.gate, stream);
     hipLaunchKernelGGL(sp_tables, dim3(blocks), dim3(256), 0, stream, sorted, prm.size, prm.ta, prm.tf, n, ws.slots, prm.acc,
-                       ws.by_rank, ws.size_by_rank, ws.fit_by_rank, ws.rank_of, ws.gate);
+                       ws.by_rank, ws.size_by_rank, ws.fit_by_rank, ws.rank_of, ws.is_large, ws.hist, ws.gate);
+    launch_scan(ws.is_large, ws.slots, ws.large_before, ws.scan_chunks, ws.scan_total, ws.gate, stream);
     hipLaunchKernelGGL(sp_windows, dim3(blocks), dim3(256), 0, stream, ws.by_rank, prm.ta, prm.tf, n, prm.acc, prm.size,
-                       ws.rank_of, ws.record, ws.hist, ws.gate);
+                       ws.rank_of, ws.large_before, ws.record, ws.large_fit, ws.hist, ws.gate);
     hipLaunchKernelGGL(sp_confirm, dim3(1), dim3(64), 0, stream, acc, ws.hist, n, ws.gate);
 
     SplitTables tb;
     tb.by_rank = ws.by_rank; tb.size_by_rank = ws.size_by_rank; tb.fit_by_rank = ws.fit_by_rank; tb.record = ws.record;
-    tb.addr = ws.addr; tb.group_bins = ws.group_bins; tb.group_top = ws.group_top;
+    tb.addr = ws.addr; tb.group_span = ws.group_span; tb.large_before = ws.large_before; tb.large_fit = ws.large_fit;
+    tb.large_addr = ws.large_addr; tb.large_slots = ws.large_slots;
     tb.slots = ws.slots; tb.groups = ws.slots / kWave; tb.list_cap = list_cap;
     tb.next_plan = ws.hist + kSpHistNextPlan;
     tb.region_shift = 6;
