@@ -720,6 +720,8 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
                 // wave settles these very requests, so it keeps their parts of the pool to itself (lane j:
                 // request wave + j * kWaves)
                 uint32_t part_first = 0, part_count = 0;
+                uint64_t rivals[kMine];
+                uint32_t found[kMine], total = 0;
 #pragma unroll
                 for (int j = 0; j < kMine; ++j) {
                     const int q = wave + j * kWaves;
@@ -728,17 +730,24 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
                     const uint32_t q_ta = read_lane(my_ta, q);
                     const bool rival = whi - wlo <= (uint32_t)kWave && wlo + lane < whi && f_addr[j] != kSpUnplaced &&
                                        f_fit[j].y > q_ta;
-                    const uint64_t rivals = __builtin_amdgcn_ballot_w64(rival);
-                    const uint32_t found = (uint32_t)__builtin_popcountll(rivals);
-                    uint32_t first = 0;
-                    if (found) {                                               // (uniform)
-                        if (lane == 0) first = atomicAdd(&sh.pool_used, found);
-                        first = read_lane(first, 0);
-                    }
-                    const bool fits = first + found <= (uint32_t)kSpPool;
-                    if (rival && fits) sh.pool[first + lanes_below(rivals)] = Span<uint32_t>{f_addr[j], f_addr[j] + f_fit[j].x};
+                    rivals[j] = __builtin_amdgcn_ballot_w64(rival);
+                    found[j] = (uint32_t)__builtin_popcountll(rivals[j]);
+                    total += found[j];
+                }
+                // (room in the pool for all of them at once)
+                uint32_t first = 0;
+                if (total) {                                                   // (uniform)
+                    if (lane == 0) first = atomicAdd(&sh.pool_used, total);
+                    first = read_lane(first, 0);
+                }
+#pragma unroll
+                for (int j = 0; j < kMine; ++j) {
+                    const bool fits = first + found[j] <= (uint32_t)kSpPool;
+                    if (((rivals[j] >> lane) & 1) && fits)
+                        sh.pool[first + lanes_below(rivals[j])] = Span<uint32_t>{f_addr[j], f_addr[j] + f_fit[j].x};
                     part_first = write_lane(part_first, first, j);
-                    part_count = write_lane(part_count, fits ? found : kSpRefetch, j);
+                    part_count = write_lane(part_count, fits ? found[j] : kSpRefetch, j);
+                    first += fits ? found[j] : 0u;
                 }
                 __syncthreads();
                 const uint64_t dep = sh.dep[lane];
