@@ -494,13 +494,16 @@ __device__ __forceinline__ uint32_t settle_request(const SpList& list, uint32_t 
     rq.s = read_lane(bt.size, (int)q); rq.ta = read_lane(bt.ta, (int)q); rq.tf = read_lane(bt.tf, (int)q);
     rq.wlo = read_lane(bt.wlo, (int)q); rq.whi = read_lane(bt.whi, (int)q);
     const uint32_t own_rank = read_lane(bt.rank, (int)q) & kSpRankMask;
-    // earlier requests of the batch with a conflicting lifetime: all settled by now
+    // What the first step needs from LDS is asked for in one go: the addresses of the batch, the
+    // request's part of the pool, the lowest 64 blocks of the list.
+    const uint32_t batch_addr = sh.rq_addr[b0 + lane];
+    Span<uint32_t> pooled = {0u, 0u};
+    if constexpr (!kWide) pooled = sh.pool[umin(pool_first + (uint32_t)lane, (uint32_t)kSpPool - 1)];
+    SpList::Entry en = list.load(umin((uint32_t)lane, count ? count - 1 : 0u));
+    // earlier requests of the batch with a conflicting lifetime: all settled by now (the mask says which lanes count)
     rq.rivals_in = dep_q;
-    rq.in_lo = 0; rq.in_hi = 0;
-    if (dep_q) {                                                    // (uniform)
-        rq.in_lo = sh.rq_addr[b0 + lane];
-        rq.in_hi = rq.in_lo + bt.size;
-    }
+    rq.in_lo = batch_addr;
+    rq.in_hi = batch_addr + bt.size;
     rq.rivals_w = 0; rq.w_lo = 0; rq.w_hi = 0;
     rq.large_lo = 0; rq.large_hi = 0;
     if constexpr (kWide) {
@@ -510,13 +513,9 @@ __device__ __forceinline__ uint32_t settle_request(const SpList& list, uint32_t 
     if constexpr (!kWide) {
         // conflicting short blocks of its window, as gathered when the batch began
         if (in_pool != kSpRefetch) {
-            if (in_pool) {                                          // (uniform)
-                Span<uint32_t> sp = {0u, 0u};
-                if ((uint32_t)lane < in_pool) sp = sh.pool[pool_first + lane];
-                rq.rivals_w = in_pool >= (uint32_t)kWave ? ~0ull : (1ull << in_pool) - 1;
-                rq.w_lo = sp.lo;
-                rq.w_hi = sp.hi;
-            }
+            rq.rivals_w = in_pool >= (uint32_t)kWave ? ~0ull : (1ull << in_pool) - 1;
+            rq.w_lo = pooled.lo;
+            rq.w_hi = pooled.hi;
         } else {
             const uint32_t k = rq.wlo + lane;                       // < slots
             const uint32_t a = pt.addr[k];
@@ -531,7 +530,9 @@ __device__ __forceinline__ uint32_t settle_request(const SpList& list, uint32_t 
     for (uint32_t k0 = 0; k0 < count; k0 += kWave) {
         const uint32_t k = k0 + lane;
         const bool valid = k < count;
-        const SpList::Entry en = list.load(valid ? k : count - 1);
+        // (the blocks of the next step are asked for before this step's are looked at)
+        SpList::Entry next = en;
+        if (k0 + kWave < count) next = list.load(umin(k + kWave, count - 1));
         const bool conflict = valid && en.ta() < rq.tf && rq.ta < en.tf();
         const uint32_t incl = wave_scan_max(conflict ? en.hi() : 0u);
         const uint32_t before = umax(run, wave_shift_up(incl, 0u));
@@ -545,6 +546,7 @@ __device__ __forceinline__ uint32_t settle_request(const SpList& list, uint32_t 
             if (c <= limit && limit - c >= rq.s) return c;
         }
         run = umax(run, read_lane(incl, kWave - 1));
+        en = next;
     }
     return clear_others<kWide, kWaves>(rq, own_rank, run, 0xffffffffu, tb, pt, turn, sh);     // on top of every conflicting long block
 }
