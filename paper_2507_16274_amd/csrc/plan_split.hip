@@ -77,6 +77,8 @@ struct SplitLds {
     uint2 pend_life[kSpBatch];
     Span<uint32_t> pool[kSpPool];                // conflicting short blocks of the windows of the batch's requests
     uint32_t pool_used;
+    uint32_t pool_first[kSpBatch];               // where a request's part of the pool begins,
+    uint32_t pool_count[kSpBatch];               // how many blocks it holds (kSpRefetch: they did not fit)
     uint32_t region_min[kWave];                  // lowest start / highest end address of the placed small short blocks of a
     uint32_t region_max[kWave];                  // region of ranks (64 regions cover the table)
     uint32_t large_min, large_max;               // the same over all placed large short blocks
@@ -629,10 +631,6 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
     const uint32_t shift = (uint32_t)(mode & 63);
     const int lane = lane_id(), wave = wave_id();
     if (blockIdx.x == 0 && threadIdx.x == 0) const_cast<uint64_t*>(prm.acc)[kAccKernel] = STALLOC_KERNEL_LONG_LIST | (32u << 8);
-    // the requests of a batch this wave settles: positions wave, wave + kWaves, ...
-    uint64_t stripe = 0;
-    for (int e = wave; e < kSpBatch; e += kWaves) stripe |= 1ull << e;
-
     SpList list, spare;
     list.bind(smem + sizeof(SplitLds), tb.list_cap);
     spare = list;
@@ -660,6 +658,7 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
         if (threadIdx.x < kWave) { sh.region_min[threadIdx.x] = 0xffffffffu; sh.region_max[threadIdx.x] = 0u; }
         if (threadIdx.x == 0) { sh.extent_now = 0; sh.peak = 0; sh.pool_used = 0; sh.reach[0] = 0; sh.large_min = 0xffffffffu; sh.large_max = 0u; }
         uint32_t turn = 0;                                            // calls of window_reach: slot 0 is clear
+        uint32_t round = 0;                                           // rounds so far: which wave takes the first ready request
 
         for (uint32_t r0 = 0; r0 < n; r0 += kSpRefill) {
             const uint32_t staged = n - r0 < (uint32_t)kSpRefill ? n - r0 : (uint32_t)kSpRefill;
@@ -721,7 +720,6 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
                 // the placed short blocks of each window that conflict in lifetime, packed into the pool; this
                 // wave settles these very requests, so it keeps their parts of the pool to itself (lane j:
                 // request wave + j * kWaves)
-                uint32_t part_first = 0, part_count = 0;
                 uint64_t rivals[kMine];
                 uint32_t found[kMine], total = 0;
 #pragma unroll
@@ -747,12 +745,15 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
                     const bool fits = first + found[j] <= (uint32_t)kSpPool;
                     if (((rivals[j] >> lane) & 1) && fits)
                         sh.pool[first + lanes_below(rivals[j])] = Span<uint32_t>{f_addr[j], f_addr[j] + f_fit[j].x};
-                    part_first = write_lane(part_first, first, j);
-                    part_count = write_lane(part_count, fits ? found[j] : kSpRefetch, j);
+                    if (lane == 0) {
+                        sh.pool_first[wave + j * kWaves] = first;
+                        sh.pool_count[wave + j * kWaves] = fits ? found[j] : kSpRefetch;
+                    }
                     first += fits ? found[j] : 0u;
                 }
                 __syncthreads();
                 const uint64_t dep = sh.dep[lane];
+                const uint32_t part_first = sh.pool_first[lane], part_count = sh.pool_count[lane];
                 const uint64_t all = nb == (uint32_t)kSpBatch ? ~0ull : (1ull << nb) - 1;
                 uint64_t done = 0;
                 const uint64_t wide = __builtin_amdgcn_ballot_w64(mine && my_whi - my_wlo > (uint32_t)kWave);
@@ -760,12 +761,15 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
                     // settled: bit set in `done`; ready: everything it waits for is settled.  (What is ready
                     // together does not conflict with each other, so the order inside a round is free.)
                     const uint64_t ready = __builtin_amdgcn_ballot_w64(mine && !((done >> lane) & 1) && (dep & ~done) == 0);
-                    // the waves share the requests with narrow windows, a request each ...
-                    for (uint64_t todo = ready & stripe & ~wide; todo; todo &= todo - 1) {
+                    // the ready requests with narrow windows go round the waves, a request each ...
+                    const uint64_t narrow = ready & ~wide;
+                    const bool take = ((narrow >> lane) & 1) && (lanes_below(narrow) + round) % kWaves == (uint32_t)wave;
+                    ++round;
+                    for (uint64_t todo = __builtin_amdgcn_ballot_w64(take); todo; todo &= todo - 1) {
                         const int q = __builtin_ctzll(todo);
                         const uint32_t x = settle_request<false, kWaves>(list, count, b0, (uint32_t)q, readlane64(dep, q), bt,
-                                                                         read_lane(part_first, q / kWaves),
-                                                                         read_lane(part_count, q / kWaves), tb, pt, turn, sh);
+                                                                         read_lane(part_first, q), read_lane(part_count, q), tb, pt,
+                                                                         turn, sh);
                         if (lane == 0) {
                             sh.rq_addr[b0 + q] = x;
                             atomicMax(&sh.peak, x + read_lane(my_size, q));
