@@ -173,20 +173,26 @@ __device__ __forceinline__ void merge_pass(const List& list, const List& dst, ui
 constexpr int kMergeSub = STALLOC_MERGE_SUB;     // 64-entry steps one wave handles per merge segment
 
 // Merges the side buffer (sh.pend_*, sorted, `pending` >= 1 blocks, already visible to the whole
-// workgroup) into the sorted list.  The list is cut into segments of kThreads * kMergeSub
+// workgroup) into the sorted list.  The list is cut into segments of kThreads * kSub
 // entries which are handled from the top down: blocks only move up, so a segment's writes
 // never touch entries of the segments below it, which are read later.  When the list is in LDS
 // the merge is in place (a barrier separates a segment's reads from its writes); otherwise
 // it goes into the spare slab.
-template <typename Addr, bool kLds, int kThreads, typename List, typename Lds>
+template <typename Addr, bool kLds, int kThreads, int kSub = kMergeSub, typename List, typename Lds>
 __device__ __forceinline__ void merge_pending(List& list, List& spare, uint32_t count, uint32_t pending, Lds& sh)
 {
-    constexpr uint32_t kSegment = (uint32_t)kThreads * kMergeSub;
+    constexpr uint32_t kSegment = (uint32_t)kThreads * kSub;
     const Pending<Addr> pd = load_pending<Addr>(sh, pending);
     const List& dst = kLds ? list : spare;
     const uint32_t segments = count / kSegment + 1;          // the position just past the end counts too
-    for (uint32_t g = segments; g-- > 0;)
-        merge_pass<Addr, kLds, kThreads, kMergeSub>(list, dst, count, g * kSegment, pd, pending, sh);
+    for (uint32_t g = segments; g-- > 0;) {
+        merge_pass<Addr, kLds, kThreads, kSub>(list, dst, count, g * kSegment, pd, pending, sh);
+        // In place, a block stays where it is when no pending block starts at or below it: once the
+        // block in front of a segment starts below the lowest pending block, the rest is done.
+        if constexpr (kLds) {
+            if (g > 0 && read_lane((Addr)list.load(g * kSegment - 1).lo(), 0) < read_lane(pd.lo, 0)) break;
+        }
+    }
     if constexpr (!kLds) { List t = list; list = spare; spare = t; }
     __syncthreads();
 }

@@ -824,7 +824,8 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
                 }
                 __syncthreads();
                 if (pending) {
-                    merge_pending<uint32_t, true, kThreads>(list, spare, count, pending, sh);
+                    // (short segments: the few long blocks of a batch mostly leave the lower part of the list as it is)
+                    merge_pending<uint32_t, true, kThreads, 1>(list, spare, count, pending, sh);
                     count += pending;
                 }
             }
