@@ -326,6 +326,10 @@ typedef struct stalloc_plan_info {
     uint32_t long_requests;      /* ... and how many there are                                    */
     uint32_t address_bits;       /* width of the addresses the kernel keeps per placed block: 16, 22, 32 (counts of
                                     granules) or 64 (bytes)                                       */
+    uint64_t large_size;         /* STALLOC_KERNEL_LONG_LIST: short-lived requests of at least this many bytes are
+                                    kept in a table of their own as well (0: none are)            */
+    uint32_t large_requests;     /* ... and how many there are                                    */
+    uint32_t reserved;
 } stalloc_plan_info;
 
 int stalloc_plan_report(const void *workspace, stalloc_plan_info *info, void *hip_stream);

@@ -78,6 +78,8 @@ constexpr int kAccSplit = 7;                   // bit 0: the kernel that keeps o
                                                // trace; bits 8..31: its lifetime threshold; bits 32..63: long-lived requests
 constexpr int kAccKernel = 8;                  // which placement kernel took the trace (stalloc_plan_kernel in stalloc.h)
 constexpr int kAccWidePlans = 9;               // plans that outgrew 32-bit granule counts and were placed with 64-bit addresses
+constexpr int kAccLargeShort = 10;             // long-list kernel: size (granules) from which a short-lived block counts as large
+                                               // (0xffffffff: none does); bits 32..63: how many do
 constexpr uint64_t kModeNarrow = 1ull << 8;
 constexpr uint64_t kModeCompact = 1ull << 9;   // sum of sizes in granules below 2^16 as well
 constexpr uint64_t kModeBitmap = 1ull << 10;   // sum <= kBitmapGranules and every size <= kBitmapMaxSize granules

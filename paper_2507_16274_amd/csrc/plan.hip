@@ -676,6 +676,10 @@ extern "C" int stalloc_plan_report(const void* workspace, stalloc_plan_info* inf
     info->plans_64bit = (uint32_t)acc[kAccWidePlans];
     info->lifetime_threshold = (acc[kAccSplit] & 1) ? (uint32_t)((acc[kAccSplit] >> 8) & 0xffffffu) : 0u;
     info->long_requests = (acc[kAccSplit] & 1) ? (uint32_t)(acc[kAccSplit] >> 32) : 0u;
+    const bool large = (acc[kAccSplit] & 1) && (uint32_t)acc[kAccLargeShort] != 0xffffffffu;
+    info->large_size = large ? (acc[kAccLargeShort] & 0xffffffffull) << (acc[kAccMode] & 63) : 0ull;
+    info->large_requests = large ? (uint32_t)(acc[kAccLargeShort] >> 32) : 0u;
+    info->reserved = 0;
     return STALLOC_OK;
 }
 

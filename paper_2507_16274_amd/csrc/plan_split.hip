@@ -329,6 +329,8 @@ struct SplitTables {
     uint32_t list_cap;           // entries of the LDS list
     uint32_t region_shift;       // 2^region_shift ranks share one summary in LDS; at most 64 regions cover all slots
     uint32_t* next_plan;         // [1] plans handed out so far
+    const uint32_t* sigma;       // [1] size from which a short-lived block counts as large
+    const uint32_t* large_total; // [1] how many do
 };
 
 // What one wave knows about the request it settles.
@@ -630,7 +632,10 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
     const bool try32 = (mode & kModeTry32) != 0;
     const uint32_t shift = (uint32_t)(mode & 63);
     const int lane = lane_id(), wave = wave_id();
-    if (blockIdx.x == 0 && threadIdx.x == 0) const_cast<uint64_t*>(prm.acc)[kAccKernel] = STALLOC_KERNEL_LONG_LIST | (32u << 8);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        const_cast<uint64_t*>(prm.acc)[kAccKernel] = STALLOC_KERNEL_LONG_LIST | (32u << 8);
+        const_cast<uint64_t*>(prm.acc)[kAccLargeShort] = (uint64_t)*tb.sigma | ((uint64_t)*tb.large_total << 32);
+    }
     SpList list, spare;
     list.bind(smem + sizeof(SplitLds), tb.list_cap);
     spare = list;
@@ -905,6 +910,8 @@ bool launch_plan_split(const PlanParams& prm, uint32_t t_end, const SplitWorkspa
     tb.large_addr = ws.large_addr; tb.large_slots = ws.large_slots;
     tb.slots = ws.slots; tb.groups = ws.slots / kWave; tb.list_cap = list_cap;
     tb.next_plan = ws.hist + kSpHistNextPlan;
+    tb.sigma = ws.hist + kSpHistSigma;
+    tb.large_total = ws.scan_total;
     tb.region_shift = 6;
     while (((uint64_t)ws.slots + (1ull << tb.region_shift) - 1) >> tb.region_shift > (uint64_t)kWave) ++tb.region_shift;
     auto kernel = &plan_split_kernel<kSpThreads>;

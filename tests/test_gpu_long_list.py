@@ -99,6 +99,39 @@ def test_random_traces_of_two_kinds(S, oracle, seed):
     assert got["info"]["granule_log2"] == (0 if odd else 9)
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_large_short_lived_blocks_have_a_table_of_their_own(S, oracle, seed):
+    """A twelfth to a tenth of the short-lived requests are as large as the long-lived ones, the others
+    small, with empty size classes between (as in a training trace): the large ones are also kept in a
+    table that a long-lived request reads whole.  Several large sizes, tied timestamps, bursts that give
+    large short requests wide windows of their own; a trace in which too many are large has no such table."""
+    rng = np.random.default_rng(9100 + seed)
+    n = int(rng.integers(9600, 13000))
+    small = [512, 1024, 1536, 4096, 1 << 16]
+    large = [1 << 20, 3 << 19, 1 << 21] if seed % 2 == 0 else [1 << 24]
+    share = 11 if seed < 4 else 3                                     # one large size among `share` + 1 choices
+    sizes_short = [int(rng.choice(small)) for _ in range(share * len(large))] + large
+    quantum = 2 if seed == 3 else 1
+    tr = two_kinds(rng, n, int(rng.integers(100, 900)), 15 if quantum == 1 else 7, [1 << 20, 3 << 20, 1 << 22], sizes_short,
+                   quantum=quantum)
+    if seed == 1:                                                     # a burst of short-lived requests, large ones among them
+        ts, te = tr.t_alloc.astype(np.int64), tr.t_free.astype(np.int64)
+        burst = np.nonzero(te - ts <= 15)[0][:120]
+        life = te[burst] - ts[burst]
+        ts[burst] = 7000
+        te[burst] = 7000 + life
+        tr = Trace(name="burst", size=tr.size, t_alloc=ts.astype(np.uint32), t_free=te.astype(np.uint32), t_end=int(te.max()))
+    got, a, ext = _compare(S, oracle, tr, _orders(rng, tr, 3))
+    short = (tr.t_free.astype(np.int64) - tr.t_alloc) <= got["info"]["lifetime_threshold"]
+    # (the smallest size class from which at most an eighth are large, at the widest gap between classes)
+    want = {0: 1 << 20, 1: 1 << 24, 2: 1 << 20, 3: 1 << 24, 4: 1 << 21, 5: 0}[seed]   # 4: only the largest of three; 5: a quarter in one class
+    assert got["info"]["large_size"] == want
+    if want:
+        assert got["info"]["large_requests"] == int((short & (tr.size >= want)).sum()) > 500
+    else:
+        assert got["info"]["large_requests"] == 0
+
+
 def test_crowded_short_lived_requests_overflow_the_window_pool(S, oracle):
     """Short lifetimes of up to 31 timestamps: late in an order a request finds some twenty placed
     short blocks in its window, more than the LDS pool of a batch holds for all 64 requests; the windows
