@@ -52,7 +52,7 @@ KERNEL_NAMES = {"bitmap": "plan_bitmap_kernel", "list_lds": "plan_kernel", "list
 # known size in the same run; the summaries are under profiles/).  Keyed by (configuration, orders);
 # each entry names the kernel sources it was measured with (source_digest() below): with any other
 # sources the figure is not reported.
-MEASURED_TRAFFIC = {(5, 4096): {"bytes": (705_313_000 * 2 + 478_457_000) * 1024, "sources": "0c55439974f5f914"}}
+MEASURED_TRAFFIC = {(5, 4096): {"bytes": (260_895_102 * 2 + 102_138_487) * 1024, "sources": "1bd967b4043a93e5"}}
 
 
 def source_digest() -> str:
@@ -253,6 +253,7 @@ def main() -> int:
         "traffic": traffic["bytes"] if traffic and traffic["sources"] == digest else None,
         "kernel_ms": plan_ms, "placement_kernel": info["kernel"], "stored_block_bytes": entry_bytes, "blocks_in_lds": in_lds,
         "lifetime_threshold": info["lifetime_threshold"], "long_requests": info["long_requests"],
+        "large_short_lived_from_bytes": info["large_size"], "large_short_lived_requests": info["large_requests"],
         "plans_placed_again_with_64_bit_addresses": info["plans_64bit"],
         "algorithmic_ops": algo_ops, "algorithmic_list_bytes": state_bytes, "algorithmic_hbm_bytes": hbm_bytes,
         "floor_ms": {k: v * 1e3 for k, v in floors.items()},

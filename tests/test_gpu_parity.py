@@ -411,6 +411,11 @@ def test_plan_config5_full_launch_stratified_orderings(S, oracle, half):
     full = _compare_rows_of_full_launch(S, oracle, 5, rows[half::2])
     assert full["info"]["kernel"] == "long_list" and full["info"]["plans_64bit"] == 0
     assert full["info"]["lifetime_threshold"] == 15 and full["info"]["long_requests"] == 4271
+    # the short-lived requests of 128 MiB and more (nothing between 64 KiB and them) have a table of their own
+    tr = make_trace(5)
+    short = tr.t_free.astype(np.int64) - tr.t_alloc <= 15
+    assert full["info"]["large_size"] == 1 << 27
+    assert full["info"]["large_requests"] == int((short & (tr.size >= 1 << 27)).sum()) > 0
 
 
 @pytest.mark.parametrize("n_clique,n_extra,unit,fill", [(230, 70, 1 << 24, 0.80), (230, 70, 1 << 24, 0.875),
