@@ -106,6 +106,9 @@ def main() -> int:
     ap.add_argument("--layers", action="store_true",
                     help="also build the memory-layers of the trace (Algorithm 1), plan the layers under as many "
                          "orders and expand the plans to the requests, in a timed region of its own")
+    ap.add_argument("--fusion", action="store_true",
+                    help="also fuse every candidate pair of HomoPhase groups of the trace (Sec. 5.1) in a timed region "
+                         "of its own")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference dispatch for HBM byte counters)")
     args = ap.parse_args()
@@ -364,6 +367,34 @@ def main() -> int:
                          "frac": 4 * n * P / (mo_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
                          "algorithmic_bytes": 4 * n * P,
                          "sort_buffer_GBs": (32 * passes + 4) * n * P / (mo_ms * 1e-3) / 1e9}}
+
+    if args.fusion:
+        # HomoPhase groups (requests allocated in one phase and released in one other phase) and every pair of
+        # them in which one is released in the phase the other is allocated in: one workgroup per pair, a
+        # chain of placement steps inside (bound by that chain, not by bytes or lane operations).
+        from workloads.groups import candidate_pairs, flatten_pairs
+        groups, pairs = candidate_pairs(tr.p_alloc, tr.p_free)
+        members, begin, count1, largest = flatten_pairs(groups, pairs)
+        dev = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int32)).cuda()
+        d_members, d_begin, d_count1 = dev(members), dev(begin), dev(count1)
+        cache_f = {}
+        fuse = lambda: S.stalloc_fuse_groups(size, ta, tf, tr.t_end, d_members, d_begin, d_count1, largest, workspace_cache=cache_f)
+        for _ in range(max(args.warmup, 1)):
+            fuse()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            f = fuse()
+        e1.record()
+        torch.cuda.synchronize()
+        S.check_status(f, "stalloc_fuse_groups")
+        f_acc, f_ext = f["accepted"].cpu().numpy(), f["extents"].cpu().numpy().view(np.uint64)
+        if (f_ext[:, 2] > f_ext[:, 0] + f_ext[:, 1]).any() or (f_ext[:, 2] < np.maximum(f_ext[:, 0], f_ext[:, 1])).any():
+            print("bench.py: a fused plan is larger than its two plans stacked, or smaller than the larger of them", file=sys.stderr)
+            return 1
+        result["fusion"] = {"groups": len(groups), "pairs": len(pairs), "requests_in_pairs": int(len(members)),
+                            "largest_pair": largest, "accepted": int(f_acc.sum()), "ms_per_call": e0.elapsed_time(e1) / args.steps}
 
     if args.layers:
         # HomoSize groups -> memory-layers (Sec. 5.1, Algorithm 1), each layer planned as one request under
