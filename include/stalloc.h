@@ -95,6 +95,23 @@ int stalloc_plan(const stalloc_trace *trace, const uint32_t *orders, uint32_t P,
                  void *workspace, size_t *workspace_bytes, void *hip_stream);
 
 /*
+ * stalloc_plan for a caller that knows something about its sizes (same rule, same results; Sec. 5.1).
+ * Which kernel places a trace is decided on the device, so stalloc_plan sizes its workspace for all
+ * of them, among them the one for traces of few granules with its index of lifetime-overlapping pairs
+ * (about 2 n^2 bytes for n <= 32768).  With
+ *   largest_size  no request is larger than this many bytes (> 0), and
+ *   granule       a power of two that divides every size (1 if nothing better is known),
+ * a call whose sizes cannot suit that kernel (largest_size / granule > 31) leaves it and its index out
+ * of the launch and of the workspace.  The figures are only used to leave work out: wrong ones cost
+ * time or memory, never correctness.  The workspace query and the call must be given the same two.
+ */
+int stalloc_plan_sized(const stalloc_trace *trace, const uint32_t *orders, uint32_t P,
+                       uint64_t *offsets, uint64_t *peaks, uint64_t *best_offsets,
+                       uint32_t *best_plan, uint32_t *device_status,
+                       uint64_t largest_size, uint64_t granule,
+                       void *workspace, size_t *workspace_bytes, void *hip_stream);
+
+/*
  * Pairwise check of the constraint of Sec. 5.1 for P plans of one trace.
  *
  *   offsets     device [P][n].  offsets + size must stay below 2^64 for every request of every

@@ -27,7 +27,7 @@ EXPORTS = ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_l
            "stalloc_reusable_space",
            "stalloc_memory_layers", "stalloc_expand_layers", "stalloc_tmp", "stalloc_make_orders",
            "stalloc_status_string", "stalloc_plan_lds_capacity", "stalloc_plan_report", "stalloc_probe",
-           "stalloc_fuse_groups")
+           "stalloc_fuse_groups", "stalloc_plan_sized")
 KERNELS = {0: "none", 1: "bitmap", 2: "list_lds", 3: "list_memory", 4: "long_list"}
 
 
@@ -58,6 +58,7 @@ def _load() -> ctypes.CDLL:
     szp = ctypes.POINTER(ctypes.c_size_t)
     tp = ctypes.POINTER(_Trace)
     lib.stalloc_plan.argtypes = [tp, vp, u32, vp, vp, vp, vp, vp, vp, szp, vp]
+    lib.stalloc_plan_sized.argtypes = [tp, vp, u32, vp, vp, vp, vp, vp, ctypes.c_uint64, ctypes.c_uint64, vp, szp, vp]
     lib.stalloc_validate.argtypes = [tp, vp, u32, vp, vp, vp, vp, szp, vp]
     lib.stalloc_lower_bound.argtypes = [tp, vp, vp, vp, vp, szp, vp]
     lib.stalloc_lower_bound_static.argtypes = [tp, vp, vp, vp, vp]
@@ -69,7 +70,7 @@ def _load() -> ctypes.CDLL:
     lib.stalloc_fuse_groups.argtypes = [tp, vp, vp, vp, u32, u32, vp, vp, vp, vp, vp, vp, szp, vp]
     for name in ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_lower_bound_static",
                  "stalloc_reusable_space", "stalloc_memory_layers", "stalloc_expand_layers", "stalloc_tmp",
-                 "stalloc_make_orders", "stalloc_fuse_groups"):
+                 "stalloc_make_orders", "stalloc_fuse_groups", "stalloc_plan_sized"):
         getattr(lib, name).restype = ctypes.c_int
     lib.stalloc_plan_report.argtypes = [vp, ctypes.POINTER(_PlanInfo), vp]
     lib.stalloc_plan_report.restype = ctypes.c_int
@@ -129,6 +130,19 @@ def stalloc_plan(size, t_alloc, t_free, t_end: int, orders, *, want_offsets: boo
     peaks int64 [P], best_offsets int64 [n] (None unless want_best_offsets),
     best_plan int32 [1], status int32 [1].  `out` may carry preallocated outputs.
     """
+    return _plan(lib.stalloc_plan, "stalloc_plan", (), size, t_alloc, t_free, t_end, orders, want_offsets, want_best_offsets,
+                 stream, workspace_cache, out)
+
+
+def stalloc_plan_sized(size, t_alloc, t_free, t_end: int, orders, largest_size: int, granule: int, *,
+                       want_offsets: bool = True, want_best_offsets: bool = True, stream=None,
+                       workspace_cache: Optional[Dict] = None, out: Optional[Dict] = None) -> Dict[str, torch.Tensor]:
+    """stalloc_plan for a caller that knows an upper bound of its sizes and a power of two dividing them all."""
+    return _plan(lib.stalloc_plan_sized, "stalloc_plan_sized", (int(largest_size), int(granule)), size, t_alloc, t_free, t_end,
+                 orders, want_offsets, want_best_offsets, stream, workspace_cache, out)
+
+
+def _plan(fn, name, extra, size, t_alloc, t_free, t_end, orders, want_offsets, want_best_offsets, stream, workspace_cache, out):
     tr = _trace(size, t_alloc, t_free, t_end)
     if orders.dim() != 2 or orders.shape[1] != tr.n:
         raise ValueError("orders must be [P][n]")
@@ -151,13 +165,14 @@ def stalloc_plan(size, t_alloc, t_free, t_end: int, orders, *, want_offsets: boo
     args = (ctypes.byref(tr), _dev(orders, torch.int32, "orders"), P,
             _dev(out["offsets"], torch.int64, "offsets"), _dev(out["peaks"], torch.int64, "peaks"),
             _dev(out["best_offsets"], torch.int64, "best_offsets"),
-            _dev(out["best_plan"], torch.int32, "best_plan"), _dev(out["status"], torch.int32, "status"))
+            _dev(out["best_plan"], torch.int32, "best_plan"), _dev(out["status"], torch.int32, "status")) + tuple(extra)
     need = ctypes.c_size_t(0)
-    _check(lib.stalloc_plan(*args, None, ctypes.byref(need), None), "stalloc_plan(workspace query)")
+    _check(fn(*args, None, ctypes.byref(need), None), name + "(workspace query)")
     ws = _workspace(need.value, dev, workspace_cache)
     have = ctypes.c_size_t(ws.numel())
-    _check(lib.stalloc_plan(*args, ws.data_ptr(), ctypes.byref(have), _stream(stream)), "stalloc_plan")
+    _check(fn(*args, ws.data_ptr(), ctypes.byref(have), _stream(stream)), name)
     out["workspace"] = ws
+    out["workspace_bytes"] = need.value
     return out
 
 

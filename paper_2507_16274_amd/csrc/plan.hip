@@ -690,9 +690,11 @@ extern "C" uint32_t stalloc_plan_lds_capacity(void)
     return lds_capacity_entries<uint32_t, kThreadsLds>(di.lds_per_block, entry_bytes<uint32_t>());
 }
 
-extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uint32_t P, uint64_t* offsets,
-                            uint64_t* peaks, uint64_t* best_offsets, uint32_t* best_plan, uint32_t* device_status,
-                            void* workspace, size_t* workspace_bytes, void* hip_stream)
+// allow_bitmap: false when the caller has said that its sizes cannot suit the occupancy-bitmap kernel; that
+// kernel and its index of lifetime-overlapping pairs are then left out of the call and of the workspace.
+static int plan_call(const stalloc_trace* tr, const uint32_t* orders, uint32_t P, uint64_t* offsets, uint64_t* peaks,
+                     uint64_t* best_offsets, uint32_t* best_plan, uint32_t* device_status, bool allow_bitmap,
+                     void* workspace, size_t* workspace_bytes, void* hip_stream)
 {
     if (!trace_args_ok(tr) || P == 0 || !workspace_bytes) return STALLOC_ERR_INVALID_ARG;
     DeviceInfo di;
@@ -715,7 +717,7 @@ extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uin
     uint32_t* wide_plans = cv.take<uint32_t>(P);
     // occupancy-bitmap variant: lifetime-conflict index of the trace
     uint32_t pool_words[kBitmapShapes];
-    const bool bitmap = bitmap_plan_shapes(n, di, pool_words);
+    const bool bitmap = bitmap_plan_shapes(n, di, pool_words) && allow_bitmap;
     uint32_t* nbr_begin = bitmap ? cv.take<uint32_t>((size_t)n + 2) : nullptr;
     uint16_t* nbr = bitmap ? cv.take<uint16_t>(bitmap_index_entries(n)) : nullptr;
     // variant for long traces with few long-lived requests: tables in allocation-time order
@@ -761,4 +763,23 @@ extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uin
                            device_status);
     }
     return hipGetLastError() == hipSuccess ? STALLOC_OK : STALLOC_ERR_DEVICE;
+}
+
+extern "C" int stalloc_plan(const stalloc_trace* tr, const uint32_t* orders, uint32_t P, uint64_t* offsets,
+                            uint64_t* peaks, uint64_t* best_offsets, uint32_t* best_plan, uint32_t* device_status,
+                            void* workspace, size_t* workspace_bytes, void* hip_stream)
+{
+    return plan_call(tr, orders, P, offsets, peaks, best_offsets, best_plan, device_status, true, workspace, workspace_bytes,
+                     hip_stream);
+}
+
+extern "C" int stalloc_plan_sized(const stalloc_trace* tr, const uint32_t* orders, uint32_t P, uint64_t* offsets,
+                                  uint64_t* peaks, uint64_t* best_offsets, uint32_t* best_plan, uint32_t* device_status,
+                                  uint64_t largest_size, uint64_t granule, void* workspace, size_t* workspace_bytes,
+                                  void* hip_stream)
+{
+    if (granule == 0 || (granule & (granule - 1)) != 0 || largest_size == 0) return STALLOC_ERR_INVALID_ARG;
+    const bool allow_bitmap = largest_size / granule <= kBitmapMaxSize;
+    return plan_call(tr, orders, P, offsets, peaks, best_offsets, best_plan, device_status, allow_bitmap, workspace,
+                     workspace_bytes, hip_stream);
 }

@@ -152,6 +152,36 @@ def test_validate_ragged_tile_sizes(S, oracle):
             assert (int(cnt[p]), tuple(int(x) for x in pair[p])) == want
 
 
+def test_plan_sized_leaves_the_bitmap_kernel_and_its_index_out_when_the_sizes_rule_it_out(S, oracle):
+    """Config 2 suits the occupancy-bitmap kernel (sizes of 1 to 8 granules of 32 MiB).  Told the truth about
+    its sizes, the sized call does what stalloc_plan does; told that sizes reach 64 granules, it leaves
+    that kernel and its index of lifetime-overlapping pairs (76 MB here) out and the sorted list places the
+    trace: same addresses either way.  Nonsense figures are refused on the host."""
+    import torch
+    tr = make_trace(2)
+    orders = make_orderings(tr, 16)
+    size, ta, tf = S.trace_to_device(tr)
+    o = torch.from_numpy(orders.view(np.int32)).cuda()
+    a, ext = oracle.plan_many(tr.size, tr.t_alloc, tr.t_free, orders, threads=THREADS, method="lists")
+    plain = S.stalloc_plan(size, ta, tf, tr.t_end, o)
+    kinds = {}
+    for name, largest, granule in (("true", int(tr.size.max()), 1 << 25), ("ruled out", 64 << 25, 1 << 25),
+                                   ("no granule known", int(tr.size.max()), 1)):
+        out = S.stalloc_plan_sized(size, ta, tf, tr.t_end, o, largest, granule)
+        torch.cuda.synchronize()
+        assert int(out["status"].item()) == 0
+        assert np.array_equal(out["offsets"].cpu().numpy().view(np.uint64), a), name
+        assert np.array_equal(out["peaks"].cpu().numpy().view(np.uint64), ext), name
+        kinds[name] = (S.stalloc_plan_report(out)["kernel"], out["workspace_bytes"])
+    assert kinds["true"] == ("bitmap", plain["workspace_bytes"])
+    assert kinds["ruled out"][0] == kinds["no granule known"][0] == "list_lds"
+    assert kinds["ruled out"][1] == kinds["no granule known"][1] < plain["workspace_bytes"] - 70_000_000
+    for largest, granule in ((0, 512), (4096, 0), (4096, 768)):
+        with pytest.raises(S.StallocError) as err:
+            S.stalloc_plan_sized(size, ta, tf, tr.t_end, o, largest, granule)
+        assert err.value.code == 1
+
+
 def test_validate_reports_an_address_range_that_would_wrap(S, oracle):
     """A corrupted plan with an address near 2^64: offset + size wraps to a small number and the block
     would look disjoint from everything.  The call reports it and still counts what the block covers."""
