@@ -26,7 +26,6 @@ this machine's host cores: one thread on a fixed few orders, and all threads.
 from __future__ import annotations
 
 import argparse
-import glob
 import hashlib
 import json
 import os
@@ -50,17 +49,22 @@ KERNEL_NAMES = {"bitmap": "plan_bitmap_kernel", "list_lds": "plan_kernel", "list
 # HBM-side bytes per launch of the placement kernel, from two rocprofv3 --pmc runs of this script
 # (FETCH_SIZE and WRITE_SIZE in KiB, each scaled by what the same counter reads for a plain copy of
 # known size in the same run; the summaries are under profiles/).  Keyed by (configuration, orders);
-# each entry names the kernel sources it was measured with (source_digest() below): with any other
-# sources the figure is not reported.
-MEASURED_TRAFFIC = {(5, 4096): {"bytes": (260_848_785 * 2 + 102_138_250) * 1024, "sources": "951e525a2e112302"}}
+# each entry names the sources of stalloc_plan it was measured with (source_digest() below): with any
+# other sources the figure is not reported.
+MEASURED_TRAFFIC = {(5, 4096): {"bytes": (260_848_785 * 2 + 102_138_250) * 1024, "sources": "3210988e9872cc17"}}
+
+
+# The sources stalloc_plan and its kernels are built from (the other entry points have files of their own).
+PLAN_SOURCES = ("plan.hip", "plan_split.hip", "plan_bitmap.hip", "plan_list.h", "plan_params.h", "host_util.h", "wave.h",
+                "sort_keys.h", "trace_check.hip", "orders.hip", "layers.hip")
 
 
 def source_digest() -> str:
-    """SHA-256 over the kernel sources the library is built from (csrc/*.hip, csrc/*.h, by name)."""
+    """SHA-256 over the sources of stalloc_plan and its kernels (csrc/, by name)."""
     h = hashlib.sha256()
-    for path in sorted(glob.glob(os.path.join(ROOT, "paper_2507_16274_amd", "csrc", "*.h*"))):
-        h.update(os.path.basename(path).encode())
-        h.update(open(path, "rb").read())
+    for name in sorted(PLAN_SOURCES):
+        h.update(name.encode())
+        h.update(open(os.path.join(ROOT, "paper_2507_16274_amd", "csrc", name), "rb").read())
     return h.hexdigest()[:16]
 
 

@@ -293,7 +293,8 @@ int stalloc_make_orders(const stalloc_trace *trace, uint32_t first_plan, uint32_
  *                 The requests of one pair must be distinct (not detected: the result is then
  *                 unspecified, but memory-safe); an entry >= n sets device_status to
  *                 STALLOC_ERR_BAD_ORDER.
- *   pair_begin    device [k+1], ascending, pair_begin[0] = 0.
+ *   pair_begin    device [k+1], ascending, pair_begin[0] = 0, pair_begin[k] <= m (a pair that reaches
+ *                 beyond m, or backwards, sets device_status to STALLOC_ERR_INVALID_ARG).
  *   count1        device [k]: how many of pair p's requests belong to its first group; both
  *                 groups must be non-empty (else device_status = STALLOC_ERR_INVALID_ARG).
  *   largest_pair  the largest pair_begin[p+1] - pair_begin[p]; a pair lives in one workgroup's
@@ -307,7 +308,7 @@ int stalloc_make_orders(const stalloc_trace *trace, uint32_t first_plan, uint32_
  * Outputs of a pair are written only when device_status stays STALLOC_OK up to its turn.
  */
 int stalloc_fuse_groups(const stalloc_trace *trace, const uint32_t *members, const uint32_t *pair_begin,
-                        const uint32_t *count1, uint32_t k, uint32_t largest_pair, uint32_t *order,
+                        const uint32_t *count1, uint32_t k, uint32_t m, uint32_t largest_pair, uint32_t *order,
                         uint64_t *addr, uint64_t *extents, uint32_t *accepted, uint32_t *device_status,
                         void *workspace, size_t *workspace_bytes, void *hip_stream);
 

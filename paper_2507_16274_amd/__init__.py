@@ -67,7 +67,7 @@ def _load() -> ctypes.CDLL:
     lib.stalloc_expand_layers.argtypes = [u32, u32, vp, vp, u32, vp, vp, vp]
     lib.stalloc_tmp.argtypes = [tp, vp, u32, vp, vp, vp, szp, vp]
     lib.stalloc_make_orders.argtypes = [tp, u32, u32, ctypes.c_uint64, vp, vp, vp, szp, vp]
-    lib.stalloc_fuse_groups.argtypes = [tp, vp, vp, vp, u32, u32, vp, vp, vp, vp, vp, vp, szp, vp]
+    lib.stalloc_fuse_groups.argtypes = [tp, vp, vp, vp, u32, u32, u32, vp, vp, vp, vp, vp, vp, szp, vp]
     for name in ("stalloc_plan", "stalloc_validate", "stalloc_lower_bound", "stalloc_lower_bound_static",
                  "stalloc_reusable_space", "stalloc_memory_layers", "stalloc_expand_layers", "stalloc_tmp",
                  "stalloc_make_orders", "stalloc_fuse_groups", "stalloc_plan_sized"):
@@ -356,7 +356,7 @@ def stalloc_fuse_groups(size, t_alloc, t_free, t_end: int, members, pair_begin, 
            "accepted": torch.empty(k, dtype=torch.int32, device=dev),
            "status": torch.empty(1, dtype=torch.int32, device=dev)}
     args = (ctypes.byref(tr), _dev(members, torch.int32, "members"), _dev(pair_begin, torch.int32, "pair_begin"),
-            _dev(count1, torch.int32, "count1"), k, int(largest_pair), out["order"].data_ptr(), out["addr"].data_ptr(),
+            _dev(count1, torch.int32, "count1"), k, m, int(largest_pair), out["order"].data_ptr(), out["addr"].data_ptr(),
             out["extents"].data_ptr(), out["accepted"].data_ptr(), out["status"].data_ptr())
     need = ctypes.c_size_t(0)
     _check(lib.stalloc_fuse_groups(*args, None, ctypes.byref(need), None), "stalloc_fuse_groups(workspace query)")

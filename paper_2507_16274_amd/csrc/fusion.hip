@@ -39,6 +39,7 @@ struct FuseParams {
     uint32_t* accepted;
     uint32_t* status;
     uint32_t n;
+    uint32_t entries;        // length of members / order / addr
     uint32_t cap;            // requests of one pair that fit the LDS arrays
 };
 
@@ -68,9 +69,10 @@ __global__ void __launch_bounds__(kFuThreads) fuse_pairs(FuseParams prm)
     __shared__ uint32_t t_lo[2], t_hi[2];
     if (*prm.status != STALLOC_OK) return;
     const uint32_t p = blockIdx.x, tid = threadIdx.x;
-    const uint32_t m0 = prm.pair_begin[p], m = prm.pair_begin[p + 1] - m0, c1 = prm.count1[p];
-    if (m > prm.cap || c1 == 0 || c1 >= m) {                        // (uniform) nothing sensible to do
-        if (tid == 0) atomicMax(prm.status, (uint32_t)(m > prm.cap ? STALLOC_ERR_TOO_LARGE : STALLOC_ERR_INVALID_ARG));
+    const uint32_t m0 = prm.pair_begin[p], m1 = prm.pair_begin[p + 1], m = m1 - m0, c1 = prm.count1[p];
+    const bool outside = m1 < m0 || m1 > prm.entries;               // (nothing is read or written beyond the arrays)
+    if (outside || m > prm.cap || c1 == 0 || c1 >= m) {             // (uniform) nothing sensible to do
+        if (tid == 0) atomicMax(prm.status, (uint32_t)(!outside && m > prm.cap ? STALLOC_ERR_TOO_LARGE : STALLOC_ERR_INVALID_ARG));
         return;
     }
     uint32_t* id = reinterpret_cast<uint32_t*>(smem);                 // [cap] request numbers, as given
@@ -191,11 +193,11 @@ __global__ void __launch_bounds__(kFuThreads) fuse_pairs(FuseParams prm)
 using namespace stalloc;
 
 extern "C" int stalloc_fuse_groups(const stalloc_trace* tr, const uint32_t* members, const uint32_t* pair_begin,
-                                   const uint32_t* count1, uint32_t k, uint32_t largest_pair, uint32_t* order,
+                                   const uint32_t* count1, uint32_t k, uint32_t m, uint32_t largest_pair, uint32_t* order,
                                    uint64_t* addr, uint64_t* extents, uint32_t* accepted, uint32_t* device_status,
                                    void* workspace, size_t* workspace_bytes, void* hip_stream)
 {
-    if (!trace_args_ok(tr) || k == 0 || largest_pair < 2 || !workspace_bytes) return STALLOC_ERR_INVALID_ARG;
+    if (!trace_args_ok(tr) || k == 0 || largest_pair < 2 || m < 2 || !workspace_bytes) return STALLOC_ERR_INVALID_ARG;
     DeviceInfo di;
     if (!device_info(&di)) return STALLOC_ERR_DEVICE;
     const size_t per_request = 2 * sizeof(uint32_t) + 2 * sizeof(uint64_t) + 2 * sizeof(uint32_t);
@@ -219,7 +221,7 @@ extern "C" int stalloc_fuse_groups(const stalloc_trace* tr, const uint32_t* memb
     FuseParams prm;
     prm.size = tr->size; prm.ta = tr->t_alloc; prm.tf = tr->t_free; prm.members = members; prm.pair_begin = pair_begin;
     prm.count1 = count1; prm.order = order; prm.addr = addr; prm.extents = extents; prm.accepted = accepted;
-    prm.status = device_status; prm.n = tr->n;
+    prm.status = device_status; prm.n = tr->n; prm.entries = m;
     prm.cap = (largest_pair + 1) & ~1u;                               // (keeps the 64-bit arrays aligned)
     hipLaunchKernelGGL(fuse_pairs, dim3(k), dim3(kFuThreads), (size_t)prm.cap * per_request, stream, prm);
     return hipGetLastError() == hipSuccess ? STALLOC_OK : STALLOC_ERR_DEVICE;

@@ -106,3 +106,6 @@ def test_a_large_pair_at_the_lds_limit_and_errors(S, oracle):
     assert _fuse(S, tr, members, begin, np.asarray([0], dtype=np.uint32), largest)["status"] == 1
     bad = members.copy(); bad[17] = n
     assert _fuse(S, tr, bad, begin, count1, largest)["status"] == 6
+    # pairs that reach beyond the member list, or backwards: reported, nothing read or written out there
+    assert _fuse(S, tr, members, np.asarray([0, len(members) + 1], dtype=np.uint32), count1, largest)["status"] == 1
+    assert _fuse(S, tr, members, np.asarray([4000, 100], dtype=np.uint32), count1, largest)["status"] == 1
