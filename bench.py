@@ -525,7 +525,8 @@ def main() -> int:
         a_cpu, e_single = oracle.plan_many(tr.size, tr.t_alloc, tr.t_free, host_rows[:single_rows], threads=1,
                                            method="lists", lists=lists)
         single_wall = time.perf_counter() - t1
-        many = int(max(1, min(len(sample_rows), cores * args.cpu_seconds / max(one, 1e-6))))
+        # (whole rounds of one row per thread; side by side the rows take about twice as long as the first one alone)
+        many = int(max(1, min(len(sample_rows), cores * max(1, int(args.cpu_seconds / max(2.2 * one, 1e-6))))))
         pick = np.linspace(0, len(sample_rows) - 1, many).astype(np.int64)
         t1 = time.perf_counter()
         a_cpu, e_cpu = oracle.plan_many(tr.size, tr.t_alloc, tr.t_free, host_rows[pick], threads=cores,
