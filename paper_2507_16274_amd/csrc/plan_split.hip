@@ -555,6 +555,86 @@ __device__ __forceinline__ uint32_t settle_request(const SpList& list, uint32_t 
     return clear_others<kWide, kWaves>(rq, own_rank, run, 0xffffffffu, tb, pt, turn, sh);     // on top of every conflicting long block
 }
 
+// Up to four requests with narrow windows settled at once, each by one row of 16 lanes of the
+// wave: the same steps as settle_request (walk over the long blocks, here 16 a step, holes in
+// address order, moving up past the other conflicting blocks that reach into [c, c + size)), taken
+// by the four rows side by side; a row that is done waits for the others.  `group` holds the
+// requests (bits = places in the batch); each has at most 16 other conflicting blocks to look
+// at -- its part of the pool and the requests of the batch settled before it.  The addresses go
+// to sh.rq_addr, the extent to sh.peak.
+template <typename Lds>
+__device__ __forceinline__ void settle_rows(const SpList& list, uint32_t count, uint32_t b0, uint64_t group, uint64_t dep,
+                                            const SpBatch& bt, uint32_t part_first, uint32_t part_count, Lds& sh)
+{
+    const int lane = lane_id();
+    const uint32_t row = (uint32_t)lane >> 4, at = (uint32_t)lane & 15u, row_first = row * 16u;
+    // the row's request: the row-th of the group
+    const uint64_t g1 = group & (group - 1), g2 = g1 & (g1 - 1), g3 = g2 & (g2 - 1);
+    const uint32_t q0 = (uint32_t)__builtin_ctzll(group), q1 = g1 ? (uint32_t)__builtin_ctzll(g1) : 0u,
+                   q2 = g2 ? (uint32_t)__builtin_ctzll(g2) : 0u, q3 = g3 ? (uint32_t)__builtin_ctzll(g3) : 0u;
+    const uint32_t q = row == 0 ? q0 : row == 1 ? q1 : row == 2 ? q2 : q3;
+    const bool active = row < (uint32_t)__builtin_popcountll(group);
+    const uint32_t s = lane_gather(bt.size, (int)q), ta = lane_gather(bt.ta, (int)q), tf = lane_gather(bt.tf, (int)q);
+    const uint32_t in_pool = lane_gather(part_count, (int)q), pool_at = lane_gather(part_first, (int)q);
+    uint64_t before_it = lane_gather(dep, (int)q);                    // earlier requests of the batch with a conflicting lifetime
+    // the other blocks the request has to keep clear of, one per lane of the row
+    uint32_t r_lo = 0xffffffffu, r_hi = 0u;
+    if (active) {
+        if (at < in_pool) {
+            const Span<uint32_t> sp = sh.pool[pool_at + at];
+            r_lo = sp.lo; r_hi = sp.hi;
+        } else if (at - in_pool < (uint32_t)__builtin_popcountll(before_it)) {
+            for (uint32_t t = at - in_pool; t > 0; --t) before_it &= before_it - 1;
+            const uint32_t e = (uint32_t)__builtin_ctzll(before_it);
+            r_lo = sh.rq_addr[b0 + e];
+            r_hi = r_lo + sh.rq_size[b0 + e];
+        }
+    }
+    // Lowest address >= c at which [c, c + s) meets none of them; stops once the request cannot end by `limit`.
+    auto clear_others_in_rows = [&](uint32_t c, uint32_t limit, bool trying) -> uint32_t {
+        for (;;) {
+            const bool fits = trying && c <= limit && limit - c >= s;
+            const bool hit = fits && r_lo < c + s && c < r_hi;
+            const uint64_t hits = __builtin_amdgcn_ballot_w64(hit);
+            if (hits == 0) return c;                                  // (uniform)
+            const uint32_t reach = row_max(hit ? r_hi : 0u);
+            c = umax(c, reach);                                       // (reach > c in a row with a hit, 0 in the others)
+        }
+    };
+    uint32_t run = 0, x = 0;
+    bool settled = !active;
+    for (uint32_t k0 = 0; k0 < count; k0 += 16) {
+        if (__builtin_amdgcn_ballot_w64(!settled) == 0) break;        // (uniform)
+        const uint32_t k = k0 + at;
+        const bool valid = k < count;
+        const SpList::Entry en = list.load(valid ? k : count - 1);
+        const bool conflict = valid && en.ta() < tf && ta < en.tf();
+        const uint32_t incl = row_scan_max(conflict ? en.hi() : 0u);
+        const uint32_t before = umax(run, row_shift_up(incl, 0u));
+        // a hole [before, lo) in front of a conflicting block, large enough as such
+        const uint64_t opens = __builtin_amdgcn_ballot_w64(!settled && conflict && en.lo() >= before && en.lo() - before >= s);
+        uint32_t holes = (uint32_t)(opens >> row_first) & 0xffffu;
+        for (;;) {
+            const bool trying = holes != 0 && !settled;
+            if (__builtin_amdgcn_ballot_w64(trying) == 0) break;      // (uniform)
+            const int from = (int)(row_first + (trying ? (uint32_t)__builtin_ctz(holes) : 0u));
+            const uint32_t limit = lane_gather(en.lo(), from);
+            const uint32_t c = clear_others_in_rows(lane_gather(before, from), limit, trying);
+            if (trying && c <= limit && limit - c >= s) { settled = true; x = c; }
+            holes &= holes - 1;
+        }
+        run = umax(run, lane_gather(incl, (int)row_first + 15));
+    }
+    if (__builtin_amdgcn_ballot_w64(!settled)) {                      // on top of every conflicting long block
+        const uint32_t c = clear_others_in_rows(run, 0xffffffffu, !settled);
+        if (!settled) x = c;
+    }
+    if (active && at == 0) {
+        sh.rq_addr[b0 + q] = x;
+        atomicMax(&sh.peak, x + s);
+    }
+}
+
 // A request with a wide window, settled by the whole workgroup: the waves walk one part of the
 // list of long blocks each and write down the holes that are large enough as such; then all
 // waves try them in address order, sharing the look-ups in the table of short blocks.  Called by
@@ -762,6 +842,9 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
                 const uint64_t all = nb == (uint32_t)kSpBatch ? ~0ull : (1ull << nb) - 1;
                 uint64_t done = 0;
                 const uint64_t wide = __builtin_amdgcn_ballot_w64(mine && my_whi - my_wlo > (uint32_t)kWave);
+                // requests whose other conflicting blocks (their part of the pool, earlier requests of the batch) fit 16 lanes
+                const uint64_t fits_row = __builtin_amdgcn_ballot_w64(part_count != kSpRefetch &&
+                                                                      part_count + (uint32_t)__builtin_popcountll(dep) <= 16u);
                 while (done != all) {
                     // settled: bit set in `done`; ready: everything it waits for is settled.  (What is ready
                     // together does not conflict with each other, so the order inside a round is free.)
@@ -770,7 +853,9 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
                     const uint64_t narrow = ready & ~wide;
                     const bool take = ((narrow >> lane) & 1) && (lanes_below(narrow) + round) % kWaves == (uint32_t)wave;
                     ++round;
-                    for (uint64_t todo = __builtin_amdgcn_ballot_w64(take); todo; todo &= todo - 1) {
+                    // (four at a time, a row of 16 lanes each, when what each has to keep clear of fits a row)
+                    const uint64_t mine_now = __builtin_amdgcn_ballot_w64(take);
+                    for (uint64_t todo = mine_now & ~fits_row; todo; todo &= todo - 1) {
                         const int q = __builtin_ctzll(todo);
                         const uint32_t x = settle_request<false, kWaves>(list, count, b0, (uint32_t)q, readlane64(dep, q), bt,
                                                                          read_lane(part_first, q), read_lane(part_count, q), tb, pt,
@@ -779,6 +864,14 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
                             sh.rq_addr[b0 + q] = x;
                             atomicMax(&sh.peak, x + read_lane(my_size, q));
                         }
+                    }
+                    for (uint64_t todo = mine_now & fits_row; todo;) {
+                        uint64_t rest = todo & (todo - 1);
+                        rest &= rest - 1;
+                        rest &= rest - 1;
+                        rest &= rest - 1;                                         // (todo without its four lowest bits)
+                        settle_rows(list, count, b0, todo & ~rest, dep, bt, part_first, part_count, sh);
+                        todo = rest;
                     }
                     // ... and the workgroup as a whole takes the requests with wide windows one by one
                     for (uint64_t todo = ready & wide; todo; todo &= todo - 1) {

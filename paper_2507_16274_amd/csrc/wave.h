@@ -14,6 +14,7 @@ __device__ __forceinline__ uint64_t umin64(uint64_t a, uint64_t b) { return a < 
 // DPP controls (GFX9 encoding)
 constexpr int kDppRowShr1 = 0x111, kDppRowShr2 = 0x112, kDppRowShr4 = 0x114, kDppRowShr8 = 0x118;
 constexpr int kDppRowBcast15 = 0x142, kDppRowBcast31 = 0x143, kDppWaveShr1 = 0x138;
+constexpr int kDppRowRor1 = 0x121, kDppRowRor2 = 0x122, kDppRowRor4 = 0x124, kDppRowRor8 = 0x128;
 
 // Lanes whose DPP source does not exist, or whose row is masked out, receive `fill`.
 template <int kCtrl, int kRowMask = 0xf>
@@ -118,6 +119,20 @@ __device__ __forceinline__ uint32_t row_scan_max(uint32_t v)
     v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, kDppRowShr4, 0xf, 0xf, false));
     v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, kDppRowShr8, 0xf, 0xf, false));
     return v;
+}
+// Maximum over each row of 16 lanes, in all of its lanes (rotations inside the row).
+__device__ __forceinline__ uint32_t row_max(uint32_t v)
+{
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, kDppRowRor1, 0xf, 0xf, false));
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, kDppRowRor2, 0xf, 0xf, false));
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, kDppRowRor4, 0xf, 0xf, false));
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, kDppRowRor8, 0xf, 0xf, false));
+    return v;
+}
+// The value of the lane before, inside each row of 16 lanes; `fill` in the row's first lane.
+__device__ __forceinline__ uint32_t row_shift_up(uint32_t v, uint32_t fill)
+{
+    return __builtin_amdgcn_update_dpp(fill, v, kDppRowShr1, 0xf, 0xf, false);
 }
 __device__ __forceinline__ uint64_t row_scan_max(uint64_t v)
 {
