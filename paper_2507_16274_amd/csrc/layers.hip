@@ -16,8 +16,9 @@
 //            the start flags number the groups.
 //   build    One wave per group walks its requests in order -- the construction is
 //            sequential by nature, the groups are what runs in parallel.  The ends of the
-//            first 512 layers of the group live in registers (lane = layer mod 64); finding
-//            the free layer with the latest end is a 32-bit wave maximum (DPP) and a ballot.
+//            first 1024 layers of the group live in registers (lane = layer mod 64); finding
+//            the free layer with the latest end is a 32-bit wave maximum (DPP) and a ballot,
+//            in code chosen once per 64 requests for the registers they can come to use.
 //            Further layers, if a group ever needs them, are kept in memory.
 //   number   Exclusive sums of the groups' layer counts give every group its first layer.
 //   emit     layer_of per request; size, first allocation and last release per layer.
@@ -28,8 +29,8 @@
 namespace stalloc {
 
 constexpr int kLyTile = kSortTile;
-constexpr int kLyRegs = 8;                       // 64 layers per register: 512 layers of a group in registers
-static_assert(kLyRegs == 8, "ly_build dispatches on one to eight registers in use");
+constexpr int kLyRegs = 16;                      // 64 layers per register: 1024 layers of a group in registers
+static_assert(kLyRegs == 16, "ly_build dispatches on one to sixteen registers in use");
 
 __global__ void ly_init(uint32_t* v, uint32_t n)
 {
@@ -173,24 +174,47 @@ struct LyBuild {
     uint32_t n;
 };
 
+// Groups with at most this many registers of layers are tested for being idle: the groups of small
+// transient tensors, a few layers each, are idle between most of their requests; those with hundreds
+// of layers hardly ever (and the number of registers in use only grows, so once a group is past
+// the limit the record below is no longer needed).
+constexpr int kLyIdleRegs = 2;
+
+// The group's layer that was released last (the lowest-numbered of several released together): when a
+// request starts at or after that release, every layer of the group is free and this is the one it
+// takes -- no search.  Kept up to date as requests are appended to layers.
+struct LastReleased {
+    uint32_t end, layer;             // (uniform)
+    __device__ __forceinline__ void appended(uint32_t te, uint32_t to_layer)
+    {
+        if (te > end) { end = te; layer = to_layer; }
+        else if (te == end && to_layer < layer) layer = to_layer;
+    }
+};
+
 // One request of a group whose layers all sit in the first kRegs registers (a layer it opens
 // included): returns its layer and makes the request the layer's last one.  `layers` is uniform.
 template <int kRegs>
-__device__ __forceinline__ uint32_t take_layer(uint32_t (&end_of)[kLyRegs], uint32_t ts, uint32_t te, uint32_t layers)
+__device__ __forceinline__ uint32_t take_layer(uint32_t (&end_of)[kLyRegs], uint32_t ts, uint32_t te, uint32_t layers,
+                                               const LastReleased& last)
 {
     const uint32_t lane = (uint32_t)lane_id();
-    // latest end among the free layers (an end is a free time, hence >= 1; 0 = not opened)
-    uint32_t latest = 0;
-#pragma unroll
-    for (int r = 0; r < kRegs; ++r) latest = umax(latest, end_of[r] <= ts ? end_of[r] : 0u);
-    const uint32_t best = __builtin_amdgcn_readlane(wave_scan_max(latest), kWave - 1);
     uint32_t layer = layers;                                              // a new one unless a free layer is found
-    if (best != 0) {
-        bool found = false;
+    if (kRegs <= kLyIdleRegs && layers != 0 && ts >= last.end) {
+        layer = last.layer;                                               // the whole group is idle
+    } else {
+        // latest end among the free layers (an end is a free time, hence >= 1; 0 = not opened)
+        uint32_t latest = 0;
 #pragma unroll
-        for (int r = 0; r < kRegs; ++r) {
-            const uint64_t hit = __builtin_amdgcn_ballot_w64(end_of[r] == best);
-            if (!found && hit) { layer = (uint32_t)r * kWave + (uint32_t)__builtin_ctzll(hit); found = true; }
+        for (int r = 0; r < kRegs; ++r) latest = umax(latest, end_of[r] <= ts ? end_of[r] : 0u);
+        const uint32_t best = __builtin_amdgcn_readlane(wave_scan_max(latest), kWave - 1);
+        if (best != 0) {
+            bool found = false;
+#pragma unroll
+            for (int r = 0; r < kRegs; ++r) {
+                const uint64_t hit = __builtin_amdgcn_ballot_w64(end_of[r] == best);
+                if (!found && hit) { layer = (uint32_t)r * kWave + (uint32_t)__builtin_ctzll(hit); found = true; }
+            }
         }
     }
 #pragma unroll
@@ -198,59 +222,105 @@ __device__ __forceinline__ uint32_t take_layer(uint32_t (&end_of)[kLyRegs], uint
     return layer;
 }
 
+// The (up to 64) requests a wave has loaded, lane q holding request q, taken one by one while all
+// layers the group can have by the end of the block sit in the first kRegs registers.  Returns the
+// layer of the request this lane loaded; `layers` and `last` are kept up to date.
+template <int kRegs>
+__device__ __forceinline__ uint32_t take_block(uint32_t (&end_of)[kLyRegs], uint32_t ts_k, uint32_t te_k, int members,
+                                               uint32_t& layers, LastReleased& last, uint32_t* first_ts)
+{
+    const int lane = lane_id();
+    uint32_t mine = 0;
+    uint32_t opened = layers;                                             // (uniform)
+    LastReleased lr = last;
+    for (int q = 0; q < members; ++q) {
+        const uint32_t ts = __builtin_amdgcn_readlane(ts_k, q), te = __builtin_amdgcn_readlane(te_k, q);
+        const uint32_t layer = take_layer<kRegs>(end_of, ts, te, opened, lr);
+        if (layer == opened) {
+            if (lane == 0) first_ts[opened] = ts;
+            ++opened;
+        }
+        if (kRegs <= kLyIdleRegs) lr.appended(te, layer);
+        if (lane == q) mine = layer;
+    }
+    layers = opened;
+    last = lr;
+    return mine;
+}
+
 __global__ void __launch_bounds__(256) ly_build(LyBuild g)
 {
     if (*g.status != STALLOC_OK) return;
     const int lane = lane_id();
     const uint32_t groups = *g.n_groups;
-    for (uint32_t grp = blockIdx.x * 4 + (uint32_t)wave_id(); grp < groups; grp += gridDim.x * 4) {
+    // (the wave's number, the same in all its lanes, as a scalar: the loops below then run on scalar
+    // counters and branches instead of lane masks)
+    const uint32_t first_group = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (uint32_t)wave_id());
+    for (uint32_t grp = first_group; grp < groups; grp += gridDim.x * 4) {
         const uint32_t s = g.group_start[grp];
         const uint32_t e = grp + 1 < groups ? g.group_start[grp + 1] : g.n;
         uint32_t end_of[kLyRegs];        // lane holds the ends of layers lane, 64 + lane, ...; 0 = not opened
 #pragma unroll
         for (int r = 0; r < kLyRegs; ++r) end_of[r] = 0;
         uint32_t layers = 0;             // (uniform) layers opened so far
+        LastReleased last = {0, 0};
+        uint32_t regs = 0;               // (uniform) registers of end_of in use
+        // the lifetimes of the next 64 requests are on their way while these 64 are taken one by one
+        uint32_t ts_next = 0, te_next = 0;
+        if (s + lane < e) {
+            const uint32_t i = g.sorted[s + lane];
+            ts_next = g.ta[i];
+            te_next = g.tf[i];
+        }
         for (uint32_t base = s; base < e; base += kWave) {
             const uint32_t k = base + lane;
-            uint32_t ts_k = 0, te_k = 0;
-            if (k < e) {
-                const uint32_t i = g.sorted[k];
-                ts_k = g.ta[i];
-                te_k = g.tf[i];
+            const uint32_t ts_k = ts_next, te_k = te_next;
+            if (k + kWave < e) {
+                const uint32_t i = g.sorted[k + kWave];
+                ts_next = g.ta[i];
+                te_next = g.tf[i];
             }
             uint32_t mine = 0;           // layer of the request this lane loaded
             const int members = e - base < (uint32_t)kWave ? (int)(e - base) : kWave;
+            layers = __builtin_amdgcn_readfirstlane(layers);
+            // registers that hold every layer the group can have once these requests are placed (never
+            // fewer than for an earlier block, a short last one included: see kLyIdleRegs)
+            regs = umax(regs, (layers + (uint32_t)members + kWave - 1) / kWave);
+            if (regs <= (uint32_t)kLyRegs) {
+                // the usual case: everything in registers, code specialised for the registers in use
+                uint32_t* const first_ts = g.first_ts + s;
+                switch (regs) {
+                    case 1: mine = take_block<1>(end_of, ts_k, te_k, members, layers, last, first_ts); break;
+                    case 2: mine = take_block<2>(end_of, ts_k, te_k, members, layers, last, first_ts); break;
+                    case 3: mine = take_block<3>(end_of, ts_k, te_k, members, layers, last, first_ts); break;
+                    case 4: mine = take_block<4>(end_of, ts_k, te_k, members, layers, last, first_ts); break;
+                    case 5: mine = take_block<5>(end_of, ts_k, te_k, members, layers, last, first_ts); break;
+                    case 6: mine = take_block<6>(end_of, ts_k, te_k, members, layers, last, first_ts); break;
+                    case 7: mine = take_block<7>(end_of, ts_k, te_k, members, layers, last, first_ts); break;
+                    case 8: mine = take_block<8>(end_of, ts_k, te_k, members, layers, last, first_ts); break;
+                    case 9: mine = take_block<9>(end_of, ts_k, te_k, members, layers, last, first_ts); break;
+                    case 10: mine = take_block<10>(end_of, ts_k, te_k, members, layers, last, first_ts); break;
+                    case 11: mine = take_block<11>(end_of, ts_k, te_k, members, layers, last, first_ts); break;
+                    case 12: mine = take_block<12>(end_of, ts_k, te_k, members, layers, last, first_ts); break;
+                    case 13: mine = take_block<13>(end_of, ts_k, te_k, members, layers, last, first_ts); break;
+                    case 14: mine = take_block<14>(end_of, ts_k, te_k, members, layers, last, first_ts); break;
+                    case 15: mine = take_block<15>(end_of, ts_k, te_k, members, layers, last, first_ts); break;
+                    default: mine = take_block<16>(end_of, ts_k, te_k, members, layers, last, first_ts); break;
+                }
+                if (k < e) g.local[k] = mine;
+                continue;
+            }
+            // a group that may pass 1024 layers: the further ones are kept in memory
             for (int q = 0; q < members; ++q) {
                 const uint32_t ts = __builtin_amdgcn_readlane(ts_k, q), te = __builtin_amdgcn_readlane(te_k, q);
                 layers = __builtin_amdgcn_readfirstlane(layers);
-                if (layers < (uint32_t)(kLyRegs * kWave)) {
-                    // the usual case: everything in registers, code specialised for the registers in use
-                    uint32_t layer;
-                    switch (layers / kWave) {
-                        case 0: layer = take_layer<1>(end_of, ts, te, layers); break;
-                        case 1: layer = take_layer<2>(end_of, ts, te, layers); break;
-                        case 2: layer = take_layer<3>(end_of, ts, te, layers); break;
-                        case 3: layer = take_layer<4>(end_of, ts, te, layers); break;
-                        case 4: layer = take_layer<5>(end_of, ts, te, layers); break;
-                        case 5: layer = take_layer<6>(end_of, ts, te, layers); break;
-                        case 6: layer = take_layer<7>(end_of, ts, te, layers); break;
-                        default: layer = take_layer<8>(end_of, ts, te, layers); break;
-                    }
-                    if (layer == layers) {
-                        if (lane == 0) g.first_ts[s + layers] = ts;
-                        ++layers;
-                    }
-                    if (lane == q) mine = layer;
-                    continue;
-                }
-                // a group with 512 layers or more: the further ones are kept in memory
                 uint32_t latest = 0;
 #pragma unroll
                 for (int r = 0; r < kLyRegs; ++r)
                     if ((uint32_t)r * kWave < layers) latest = umax(latest, end_of[r] <= ts ? end_of[r] : 0u);   // (uniform)
                 const uint32_t in_regs = __builtin_amdgcn_readlane(wave_scan_max(latest), kWave - 1);
                 uint32_t in_mem = 0;
-                for (uint32_t l0 = kLyRegs * kWave; l0 < layers; l0 += kWave) {    // (only groups with more than 512 layers)
+                for (uint32_t l0 = kLyRegs * kWave; l0 < layers; l0 += kWave) {
                     const uint32_t l = l0 + lane;
                     const uint32_t v = l < layers ? __hip_atomic_load(&g.ends[s + l], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
                     in_mem = umax(in_mem, __builtin_amdgcn_readlane(wave_scan_max(v <= ts ? v : 0u), kWave - 1));

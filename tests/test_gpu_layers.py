@@ -61,11 +61,13 @@ def test_random_traces(S, oracle, seed):
     _compare(S, oracle, size, ts, te, t_end)
 
 
-def test_group_with_more_layers_than_registers_hold(S, oracle):
-    """700 requests of one size alive together, then waves of requests that take over released layers:
-    the layers past the 512th are kept in memory."""
+@pytest.mark.parametrize("n0", [700, 1300])
+def test_group_with_more_layers_than_registers_hold(S, oracle, n0):
+    """700 or 1300 requests of one size alive together, then waves of requests that take over released
+    layers: up to 1024 layers of a group sit in registers (eleven of them for 700), the layers past the
+    1024th are kept in memory."""
     rng = np.random.default_rng(9200)
-    n0, n1 = 700, 1500
+    n1 = 1500
     ts0 = rng.integers(0, 50, n0)
     te0 = 100 + rng.integers(0, 400, n0)
     ts1 = rng.integers(100, 900, n1)
@@ -75,7 +77,7 @@ def test_group_with_more_layers_than_registers_hold(S, oracle):
     size = np.full(n0 + n1, 4096, np.uint64)
     size[rng.integers(0, n0 + n1, 40)] = 64            # a second, small group beside it
     layer_of, l_size, _, _ = _compare(S, oracle, size, ts, te, int(te.max()))
-    assert int((l_size == 4096).sum()) > 512
+    assert int((l_size == 4096).sum()) > (512 if n0 == 700 else 1024)
 
 
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5, 6])
