@@ -220,6 +220,9 @@ __device__ __forceinline__ uint32_t umin(uint32_t a, uint32_t b) { return a < b 
 __device__ __forceinline__ uint64_t umax(uint64_t a, uint64_t b) { return a > b ? a : b; }
 
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
-__device__ __forceinline__ int wave_id() { return (int)(threadIdx.x >> 6); }
+// The wave's number within its workgroup, the same in all 64 lanes: taken from the first lane so that
+// the compiler keeps it, and what is computed from it (loop bounds, shares of a list), in scalar
+// registers and branches on it without lane masks.
+__device__ __forceinline__ int wave_id() { return (int)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6); }
 
 }  // namespace stalloc
