@@ -181,8 +181,6 @@ __global__ void __launch_bounds__(256) nbr_fill(PlanParams prm)
 
 // ---------------------------------------------------------------------------------------------
 
-__device__ __forceinline__ uint32_t uniform(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
-
 // A placed block as the build phase wants it: bits 0-21 address in granules (bits 0-4 = first bit
 // b in its first word, bits 5-21 = that word), bits 22-26 size in granules (1..31), bits 27-31 the
 // number of granules that spill into the next word.  0 = not placed.

@@ -680,6 +680,8 @@ __device__ __forceinline__ uint32_t settle_wide(const SpList& list, uint32_t cou
         if (lane == 0) { sh.wide_holes[wave] = found; sh.wide_part_top[wave] = run; }
     }
     __syncthreads();
+    not_before_here(rq.large_lo);                                     // (the two reads had the walk's time to arrive)
+    not_before_here(rq.large_hi);
     uint32_t top = 0;                                                 // highest end of the conflicting blocks of the parts below
     for (int w = 0; w < kWaves; ++w) {
         const uint32_t found = sh.wide_holes[w];
@@ -764,6 +766,7 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
             __syncthreads();
 
             for (uint32_t b0 = 0; b0 < staged; b0 += kSpBatch) {
+                vector_memory_done();     // (the previous batch's accesses: the window reads below go out as one run)
                 const uint32_t nb = staged - b0 < (uint32_t)kSpBatch ? staged - b0 : (uint32_t)kSpBatch;
                 const bool mine = lane < (int)nb;
                 const uint32_t my_size = mine ? sh.rq_size[b0 + lane] : 0u;

@@ -219,6 +219,26 @@ __device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b 
 __device__ __forceinline__ uint32_t umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
 __device__ __forceinline__ uint64_t umax(uint64_t a, uint64_t b) { return a > b ? a : b; }
 
+// A value that is the same in all lanes of the wave (read by every lane from one LDS word, say),
+// as a scalar: the compiler cannot know, and would otherwise branch on it with lane masks.
+__device__ __forceinline__ uint32_t uniform(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// Waits until every vector-memory access this wave has issued is complete.  Placed where that is
+// the case anyway (long after the last one was issued), it tells the compiler so: without it, a load
+// left unread on some path through a loop keeps its register marked as in flight, and the first
+// write to that register -- in the middle of a run of loads meant to go out together -- is made to
+// wait for all of them.
+__device__ __forceinline__ void vector_memory_done() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0), nothing else
+
+// A value loaded from memory is not looked at before this point: without it the compiler may move
+// the first use (and with it the wait for the load) up to where the load was issued.
+// (For a value that is the same in all lanes; it is handed on as a scalar.)
+__device__ __forceinline__ void not_before_here(uint32_t& v)
+{
+    asm volatile("" : "+v"(v));
+    v = __builtin_amdgcn_readfirstlane(v);
+}
+
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
 // The wave's number within its workgroup, the same in all 64 lanes: taken from the first lane so that
 // the compiler keeps it, and what is computed from it (loop bounds, shares of a list), in scalar
