@@ -682,22 +682,36 @@ __device__ __forceinline__ uint32_t settle_wide(const SpList& list, uint32_t cou
     __syncthreads();
     not_before_here(rq.large_lo);                                     // (the two reads had the walk's time to arrive)
     not_before_here(rq.large_hi);
-    uint32_t top = 0;                                                 // highest end of the conflicting blocks of the parts below
-    for (int w = 0; w < kWaves; ++w) {
-        const uint32_t found = sh.wide_holes[w];
-        const uint32_t listed = found < (uint32_t)kSpWideHoles ? found : (uint32_t)kSpWideHoles;
-        for (uint32_t i = 0; i < listed; ++i) {
-            const Span<uint32_t> hole = sh.wide_hole[w][i];           // {end, covered within the part}
-            const uint32_t covered = umax(hole.hi, top);
-            if (hole.lo < covered || hole.lo - covered < rq.s) continue;
-            const uint32_t c = clear_others<true, kWaves>(rq, own_rank, covered, hole.lo, tb, pt, turn, sh);
-            if (c <= hole.lo && hole.lo - c >= rq.s) return c;
-        }
-        // more candidates in this part than were written down and none so far took the request: every wave walks the list
-        if (found > listed) return settle_request<true, kWaves>(list, count, b0, q, dep_q, bt, 0u, 0u, tb, pt, turn, sh);
-        top = umax(top, sh.wide_part_top[w]);
+    // All candidates at once, lane 8 w + i holding candidate i of part w (address order = lane order):
+    // what the parts below a part cover is a running maximum over the parts' highest ends, and a
+    // candidate is a hole if the request fits between that (or what its own part covers in front of
+    // it) and the block behind it.
+    static_assert(kSpWideHoles <= 7 && kWaves * 8 <= kWave, "eight lanes per part, the last one for the part's highest end");
+    const uint32_t part = (uint32_t)lane >> 3, slot = (uint32_t)lane & 7u;
+    uint32_t found = 0, part_top = 0;
+    Span<uint32_t> hole = {0u, 0u};                                   // {end, covered within the part}
+    if (part < (uint32_t)kWaves) {
+        found = sh.wide_holes[part];
+        part_top = sh.wide_part_top[part];
+        if (slot < (uint32_t)kSpWideHoles) hole = sh.wide_hole[part][slot];
     }
-    return clear_others<true, kWaves>(rq, own_rank, top, 0xffffffffu, tb, pt, turn, sh);
+    const uint32_t tops = wave_scan_max(slot == 7u ? part_top : 0u);  // in a part's first seven lanes: the parts below
+    const uint32_t covered = umax(hole.hi, tops);
+    uint64_t holes = __builtin_amdgcn_ballot_w64(slot < umin(found, (uint32_t)kSpWideHoles) && hole.lo >= covered &&
+                                                 hole.lo - covered >= rq.s);
+    // parts with more candidates than were written down (bit 8 w): if none of the holes up to the end
+    // of such a part takes the request, every wave walks the list
+    const uint64_t more = __builtin_amdgcn_ballot_w64(slot == 0u && found > (uint32_t)kSpWideHoles);
+    while (holes) {
+        const int at = __builtin_ctzll(holes);
+        holes &= holes - 1;
+        if (more & ((1ull << (at & ~7)) - 1)) break;                  // (a part below this one has more)
+        const uint32_t end = read_lane(hole.lo, at);
+        const uint32_t c = clear_others<true, kWaves>(rq, own_rank, read_lane(covered, at), end, tb, pt, turn, sh);
+        if (c <= end && end - c >= rq.s) return c;
+    }
+    if (more) return settle_request<true, kWaves>(list, count, b0, q, dep_q, bt, 0u, 0u, tb, pt, turn, sh);
+    return clear_others<true, kWaves>(rq, own_rank, read_lane(tops, kWave - 1), 0xffffffffu, tb, pt, turn, sh);
 }
 
 template <int kThreads>
