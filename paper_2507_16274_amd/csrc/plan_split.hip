@@ -83,10 +83,11 @@ struct SplitLds {
     uint32_t region_max[kWave];                  // region of ranks (64 regions cover the table)
     uint32_t large_min, large_max;               // the same over all placed large short blocks
     uint32_t reach[3];                           // window_reach: what the waves found, three calls in rotation
-    // request with a wide window: every wave walks one part of the list
-    Span<uint32_t> wide_hole[kSpMaxWaves][kSpWideHoles];   // candidate holes of that part {end, covered within the part}, in address order
-    uint32_t wide_holes[kSpMaxWaves];            // how many there are (may exceed what is stored)
-    uint32_t wide_part_top[kSpMaxWaves];         // highest end of the conflicting long blocks of that part
+    // request with a wide window: every wave walks one part of the list.  Two sets, used in turn: the
+    // waves still reading one request's set are a barrier away from those already writing the next but one's.
+    Span<uint32_t> wide_hole[2][kSpMaxWaves][kSpWideHoles];   // candidate holes of that part {end, covered within the part}, in address order
+    uint32_t wide_holes[2][kSpMaxWaves];         // how many there are (may exceed what is stored)
+    uint32_t wide_part_top[2][kSpMaxWaves];      // highest end of the conflicting long blocks of that part
     uint32_t next_plan;                          // the plan this workgroup takes next
     uint32_t extent_now;                         // extent after the last finished batch
     uint32_t peak;                               // running extent
@@ -642,7 +643,7 @@ __device__ __forceinline__ void settle_rows(const SpList& list, uint32_t count, 
 template <int kWaves, typename Lds>
 __device__ __forceinline__ uint32_t settle_wide(const SpList& list, uint32_t count, uint32_t b0, uint32_t q, uint64_t dep_q,
                                                 const SpBatch& bt, const SplitTables& tb, const SpTable& pt, uint32_t& turn,
-                                                Lds& sh)
+                                                uint32_t& wide_turn, Lds& sh)
 {
     const int lane = lane_id();
     SpRequest rq;
@@ -655,7 +656,8 @@ __device__ __forceinline__ uint32_t settle_wide(const SpList& list, uint32_t cou
     rq.rivals_w = 0; rq.w_lo = 0; rq.w_hi = 0;
     rq.large_lo = tb.large_before[rq.wlo];                        // (looked at after the walk over the list)
     rq.large_hi = tb.large_before[rq.whi];
-    __syncthreads();                                              // the holes of the previous such request are no longer read
+    const uint32_t set = wide_turn & 1u;                          // (the set before the last one's: a barrier has passed since it was read)
+    ++wide_turn;
     // Every wave takes one part of the list and writes down what may be a hole large enough as such,
     // as seen from the part's start, and the highest end of the part's conflicting blocks; what the
     // parts below cover is known once all waves are done, and decides which of them are holes.
@@ -673,11 +675,11 @@ __device__ __forceinline__ uint32_t settle_wide(const SpList& list, uint32_t cou
             const uint32_t before = umax(run, wave_shift_up(incl, 0u));
             const uint64_t opens = __builtin_amdgcn_ballot_w64(conflict && en.lo() >= before && en.lo() - before >= rq.s);
             const uint32_t at = found + lanes_below(opens);
-            if (((opens >> lane) & 1) && at < (uint32_t)kSpWideHoles) sh.wide_hole[wave][at] = Span<uint32_t>{en.lo(), before};
+            if (((opens >> lane) & 1) && at < (uint32_t)kSpWideHoles) sh.wide_hole[set][wave][at] = Span<uint32_t>{en.lo(), before};
             found += (uint32_t)__builtin_popcountll(opens);
             run = umax(run, read_lane(incl, kWave - 1));
         }
-        if (lane == 0) { sh.wide_holes[wave] = found; sh.wide_part_top[wave] = run; }
+        if (lane == 0) { sh.wide_holes[set][wave] = found; sh.wide_part_top[set][wave] = run; }
     }
     __syncthreads();
     not_before_here(rq.large_lo);                                     // (the two reads had the walk's time to arrive)
@@ -691,9 +693,9 @@ __device__ __forceinline__ uint32_t settle_wide(const SpList& list, uint32_t cou
     uint32_t found = 0, part_top = 0;
     Span<uint32_t> hole = {0u, 0u};                                   // {end, covered within the part}
     if (part < (uint32_t)kWaves) {
-        found = sh.wide_holes[part];
-        part_top = sh.wide_part_top[part];
-        if (slot < (uint32_t)kSpWideHoles) hole = sh.wide_hole[part][slot];
+        found = sh.wide_holes[set][part];
+        part_top = sh.wide_part_top[set][part];
+        if (slot < (uint32_t)kSpWideHoles) hole = sh.wide_hole[set][part][slot];
     }
     const uint32_t tops = wave_scan_max(slot == 7u ? part_top : 0u);  // in a part's first seven lanes: the parts below
     const uint32_t covered = umax(hole.hi, tops);
@@ -759,6 +761,7 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
         if (threadIdx.x < kWave) { sh.region_min[threadIdx.x] = 0xffffffffu; sh.region_max[threadIdx.x] = 0u; }
         if (threadIdx.x == 0) { sh.extent_now = 0; sh.peak = 0; sh.pool_used = 0; sh.reach[0] = 0; sh.large_min = 0xffffffffu; sh.large_max = 0u; }
         uint32_t turn = 0;                                            // calls of window_reach: slot 0 is clear
+        uint32_t wide_turn = 0;                                       // requests settled by the whole workgroup
         uint32_t round = 0;                                           // rounds so far: which wave takes the first ready request
 
         for (uint32_t r0 = 0; r0 < n; r0 += kSpRefill) {
@@ -893,7 +896,7 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
                     // ... and the workgroup as a whole takes the requests with wide windows one by one
                     for (uint64_t todo = ready & wide; todo; todo &= todo - 1) {
                         const int q = __builtin_ctzll(todo);
-                        const uint32_t x = settle_wide<kWaves>(list, count, b0, (uint32_t)q, readlane64(dep, q), bt, tb, pt, turn, sh);
+                        const uint32_t x = settle_wide<kWaves>(list, count, b0, (uint32_t)q, readlane64(dep, q), bt, tb, pt, turn, wide_turn, sh);
                         if (threadIdx.x == 0) {
                             sh.rq_addr[b0 + q] = x;
                             atomicMax(&sh.peak, x + read_lane(my_size, q));
