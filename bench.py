@@ -204,7 +204,7 @@ def main() -> int:
     # which kernel placed the trace and how it stores a placed block (decided on the device)
     info = S.stalloc_plan_report(plan)
     in_lds = info["kernel"] != "list_memory"
-    entry_bytes = {"bitmap": 4, "long_list": 16}.get(info["kernel"], {16: 8, 32: 16, 64: 24}.get(info["address_bits"], 24))
+    entry_bytes = {"bitmap": 4, "long_list": info["list_entry_bytes"] or 16}.get(info["kernel"], {16: 8, 32: 16, 64: 24}.get(info["address_bits"], 24))
     pairs = stats["E"] * P                       # lifetime-overlapping (earlier, later) pairs examined at least once
     t_s = plan_ms * 1e-3
     hbm_bytes = PER_PLACEMENT_BYTES * n * P

@@ -347,7 +347,10 @@ typedef struct stalloc_plan_info {
     uint64_t large_size;         /* STALLOC_KERNEL_LONG_LIST: short-lived requests of at least this many bytes are
                                     kept in a table of their own as well (0: none are)            */
     uint32_t large_requests;     /* ... and how many there are                                    */
-    uint32_t reserved;
+    uint32_t list_entry_bytes;   /* STALLOC_KERNEL_LONG_LIST: bytes of a block in the sorted list: 16 (address range and
+                                    lifetime; two workgroups per CU) or 8 (start address, ranks among the long-lived
+                                    requests' allocation and release times in place of the times, size class; three
+                                    workgroups per CU); 0 for the other kernels                    */
 } stalloc_plan_info;
 
 int stalloc_plan_report(const void *workspace, stalloc_plan_info *info, void *hip_stream);

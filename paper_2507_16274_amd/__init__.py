@@ -46,7 +46,7 @@ class _PlanInfo(ctypes.Structure):
     _fields_ = [("kernel", ctypes.c_uint32), ("granule_log2", ctypes.c_uint32), ("granules", ctypes.c_uint64),
                 ("plans_64bit", ctypes.c_uint32), ("lifetime_threshold", ctypes.c_uint32),
                 ("long_requests", ctypes.c_uint32), ("address_bits", ctypes.c_uint32),
-                ("large_size", ctypes.c_uint64), ("large_requests", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+                ("large_size", ctypes.c_uint64), ("large_requests", ctypes.c_uint32), ("list_entry_bytes", ctypes.c_uint32)]
 
 
 def _load() -> ctypes.CDLL:
@@ -183,7 +183,8 @@ def stalloc_plan_report(plan: Dict[str, torch.Tensor], *, stream=None) -> Dict[s
     return {"kernel": KERNELS.get(info.kernel, str(info.kernel)), "granule_log2": info.granule_log2,
             "granules": info.granules, "plans_64bit": info.plans_64bit,
             "lifetime_threshold": info.lifetime_threshold, "long_requests": info.long_requests,
-            "address_bits": info.address_bits, "large_size": info.large_size, "large_requests": info.large_requests}
+            "address_bits": info.address_bits, "large_size": info.large_size, "large_requests": info.large_requests,
+            "list_entry_bytes": info.list_entry_bytes}
 
 
 def stalloc_probe(what: int, buffer: torch.Tensor, iters: int = 0, *, stream=None) -> int:

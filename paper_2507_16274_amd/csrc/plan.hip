@@ -679,7 +679,7 @@ extern "C" int stalloc_plan_report(const void* workspace, stalloc_plan_info* inf
     const bool large = (acc[kAccSplit] & 1) && (uint32_t)acc[kAccLargeShort] != 0xffffffffu;
     info->large_size = large ? (acc[kAccLargeShort] & 0xffffffffull) << (acc[kAccMode] & 63) : 0ull;
     info->large_requests = large ? (uint32_t)(acc[kAccLargeShort] >> 32) : 0u;
-    info->reserved = 0;
+    info->list_entry_bytes = (uint32_t)((acc[kAccKernel] >> 16) & 0xffu);
     return STALLOC_OK;
 }
 
@@ -723,7 +723,7 @@ static int plan_call(const stalloc_trace* tr, const uint32_t* orders, uint32_t P
     // variant for long traces with few long-lived requests: tables in allocation-time order
     const bool split = !lds32;
     SplitWorkspace sw;
-    if (split) split_workspace(n, di, cv, &sw);
+    if (split) split_workspace(n, tr->t_end, di, cv, &sw);
     if (!workspace) { *workspace_bytes = cv.used; return STALLOC_OK; }
     if (!orders || !peaks || !best_plan || !device_status || *workspace_bytes < cv.used ||
         (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)))

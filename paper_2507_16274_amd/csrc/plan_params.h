@@ -65,9 +65,14 @@ struct SplitWorkspace {
     uint32_t* scan_total;
     uint2* large_fit;
     uint32_t* large_addr;
-    uint32_t slots, large_slots, n_pad, grid;
+    uint32_t* allocated_at;      // list with ranks in place of times: marks per timestamp, their exclusive sums, size classes
+    uint32_t* released_at;
+    uint32_t* class_size;
+    uint32_t* allocated_before;
+    uint32_t* released_before;
+    uint32_t slots, large_slots, n_pad, grid, times;
 };
-size_t split_workspace(uint32_t n, const DeviceInfo& di, Carver& cv, SplitWorkspace* ws);
+size_t split_workspace(uint32_t n, uint32_t t_end, const DeviceInfo& di, Carver& cv, SplitWorkspace* ws);
 bool launch_plan_split(const PlanParams& prm, uint32_t t_end, const SplitWorkspace& ws, const DeviceInfo& di, hipStream_t stream);
 
 // Fills PlanParams::bitmap_pool_words for a trace of n requests; false if no shape fits.

@@ -41,6 +41,8 @@
 // no such theta exists, or in which many short requests have wide windows all the same (dense or
 // tied timestamps), are left to the sorted-list kernel.  Addresses are 32-bit granule counts, with the same plan-by-plan
 // hand-over to the 64-bit sorted-list kernel as there.
+#include <type_traits>
+
 #include "host_util.h"
 #include "plan_list.h"
 #include "plan_params.h"
@@ -63,6 +65,46 @@ constexpr uint32_t kSpRankMask = 0x3fffffffu;
 constexpr int kSpMaxThetaBits = 12;              // theta < 2^12 events
 using SpList = BlockList<uint32_t, false>;
 
+// The same list in 8 bytes per block, which lets a third workgroup share the LDS of a CU: the start
+// address, and in the second word, instead of the two times, the block's ranks among the long-lived
+// requests' allocation times (13 bits) and release times (13 bits, plus one), and the class of its
+// size (6 bits; the sizes of the classes sit in an LDS table).  With, per request, the number A of
+// long-lived requests allocated before its release and the number B released by its allocation, a
+// block's lifetime conflicts with the request's if rank_alloc < A and B < rank_release + 1: the
+// same two compares as on times.  Usable with at most 8190 long-lived requests of at most 64 sizes.
+constexpr uint32_t kSpRankBits = 13;
+constexpr uint32_t kSpRankedMost = (1u << kSpRankBits) - 2;
+constexpr int kSpSizeClasses = 64;
+struct RankedList {
+    typedef uint32_t addr_type;
+    static constexpr size_t kEntryBytes = sizeof(uint2);
+    struct Entry {
+        uint2 c;
+        uint32_t end;
+        __device__ __forceinline__ uint32_t lo() const { return c.x; }
+        __device__ __forceinline__ uint32_t hi() const { return end; }
+        __device__ __forceinline__ uint32_t ta() const { return c.y & ((1u << kSpRankBits) - 1); }
+        __device__ __forceinline__ uint32_t tf() const { return (c.y >> kSpRankBits) & ((1u << kSpRankBits) - 1); }
+    };
+    uint2* cell;
+    const uint32_t* class_size;      // [64] in LDS
+    __device__ __forceinline__ void bind(unsigned char* base, uint32_t) { cell = reinterpret_cast<uint2*>(base); }
+    __device__ __forceinline__ Entry load(uint32_t k) const
+    {
+        const uint2 c = cell[k];
+        return Entry{c, c.x + class_size[c.y >> (2 * kSpRankBits)]};
+    }
+    __device__ __forceinline__ void store(uint32_t k, const Entry& e) const { cell[k] = e.c; }
+    // (second word as made by sp_windows; hi is implied by the class)
+    static __device__ __forceinline__ Entry make(uint32_t lo, uint32_t hi, uint32_t ranks_and_class, uint32_t)
+    {
+        return Entry{make_uint2(lo, ranks_and_class), hi};
+    }
+    static __device__ __forceinline__ Entry none() { return Entry{make_uint2(0u, 0u), 0u}; }
+};
+template <typename List> struct ListTraits { static constexpr bool kRanked = false; };
+template <> struct ListTraits<RankedList> { static constexpr bool kRanked = true; };
+
 struct SplitLds {
     uint32_t rq_id[kSpRefill];
     uint32_t rq_size[kSpRefill];                 // granules
@@ -72,6 +114,9 @@ struct SplitLds {
     uint32_t rq_wlo[kSpRefill];                  // window of that order holding the short requests that can conflict
     uint32_t rq_whi[kSpRefill];
     uint32_t rq_addr[kSpRefill];                 // granules
+    uint32_t rq_counts[kSpRefill];               // ranked list: A | B << 16 (long-lived requests allocated before its release, released by its allocation)
+    uint32_t rq_extra[kSpRefill];                // a large short block's place in the table of those; a long block's second list word (ranked list)
+    uint32_t class_size[kSpSizeClasses];         // ranked list: sizes (granules) of the long-lived requests' size classes
     uint64_t dep[kSpBatch];                      // earlier requests of the batch with a conflicting lifetime
     Span<uint32_t> pend_span[kSpBatch];          // long blocks of the batch, sorted by address, for the merge
     uint2 pend_life[kSpBatch];
@@ -93,10 +138,15 @@ struct SplitLds {
     uint32_t peak;                               // running extent
 };
 
-__host__ __device__ inline uint32_t split_list_capacity(size_t lds_per_workgroup)
+__host__ __device__ inline uint32_t split_list_capacity(size_t lds_per_workgroup, size_t entry_bytes = SpList::kEntryBytes)
 {
-    return lds_per_workgroup > sizeof(SplitLds) + 1024 ? (uint32_t)((lds_per_workgroup - sizeof(SplitLds)) / SpList::kEntryBytes) : 0u;
+    return lds_per_workgroup > sizeof(SplitLds) + 1024 ? (uint32_t)((lds_per_workgroup - sizeof(SplitLds)) / entry_bytes) : 0u;
 }
+
+// LDS of a workgroup when three share a CU (the allocation is rounded up, hence the slack).
+inline size_t ranked_lds(const DeviceInfo& di) { return di.lds_per_block / 3 - 2048; }
+// The ranked list needs two words per timestamp of the trace; traces whose timestamps are far apart do without it.
+inline bool ranked_possible(uint32_t n, uint32_t t_end) { return (uint64_t)t_end <= 4ull * n + 4096; }
 
 // ------------------------------------------------------------------------------------------
 // Once per call: lifetime classes, allocation-time order, windows.
@@ -122,6 +172,7 @@ constexpr int kSpHistWords = 80;                 // 32 lifetime classes, then [3
 constexpr int kSpHistWide = 32;
 constexpr int kSpHistNextPlan = 33;              // (the counter that hands out plans lives behind the histogram)
 constexpr int kSpHistSigma = 34;                 // sizes of at least this many granules count as large among the short-lived
+constexpr int kSpHistTooManySizes = 35;          // ranked list: the long-lived requests have more than 64 sizes
 constexpr int kSpHistSizes = 40;                 // 32 size classes of the short-lived requests
 
 __global__ void sp_clear_histogram(uint32_t* hist, uint32_t* gate)
@@ -212,6 +263,48 @@ __global__ void sp_sigma(uint32_t* hist, const uint32_t* gate)
     hist[kSpHistSigma] = sigma;
 }
 
+// For the list with ranks in place of times (RankedList): marks the allocation and release times of the
+// long-lived requests (exclusive sums of the marks are the ranks and the counts A, B) and collects
+// their sizes in a table of 64 classes.
+__global__ void sp_clear_words(uint32_t* v, size_t m, const uint32_t* gate)
+{
+    if (*gate != 0) return;
+    for (size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x; k < m; k += (size_t)gridDim.x * blockDim.x) v[k] = 0;
+}
+
+__global__ void __launch_bounds__(256)
+sp_long_marks(const uint64_t* __restrict__ size, const uint32_t* __restrict__ ta, const uint32_t* __restrict__ tf, uint32_t n,
+              const uint64_t* acc, uint32_t* allocated_at, uint32_t* released_at, uint32_t* class_size, uint32_t* hist,
+              const uint32_t* gate)
+{
+    if (*gate != 0) return;
+    const uint32_t shift = (uint32_t)(acc[kAccMode] & 63);
+    const uint32_t theta = (uint32_t)((acc[kAccSplit] >> 8) & 0xffffffu);
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+        if (tf[i] - ta[i] <= theta) continue;
+        atomicAdd(&allocated_at[ta[i]], 1u);
+        atomicAdd(&released_at[tf[i]], 1u);
+        const uint32_t s = (uint32_t)(size[i] >> shift);             // >= 1; 0 marks an empty class
+        bool placed = false;
+        for (int c = 0; c < kSpSizeClasses && !placed; ++c) {
+            const uint32_t old = atomicCAS(&class_size[c], 0u, s);
+            placed = old == 0u || old == s;
+        }
+        if (!placed) hist[kSpHistTooManySizes] = 1u;
+    }
+}
+
+// acc[kAccSplit] bit 1: the list holds ranks in place of times (8-byte entries, three workgroups per CU).
+// (sp_decide has admitted as many long-lived requests as the larger of the two lists holds: a trace
+// that needs the ranked list for its length and cannot have it is left to the sorted-list kernel.)
+__global__ void sp_ranked_decide(uint64_t* acc, const uint32_t* hist, uint32_t list_cap, uint32_t ranked_cap, uint32_t* gate)
+{
+    if (threadIdx.x != 0 || *gate != 0) return;
+    const uint32_t longs = (uint32_t)(acc[kAccSplit] >> 32);
+    if (hist[kSpHistTooManySizes] == 0 && longs <= kSpRankedMost && longs <= ranked_cap) acc[kAccSplit] |= 2ull;
+    else if (longs > list_cap) { acc[kAccSplit] = 0; *gate = 1; }
+}
+
 // Keys (t_alloc, request) of one tile, sorted in LDS.
 __global__ void __launch_bounds__(kSortTile)
 sp_sort_tiles(const uint32_t* __restrict__ ta, uint32_t n, ulonglong2* keys, const uint32_t* gate)
@@ -268,17 +361,21 @@ __device__ __forceinline__ uint32_t first_rank_at(const uint4* __restrict__ by_r
 }
 
 // Second word of a request's record: (window start, window end, for a large short block its place
-// among the large short blocks in allocation-time order, -).
+// among the large short blocks in allocation-time order, -); with a ranked list: (.., .., for a
+// long-lived request the second word of its list entry, A | B << 16).
 // Window of request i: ranks of the requests allocated in (t_alloc - theta, t_free).  A short
 // request j (lifetime <= theta) whose lifetime conflicts with i's has t_alloc_j < t_free_i and
 // t_alloc_j >= t_free_j - theta > t_alloc_i - theta, so it lies in the window.
 __global__ void __launch_bounds__(256)
 sp_windows(const uint4* __restrict__ by_rank, const uint32_t* __restrict__ ta, const uint32_t* __restrict__ tf, uint32_t n,
            const uint64_t* acc, const uint64_t* __restrict__ size, const uint32_t* __restrict__ rank_of,
-           const uint32_t* __restrict__ large_before, uint4* record, uint2* large_fit, uint32_t* hist, const uint32_t* gate)
+           const uint32_t* __restrict__ large_before, const uint32_t* __restrict__ allocated_before,
+           const uint32_t* __restrict__ released_before, const uint32_t* __restrict__ class_size, uint4* record,
+           uint2* large_fit, uint32_t* hist, const uint32_t* gate)
 {
     if (*gate != 0) return;
     const uint32_t theta = (uint32_t)((acc[kAccSplit] >> 8) & 0xffffffu);
+    const bool ranked = (acc[kAccSplit] & 2) != 0;
     uint32_t wide = 0;
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
         const uint32_t a = ta[i];
@@ -288,8 +385,19 @@ sp_windows(const uint4* __restrict__ by_rank, const uint32_t* __restrict__ ta, c
         // large_before[k] = large short blocks among the ranks below k: a large short block's place in
         // the table of those
         const bool large = (rank_of[i] & kSpLargeFlag) != 0;
-        const uint32_t place = large ? large_before[rank_of[i] & kSpRankMask] : 0u;
-        record[2 * i + 1] = make_uint4(w.x, w.y, place, 0u);
+        uint32_t extra = large ? large_before[rank_of[i] & kSpRankMask] : 0u, counts = 0u;
+        const uint32_t place = extra;
+        if (ranked) {
+            // allocated_before[t] = long-lived requests allocated before t, released_before[t] = released before t
+            counts = allocated_before[tf[i]] | (released_before[a + 1] << 16);
+            if (rank_of[i] & kSpLongFlag) {
+                const uint32_t s = (uint32_t)(size[i] >> (acc[kAccMode] & 63));
+                uint32_t cls = 0;
+                while (cls < (uint32_t)kSpSizeClasses - 1 && class_size[cls] != s) ++cls;
+                extra = allocated_before[a] | ((released_before[tf[i]] + 1u) << kSpRankBits) | (cls << (2 * kSpRankBits));
+            }
+        }
+        record[2 * i + 1] = make_uint4(w.x, w.y, extra, counts);
         if (large) large_fit[place] = make_uint2((uint32_t)(size[i] >> (acc[kAccMode] & 63)), tf[i]);
         wide += w.y - w.x > (uint32_t)kWave ? 1u : 0u;
     }
@@ -332,11 +440,14 @@ struct SplitTables {
     uint32_t* next_plan;         // [1] plans handed out so far
     const uint32_t* sigma;       // [1] size from which a short-lived block counts as large
     const uint32_t* large_total; // [1] how many do
+    const uint32_t* class_size;  // [64] ranked list: sizes of the long-lived requests' size classes
 };
 
 // What one wave knows about the request it settles.
 struct SpRequest {
     uint32_t s, ta, tf;
+    uint32_t list_a, list_b;         // a listed block conflicts in lifetime if block.ta() < list_a and list_b < block.tf():
+                                     // (t_free, t_alloc) of the request, or its counts (A, B) with a ranked list
     uint32_t wlo, whi;
     uint32_t large_lo, large_hi;     // the window in the table of large short blocks (wide windows only)
     // blocks settled earlier in the batch (lane = position in the batch)
@@ -482,15 +593,22 @@ __device__ __forceinline__ uint32_t clear_others(const SpRequest& rq, uint32_t o
 
 // The requests of the batch as the lanes of a wave hold them (lane = position in the batch).
 struct SpBatch {
-    uint32_t size, ta, tf, rank, wlo, whi;
+    uint32_t size, ta, tf, rank, wlo, whi, counts;
 };
+
+template <typename List>
+__device__ __forceinline__ void list_operands(SpRequest& rq, uint32_t counts)
+{
+    if constexpr (ListTraits<List>::kRanked) { rq.list_a = counts & 0xffffu; rq.list_b = counts >> 16; }
+    else { rq.list_a = rq.tf; rq.list_b = rq.ta; }
+}
 
 // Settles request q of the batch: the lowest address at which it conflicts with nothing placed
 // before it.  A request whose window fits the lanes of a wave (kWide false) is settled by one
 // wave; one with a wider window by all waves of the workgroup together, every wave taking the
 // same steps (they read the same LDS) and sharing only the look-ups in the table.
-template <bool kWide, int kWaves, typename Lds>
-__device__ __forceinline__ uint32_t settle_request(const SpList& list, uint32_t count, uint32_t b0, uint32_t q,
+template <bool kWide, int kWaves, typename List, typename Lds>
+__device__ __forceinline__ uint32_t settle_request(const List& list, uint32_t count, uint32_t b0, uint32_t q,
                                                    uint64_t dep_q, const SpBatch& bt, uint32_t pool_first, uint32_t in_pool,
                                                    const SplitTables& tb, const SpTable& pt, uint32_t& turn, Lds& sh)
 {
@@ -498,13 +616,14 @@ __device__ __forceinline__ uint32_t settle_request(const SpList& list, uint32_t 
     SpRequest rq;
     rq.s = read_lane(bt.size, (int)q); rq.ta = read_lane(bt.ta, (int)q); rq.tf = read_lane(bt.tf, (int)q);
     rq.wlo = read_lane(bt.wlo, (int)q); rq.whi = read_lane(bt.whi, (int)q);
+    list_operands<List>(rq, read_lane(bt.counts, (int)q));
     const uint32_t own_rank = read_lane(bt.rank, (int)q) & kSpRankMask;
     // What the first step needs from LDS is asked for in one go: the addresses of the batch, the
     // request's part of the pool, the lowest 64 blocks of the list.
     const uint32_t batch_addr = sh.rq_addr[b0 + lane];
     Span<uint32_t> pooled = {0u, 0u};
     if constexpr (!kWide) pooled = sh.pool[umin(pool_first + (uint32_t)lane, (uint32_t)kSpPool - 1)];
-    SpList::Entry en = list.load(umin((uint32_t)lane, count ? count - 1 : 0u));
+    typename List::Entry en = list.load(umin((uint32_t)lane, count ? count - 1 : 0u));
     // earlier requests of the batch with a conflicting lifetime: all settled by now (the mask says which lanes count)
     rq.rivals_in = dep_q;
     rq.in_lo = batch_addr;
@@ -536,9 +655,9 @@ __device__ __forceinline__ uint32_t settle_request(const SpList& list, uint32_t 
         const uint32_t k = k0 + lane;
         const bool valid = k < count;
         // (the blocks of the next step are asked for before this step's are looked at)
-        SpList::Entry next = en;
+        typename List::Entry next = en;
         if (k0 + kWave < count) next = list.load(umin(k + kWave, count - 1));
-        const bool conflict = valid && en.ta() < rq.tf && rq.ta < en.tf();
+        const bool conflict = valid && en.ta() < rq.list_a && rq.list_b < en.tf();
         const uint32_t incl = wave_scan_max(conflict ? en.hi() : 0u);
         const uint32_t before = umax(run, wave_shift_up(incl, 0u));
         // a hole [before, lo) in front of a conflicting block, large enough as such
@@ -563,8 +682,8 @@ __device__ __forceinline__ uint32_t settle_request(const SpList& list, uint32_t 
 // requests (bits = places in the batch); each has at most 16 other conflicting blocks to look
 // at -- its part of the pool and the requests of the batch settled before it.  The addresses go
 // to sh.rq_addr, the extent to sh.peak.
-template <typename Lds>
-__device__ __forceinline__ void settle_rows(const SpList& list, uint32_t count, uint32_t b0, uint64_t group, uint64_t dep,
+template <typename List, typename Lds>
+__device__ __forceinline__ void settle_rows(const List& list, uint32_t count, uint32_t b0, uint64_t group, uint64_t dep,
                                             const SpBatch& bt, uint32_t part_first, uint32_t part_count, Lds& sh)
 {
     const int lane = lane_id();
@@ -575,7 +694,14 @@ __device__ __forceinline__ void settle_rows(const SpList& list, uint32_t count, 
                    q2 = g2 ? (uint32_t)__builtin_ctzll(g2) : 0u, q3 = g3 ? (uint32_t)__builtin_ctzll(g3) : 0u;
     const uint32_t q = row == 0 ? q0 : row == 1 ? q1 : row == 2 ? q2 : q3;
     const bool active = row < (uint32_t)__builtin_popcountll(group);
-    const uint32_t s = lane_gather(bt.size, (int)q), ta = lane_gather(bt.ta, (int)q), tf = lane_gather(bt.tf, (int)q);
+    const uint32_t s = lane_gather(bt.size, (int)q);
+    uint32_t list_a, list_b;                                          // (see SpRequest)
+    if constexpr (ListTraits<List>::kRanked) {
+        const uint32_t counts = lane_gather(bt.counts, (int)q);
+        list_a = counts & 0xffffu; list_b = counts >> 16;
+    } else {
+        list_a = lane_gather(bt.tf, (int)q); list_b = lane_gather(bt.ta, (int)q);
+    }
     const uint32_t in_pool = lane_gather(part_count, (int)q), pool_at = lane_gather(part_first, (int)q);
     uint64_t before_it = lane_gather(dep, (int)q);                    // earlier requests of the batch with a conflicting lifetime
     // the other blocks the request has to keep clear of, one per lane of the row
@@ -608,8 +734,8 @@ __device__ __forceinline__ void settle_rows(const SpList& list, uint32_t count, 
         if (__builtin_amdgcn_ballot_w64(!settled) == 0) break;        // (uniform)
         const uint32_t k = k0 + at;
         const bool valid = k < count;
-        const SpList::Entry en = list.load(valid ? k : count - 1);
-        const bool conflict = valid && en.ta() < tf && ta < en.tf();
+        const typename List::Entry en = list.load(valid ? k : count - 1);
+        const bool conflict = valid && en.ta() < list_a && list_b < en.tf();
         const uint32_t incl = row_scan_max(conflict ? en.hi() : 0u);
         const uint32_t before = umax(run, row_shift_up(incl, 0u));
         // a hole [before, lo) in front of a conflicting block, large enough as such
@@ -640,8 +766,8 @@ __device__ __forceinline__ void settle_rows(const SpList& list, uint32_t count, 
 // list of long blocks each and write down the holes that are large enough as such; then all
 // waves try them in address order, sharing the look-ups in the table of short blocks.  Called by
 // all waves.
-template <int kWaves, typename Lds>
-__device__ __forceinline__ uint32_t settle_wide(const SpList& list, uint32_t count, uint32_t b0, uint32_t q, uint64_t dep_q,
+template <int kWaves, typename List, typename Lds>
+__device__ __forceinline__ uint32_t settle_wide(const List& list, uint32_t count, uint32_t b0, uint32_t q, uint64_t dep_q,
                                                 const SpBatch& bt, const SplitTables& tb, const SpTable& pt, uint32_t& turn,
                                                 uint32_t& wide_turn, Lds& sh)
 {
@@ -649,6 +775,7 @@ __device__ __forceinline__ uint32_t settle_wide(const SpList& list, uint32_t cou
     SpRequest rq;
     rq.s = read_lane(bt.size, (int)q); rq.ta = read_lane(bt.ta, (int)q); rq.tf = read_lane(bt.tf, (int)q);
     rq.wlo = read_lane(bt.wlo, (int)q); rq.whi = read_lane(bt.whi, (int)q);
+    list_operands<List>(rq, read_lane(bt.counts, (int)q));
     const uint32_t own_rank = read_lane(bt.rank, (int)q) & kSpRankMask;
     rq.rivals_in = dep_q;
     rq.in_lo = sh.rq_addr[b0 + lane];
@@ -669,8 +796,8 @@ __device__ __forceinline__ uint32_t settle_wide(const SpList& list, uint32_t cou
         for (uint32_t k0 = k_begin; k0 < k_end; k0 += kWave) {
             const uint32_t k = k0 + lane;
             const bool valid = k < k_end;
-            const SpList::Entry en = list.load(valid ? k : k_end - 1);
-            const bool conflict = valid && en.ta() < rq.tf && rq.ta < en.tf();
+            const typename List::Entry en = list.load(valid ? k : k_end - 1);
+            const bool conflict = valid && en.ta() < rq.list_a && rq.list_b < en.tf();
             const uint32_t incl = wave_scan_max(conflict ? en.hi() : 0u);
             const uint32_t before = umax(run, wave_shift_up(incl, 0u));
             const uint64_t opens = __builtin_amdgcn_ballot_w64(conflict && en.lo() >= before && en.lo() - before >= rq.s);
@@ -716,9 +843,13 @@ __device__ __forceinline__ uint32_t settle_wide(const SpList& list, uint32_t cou
     return clear_others<true, kWaves>(rq, own_rank, read_lane(tops, kWave - 1), 0xffffffffu, tb, pt, turn, sh);
 }
 
-template <int kThreads>
-__global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm, SplitTables tb)
+// kRanked: the list holds ranks in place of times (RankedList, 8 bytes a block) and three workgroups
+// share a CU (six waves per SIMD: 80 registers); else 16 bytes a block and two workgroups.  Both are
+// enqueued; acc[kAccSplit] bit 1 says which one works.
+template <int kThreads, bool kRanked>
+__global__ void __launch_bounds__(kThreads, kRanked ? 6 : 4) plan_split_kernel(PlanParams prm, SplitTables tb)
 {
+    using List = typename std::conditional<kRanked, RankedList, SpList>::type;
     static_assert(kThreads / kWave <= kSpMaxWaves, "a wave's part of the list has its own LDS words");
     constexpr int kWaves = kThreads / kWave;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -726,16 +857,21 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
     const uint32_t n = prm.n;
     if (*prm.status != STALLOC_OK) return;
     if (!(prm.acc[kAccSplit] & 1)) return;                            // another kernel places this trace
+    if (((prm.acc[kAccSplit] & 2) != 0) != kRanked) return;           // the other form of the list does
     const uint64_t mode = prm.acc[kAccMode];
     const bool try32 = (mode & kModeTry32) != 0;
     const uint32_t shift = (uint32_t)(mode & 63);
     const int lane = lane_id(), wave = wave_id();
     if (blockIdx.x == 0 && threadIdx.x == 0) {
-        const_cast<uint64_t*>(prm.acc)[kAccKernel] = STALLOC_KERNEL_LONG_LIST | (32u << 8);
+        const_cast<uint64_t*>(prm.acc)[kAccKernel] = STALLOC_KERNEL_LONG_LIST | (32u << 8) | ((uint64_t)List::kEntryBytes << 16);
         const_cast<uint64_t*>(prm.acc)[kAccLargeShort] = (uint64_t)*tb.sigma | ((uint64_t)*tb.large_total << 32);
     }
-    SpList list, spare;
+    List list, spare;
     list.bind(smem + sizeof(SplitLds), tb.list_cap);
+    if constexpr (kRanked) {
+        list.class_size = sh.class_size;
+        if (threadIdx.x < kSpSizeClasses) sh.class_size[threadIdx.x] = tb.class_size[threadIdx.x];   // (barriers follow)
+    }
     spare = list;
     SpTable pt;
     pt.addr = tb.addr + (size_t)blockIdx.x * tb.slots;
@@ -778,6 +914,8 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
                 sh.rq_rank[threadIdx.x] = r0.w;
                 sh.rq_wlo[threadIdx.x] = r1.x;
                 sh.rq_whi[threadIdx.x] = r1.y;
+                sh.rq_extra[threadIdx.x] = r1.z;
+                sh.rq_counts[threadIdx.x] = r1.w;
             }
             if (threadIdx.x < kSpBatch) sh.dep[threadIdx.x] = 0;
             __syncthreads();
@@ -792,7 +930,8 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
                 const uint32_t my_rank = mine ? sh.rq_rank[b0 + lane] : 0u;
                 const uint32_t my_wlo = mine ? sh.rq_wlo[b0 + lane] : 0u;
                 const uint32_t my_whi = mine ? sh.rq_whi[b0 + lane] : 0u;
-                const SpBatch bt = {my_size, my_ta, my_tf, my_rank, my_wlo, my_whi};
+                const uint32_t my_counts = mine ? sh.rq_counts[b0 + lane] : 0u;
+                const SpBatch bt = {my_size, my_ta, my_tf, my_rank, my_wlo, my_whi, my_counts};
                 if (try32) {
                     // no address of this batch exceeds the extent so far plus the sizes of the batch
                     const uint64_t growth = wave_sum64((uint64_t)my_size);
@@ -911,7 +1050,7 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
                     const uint32_t rank = my_rank & kSpRankMask;
                     addr[rank] = x;
                     if (my_rank & kSpLargeFlag) {
-                        pt.large_addr[tb.record[2 * (size_t)sh.rq_id[b0 + lane] + 1].z] = x;
+                        pt.large_addr[sh.rq_extra[b0 + lane]] = x;
                         atomicMin(&sh.large_min, x);
                         atomicMax(&sh.large_max, x + my_size);
                     } else {
@@ -935,7 +1074,7 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
                     }
                     if (pending && ((longs >> lane) & 1)) {
                         sh.pend_span[place] = Span<uint32_t>{x, x + my_size};
-                        sh.pend_life[place] = make_uint2(my_ta, my_tf);
+                        sh.pend_life[place] = kRanked ? make_uint2(sh.rq_extra[b0 + lane], 0u) : make_uint2(my_ta, my_tf);
                     }
                     if (lane == 0) { sh.extent_now = sh.peak; sh.pool_used = 0; }
                     if (lane < kSpBatch) sh.dep[lane] = 0;
@@ -961,11 +1100,12 @@ __global__ void __launch_bounds__(kThreads, 4) plan_split_kernel(PlanParams prm,
     }
 }
 
-size_t split_workspace(uint32_t n, const DeviceInfo& di, Carver& cv, SplitWorkspace* ws)
+size_t split_workspace(uint32_t n, uint32_t t_end, const DeviceInfo& di, Carver& cv, SplitWorkspace* ws)
 {
     const uint32_t n_pad = (n + kSortTile - 1) / kSortTile * kSortTile;
     const uint32_t slots = (n + kWave - 1) / kWave * kWave + kWave;
-    uint32_t grid = (uint32_t)di.cus * 2;
+    const bool ranked = ranked_possible(n, t_end);
+    uint32_t grid = (uint32_t)di.cus * (ranked ? 3 : 2);              // resident workgroups: tables for each
     ws->hist = cv.take<uint32_t>(kSpHistWords);
     ws->gate = cv.take<uint32_t>(1);
     ws->keys = cv.take<ulonglong2>(n_pad);
@@ -981,7 +1121,15 @@ size_t split_workspace(uint32_t n, const DeviceInfo& di, Carver& cv, SplitWorksp
     ws->group_span = cv.take<uint2>((size_t)grid * (slots / kWave));
     ws->is_large = cv.take<uint32_t>(slots);
     ws->large_before = cv.take<uint32_t>(slots);
-    ws->scan_chunks = cv.take<uint32_t>((slots + 1023) / 1024);
+    const size_t times = ranked ? (size_t)t_end + 2 : 0;
+    ws->scan_chunks = cv.take<uint32_t>(((times > slots ? times : slots) + 1023) / 1024);
+    // ranked list: marks at the long-lived requests' allocation and release times (one block: cleared together), their sums
+    ws->allocated_at = cv.take<uint32_t>(2 * times + kSpSizeClasses);
+    ws->released_at = ws->allocated_at + times;
+    ws->class_size = ws->released_at + times;
+    ws->allocated_before = cv.take<uint32_t>(times);
+    ws->released_before = cv.take<uint32_t>(times);
+    ws->times = (uint32_t)times;
     ws->scan_total = cv.take<uint32_t>(1);
     ws->large_fit = cv.take<uint2>(large_slots);
     ws->large_addr = cv.take<uint32_t>((size_t)grid * large_slots);
@@ -997,6 +1145,8 @@ bool launch_plan_split(const PlanParams& prm, uint32_t t_end, const SplitWorkspa
     const uint32_t n = prm.n;
     const size_t lds = di.lds_per_block / 2;                          // two workgroups per CU
     const uint32_t list_cap = split_list_capacity(lds);
+    const bool ranked = ws.times != 0;
+    const uint32_t ranked_cap = ranked ? split_list_capacity(ranked_lds(di), RankedList::kEntryBytes) : 0u;
     uint32_t blocks = (n + 255) / 256;
     if (blocks > 1024) blocks = 1024;
     uint64_t* acc = const_cast<uint64_t*>(prm.acc);
@@ -1004,7 +1154,8 @@ bool launch_plan_split(const PlanParams& prm, uint32_t t_end, const SplitWorkspa
     hipLaunchKernelGGL(sp_clear_histogram, dim3(1), dim3(64), 0, stream, ws.hist, ws.gate);
     hipLaunchKernelGGL(sp_histogram, dim3(blocks > 256 ? 256 : blocks), dim3(256), 0, stream, prm.ta, prm.tf, n, ws.hist,
                        prm.status);
-    hipLaunchKernelGGL(sp_decide, dim3(1), dim3(64), 0, stream, acc, ws.hist, n, t_end, list_cap, prm, ws.gate, prm.status);
+    hipLaunchKernelGGL(sp_decide, dim3(1), dim3(64), 0, stream, acc, ws.hist, n, t_end, list_cap > ranked_cap ? list_cap : ranked_cap,
+                       prm, ws.gate, prm.status);
     hipLaunchKernelGGL(sp_size_histogram, dim3(blocks > 256 ? 256 : blocks), dim3(256), 0, stream, prm.size, prm.ta, prm.tf, n,
                        prm.acc, ws.hist, ws.gate);
     hipLaunchKernelGGL(sp_sigma, dim3(1), dim3(64), 0, stream, ws.hist, ws.gate);
@@ -1012,9 +1163,19 @@ bool launch_plan_split(const PlanParams& prm, uint32_t t_end, const SplitWorkspa
     const ulonglong2* sorted = launch_merge_tiles(ws.keys, ws.spare, ws.n_pad, 1, ws.gate, stream);
     hipLaunchKernelGGL(sp_tables, dim3(blocks), dim3(256), 0, stream, sorted, prm.size, prm.ta, prm.tf, n, ws.slots, prm.acc,
                        ws.by_rank, ws.size_by_rank, ws.fit_by_rank, ws.rank_of, ws.is_large, ws.hist, ws.gate);
+    if (ranked) {
+        hipLaunchKernelGGL(sp_clear_words, dim3(256), dim3(256), 0, stream, ws.allocated_at, 2 * (size_t)ws.times + kSpSizeClasses,
+                           ws.gate);
+        hipLaunchKernelGGL(sp_long_marks, dim3(blocks > 256 ? 256 : blocks), dim3(256), 0, stream, prm.size, prm.ta, prm.tf, n,
+                           prm.acc, ws.allocated_at, ws.released_at, ws.class_size, ws.hist, ws.gate);
+        launch_scan(ws.allocated_at, ws.times, ws.allocated_before, ws.scan_chunks, ws.scan_total, ws.gate, stream);
+        launch_scan(ws.released_at, ws.times, ws.released_before, ws.scan_chunks, ws.scan_total, ws.gate, stream);
+        hipLaunchKernelGGL(sp_ranked_decide, dim3(1), dim3(64), 0, stream, acc, ws.hist, list_cap, ranked_cap, ws.gate);
+    }
     launch_scan(ws.is_large, ws.slots, ws.large_before, ws.scan_chunks, ws.scan_total, ws.gate, stream);
     hipLaunchKernelGGL(sp_windows, dim3(blocks), dim3(256), 0, stream, ws.by_rank, prm.ta, prm.tf, n, prm.acc, prm.size,
-                       ws.rank_of, ws.large_before, ws.record, ws.large_fit, ws.hist, ws.gate);
+                       ws.rank_of, ws.large_before, ws.allocated_before, ws.released_before, ws.class_size, ws.record,
+                       ws.large_fit, ws.hist, ws.gate);
     hipLaunchKernelGGL(sp_confirm, dim3(1), dim3(64), 0, stream, acc, ws.hist, n, ws.gate);
 
     SplitTables tb;
@@ -1027,18 +1188,30 @@ bool launch_plan_split(const PlanParams& prm, uint32_t t_end, const SplitWorkspa
     tb.large_total = ws.scan_total;
     tb.region_shift = 6;
     while (((uint64_t)ws.slots + (1ull << tb.region_shift) - 1) >> tb.region_shift > (uint64_t)kWave) ++tb.region_shift;
-    auto kernel = &plan_split_kernel<kSpThreads>;
+    tb.class_size = ws.class_size;
+    auto kernel = &plan_split_kernel<kSpThreads, false>;
+    auto kernel_ranked = &plan_split_kernel<kSpThreads, true>;
     static std::atomic<bool> attr_set[64] = {};        // (set twice at worst when threads race)
     if (!attr_set[di.device]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)di.lds_per_block) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(kernel_ranked), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)di.lds_per_block) != hipSuccess)
             return false;
         attr_set[di.device] = true;
     }
-    uint32_t grid = ws.grid;
+    // exactly one of the two does the work (acc[kAccSplit] bit 1)
+    uint32_t grid = (uint32_t)di.cus * 2;
     if (grid > prm.P) grid = prm.P;
     const size_t lds_bytes = sizeof(SplitLds) + (size_t)list_cap * SpList::kEntryBytes;
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(kSpThreads), lds_bytes, stream, prm, tb);
+    if (ranked) {
+        grid = ws.grid;                                               // three per CU
+        if (grid > prm.P) grid = prm.P;
+        tb.list_cap = ranked_cap;
+        hipLaunchKernelGGL(kernel_ranked, dim3(grid), dim3(kSpThreads), sizeof(SplitLds) + (size_t)ranked_cap * RankedList::kEntryBytes,
+                           stream, prm, tb);
+    }
     return true;
 }
 
