@@ -199,6 +199,27 @@ def test_plans_that_outgrow_32_bit_counts_are_placed_again(S, oracle, fill):
     assert bool((ext > np.uint64(2 ** 32)).all()) == (fill > 1.0)
 
 
+def test_both_forms_of_the_list(S, oracle):
+    """The list holds 8 bytes a block (ranks among the long-lived requests' allocation and release times
+    in place of the times, a size class) when those requests have at most 64 sizes and the timestamps
+    are not far apart, else 16 bytes; tied timestamps, and long-lived requests that begin or end together,
+    in both."""
+    rng = np.random.default_rng(1212)
+    few = two_kinds(rng, 9800, 700, 15, [1 << 20, 3 << 20, 5 << 19, 1 << 22], [512, 1024, 4096])
+    many = two_kinds(rng, 9800, 700, 15, [(k + 1) << 16 for k in range(80)], [512, 1024, 4096])
+    tied = two_kinds(rng, 9900, 600, 7, [1 << 20, 3 << 20], [512, 1536], quantum=2)
+    ts, te = tied.t_alloc.astype(np.int64), tied.t_free.astype(np.int64)
+    long_ids = np.nonzero(te - ts > 7)[0]
+    ts[long_ids[:40]] = ts[long_ids[:40]].min()                          # forty begin together, forty end together
+    te[long_ids[40:80]] = te[long_ids[40:80]].max()
+    tied = Trace(name="tied", size=tied.size, t_alloc=ts.astype(np.uint32), t_free=te.astype(np.uint32), t_end=int(te.max()))
+    sparse = Trace(name="sparse", size=few.size, t_alloc=few.t_alloc * np.uint32(9), t_free=few.t_free * np.uint32(9),
+                   t_end=int(few.t_end) * 9)
+    for tr, want in ((few, 8), (many, 16), (tied, 8), (sparse, 16)):
+        got, _, _ = _compare(S, oracle, tr, _orders(rng, tr, 2))
+        assert got["info"]["list_entry_bytes"] == want, (tr.name, got["info"])
+
+
 def test_traces_the_kernel_leaves_to_the_sorted_list(S, oracle):
     """Too many long-lived requests for the LDS list, and timestamps so coarse that every window is
     wide: the sorted-list kernel places these; results equal the oracle's all the same."""

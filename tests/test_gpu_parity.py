@@ -446,6 +446,7 @@ def test_plan_config5_full_launch_stratified_orderings(S, oracle, half):
     short = tr.t_free.astype(np.int64) - tr.t_alloc <= 15
     assert full["info"]["large_size"] == 1 << 27
     assert full["info"]["large_requests"] == int((short & (tr.size >= 1 << 27)).sum()) > 0
+    assert full["info"]["list_entry_bytes"] == 8                           # (six sizes among the 4271 long-lived requests)
 
 
 @pytest.mark.parametrize("n_clique,n_extra,unit,fill", [(230, 70, 1 << 24, 0.80), (230, 70, 1 << 24, 0.875),
