@@ -1014,7 +1014,10 @@ __global__ void __launch_bounds__(kThreads, kRanked ? 6 : 4) plan_split_kernel(P
                     ++round;
                     // (four at a time, a row of 16 lanes each, when what each has to keep clear of fits a row)
                     const uint64_t mine_now = __builtin_amdgcn_ballot_w64(take);
-                    for (uint64_t todo = mine_now & ~fits_row; todo; todo &= todo - 1) {
+                    // (a lone request has the whole wave to itself: 64 list blocks a step instead of 16, and none
+                    // of the gathering that gives each of four requests a row)
+                    const uint64_t in_rows = (mine_now & (mine_now - 1)) ? mine_now & fits_row : 0ull;
+                    for (uint64_t todo = mine_now & ~in_rows; todo; todo &= todo - 1) {
                         const int q = __builtin_ctzll(todo);
                         const uint32_t x = settle_request<false, kWaves>(list, count, b0, (uint32_t)q, readlane64(dep, q), bt,
                                                                          read_lane(part_first, q), read_lane(part_count, q), tb, pt,
@@ -1024,7 +1027,7 @@ __global__ void __launch_bounds__(kThreads, kRanked ? 6 : 4) plan_split_kernel(P
                             atomicMax(&sh.peak, x + read_lane(my_size, q));
                         }
                     }
-                    for (uint64_t todo = mine_now & fits_row; todo;) {
+                    for (uint64_t todo = in_rows; todo;) {
                         uint64_t rest = todo & (todo - 1);
                         rest &= rest - 1;
                         rest &= rest - 1;
