@@ -32,9 +32,14 @@
 //
 // Requests are settled in batches of 64 of the order.  Inside a batch a request waits only for
 // the earlier requests of the batch whose lifetime conflicts with its own; everything that is
-// ready is settled at once, one request per wave, so that a batch takes as many rounds as its
-// longest chain of conflicts (mostly one or two).  The long blocks of a batch are merged into
-// the sorted list when the batch is done.
+// ready is settled at once, dealt out to the waves (a wave with several short-lived requests
+// settles up to four side by side, a row of 16 lanes each; the whole workgroup takes a
+// long-lived one together), so that a batch takes as many rounds as its longest chain of
+// conflicts (mostly two to four).  The long blocks of a batch are merged into the sorted list
+// when the batch is done.
+//
+// The list comes in two forms (RankedList below): 16 bytes a block with its two times, two
+// workgroups per CU, or 8 bytes a block with ranks in place of the times, three per CU.
 //
 // theta = 2^c - 1 is chosen so that the long requests fit the LDS list and are at most an eighth
 // of all requests while the windows of the short ones stay narrow (sp_decide); traces for which
