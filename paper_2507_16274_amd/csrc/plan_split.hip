@@ -502,7 +502,7 @@ __device__ __forceinline__ uint32_t window_reach(const SpRequest& rq, uint32_t o
     ++turn;
     if (threadIdx.x == 0) sh.reach[(slot + 1) % 3] = 0;                                 // for the call after this one
     uint32_t reach = 0;
-    constexpr int kFlight = 6;                                                          // groups whose reads are under way together
+    constexpr int kFlight = 4;                                                          // groups whose reads are under way together
     if (large) {
         const uint32_t l_begin = rq.large_lo / kWave, l_end = (rq.large_hi + kWave - 1) / kWave;
         for (uint32_t g0 = l_begin + (uint32_t)wave; g0 < l_end; g0 += kFlight * kWaves) {
